@@ -1,0 +1,381 @@
+// CPU checker for the sparse-embedding path (TEST INFRASTRUCTURE, not a product path).
+//
+// A plain, single-threaded, obviously-correct statement of what one device
+// computes for the embedding layer of a generative recommendation model:
+// tagged IDs of merged tables (Sec. 3.2, Eq. 8), ID deduplication with inverse
+// indices (Sec. 3.3), a dynamic key -> embedding-row table with real-time
+// insertion and deletion (Sec. 3.1), per-ID gradient aggregation and an update
+// of the activated rows only (Sec. 2 "Backward Update"; App. C "Gradient
+// Accumulation").  The table is a std::unordered_map, the unique is a
+// std::sort; there is no blocking, fusion or reordering.
+//
+// Only tests, the smoke check and the benchmark's cpu_baseline leg may call
+// this library.  It shares no source, header, table or constant generator with
+// the GPU library.
+//
+// Parity pins live in tests/test_oracle_*.py.  Parts whose definition the paper
+// leaves open (row initialisation, the optimizer, the eviction predicate) follow
+// the readings listed in DESIGN.md; no function here is "parity unpinned".
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <unordered_map>
+#include <vector>
+
+namespace {
+
+constexpr int kF32 = 0;
+constexpr int kBF16 = 1;
+
+struct Row {
+    std::vector<float> w;   // bf16 tables keep bf16-representable floats
+    float acc = 0.0f;       // row-wise Adagrad accumulator
+    uint32_t last_seen = 0; // step of the last find-or-insert that touched the key
+    uint32_t freq = 0;      // number of find-or-insert elements that touched the key
+};
+
+struct Table {
+    int dim;
+    int dtype;
+    float init_scale;
+    std::unordered_map<uint64_t, Row> map;
+};
+
+// ---- bf16 <-> float, written out (round to nearest, ties to even) ---------
+inline float bf16_bits_to_float(uint16_t h) {
+    uint32_t u = static_cast<uint32_t>(h) << 16;
+    float f;
+    std::memcpy(&f, &u, 4);
+    return f;
+}
+inline uint16_t float_to_bf16_bits(float f) {
+    uint32_t u;
+    std::memcpy(&u, &f, 4);
+    uint32_t keep_lsb = (u >> 16) & 1u;
+    u += 0x7FFFu + keep_lsb;
+    return static_cast<uint16_t>(u >> 16);
+}
+// One rounding from double straight to a bf16-representable float (normal range).
+inline float double_to_bf16_float(double d) {
+    uint64_t u;
+    std::memcpy(&u, &d, 8);
+    const int drop = 52 - 7;
+    uint64_t keep_lsb = (u >> drop) & 1ull;
+    u += ((1ull << (drop - 1)) - 1ull) + keep_lsb;
+    u &= ~((1ull << drop) - 1ull);
+    double r;
+    std::memcpy(&r, &u, 8);
+    return static_cast<float>(r); // exact: r has 8 significant bits
+}
+
+// ---- key-seeded row initialisation ----------------------------------------
+// Element j of the row of `key` is the (j+1)-th output of a splitmix64 stream
+// seeded with the tagged key, mapped to a 24-bit signed integer and scaled by
+// init_scale * 2^-23, i.e. uniform on [-init_scale, init_scale).
+inline uint64_t splitmix_out(uint64_t seed, uint64_t nth /*1-based*/) {
+    uint64_t z = seed + nth * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+inline float init_value(uint64_t key, int j, float init_scale, int dtype) {
+    uint64_t z = splitmix_out(key, static_cast<uint64_t>(j) + 1ull);
+    int32_t q = static_cast<int32_t>(z >> 40) - (1 << 23);
+    double c = static_cast<double>(init_scale) * (1.0 / 8388608.0); // exact power-of-two scaling
+    float v = static_cast<float>(static_cast<double>(q) * c);     // one rounding, as one fp32 multiply
+    if (dtype == kBF16) v = bf16_bits_to_float(float_to_bf16_bits(v));
+    return v;
+}
+
+Row fresh_row(const Table& t, uint64_t key) {
+    Row r;
+    r.w.resize(t.dim);
+    for (int j = 0; j < t.dim; ++j) r.w[j] = init_value(key, j, t.init_scale, t.dtype);
+    return r;
+}
+
+inline bool key_ok(uint64_t k) { return (k >> 63) == 0; }
+
+} // namespace
+
+extern "C" {
+
+// ---------------------------------------------------------------------------
+// Table merging (Sec. 3.2 "Automated Merging Table"): logical tables with the
+// same (dim, dtype) share one hash table.  Merged tables are numbered in order
+// of first appearance.  Returns the number of merged tables.
+int orc_plan_merge(const int* dims, const int* dtypes, int m, int* merged_of) {
+    std::vector<std::pair<int, int>> seen;
+    for (int t = 0; t < m; ++t) {
+        std::pair<int, int> sig(dims[t], dtypes[t]);
+        auto it = std::find(seen.begin(), seen.end(), sig);
+        if (it == seen.end()) {
+            seen.push_back(sig);
+            merged_of[t] = static_cast<int>(seen.size()) - 1;
+        } else {
+            merged_of[t] = static_cast<int>(it - seen.begin());
+        }
+    }
+    return static_cast<int>(seen.size());
+}
+
+// Number of identifier bits for m tables: k = ceil(log2(m + 1))  (Sec. 3.2).
+int orc_tag_bits(int m) {
+    int k = 0;
+    while ((1ll << k) < static_cast<long long>(m) + 1) ++k;
+    return k;
+}
+
+// Eq. 8: ID = (i << (63 - k)) | x, top bit zero.  Element e belongs to the
+// field f with field_off[f] <= e < field_off[f+1]; field_tag[f] is the
+// 0-based logical table index i.  A raw ID that does not fit in 63-k bits is
+// counted in *err_count and wrapped into range (x mod 2^(63-k)).
+int orc_tag_keys(const uint64_t* x, const int64_t* field_off, const uint8_t* field_tag, int n_fields,
+                 int tag_bits, uint64_t* key_out, int64_t* err_count) {
+    if (tag_bits < 0 || tag_bits > 16) return -1;
+    const int shift = 63 - tag_bits;
+    const uint64_t low_mask = (1ull << shift) - 1ull;
+    int64_t errs = 0;
+    for (int f = 0; f < n_fields; ++f) {
+        if (tag_bits < 8 && (field_tag[f] >> tag_bits) != 0) return -1; // table index needs more than k bits
+        for (int64_t e = field_off[f]; e < field_off[f + 1]; ++e) {
+            uint64_t v = x[e];
+            if (v > low_mask) { ++errs; v &= low_mask; }
+            key_out[e] = (static_cast<uint64_t>(field_tag[f]) << shift) | v;
+        }
+    }
+    if (err_count) *err_count = errs;
+    return 0;
+}
+
+// ---------------------------------------------------------------------------
+// Deduplication (Sec. 3.3): the distinct keys in ascending order, for every
+// input position the index of its key among them, and how often each occurs.
+int64_t orc_dedup(const uint64_t* key, int64_t n, uint64_t* uniq, int32_t* inverse, int32_t* counts) {
+    std::vector<uint64_t> s(key, key + n);
+    std::sort(s.begin(), s.end());
+    s.erase(std::unique(s.begin(), s.end()), s.end());
+    const int64_t U = static_cast<int64_t>(s.size());
+    for (int64_t u = 0; u < U; ++u) {
+        uniq[u] = s[u];
+        if (counts) counts[u] = 0;
+    }
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t u = std::lower_bound(s.begin(), s.end(), key[i]) - s.begin();
+        inverse[i] = static_cast<int32_t>(u);
+        if (counts) ++counts[u];
+    }
+    return U;
+}
+
+// ---------------------------------------------------------------------------
+// Dynamic table (Sec. 3.1).
+void* orc_table_create(int dim, int dtype, float init_scale) {
+    if (dim <= 0 || (dtype != kF32 && dtype != kBF16)) return nullptr;
+    Table* t = new Table();
+    t->dim = dim;
+    t->dtype = dtype;
+    t->init_scale = init_scale;
+    return t;
+}
+void orc_table_destroy(void* h) { delete static_cast<Table*>(h); }
+int64_t orc_size(void* h) { return static_cast<int64_t>(static_cast<Table*>(h)->map.size()); }
+
+// Closed-form initial row of a key (what a never-updated row must equal).
+void orc_init_row(uint64_t key, int dim, int dtype, float init_scale, float* out) {
+    for (int j = 0; j < dim; ++j) out[j] = init_value(key, j, init_scale, dtype);
+}
+
+// Find each key; an absent key is inserted with its initial row, acc = 0,
+// freq = 0.  Then every element (duplicates included) counts one touch:
+// freq += 1, last_seen = step.  inserted[i] = 1 for the element that created
+// the entry.  Keys with the top bit set are rejected (return -2, nothing done).
+int orc_find_or_insert(void* h, const uint64_t* key, int64_t n, uint32_t step, uint8_t* inserted) {
+    Table& t = *static_cast<Table*>(h);
+    for (int64_t i = 0; i < n; ++i)
+        if (!key_ok(key[i])) return -2;
+    for (int64_t i = 0; i < n; ++i) {
+        auto it = t.map.find(key[i]);
+        bool created = false;
+        if (it == t.map.end()) {
+            it = t.map.emplace(key[i], fresh_row(t, key[i])).first;
+            created = true;
+        }
+        it->second.freq += 1;
+        it->second.last_seen = step;
+        if (inserted) inserted[i] = created ? 1 : 0;
+    }
+    return 0;
+}
+
+// Bulk-load semantics for keys that exist before the first step: identical to
+// one find-or-insert touch at step 0, applied only to keys not yet present
+// (so calling it again, or lazily for the keys a step is about to touch, is
+// harmless).
+int orc_prepopulate(void* h, const uint64_t* key, int64_t n) {
+    Table& t = *static_cast<Table*>(h);
+    for (int64_t i = 0; i < n; ++i) {
+        if (!key_ok(key[i])) return -2;
+        if (t.map.find(key[i]) == t.map.end()) {
+            Row r = fresh_row(t, key[i]);
+            r.freq = 1;
+            r.last_seen = 0;
+            t.map.emplace(key[i], std::move(r));
+        }
+    }
+    return 0;
+}
+
+// Read-only membership.
+int orc_find(void* h, const uint64_t* key, int64_t n, uint8_t* found) {
+    Table& t = *static_cast<Table*>(h);
+    for (int64_t i = 0; i < n; ++i) found[i] = t.map.count(key[i]) ? 1 : 0;
+    return 0;
+}
+
+// Rows of the given keys as float32 [n, dim]; an absent key reads as zeros.
+int orc_lookup(void* h, const uint64_t* key, int64_t n, float* out) {
+    Table& t = *static_cast<Table*>(h);
+    for (int64_t i = 0; i < n; ++i) {
+        auto it = t.map.find(key[i]);
+        float* o = out + i * t.dim;
+        if (it == t.map.end()) {
+            for (int j = 0; j < t.dim; ++j) o[j] = 0.0f;
+        } else {
+            for (int j = 0; j < t.dim; ++j) o[j] = it->second.w[j];
+        }
+    }
+    return 0;
+}
+
+// The forward pass by its plain definition, without deduplication: every
+// position looks its key up directly; absent keys are created on the spot.
+// Touch counters are left alone (freq = 0 for rows created here).
+int orc_direct_lookup(void* h, const uint64_t* key, int64_t n, uint32_t step, float* out) {
+    Table& t = *static_cast<Table*>(h);
+    for (int64_t i = 0; i < n; ++i) {
+        if (!key_ok(key[i])) return -2;
+        auto it = t.map.find(key[i]);
+        if (it == t.map.end()) {
+            Row r = fresh_row(t, key[i]);
+            r.last_seen = step;
+            it = t.map.emplace(key[i], std::move(r)).first;
+        }
+        for (int j = 0; j < t.dim; ++j) out[i * t.dim + j] = it->second.w[j];
+    }
+    return 0;
+}
+
+// Expand: E[i,:] = E_u[inverse[i],:]  (undoes the deduplication).
+int orc_expand(const float* uniq_rows, const int32_t* inverse, int64_t n, int dim, float* out) {
+    for (int64_t i = 0; i < n; ++i)
+        for (int j = 0; j < dim; ++j) out[i * dim + j] = uniq_rows[static_cast<int64_t>(inverse[i]) * dim + j];
+    return 0;
+}
+
+// Gradient aggregation per distinct key: g[u,:] = sum over positions i with
+// inverse[i] == u of G[i,:], accumulated in double in input order and rounded
+// once to float.
+int orc_segment_reduce(const float* grad, const int32_t* inverse, int64_t n, int64_t n_unique, int dim,
+                       float* reduced) {
+    std::vector<double> sum(static_cast<size_t>(n_unique) * dim, 0.0);
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t u = inverse[i];
+        if (u < 0 || u >= n_unique) return -1;
+        for (int j = 0; j < dim; ++j) sum[u * dim + j] += static_cast<double>(grad[i * dim + j]);
+    }
+    for (size_t e = 0; e < sum.size(); ++e) reduced[e] = static_cast<float>(sum[e]);
+    return 0;
+}
+
+// Row-wise Adagrad on the rows of the given keys only:
+//   acc <- acc + (1/D) * sum_j g_j^2 ;  w_j <- w_j - lr * g_j / (sqrt(acc) + eps)
+// evaluated in double from the stored state, each stored value rounded once.
+// Absent keys are skipped.  A key listed twice is updated twice, in order.
+int orc_apply_adagrad(void* h, const uint64_t* key, int64_t n, const float* g, float lr, float eps) {
+    Table& t = *static_cast<Table*>(h);
+    const int D = t.dim;
+    for (int64_t u = 0; u < n; ++u) {
+        auto it = t.map.find(key[u]);
+        if (it == t.map.end()) continue;
+        Row& r = it->second;
+        double ss = 0.0;
+        for (int j = 0; j < D; ++j) ss += static_cast<double>(g[u * D + j]) * static_cast<double>(g[u * D + j]);
+        double acc = static_cast<double>(r.acc) + ss / static_cast<double>(D);
+        double denom = std::sqrt(acc) + static_cast<double>(eps);
+        for (int j = 0; j < D; ++j) {
+            double w = static_cast<double>(r.w[j]) - static_cast<double>(lr) * static_cast<double>(g[u * D + j]) / denom;
+            r.w[j] = (t.dtype == kBF16) ? double_to_bf16_float(w) : static_cast<float>(w);
+        }
+        r.acc = static_cast<float>(acc);
+    }
+    return 0;
+}
+
+// Eviction at step `now`.  A key goes when it has not been touched for `ttl`
+// steps (rule active when ttl > 0), or when it was touched fewer than
+// `min_freq` times and not within the last `grace` steps (rule active when
+// min_freq > 0).  The erased keys are written in ascending order; returns how
+// many.  evicted may be null.
+int64_t orc_evict(void* h, uint32_t now, uint32_t ttl, uint32_t min_freq, uint32_t grace, uint64_t* evicted) {
+    Table& t = *static_cast<Table*>(h);
+    std::vector<uint64_t> gone;
+    for (const auto& kv : t.map) {
+        uint32_t age = now - kv.second.last_seen;
+        bool stale = (ttl > 0) && (age >= ttl);
+        bool rare = (min_freq > 0) && (kv.second.freq < min_freq) && (age >= grace);
+        if (stale || rare) gone.push_back(kv.first);
+    }
+    std::sort(gone.begin(), gone.end());
+    for (uint64_t k : gone) t.map.erase(k);
+    if (evicted) std::copy(gone.begin(), gone.end(), evicted);
+    return static_cast<int64_t>(gone.size());
+}
+
+// Dump of the whole table ordered by key (values as float32).  Any output may
+// be null.  Returns the number of entries.
+int64_t orc_export(void* h, uint64_t* keys, float* values, float* acc, uint32_t* last_seen, uint32_t* freq) {
+    Table& t = *static_cast<Table*>(h);
+    std::vector<uint64_t> ks;
+    ks.reserve(t.map.size());
+    for (const auto& kv : t.map) ks.push_back(kv.first);
+    std::sort(ks.begin(), ks.end());
+    for (size_t i = 0; i < ks.size(); ++i) {
+        const Row& r = t.map.at(ks[i]);
+        if (keys) keys[i] = ks[i];
+        if (values) std::copy(r.w.begin(), r.w.end(), values + i * t.dim);
+        if (acc) acc[i] = r.acc;
+        if (last_seen) last_seen[i] = r.last_seen;
+        if (freq) freq[i] = r.freq;
+    }
+    return static_cast<int64_t>(ks.size());
+}
+
+// State of the given keys (for sampled comparisons on large tables).
+// present[i] = 0 leaves the other outputs of that entry untouched.
+int orc_peek(void* h, const uint64_t* key, int64_t n, uint8_t* present, float* values, float* acc,
+             uint32_t* last_seen, uint32_t* freq) {
+    Table& t = *static_cast<Table*>(h);
+    for (int64_t i = 0; i < n; ++i) {
+        auto it = t.map.find(key[i]);
+        present[i] = it != t.map.end();
+        if (!present[i]) continue;
+        const Row& r = it->second;
+        if (values) std::copy(r.w.begin(), r.w.end(), values + i * t.dim);
+        if (acc) acc[i] = r.acc;
+        if (last_seen) last_seen[i] = r.last_seen;
+        if (freq) freq[i] = r.freq;
+    }
+    return 0;
+}
+
+// bf16 helpers exposed for the tests' own cross-checks.
+void orc_float_to_bf16(const float* in, int64_t n, uint16_t* out) {
+    for (int64_t i = 0; i < n; ++i) out[i] = float_to_bf16_bits(in[i]);
+}
+void orc_bf16_to_float(const uint16_t* in, int64_t n, float* out) {
+    for (int64_t i = 0; i < n; ++i) out[i] = bf16_bits_to_float(in[i]);
+}
+
+} // extern "C"

@@ -1,0 +1,370 @@
+"""Pins of the CPU checker against things other than itself.
+
+Each test ties one function of ``oracle/`` to what the paper or plain
+mathematics fixes: the paper's worked tagging example, brute force on tiny
+inputs, library routines on special cases (``torch.unique``,
+``torch.optim.Adagrad`` at dim 1, ``numpy.add.at``, torch's bfloat16 cast),
+closed forms and invariants.  None of them needs a GPU.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from workloads import make_config, normal_grads
+
+
+def _read_rows(path):
+    with open(path) as f:
+        return [ln.split() for ln in f if ln.strip() and not ln.startswith("#")]
+
+
+# --------------------------------------------------------------------------- #
+# tagging (Sec. 3.2, Eq. 8)
+# --------------------------------------------------------------------------- #
+def test_tag_bits_paper_example_and_formula(golden_dir):
+    m, k, shift, row_bits, max_rows_log2 = map(int, _read_rows(os.path.join(golden_dir, "eq8_table_tag_example.txt"))[0])
+    assert oracle.tag_bits(m) == k
+    assert 63 - k == shift == row_bits == max_rows_log2
+    for m_, k_ in _read_rows(os.path.join(golden_dir, "tag_bits_formula.txt")):
+        assert oracle.tag_bits(int(m_)) == int(k_)
+
+
+def test_tag_keys_bit_layout():
+    # three tables, two identifier bits: table i sits at bit 61 (Eq. 8 with k = 2)
+    x = np.array([0, 1, 5, (1 << 61) - 1, 7, 7, 7], dtype=np.uint64)
+    off = np.array([0, 3, 4, 7], dtype=np.int64)
+    tags = np.array([0, 1, 2], dtype=np.uint8)
+    key, errs = oracle.tag_keys(x, off, tags, 2)
+    assert errs == 0
+    assert key.tolist() == [0, 1, 5, (1 << 61) | ((1 << 61) - 1), (2 << 61) | 7, (2 << 61) | 7, (2 << 61) | 7]
+    assert (key >> np.uint64(63) == 0).all()                       # offset stays a positive int64
+    assert ((key >> np.uint64(61)).astype(np.int64) == [0, 0, 0, 1, 2, 2, 2]).all()   # tag round trip
+    assert ((key & np.uint64((1 << 61) - 1)) == x).all()           # raw ID round trip
+    # same raw ID in two tables -> two different keys
+    assert key[4] != (1 << 61) | 7
+
+
+def test_tag_keys_range_error_is_counted():
+    x = np.array([1 << 61, 3], dtype=np.uint64)     # first ID needs 62 bits, only 61 available
+    key, errs = oracle.tag_keys(x, np.array([0, 2], dtype=np.int64), np.array([1], dtype=np.uint8), 2)
+    assert errs == 1
+    assert key.tolist() == [(1 << 61) | 0, (1 << 61) | 3]
+    with pytest.raises(ValueError):   # table index 4 does not fit in 2 bits
+        oracle.tag_keys(x, np.array([0, 2], dtype=np.int64), np.array([4], dtype=np.uint8), 2)
+
+
+def test_tag_keys_eight_bit_tags_and_empty_fields():
+    rng = np.random.default_rng(1)
+    x = rng.integers(0, 1 << 55, size=100, dtype=np.uint64)
+    off = np.array([0, 0, 40, 40, 100], dtype=np.int64)
+    tags = np.array([9, 200, 3, 31], dtype=np.uint8)
+    key, errs = oracle.tag_keys(x, off, tags, 8)
+    assert errs == 0
+    expect_tag = np.array([200] * 40 + [31] * 60, dtype=np.uint64)
+    assert ((key >> np.uint64(55)) == expect_tag).all()
+    assert ((key & np.uint64((1 << 55) - 1)) == x).all()
+
+
+def test_plan_merge_groups_by_dim_and_dtype():
+    merged_of, n = oracle.plan_merge([64, 16, 64, 128, 16, 64], [0, 0, 0, 0, 1, 0])
+    assert n == 4
+    assert merged_of.tolist() == [0, 1, 0, 2, 3, 0]     # order of first appearance; (16,bf16) != (16,f32)
+
+
+# --------------------------------------------------------------------------- #
+# deduplication (Sec. 3.3)
+# --------------------------------------------------------------------------- #
+def _brute_dedup(keys):
+    keys = [int(k) for k in keys]
+    uniq = []
+    for k in keys:                     # O(N^2): no sort, no hashing
+        if all(k != u for u in uniq):
+            uniq.append(k)
+    for i in range(len(uniq)):         # selection sort
+        for j in range(i + 1, len(uniq)):
+            if uniq[j] < uniq[i]:
+                uniq[i], uniq[j] = uniq[j], uniq[i]
+    inverse = [next(p for p, u in enumerate(uniq) if u == k) for k in keys]
+    counts = [sum(1 for k in keys if k == u) for u in uniq]
+    return uniq, inverse, counts
+
+
+@pytest.mark.parametrize("case", ["random", "all_equal", "all_distinct", "empty", "single", "big_values"])
+def test_dedup_brute_force(case):
+    rng = np.random.default_rng(7)
+    keys = {
+        "random": rng.integers(0, 20, size=64),
+        "all_equal": np.full(33, 12345),
+        "all_distinct": rng.permutation(50) * 3 + 1,
+        "empty": np.zeros(0),
+        "single": np.array([9]),
+        "big_values": rng.integers(0, 4, size=40) * ((1 << 61) + 12345) + (1 << 59),
+    }[case].astype(np.uint64)
+    uniq, inverse, counts = oracle.dedup(keys)
+    bu, bi, bc = _brute_dedup(keys)
+    assert uniq.tolist() == bu and inverse.tolist() == bi and counts.tolist() == bc
+
+
+def test_dedup_matches_torch_unique_and_invariants():
+    w = make_config(1)
+    b = w.next_step(0)
+    keys = np.concatenate(b.ids)
+    uniq, inverse, counts = oracle.dedup(keys)
+    tu, ti, tc = torch.unique(torch.from_numpy(keys.astype(np.int64)), sorted=True, return_inverse=True,
+                              return_counts=True)
+    assert np.array_equal(uniq.astype(np.int64), tu.numpy())
+    assert np.array_equal(inverse.astype(np.int64), ti.numpy())
+    assert np.array_equal(counts.astype(np.int64), tc.numpy())
+    assert np.array_equal(uniq[inverse], keys)                  # every inverse index maps back to its key
+    assert (np.diff(uniq.astype(np.int64)) > 0).all()           # strictly increasing
+    assert counts.sum() == len(keys) and len(uniq) == len(set(keys.tolist()))
+
+
+# --------------------------------------------------------------------------- #
+# row initialisation (reading A2: key-seeded splitmix64 stream -> U[-s, s))
+# --------------------------------------------------------------------------- #
+def test_init_row_from_published_splitmix_vector(golden_dir):
+    outs = [int(r[0], 16) for r in _read_rows(os.path.join(golden_dir, "splitmix64_seed0.txt"))]
+    row = oracle.init_row(0, len(outs), oracle.F32, 0.01)
+    for j, z in enumerate(outs):
+        q = (z >> 40) - (1 << 23)                                  # top 24 bits, centred
+        expect = np.float32(np.float32(q) * (np.float32(0.01) * np.float32(2.0 ** -23)))
+        assert row[j] == expect
+    # a different scale only rescales by an exact power-of-two-free constant: check 1.0 -> q * 2^-23 exactly
+    row1 = oracle.init_row(0, len(outs), oracle.F32, 1.0)
+    for j, z in enumerate(outs):
+        assert float(row1[j]) == ((z >> 40) - (1 << 23)) / float(1 << 23)
+
+
+def test_init_row_distribution_and_determinism():
+    rows = np.stack([oracle.init_row(int(k), 64) for k in range(1000, 3000)])
+    assert rows.min() >= -0.01 and rows.max() < 0.01
+    assert abs(rows.mean()) < 2e-4
+    assert abs(rows.var() - 0.01 ** 2 / 3) < 0.02 * (0.01 ** 2 / 3)     # variance of U(-s, s) is s^2/3
+    assert np.array_equal(oracle.init_row(77, 64), oracle.init_row(77, 64))
+    assert not np.array_equal(oracle.init_row(77, 64), oracle.init_row(78, 64))
+    # a prefix of a longer row is the shorter row: element j depends on (key, j) only
+    assert np.array_equal(oracle.init_row(77, 128)[:64], oracle.init_row(77, 64))
+    # the tag takes part: same raw ID in tables 0 and 1 gives different rows
+    assert not np.array_equal(oracle.init_row(5, 16), oracle.init_row((1 << 61) | 5, 16))
+    # columns are uncorrelated across keys
+    c = np.corrcoef(rows[:, 0], rows[:, 1])[0, 1]
+    assert abs(c) < 0.08
+
+
+def test_bf16_rounding_matches_torch_cast():
+    rng = np.random.default_rng(3)
+    a = np.concatenate([rng.standard_normal(4096).astype(np.float32) * 0.01,
+                        np.array([1.0, 1.00390625, 1.001953125, 1.005859375, -1.001953125], dtype=np.float32)])
+    bits = oracle.float_to_bf16_bits(a)
+    t = torch.from_numpy(a).to(torch.bfloat16)
+    assert np.array_equal(bits.astype(np.int16), t.view(torch.int16).numpy())
+    assert np.array_equal(oracle.bf16_bits_to_float(bits), t.to(torch.float32).numpy())
+    r = oracle.init_row(123, 128, oracle.BF16)
+    assert np.array_equal(r, torch.from_numpy(oracle.init_row(123, 128, oracle.F32)).to(torch.bfloat16).float().numpy())
+
+
+# --------------------------------------------------------------------------- #
+# dynamic table: insert / lookup (Sec. 3.1)
+# --------------------------------------------------------------------------- #
+def test_find_or_insert_lookup_and_counters():
+    t = oracle.Table(32)
+    keys = np.array([11, 5, 11, 99, 5, 11], dtype=np.uint64)
+    ins = t.find_or_insert(keys, step=4)
+    assert ins.tolist() == [1, 1, 0, 1, 0, 0] and len(t) == 3
+    rows = t.lookup(keys)
+    for i, k in enumerate(keys):
+        assert np.array_equal(rows[i], oracle.init_row(int(k), 32))     # lookup after insert = initial row
+    ins2 = t.find_or_insert(np.array([5, 11, 99], dtype=np.uint64), step=5)
+    assert ins2.sum() == 0 and len(t) == 3                             # second call inserts nothing
+    k, v, acc, last_seen, freq = t.export()
+    assert k.tolist() == [5, 11, 99]
+    assert freq.tolist() == [3, 4, 2] and last_seen.tolist() == [5, 5, 5] and (acc == 0).all()
+    assert t.find(np.array([5, 6], dtype=np.uint64)).tolist() == [1, 0]
+    assert (t.lookup(np.array([6], dtype=np.uint64)) == 0).all()        # absent key reads as zeros
+    with pytest.raises(ValueError):
+        t.find_or_insert(np.array([1 << 63], dtype=np.uint64), 0)       # top bit must stay clear
+
+
+def test_prepopulate_equals_one_touch_at_step_zero():
+    a, b = oracle.Table(8), oracle.Table(8)
+    keys = np.array([3, 1, 2], dtype=np.uint64)
+    a.find_or_insert(keys, step=0)
+    b.prepopulate(keys)
+    b.prepopulate(keys[:2])                                            # idempotent
+    for x, y in zip(a.export(), b.export()):
+        assert np.array_equal(x, y)
+
+
+def test_dedup_lookup_expand_equals_direct_lookup():
+    # Sec. 3.3: deduplication only removes repeated transmission; the forward result is unchanged.
+    w = make_config(1)
+    b = w.next_step(0)
+    off = np.concatenate([[0], np.cumsum([len(i) for i in b.ids])]).astype(np.int64)
+    key, _ = oracle.tag_keys(np.concatenate(b.ids), off, np.zeros(4, dtype=np.uint8), oracle.tag_bits(1))
+    t1, t2 = oracle.Table(32), oracle.Table(32)
+    uniq, inverse, _ = oracle.dedup(key)
+    t1.find_or_insert(uniq, 0)
+    E = oracle.expand(t1.lookup(uniq), inverse)
+    E_direct = t2.direct_lookup(key, 0)
+    assert np.array_equal(E, E_direct)
+    assert np.array_equal(t1.export()[0], t2.export()[0]) and np.array_equal(t1.export()[1], t2.export()[1])
+
+
+# --------------------------------------------------------------------------- #
+# gradient aggregation (Sec. 2 "Backward Update")
+# --------------------------------------------------------------------------- #
+def test_segment_reduce_exact_cases_and_conservation():
+    rng = np.random.default_rng(5)
+    n, U, D = 3000, 37, 8
+    inverse = rng.integers(0, U, size=n).astype(np.int32)
+    counts = np.bincount(inverse, minlength=U)
+    ones = oracle.segment_reduce(np.ones((n, D), dtype=np.float32), inverse, U)
+    assert np.array_equal(ones, np.repeat(counts[:, None], D, 1).astype(np.float32))     # G == 1 -> counts
+    gi = rng.integers(-8, 9, size=(n, D)).astype(np.float32)
+    ref = np.zeros((U, D), dtype=np.float64)
+    np.add.at(ref, inverse, gi.astype(np.float64))
+    assert np.array_equal(oracle.segment_reduce(gi, inverse, U), ref.astype(np.float32))  # integers: exact
+    g = normal_grads(1, 0, n, D)
+    red = oracle.segment_reduce(g, inverse, U)
+    ref = np.zeros((U, D), dtype=np.float64)
+    np.add.at(ref, inverse, g.astype(np.float64))
+    assert np.array_equal(red, ref.astype(np.float32))                # float64 accumulate, one rounding
+    assert np.allclose(red.astype(np.float64).sum(0), g.astype(np.float64).sum(0), rtol=0, atol=1e-3)  # conserved
+    # a transposed or mis-indexed operand shows up here: segment u must only see its own rows
+    one_hot = np.zeros((n, D), dtype=np.float32)
+    one_hot[17, 3] = 2.0
+    r = oracle.segment_reduce(one_hot, inverse, U)
+    assert r[inverse[17], 3] == 2.0 and r.sum() == 2.0
+    with pytest.raises(ValueError):
+        oracle.segment_reduce(g, inverse, int(inverse.max()))     # one segment too few
+
+
+# --------------------------------------------------------------------------- #
+# row-wise Adagrad (reading A1)
+# --------------------------------------------------------------------------- #
+def test_adagrad_dim1_equals_torch_optim_adagrad():
+    # With one element per row, row-wise Adagrad is the element-wise Adagrad of the library.
+    keys = np.arange(1, 41, dtype=np.uint64)
+    t = oracle.Table(1)
+    t.find_or_insert(keys, 0)
+    p = torch.nn.Parameter(torch.from_numpy(t.lookup(keys).astype(np.float64)).clone())
+    opt = torch.optim.Adagrad([p], lr=float(np.float32(0.01)), eps=float(np.float32(1e-8)),
+                              initial_accumulator_value=0.0)
+    rng = np.random.default_rng(11)
+    for step in range(5):
+        g = rng.standard_normal((40, 1)).astype(np.float32)
+        t.apply_adagrad(keys, g, 0.01, 1e-8)
+        p.grad = torch.from_numpy(g.astype(np.float64))
+        opt.step()
+        # library result in float64 vs checker (float64 math, stored in float32 each step)
+        assert np.allclose(t.lookup(keys), p.detach().numpy(), rtol=2e-6, atol=1e-9)
+
+
+def test_adagrad_first_step_closed_form_and_untouched_rows():
+    D = 16
+    keys = np.array([10, 20, 30, 40], dtype=np.uint64)
+    t = oracle.Table(D)
+    t.find_or_insert(keys, 0)
+    w0 = t.lookup(keys).astype(np.float64)
+    rng = np.random.default_rng(2)
+    g = rng.standard_normal((2, D)).astype(np.float32)
+    g[1, :] = -3.0                                               # constant-gradient row
+    t.apply_adagrad(keys[[0, 2]], g, 0.01, 1e-8)
+    k, v, acc, _, _ = t.export()
+    # independent recomputation with torch float64 tensor ops
+    gt = torch.from_numpy(g).double()
+    acc_t = (gt * gt).mean(dim=1)
+    w_t = torch.from_numpy(w0[[0, 2]]) - float(np.float32(0.01)) * gt / (acc_t.sqrt() + float(np.float32(1e-8)))[:, None]
+    assert np.array_equal(acc[[0, 2]], acc_t.float().numpy())                 # acc = mean(g^2) on the first step
+    assert np.array_equal(v[[0, 2]], w_t.float().numpy())
+    assert np.allclose(v[2], w0[2] + 0.01, rtol=0, atol=1e-8)                  # w - lr * sign(c), c < 0
+    assert np.array_equal(v[[1, 3]], w0[[1, 3]].astype(np.float32)) and (acc[[1, 3]] == 0).all()   # rows not listed
+    # absent key is skipped, table unchanged in size
+    t.apply_adagrad(np.array([999], dtype=np.uint64), g[:1], 0.01, 1e-8)
+    assert len(t) == 4
+    # second step accumulates: acc = mean(g1^2) + mean(g2^2)
+    t.apply_adagrad(keys[[0]], g[:1], 0.01, 1e-8)
+    assert np.isclose(t.export()[2][0], 2 * float(acc_t[0]), rtol=1e-6)
+
+
+def test_adagrad_bf16_rows_round_once_to_nearest_even():
+    D = 8
+    keys = np.array([7], dtype=np.uint64)
+    t = oracle.Table(D, oracle.BF16)
+    t.find_or_insert(keys, 0)
+    w0 = t.lookup(keys).astype(np.float64)
+    g = (np.arange(D, dtype=np.float32).reshape(1, D) - 3.5) * 0.25
+    t.apply_adagrad(keys, g, 0.01, 1e-8)
+    acc = (g.astype(np.float64) ** 2).mean()
+    w = w0 - float(np.float32(0.01)) * g.astype(np.float64) / (np.sqrt(acc) + float(np.float32(1e-8)))
+    # nearest bf16 neighbours of the exact value: the stored value must be the closer one
+    got = t.lookup(keys).astype(np.float64)
+    lo = torch.from_numpy(w).float()
+    cand = torch.stack([lo.to(torch.bfloat16).double(),
+                        (lo * (1 + 2 ** -7)).to(torch.bfloat16).double(),
+                        (lo * (1 - 2 ** -7)).to(torch.bfloat16).double()])
+    best = cand.gather(0, (cand - torch.from_numpy(w)).abs().argmin(0, keepdim=True))[0].numpy()
+    assert np.array_equal(got, best)
+    assert np.array_equal(oracle.float_to_bf16_bits(got.astype(np.float32)).astype(np.uint32) << 16,
+                          got.astype(np.float32).view(np.uint32))          # stored values are bf16-representable
+
+
+# --------------------------------------------------------------------------- #
+# eviction (reading A9)
+# --------------------------------------------------------------------------- #
+def test_evict_brute_force_predicate_and_reinsert():
+    t = oracle.Table(4)
+    rng = np.random.default_rng(9)
+    for step in range(0, 40):
+        ks = rng.integers(0, 60, size=8).astype(np.uint64)
+        t.find_or_insert(np.unique(ks), step)
+    t.apply_adagrad(np.array([1, 2, 3], dtype=np.uint64), np.ones((3, 4), dtype=np.float32), 0.01)
+    keys, vals, acc, last_seen, freq = t.export()
+    now, ttl, min_freq, grace = 40, 15, 3, 5
+    expect = sorted(int(k) for k, ls, fq in zip(keys, last_seen, freq)
+                    if (now - int(ls) >= ttl) or (int(fq) < min_freq and now - int(ls) >= grace))
+    assert 0 < len(expect) < len(keys)
+    gone = t.evict(now, ttl, min_freq, grace)
+    assert gone.tolist() == expect                                        # ascending, exactly the predicate
+    assert len(t) == len(keys) - len(expect)
+    assert t.find(gone).sum() == 0                                        # evicted keys read as absent
+    k2, v2, a2, _, _ = t.export()
+    keep = ~np.isin(keys, gone)
+    assert np.array_equal(k2, keys[keep]) and np.array_equal(v2, vals[keep]) and np.array_equal(a2, acc[keep])
+    # a later re-insert is a fresh insert
+    ins = t.find_or_insert(gone[:1], 41)
+    assert ins.tolist() == [1]
+    p, v, a, ls, fq = t.peek(gone[:1])
+    assert p[0] == 1 and np.array_equal(v[0], oracle.init_row(int(gone[0]), 4)) and a[0] == 0 and fq[0] == 1
+    # rules are switched off by a zero threshold
+    assert len(t.evict(1000, 0, 0, 0)) == 0
+    n = len(t)
+    assert len(t.evict(1000, 1, 0, 0)) == n and len(t) == 0
+
+
+def test_three_steps_of_tiny_config_conserve_and_stay_finite():
+    """Whole-step sanity on configuration 1: sizes, conservation, monotone accumulator."""
+    w = make_config(1)
+    t = oracle.Table(32)
+    prev_acc = {}
+    for step in range(3):
+        b = w.next_step(step)
+        off = np.concatenate([[0], np.cumsum([len(i) for i in b.ids])]).astype(np.int64)
+        key, _ = oracle.tag_keys(np.concatenate(b.ids), off, np.zeros(4, dtype=np.uint8), 1)
+        uniq, inverse, counts = oracle.dedup(key)
+        t.find_or_insert(uniq, step)
+        G = normal_grads(w.seed, step, len(key), 32)
+        g = oracle.segment_reduce(G, inverse, len(uniq))
+        assert np.allclose(g.sum(0), G.astype(np.float64).sum(0), atol=1e-2)
+        t.apply_adagrad(uniq, g, w.lr, w.eps)
+        keys, vals, acc, last_seen, freq = t.export()
+        assert np.isfinite(vals).all() and (acc >= 0).all()
+        touched = np.isin(keys, uniq)
+        assert (last_seen[touched] == step).all() and (last_seen[~touched] < step).all()
+        for k, a in zip(keys.tolist(), acc.tolist()):
+            assert a >= prev_acc.get(k, 0.0)
+            prev_acc[k] = a
