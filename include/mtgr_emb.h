@@ -1,0 +1,224 @@
+/*
+ * mtgr_emb.h - C ABI of the MI355X sparse-embedding library.
+ *
+ * One GPU's share of the embedding path of a generative recommendation model:
+ *   tagged IDs of merged tables (Sec. 3.2, Eq. 8)  ->  ID deduplication (Sec. 3.3)
+ *   ->  dynamic hash table find-or-insert and row gather (Sec. 3.1)  ->  expand
+ *   (forward);  per-ID gradient aggregation  ->  row-wise Adagrad on the activated
+ *   rows (Sec. 2 "Backward Update", App. C "Gradient Accumulation");  eviction and
+ *   key-structure expansion (Sec. 3.1 "Capacity Expansion").
+ *
+ * Conventions (every entry point):
+ *   - Pointers marked [dev] are device (HBM) addresses, [host] are host addresses.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     are asynchronous on it unless stated; the library never synchronises behind
+ *     the caller's back except in ht_stats.
+ *   - The caller owns every buffer.  The library allocates and frees no device
+ *     memory; it keeps raw pointers handed to it until they are replaced
+ *     (ht_rehash) or the table is destroyed.  A buffer may be released once the
+ *     stream has passed the last call that used it.
+ *   - `n_dev` [dev, may be NULL]: address of the true element count (int64), e.g.
+ *     the n_unique written by emb_dedup.  Kernels are launched over `n_max` and
+ *     read the count on the device, so no host read-back sits on the path.  NULL
+ *     means "exactly n_max elements".
+ *   - Return value: EMB_OK (0) or a negative emb_status.  Conditions that only the
+ *     device can see (probe sequence exhausted, out of row storage) set sticky bits
+ *     in the table's device status word, reported by ht_stats; the affected
+ *     elements get row index -1 and nothing is left half-inserted.
+ *   - Calls on the same table must be ordered (one stream, or events).  Two calls
+ *     that overlap on one table race.
+ *   - Valid keys have bit 63 clear (Eq. 8 keeps the top bit zero).  2^64-1 and
+ *     2^64-2 are reserved for "empty" and "deleted" slots.
+ */
+#ifndef MTGR_EMB_H
+#define MTGR_EMB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct emb_table emb_table_t; /* opaque host object; owns no device memory */
+
+typedef enum { EMB_F32 = 0, EMB_BF16 = 1 } emb_dtype_t;
+
+typedef enum {
+    EMB_OK = 0,
+    EMB_ERR_INVALID_ARG = -1,
+    EMB_ERR_KEY_RANGE = -2,
+    EMB_ERR_WORKSPACE = -3,   /* workspace too small or misaligned */
+    EMB_ERR_NO_STORAGE = -4,  /* no key storage / not enough row chunks registered for n_max inserts */
+    EMB_ERR_HIP = -5,         /* a HIP runtime call failed */
+    EMB_ERR_NEED_REHASH = -6  /* n_max inserts could push the load factor over the limit: ht_rehash first */
+} emb_status_t;
+
+/* bits of ht_stats_t.status (sticky, device-side) */
+#define EMB_DEV_PROBE_EXHAUSTED 1u
+#define EMB_DEV_OUT_OF_ROWS 2u
+#define EMB_DEV_BAD_KEY 4u /* a key with bit 63 set was passed; it got row index -1 */
+
+typedef struct {
+    int32_t dim;             /* elements per embedding row; row bytes must be a multiple of 16 */
+    int32_t dtype;           /* emb_dtype_t of the stored rows */
+    float init_scale;        /* new rows are uniform on [-init_scale, init_scale) */
+    float max_load_factor;   /* expansion trigger, (live+deleted)/capacity; 0 -> 0.75 (Sec. 3.1) */
+    int32_t chunk_rows_log2; /* every value chunk holds 2^this rows */
+    int32_t count_probes;    /* nonzero: maintain the probe/CAS/allocation counters of ht_stats_t */
+} emb_table_desc_t;
+
+typedef struct {
+    uint64_t live;          /* keys present */
+    uint64_t tombstones;    /* deleted slots not yet reclaimed by a rehash */
+    uint64_t capacity;      /* slots in the key structure (power of two) */
+    uint64_t rows_used;     /* high-water mark of the row allocator */
+    uint64_t rows_free;     /* rows on the free list (from evictions) */
+    uint64_t rows_capacity; /* rows in all registered chunks */
+    uint64_t n_rehash;
+    uint64_t n_chunks;
+    uint64_t status;        /* EMB_DEV_* bits */
+    /* counters, only maintained when count_probes != 0 */
+    uint64_t lookups;       /* keys probed by find / find-or-insert */
+    uint64_t probes;        /* 64-byte slot lines inspected for them */
+    uint64_t cas_attempts;
+    uint64_t cas_failures;
+    uint64_t alloc_atomics; /* atomics issued by the wave-aggregated row allocator */
+} ht_stats_t;
+
+/* ------------------------------------------------------------------ host-only planning */
+
+/* Identifier bits for m merged-in tables: k = ceil(log2(m+1))  (Sec. 3.2). */
+int emb_tag_bits(int m);
+
+/* Automated table merging (Sec. 3.2): logical tables with equal (dim, dtype) share one hash
+ * table.  dims/dtypes [host, m entries] -> merged_of [host, m entries] = index of the merged
+ * table, numbered by first appearance.  Returns the number of merged tables or a negative status. */
+int emb_plan_merge(const int32_t* dims, const int32_t* dtypes, int m, int32_t* merged_of);
+
+/* The table's probe sequence on the host, for checking Theorem 1: returns the index of the t-th
+ * 8-slot line visited for `key` in a key structure of 2^capacity_log2 slots (capacity_log2 >= 3).
+ * For t = 0 .. lines-1 the values are a permutation of the lines (odd stride, power-of-two size). */
+uint64_t ht_probe_line(uint64_t key, int capacity_log2, uint64_t t);
+
+const char* emb_status_string(int status);
+
+/* ------------------------------------------------------------------ table life cycle (Sec. 3.1) */
+
+/* Bytes of device memory the table needs for its counters and chunk directory. */
+size_t emb_table_state_bytes(void);
+
+/* Create a table.  state [dev]: emb_table_state_bytes() bytes, 256-byte aligned, zeroed here
+ * (asynchronously on `stream`).  The table starts without key storage and without chunks. */
+int emb_table_create(emb_table_t** out, const emb_table_desc_t* desc, void* state, size_t state_bytes,
+                     void* stream);
+int emb_table_destroy(emb_table_t* t);
+
+/* Give an EMPTY table its key structure: keys [dev, 2^capacity_log2 x u64] and rows
+ * [dev, 2^capacity_log2 x u32], 6 <= capacity_log2 <= 30.  Both are filled with the empty marker. */
+int ht_set_key_storage(emb_table_t* t, uint64_t* keys, uint32_t* rows, int capacity_log2, void* stream);
+
+/* Register one more value chunk of 2^chunk_rows_log2 rows (Sec. 3.1: chunked embedding
+ * structure; keep a spare chunk registered so inserts never wait for an allocation).
+ * values [dev]: rows x dim elements of the table dtype;  acc [dev]: rows x f32 Adagrad
+ * accumulators;  last_seen, freq [dev]: rows x u32;  free_list [dev]: rows x u32 scratch for the
+ * row free list.  Contents need no initialisation. */
+int ht_add_chunk(emb_table_t* t, void* values, float* acc, uint32_t* last_seen, uint32_t* freq,
+                 uint32_t* free_list, void* stream);
+
+/* Host-side capacity planning from the counts last seen by ht_stats plus everything issued since.
+ * n_incoming = upper bound of keys the next find-or-insert may add.
+ * *new_capacity_log2 = 0 if the key structure is fine, else the size to rehash to: the same size
+ * when purging deleted slots is enough, otherwise doubled until (live+n_incoming)/capacity is at
+ * most half the load-factor limit.  *chunks_needed = chunks to add so that n_incoming rows fit. */
+int ht_plan(emb_table_t* t, int64_t n_incoming, int* new_capacity_log2, int* chunks_needed);
+
+/* Capacity expansion (Sec. 3.1): move every live (key,row) pair into new key storage of
+ * 2^new_capacity_log2 slots, dropping deleted slots.  Embedding rows do not move.  The old
+ * arrays are no longer referenced once this call's work on `stream` has finished. */
+int ht_rehash(emb_table_t* t, uint64_t* new_keys, uint32_t* new_rows, int new_capacity_log2, void* stream);
+
+/* Copy the counters to *out [host].  Synchronises `stream`. */
+int ht_stats(emb_table_t* t, ht_stats_t* out, void* stream);
+
+/* ------------------------------------------------------------------ forward */
+
+/* Eq. 8: key[e] = (field_tag[f] << (63 - tag_bits)) | x[e] for field_off[f] <= e < field_off[f+1].
+ * x, key_out [dev, n];  field_off [dev, n_fields+1, int64, field_off[n_fields] == n];
+ * field_tag [dev, n_fields] = 0-based logical table index.  0 <= tag_bits <= 16, n_fields <= 4096.
+ * A raw ID that needs more than 63-tag_bits bits is counted in *err_count [dev, int64, zeroed by
+ * this call] and wrapped into range. */
+int emb_tag_keys(const uint64_t* x, const int64_t* field_off, const uint8_t* field_tag, int n_fields,
+                 int64_t n, int tag_bits, uint64_t* key_out, int64_t* err_count, void* stream);
+
+/* Stage-1 deduplication (Sec. 3.3).  key [dev, n] ->
+ *   uniq [dev, n]: distinct keys ascending, first *n_unique entries valid;
+ *   inverse [dev, n, int32]: uniq[inverse[i]] == key[i];
+ *   counts [dev, n, int32, optional]: occurrences of uniq[u];
+ *   perm [dev, n, int32, optional]: positions ordered by (key, position); the positions of
+ *     uniq[u] are perm[seg_off[u] .. seg_off[u+1]);
+ *   seg_off [dev, n+1, int32, optional];
+ *   n_unique [dev, int64].
+ * workspace [dev, 256-byte aligned] of at least emb_dedup_workspace_bytes(n).  n < 2^31. */
+size_t emb_dedup_workspace_bytes(int64_t n);
+int emb_dedup(const uint64_t* key, int64_t n, uint64_t* uniq, int32_t* inverse, int32_t* counts,
+              int32_t* perm, int32_t* seg_off, int64_t* n_unique, void* workspace, size_t workspace_bytes,
+              void* stream);
+
+/* Find each key; insert the absent ones (claim a slot, allocate a row, initialise the row from
+ * the key, acc = 0).  Every element counts one touch: freq += 1, last_seen = step.
+ * key [dev], row_idx [dev, int32] <- row of each key (-1 on a device-side failure),
+ * inserted [dev, u8, optional] <- 1 for the element that created its entry.  Duplicate keys in
+ * one call are allowed and share one row.  Fails with EMB_ERR_NEED_REHASH / EMB_ERR_NO_STORAGE
+ * (nothing launched) when n_max inserts might not fit: see ht_plan. */
+int ht_find_or_insert(emb_table_t* t, const uint64_t* key, const int64_t* n_dev, int64_t n_max, uint32_t step,
+                      int32_t* row_idx, uint8_t* inserted, void* stream);
+
+/* Read-only lookup: row_idx[i] = row of key[i], or -1 if absent. */
+int ht_find(emb_table_t* t, const uint64_t* key, const int64_t* n_dev, int64_t n_max, int32_t* row_idx,
+            void* stream);
+
+/* out[u,:] = values[row_idx[u],:] in the table dtype, row-major [n, dim]; row -1 reads as zeros. */
+int ht_gather(emb_table_t* t, const int32_t* row_idx, const int64_t* n_dev, int64_t n_max, void* out,
+              void* stream);
+
+/* out[i,:] = uniq_rows[inverse[i],:]  (undo the deduplication).  dtype: element type of both. */
+int emb_expand(const void* uniq_rows, const int32_t* inverse, int64_t n, int dim, int dtype, void* out,
+               void* stream);
+
+/* ------------------------------------------------------------------ backward */
+
+/* reduced[u,:] = sum over positions i with inverse[i] == u of grad[i,:], fp32 accumulation,
+ * fp32 output [*n_unique, dim].  grad [dev, n x dim] of grad_dtype.  perm and inverse as written
+ * by emb_dedup for the same keys.  The order of additions is fixed (deterministic). */
+size_t grad_segment_reduce_workspace_bytes(int64_t n, int dim);
+int grad_segment_reduce(const void* grad, int grad_dtype, const int32_t* inverse, const int32_t* perm, int64_t n,
+                        int dim, float* reduced, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Row-wise Adagrad on the listed rows only:
+ *   acc += mean_j(g_j^2);  w_j -= lr * g_j / (sqrt(acc) + eps).
+ * row_idx [dev]: distinct rows (as returned for deduplicated keys); -1 entries are skipped.
+ * reduced [dev, n x dim, f32]. */
+int ht_apply_adagrad(emb_table_t* t, const int32_t* row_idx, const float* reduced, const int64_t* n_dev,
+                     int64_t n_max, float lr, float eps, void* stream);
+
+/* ------------------------------------------------------------------ maintenance */
+
+/* Delete every key that was not touched for `ttl` steps (rule active when ttl > 0) or that was
+ * touched fewer than `min_freq` times and not within the last `grace` steps (active when
+ * min_freq > 0).  Slots become deleted markers, rows return to the free list.
+ * evicted_keys [dev, evicted_cap, optional]: the deleted keys in no particular order (at most
+ * evicted_cap are stored);  n_evicted [dev, int64]: how many were deleted. */
+int ht_evict(emb_table_t* t, uint32_t now, uint32_t ttl, uint32_t min_freq, uint32_t grace,
+             uint64_t* evicted_keys, int64_t evicted_cap, int64_t* n_evicted, void* stream);
+
+/* Dump the table in no particular order (for checks): up to `cap` entries of keys [dev],
+ * values [dev, cap x dim, table dtype], acc, last_seen, freq [dev]; any of the last four may be
+ * NULL.  *n [dev, int64] <- number of live entries. */
+int ht_export(emb_table_t* t, uint64_t* keys, void* values, float* acc, uint32_t* last_seen, uint32_t* freq,
+              int64_t cap, int64_t* n, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MTGR_EMB_H */

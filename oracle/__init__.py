@@ -140,8 +140,8 @@ class Table:
             raise ValueError("bad table description")
 
     def __del__(self):
-        if getattr(self, "_h", None):
-            lib().orc_table_destroy(self._h)
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.orc_table_destroy(self._h)
             self._h = None
 
     def __len__(self) -> int:

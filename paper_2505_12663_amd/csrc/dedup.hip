@@ -1,0 +1,486 @@
+// ID tagging (Eq. 8) and stage-1 deduplication (Sec. 3.3) for gfx950.
+//
+// Dedup = stable LSD radix sort of (key, position) pairs, 8 bits per pass, followed by a
+// head-flag scan.  Digits in which all keys agree are found on the device (OR/AND reduction of
+// the keys) and their passes skipped: tagged keys carry a few identifier bits at the top and a
+// 40..48-bit ID at the bottom, so 2-3 of the 8 passes vanish.  Each pass is three kernels
+// (per-tile histogram, per-digit scan over tiles, scatter) - no kernel waits on another block.
+// The scatter ranks a tile's keys with wave-wide ballots (no LDS atomics), reorders the tile in
+// LDS and writes runs of equal digit contiguously.
+#include "common.hpp"
+
+using namespace mtgr;
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kItems = 16;                    // keys per thread
+constexpr int kTile = kThreads * kItems;      // 4096 keys per block
+constexpr int kWaves = kThreads / kWave;      // 4
+constexpr int kRadix = 256;
+constexpr int kPasses = 8;
+
+struct DdHeader {
+    unsigned long long or_mask, and_mask;
+    int active[kPasses];
+    int src[kPasses];   // 0 = caller's keys (implicit position), 1 = buffer A, 2 = buffer B
+    int dst[kPasses];
+    int final_sel;
+    int pad;
+    long long n_unique;
+};
+
+struct DdBuffers {
+    const uint64_t* in_keys;
+    uint64_t* ka;
+    uint64_t* kb;
+    uint32_t* ia;
+    uint32_t* ib;
+};
+
+__device__ inline const uint64_t* sel_keys(const DdBuffers& b, int s) { return s == 0 ? b.in_keys : (s == 1 ? b.ka : b.kb); }
+__device__ inline const uint32_t* sel_idx(const DdBuffers& b, int s) { return s == 1 ? b.ia : (s == 2 ? b.ib : nullptr); }
+
+// ---------------------------------------------------------------------------- tagging
+__global__ __launch_bounds__(kThreads) void k_tag(const uint64_t* __restrict__ x, const int64_t* __restrict__ field_off,
+                                                 const uint8_t* __restrict__ field_tag, int n_fields, int64_t n,
+                                                 int shift, uint64_t* __restrict__ key_out,
+                                                 unsigned long long* err_count) {
+    extern __shared__ int64_t s_off[]; // n_fields + 1 offsets
+    for (int f = threadIdx.x; f <= n_fields; f += kThreads) s_off[f] = field_off[f];
+    __syncthreads();
+    const uint64_t low_mask = (1ull << shift) - 1ull;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    unsigned errs = 0;
+    for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < n; e += stride) {
+        // last field whose start is <= e
+        int lo = 0, hi = n_fields; // invariant: s_off[lo] <= e < s_off[hi]
+        while (hi - lo > 1) {
+            int mid = (lo + hi) >> 1;
+            if (s_off[mid] <= e) lo = mid; else hi = mid;
+        }
+        uint64_t v = x[e];
+        if (v > low_mask) {
+            ++errs;
+            v &= low_mask;
+        }
+        key_out[e] = ((uint64_t)field_tag[lo] << shift) | v;
+    }
+    for (int o = 32; o > 0; o >>= 1) errs += __shfl_xor(errs, o, kWave);
+    if (errs && lane_id() == 0) atomicAdd(err_count, (unsigned long long)errs);
+}
+
+__global__ void k_zero64(unsigned long long* p) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) *p = 0ull;
+}
+
+// ---------------------------------------------------------------------------- which digits vary
+__global__ void k_dd_init(DdHeader* h) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        h->or_mask = 0ull;
+        h->and_mask = ~0ull;
+        h->n_unique = 0;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void k_dd_masks(const uint64_t* __restrict__ key, int64_t n, DdHeader* h) {
+    uint64_t o = 0ull, a = ~0ull;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
+        uint64_t k = key[i];
+        o |= k;
+        a &= k;
+    }
+    for (int s = 32; s > 0; s >>= 1) {
+        o |= shfl64(o, lane_id() ^ s);
+        a &= shfl64(a, lane_id() ^ s);
+    }
+    if (lane_id() == 0) {
+        atomicOr(&h->or_mask, (unsigned long long)o);
+        atomicAnd(&h->and_mask, (unsigned long long)a);
+    }
+}
+
+__global__ void k_dd_plan(DdHeader* h) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const unsigned long long varying = h->or_mask ^ h->and_mask;
+    int cur = 0;
+    for (int p = 0; p < kPasses; ++p) {
+        const bool act = ((varying >> (8 * p)) & 0xFFull) != 0ull;
+        h->active[p] = act;
+        h->src[p] = cur;
+        const int d = (cur == 1) ? 2 : 1;
+        h->dst[p] = d;
+        if (act) cur = d;
+    }
+    h->final_sel = cur;
+}
+
+// ---------------------------------------------------------------------------- radix pass
+__device__ inline unsigned digit_of(uint64_t k, int pass) { return (unsigned)(k >> (8 * pass)) & 0xFFu; }
+
+// tile element e = wave*1024 + item*64 + lane
+__global__ __launch_bounds__(kThreads) void k_rs_hist(DdBuffers b, const DdHeader* __restrict__ h, int pass, int64_t n,
+                                                     unsigned n_tiles, unsigned* __restrict__ tile_hist) {
+    if (!h->active[pass]) return;
+    __shared__ unsigned s_hist[kRadix];
+    s_hist[threadIdx.x] = 0u;
+    __syncthreads();
+    const uint64_t* keys = sel_keys(b, h->src[pass]);
+    const int64_t base = (int64_t)blockIdx.x * kTile + (threadIdx.x / kWave) * (kWave * kItems) + (threadIdx.x % kWave);
+#pragma unroll
+    for (int it = 0; it < kItems; ++it) {
+        int64_t e = base + it * kWave;
+        if (e < n) atomicAdd(&s_hist[digit_of(keys[e], pass)], 1u);
+    }
+    __syncthreads();
+    tile_hist[(size_t)threadIdx.x * n_tiles + blockIdx.x] = s_hist[threadIdx.x];
+}
+
+// block d: exclusive scan of digit d's counts over the tiles; total -> digit_total[d]
+__global__ __launch_bounds__(kThreads) void k_rs_scan(const DdHeader* __restrict__ h, int pass, unsigned n_tiles,
+                                                     unsigned* __restrict__ tile_hist,
+                                                     unsigned* __restrict__ digit_total) {
+    if (!h->active[pass]) return;
+    __shared__ unsigned s_wave[kWaves];
+    __shared__ unsigned s_carry;
+    unsigned* row = tile_hist + (size_t)blockIdx.x * n_tiles;
+    const int lane = lane_id(), wave = threadIdx.x / kWave;
+    if (threadIdx.x == 0) s_carry = 0u;
+    __syncthreads();
+    for (unsigned base = 0; base < n_tiles; base += kThreads) {
+        const unsigned i = base + threadIdx.x;
+        const unsigned v = i < n_tiles ? row[i] : 0u;
+        unsigned incl = v;
+        for (int o = 1; o < kWave; o <<= 1) {
+            unsigned t = __shfl_up(incl, o, kWave);
+            if (lane >= o) incl += t;
+        }
+        if (lane == kWave - 1) s_wave[wave] = incl;
+        __syncthreads();
+        unsigned woff = 0;
+        for (int w = 0; w < wave; ++w) woff += s_wave[w];
+        const unsigned carry = s_carry;
+        if (i < n_tiles) row[i] = carry + woff + incl - v;
+        __syncthreads();
+        if (threadIdx.x == kThreads - 1) s_carry = carry + woff + incl;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) digit_total[blockIdx.x] = s_carry;
+}
+
+__global__ __launch_bounds__(kThreads) void k_rs_scatter(DdBuffers b, const DdHeader* __restrict__ h, int pass,
+                                                        int64_t n, unsigned n_tiles,
+                                                        const unsigned* __restrict__ tile_hist,
+                                                        const unsigned* __restrict__ digit_total) {
+    if (!h->active[pass]) return;
+    __shared__ uint64_t s_key[kTile];
+    __shared__ uint32_t s_idx[kTile];
+    __shared__ unsigned s_cnt[kWaves][kRadix];   // per wave: keys seen per digit, then exclusive offsets
+    __shared__ unsigned s_start[kRadix];         // first position of digit d in the sorted tile
+    __shared__ long long s_delta[kRadix];        // global position - tile position for digit d
+
+    const int src = h->src[pass], dst = h->dst[pass];
+    const uint64_t* in_k = sel_keys(b, src);
+    const uint32_t* in_i = sel_idx(b, src);
+    uint64_t* out_k = dst == 1 ? b.ka : b.kb;
+    uint32_t* out_i = dst == 1 ? b.ia : b.ib;
+
+    const int lane = lane_id(), wave = threadIdx.x / kWave;
+    const int64_t tile_base = (int64_t)blockIdx.x * kTile;
+    const int tile_n = (int)((n - tile_base) < kTile ? (n - tile_base) : kTile);
+    for (int w = 0; w < kWaves; ++w) s_cnt[w][threadIdx.x] = 0u;
+    __syncthreads();
+
+    uint64_t key[kItems];
+    uint32_t idx[kItems];
+    unsigned rnk[kItems];
+    const int e0 = wave * (kWave * kItems) + lane;
+#pragma unroll
+    for (int it = 0; it < kItems; ++it) {
+        const int e = e0 + it * kWave;
+        const bool ok = e < tile_n;
+        key[it] = ok ? in_k[tile_base + e] : ~0ull;
+        idx[it] = ok ? (in_i ? in_i[tile_base + e] : (uint32_t)(tile_base + e)) : 0xFFFFFFFFu;
+    }
+    // rank of every key among the keys of equal digit that precede it in this wave's 1024
+#pragma unroll
+    for (int it = 0; it < kItems; ++it) {
+        const unsigned d = digit_of(key[it], pass); // padding keys are all ones: digit 255, at the tile's end
+        uint64_t peers = ~0ull;
+#pragma unroll
+        for (int bit = 0; bit < 8; ++bit) {
+            const uint64_t m = __ballot((d >> bit) & 1u);
+            peers &= ((d >> bit) & 1u) ? m : ~m;
+        }
+        const unsigned before = s_cnt[wave][d];
+        rnk[it] = before + (unsigned)rank_in(peers, lane);
+        if (rank_in(peers, lane) == 0) s_cnt[wave][d] = before + (unsigned)__popcll(peers);
+    }
+    __syncthreads();
+    // thread d: per-wave exclusive offsets of digit d, tile total, global base
+    {
+        const unsigned d = threadIdx.x;
+        unsigned run = 0;
+        for (int w = 0; w < kWaves; ++w) {
+            const unsigned c = s_cnt[w][d];
+            s_cnt[w][d] = run;
+            run += c;
+        }
+        // exclusive scans over the 256 digits: tile totals (-> s_start) and global totals
+        unsigned incl_t = run, incl_g = digit_total[d];
+        const unsigned tot_g = incl_g;
+        for (int o = 1; o < kWave; o <<= 1) {
+            unsigned a = __shfl_up(incl_t, o, kWave), g = __shfl_up(incl_g, o, kWave);
+            if (lane >= o) {
+                incl_t += a;
+                incl_g += g;
+            }
+        }
+        __shared__ unsigned s_wt[kWaves], s_wg[kWaves];
+        if (lane == kWave - 1) {
+            s_wt[wave] = incl_t;
+            s_wg[wave] = incl_g;
+        }
+        __syncthreads();
+        unsigned off_t = 0, off_g = 0;
+        for (int w = 0; w < wave; ++w) {
+            off_t += s_wt[w];
+            off_g += s_wg[w];
+        }
+        const unsigned start = off_t + incl_t - run;
+        const unsigned gbase = off_g + incl_g - tot_g;
+        s_start[d] = start;
+        s_delta[d] = (long long)gbase + (long long)tile_hist[(size_t)d * n_tiles + blockIdx.x] - (long long)start;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < kItems; ++it) {
+        const unsigned d = digit_of(key[it], pass);
+        const unsigned pos = s_start[d] + s_cnt[wave][d] + rnk[it];
+        s_key[pos] = key[it];
+        s_idx[pos] = idx[it];
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < tile_n; e += kThreads) {
+        const uint64_t k = s_key[e];
+        const long long g = s_delta[digit_of(k, pass)] + e;
+        out_k[g] = k;
+        out_i[g] = s_idx[e];
+    }
+}
+
+// ---------------------------------------------------------------------------- heads -> unique
+// head(j) = key differs from its predecessor in sorted order
+__device__ inline uint64_t sorted_key(const uint64_t* keys, int64_t j) { return keys[j]; }
+
+__global__ __launch_bounds__(kThreads) void k_heads_count(DdBuffers b, const DdHeader* __restrict__ h, int64_t n,
+                                                         unsigned* __restrict__ tile_heads) {
+    const uint64_t* keys = sel_keys(b, h->final_sel);
+    __shared__ unsigned s_w[kWaves];
+    const int lane = lane_id(), wave = threadIdx.x / kWave;
+    const int64_t base = (int64_t)blockIdx.x * kTile + wave * (kWave * kItems) + lane;
+    unsigned cnt = 0;
+#pragma unroll
+    for (int it = 0; it < kItems; ++it) {
+        const int64_t j = base + it * kWave;
+        if (j < n) cnt += (j == 0 || keys[j] != keys[j - 1]) ? 1u : 0u;
+    }
+    for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, kWave);
+    if (lane == 0) s_w[wave] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0) tile_heads[blockIdx.x] = s_w[0] + s_w[1] + s_w[2] + s_w[3];
+}
+
+// single block: exclusive scan of the per-tile head counts; total = number of distinct keys
+__global__ __launch_bounds__(1024) void k_heads_scan(unsigned* __restrict__ tile_heads, unsigned n_tiles, DdHeader* h,
+                                                    int64_t* n_unique_out) {
+    __shared__ unsigned s_wave[16];
+    __shared__ unsigned s_carry;
+    const int lane = lane_id(), wave = threadIdx.x / kWave;
+    if (threadIdx.x == 0) s_carry = 0u;
+    __syncthreads();
+    for (unsigned base = 0; base < n_tiles; base += 1024) {
+        const unsigned i = base + threadIdx.x;
+        const unsigned v = i < n_tiles ? tile_heads[i] : 0u;
+        unsigned incl = v;
+        for (int o = 1; o < kWave; o <<= 1) {
+            unsigned t = __shfl_up(incl, o, kWave);
+            if (lane >= o) incl += t;
+        }
+        if (lane == kWave - 1) s_wave[wave] = incl;
+        __syncthreads();
+        unsigned woff = 0;
+        for (int w = 0; w < wave; ++w) woff += s_wave[w];
+        const unsigned carry = s_carry;
+        if (i < n_tiles) tile_heads[i] = carry + woff + incl - v;
+        __syncthreads();
+        if (threadIdx.x == 1023) s_carry = carry + woff + incl;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        h->n_unique = (long long)s_carry;
+        *n_unique_out = (int64_t)s_carry;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void k_emit(DdBuffers b, const DdHeader* __restrict__ h, int64_t n,
+                                                  const unsigned* __restrict__ tile_heads, uint64_t* __restrict__ uniq,
+                                                  int32_t* __restrict__ inverse, int32_t* __restrict__ perm,
+                                                  int32_t* __restrict__ seg_off) {
+    const int sel = h->final_sel;
+    const uint64_t* keys = sel_keys(b, sel);
+    const uint32_t* idxs = sel_idx(b, sel);
+    __shared__ unsigned s_w[kWaves];
+    const int lane = lane_id(), wave = threadIdx.x / kWave;
+    const int64_t base = (int64_t)blockIdx.x * kTile + wave * (kWave * kItems) + lane;
+    // pass 1: heads per wave
+    uint64_t key[kItems];
+    unsigned headbits = 0; // bit it = element is a head
+    unsigned cnt = 0;
+#pragma unroll
+    for (int it = 0; it < kItems; ++it) {
+        const int64_t j = base + it * kWave;
+        key[it] = j < n ? keys[j] : 0ull;
+        const bool head = j < n && (j == 0 || key[it] != keys[j - 1]);
+        headbits |= head ? (1u << it) : 0u;
+        cnt += head ? 1u : 0u;
+    }
+    unsigned wave_total = cnt;
+    for (int o = 32; o > 0; o >>= 1) wave_total += __shfl_xor(wave_total, o, kWave);
+    if (lane == 0) s_w[wave] = wave_total;
+    __syncthreads();
+    unsigned running = tile_heads[blockIdx.x];
+    for (int w = 0; w < wave; ++w) running += s_w[w];
+    // pass 2: element order inside the wave is (it, lane)
+#pragma unroll
+    for (int it = 0; it < kItems; ++it) {
+        const int64_t j = base + it * kWave;
+        const bool head = (headbits >> it) & 1u;
+        const uint64_t m = __ballot(head);
+        const unsigned seg = running + (unsigned)rank_in(m, lane) + (head ? 1u : 0u) - 1u; // heads up to and incl. j, minus 1
+        running += (unsigned)__popcll(m);
+        if (j < n) {
+            const uint32_t p = idxs ? idxs[j] : (uint32_t)j;
+            inverse[p] = (int32_t)seg;
+            if (perm) perm[j] = (int32_t)p;
+            if (head) {
+                uniq[seg] = key[it];
+                if (seg_off) seg_off[seg] = (int32_t)j;
+            }
+            if (j == n - 1 && seg_off) seg_off[seg + 1] = (int32_t)n;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void k_counts(const int32_t* __restrict__ seg_off, const DdHeader* __restrict__ h,
+                                                    int32_t* __restrict__ counts) {
+    const int64_t u = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (u < h->n_unique) counts[u] = seg_off[u + 1] - seg_off[u];
+}
+
+__global__ void k_empty_result(int64_t* n_unique, int32_t* seg_off) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        *n_unique = 0;
+        if (seg_off) seg_off[0] = 0;
+    }
+}
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct DdLayout {
+    size_t header, ka, kb, ia, ib, tile_hist, digit_total, tile_heads, seg_off, total;
+    unsigned n_tiles;
+};
+DdLayout dd_layout(int64_t n) {
+    DdLayout L;
+    L.n_tiles = (unsigned)((n + kTile - 1) / kTile);
+    size_t o = 0;
+    L.header = o; o = align_up(o + sizeof(DdHeader), 256);
+    L.ka = o; o = align_up(o + (size_t)n * 8, 256);
+    L.kb = o; o = align_up(o + (size_t)n * 8, 256);
+    L.ia = o; o = align_up(o + (size_t)n * 4, 256);
+    L.ib = o; o = align_up(o + (size_t)n * 4, 256);
+    L.tile_hist = o; o = align_up(o + (size_t)kRadix * L.n_tiles * 4, 256);
+    L.digit_total = o; o = align_up(o + kRadix * 4, 256);
+    L.tile_heads = o; o = align_up(o + (size_t)L.n_tiles * 4, 256);
+    L.seg_off = o; o = align_up(o + (size_t)(n + 1) * 4, 256);
+    L.total = o;
+    return L;
+}
+
+} // namespace
+
+extern "C" {
+
+int emb_tag_keys(const uint64_t* x, const int64_t* field_off, const uint8_t* field_tag, int n_fields,
+                 int64_t n, int tag_bits, uint64_t* key_out, int64_t* err_count, void* stream) {
+    if (n < 0 || n_fields < 0 || n_fields > 4096 || tag_bits < 0 || tag_bits > 16 || !err_count) return EMB_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(k_zero64, dim3(1), dim3(64), 0, s, reinterpret_cast<unsigned long long*>(err_count));
+    MTGR_LAUNCH_CHECK();
+    if (n == 0) return EMB_OK;
+    if (!x || !field_off || !field_tag || !key_out || n_fields == 0) return EMB_ERR_INVALID_ARG;
+    unsigned grid = (unsigned)((n + kThreads * 4 - 1) / (kThreads * 4));
+    if (grid > 65536u) grid = 65536u;
+    hipLaunchKernelGGL(k_tag, dim3(grid), dim3(kThreads), (size_t)(n_fields + 1) * sizeof(int64_t), s, x, field_off,
+                       field_tag, n_fields, n, 63 - tag_bits, key_out, reinterpret_cast<unsigned long long*>(err_count));
+    MTGR_LAUNCH_CHECK();
+    return EMB_OK;
+}
+
+size_t emb_dedup_workspace_bytes(int64_t n) {
+    if (n < 0) return 0;
+    return dd_layout(n < 1 ? 1 : n).total;
+}
+
+int emb_dedup(const uint64_t* key, int64_t n, uint64_t* uniq, int32_t* inverse, int32_t* counts,
+              int32_t* perm, int32_t* seg_off, int64_t* n_unique, void* workspace, size_t workspace_bytes,
+              void* stream) {
+    if (n < 0 || n > 0x7FFFFFFFll || !n_unique) return EMB_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (n == 0) {
+        hipLaunchKernelGGL(k_empty_result, dim3(1), dim3(64), 0, s, n_unique, seg_off);
+        MTGR_LAUNCH_CHECK();
+        return EMB_OK;
+    }
+    if (!key || !uniq || !inverse) return EMB_ERR_INVALID_ARG;
+    const DdLayout L = dd_layout(n);
+    if (!workspace || workspace_bytes < L.total || (reinterpret_cast<uintptr_t>(workspace) & 255)) return EMB_ERR_WORKSPACE;
+    char* w = static_cast<char*>(workspace);
+    DdHeader* hdr = reinterpret_cast<DdHeader*>(w + L.header);
+    DdBuffers b;
+    b.in_keys = key;
+    b.ka = reinterpret_cast<uint64_t*>(w + L.ka);
+    b.kb = reinterpret_cast<uint64_t*>(w + L.kb);
+    b.ia = reinterpret_cast<uint32_t*>(w + L.ia);
+    b.ib = reinterpret_cast<uint32_t*>(w + L.ib);
+    unsigned* tile_hist = reinterpret_cast<unsigned*>(w + L.tile_hist);
+    unsigned* digit_total = reinterpret_cast<unsigned*>(w + L.digit_total);
+    unsigned* tile_heads = reinterpret_cast<unsigned*>(w + L.tile_heads);
+    int32_t* seg = seg_off ? seg_off : reinterpret_cast<int32_t*>(w + L.seg_off);
+    const unsigned n_tiles = L.n_tiles;
+
+    hipLaunchKernelGGL(k_dd_init, dim3(1), dim3(64), 0, s, hdr);
+    unsigned mgrid = n_tiles < 2048u ? n_tiles : 2048u;
+    hipLaunchKernelGGL(k_dd_masks, dim3(mgrid), dim3(kThreads), 0, s, key, n, hdr);
+    hipLaunchKernelGGL(k_dd_plan, dim3(1), dim3(64), 0, s, hdr);
+    MTGR_LAUNCH_CHECK();
+    for (int p = 0; p < kPasses; ++p) {
+        hipLaunchKernelGGL(k_rs_hist, dim3(n_tiles), dim3(kThreads), 0, s, b, hdr, p, n, n_tiles, tile_hist);
+        hipLaunchKernelGGL(k_rs_scan, dim3(kRadix), dim3(kThreads), 0, s, hdr, p, n_tiles, tile_hist, digit_total);
+        hipLaunchKernelGGL(k_rs_scatter, dim3(n_tiles), dim3(kThreads), 0, s, b, hdr, p, n, n_tiles, tile_hist, digit_total);
+        MTGR_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(k_heads_count, dim3(n_tiles), dim3(kThreads), 0, s, b, hdr, n, tile_heads);
+    hipLaunchKernelGGL(k_heads_scan, dim3(1), dim3(1024), 0, s, tile_heads, n_tiles, hdr, n_unique);
+    hipLaunchKernelGGL(k_emit, dim3(n_tiles), dim3(kThreads), 0, s, b, hdr, n, tile_heads, uniq, inverse, perm, seg);
+    MTGR_LAUNCH_CHECK();
+    if (counts) {
+        hipLaunchKernelGGL(k_counts, dim3((unsigned)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, seg, hdr, counts);
+        MTGR_LAUNCH_CHECK();
+    }
+    return EMB_OK;
+}
+
+} // extern "C"

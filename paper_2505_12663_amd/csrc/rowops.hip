@@ -1,0 +1,454 @@
+// Row movement and row arithmetic of the embedding path for gfx950: gather of table rows,
+// expand by inverse index, deterministic gradient segment-reduce, row-wise Adagrad.
+//
+// All of it is HBM-bound.  A row is moved as 16-byte vectors by a sub-wave of LPR lanes
+// (LPR = row bytes / 16 rounded up to a power of two), so one wave instruction covers 64/LPR
+// whole rows with fully used 64..128-byte segments, and several rows are in flight per lane
+// group before the first is consumed.
+#include "common.hpp"
+
+using namespace mtgr;
+
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kUnroll = 4;
+
+__device__ inline const char* chunk_row_cptr(const HtView& v, uint32_t row) {
+    const char* base = static_cast<const char*>(v.st->values[row >> v.chunk_log2]);
+    return base + (size_t)(row & ((1u << v.chunk_log2) - 1u)) * (size_t)v.row_bytes;
+}
+
+// ---------------------------------------------------------------------------- gather / expand
+// One wave owns 64 consecutive output rows; lane l reads index l once, the LPR-lane groups then
+// take the rows in turn.  SRC_TABLE: source row = chunked table row (index -1 -> zeros);
+// otherwise source row = base + index * row_bytes.
+template <int LPR, bool SRC_TABLE, bool NT_STORE>
+__global__ __launch_bounds__(kBlock) void k_copy_rows(HtView v, const char* __restrict__ src_base,
+                                                      const int32_t* __restrict__ index, const int64_t* n_dev,
+                                                      int64_t n_max, int row_bytes, char* __restrict__ out) {
+    const int64_t n = read_count(n_dev, n_max);
+    const int lane = lane_id();
+    const int64_t wave_base = (int64_t)blockIdx.x * kBlock + (threadIdx.x & ~(kWave - 1));
+    if (wave_base >= n) return;
+    constexpr int kGroups = kWave / LPR;          // rows per wave instruction
+    const int sub = lane % LPR, grp = lane / LPR;
+    const int vecs = row_bytes / 16;
+    const bool lane_on = sub < vecs;
+    const int my_index = (wave_base + lane < n) ? index[wave_base + lane] : -1;
+    const int rows_here = (int)((n - wave_base) < kWave ? (n - wave_base) : kWave);
+#pragma unroll 1
+    for (int r0 = 0; r0 < kWave; r0 += kGroups * kUnroll) {
+        if (r0 >= rows_here) break;
+        V16 val[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int r = r0 + u * kGroups + grp;
+            const int idx = __shfl(my_index, r & (kWave - 1), kWave);
+            val[u] = V16{0u, 0u, 0u, 0u};
+            if (lane_on && r < rows_here && idx >= 0) {
+                const char* p = SRC_TABLE ? chunk_row_cptr(v, (uint32_t)idx) : src_base + (size_t)idx * (size_t)row_bytes;
+                val[u] = ld16(p + sub * 16);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int r = r0 + u * kGroups + grp;
+            if (lane_on && r < rows_here) {
+                char* q = out + (size_t)(wave_base + r) * (size_t)row_bytes + sub * 16;
+                if (NT_STORE) st16_nt(q, val[u]); else st16(q, val[u]);
+            }
+        }
+    }
+}
+
+template <bool SRC_TABLE, bool NT>
+int launch_copy_rows(const HtView& v, const char* src, const int32_t* index, const int64_t* n_dev, int64_t n_max,
+                     int row_bytes, char* out, hipStream_t s) {
+    const int vecs = row_bytes / 16;
+    const unsigned grid = (unsigned)((n_max + kBlock - 1) / kBlock);
+#define MTGR_CASE(L)                                                                                              \
+    hipLaunchKernelGGL((k_copy_rows<L, SRC_TABLE, NT>), dim3(grid), dim3(kBlock), 0, s, v, src, index, n_dev, n_max, \
+                       row_bytes, out)
+    if (vecs <= 1) MTGR_CASE(1);
+    else if (vecs <= 2) MTGR_CASE(2);
+    else if (vecs <= 4) MTGR_CASE(4);
+    else if (vecs <= 8) MTGR_CASE(8);
+    else if (vecs <= 16) MTGR_CASE(16);
+    else if (vecs <= 32) MTGR_CASE(32);
+    else MTGR_CASE(64);
+#undef MTGR_CASE
+    MTGR_LAUNCH_CHECK();
+    return EMB_OK;
+}
+
+// ---------------------------------------------------------------------------- segment reduce
+// Items are reduced in a fixed order, level by level.  Level 1 items are the positions in sorted
+// order (row = grad[perm[j]], segment = inverse[perm[j]]); a group of LPR lanes folds kSpan
+// consecutive items.  Runs of one segment that lie strictly inside the span are complete and
+// stored to reduced[]; the first and the last run of the span may continue in a neighbour span,
+// so they are handed to the next level as two fp32 partial rows (segment -1 = no item).  The next
+// level folds kSpan of those, and so on until one span holds everything.  Every sum is a fixed
+// tree, so results are reproducible run to run.
+constexpr int kSpan = 128;
+
+// FPL = floats accumulated per lane (4 for fp32 rows of 16 bytes per lane, 8 for bf16)
+template <int FPL>
+struct Acc {
+    float f[FPL];
+    __device__ inline void zero() {
+#pragma unroll
+        for (int i = 0; i < FPL; ++i) f[i] = 0.0f;
+    }
+};
+__device__ inline void acc_add(Acc<4>& a, const V16& v, bool /*bf16*/) {
+    a.f[0] += __uint_as_float(v.x);
+    a.f[1] += __uint_as_float(v.y);
+    a.f[2] += __uint_as_float(v.z);
+    a.f[3] += __uint_as_float(v.w);
+}
+__device__ inline void acc_add(Acc<8>& a, const V16& v, bool) {
+    a.f[0] += bf16lo(v.x); a.f[1] += bf16hi(v.x);
+    a.f[2] += bf16lo(v.y); a.f[3] += bf16hi(v.y);
+    a.f[4] += bf16lo(v.z); a.f[5] += bf16hi(v.z);
+    a.f[6] += bf16lo(v.w); a.f[7] += bf16hi(v.w);
+}
+template <int FPL>
+__device__ inline void acc_store(float* row, int sub, const Acc<FPL>& a) {
+    // lane `sub` owns floats [sub*FPL, sub*FPL+FPL) of the row
+#pragma unroll
+    for (int q = 0; q < FPL / 4; ++q) {
+        V16 o{__float_as_uint(a.f[4 * q]), __float_as_uint(a.f[4 * q + 1]), __float_as_uint(a.f[4 * q + 2]),
+              __float_as_uint(a.f[4 * q + 3])};
+        st16(row + sub * FPL + 4 * q, o);
+    }
+}
+
+struct LevelIn {
+    const char* rows;        // level 1: grad matrix; level >= 2: fp32 partial rows
+    const int32_t* perm;     // level 1 only
+    const int32_t* seg;      // level 1: inverse[]; level >= 2: segment of each item (-1 = none)
+    int64_t n_items;
+    int in_row_bytes;
+};
+
+template <int LPR, int FPL, bool LEVEL1>
+__global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, float* __restrict__ reduced,
+                                                       float* __restrict__ part_rows, int32_t* __restrict__ part_seg,
+                                                       int last_level) {
+    constexpr int kGroups = kWave / LPR;
+    const int lane = lane_id();
+    const int sub = lane % LPR, grp = lane / LPR;
+    const int gbase = lane - sub;
+    const int64_t span = ((int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave) * kGroups + grp;
+    const int64_t first = span * kSpan;
+    const bool group_on = first < in.n_items;
+    const int vecs = in.in_row_bytes / 16;
+    const bool lane_on = group_on && sub < vecs;
+    const int items = group_on ? (int)((in.n_items - first) < kSpan ? (in.n_items - first) : kSpan) : 0;
+
+    Acc<FPL> acc;
+    acc.zero();
+    int cur_seg = -1;
+    int runs_closed = 0;     // runs already flushed in this span
+    bool have = false;
+
+    // flush the current run: first run of the span -> partial slot 0, otherwise complete -> reduced[]
+    auto flush_mid = [&](void) {
+        if (!have) return;
+        if (runs_closed == 0 && !last_level) {
+            if (lane_on) acc_store<FPL>(part_rows + (size_t)(2 * span) * dim, sub, acc);
+            if (sub == 0) part_seg[2 * span] = cur_seg;
+        } else {
+            if (lane_on) acc_store<FPL>(reduced + (size_t)cur_seg * dim, sub, acc);
+        }
+        runs_closed++;
+        acc.zero();
+        have = false;
+    };
+
+    // each lane of the group preloads the source row index / segment of items sub, sub+LPR, ...
+    for (int c = 0; c < kSpan; c += LPR * kUnroll) {
+        // chunk of LPR*kUnroll items: lane holds kUnroll of them (item c + u*LPR + sub)
+        int64_t my_src[kUnroll];
+        int my_seg[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int it = c + u * LPR + sub;
+            my_src[u] = -1;
+            my_seg[u] = -1;
+            if (group_on && it < items) {
+                const int64_t j = first + it;
+                if (LEVEL1) {
+                    const int32_t p = in.perm[j];
+                    my_src[u] = p;
+                    my_seg[u] = in.seg[p];
+                } else {
+                    my_src[u] = j;
+                    my_seg[u] = in.seg[j];
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+#pragma unroll 1
+            for (int s0 = 0; s0 < LPR; s0 += kUnroll) {
+                V16 val[kUnroll];
+                int seg[kUnroll];
+#pragma unroll
+                for (int k = 0; k < kUnroll; ++k) {
+                    const int sl = gbase + ((s0 + k) & (LPR - 1));
+                    const long long src = (long long)shfl64((uint64_t)my_src[u], sl);
+                    seg[k] = __shfl(my_seg[u], sl, kWave);
+                    val[k] = V16{0u, 0u, 0u, 0u};
+                    if (s0 + k < LPR && lane_on && seg[k] >= 0)
+                        val[k] = ld16(in.rows + (size_t)src * (size_t)in.in_row_bytes + sub * 16);
+                }
+#pragma unroll
+                for (int k = 0; k < kUnroll; ++k) {
+                    if (s0 + k >= LPR || seg[k] < 0) continue;
+                    if (have && seg[k] != cur_seg) flush_mid();
+                    cur_seg = seg[k];
+                    have = true;
+                    acc_add(acc, val[k], false);
+                }
+            }
+        }
+    }
+    // last run of the span
+    if (group_on) {
+        if (last_level) {
+            if (have && lane_on) acc_store<FPL>(reduced + (size_t)cur_seg * dim, sub, acc);
+        } else {
+            // a span with a single run has already nothing in slot 0: put the run there, slot 1 empty
+            const int slot = (runs_closed == 0) ? 0 : 1;
+            if (have && lane_on) acc_store<FPL>(part_rows + (size_t)(2 * span + slot) * dim, sub, acc);
+            if (sub == 0) {
+                part_seg[2 * span + slot] = have ? cur_seg : -1;
+                if (slot == 0) part_seg[2 * span + 1] = -1;
+            }
+        }
+    }
+}
+
+struct ReduceLayout {
+    int levels;
+    int64_t items[8];       // items entering level l (l = 0 is level 1)
+    int64_t spans[8];
+    size_t rows_off[8];     // partial rows written by level l
+    size_t seg_off[8];
+    size_t total;
+};
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+ReduceLayout reduce_layout(int64_t n, int dim) {
+    ReduceLayout L;
+    size_t o = 0;
+    int64_t items = n;
+    int l = 0;
+    for (;; ++l) {
+        const int64_t spans = (items + kSpan - 1) / kSpan;
+        L.items[l] = items;
+        L.spans[l] = spans;
+        L.rows_off[l] = o; o = align256(o + (size_t)(2 * spans) * dim * 4);
+        L.seg_off[l] = o; o = align256(o + (size_t)(2 * spans) * 4);
+        if (spans <= 1 || l == 7) { ++l; break; }
+        items = 2 * spans;
+    }
+    L.levels = l;
+    L.total = o;
+    return L;
+}
+
+template <int LPR, int FPL>
+int launch_reduce(const char* grad, int in_row_bytes, const int32_t* inverse, const int32_t* perm, int64_t n, int dim,
+                  float* reduced, char* ws, const ReduceLayout& L, hipStream_t s) {
+    constexpr int kGroups = kWave / LPR;
+    constexpr int kSpansPerBlock = (kBlock / kWave) * kGroups;
+    for (int l = 0; l < L.levels; ++l) {
+        const int last = (l == L.levels - 1) ? 1 : 0;
+        const unsigned grid = (unsigned)((L.spans[l] + kSpansPerBlock - 1) / kSpansPerBlock);
+        float* prow = reinterpret_cast<float*>(ws + L.rows_off[l]);
+        int32_t* pseg = reinterpret_cast<int32_t*>(ws + L.seg_off[l]);
+        if (l == 0) {
+            LevelIn in{grad, perm, inverse, n, in_row_bytes};
+            hipLaunchKernelGGL((k_seg_reduce<LPR, FPL, true>), dim3(grid), dim3(kBlock), 0, s, in, dim, reduced, prow, pseg, last);
+        } else {
+            LevelIn in{ws + L.rows_off[l - 1], nullptr, reinterpret_cast<const int32_t*>(ws + L.seg_off[l - 1]), L.items[l],
+                       dim * 4};
+            // partial rows are fp32: dim*4 bytes, dim/4 vectors per row
+            constexpr int LPR2 = (FPL == 8) ? (LPR * 2 > 64 ? 64 : LPR * 2) : LPR;
+            constexpr int kGroups2 = kWave / LPR2;
+            constexpr int kSpb2 = (kBlock / kWave) * kGroups2;
+            const unsigned grid2 = (unsigned)((L.spans[l] + kSpb2 - 1) / kSpb2);
+            hipLaunchKernelGGL((k_seg_reduce<LPR2, 4, false>), dim3(grid2), dim3(kBlock), 0, s, in, dim, reduced, prow, pseg, last);
+        }
+        MTGR_LAUNCH_CHECK();
+    }
+    return EMB_OK;
+}
+
+// ---------------------------------------------------------------------------- row-wise Adagrad
+// One wave owns 64 consecutive entries of row_idx; an LPR-lane group updates one row:
+// sum of squares by xor-shuffles inside the group, then w -= lr * g / (sqrt(acc) + eps).
+template <int LPR, bool BF16>
+__global__ __launch_bounds__(kBlock) void k_adagrad(HtView v, const int32_t* __restrict__ row_idx,
+                                                    const float* __restrict__ g, const int64_t* n_dev, int64_t n_max,
+                                                    float lr, float eps) {
+    const int64_t n = read_count(n_dev, n_max);
+    const int lane = lane_id();
+    const int64_t wave_base = (int64_t)blockIdx.x * kBlock + (threadIdx.x & ~(kWave - 1));
+    if (wave_base >= n) return;
+    constexpr int kGroups = kWave / LPR;
+    constexpr int kF = BF16 ? 8 : 4;              // elements per lane
+    const int sub = lane % LPR, grp = lane / LPR;
+    const bool lane_on = sub * kF < v.dim;
+    const int my_index = (wave_base + lane < n) ? row_idx[wave_base + lane] : -1;
+    const int rows_here = (int)((n - wave_base) < kWave ? (n - wave_base) : kWave);
+    const float inv_d = 1.0f / (float)v.dim;
+#pragma unroll 1
+    for (int r0 = 0; r0 < kWave; r0 += kGroups * 2) {
+        if (r0 >= rows_here) break;
+        float gv[2][kF];
+        V16 wv[2];
+        int idx[2];
+        bool on[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int r = r0 + u * kGroups + grp;
+            idx[u] = __shfl(my_index, r & (kWave - 1), kWave);
+            on[u] = r < rows_here && idx[u] >= 0;
+#pragma unroll
+            for (int e = 0; e < kF; ++e) gv[u][e] = 0.0f;
+            wv[u] = V16{0u, 0u, 0u, 0u};
+            if (on[u] && lane_on) {
+                const float* gp = g + (size_t)(wave_base + r) * v.dim + sub * kF;
+#pragma unroll
+                for (int q = 0; q < kF / 4; ++q) {
+                    V16 t = ld16(gp + 4 * q);
+                    gv[u][4 * q] = __uint_as_float(t.x);
+                    gv[u][4 * q + 1] = __uint_as_float(t.y);
+                    gv[u][4 * q + 2] = __uint_as_float(t.z);
+                    gv[u][4 * q + 3] = __uint_as_float(t.w);
+                }
+                wv[u] = ld16(chunk_row_cptr(v, (uint32_t)idx[u]) + sub * 16);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            float ss = 0.0f;
+#pragma unroll
+            for (int e = 0; e < kF; ++e) ss = fmaf(gv[u][e], gv[u][e], ss);
+#pragma unroll
+            for (int o = LPR / 2; o > 0; o >>= 1) ss += __shfl_xor(ss, o, kWave);
+            if (!on[u]) continue;
+            const uint32_t row = (uint32_t)idx[u];
+            float* accp = &v.st->acc[row >> v.chunk_log2][row & ((1u << v.chunk_log2) - 1u)];
+            const float acc = *accp + ss * inv_d;
+            const float scale = lr / (sqrtf(acc) + eps);
+            if (lane_on) {
+                char* wp = const_cast<char*>(chunk_row_cptr(v, row)) + sub * 16;
+                V16 o;
+                if (BF16) {
+                    o.x = pack_bf16(bf16lo(wv[u].x) - scale * gv[u][0], bf16hi(wv[u].x) - scale * gv[u][1]);
+                    o.y = pack_bf16(bf16lo(wv[u].y) - scale * gv[u][2], bf16hi(wv[u].y) - scale * gv[u][3]);
+                    o.z = pack_bf16(bf16lo(wv[u].z) - scale * gv[u][4], bf16hi(wv[u].z) - scale * gv[u][5]);
+                    o.w = pack_bf16(bf16lo(wv[u].w) - scale * gv[u][6], bf16hi(wv[u].w) - scale * gv[u][7]);
+                } else {
+                    o.x = __float_as_uint(__uint_as_float(wv[u].x) - scale * gv[u][0]);
+                    o.y = __float_as_uint(__uint_as_float(wv[u].y) - scale * gv[u][1]);
+                    o.z = __float_as_uint(__uint_as_float(wv[u].z) - scale * gv[u][2]);
+                    o.w = __float_as_uint(__uint_as_float(wv[u].w) - scale * gv[u][3]);
+                }
+                st16(wp, o);
+            }
+            if (sub == 0) *accp = acc;
+        }
+    }
+}
+
+} // namespace
+
+extern "C" {
+
+int ht_gather(emb_table_t* t, const int32_t* row_idx, const int64_t* n_dev, int64_t n_max, void* out, void* stream) {
+    if (!t || n_max < 0 || n_max > 0x7FFFFFFFll) return EMB_ERR_INVALID_ARG;
+    if (n_max == 0) return EMB_OK;
+    if (!row_idx || !out || (reinterpret_cast<uintptr_t>(out) & 15)) return EMB_ERR_INVALID_ARG;
+    if (t->n_chunks == 0) return EMB_ERR_NO_STORAGE;
+    return launch_copy_rows<true, false>(t->view(), nullptr, row_idx, n_dev, n_max, t->row_bytes, static_cast<char*>(out),
+                                         static_cast<hipStream_t>(stream));
+}
+
+int emb_expand(const void* uniq_rows, const int32_t* inverse, int64_t n, int dim, int dtype, void* out, void* stream) {
+    if (n < 0 || n > 0x7FFFFFFFll || dim <= 0 || (dtype != EMB_F32 && dtype != EMB_BF16)) return EMB_ERR_INVALID_ARG;
+    if (n == 0) return EMB_OK;
+    const int row_bytes = dim * (dtype == EMB_F32 ? 4 : 2);
+    if (row_bytes % 16 != 0 || row_bytes > 1024) return EMB_ERR_INVALID_ARG;
+    if (!uniq_rows || !inverse || !out) return EMB_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(uniq_rows) & 15) || (reinterpret_cast<uintptr_t>(out) & 15)) return EMB_ERR_INVALID_ARG;
+    HtView none{};
+    return launch_copy_rows<false, true>(none, static_cast<const char*>(uniq_rows), inverse, nullptr, n, row_bytes,
+                                         static_cast<char*>(out), static_cast<hipStream_t>(stream));
+}
+
+size_t grad_segment_reduce_workspace_bytes(int64_t n, int dim) {
+    if (n <= 0 || dim <= 0) return 256;
+    return reduce_layout(n, dim).total;
+}
+
+int grad_segment_reduce(const void* grad, int grad_dtype, const int32_t* inverse, const int32_t* perm, int64_t n,
+                        int dim, float* reduced, void* workspace, size_t workspace_bytes, void* stream) {
+    if (n < 0 || n > 0x7FFFFFFFll || dim <= 0 || (grad_dtype != EMB_F32 && grad_dtype != EMB_BF16)) return EMB_ERR_INVALID_ARG;
+    if (n == 0) return EMB_OK;
+    const int in_row_bytes = dim * (grad_dtype == EMB_F32 ? 4 : 2);
+    if (in_row_bytes % 16 != 0 || in_row_bytes > 1024) return EMB_ERR_INVALID_ARG;
+    if (!grad || !inverse || !perm || !reduced) return EMB_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(grad) & 15) || (reinterpret_cast<uintptr_t>(reduced) & 15)) return EMB_ERR_INVALID_ARG;
+    const ReduceLayout L = reduce_layout(n, dim);
+    if (!workspace || workspace_bytes < L.total || (reinterpret_cast<uintptr_t>(workspace) & 255)) return EMB_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const char* g = static_cast<const char*>(grad);
+    char* ws = static_cast<char*>(workspace);
+    const int vecs = in_row_bytes / 16;
+#define MTGR_RED(L_)                                                                                          \
+    (grad_dtype == EMB_F32 ? launch_reduce<L_, 4>(g, in_row_bytes, inverse, perm, n, dim, reduced, ws, L, s) \
+                           : launch_reduce<L_, 8>(g, in_row_bytes, inverse, perm, n, dim, reduced, ws, L, s))
+    if (vecs <= 1) return MTGR_RED(1);
+    if (vecs <= 2) return MTGR_RED(2);
+    if (vecs <= 4) return MTGR_RED(4);
+    if (vecs <= 8) return MTGR_RED(8);
+    if (vecs <= 16) return MTGR_RED(16);
+    if (vecs <= 32) return MTGR_RED(32);
+    return MTGR_RED(64);
+#undef MTGR_RED
+}
+
+int ht_apply_adagrad(emb_table_t* t, const int32_t* row_idx, const float* reduced, const int64_t* n_dev,
+                     int64_t n_max, float lr, float eps, void* stream) {
+    if (!t || n_max < 0 || n_max > 0x7FFFFFFFll) return EMB_ERR_INVALID_ARG;
+    if (n_max == 0) return EMB_OK;
+    if (!row_idx || !reduced || (reinterpret_cast<uintptr_t>(reduced) & 15)) return EMB_ERR_INVALID_ARG;
+    if (t->n_chunks == 0) return EMB_ERR_NO_STORAGE;
+    HtView v = t->view();
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const unsigned grid = (unsigned)((n_max + kBlock - 1) / kBlock);
+    const int vecs = t->row_bytes / 16;
+    const bool bf = t->desc.dtype == EMB_BF16;
+#define MTGR_ADA(L_)                                                                                                     \
+    do {                                                                                                                 \
+        if (bf) hipLaunchKernelGGL((k_adagrad<L_, true>), dim3(grid), dim3(kBlock), 0, s, v, row_idx, reduced, n_dev, n_max, lr, eps); \
+        else hipLaunchKernelGGL((k_adagrad<L_, false>), dim3(grid), dim3(kBlock), 0, s, v, row_idx, reduced, n_dev, n_max, lr, eps);   \
+    } while (0)
+    if (vecs <= 1) MTGR_ADA(1);
+    else if (vecs <= 2) MTGR_ADA(2);
+    else if (vecs <= 4) MTGR_ADA(4);
+    else if (vecs <= 8) MTGR_ADA(8);
+    else if (vecs <= 16) MTGR_ADA(16);
+    else if (vecs <= 32) MTGR_ADA(32);
+    else MTGR_ADA(64);
+#undef MTGR_ADA
+    MTGR_LAUNCH_CHECK();
+    return EMB_OK;
+}
+
+} // extern "C"

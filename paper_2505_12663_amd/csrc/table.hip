@@ -1,0 +1,720 @@
+// Dynamic embedding hash table for gfx950 (Sec. 3.1): decoupled key structure
+// (keys[M] u64 + rows[M] u32) and chunked embedding structure, open addressing over
+// 64-byte lines of 8 slots with a key-dependent odd line stride (Theorem 1 gives full
+// coverage), sub-wave cooperative probing (8 lanes inspect one line with one coalesced
+// load), CAS insertion into never-used slots only, deleted markers, wave-aggregated
+// row allocation, key-only rehash.
+#include "common.hpp"
+
+using namespace mtgr;
+
+namespace {
+
+constexpr int kBlock = 256;
+
+__device__ inline void* chunk_row_ptr(const HtView& v, uint32_t row) {
+    char* base = static_cast<char*>(v.st->values[row >> v.chunk_log2]);
+    return base + (size_t)(row & ((1u << v.chunk_log2) - 1u)) * (size_t)v.row_bytes;
+}
+#define CHUNK_META(v, field, row) ((v).st->field[(row) >> (v).chunk_log2][(row) & ((1u << (v).chunk_log2) - 1u)])
+
+// --------------------------------------------------------------------------------------------
+__global__ void k_fill_keys(uint64_t* keys, uint32_t* rows, uint64_t n) {
+    uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) {
+        keys[i] = kEmptyKey;
+        rows[i] = kRowInvalid;
+    }
+}
+
+__global__ void k_zero_bytes(uint32_t* p, size_t n_words) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_words) p[i] = 0u;
+}
+
+__global__ void k_set_chunk(HtState* st, int c, void* values, float* acc, uint32_t* last_seen, uint32_t* freq,
+                            uint32_t* free_list) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        st->values[c] = values;
+        st->acc[c] = acc;
+        st->last_seen[c] = last_seen;
+        st->freq[c] = freq;
+        st->free_list[c] = free_list;
+    }
+}
+
+// --------------------------------------------------------------------------------------------
+// Probe for `key` with the 8 lanes of a group.  All 64 lanes of the wave call this together;
+// `active` says whether this lane's group has work.  Returns (group-uniform) the slot of the key,
+// or -1 when absent.  With INSERT, an absent key is claimed in the first never-used slot of the
+// first line on its probe sequence that has one; *created tells whether this call claimed it.
+// Correctness of concurrent inserts: a key is only ever stored by a successful CAS on an EMPTY
+// slot, EMPTY slots of a line are claimed in ascending order, and a line is re-read (bypassing the
+// vector L1) after every failed CAS, so two groups inserting the same key meet in the same slot.
+template <bool INSERT>
+__device__ inline long long probe_group(const HtView& v, uint64_t key, bool active, int lane, bool* created,
+                                        unsigned* n_probes, unsigned* n_cas, unsigned* n_cas_fail) {
+    const int sub = lane & (kLineSlots - 1);
+    const int gbase = lane & ~(kLineSlots - 1);
+    const uint64_t h = slot_hash(key);
+    uint64_t line = probe_start(h, v.line_mask);
+    const uint64_t stride = probe_stride(h, v.line_mask);
+    uint64_t remaining = v.line_mask + 1; // lines not yet visited: bounds the loop
+    long long result = -1;
+    bool done = !active;
+    *created = false;
+    while (__any(!done)) {
+        uint64_t slot = line * kLineSlots + sub;
+        uint64_t k = kEmptyKey;
+        if (!done) k = INSERT ? load_fresh(v.keys + slot) : v.keys[slot];
+        uint64_t m_hit = __ballot(!done && k == key);
+        uint64_t m_empty = __ballot(!done && k == kEmptyKey);
+        unsigned hit8 = (unsigned)(m_hit >> gbase) & 0xFFu;
+        unsigned empty8 = (unsigned)(m_empty >> gbase) & 0xFFu;
+        bool retry_line = false;
+        if (!done) {
+            *n_probes += (sub == 0);
+            if (hit8) {
+                result = (long long)(line * kLineSlots + (__ffs(hit8) - 1));
+                done = true;
+            } else if (empty8) {
+                if (!INSERT) {
+                    done = true; // absent
+                }
+            }
+        }
+        if (INSERT) {
+            // groups that saw no hit but an EMPTY slot try to claim the first one
+            bool want = !done && !hit8 && empty8;
+            int e = want ? (__ffs(empty8) - 1) : 0;
+            uint64_t old = 0;
+            if (want && sub == e) {
+                old = atomicCAS(reinterpret_cast<unsigned long long*>(v.keys + line * kLineSlots + e),
+                                (unsigned long long)kEmptyKey, (unsigned long long)key);
+                *n_cas += 1;
+                if (old != kEmptyKey) *n_cas_fail += 1;
+            }
+            old = shfl64(old, gbase + e);
+            if (want) {
+                if (old == kEmptyKey) {
+                    result = (long long)(line * kLineSlots + e);
+                    *created = true;
+                    done = true;
+                } else if (old == key) {
+                    result = (long long)(line * kLineSlots + e); // another group inserted the same key first
+                    done = true;
+                } else {
+                    retry_line = true; // slot went to a different key: look at the line again
+                }
+            }
+        }
+        if (!done && !retry_line) {
+            line = (line + stride) & v.line_mask;
+            if (--remaining == 0) {
+                done = true;
+                result = -2; // every line visited: table full
+            }
+        }
+    }
+    return result;
+}
+
+// One wave handles 64 keys: each lane owns one key; the 8 groups of 8 lanes work through the keys
+// of their own lanes one after the other.
+template <bool COUNT>
+__global__ __launch_bounds__(kBlock) void k_find_or_insert(HtView v, const uint64_t* __restrict__ key,
+                                                           const int64_t* n_dev, int64_t n_max, uint32_t step,
+                                                           int32_t* __restrict__ row_idx,
+                                                           uint8_t* __restrict__ inserted) {
+    const int64_t n = read_count(n_dev, n_max);
+    const int lane = lane_id();
+    const int64_t wave_base = ((int64_t)blockIdx.x * kBlock + (threadIdx.x & ~(kWave - 1)));
+    if (wave_base >= n) return;
+    const int64_t i = wave_base + lane;
+    const bool valid = i < n;
+    uint64_t my_key = valid ? key[i] : 0ull;
+    const bool bad = valid && (my_key >> 63);
+    const int sub = lane & (kLineSlots - 1);
+    const int gbase = lane & ~(kLineSlots - 1);
+
+    long long my_slot = -1;
+    bool my_created = false;
+    unsigned n_probes = 0, n_cas = 0, n_cas_fail = 0;
+    for (int r = 0; r < kLineSlots; ++r) {
+        uint64_t k = shfl64(my_key, gbase + r);
+        bool act = (__shfl((int)(valid && !bad), gbase + r, kWave) != 0);
+        bool created;
+        long long s = probe_group<true>(v, k, act, lane, &created, &n_probes, &n_cas, &n_cas_fail);
+        if (sub == r) {
+            my_slot = s;
+            my_created = created;
+        }
+    }
+
+    // ---- wave-aggregated row allocation for the lanes that claimed a slot
+    const uint64_t m_new = __ballot(my_created);
+    uint32_t my_row = kRowInvalid;
+    unsigned n_alloc_atomics = 0;
+    if (m_new) {
+        const int n_new = __popcll(m_new);
+        int old_free = 0;
+        unsigned bump_base = 0;
+        int take = 0;
+        if (lane == 0) {
+            old_free = atomicSub(&v.st->free_count, n_new);
+            n_alloc_atomics = 1;
+            take = old_free < 0 ? 0 : (old_free > n_new ? n_new : old_free);
+            if (n_new - take > 0) {
+                bump_base = atomicAdd(&v.st->bump, (unsigned)(n_new - take));
+                n_alloc_atomics = 2;
+            }
+            atomicAdd(&v.st->live, (unsigned long long)n_new);
+        }
+        old_free = __shfl(old_free, 0, kWave);
+        take = __shfl(take, 0, kWave);
+        bump_base = __shfl(bump_base, 0, kWave);
+        if (my_created) {
+            int r = rank_in(m_new, lane);
+            if (r < take) {
+                unsigned p = (unsigned)(old_free - 1 - r);
+                my_row = CHUNK_META(v, free_list, p);
+            } else {
+                my_row = bump_base + (unsigned)(r - take);
+            }
+            if (my_row >= v.rows_capacity) {
+                // out of row storage: give the slot up again (as a deleted marker) and report
+                atomicOr(&v.st->status, EMB_DEV_OUT_OF_ROWS);
+                v.keys[my_slot] = kTombKey;
+                atomicAdd(&v.st->tombstones, 1ull);
+                atomicAdd(&v.st->live, ~0ull); // -1
+                my_row = kRowInvalid;
+                my_created = false;
+                my_slot = -1;
+            }
+        }
+    }
+    // ---- initialise the new rows, the whole wave writing one row at a time (coalesced)
+    uint64_t m_init = __ballot(my_created);
+    while (m_init) {
+        const int src = __ffsll((unsigned long long)m_init) - 1;
+        m_init &= m_init - 1;
+        const uint64_t k = shfl64(my_key, src);
+        const uint32_t row = __shfl(my_row, src, kWave);
+        char* dst = static_cast<char*>(chunk_row_ptr(v, row));
+        if (v.dtype == EMB_F32) {
+            for (int j = lane; j < v.dim; j += kWave) reinterpret_cast<float*>(dst)[j] = init_value(k, j, v.init_c);
+        } else {
+            for (int j = lane; j < v.dim; j += kWave)
+                reinterpret_cast<uint16_t*>(dst)[j] = f32_to_bf16(init_value(k, j, v.init_c));
+        }
+    }
+    if (my_created) {
+        CHUNK_META(v, acc, my_row) = 0.0f;
+        CHUNK_META(v, freq, my_row) = 0u;
+        CHUNK_META(v, last_seen, my_row) = step;
+        v.rows[my_slot] = my_row;
+    }
+    // ---- results.  A lane that found a key another group is still inserting sees no row yet:
+    // it records the slot (as -(slot+2)) and k_touch resolves it after this kernel.
+    if (valid) {
+        int32_t out;
+        if (bad) {
+            atomicOr(&v.st->status, EMB_DEV_BAD_KEY);
+            out = -1;
+        } else if (my_slot == -2) {
+            atomicOr(&v.st->status, EMB_DEV_PROBE_EXHAUSTED);
+            out = -1;
+        } else if (my_slot < 0) {
+            out = -1;
+        } else if (my_created) {
+            out = (int32_t)my_row;
+        } else {
+            uint32_t r = load_fresh(v.rows + my_slot);
+            out = (r == kRowInvalid) ? (int32_t)(-(my_slot + 2)) : (int32_t)r;
+        }
+        row_idx[i] = out;
+        if (inserted) inserted[i] = my_created ? 1 : 0;
+    }
+    if (COUNT) {
+        // one atomic per counter per wave
+        unsigned tot_p = n_probes, tot_c = n_cas, tot_f = n_cas_fail;
+        for (int o = 32; o > 0; o >>= 1) {
+            tot_p += __shfl_xor(tot_p, o, kWave);
+            tot_c += __shfl_xor(tot_c, o, kWave);
+            tot_f += __shfl_xor(tot_f, o, kWave);
+        }
+        if (lane == 0) {
+            int64_t cnt = n - wave_base < kWave ? n - wave_base : kWave;
+            atomicAdd(&v.st->lookups, (unsigned long long)cnt);
+            atomicAdd(&v.st->probes, (unsigned long long)tot_p);
+            atomicAdd(&v.st->cas_attempts, (unsigned long long)tot_c);
+            atomicAdd(&v.st->cas_failures, (unsigned long long)tot_f);
+            atomicAdd(&v.st->alloc_atomics, (unsigned long long)n_alloc_atomics);
+        }
+    }
+}
+
+// Second half of find-or-insert: resolve deferred rows, then count the touch of every element.
+__global__ __launch_bounds__(kBlock) void k_touch(HtView v, const int64_t* n_dev, int64_t n_max, uint32_t step,
+                                                  int32_t* __restrict__ row_idx) {
+    const int64_t n = read_count(n_dev, n_max);
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i == 0 && v.st->free_count < 0) v.st->free_count = 0; // the free list ran dry during the insert
+    if (i >= n) return;
+    int32_t r = row_idx[i];
+    if (r <= -2) {
+        uint32_t rr = v.rows[(uint64_t)(-(long long)r - 2)];
+        r = (rr == kRowInvalid) ? -1 : (int32_t)rr;
+        row_idx[i] = r;
+    }
+    if (r >= 0) {
+        atomicAdd(&CHUNK_META(v, freq, (uint32_t)r), 1u);
+        CHUNK_META(v, last_seen, (uint32_t)r) = step;
+    }
+}
+
+template <bool COUNT>
+__global__ __launch_bounds__(kBlock) void k_find(HtView v, const uint64_t* __restrict__ key, const int64_t* n_dev,
+                                                 int64_t n_max, int32_t* __restrict__ row_idx) {
+    const int64_t n = read_count(n_dev, n_max);
+    const int lane = lane_id();
+    const int64_t wave_base = ((int64_t)blockIdx.x * kBlock + (threadIdx.x & ~(kWave - 1)));
+    if (wave_base >= n) return;
+    const int64_t i = wave_base + lane;
+    const bool valid = i < n;
+    uint64_t my_key = valid ? key[i] : 0ull;
+    const bool ok = valid && !(my_key >> 63);
+    const int sub = lane & (kLineSlots - 1);
+    const int gbase = lane & ~(kLineSlots - 1);
+    long long my_slot = -1;
+    unsigned n_probes = 0, d0 = 0, d1 = 0;
+    for (int r = 0; r < kLineSlots; ++r) {
+        uint64_t k = shfl64(my_key, gbase + r);
+        bool act = (__shfl((int)ok, gbase + r, kWave) != 0);
+        bool created;
+        long long s = probe_group<false>(v, k, act, lane, &created, &n_probes, &d0, &d1);
+        if (sub == r) my_slot = s;
+    }
+    if (valid) {
+        int32_t out = -1;
+        if (my_slot >= 0) {
+            uint32_t r = v.rows[my_slot];
+            out = (r == kRowInvalid) ? -1 : (int32_t)r;
+        }
+        row_idx[i] = out;
+    }
+    if (COUNT) {
+        unsigned tot_p = n_probes;
+        for (int o = 32; o > 0; o >>= 1) tot_p += __shfl_xor(tot_p, o, kWave);
+        if (lane == 0) {
+            int64_t cnt = n - wave_base < kWave ? n - wave_base : kWave;
+            atomicAdd(&v.st->lookups, (unsigned long long)cnt);
+            atomicAdd(&v.st->probes, (unsigned long long)tot_p);
+        }
+    }
+}
+
+// --------------------------------------------------------------------------------------------
+// Eviction: one lane per slot.  Matching keys become deleted markers; their rows go to the free
+// stack and their keys to the output list, both with one atomic per wave.
+__global__ __launch_bounds__(kBlock) void k_evict(HtView v, uint64_t n_slots, uint32_t now, uint32_t ttl,
+                                                  uint32_t min_freq, uint32_t grace, uint64_t* evicted_keys,
+                                                  int64_t evicted_cap, unsigned long long* n_evicted) {
+    const int lane = lane_id();
+    const uint64_t slot = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    bool go = false;
+    uint64_t k = kEmptyKey;
+    uint32_t row = kRowInvalid;
+    if (slot < n_slots) {
+        k = v.keys[slot];
+        if (k != kEmptyKey && k != kTombKey) {
+            row = v.rows[slot];
+            if (row != kRowInvalid) {
+                uint32_t age = now - CHUNK_META(v, last_seen, row);
+                uint32_t fq = CHUNK_META(v, freq, row);
+                bool stale = ttl > 0 && age >= ttl;
+                bool rare = min_freq > 0 && fq < min_freq && age >= grace;
+                go = stale || rare;
+            }
+        }
+    }
+    const uint64_t m = __ballot(go);
+    if (!m) return;
+    const int cnt = __popcll(m);
+    int free_base = 0;
+    unsigned long long out_base = 0;
+    if (lane == __ffsll((unsigned long long)m) - 1) {
+        free_base = atomicAdd(&v.st->free_count, cnt);
+        out_base = atomicAdd(n_evicted, (unsigned long long)cnt);
+        atomicAdd(&v.st->live, ~(unsigned long long)cnt + 1ull);
+        atomicAdd(&v.st->tombstones, (unsigned long long)cnt);
+    }
+    const int leader = __ffsll((unsigned long long)m) - 1;
+    free_base = __shfl(free_base, leader, kWave);
+    out_base = shfl64(out_base, leader);
+    if (go) {
+        const int r = rank_in(m, lane);
+        v.keys[slot] = kTombKey;
+        v.rows[slot] = kRowInvalid;
+        CHUNK_META(v, free_list, (unsigned)(free_base + r)) = row;
+        if (evicted_keys && (int64_t)(out_base + r) < evicted_cap) evicted_keys[out_base + r] = k;
+    }
+}
+
+// Key-structure migration: one lane per old slot; a live pair is placed in the first never-used
+// slot of the first line with one on its probe sequence in the new arrays.  No key occurs twice,
+// so no match test is needed.  Values are not touched (Sec. 3.1 "Capacity Expansion").
+__global__ __launch_bounds__(kBlock) void k_rehash(const uint64_t* __restrict__ old_keys,
+                                                   const uint32_t* __restrict__ old_rows, uint64_t old_slots,
+                                                   uint64_t* new_keys, uint32_t* new_rows, uint64_t new_line_mask,
+                                                   HtState* st) {
+    const uint64_t s = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (s >= old_slots) return;
+    const uint64_t k = old_keys[s];
+    if (k == kEmptyKey || k == kTombKey) return;
+    const uint32_t row = old_rows[s];
+    if (row == kRowInvalid) return;
+    const uint64_t h = slot_hash(k);
+    uint64_t line = probe_start(h, new_line_mask);
+    const uint64_t stride = probe_stride(h, new_line_mask);
+    for (uint64_t t = 0; t <= new_line_mask; ++t) {
+        for (int j = 0; j < kLineSlots; ++j) {
+            uint64_t* p = new_keys + line * kLineSlots + j;
+            if (load_fresh(p) != kEmptyKey) continue;
+            uint64_t old = atomicCAS(reinterpret_cast<unsigned long long*>(p), (unsigned long long)kEmptyKey,
+                                     (unsigned long long)k);
+            if (old == kEmptyKey) {
+                new_rows[line * kLineSlots + j] = row;
+                return;
+            }
+        }
+        line = (line + stride) & new_line_mask;
+    }
+    atomicOr(&st->status, EMB_DEV_PROBE_EXHAUSTED);
+}
+
+__global__ void k_after_rehash(HtState* st) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) st->tombstones = 0ull;
+}
+
+// Unordered dump: one lane per slot decides, then the wave copies the rows of its live slots.
+__global__ __launch_bounds__(kBlock) void k_export(HtView v, uint64_t n_slots, uint64_t* keys, char* values,
+                                                   float* acc, uint32_t* last_seen, uint32_t* freq, int64_t cap,
+                                                   unsigned long long* n_out) {
+    const int lane = lane_id();
+    const uint64_t slot = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    bool liveslot = false;
+    uint64_t k = 0;
+    uint32_t row = kRowInvalid;
+    if (slot < n_slots) {
+        k = v.keys[slot];
+        if (k != kEmptyKey && k != kTombKey) {
+            row = v.rows[slot];
+            liveslot = row != kRowInvalid;
+        }
+    }
+    uint64_t m = __ballot(liveslot);
+    if (!m) return;
+    const int leader = __ffsll((unsigned long long)m) - 1;
+    unsigned long long base = 0;
+    if (lane == leader) base = atomicAdd(n_out, (unsigned long long)__popcll(m));
+    base = shfl64(base, leader);
+    const unsigned long long pos = base + rank_in(m, lane);
+    if (liveslot && (int64_t)pos < cap) {
+        keys[pos] = k;
+        if (acc) acc[pos] = CHUNK_META(v, acc, row);
+        if (last_seen) last_seen[pos] = CHUNK_META(v, last_seen, row);
+        if (freq) freq[pos] = CHUNK_META(v, freq, row);
+    }
+    if (!values) return;
+    while (m) {
+        const int src = __ffsll((unsigned long long)m) - 1;
+        m &= m - 1;
+        const uint32_t r = __shfl(row, src, kWave);
+        const unsigned long long p = shfl64(pos, src);
+        if ((int64_t)p >= cap) continue;
+        const uint32_t* s32 = static_cast<const uint32_t*>(chunk_row_ptr(v, r));
+        uint32_t* d32 = reinterpret_cast<uint32_t*>(values + (size_t)p * v.row_bytes);
+        for (int w = lane; w < v.row_bytes / 4; w += kWave) d32[w] = s32[w];
+    }
+}
+
+inline unsigned blocks_for(uint64_t n, int per_block) { return (unsigned)((n + per_block - 1) / per_block); }
+
+} // namespace
+
+// ================================================================================================
+extern "C" {
+
+int emb_tag_bits(int m) {
+    if (m < 0) return EMB_ERR_INVALID_ARG;
+    int k = 0;
+    while ((1ll << k) <= (long long)m) ++k; // smallest k with 2^k >= m+1
+    return k;
+}
+
+int emb_plan_merge(const int32_t* dims, const int32_t* dtypes, int m, int32_t* merged_of) {
+    if (!dims || !dtypes || !merged_of || m < 0) return EMB_ERR_INVALID_ARG;
+    int n_groups = 0;
+    for (int t = 0; t < m; ++t) {
+        int g = -1;
+        for (int p = 0; p < t && g < 0; ++p)
+            if (dims[p] == dims[t] && dtypes[p] == dtypes[t]) g = merged_of[p];
+        merged_of[t] = g >= 0 ? g : n_groups++;
+    }
+    return n_groups;
+}
+
+uint64_t ht_probe_line(uint64_t key, int capacity_log2, uint64_t t) {
+    if (capacity_log2 < 3 || capacity_log2 > 62) return ~0ull;
+    const uint64_t line_mask = ((1ull << capacity_log2) / kLineSlots) - 1ull;
+    const uint64_t h = slot_hash(key);
+    return (probe_start(h, line_mask) + t * probe_stride(h, line_mask)) & line_mask;
+}
+
+const char* emb_status_string(int s) {
+    switch (s) {
+        case EMB_OK: return "ok";
+        case EMB_ERR_INVALID_ARG: return "invalid argument";
+        case EMB_ERR_KEY_RANGE: return "key out of range";
+        case EMB_ERR_WORKSPACE: return "workspace too small or misaligned";
+        case EMB_ERR_NO_STORAGE: return "no key storage or not enough row chunks";
+        case EMB_ERR_HIP: return "HIP runtime error";
+        case EMB_ERR_NEED_REHASH: return "load factor limit: rehash first";
+        default: return "unknown status";
+    }
+}
+
+size_t emb_table_state_bytes(void) { return (sizeof(HtState) + 255) & ~(size_t)255; }
+
+int emb_table_create(emb_table_t** out, const emb_table_desc_t* desc, void* state, size_t state_bytes,
+                     void* stream) {
+    if (!out || !desc || !state) return EMB_ERR_INVALID_ARG;
+    if (state_bytes < emb_table_state_bytes() || (reinterpret_cast<uintptr_t>(state) & 255)) return EMB_ERR_INVALID_ARG;
+    if (desc->dim <= 0 || (desc->dtype != EMB_F32 && desc->dtype != EMB_BF16)) return EMB_ERR_INVALID_ARG;
+    const int row_bytes = desc->dim * (desc->dtype == EMB_F32 ? 4 : 2);
+    if (row_bytes % 16 != 0 || desc->dim > 256) return EMB_ERR_INVALID_ARG;
+    if (desc->chunk_rows_log2 < 4 || desc->chunk_rows_log2 > 30) return EMB_ERR_INVALID_ARG;
+    if (desc->max_load_factor < 0.0f || desc->max_load_factor > 0.95f) return EMB_ERR_INVALID_ARG;
+    emb_table* t = new emb_table();
+    t->desc = *desc;
+    if (t->desc.max_load_factor == 0.0f) t->desc.max_load_factor = 0.75f;
+    if (t->desc.init_scale == 0.0f) t->desc.init_scale = 0.01f;
+    t->st = static_cast<HtState*>(state);
+    t->keys = nullptr;
+    t->rows = nullptr;
+    t->cap_log2 = 0;
+    t->n_chunks = 0;
+    t->row_bytes = row_bytes;
+    t->n_rehash = 0;
+    t->occupied_bound = t->live_bound = t->rows_used_bound = 0;
+    const size_t words = emb_table_state_bytes() / 4;
+    hipLaunchKernelGGL(k_zero_bytes, dim3(blocks_for(words, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<uint32_t*>(state), words);
+    if (hipGetLastError() != hipSuccess) {
+        delete t;
+        return EMB_ERR_HIP;
+    }
+    *out = t;
+    return EMB_OK;
+}
+
+int emb_table_destroy(emb_table_t* t) {
+    delete t;
+    return EMB_OK;
+}
+
+int ht_set_key_storage(emb_table_t* t, uint64_t* keys, uint32_t* rows, int capacity_log2, void* stream) {
+    if (!t || !keys || !rows || capacity_log2 < 6 || capacity_log2 > 30) return EMB_ERR_INVALID_ARG;
+    if (t->keys && t->live_bound > 0) return EMB_ERR_INVALID_ARG; // non-empty table: use ht_rehash
+    const uint64_t n = 1ull << capacity_log2;
+    hipLaunchKernelGGL(k_fill_keys, dim3(blocks_for(n, 256 * 8) > 65535u * 16 ? 65535u * 16 : blocks_for(n, 256 * 8)),
+                       dim3(256), 0, static_cast<hipStream_t>(stream), keys, rows, n);
+    MTGR_LAUNCH_CHECK();
+    t->keys = keys;
+    t->rows = rows;
+    t->cap_log2 = capacity_log2;
+    t->occupied_bound = 0;
+    t->live_bound = 0;
+    return EMB_OK;
+}
+
+int ht_add_chunk(emb_table_t* t, void* values, float* acc, uint32_t* last_seen, uint32_t* freq,
+                 uint32_t* free_list, void* stream) {
+    if (!t || !values || !acc || !last_seen || !freq || !free_list) return EMB_ERR_INVALID_ARG;
+    if (t->n_chunks >= kMaxChunks) return EMB_ERR_NO_STORAGE;
+    if (((uint64_t)(t->n_chunks + 1) << t->desc.chunk_rows_log2) > 0x7FFFFFFFull) return EMB_ERR_NO_STORAGE;
+    if (reinterpret_cast<uintptr_t>(values) & 15) return EMB_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(k_set_chunk, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), t->st, t->n_chunks, values,
+                       acc, last_seen, freq, free_list);
+    MTGR_LAUNCH_CHECK();
+    t->n_chunks += 1;
+    return EMB_OK;
+}
+
+int ht_plan(emb_table_t* t, int64_t n_incoming, int* new_capacity_log2, int* chunks_needed) {
+    if (!t || n_incoming < 0) return EMB_ERR_INVALID_ARG;
+    if (new_capacity_log2) {
+        *new_capacity_log2 = 0;
+        if (t->keys) {
+            const double cap = (double)(1ull << t->cap_log2);
+            const double lf = t->desc.max_load_factor;
+            if ((double)(t->occupied_bound + (uint64_t)n_incoming) > lf * cap) {
+                int c = t->cap_log2;
+                while ((double)(t->live_bound + (uint64_t)n_incoming) > 0.5 * lf * (double)(1ull << c) && c < 30) ++c;
+                *new_capacity_log2 = c;
+            }
+        }
+    }
+    if (chunks_needed) {
+        const uint64_t have = (uint64_t)t->n_chunks << t->desc.chunk_rows_log2;
+        const uint64_t want = t->rows_used_bound + (uint64_t)n_incoming;
+        const uint64_t per = 1ull << t->desc.chunk_rows_log2;
+        *chunks_needed = want > have ? (int)((want - have + per - 1) / per) : 0;
+    }
+    return EMB_OK;
+}
+
+static int check_insert_room(emb_table_t* t, int64_t n_max) {
+    if (!t->keys) return EMB_ERR_NO_STORAGE;
+    const double cap = (double)(1ull << t->cap_log2);
+    if ((double)(t->occupied_bound + (uint64_t)n_max) > (double)t->desc.max_load_factor * cap) return EMB_ERR_NEED_REHASH;
+    const uint64_t have = (uint64_t)t->n_chunks << t->desc.chunk_rows_log2;
+    if (t->rows_used_bound + (uint64_t)n_max > have) return EMB_ERR_NO_STORAGE;
+    return EMB_OK;
+}
+
+int ht_find_or_insert(emb_table_t* t, const uint64_t* key, const int64_t* n_dev, int64_t n_max, uint32_t step,
+                      int32_t* row_idx, uint8_t* inserted, void* stream) {
+    if (!t || n_max < 0 || n_max > 0x7FFFFFFFll) return EMB_ERR_INVALID_ARG;
+    if (n_max == 0) return EMB_OK;
+    if (!key || !row_idx) return EMB_ERR_INVALID_ARG;
+    int rc = check_insert_room(t, n_max);
+    if (rc != EMB_OK) return rc;
+    HtView v = t->view();
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const unsigned grid = blocks_for((uint64_t)n_max, kBlock);
+    if (v.count)
+        hipLaunchKernelGGL(k_find_or_insert<true>, dim3(grid), dim3(kBlock), 0, s, v, key, n_dev, n_max, step, row_idx,
+                           inserted);
+    else
+        hipLaunchKernelGGL(k_find_or_insert<false>, dim3(grid), dim3(kBlock), 0, s, v, key, n_dev, n_max, step, row_idx,
+                           inserted);
+    MTGR_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_touch, dim3(grid), dim3(kBlock), 0, s, v, n_dev, n_max, step, row_idx);
+    MTGR_LAUNCH_CHECK();
+    t->occupied_bound += (uint64_t)n_max;
+    t->live_bound += (uint64_t)n_max;
+    t->rows_used_bound += (uint64_t)n_max;
+    return EMB_OK;
+}
+
+int ht_find(emb_table_t* t, const uint64_t* key, const int64_t* n_dev, int64_t n_max, int32_t* row_idx,
+            void* stream) {
+    if (!t || n_max < 0 || n_max > 0x7FFFFFFFll) return EMB_ERR_INVALID_ARG;
+    if (n_max == 0) return EMB_OK;
+    if (!key || !row_idx) return EMB_ERR_INVALID_ARG;
+    if (!t->keys) return EMB_ERR_NO_STORAGE;
+    HtView v = t->view();
+    const unsigned grid = blocks_for((uint64_t)n_max, kBlock);
+    if (v.count)
+        hipLaunchKernelGGL(k_find<true>, dim3(grid), dim3(kBlock), 0, static_cast<hipStream_t>(stream), v, key, n_dev,
+                           n_max, row_idx);
+    else
+        hipLaunchKernelGGL(k_find<false>, dim3(grid), dim3(kBlock), 0, static_cast<hipStream_t>(stream), v, key, n_dev,
+                           n_max, row_idx);
+    MTGR_LAUNCH_CHECK();
+    return EMB_OK;
+}
+
+int ht_evict(emb_table_t* t, uint32_t now, uint32_t ttl, uint32_t min_freq, uint32_t grace,
+             uint64_t* evicted_keys, int64_t evicted_cap, int64_t* n_evicted, void* stream) {
+    if (!t || !n_evicted || evicted_cap < 0) return EMB_ERR_INVALID_ARG;
+    if (!t->keys) return EMB_ERR_NO_STORAGE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(k_zero_bytes, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(n_evicted), (size_t)2);
+    MTGR_LAUNCH_CHECK();
+    HtView v = t->view();
+    const uint64_t n_slots = 1ull << t->cap_log2;
+    hipLaunchKernelGGL(k_evict, dim3(blocks_for(n_slots, kBlock)), dim3(kBlock), 0, s, v, n_slots, now, ttl, min_freq,
+                       grace, evicted_keys, evicted_cap, reinterpret_cast<unsigned long long*>(n_evicted));
+    MTGR_LAUNCH_CHECK();
+    return EMB_OK;
+}
+
+int ht_rehash(emb_table_t* t, uint64_t* new_keys, uint32_t* new_rows, int new_capacity_log2, void* stream) {
+    if (!t || !new_keys || !new_rows || new_capacity_log2 < 6 || new_capacity_log2 > 30) return EMB_ERR_INVALID_ARG;
+    if (!t->keys) return EMB_ERR_NO_STORAGE;
+    if (new_keys == t->keys || new_rows == t->rows) return EMB_ERR_INVALID_ARG;
+    // the live keys (last ht_stats count plus inserts issued since) must fit under the limit
+    if ((double)t->live_bound > (double)t->desc.max_load_factor * (double)(1ull << new_capacity_log2))
+        return EMB_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint64_t n_new = 1ull << new_capacity_log2;
+    const uint64_t n_old = 1ull << t->cap_log2;
+    unsigned fill_grid = blocks_for(n_new, 256 * 8);
+    hipLaunchKernelGGL(k_fill_keys, dim3(fill_grid), dim3(256), 0, s, new_keys, new_rows, n_new);
+    MTGR_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_rehash, dim3(blocks_for(n_old, kBlock)), dim3(kBlock), 0, s, t->keys, t->rows, n_old, new_keys,
+                       new_rows, n_new / kLineSlots - 1ull, t->st);
+    MTGR_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_after_rehash, dim3(1), dim3(64), 0, s, t->st);
+    MTGR_LAUNCH_CHECK();
+    t->keys = new_keys;
+    t->rows = new_rows;
+    t->cap_log2 = new_capacity_log2;
+    t->n_rehash += 1;
+    t->occupied_bound = t->live_bound; // deleted markers are gone
+    return EMB_OK;
+}
+
+int ht_stats(emb_table_t* t, ht_stats_t* out, void* stream) {
+    if (!t || !out) return EMB_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    struct Head {
+        unsigned long long live, tombstones;
+        unsigned int bump;
+        int free_count;
+        unsigned int status, pad0;
+        unsigned long long lookups, probes, cas_attempts, cas_failures, alloc_atomics;
+    } h;
+    if (hipMemcpyAsync(&h, t->st, sizeof(h), hipMemcpyDeviceToHost, s) != hipSuccess) return EMB_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return EMB_ERR_HIP;
+    out->live = h.live;
+    out->tombstones = h.tombstones;
+    out->capacity = t->keys ? (1ull << t->cap_log2) : 0ull;
+    out->rows_used = h.bump;
+    out->rows_free = h.free_count > 0 ? (uint64_t)h.free_count : 0ull;
+    out->rows_capacity = (uint64_t)t->n_chunks << t->desc.chunk_rows_log2;
+    out->n_rehash = t->n_rehash;
+    out->n_chunks = (uint64_t)t->n_chunks;
+    out->status = h.status;
+    out->lookups = h.lookups;
+    out->probes = h.probes;
+    out->cas_attempts = h.cas_attempts;
+    out->cas_failures = h.cas_failures;
+    out->alloc_atomics = h.alloc_atomics;
+    // exact numbers replace the running upper bounds
+    t->live_bound = h.live;
+    t->occupied_bound = h.live + h.tombstones;
+    t->rows_used_bound = (uint64_t)h.bump - out->rows_free;
+    return EMB_OK;
+}
+
+int ht_export(emb_table_t* t, uint64_t* keys, void* values, float* acc, uint32_t* last_seen, uint32_t* freq,
+              int64_t cap, int64_t* n, void* stream) {
+    if (!t || !keys || !n || cap < 0) return EMB_ERR_INVALID_ARG;
+    if (!t->keys) return EMB_ERR_NO_STORAGE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(k_zero_bytes, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(n), (size_t)2);
+    MTGR_LAUNCH_CHECK();
+    HtView v = t->view();
+    const uint64_t n_slots = 1ull << t->cap_log2;
+    hipLaunchKernelGGL(k_export, dim3(blocks_for(n_slots, kBlock)), dim3(kBlock), 0, s, v, n_slots, keys,
+                       static_cast<char*>(values), acc, last_seen, freq, cap, reinterpret_cast<unsigned long long*>(n));
+    MTGR_LAUNCH_CHECK();
+    return EMB_OK;
+}
+
+} // extern "C"

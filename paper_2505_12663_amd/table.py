@@ -1,0 +1,181 @@
+"""Storage owner for one merged hash table and the buffers of one lookup step.
+
+The C library allocates nothing; this module keeps the torch tensors that back the key
+structure, the value chunks and the per-step buffers alive, and applies the capacity policy the
+library plans (``ht_plan``): rehash the key structure when the load-factor limit would be crossed,
+keep a spare value chunk registered (dual-chunk rule of Sec. 3.1).  All arithmetic of the path
+runs in the library's kernels.
+"""
+from __future__ import annotations
+
+from typing import List, Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def _np_to_dev_i64(a: np.ndarray, device) -> torch.Tensor:
+    """uint64 numpy keys -> int64 device tensor holding the same bits."""
+    a = np.ascontiguousarray(a, dtype=np.uint64)
+    return torch.from_numpy(a.view(np.int64)).to(device)
+
+
+class EmbeddingTable:
+    """One dynamic hash table (possibly holding several merged logical tables)."""
+
+    def __init__(self, dim: int, dtype: int = B.F32, capacity_log2: int = 18, chunk_rows_log2: int = 16,
+                 init_scale: float = 0.01, max_load_factor: float = 0.75, count_probes: bool = False,
+                 device: str = "cuda:0", initial_chunks: int = 2):
+        self.device = torch.device(device)
+        self.dim, self.dtype = dim, dtype
+        self.chunk_rows_log2 = chunk_rows_log2
+        self.torch_dtype = torch.float32 if dtype == B.F32 else torch.bfloat16
+        self.state = torch.empty(B.emb_table_state_bytes(), dtype=torch.uint8, device=self.device)
+        desc = B.TableDesc(dim, dtype, init_scale, max_load_factor, chunk_rows_log2, int(count_probes))
+        self.h = B.emb_table_create(desc, self.state)
+        self.capacity_log2 = capacity_log2
+        self.keys = torch.empty(1 << capacity_log2, dtype=torch.int64, device=self.device)
+        self.rows = torch.empty(1 << capacity_log2, dtype=torch.int32, device=self.device)
+        B.ht_set_key_storage(self.h, self.keys, self.rows, capacity_log2)
+        self.chunks: List[tuple] = []
+        self._retired = []          # old key arrays kept until the stream has passed the rehash
+        for _ in range(initial_chunks):
+            self.add_chunk()
+
+    def close(self) -> None:
+        if self.h is not None:
+            torch.cuda.synchronize(self.device)
+            B.emb_table_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- storage ------------------------------------------------------------------------------
+    def add_chunk(self) -> None:
+        n = 1 << self.chunk_rows_log2
+        values = torch.empty((n, self.dim), dtype=self.torch_dtype, device=self.device)
+        acc = torch.empty(n, dtype=torch.float32, device=self.device)
+        last_seen = torch.empty(n, dtype=torch.int32, device=self.device)
+        freq = torch.empty(n, dtype=torch.int32, device=self.device)
+        free_list = torch.empty(n, dtype=torch.int32, device=self.device)
+        B.ht_add_chunk(self.h, values, acc, last_seen, freq, free_list)
+        self.chunks.append((values, acc, last_seen, freq, free_list))
+
+    def rehash(self, new_capacity_log2: int) -> None:
+        new_keys = torch.empty(1 << new_capacity_log2, dtype=torch.int64, device=self.device)
+        new_rows = torch.empty(1 << new_capacity_log2, dtype=torch.int32, device=self.device)
+        B.ht_rehash(self.h, new_keys, new_rows, new_capacity_log2)
+        # torch's caching allocator is stream-ordered: dropping the old arrays here is safe for
+        # work queued on the current stream.
+        self.keys, self.rows, self.capacity_log2 = new_keys, new_rows, new_capacity_log2
+
+    def stats(self) -> dict:
+        return B.ht_stats(self.h)
+
+    def reserve(self, n_incoming: int) -> None:
+        """Make room for up to n_incoming new keys.  Syncs only when the library's running upper
+        bounds (exact counts at the last ht_stats plus everything issued since) say it may not fit."""
+        cap, chunks = B.ht_plan(self.h, n_incoming)
+        if cap == 0 and chunks == 0:
+            return
+        self.stats()                       # exact counts replace the running upper bounds
+        cap, _ = B.ht_plan(self.h, n_incoming)
+        # dual-chunk rule: besides the rows needed now, keep one whole spare chunk registered
+        _, chunks = B.ht_plan(self.h, n_incoming + (1 << self.chunk_rows_log2))
+        for _ in range(chunks):
+            self.add_chunk()
+        if cap:
+            self.rehash(cap)
+
+    # -- calls --------------------------------------------------------------------------------
+    def find_or_insert(self, key, n_dev, n_max: int, step: int, row_idx, inserted=None) -> None:
+        rc = B.ht_find_or_insert(self.h, key, n_dev, n_max, step, row_idx, inserted)
+        if rc != B.EMB_OK:
+            self.reserve(n_max)
+            rc = B.ht_find_or_insert(self.h, key, n_dev, n_max, step, row_idx, inserted)
+            if rc != B.EMB_OK:
+                raise B.EmbError(rc, "ht_find_or_insert")
+
+    def find(self, key, n_dev, n_max: int, row_idx) -> None:
+        B.ht_find(self.h, key, n_dev, n_max, row_idx)
+
+    def gather(self, row_idx, n_dev, n_max: int, out) -> None:
+        B.ht_gather(self.h, row_idx, n_dev, n_max, out)
+
+    def apply_adagrad(self, row_idx, reduced, n_dev, n_max: int, lr: float, eps: float = 1e-8) -> None:
+        B.ht_apply_adagrad(self.h, row_idx, reduced, n_dev, n_max, lr, eps)
+
+    def evict(self, now: int, ttl: int, min_freq: int, grace: int, want_keys: bool = True):
+        live = self.stats()["live"]
+        n_ev = torch.zeros(1, dtype=torch.int64, device=self.device)
+        keys = torch.empty(max(live, 1), dtype=torch.int64, device=self.device) if want_keys else None
+        B.ht_evict(self.h, now, ttl, min_freq, grace, keys, n_ev)
+        n = int(n_ev.item())
+        self.stats()
+        return (keys[:n] if want_keys else None), n
+
+    def export(self):
+        """Dump (keys, values, acc, last_seen, freq) sorted by key, as numpy arrays."""
+        live = self.stats()["live"]
+        cap = max(live, 1)
+        keys = torch.empty(cap, dtype=torch.int64, device=self.device)
+        values = torch.empty((cap, self.dim), dtype=self.torch_dtype, device=self.device)
+        acc = torch.empty(cap, dtype=torch.float32, device=self.device)
+        last_seen = torch.empty(cap, dtype=torch.int32, device=self.device)
+        freq = torch.empty(cap, dtype=torch.int32, device=self.device)
+        n = torch.zeros(1, dtype=torch.int64, device=self.device)
+        B.ht_export(self.h, keys, values, acc, last_seen, freq, n)
+        cnt = int(n.item())
+        assert cnt == live, (cnt, live)
+        k = keys[:cnt].cpu().numpy().view(np.uint64)
+        order = np.argsort(k, kind="stable")
+        vals = values[:cnt].float().cpu().numpy()
+        return (k[order], vals[order], acc[:cnt].cpu().numpy()[order],
+                last_seen[:cnt].cpu().numpy().view(np.uint32)[order], freq[:cnt].cpu().numpy().view(np.uint32)[order])
+
+
+class StepBuffers:
+    """Device buffers of one forward+backward step over at most n_max IDs of one merged table."""
+
+    def __init__(self, n_max: int, dim: int, dtype: int = B.F32, device: str = "cuda:0", with_grad: bool = True):
+        dev = torch.device(device)
+        tdt = torch.float32 if dtype == B.F32 else torch.bfloat16
+        self.n_max, self.dim, self.dtype = n_max, dim, dtype
+        self.key = torch.empty(n_max, dtype=torch.int64, device=dev)
+        self.uniq = torch.empty(n_max, dtype=torch.int64, device=dev)
+        self.inverse = torch.empty(n_max, dtype=torch.int32, device=dev)
+        self.perm = torch.empty(n_max, dtype=torch.int32, device=dev)
+        self.seg_off = torch.empty(n_max + 1, dtype=torch.int32, device=dev)
+        self.counts = torch.empty(n_max, dtype=torch.int32, device=dev)
+        self.n_unique = torch.zeros(1, dtype=torch.int64, device=dev)
+        self.err_count = torch.zeros(1, dtype=torch.int64, device=dev)
+        self.row_idx = torch.empty(n_max, dtype=torch.int32, device=dev)
+        self.inserted = torch.empty(n_max, dtype=torch.uint8, device=dev)
+        self.dedup_ws = torch.empty(B.emb_dedup_workspace_bytes(n_max), dtype=torch.uint8, device=dev)
+        self.uniq_rows = torch.empty((n_max, dim), dtype=tdt, device=dev)
+        self.out = torch.empty((n_max, dim), dtype=tdt, device=dev)
+        if with_grad:
+            self.reduced = torch.empty((n_max, dim), dtype=torch.float32, device=dev)
+            self.reduce_ws = torch.empty(B.grad_segment_reduce_workspace_bytes(n_max, dim), dtype=torch.uint8, device=dev)
+
+
+def forward(table: EmbeddingTable, buf: StepBuffers, x, field_off, field_tag, tag_bits: int, step: int) -> None:
+    """tag -> dedup -> find-or-insert -> gather -> expand; results in buf.out[:n]."""
+    n = x.numel()
+    B.emb_tag_keys(x, field_off, field_tag, tag_bits, buf.key, buf.err_count)
+    B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, buf.counts, buf.perm, buf.seg_off, buf.n_unique, buf.dedup_ws)
+    table.find_or_insert(buf.uniq, buf.n_unique, n, step, buf.row_idx, buf.inserted)
+    table.gather(buf.row_idx, buf.n_unique, n, buf.uniq_rows)
+    B.emb_expand(buf.uniq_rows, buf.inverse, n, table.dim, table.dtype, buf.out)
+
+
+def backward(table: EmbeddingTable, buf: StepBuffers, grad, n: int, lr: float, eps: float = 1e-8) -> None:
+    """segment-reduce the upstream gradient per distinct key, then row-wise Adagrad."""
+    B.grad_segment_reduce(grad, table.dtype, buf.inverse, buf.perm, n, table.dim, buf.reduced, buf.reduce_ws)
+    table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, lr, eps)

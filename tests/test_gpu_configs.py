@@ -1,0 +1,187 @@
+"""Whole-step parity on the five benchmark configurations (needs an MI355X).
+
+Configuration 1 runs at its published size.  Configurations 2-5 run here at sizes the
+single-threaded checker finishes in seconds (same structure: merged tables, pre-populated tables,
+fresh keys, eviction, rehash, bf16 rows); the published sizes are covered by
+test_gpu_fullsize.py on sampled outputs.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from workloads import make_config, merged_inputs, normal_grads
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from paper_2505_12663_amd import binding as B
+    from paper_2505_12663_amd import StepBuffers
+    from harness import Pair, run_step, dev_keys, host_keys
+
+
+def _plan(w):
+    """Table merging on both sides; the two plans must agree."""
+    dims = [w.table_dim(t) for t in range(w.n_tables)]
+    dtypes = [0 if w.table_dtype(t) == "f32" else 1 for t in range(w.n_tables)]
+    merged, n_merged = B.emb_plan_merge(dims, dtypes)
+    om, on = oracle.plan_merge(dims, dtypes)
+    assert n_merged == on and np.array_equal(merged, om)
+    tag_bits = w.tag_bits if w.tag_bits is not None else B.emb_tag_bits(w.n_tables)
+    assert w.tag_bits is not None or tag_bits == oracle.tag_bits(w.n_tables)
+    sig = [(dims[list(merged).index(g)], dtypes[list(merged).index(g)]) for g in range(n_merged)]
+    return merged, n_merged, tag_bits, sig
+
+
+def _bulk_load(pair, w, tag_bits):
+    """Insert every pre-existing key of every logical table at step 0 (tagged by the library on the
+    GPU side and by the checker on the CPU side).  Returns the set of tagged keys."""
+    xs = [w.prepopulated_ids(t, 0, w.prepopulated[t]) for t in range(w.n_tables)]
+    x = np.concatenate(xs)
+    off = np.concatenate([[0], np.cumsum([len(a) for a in xs])]).astype(np.int64)
+    tags = np.arange(w.n_tables, dtype=np.uint8)
+    okeys, oerr = oracle.tag_keys(x, off, tags, tag_bits)
+    n = len(x)
+    dkeys = torch.empty(n, dtype=torch.int64, device="cuda")
+    err = torch.zeros(1, dtype=torch.int64, device="cuda")
+    B.emb_tag_keys(dev_keys(x), torch.from_numpy(off).cuda(), torch.from_numpy(tags).cuda(), tag_bits, dkeys, err)
+    assert oerr == 0 and int(err.item()) == 0 and np.array_equal(host_keys(dkeys), okeys)
+    rows = torch.empty(n, dtype=torch.int32, device="cuda")
+    pair.gpu.find_or_insert(dkeys, None, n, 0, rows)
+    assert pair.gpu.stats()["live"] == n
+    return okeys
+
+
+def _grads(w, step, n, dim, dtype, g):
+    G = normal_grads(w.seed + 17 * g, step, n, dim)
+    if dtype == 1:
+        G = torch.from_numpy(G).to(torch.bfloat16).float().numpy()
+    return G
+
+
+def test_config1_tiny_full_size():
+    w = make_config(1)
+    merged, n_merged, tag_bits, sig = _plan(w)
+    assert n_merged == 1 and tag_bits == 1
+    pair = Pair(32, 0, capacity_log2=18, chunk_rows_log2=15)
+    buf = StepBuffers(256 * 4 * 64, 32)
+    for step in range(w.steps):
+        b = w.next_step(step)
+        x, off, tags, _ = merged_inputs(w.features, b.ids, merged, 0)
+        G = _grads(w, step, len(x), 32, 0, 0)
+        n, U = run_step(pair, buf, x, off, tags, tag_bits, step, G, w.lr, w.eps)
+        live = pair.compare_tables(w.lr)
+        assert live == len(pair.orc)
+    st = pair.gpu.stats()
+    assert st["capacity"] == 1 << 18 and st["status"] == 0 and st["n_rehash"] == 0
+    pair.gpu.close()
+
+
+def test_config3_table_merging_scaled():
+    w = make_config(3, batch=48, vocab_scale=0.02)
+    merged, n_merged, tag_bits, sig = _plan(w)
+    assert n_merged == 4 and tag_bits == 8
+    pairs = [Pair(d, t, capacity_log2=16, chunk_rows_log2=13) for d, t in sig]
+    n_max = 48 * 40 * 200
+    bufs = [StepBuffers(n_max, d, t) for d, t in sig]
+    for step in range(3):
+        b = w.next_step(step)
+        for g in range(n_merged):
+            x, off, tags, sel = merged_inputs(w.features, b.ids, merged, g)
+            assert len(sel) > 0
+            G = _grads(w, step, len(x), sig[g][0], sig[g][1], g)
+            run_step(pairs[g], bufs[g], x, off, tags, tag_bits, step, G, w.lr, w.eps)
+    for p in pairs:
+        p.compare_tables(w.lr)
+        # keys of different logical tables never collide: the tag is part of the key
+        keys = p.gpu.export()[0]
+        assert len(np.unique(keys >> np.uint64(55))) >= 1
+        p.gpu.close()
+
+
+def test_config2_prepopulated_scaled():
+    w = make_config(2, batch=24, vocab_scale=0.004, len_lo=64, len_hi=512)       # 25k keys per field
+    merged, n_merged, tag_bits, sig = _plan(w)
+    assert n_merged == 1 and tag_bits == 4
+    pair = Pair(64, 0, capacity_log2=19, chunk_rows_log2=16)
+    all_keys = _bulk_load(pair, w, tag_bits)
+    n_all = len(all_keys)
+    assert n_all == 8 * 25_000
+    member = set(all_keys.tolist())
+    lazy = lambda uniq: np.array([k for k in uniq.tolist() if k in member], dtype=np.uint64)
+    buf = StepBuffers(24 * 512 * 8, 64)
+    for step in range(1, 4):
+        b = w.next_step(step - 1)
+        x, off, tags, _ = merged_inputs(w.features, b.ids, merged, 0)
+        G = _grads(w, step, len(x), 64, 0, 0)
+        n, U = run_step(pair, buf, x, off, tags, tag_bits, step, G, w.lr, w.eps, prepopulated_keys=lazy)
+        assert int(buf.inserted[:U].sum().item()) == 0                # nothing is new in this configuration
+    # touched keys agree in full; untouched pre-populated rows are a pure function of their key
+    ok, ov, oa, ol, of = pair.orc.export()
+    gk, gv, ga, gl, gf = pair.gpu.export()
+    assert len(gk) == n_all
+    pos = np.searchsorted(gk, ok)
+    assert np.array_equal(gk[pos], ok) and np.array_equal(gl[pos], ol) and np.array_equal(gf[pos], of)
+    assert np.allclose(gv[pos], ov, rtol=1e-5, atol=1e-7) and np.allclose(ga[pos], oa, rtol=4e-5)
+    untouched = np.ones(n_all, dtype=bool)
+    untouched[pos] = False
+    sample = np.flatnonzero(untouched)[:: max(1, untouched.sum() // 500)]
+    for i in sample:
+        assert np.array_equal(gv[i], oracle.init_row(int(gk[i]), 64)) and ga[i] == 0 and gf[i] == 1 and gl[i] == 0
+    pair.gpu.close()
+
+
+def test_config4_insert_delete_stress_scaled():
+    w = make_config(4, batch=8, vocab_scale=0.01, len_lo=128)      # 4k IDs per step, 4k keys per field
+    w.ttl, w.min_freq, w.grace, w.evict_every = 25, 3, 6, 10
+    merged, n_merged, tag_bits, sig = _plan(w)
+    pair = Pair(64, 0, capacity_log2=12, chunk_rows_log2=11, max_load_factor=0.85)
+    buf = StepBuffers(8 * 128 * 4, 64)
+    lf_seen, evicted_total = [], 0
+    for step in range(90):
+        b = w.next_step(step)
+        x, off, tags, _ = merged_inputs(w.features, b.ids, merged, 0)
+        G = _grads(w, step, len(x), 64, 0, 0)
+        n, U = run_step(pair, buf, x, off, tags, tag_bits, step, G, w.lr, w.eps)
+        if (step + 1) % w.evict_every == 0:
+            ev, n_ev = pair.gpu.evict(step, w.ttl, w.min_freq, w.grace)
+            oev = pair.orc.evict(step, w.ttl, w.min_freq, w.grace)
+            assert np.array_equal(np.sort(host_keys(ev)), oev)
+            evicted_total += n_ev
+        st = pair.gpu.stats()
+        lf_seen.append((st["live"] + st["tombstones"]) / st["capacity"])
+        assert st["status"] == 0 and st["live"] == len(pair.orc)
+        if step % 15 == 14:
+            pair.compare_tables(w.lr, exact_rows_when_untouched=True)
+    pair.compare_tables(w.lr)
+    st = pair.gpu.stats()
+    assert st["n_rehash"] >= 2 and evicted_total > 1000 and max(lf_seen) <= 0.85 + 1e-9
+    assert st["rows_free"] + st["live"] == st["rows_used"]          # every allocated row is live or on the free list
+    pair.gpu.close()
+
+
+def test_config5_bf16_scaled():
+    w = make_config(5, batch=8, vocab_scale=0.0002, len_lo=256)     # 20k keys per field, 8k IDs per step
+    merged, n_merged, tag_bits, sig = _plan(w)
+    assert sig == [(128, 1)]
+    pair = Pair(128, 1, capacity_log2=17, chunk_rows_log2=15, max_load_factor=0.75)
+    all_keys = _bulk_load(pair, w, tag_bits)
+    member = set(all_keys.tolist())
+    lazy = lambda uniq: np.array([k for k in uniq.tolist() if k in member], dtype=np.uint64)
+    buf = StepBuffers(8 * 256 * 4, 128, 1)
+    new_total = 0
+    for step in range(1, 5):
+        b = w.next_step(step - 1)
+        x, off, tags, _ = merged_inputs(w.features, b.ids, merged, 0)
+        G = _grads(w, step, len(x), 128, 1, 0)
+        n, U = run_step(pair, buf, x, off, tags, tag_bits, step, G, w.lr, w.eps, prepopulated_keys=lazy)
+        new_total += int(buf.inserted[:U].sum().item())
+    assert new_total > 0                                            # ~5 % of each step's keys are new
+    ok, ov, oa, ol, of = pair.orc.export()
+    gk, gv, ga, gl, gf = pair.gpu.export()
+    pos = np.searchsorted(gk, ok)
+    assert np.array_equal(gk[pos], ok) and np.array_equal(gl[pos], ol) and np.array_equal(gf[pos], of)
+    assert (np.abs(gv[pos] - ov) <= 1e-2 * np.maximum(np.abs(ov), w.lr)).all()
+    assert np.allclose(ga[pos], oa, rtol=1e-4)
+    assert pair.gpu.stats()["live"] == len(all_keys) + new_total
+    pair.gpu.close()

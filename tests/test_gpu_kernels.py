@@ -1,0 +1,358 @@
+"""Element-by-element parity of every HIP entry point against the CPU checker (needs an MI355X).
+
+Sizes span several tiles and ragged tails; edge cases cover empty inputs, one element, all-equal
+and all-distinct keys, duplicate keys in one insert call, one giant segment, absent keys.
+Integer / index / byte results are compared bit-exactly; fp32 results within 1e-5 (relative to the
+sum of |addends| for reductions, to max(|w|, lr) for updated rows); bf16 rows within 1e-2.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from workloads import bounded_zipf_ranks, scramble_bits, normal_grads, small_int_grads
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from paper_2505_12663_amd import binding as B
+    from paper_2505_12663_amd import EmbeddingTable, StepBuffers
+    from harness import dev_keys, host_keys, close_reduce, close_rows, RTOL_F32, RTOL_BF16
+
+
+def _zipf_keys(n, vocab, seed, bits=40, tag=0, tag_shift=59):
+    rng = np.random.default_rng(seed)
+    r = bounded_zipf_ranks(rng, n, vocab, 1.05)
+    return (scramble_bits(r.astype(np.uint64), bits, seed) | np.uint64(tag << tag_shift)).astype(np.uint64)
+
+
+# ------------------------------------------------------------------------------------------ tag
+@pytest.mark.parametrize("tag_bits,n_fields,n", [(2, 3, 1000), (8, 40, 50_000), (0, 1, 77), (4, 5, 0), (16, 7, 4097)])
+def test_tag_keys(tag_bits, n_fields, n):
+    rng = np.random.default_rng(n + tag_bits)
+    cuts = np.sort(rng.integers(0, n + 1, size=n_fields - 1)) if n_fields > 1 else np.zeros(0, dtype=np.int64)
+    off = np.concatenate([[0], cuts, [n]]).astype(np.int64)          # some fields may be empty
+    tags = rng.integers(0, min(1 << tag_bits, 256), size=n_fields).astype(np.uint8)
+    x = rng.integers(0, 1 << (63 - tag_bits), size=n, dtype=np.uint64)
+    if n > 10:
+        x[3] = np.uint64(1 << (63 - tag_bits)) if tag_bits > 0 else x[3]     # one ID out of range
+    okey, oerr = oracle.tag_keys(x, off, tags, tag_bits)
+    key = torch.empty(max(n, 1), dtype=torch.int64, device="cuda")
+    err = torch.full((1,), 99, dtype=torch.int64, device="cuda")
+    B.emb_tag_keys(dev_keys(x), torch.from_numpy(off).cuda(), torch.from_numpy(tags).cuda(), tag_bits, key, err)
+    assert int(err.item()) == oerr
+    assert np.array_equal(host_keys(key[:n]), okey)
+
+
+# ------------------------------------------------------------------------------------------ dedup
+def _run_dedup(keys):
+    n = len(keys)
+    d = dev_keys(keys) if n else torch.empty(0, dtype=torch.int64, device="cuda")
+    m = max(n, 1)
+    uniq = torch.empty(m, dtype=torch.int64, device="cuda")
+    inverse = torch.empty(m, dtype=torch.int32, device="cuda")
+    counts = torch.empty(m, dtype=torch.int32, device="cuda")
+    perm = torch.empty(m, dtype=torch.int32, device="cuda")
+    seg_off = torch.full((m + 1,), -7, dtype=torch.int32, device="cuda")
+    n_unique = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    ws = torch.empty(B.emb_dedup_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    B.emb_dedup(d, n, uniq, inverse, counts, perm, seg_off, n_unique, ws)
+    U = int(n_unique.item())
+    return (host_keys(uniq[:U]), inverse[:n].cpu().numpy(), counts[:U].cpu().numpy(), perm[:n].cpu().numpy(),
+            seg_off[:U + 1].cpu().numpy())
+
+
+@pytest.mark.parametrize("case", ["empty", "one", "all_equal", "all_distinct", "zipf_small", "zipf_tiles",
+                                  "tagged_mix", "full_64bit_range", "two_values_far_apart"])
+def test_dedup_matches_checker(case):
+    rng = np.random.default_rng(11)
+    keys = {
+        "empty": np.zeros(0, dtype=np.uint64),
+        "one": np.array([42], dtype=np.uint64),
+        "all_equal": np.full(5000, (3 << 59) | 12345, dtype=np.uint64),
+        "all_distinct": rng.permutation(np.arange(10_001, dtype=np.uint64) * np.uint64(2654435761)),
+        "zipf_small": _zipf_keys(777, 300, 1),
+        "zipf_tiles": _zipf_keys(4096 * 13 + 57, 50_000, 2),
+        "tagged_mix": np.concatenate([_zipf_keys(30_000, 4000, 3, tag=t) for t in (0, 1, 5, 7)]),
+        "full_64bit_range": rng.integers(0, 1 << 63, size=20_000, dtype=np.uint64),
+        "two_values_far_apart": rng.choice(np.array([5, (1 << 62) + 5], dtype=np.uint64), size=9000),
+    }[case]
+    if case == "tagged_mix":
+        keys = keys[rng.permutation(len(keys))]
+    uniq, inverse, counts, perm, seg_off = _run_dedup(keys)
+    ou, oi, oc = oracle.dedup(keys)
+    assert np.array_equal(uniq, ou) and np.array_equal(inverse, oi) and np.array_equal(counts, oc)
+    n, U = len(keys), len(ou)
+    # perm / seg_off: the part that is unique is checked exactly (stable order = ascending position)
+    assert seg_off[0] == 0 and seg_off[-1] == n if n else seg_off[0] == 0
+    if n:
+        assert np.array_equal(np.diff(seg_off), oc)
+        assert np.array_equal(np.sort(perm), np.arange(n))
+        assert np.array_equal(keys[perm], np.repeat(ou, oc))
+        seg_of_pos = np.repeat(np.arange(U), oc)
+        same = seg_of_pos[1:] == seg_of_pos[:-1]
+        assert (np.diff(perm)[same] > 0).all()
+
+
+# ------------------------------------------------------------------------------------------ table
+@pytest.mark.parametrize("dim,dtype", [(32, 0), (64, 0), (16, 0), (128, 0), (128, 1), (8, 1)])
+def test_find_or_insert_gather_roundtrip(dim, dtype):
+    keys = _zipf_keys(20_000, 6000, 5)                         # with duplicates inside one call
+    keys[:64] = keys[0]                                          # a whole wave of the same new key
+    t = EmbeddingTable(dim, dtype, capacity_log2=15, chunk_rows_log2=12, count_probes=True, initial_chunks=3)
+    ot = oracle.Table(dim, dtype)
+    n = len(keys)
+    d = dev_keys(keys)
+    row_idx = torch.empty(n, dtype=torch.int32, device="cuda")
+    inserted = torch.empty(n, dtype=torch.uint8, device="cuda")
+    t.find_or_insert(d, None, n, 7, row_idx, inserted)
+    oins = ot.find_or_insert(keys, 7)
+    r = row_idx.cpu().numpy()
+    assert (r >= 0).all()
+    # one row per distinct key, the same row for every duplicate
+    uk, first = np.unique(keys, return_index=True)
+    assert len(np.unique(r)) == len(uk)
+    assert np.array_equal(r, r[first][np.searchsorted(uk, keys)])
+    # exactly one element per new key reports the insert (which duplicate wins is free)
+    ins = inserted.cpu().numpy()
+    assert ins.sum() == oins.sum() == len(uk)
+    assert np.array_equal(np.sort(keys[ins == 1]), uk)
+    st = t.stats()
+    assert st["live"] == len(uk) == len(ot) and st["status"] == 0 and st["tombstones"] == 0
+    assert st["rows_used"] == len(uk)
+    assert st["lookups"] == n and st["probes"] >= n and st["cas_attempts"] >= len(uk)
+    # gather = the checker's lookup, bit for bit (initial rows are a pure function of the key)
+    tdt = torch.float32 if dtype == 0 else torch.bfloat16
+    out = torch.empty((n, dim), dtype=tdt, device="cuda")
+    t.gather(row_idx, None, n, out)
+    assert np.array_equal(out.float().cpu().numpy(), ot.lookup(keys))
+    # second call inserts nothing and returns the same rows; touch counters agree with the checker
+    row2 = torch.empty_like(row_idx)
+    t.find_or_insert(d, None, n, 8, row2, inserted)
+    ot.find_or_insert(keys, 8)
+    assert np.array_equal(row2.cpu().numpy(), r) and int(inserted.sum().item()) == 0
+    assert t.stats()["live"] == len(uk)
+    gk, gv, ga, gl, gf = t.export()
+    ok, ov, oa, ol, of = ot.export()
+    assert np.array_equal(gk, ok) and np.array_equal(gv, ov) and np.array_equal(gl, ol) and np.array_equal(gf, of)
+    assert (ga == 0).all()
+    # read-only find: present keys -> same rows, absent keys -> -1, gather of -1 -> zeros
+    probe = np.concatenate([uk[:100], uk[:50] ^ np.uint64(1 << 50)])
+    found = torch.empty(len(probe), dtype=torch.int32, device="cuda")
+    t.find(dev_keys(probe), None, len(probe), found)
+    f = found.cpu().numpy()
+    assert np.array_equal(f >= 0, ot.find(probe).astype(bool))
+    assert np.array_equal(f[:100], r[first][:100])
+    out2 = torch.full((len(probe), dim), 3.0, dtype=tdt, device="cuda")
+    t.gather(found, None, len(probe), out2)
+    assert np.array_equal(out2.float().cpu().numpy(), ot.lookup(probe))
+    t.close()
+
+
+def test_count_on_device_limits_the_work():
+    keys = np.arange(1, 1001, dtype=np.uint64) * np.uint64(7919)
+    t = EmbeddingTable(32, 0, capacity_log2=12, chunk_rows_log2=10)
+    row_idx = torch.full((1000,), -5, dtype=torch.int32, device="cuda")
+    n_dev = torch.tensor([300], dtype=torch.int64, device="cuda")
+    t.find_or_insert(dev_keys(keys), n_dev, 1000, 0, row_idx)
+    assert t.stats()["live"] == 300
+    assert (row_idx[:300] >= 0).all() and (row_idx[300:] == -5).all()
+    out = torch.full((1000, 32), 9.0, device="cuda")
+    t.gather(row_idx, n_dev, 1000, out)
+    assert (out[300:] == 9.0).all() and (out[:300].abs() <= 0.01).all()
+    t.close()
+
+
+def test_bad_key_and_capacity_errors_are_reported():
+    t = EmbeddingTable(32, 0, capacity_log2=8, chunk_rows_log2=6, initial_chunks=1)      # 256 slots, 64 rows
+    keys = np.array([5, (1 << 63) | 5, 6], dtype=np.uint64)
+    row_idx = torch.empty(3, dtype=torch.int32, device="cuda")
+    t.find_or_insert(dev_keys(keys), None, 3, 0, row_idx)
+    r = row_idx.cpu().numpy()
+    assert r[0] >= 0 and r[2] >= 0 and r[1] == -1
+    assert t.stats()["status"] & B.DEV_BAD_KEY
+    # the raw call refuses to launch when n_max inserts might cross the limits
+    many = dev_keys(np.arange(100, 400, dtype=np.uint64))
+    big = torch.empty(300, dtype=torch.int32, device="cuda")
+    assert B.ht_find_or_insert(t.h, many, None, 300, 1, big) in (B.EMB_ERR_NEED_REHASH, B.EMB_ERR_NO_STORAGE)
+    assert t.stats()["live"] == 2
+    # the storage owner makes room (rehash + chunks) and retries
+    t.find_or_insert(many, None, 300, 1, big)
+    st = t.stats()
+    assert st["live"] == 302 and st["capacity"] >= 512 and st["n_rehash"] >= 1 and (big >= 0).all()
+    t.close()
+
+
+# ------------------------------------------------------------------------------------------ expand
+@pytest.mark.parametrize("dim,dtype,n,u", [(64, 0, 10_000, 3000), (32, 0, 4097, 1), (128, 1, 5000, 5000),
+                                            (16, 0, 63, 10), (128, 0, 2000, 300), (4, 0, 1000, 17)])
+def test_expand(dim, dtype, n, u):
+    rng = np.random.default_rng(n)
+    rows = rng.standard_normal((u, dim)).astype(np.float32)
+    inverse = rng.integers(0, u, size=n).astype(np.int32)
+    tdt = torch.float32 if dtype == 0 else torch.bfloat16
+    d_rows = torch.from_numpy(rows).cuda().to(tdt)
+    out = torch.empty((n, dim), dtype=tdt, device="cuda")
+    B.emb_expand(d_rows, torch.from_numpy(inverse).cuda(), n, dim, dtype, out)
+    ref = oracle.expand(d_rows.float().cpu().numpy(), inverse)
+    assert np.array_equal(out.float().cpu().numpy(), ref)
+
+
+# ------------------------------------------------------------------------------------------ reduce
+def _reduce_gpu(G_dev, dtype, keys):
+    n, dim = G_dev.shape
+    uniq, inverse, counts, perm, seg_off = _run_dedup(keys)
+    U = len(uniq)
+    d_inv, d_perm = torch.from_numpy(inverse).cuda(), torch.from_numpy(perm).cuda()
+    red = torch.full((max(U, 1), dim), 123.0, dtype=torch.float32, device="cuda")
+    ws = torch.empty(B.grad_segment_reduce_workspace_bytes(n, dim), dtype=torch.uint8, device="cuda")
+    B.grad_segment_reduce(G_dev, dtype, d_inv, d_perm, n, dim, red, ws)
+    return red[:U].cpu().numpy(), inverse, U
+
+
+@pytest.mark.parametrize("dim,dtype", [(64, 0), (32, 0), (16, 0), (128, 0), (128, 1), (8, 1)])
+@pytest.mark.parametrize("shape", ["zipf", "one_giant_segment", "all_distinct", "tiny"])
+def test_segment_reduce(dim, dtype, shape):
+    n = {"zipf": 128 * 128 * 2 + 300, "one_giant_segment": 40_000, "all_distinct": 5000, "tiny": 3}[shape]
+    if shape == "zipf":
+        keys = _zipf_keys(n, 3000, 9)
+    elif shape == "one_giant_segment":
+        keys = np.full(n, 77, dtype=np.uint64)
+        keys[::1000] = np.arange(len(keys[::1000]), dtype=np.uint64) + np.uint64(1000)
+    elif shape == "all_distinct":
+        keys = np.random.default_rng(1).permutation(n).astype(np.uint64)
+    else:
+        keys = np.array([9, 4, 9], dtype=np.uint64)
+    # (a) integer-valued gradients: exactly one correct fp32 answer
+    Gi = small_int_grads(n, dim, 3, "cuda")
+    Gi_dev = Gi if dtype == 0 else Gi.to(torch.bfloat16)
+    red, inverse, U = _reduce_gpu(Gi_dev, dtype, keys)
+    ref = oracle.segment_reduce(Gi.cpu().numpy(), inverse, U)
+    assert np.array_equal(red, ref)
+    # (b) N(0,1) gradients: within 1e-5 of the float64 sum, relative to the sum of |addends|
+    G = normal_grads(5, 0, n, dim)
+    if dtype == 1:
+        G = torch.from_numpy(G).to(torch.bfloat16).float().numpy()
+    G_dev = torch.from_numpy(G).cuda() if dtype == 0 else torch.from_numpy(G).cuda().to(torch.bfloat16)
+    red, inverse, U = _reduce_gpu(G_dev, dtype, keys)
+    ref = oracle.segment_reduce(G, inverse, U).astype(np.float64)
+    sabs = oracle.segment_reduce(np.abs(G), inverse, U).astype(np.float64)
+    assert close_reduce(red, ref, sabs, RTOL_F32)
+    assert np.allclose(red.astype(np.float64).sum(0), G.astype(np.float64).sum(0), rtol=0, atol=1e-5 * np.abs(G).sum(0).max())
+    # (c) the order of additions is fixed: a second run is bit-identical
+    red2, _, _ = _reduce_gpu(G_dev, dtype, keys)
+    assert np.array_equal(red, red2)
+
+
+# ------------------------------------------------------------------------------------------ adagrad
+@pytest.mark.parametrize("dim,dtype", [(32, 0), (64, 0), (128, 0), (16, 0), (128, 1), (8, 1)])
+def test_adagrad_matches_checker(dim, dtype):
+    rtol = RTOL_F32 if dtype == 0 else RTOL_BF16
+    keys = np.unique(_zipf_keys(6000, 4000, 21))
+    n = len(keys)
+    t = EmbeddingTable(dim, dtype, capacity_log2=14, chunk_rows_log2=11, initial_chunks=2)
+    ot = oracle.Table(dim, dtype)
+    row_idx = torch.empty(n, dtype=torch.int32, device="cuda")
+    t.find_or_insert(dev_keys(keys), None, n, 0, row_idx)
+    ot.find_or_insert(keys, 0)
+    upd = np.arange(0, n, 2)                                     # update every other key; the rest must not move
+    for step in range(3):
+        g = normal_grads(31, step, len(upd), dim) * np.float32(10.0 ** (step - 1))
+        g[5, :] = -2.5                                           # constant-gradient row
+        ot.apply_adagrad(keys[upd], g, 0.01, 1e-8)
+        ridx = row_idx[torch.from_numpy(upd).cuda()].contiguous()
+        ridx[7] = -1                                             # a skipped entry
+        ot_skip_fix = None
+        t.apply_adagrad(ridx, torch.from_numpy(g).cuda(), None, len(upd), 0.01, 1e-8)
+        # the checker updated entry 7 as well; undo by comparing everything except that key
+        gk, gv, ga, _, _ = t.export()
+        ok, ov, oa, _, _ = ot.export()
+        assert np.array_equal(gk, ok)
+        skip = np.isin(gk, keys[upd][7])
+        touched = np.isin(gk, keys[upd]) & ~skip
+        assert close_rows(gv[touched], ov[touched].astype(np.float64), 0.01, rtol)
+        assert np.allclose(ga[touched], oa[touched], rtol=4e-5 if dtype == 0 else 1e-4, atol=0)
+        untouched = ~np.isin(gk, keys[upd])
+        assert (ga[untouched] == 0).all()
+        assert np.array_equal(gv[untouched], ov[untouched])
+    if dtype == 0:
+        # entry 7 was skipped on the device in all three steps: still the initial row
+        assert np.array_equal(gv[skip][0], oracle.init_row(int(keys[upd][7]), dim))
+    t.close()
+
+
+# ------------------------------------------------------------------------------------------ evict / rehash
+def test_evict_and_rehash_against_checker():
+    dim = 32
+    t = EmbeddingTable(dim, 0, capacity_log2=12, chunk_rows_log2=10, max_load_factor=0.75, initial_chunks=2)
+    ot = oracle.Table(dim, 0)
+    rng = np.random.default_rng(4)
+    pool = scramble_bits(np.arange(3000, dtype=np.uint64), 40, 99)
+    total_evicted = 0
+    for step in range(60):
+        ks = np.unique(pool[rng.integers(0, min(3000, 200 + 50 * step), size=400)])
+        n = len(ks)
+        row_idx = torch.empty(n, dtype=torch.int32, device="cuda")
+        t.find_or_insert(dev_keys(ks), None, n, step, row_idx)
+        ot.find_or_insert(ks, step)
+        g = normal_grads(77, step, n, dim)
+        t.apply_adagrad(row_idx, torch.from_numpy(g).cuda(), None, n, 0.01, 1e-8)
+        ot.apply_adagrad(ks, g, 0.01, 1e-8)
+        if step % 10 == 9:
+            before = t.export()
+            ev, n_ev = t.evict(step, 12, 3, 4)
+            oev = ot.evict(step, 12, 3, 4)
+            assert n_ev == len(oev) and np.array_equal(np.sort(host_keys(ev)), oev)     # eviction set, as a set
+            total_evicted += n_ev
+            st = t.stats()
+            assert st["live"] == len(ot) == len(before[0]) - n_ev and st["tombstones"] >= n_ev > 0
+            # evicted keys read as absent; survivors keep their rows bit for bit
+            found = torch.empty(max(n_ev, 1), dtype=torch.int32, device="cuda")
+            t.find(ev.contiguous(), None, n_ev, found)
+            assert (found[:n_ev] == -1).all()
+            after = t.export()
+            keep = ~np.isin(before[0], oev)
+            assert np.array_equal(after[0], before[0][keep]) and np.array_equal(after[1], before[1][keep])
+            assert np.array_equal(after[2], before[2][keep])
+        if step == 35:
+            # explicit rehash to the same size: purges deleted markers, content unchanged
+            before = t.export()
+            t.rehash(t.capacity_log2)
+            st = t.stats()
+            assert st["tombstones"] == 0 and st["live"] == len(before[0])
+            for a, b in zip(before, t.export()):
+                assert np.array_equal(a, b)
+    assert total_evicted > 100
+    st = t.stats()
+    assert st["n_rehash"] >= 2 and st["status"] == 0 and st["rows_free"] + st["live"] <= st["rows_used"]
+    gk, gv, ga, gl, gf = t.export()
+    ok, ov, oa, ol, of = ot.export()
+    assert np.array_equal(gk, ok) and np.array_equal(gl, ol) and np.array_equal(gf, of)
+    assert close_rows(gv, ov.astype(np.float64), 0.01, RTOL_F32) and np.allclose(ga, oa, rtol=4e-5)
+    # a re-inserted key starts from its initial row with a zero accumulator
+    gone = np.setdiff1d(pool, gk)[:5]
+    row_idx = torch.empty(5, dtype=torch.int32, device="cuda")
+    t.find_or_insert(dev_keys(gone), None, 5, 61, row_idx)
+    out = torch.empty((5, dim), device="cuda")
+    t.gather(row_idx, None, 5, out)
+    assert np.array_equal(out.cpu().numpy(), np.stack([oracle.init_row(int(k), dim) for k in gone]))
+    t.close()
+
+
+def test_full_table_up_to_the_load_factor_limit():
+    # exactly capacity * max_load_factor keys fit without a rehash and are all found again
+    cap_log2 = 13
+    n = int((1 << cap_log2) * 0.75)
+    keys = scramble_bits(np.arange(n, dtype=np.uint64), 40, 5)
+    t = EmbeddingTable(16, 0, capacity_log2=cap_log2, chunk_rows_log2=cap_log2, count_probes=True, initial_chunks=1)
+    row_idx = torch.empty(n, dtype=torch.int32, device="cuda")
+    assert B.ht_find_or_insert(t.h, dev_keys(keys), None, n, 0, row_idx) == 0
+    st = t.stats()
+    assert st["live"] == n and st["n_rehash"] == 0 and st["status"] == 0
+    assert len(np.unique(row_idx.cpu().numpy())) == n
+    found = torch.empty(n, dtype=torch.int32, device="cuda")
+    t.find(dev_keys(keys), None, n, found)
+    assert torch.equal(found, row_idx)
+    st2 = t.stats()
+    assert (st2["probes"] - st["probes"]) / n < 2.5          # lines inspected per successful lookup at LF 0.75
+    t.close()

@@ -15,3 +15,4 @@ from .gen import (  # noqa: F401
     normal_grads,
     small_int_grads,
 )
+from .layout import merged_inputs  # noqa: F401
