@@ -1,0 +1,248 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse-embedding step on one MI355X.
+
+A step = tag -> dedup -> find-or-insert -> gather -> expand -> (upstream gradient already in HBM)
+-> gradient segment-reduce -> row-wise Adagrad over one batch of the long-sequence lookup
+configuration (batch 512, lengths U{256..4096}, 8 fields, dim 64 fp32, 50 M-key table, Zipf 1.05).
+Inputs are resident in HBM when the timed region starts.  Prints ONE JSON line on stdout.
+
+    python bench.py [--gpus 1] [--steps 20] [--warmup 3] [--config 2] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+import torch  # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def log(msg: str) -> None:
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(n: int, u: int, u_new: int, v_row: int, v_grad: int, dim: int) -> dict:
+    """Bytes the method itself must move per step (sort passes, probe overshoot and workspace
+    traffic are overhead, not credit).  v_row / v_grad = bytes of a table row / a gradient row."""
+    red_row = 4 * dim
+    b = {
+        "tag_dedup": 8 * n + 8 * u + 4 * n,
+        "find_or_insert": (8 + 12 + 8) * u + (4 + 8) * u + u_new * (12 + v_row + 4 + 8 + 8),
+        "gather": 4 * u + 2 * v_row * u,
+        "expand": 4 * n + v_row * u + v_row * n,
+        "reduce": v_grad * n + 4 * n + red_row * u,
+        "adagrad": 4 * u + red_row * u + v_row * u + 4 * u + v_row * u + 4 * u,
+    }
+    b["total"] = sum(b.values())
+    return b
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, choices=[2, 5])
+    ap.add_argument("--batches", type=int, default=4, help="distinct pre-generated batches cycled through")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--count-probes", action="store_true", help="maintain probe/CAS counters (small overhead)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU's share of the embedding path; run it with --gpus 1 "
+              "(no collectives or sharding are part of it).", file=sys.stderr)
+        return 2
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+
+    from paper_2505_12663_amd import binding as B
+    from paper_2505_12663_amd import EmbeddingTable, StepBuffers
+    from workloads import make_config, merged_inputs
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = make_config(args.config)
+    dims = [w.table_dim(t) for t in range(w.n_tables)]
+    dtypes = [0 if w.table_dtype(t) == "f32" else 1 for t in range(w.n_tables)]
+    merged, n_merged = B.emb_plan_merge(dims, dtypes)
+    assert n_merged == 1
+    tag_bits = B.emb_tag_bits(w.n_tables)
+    dim, dtype = dims[0], dtypes[0]
+    v_row = dim * (4 if dtype == 0 else 2)
+    n_keys = sum(w.prepopulated)
+    cap_log2 = 27 if args.config == 2 else 29
+    chunk_log2 = 24 if args.config == 2 else 26
+    n_chunks = (n_keys >> chunk_log2) + 2
+
+    t0 = time.time()
+    table = EmbeddingTable(dim, dtype, capacity_log2=cap_log2, chunk_rows_log2=chunk_log2, max_load_factor=0.75,
+                           count_probes=args.count_probes, initial_chunks=n_chunks)
+    # ---- bulk load of the pre-existing keys (step 0), in slices
+    slice_n = 1 << 22
+    dk = torch.empty(slice_n, dtype=torch.int64, device=dev)
+    rows = torch.empty(slice_n, dtype=torch.int32, device=dev)
+    err = torch.zeros(1, dtype=torch.int64, device=dev)
+    for t in range(w.n_tables):
+        P = w.prepopulated[t]
+        tag = torch.tensor([t], dtype=torch.uint8, device=dev)
+        for lo in range(0, P, slice_n):
+            hi = min(P, lo + slice_n)
+            x = torch.from_numpy(w.prepopulated_ids(t, lo, hi).view(np.int64)).to(dev)
+            off = torch.tensor([0, hi - lo], dtype=torch.int64, device=dev)
+            B.emb_tag_keys(x, off, tag, tag_bits, dk, err)
+            table.find_or_insert(dk, None, hi - lo, 0, rows)
+        log(f"bulk load: logical table {t} done ({P} keys, {time.time() - t0:.1f}s)")
+    st = table.stats()
+    assert st["live"] == n_keys and st["status"] == 0, st
+    log(f"table ready: live={st['live']} capacity=2^{cap_log2} load={st['live'] / st['capacity']:.3f}")
+
+    # ---- pre-generate the batches and put them in HBM
+    batches = []
+    n_max = 0
+    for s in range(args.batches):
+        b = w.next_step(s)
+        x, off, tags, _ = merged_inputs(w.features, b.ids, merged, 0)
+        batches.append((torch.from_numpy(x.view(np.int64)).to(dev), torch.from_numpy(off).to(dev),
+                        torch.from_numpy(tags).to(dev), len(x), (x, off, tags)))
+        n_max = max(n_max, len(x))
+        log(f"batch {s}: N={len(x)} ({time.time() - t0:.1f}s)")
+    buf = StepBuffers(n_max, dim, dtype)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed)
+    grad = torch.randn((n_max, dim), generator=gen, device=dev, dtype=torch.float32)
+    if dtype == 1:
+        grad = grad.to(torch.bfloat16)
+    v_grad = v_row
+
+    phases = ["tag", "dedup", "find_or_insert", "gather", "expand", "reduce", "adagrad"]
+
+    def one_step(step: int, ev=None):
+        dx, doff, dtag, n, _ = batches[step % len(batches)]
+        rec = (lambda i: ev[i].record()) if ev is not None else (lambda i: None)
+        rec(0)
+        B.emb_tag_keys(dx, doff, dtag, tag_bits, buf.key, buf.err_count)
+        rec(1)
+        B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, None, buf.perm, None, buf.n_unique, buf.dedup_ws)
+        rec(2)
+        table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted)
+        rec(3)
+        table.gather(buf.row_idx, buf.n_unique, n, buf.uniq_rows)
+        rec(4)
+        B.emb_expand(buf.uniq_rows, buf.inverse, n, dim, dtype, buf.out)
+        rec(5)
+        B.grad_segment_reduce(grad, dtype, buf.inverse, buf.perm, n, dim, buf.reduced, buf.reduce_ws)
+        rec(6)
+        table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps)
+        rec(7)
+        return n
+
+    for s in range(args.warmup):
+        one_step(s)
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(len(phases) + 1)] for _ in range(args.steps)]
+    uniques, news, ids = [], [], 0
+    live_before = table.stats()["live"]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for k in range(args.steps):
+        ids += one_step(args.warmup + k, events[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+    ms_per_step = wall * 1e3 / args.steps
+    live_after = table.stats()["live"]
+
+    phase_ms = {p: float(np.mean([events[k][i].elapsed_time(events[k][i + 1]) for k in range(args.steps)]))
+                for i, p in enumerate(phases)}
+    # U per batch (not on the timed path)
+    u_of = {}
+    for s in range(len(batches)):
+        one_step(s)
+        u_of[s] = int(buf.n_unique.item())
+    n_avg = ids / args.steps
+    u_avg = float(np.mean([u_of[(args.warmup + k) % len(batches)] for k in range(args.steps)]))
+    u_new = (live_after - live_before) / args.steps
+    ab = algorithmic_bytes(int(n_avg), int(u_avg), int(u_new), v_row, v_grad, dim)
+    achieved = ab["total"] / (ms_per_step * 1e-3) / 1e9
+
+    # dominant kernel: the expand (one kernel = one phase): its own algorithmic bytes over its own time
+    dom = "expand"
+    dom_gbps = ab[dom] / (phase_ms[dom] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "k_copy_rows (emb_expand)", "achieved": round(dom_gbps, 1),
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                "bytes_per_launch": ab[dom], "avg_ms": round(phase_ms[dom], 4)}
+
+    result = {
+        "metric": "embedding IDs/sec fwd+bwd",
+        "value": round(ids / wall, 1),
+        "unit": "IDs/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if dtype == 0 else "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"config{args.config}:{w.name}", "batch": w.batch, "fields": len(w.features), "dim": dim,
+                   "table_keys": n_keys, "capacity_log2": cap_log2, "ids_per_step": int(n_avg),
+                   "unique_per_step": int(u_avg), "new_keys_per_step": round(u_new, 1)},
+        "unique_ids_per_sec": round(u_avg * args.steps / wall, 1),
+        "algorithmic_bytes_per_step": ab["total"],
+        "achieved_hbm_gbps": round(achieved, 1),
+        "hbm_frac_of_8TBps": round(achieved / HBM_PEAK_GBPS, 4),
+        "phase_ms": {k: round(v, 4) for k, v in phase_ms.items()},
+        "phase_gbps": {p: round(ab[q] / (phase_ms[p] * 1e-3) / 1e9, 1) for p, q in
+                       [("dedup", "tag_dedup"), ("find_or_insert", "find_or_insert"), ("gather", "gather"),
+                        ("expand", "expand"), ("reduce", "reduce"), ("adagrad", "adagrad")]},
+        "roofline": roofline,
+    }
+    if args.count_probes:
+        st = table.stats()
+        result["probe_counters"] = {k: st[k] for k in ("lookups", "probes", "cas_attempts", "cas_failures", "alloc_atomics")}
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, batches[0][4], tag_bits, dim, dtype, n_keys)
+    print(json.dumps(result), flush=True)
+    table.close()
+    return 0
+
+
+def cpu_baseline(w, batch0, tag_bits, dim, dtype, n_keys) -> dict:
+    """The CPU checker as it stands, one thread, timed on one full step of the first batch.
+    Pre-existing keys the step touches are materialised first (untimed), as the lazy checker does."""
+    import oracle
+    x, off, tags = batch0
+    log("cpu baseline: preparing (untimed)")
+    key, _ = oracle.tag_keys(x, off, tags, tag_bits)
+    uniq, _, _ = oracle.dedup(key)
+    t = oracle.Table(dim, dtype)
+    t.prepopulate(uniq)
+    rng = np.random.Generator(np.random.Philox(key=1234))
+    G = rng.standard_normal((len(x), dim), dtype=np.float32)
+    log("cpu baseline: timing one step")
+    t0 = time.perf_counter()
+    key, _ = oracle.tag_keys(x, off, tags, tag_bits)
+    uniq, inverse, _ = oracle.dedup(key)
+    t.find_or_insert(uniq, 1)
+    E_u = t.lookup(uniq)
+    E = oracle.expand(E_u, inverse)
+    g = oracle.segment_reduce(G, inverse, len(uniq))
+    t.apply_adagrad(uniq, g, w.lr, w.eps)
+    dt = time.perf_counter() - t0
+    assert E.shape == (len(x), dim)
+    return {"value": round(len(x) / dt, 1), "unit": "IDs/s", "cores": 1, "kind": "oracle",
+            "sample": f"one full step of batch 0 ({len(x)} IDs, {len(uniq)} unique), touched keys pre-materialised",
+            "seconds": round(dt, 2), "host_cpus": os.cpu_count()}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

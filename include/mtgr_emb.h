@@ -120,13 +120,15 @@ int ht_set_key_storage(emb_table_t* t, uint64_t* keys, uint32_t* rows, int capac
 
 /* Register one more value chunk of 2^chunk_rows_log2 rows (Sec. 3.1: chunked embedding
  * structure; keep a spare chunk registered so inserts never wait for an allocation).
- * values [dev]: rows x dim elements of the table dtype;  acc [dev]: rows x f32 Adagrad
- * accumulators;  last_seen, freq [dev]: rows x u32;  free_list [dev]: rows x u32 scratch for the
- * row free list.  Contents need no initialisation. */
-int ht_add_chunk(emb_table_t* t, void* values, float* acc, uint32_t* last_seen, uint32_t* freq,
-                 uint32_t* free_list, void* stream);
+ * values [dev, 16-byte aligned]: rows x dim elements of the table dtype;
+ * meta [dev, 16-byte aligned]: rows x 16 bytes of per-row auxiliary data (Adagrad accumulator f32,
+ *   last-seen step u32, touch count u32, 4 reserved bytes);
+ * free_list [dev]: rows x u32 scratch for the row free list.  Contents need no initialisation. */
+int ht_add_chunk(emb_table_t* t, void* values, void* meta, uint32_t* free_list, void* stream);
 
-/* Host-side capacity planning from the counts last seen by ht_stats plus everything issued since.
+/* Host-side capacity planning from upper bounds of the device counters: the newest copy of the
+ * counters that has reached the host (every find-or-insert / evict / rehash queues one, without
+ * blocking; ht_stats fetches one synchronously) plus the n_max of every find-or-insert issued since.
  * n_incoming = upper bound of keys the next find-or-insert may add.
  * *new_capacity_log2 = 0 if the key structure is fine, else the size to rehash to: the same size
  * when purging deleted slots is enough, otherwise doubled until (live+n_incoming)/capacity is at

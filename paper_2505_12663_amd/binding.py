@@ -70,7 +70,7 @@ def load():
         "emb_table_create": (C.c_int, [C.POINTER(vp), C.POINTER(TableDesc), vp, C.c_size_t, vp]),
         "emb_table_destroy": (C.c_int, [vp]),
         "ht_set_key_storage": (C.c_int, [vp, vp, vp, i32, vp]),
-        "ht_add_chunk": (C.c_int, [vp, vp, vp, vp, vp, vp, vp]),
+        "ht_add_chunk": (C.c_int, [vp, vp, vp, vp, vp]),
         "ht_plan": (C.c_int, [vp, i64, C.POINTER(C.c_int), C.POINTER(C.c_int)]),
         "ht_rehash": (C.c_int, [vp, vp, vp, i32, vp]),
         "ht_stats": (C.c_int, [vp, C.POINTER(HtStats), vp]),
@@ -159,9 +159,8 @@ def ht_set_key_storage(h, keys, rows, capacity_log2: int, stream=None) -> None:
     _check(load().ht_set_key_storage(h, _ptr(keys), _ptr(rows), capacity_log2, _stream(stream)), "ht_set_key_storage")
 
 
-def ht_add_chunk(h, values, acc, last_seen, freq, free_list, stream=None) -> None:
-    _check(load().ht_add_chunk(h, _ptr(values), _ptr(acc), _ptr(last_seen), _ptr(freq), _ptr(free_list),
-                               _stream(stream)), "ht_add_chunk")
+def ht_add_chunk(h, values, meta, free_list, stream=None) -> None:
+    _check(load().ht_add_chunk(h, _ptr(values), _ptr(meta), _ptr(free_list), _stream(stream)), "ht_add_chunk")
 
 
 def ht_plan(h, n_incoming: int):

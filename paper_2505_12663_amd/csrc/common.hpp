@@ -14,6 +14,15 @@ constexpr uint32_t kRowInvalid = 0xFFFFFFFFu;
 constexpr int kLineSlots = 8;                         // one probe = one aligned 64-byte line of keys
 constexpr int kMaxChunks = 256;
 
+// Per-row auxiliary data of the embedding structure, one 16-byte record per row so that the
+// touch of find-or-insert and the accumulator update of the optimizer hit the same line.
+struct __attribute__((aligned(16))) RowMeta {
+    float acc;           // row-wise Adagrad accumulator
+    uint32_t last_seen;  // step of the last find-or-insert touch
+    uint32_t freq;       // number of touches
+    uint32_t reserved;
+};
+
 // Device-resident table state: counters + chunk directory.  Lives in caller memory.
 struct HtState {
     unsigned long long live;
@@ -25,10 +34,18 @@ struct HtState {
     unsigned long long lookups, probes, cas_attempts, cas_failures, alloc_atomics;
     unsigned long long pad1[7];
     void* values[kMaxChunks];
-    float* acc[kMaxChunks];
-    uint32_t* last_seen[kMaxChunks];
-    uint32_t* freq[kMaxChunks];
+    RowMeta* meta[kMaxChunks];
     uint32_t* free_list[kMaxChunks];
+};
+
+// The first 32 bytes of HtState, as copied to the host.
+struct HtCounts {
+    unsigned long long live;
+    unsigned long long tombstones;
+    unsigned int bump;
+    int free_count;
+    unsigned int status;
+    unsigned int pad0;
 };
 
 // What a table kernel needs, passed by value.
@@ -128,6 +145,7 @@ inline int check_hip(hipError_t e) { return e == hipSuccess ? EMB_OK : EMB_ERR_H
 
 // The host object behind emb_table_t.
 struct emb_table {
+    static constexpr int kSnaps = 4;
     emb_table_desc_t desc;
     mtgr::HtState* st;          // device
     uint64_t* keys;             // device
@@ -136,10 +154,54 @@ struct emb_table {
     int n_chunks;
     int row_bytes;
     uint64_t n_rehash;
-    // host-side upper bounds between two ht_stats calls
-    uint64_t occupied_bound;    // live + tombstones
-    uint64_t live_bound;
-    uint64_t rows_used_bound;   // bump + never below what is on the free list
+    // Host-side upper bounds of the device counters: exact values as of some point of the
+    // stream (`base_*`) plus the n_max of every find-or-insert issued after that point.  The
+    // base advances without blocking: each state-changing call queues a copy of the counters to
+    // pinned host memory followed by an event, and the newest completed copy is adopted.
+    uint64_t base_live, base_tomb, base_rows;
+    uint64_t pending;
+    mtgr::HtCounts* snap_host;             // pinned, kSnaps entries
+    hipEvent_t snap_ev[kSnaps];
+    uint64_t snap_seq[kSnaps];             // 0 = never recorded
+    uint64_t snap_pending_after[kSnaps];   // n_max issued after the snapshot was queued
+    uint64_t seq, min_valid_seq, base_seq;
+    int snap_next;
+
+    uint64_t live_bound() const { return base_live + pending; }
+    uint64_t occupied_bound() const { return base_live + base_tomb + pending; }
+    uint64_t rows_used_bound() const { return base_rows + pending; }
+
+    void adopt(const mtgr::HtCounts& c, uint64_t pending_after, uint64_t s) {
+        base_live = c.live;
+        base_tomb = c.tombstones;
+        const uint64_t freec = c.free_count > 0 ? (uint64_t)c.free_count : 0ull;
+        base_rows = (uint64_t)c.bump > freec ? (uint64_t)c.bump - freec : 0ull;
+        pending = pending_after;
+        base_seq = s;
+    }
+    // adopt the newest completed snapshot, if any is newer than the current base
+    void refresh() {
+        int best = -1;
+        for (int i = 0; i < kSnaps; ++i) {
+            if (snap_seq[i] == 0 || snap_seq[i] < min_valid_seq || snap_seq[i] <= base_seq) continue;
+            if (best >= 0 && snap_seq[i] < snap_seq[best]) continue;
+            if (hipEventQuery(snap_ev[i]) == hipSuccess) best = i;
+        }
+        if (best >= 0) adopt(snap_host[best], snap_pending_after[best], snap_seq[best]);
+    }
+    void issued(uint64_t n_max) {
+        pending += n_max;
+        for (int i = 0; i < kSnaps; ++i) snap_pending_after[i] += n_max;
+    }
+    int snapshot(hipStream_t s) {
+        const int i = snap_next;
+        snap_next = (snap_next + 1) % kSnaps;
+        if (hipMemcpyAsync(&snap_host[i], st, sizeof(mtgr::HtCounts), hipMemcpyDeviceToHost, s) != hipSuccess) return EMB_ERR_HIP;
+        if (hipEventRecord(snap_ev[i], s) != hipSuccess) return EMB_ERR_HIP;
+        snap_seq[i] = ++seq;
+        snap_pending_after[i] = 0;
+        return EMB_OK;
+    }
 
     mtgr::HtView view() const {
         mtgr::HtView v;

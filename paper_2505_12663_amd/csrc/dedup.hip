@@ -75,15 +75,12 @@ __global__ void k_zero64(unsigned long long* p) {
 }
 
 // ---------------------------------------------------------------------------- which digits vary
-__global__ void k_dd_init(DdHeader* h) {
-    if (threadIdx.x == 0 && blockIdx.x == 0) {
-        h->or_mask = 0ull;
-        h->and_mask = ~0ull;
-        h->n_unique = 0;
-    }
-}
+constexpr int kMaskBlocks = 1024;
 
-__global__ __launch_bounds__(kThreads) void k_dd_masks(const uint64_t* __restrict__ key, int64_t n, DdHeader* h) {
+// every block ORs / ANDs its share of the keys and leaves one pair in `partial` (no atomics)
+__global__ __launch_bounds__(kThreads) void k_dd_masks(const uint64_t* __restrict__ key, int64_t n,
+                                                      unsigned long long* __restrict__ partial) {
+    __shared__ unsigned long long s_o[kWaves], s_a[kWaves];
     uint64_t o = 0ull, a = ~0ull;
     const int64_t stride = (int64_t)gridDim.x * kThreads;
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
@@ -96,14 +93,47 @@ __global__ __launch_bounds__(kThreads) void k_dd_masks(const uint64_t* __restric
         a &= shfl64(a, lane_id() ^ s);
     }
     if (lane_id() == 0) {
-        atomicOr(&h->or_mask, (unsigned long long)o);
-        atomicAnd(&h->and_mask, (unsigned long long)a);
+        s_o[threadIdx.x / kWave] = o;
+        s_a[threadIdx.x / kWave] = a;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < kWaves; ++w) {
+            o |= s_o[w];
+            a &= s_a[w];
+        }
+        partial[2 * blockIdx.x] = o;
+        partial[2 * blockIdx.x + 1] = a;
     }
 }
 
-__global__ void k_dd_plan(DdHeader* h) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    const unsigned long long varying = h->or_mask ^ h->and_mask;
+// one block: combine the partial masks, then lay out the passes
+__global__ __launch_bounds__(kThreads) void k_dd_plan(DdHeader* h, const unsigned long long* __restrict__ partial,
+                                                     int n_partial) {
+    __shared__ unsigned long long s_o[kWaves], s_a[kWaves];
+    uint64_t o = 0ull, a = ~0ull;
+    for (int i = threadIdx.x; i < n_partial; i += kThreads) {
+        o |= partial[2 * i];
+        a &= partial[2 * i + 1];
+    }
+    for (int s = 32; s > 0; s >>= 1) {
+        o |= shfl64(o, lane_id() ^ s);
+        a &= shfl64(a, lane_id() ^ s);
+    }
+    if (lane_id() == 0) {
+        s_o[threadIdx.x / kWave] = o;
+        s_a[threadIdx.x / kWave] = a;
+    }
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    for (int w = 1; w < kWaves; ++w) {
+        o |= s_o[w];
+        a &= s_a[w];
+    }
+    h->or_mask = o;
+    h->and_mask = a;
+    h->n_unique = 0;
+    const unsigned long long varying = o ^ a;
     int cur = 0;
     for (int p = 0; p < kPasses; ++p) {
         const bool act = ((varying >> (8 * p)) & 0xFFull) != 0ull;
@@ -389,7 +419,7 @@ __global__ void k_empty_result(int64_t* n_unique, int32_t* seg_off) {
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct DdLayout {
-    size_t header, ka, kb, ia, ib, tile_hist, digit_total, tile_heads, seg_off, total;
+    size_t header, masks, ka, kb, ia, ib, tile_hist, digit_total, tile_heads, seg_off, total;
     unsigned n_tiles;
 };
 DdLayout dd_layout(int64_t n) {
@@ -397,6 +427,7 @@ DdLayout dd_layout(int64_t n) {
     L.n_tiles = (unsigned)((n + kTile - 1) / kTile);
     size_t o = 0;
     L.header = o; o = align_up(o + sizeof(DdHeader), 256);
+    L.masks = o; o = align_up(o + (size_t)kMaskBlocks * 16, 256);
     L.ka = o; o = align_up(o + (size_t)n * 8, 256);
     L.kb = o; o = align_up(o + (size_t)n * 8, 256);
     L.ia = o; o = align_up(o + (size_t)n * 4, 256);
@@ -461,10 +492,10 @@ int emb_dedup(const uint64_t* key, int64_t n, uint64_t* uniq, int32_t* inverse, 
     int32_t* seg = seg_off ? seg_off : reinterpret_cast<int32_t*>(w + L.seg_off);
     const unsigned n_tiles = L.n_tiles;
 
-    hipLaunchKernelGGL(k_dd_init, dim3(1), dim3(64), 0, s, hdr);
-    unsigned mgrid = n_tiles < 2048u ? n_tiles : 2048u;
-    hipLaunchKernelGGL(k_dd_masks, dim3(mgrid), dim3(kThreads), 0, s, key, n, hdr);
-    hipLaunchKernelGGL(k_dd_plan, dim3(1), dim3(64), 0, s, hdr);
+    unsigned long long* masks = reinterpret_cast<unsigned long long*>(w + L.masks);
+    const unsigned mgrid = n_tiles < (unsigned)kMaskBlocks ? n_tiles : (unsigned)kMaskBlocks;
+    hipLaunchKernelGGL(k_dd_masks, dim3(mgrid), dim3(kThreads), 0, s, key, n, masks);
+    hipLaunchKernelGGL(k_dd_plan, dim3(1), dim3(kThreads), 0, s, hdr, masks, (int)mgrid);
     MTGR_LAUNCH_CHECK();
     for (int p = 0; p < kPasses; ++p) {
         hipLaunchKernelGGL(k_rs_hist, dim3(n_tiles), dim3(kThreads), 0, s, b, hdr, p, n, n_tiles, tile_hist);

@@ -342,7 +342,7 @@ __global__ __launch_bounds__(kBlock) void k_adagrad(HtView v, const int32_t* __r
             for (int o = LPR / 2; o > 0; o >>= 1) ss += __shfl_xor(ss, o, kWave);
             if (!on[u]) continue;
             const uint32_t row = (uint32_t)idx[u];
-            float* accp = &v.st->acc[row >> v.chunk_log2][row & ((1u << v.chunk_log2) - 1u)];
+            float* accp = &v.st->meta[row >> v.chunk_log2][row & ((1u << v.chunk_log2) - 1u)].acc;
             const float acc = *accp + ss * inv_d;
             const float scale = lr / (sqrtf(acc) + eps);
             if (lane_on) {

@@ -4,6 +4,8 @@
 // coverage), sub-wave cooperative probing (8 lanes inspect one line with one coalesced
 // load), CAS insertion into never-used slots only, deleted markers, wave-aggregated
 // row allocation, key-only rehash.
+#include <cstddef>
+
 #include "common.hpp"
 
 using namespace mtgr;
@@ -16,7 +18,8 @@ __device__ inline void* chunk_row_ptr(const HtView& v, uint32_t row) {
     char* base = static_cast<char*>(v.st->values[row >> v.chunk_log2]);
     return base + (size_t)(row & ((1u << v.chunk_log2) - 1u)) * (size_t)v.row_bytes;
 }
-#define CHUNK_META(v, field, row) ((v).st->field[(row) >> (v).chunk_log2][(row) & ((1u << (v).chunk_log2) - 1u)])
+#define CHUNK_META(v, row) ((v).st->meta[(row) >> (v).chunk_log2][(row) & ((1u << (v).chunk_log2) - 1u)])
+#define CHUNK_FREE(v, pos) ((v).st->free_list[(pos) >> (v).chunk_log2][(pos) & ((1u << (v).chunk_log2) - 1u)])
 
 // --------------------------------------------------------------------------------------------
 __global__ void k_fill_keys(uint64_t* keys, uint32_t* rows, uint64_t n) {
@@ -33,13 +36,10 @@ __global__ void k_zero_bytes(uint32_t* p, size_t n_words) {
     if (i < n_words) p[i] = 0u;
 }
 
-__global__ void k_set_chunk(HtState* st, int c, void* values, float* acc, uint32_t* last_seen, uint32_t* freq,
-                            uint32_t* free_list) {
+__global__ void k_set_chunk(HtState* st, int c, void* values, RowMeta* meta, uint32_t* free_list) {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
         st->values[c] = values;
-        st->acc[c] = acc;
-        st->last_seen[c] = last_seen;
-        st->freq[c] = freq;
+        st->meta[c] = meta;
         st->free_list[c] = free_list;
     }
 }
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(kBlock) void k_find_or_insert(HtView v, const uint6
             int r = rank_in(m_new, lane);
             if (r < take) {
                 unsigned p = (unsigned)(old_free - 1 - r);
-                my_row = CHUNK_META(v, free_list, p);
+                my_row = CHUNK_FREE(v, p);
             } else {
                 my_row = bump_base + (unsigned)(r - take);
             }
@@ -210,9 +210,7 @@ __global__ __launch_bounds__(kBlock) void k_find_or_insert(HtView v, const uint6
         }
     }
     if (my_created) {
-        CHUNK_META(v, acc, my_row) = 0.0f;
-        CHUNK_META(v, freq, my_row) = 0u;
-        CHUNK_META(v, last_seen, my_row) = step;
+        CHUNK_META(v, my_row) = RowMeta{0.0f, step, 0u, 0u};
         v.rows[my_slot] = my_row;
     }
     // ---- results.  A lane that found a key another group is still inserting sees no row yet:
@@ -269,8 +267,9 @@ __global__ __launch_bounds__(kBlock) void k_touch(HtView v, const int64_t* n_dev
         row_idx[i] = r;
     }
     if (r >= 0) {
-        atomicAdd(&CHUNK_META(v, freq, (uint32_t)r), 1u);
-        CHUNK_META(v, last_seen, (uint32_t)r) = step;
+        RowMeta* m = &CHUNK_META(v, (uint32_t)r);
+        atomicAdd(&m->freq, 1u);
+        m->last_seen = step;
     }
 }
 
@@ -331,8 +330,9 @@ __global__ __launch_bounds__(kBlock) void k_evict(HtView v, uint64_t n_slots, ui
         if (k != kEmptyKey && k != kTombKey) {
             row = v.rows[slot];
             if (row != kRowInvalid) {
-                uint32_t age = now - CHUNK_META(v, last_seen, row);
-                uint32_t fq = CHUNK_META(v, freq, row);
+                const RowMeta m = CHUNK_META(v, row);
+                uint32_t age = now - m.last_seen;
+                uint32_t fq = m.freq;
                 bool stale = ttl > 0 && age >= ttl;
                 bool rare = min_freq > 0 && fq < min_freq && age >= grace;
                 go = stale || rare;
@@ -357,7 +357,7 @@ __global__ __launch_bounds__(kBlock) void k_evict(HtView v, uint64_t n_slots, ui
         const int r = rank_in(m, lane);
         v.keys[slot] = kTombKey;
         v.rows[slot] = kRowInvalid;
-        CHUNK_META(v, free_list, (unsigned)(free_base + r)) = row;
+        CHUNK_FREE(v, (unsigned)(free_base + r)) = row;
         if (evicted_keys && (int64_t)(out_base + r) < evicted_cap) evicted_keys[out_base + r] = k;
     }
 }
@@ -423,9 +423,10 @@ __global__ __launch_bounds__(kBlock) void k_export(HtView v, uint64_t n_slots, u
     const unsigned long long pos = base + rank_in(m, lane);
     if (liveslot && (int64_t)pos < cap) {
         keys[pos] = k;
-        if (acc) acc[pos] = CHUNK_META(v, acc, row);
-        if (last_seen) last_seen[pos] = CHUNK_META(v, last_seen, row);
-        if (freq) freq[pos] = CHUNK_META(v, freq, row);
+        const RowMeta m = CHUNK_META(v, row);
+        if (acc) acc[pos] = m.acc;
+        if (last_seen) last_seen[pos] = m.last_seen;
+        if (freq) freq[pos] = m.freq;
     }
     if (!values) return;
     while (m) {
@@ -508,12 +509,31 @@ int emb_table_create(emb_table_t** out, const emb_table_desc_t* desc, void* stat
     t->n_chunks = 0;
     t->row_bytes = row_bytes;
     t->n_rehash = 0;
-    t->occupied_bound = t->live_bound = t->rows_used_bound = 0;
+    t->base_live = t->base_tomb = t->base_rows = t->pending = 0;
+    t->seq = t->base_seq = 0;
+    t->min_valid_seq = 1;
+    t->snap_next = 0;
+    t->snap_host = nullptr;
+    if (hipHostMalloc(reinterpret_cast<void**>(&t->snap_host), sizeof(HtCounts) * emb_table::kSnaps, hipHostMallocDefault) !=
+        hipSuccess) {
+        delete t;
+        return EMB_ERR_HIP;
+    }
+    for (int i = 0; i < emb_table::kSnaps; ++i) {
+        t->snap_seq[i] = 0;
+        t->snap_pending_after[i] = 0;
+        if (hipEventCreateWithFlags(&t->snap_ev[i], hipEventDisableTiming) != hipSuccess) {
+            for (int j = 0; j < i; ++j) (void)hipEventDestroy(t->snap_ev[j]);
+            (void)hipHostFree(t->snap_host);
+            delete t;
+            return EMB_ERR_HIP;
+        }
+    }
     const size_t words = emb_table_state_bytes() / 4;
     hipLaunchKernelGGL(k_zero_bytes, dim3(blocks_for(words, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<uint32_t*>(state), words);
     if (hipGetLastError() != hipSuccess) {
-        delete t;
+        emb_table_destroy(t);
         return EMB_ERR_HIP;
     }
     *out = t;
@@ -521,13 +541,16 @@ int emb_table_create(emb_table_t** out, const emb_table_desc_t* desc, void* stat
 }
 
 int emb_table_destroy(emb_table_t* t) {
+    if (!t) return EMB_OK;
+    for (int i = 0; i < emb_table::kSnaps; ++i) (void)hipEventDestroy(t->snap_ev[i]);
+    if (t->snap_host) (void)hipHostFree(t->snap_host);
     delete t;
     return EMB_OK;
 }
 
 int ht_set_key_storage(emb_table_t* t, uint64_t* keys, uint32_t* rows, int capacity_log2, void* stream) {
     if (!t || !keys || !rows || capacity_log2 < 6 || capacity_log2 > 30) return EMB_ERR_INVALID_ARG;
-    if (t->keys && t->live_bound > 0) return EMB_ERR_INVALID_ARG; // non-empty table: use ht_rehash
+    if (t->keys && t->live_bound() > 0) return EMB_ERR_INVALID_ARG; // non-empty table: use ht_rehash
     const uint64_t n = 1ull << capacity_log2;
     hipLaunchKernelGGL(k_fill_keys, dim3(blocks_for(n, 256 * 8) > 65535u * 16 ? 65535u * 16 : blocks_for(n, 256 * 8)),
                        dim3(256), 0, static_cast<hipStream_t>(stream), keys, rows, n);
@@ -535,19 +558,16 @@ int ht_set_key_storage(emb_table_t* t, uint64_t* keys, uint32_t* rows, int capac
     t->keys = keys;
     t->rows = rows;
     t->cap_log2 = capacity_log2;
-    t->occupied_bound = 0;
-    t->live_bound = 0;
     return EMB_OK;
 }
 
-int ht_add_chunk(emb_table_t* t, void* values, float* acc, uint32_t* last_seen, uint32_t* freq,
-                 uint32_t* free_list, void* stream) {
-    if (!t || !values || !acc || !last_seen || !freq || !free_list) return EMB_ERR_INVALID_ARG;
+int ht_add_chunk(emb_table_t* t, void* values, void* meta, uint32_t* free_list, void* stream) {
+    if (!t || !values || !meta || !free_list) return EMB_ERR_INVALID_ARG;
     if (t->n_chunks >= kMaxChunks) return EMB_ERR_NO_STORAGE;
     if (((uint64_t)(t->n_chunks + 1) << t->desc.chunk_rows_log2) > 0x7FFFFFFFull) return EMB_ERR_NO_STORAGE;
-    if (reinterpret_cast<uintptr_t>(values) & 15) return EMB_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(values) & 15) || (reinterpret_cast<uintptr_t>(meta) & 15)) return EMB_ERR_INVALID_ARG;
     hipLaunchKernelGGL(k_set_chunk, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), t->st, t->n_chunks, values,
-                       acc, last_seen, freq, free_list);
+                       static_cast<RowMeta*>(meta), free_list);
     MTGR_LAUNCH_CHECK();
     t->n_chunks += 1;
     return EMB_OK;
@@ -555,21 +575,22 @@ int ht_add_chunk(emb_table_t* t, void* values, float* acc, uint32_t* last_seen, 
 
 int ht_plan(emb_table_t* t, int64_t n_incoming, int* new_capacity_log2, int* chunks_needed) {
     if (!t || n_incoming < 0) return EMB_ERR_INVALID_ARG;
+    t->refresh();
     if (new_capacity_log2) {
         *new_capacity_log2 = 0;
         if (t->keys) {
             const double cap = (double)(1ull << t->cap_log2);
             const double lf = t->desc.max_load_factor;
-            if ((double)(t->occupied_bound + (uint64_t)n_incoming) > lf * cap) {
+            if ((double)(t->occupied_bound() + (uint64_t)n_incoming) > lf * cap) {
                 int c = t->cap_log2;
-                while ((double)(t->live_bound + (uint64_t)n_incoming) > 0.5 * lf * (double)(1ull << c) && c < 30) ++c;
+                while ((double)(t->live_bound() + (uint64_t)n_incoming) > 0.5 * lf * (double)(1ull << c) && c < 30) ++c;
                 *new_capacity_log2 = c;
             }
         }
     }
     if (chunks_needed) {
         const uint64_t have = (uint64_t)t->n_chunks << t->desc.chunk_rows_log2;
-        const uint64_t want = t->rows_used_bound + (uint64_t)n_incoming;
+        const uint64_t want = t->rows_used_bound() + (uint64_t)n_incoming;
         const uint64_t per = 1ull << t->desc.chunk_rows_log2;
         *chunks_needed = want > have ? (int)((want - have + per - 1) / per) : 0;
     }
@@ -578,10 +599,11 @@ int ht_plan(emb_table_t* t, int64_t n_incoming, int* new_capacity_log2, int* chu
 
 static int check_insert_room(emb_table_t* t, int64_t n_max) {
     if (!t->keys) return EMB_ERR_NO_STORAGE;
+    t->refresh();
     const double cap = (double)(1ull << t->cap_log2);
-    if ((double)(t->occupied_bound + (uint64_t)n_max) > (double)t->desc.max_load_factor * cap) return EMB_ERR_NEED_REHASH;
+    if ((double)(t->occupied_bound() + (uint64_t)n_max) > (double)t->desc.max_load_factor * cap) return EMB_ERR_NEED_REHASH;
     const uint64_t have = (uint64_t)t->n_chunks << t->desc.chunk_rows_log2;
-    if (t->rows_used_bound + (uint64_t)n_max > have) return EMB_ERR_NO_STORAGE;
+    if (t->rows_used_bound() + (uint64_t)n_max > have) return EMB_ERR_NO_STORAGE;
     return EMB_OK;
 }
 
@@ -604,10 +626,8 @@ int ht_find_or_insert(emb_table_t* t, const uint64_t* key, const int64_t* n_dev,
     MTGR_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_touch, dim3(grid), dim3(kBlock), 0, s, v, n_dev, n_max, step, row_idx);
     MTGR_LAUNCH_CHECK();
-    t->occupied_bound += (uint64_t)n_max;
-    t->live_bound += (uint64_t)n_max;
-    t->rows_used_bound += (uint64_t)n_max;
-    return EMB_OK;
+    t->issued((uint64_t)n_max);
+    return t->snapshot(s);
 }
 
 int ht_find(emb_table_t* t, const uint64_t* key, const int64_t* n_dev, int64_t n_max, int32_t* row_idx,
@@ -640,7 +660,7 @@ int ht_evict(emb_table_t* t, uint32_t now, uint32_t ttl, uint32_t min_freq, uint
     hipLaunchKernelGGL(k_evict, dim3(blocks_for(n_slots, kBlock)), dim3(kBlock), 0, s, v, n_slots, now, ttl, min_freq,
                        grace, evicted_keys, evicted_cap, reinterpret_cast<unsigned long long*>(n_evicted));
     MTGR_LAUNCH_CHECK();
-    return EMB_OK;
+    return t->snapshot(s);
 }
 
 int ht_rehash(emb_table_t* t, uint64_t* new_keys, uint32_t* new_rows, int new_capacity_log2, void* stream) {
@@ -648,7 +668,8 @@ int ht_rehash(emb_table_t* t, uint64_t* new_keys, uint32_t* new_rows, int new_ca
     if (!t->keys) return EMB_ERR_NO_STORAGE;
     if (new_keys == t->keys || new_rows == t->rows) return EMB_ERR_INVALID_ARG;
     // the live keys (last ht_stats count plus inserts issued since) must fit under the limit
-    if ((double)t->live_bound > (double)t->desc.max_load_factor * (double)(1ull << new_capacity_log2))
+    t->refresh();
+    if ((double)t->live_bound() > (double)t->desc.max_load_factor * (double)(1ull << new_capacity_log2))
         return EMB_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint64_t n_new = 1ull << new_capacity_log2;
@@ -665,21 +686,18 @@ int ht_rehash(emb_table_t* t, uint64_t* new_keys, uint32_t* new_rows, int new_ca
     t->rows = new_rows;
     t->cap_log2 = new_capacity_log2;
     t->n_rehash += 1;
-    t->occupied_bound = t->live_bound; // deleted markers are gone
-    return EMB_OK;
+    t->base_tomb = 0;                   // deleted markers are gone;
+    t->min_valid_seq = t->seq + 1;      // counter copies queued before this point still show them
+    return t->snapshot(s);
 }
 
 int ht_stats(emb_table_t* t, ht_stats_t* out, void* stream) {
     if (!t || !out) return EMB_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    struct Head {
-        unsigned long long live, tombstones;
-        unsigned int bump;
-        int free_count;
-        unsigned int status, pad0;
-        unsigned long long lookups, probes, cas_attempts, cas_failures, alloc_atomics;
-    } h;
-    if (hipMemcpyAsync(&h, t->st, sizeof(h), hipMemcpyDeviceToHost, s) != hipSuccess) return EMB_ERR_HIP;
+    HtState full;
+    HtCounts& h = *reinterpret_cast<HtCounts*>(&full);
+    const size_t head_bytes = offsetof(HtState, pad1);
+    if (hipMemcpyAsync(&full, t->st, head_bytes, hipMemcpyDeviceToHost, s) != hipSuccess) return EMB_ERR_HIP;
     if (hipStreamSynchronize(s) != hipSuccess) return EMB_ERR_HIP;
     out->live = h.live;
     out->tombstones = h.tombstones;
@@ -690,15 +708,14 @@ int ht_stats(emb_table_t* t, ht_stats_t* out, void* stream) {
     out->n_rehash = t->n_rehash;
     out->n_chunks = (uint64_t)t->n_chunks;
     out->status = h.status;
-    out->lookups = h.lookups;
-    out->probes = h.probes;
-    out->cas_attempts = h.cas_attempts;
-    out->cas_failures = h.cas_failures;
-    out->alloc_atomics = h.alloc_atomics;
-    // exact numbers replace the running upper bounds
-    t->live_bound = h.live;
-    t->occupied_bound = h.live + h.tombstones;
-    t->rows_used_bound = (uint64_t)h.bump - out->rows_free;
+    out->lookups = full.lookups;
+    out->probes = full.probes;
+    out->cas_attempts = full.cas_attempts;
+    out->cas_failures = full.cas_failures;
+    out->alloc_atomics = full.alloc_atomics;
+    // exact numbers replace the running upper bounds; older counter copies are obsolete
+    t->adopt(h, 0, t->seq);
+    t->min_valid_seq = t->seq + 1;
     return EMB_OK;
 }
 

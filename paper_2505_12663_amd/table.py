@@ -60,12 +60,10 @@ class EmbeddingTable:
     def add_chunk(self) -> None:
         n = 1 << self.chunk_rows_log2
         values = torch.empty((n, self.dim), dtype=self.torch_dtype, device=self.device)
-        acc = torch.empty(n, dtype=torch.float32, device=self.device)
-        last_seen = torch.empty(n, dtype=torch.int32, device=self.device)
-        freq = torch.empty(n, dtype=torch.int32, device=self.device)
+        meta = torch.empty((n, 4), dtype=torch.int32, device=self.device)        # 16 bytes per row
         free_list = torch.empty(n, dtype=torch.int32, device=self.device)
-        B.ht_add_chunk(self.h, values, acc, last_seen, freq, free_list)
-        self.chunks.append((values, acc, last_seen, freq, free_list))
+        B.ht_add_chunk(self.h, values, meta, free_list)
+        self.chunks.append((values, meta, free_list))
 
     def rehash(self, new_capacity_log2: int) -> None:
         new_keys = torch.empty(1 << new_capacity_log2, dtype=torch.int64, device=self.device)
