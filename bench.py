@@ -54,6 +54,9 @@ def main() -> int:
     ap.add_argument("--batches", type=int, default=4, help="distinct pre-generated batches cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--count-probes", action="store_true", help="maintain probe/CAS counters (small overhead)")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also run plain device-to-device copies of this many MiB (reference kernel of known "
+                         "size for scaling hardware counters; reports the copy rate)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU's share of the embedding path; run it with --gpus 1 "
@@ -130,7 +133,7 @@ def main() -> int:
         rec(0)
         B.emb_tag_keys(dx, doff, dtag, tag_bits, buf.key, buf.err_count)
         rec(1)
-        B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, None, buf.perm, None, buf.n_unique, buf.dedup_ws)
+        B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, None, buf.perm, None, buf.seg_of, buf.n_unique, buf.dedup_ws)
         rec(2)
         table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted)
         rec(3)
@@ -138,7 +141,7 @@ def main() -> int:
         rec(4)
         B.emb_expand(buf.uniq_rows, buf.inverse, n, dim, dtype, buf.out)
         rec(5)
-        B.grad_segment_reduce(grad, dtype, buf.inverse, buf.perm, n, dim, buf.reduced, buf.reduce_ws)
+        B.grad_segment_reduce(grad, dtype, buf.seg_of, buf.perm, n, dim, buf.reduced, buf.reduce_ws)
         rec(6)
         table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps)
         rec(7)
@@ -209,6 +212,20 @@ def main() -> int:
         st = table.stats()
         result["probe_counters"] = {k: st[k] for k in ("lookups", "probes", "cas_attempts", "cas_failures", "alloc_atomics")}
 
+    if args.copy_probe_mib > 0:
+        nbytes = args.copy_probe_mib << 20
+        src = torch.empty(nbytes, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        dst.copy_(src)
+        e0.record()
+        for _ in range(10):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 10
+        result["copy_probe"] = {"bytes_read": nbytes, "bytes_written": nbytes, "avg_ms": round(ms, 4),
+                                "gbps_read_plus_write": round(2 * nbytes / (ms * 1e-3) / 1e9, 1)}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, batches[0][4], tag_bits, dim, dtype, n_keys)
     print(json.dumps(result), flush=True)

@@ -80,7 +80,7 @@ typedef struct {
     uint64_t status;        /* EMB_DEV_* bits */
     /* counters, only maintained when count_probes != 0 */
     uint64_t lookups;       /* keys probed by find / find-or-insert */
-    uint64_t probes;        /* 64-byte slot lines inspected for them */
+    uint64_t probes;        /* 128-byte slot lines inspected for them */
     uint64_t cas_attempts;
     uint64_t cas_failures;
     uint64_t alloc_atomics; /* atomics issued by the wave-aggregated row allocator */
@@ -114,9 +114,10 @@ int emb_table_create(emb_table_t** out, const emb_table_desc_t* desc, void* stat
                      void* stream);
 int emb_table_destroy(emb_table_t* t);
 
-/* Give an EMPTY table its key structure: keys [dev, 2^capacity_log2 x u64] and rows
- * [dev, 2^capacity_log2 x u32], 6 <= capacity_log2 <= 30.  Both are filled with the empty marker. */
-int ht_set_key_storage(emb_table_t* t, uint64_t* keys, uint32_t* rows, int capacity_log2, void* stream);
+/* Give an EMPTY table its key structure: slots [dev, 128-byte aligned, 2^capacity_log2 x 16 bytes],
+ * 6 <= capacity_log2 <= 30.  A slot holds the 64-bit key and the 32-bit index of its embedding
+ * row (plus 4 unused bytes).  All slots are marked empty here. */
+int ht_set_key_storage(emb_table_t* t, void* slots, int capacity_log2, void* stream);
 
 /* Register one more value chunk of 2^chunk_rows_log2 rows (Sec. 3.1: chunked embedding
  * structure; keep a spare chunk registered so inserts never wait for an allocation).
@@ -136,9 +137,11 @@ int ht_add_chunk(emb_table_t* t, void* values, void* meta, uint32_t* free_list, 
 int ht_plan(emb_table_t* t, int64_t n_incoming, int* new_capacity_log2, int* chunks_needed);
 
 /* Capacity expansion (Sec. 3.1): move every live (key,row) pair into new key storage of
- * 2^new_capacity_log2 slots, dropping deleted slots.  Embedding rows do not move.  The old
- * arrays are no longer referenced once this call's work on `stream` has finished. */
-int ht_rehash(emb_table_t* t, uint64_t* new_keys, uint32_t* new_rows, int new_capacity_log2, void* stream);
+ * 2^new_capacity_log2 slots (same layout and alignment as above), dropping deleted slots.
+ * Embedding rows do not move.  The old array is no longer referenced once this call's work on
+ * `stream` has finished.  Fails with EMB_ERR_INVALID_ARG if the live keys would exceed the
+ * load-factor limit of the new structure. */
+int ht_rehash(emb_table_t* t, void* new_slots, int new_capacity_log2, void* stream);
 
 /* Copy the counters to *out [host].  Synchronises `stream`. */
 int ht_stats(emb_table_t* t, ht_stats_t* out, void* stream);
@@ -160,12 +163,14 @@ int emb_tag_keys(const uint64_t* x, const int64_t* field_off, const uint8_t* fie
  *   perm [dev, n, int32, optional]: positions ordered by (key, position); the positions of
  *     uniq[u] are perm[seg_off[u] .. seg_off[u+1]);
  *   seg_off [dev, n+1, int32, optional];
+ *   seg_of [dev, n, int32, optional]: seg_of[j] = inverse[perm[j]], the distinct-key index of the
+ *     j-th position in sorted order (non-decreasing);
  *   n_unique [dev, int64].
  * workspace [dev, 256-byte aligned] of at least emb_dedup_workspace_bytes(n).  n < 2^31. */
 size_t emb_dedup_workspace_bytes(int64_t n);
 int emb_dedup(const uint64_t* key, int64_t n, uint64_t* uniq, int32_t* inverse, int32_t* counts,
-              int32_t* perm, int32_t* seg_off, int64_t* n_unique, void* workspace, size_t workspace_bytes,
-              void* stream);
+              int32_t* perm, int32_t* seg_off, int32_t* seg_of, int64_t* n_unique, void* workspace,
+              size_t workspace_bytes, void* stream);
 
 /* Find each key; insert the absent ones (claim a slot, allocate a row, initialise the row from
  * the key, acc = 0).  Every element counts one touch: freq += 1, last_seen = step.
@@ -191,10 +196,11 @@ int emb_expand(const void* uniq_rows, const int32_t* inverse, int64_t n, int dim
 /* ------------------------------------------------------------------ backward */
 
 /* reduced[u,:] = sum over positions i with inverse[i] == u of grad[i,:], fp32 accumulation,
- * fp32 output [*n_unique, dim].  grad [dev, n x dim] of grad_dtype.  perm and inverse as written
- * by emb_dedup for the same keys.  The order of additions is fixed (deterministic). */
+ * fp32 output [*n_unique, dim].  grad [dev, n x dim] of grad_dtype, dim <= 256.  perm and seg_of as
+ * written by emb_dedup for the same keys (the sum for u runs over grad[perm[j]] for the j with
+ * seg_of[j] == u).  The order of additions is fixed, so results are reproducible run to run. */
 size_t grad_segment_reduce_workspace_bytes(int64_t n, int dim);
-int grad_segment_reduce(const void* grad, int grad_dtype, const int32_t* inverse, const int32_t* perm, int64_t n,
+int grad_segment_reduce(const void* grad, int grad_dtype, const int32_t* seg_of, const int32_t* perm, int64_t n,
                         int dim, float* reduced, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Row-wise Adagrad on the listed rows only:

@@ -69,14 +69,14 @@ def load():
         "emb_table_state_bytes": (C.c_size_t, []),
         "emb_table_create": (C.c_int, [C.POINTER(vp), C.POINTER(TableDesc), vp, C.c_size_t, vp]),
         "emb_table_destroy": (C.c_int, [vp]),
-        "ht_set_key_storage": (C.c_int, [vp, vp, vp, i32, vp]),
+        "ht_set_key_storage": (C.c_int, [vp, vp, i32, vp]),
         "ht_add_chunk": (C.c_int, [vp, vp, vp, vp, vp]),
         "ht_plan": (C.c_int, [vp, i64, C.POINTER(C.c_int), C.POINTER(C.c_int)]),
-        "ht_rehash": (C.c_int, [vp, vp, vp, i32, vp]),
+        "ht_rehash": (C.c_int, [vp, vp, i32, vp]),
         "ht_stats": (C.c_int, [vp, C.POINTER(HtStats), vp]),
         "emb_tag_keys": (C.c_int, [vp, vp, vp, i32, i64, i32, vp, vp, vp]),
         "emb_dedup_workspace_bytes": (C.c_size_t, [i64]),
-        "emb_dedup": (C.c_int, [vp, i64, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]),
+        "emb_dedup": (C.c_int, [vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]),
         "ht_find_or_insert": (C.c_int, [vp, vp, vp, i64, u32, vp, vp, vp]),
         "ht_find": (C.c_int, [vp, vp, vp, i64, vp, vp]),
         "ht_gather": (C.c_int, [vp, vp, vp, i64, vp, vp]),
@@ -154,9 +154,9 @@ def emb_table_destroy(h) -> None:
     _check(load().emb_table_destroy(h), "emb_table_destroy")
 
 
-def ht_set_key_storage(h, keys, rows, capacity_log2: int, stream=None) -> None:
-    assert keys.numel() == 1 << capacity_log2 and rows.numel() == 1 << capacity_log2
-    _check(load().ht_set_key_storage(h, _ptr(keys), _ptr(rows), capacity_log2, _stream(stream)), "ht_set_key_storage")
+def ht_set_key_storage(h, slots, capacity_log2: int, stream=None) -> None:
+    assert slots.numel() * slots.element_size() == 16 << capacity_log2
+    _check(load().ht_set_key_storage(h, _ptr(slots), capacity_log2, _stream(stream)), "ht_set_key_storage")
 
 
 def ht_add_chunk(h, values, meta, free_list, stream=None) -> None:
@@ -169,9 +169,9 @@ def ht_plan(h, n_incoming: int):
     return cap.value, chunks.value
 
 
-def ht_rehash(h, new_keys, new_rows, new_capacity_log2: int, stream=None) -> None:
-    assert new_keys.numel() == 1 << new_capacity_log2 and new_rows.numel() == 1 << new_capacity_log2
-    _check(load().ht_rehash(h, _ptr(new_keys), _ptr(new_rows), new_capacity_log2, _stream(stream)), "ht_rehash")
+def ht_rehash(h, new_slots, new_capacity_log2: int, stream=None) -> None:
+    assert new_slots.numel() * new_slots.element_size() == 16 << new_capacity_log2
+    _check(load().ht_rehash(h, _ptr(new_slots), new_capacity_log2, _stream(stream)), "ht_rehash")
 
 
 def ht_stats(h, stream=None) -> dict:
@@ -189,9 +189,9 @@ def emb_dedup_workspace_bytes(n: int) -> int:
     return int(load().emb_dedup_workspace_bytes(n))
 
 
-def emb_dedup(key, n: int, uniq, inverse, counts, perm, seg_off, n_unique, workspace, stream=None) -> None:
+def emb_dedup(key, n: int, uniq, inverse, counts, perm, seg_off, seg_of, n_unique, workspace, stream=None) -> None:
     _check(load().emb_dedup(_ptr(key), n, _ptr(uniq), _ptr(inverse), _ptr(counts), _ptr(perm), _ptr(seg_off),
-                            _ptr(n_unique), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                            _ptr(seg_of), _ptr(n_unique), _ptr(workspace), workspace.numel() * workspace.element_size(),
                             _stream(stream)), "emb_dedup")
 
 
@@ -220,8 +220,8 @@ def grad_segment_reduce_workspace_bytes(n: int, dim: int) -> int:
     return int(load().grad_segment_reduce_workspace_bytes(n, dim))
 
 
-def grad_segment_reduce(grad, grad_dtype: int, inverse, perm, n: int, dim: int, reduced, workspace, stream=None) -> None:
-    _check(load().grad_segment_reduce(_ptr(grad), grad_dtype, _ptr(inverse), _ptr(perm), n, dim, _ptr(reduced),
+def grad_segment_reduce(grad, grad_dtype: int, seg_of, perm, n: int, dim: int, reduced, workspace, stream=None) -> None:
+    _check(load().grad_segment_reduce(_ptr(grad), grad_dtype, _ptr(seg_of), _ptr(perm), n, dim, _ptr(reduced),
                                       _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
            "grad_segment_reduce")
 

@@ -11,8 +11,16 @@ constexpr int kWave = 64;
 constexpr uint64_t kEmptyKey = 0xFFFFFFFFFFFFFFFFull; // never-used slot
 constexpr uint64_t kTombKey = 0xFFFFFFFFFFFFFFFEull;  // deleted slot, reclaimed by rehash only
 constexpr uint32_t kRowInvalid = 0xFFFFFFFFu;
-constexpr int kLineSlots = 8;                         // one probe = one aligned 64-byte line of keys
+constexpr int kLineSlots = 8;                         // one probe = one aligned 128-byte line of 8 slots
 constexpr int kMaxChunks = 256;
+
+// One slot of the key structure: the key and the index of its embedding row (Sec. 3.1: the key
+// structure maps keys to pointers into the embedding structure).
+struct __attribute__((aligned(16))) Slot {
+    unsigned long long key;
+    uint32_t row;
+    uint32_t pad;
+};
 
 // Per-row auxiliary data of the embedding structure, one 16-byte record per row so that the
 // touch of find-or-insert and the accumulator update of the optimizer hit the same line.
@@ -50,8 +58,7 @@ struct HtCounts {
 
 // What a table kernel needs, passed by value.
 struct HtView {
-    uint64_t* keys;
-    uint32_t* rows;
+    Slot* slots;
     HtState* st;
     uint64_t line_mask;      // (capacity / kLineSlots) - 1
     uint32_t rows_capacity;  // rows in registered chunks
@@ -114,6 +121,9 @@ __device__ inline uint64_t shfl64(uint64_t v, int src) {
 __device__ inline uint64_t load_fresh(const uint64_t* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ inline unsigned long long load_fresh(const unsigned long long* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ inline uint32_t load_fresh(const uint32_t* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -148,8 +158,7 @@ struct emb_table {
     static constexpr int kSnaps = 4;
     emb_table_desc_t desc;
     mtgr::HtState* st;          // device
-    uint64_t* keys;             // device
-    uint32_t* rows;             // device
+    mtgr::Slot* slots;          // device
     int cap_log2;
     int n_chunks;
     int row_bytes;
@@ -205,10 +214,9 @@ struct emb_table {
 
     mtgr::HtView view() const {
         mtgr::HtView v;
-        v.keys = keys;
-        v.rows = rows;
+        v.slots = slots;
         v.st = st;
-        v.line_mask = keys ? ((1ull << cap_log2) / mtgr::kLineSlots - 1ull) : 0ull;
+        v.line_mask = slots ? ((1ull << cap_log2) / mtgr::kLineSlots - 1ull) : 0ull;
         v.rows_capacity = (uint32_t)((uint64_t)n_chunks << desc.chunk_rows_log2);
         v.chunk_log2 = desc.chunk_rows_log2;
         v.dim = desc.dim;

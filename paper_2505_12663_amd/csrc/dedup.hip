@@ -357,7 +357,7 @@ __global__ __launch_bounds__(1024) void k_heads_scan(unsigned* __restrict__ tile
 __global__ __launch_bounds__(kThreads) void k_emit(DdBuffers b, const DdHeader* __restrict__ h, int64_t n,
                                                   const unsigned* __restrict__ tile_heads, uint64_t* __restrict__ uniq,
                                                   int32_t* __restrict__ inverse, int32_t* __restrict__ perm,
-                                                  int32_t* __restrict__ seg_off) {
+                                                  int32_t* __restrict__ seg_off, int32_t* __restrict__ seg_of) {
     const int sel = h->final_sel;
     const uint64_t* keys = sel_keys(b, sel);
     const uint32_t* idxs = sel_idx(b, sel);
@@ -394,6 +394,7 @@ __global__ __launch_bounds__(kThreads) void k_emit(DdBuffers b, const DdHeader* 
             const uint32_t p = idxs ? idxs[j] : (uint32_t)j;
             inverse[p] = (int32_t)seg;
             if (perm) perm[j] = (int32_t)p;
+            if (seg_of) seg_of[j] = (int32_t)seg;
             if (head) {
                 uniq[seg] = key[it];
                 if (seg_off) seg_off[seg] = (int32_t)j;
@@ -466,8 +467,8 @@ size_t emb_dedup_workspace_bytes(int64_t n) {
 }
 
 int emb_dedup(const uint64_t* key, int64_t n, uint64_t* uniq, int32_t* inverse, int32_t* counts,
-              int32_t* perm, int32_t* seg_off, int64_t* n_unique, void* workspace, size_t workspace_bytes,
-              void* stream) {
+              int32_t* perm, int32_t* seg_off, int32_t* seg_of, int64_t* n_unique, void* workspace,
+              size_t workspace_bytes, void* stream) {
     if (n < 0 || n > 0x7FFFFFFFll || !n_unique) return EMB_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (n == 0) {
@@ -505,7 +506,7 @@ int emb_dedup(const uint64_t* key, int64_t n, uint64_t* uniq, int32_t* inverse, 
     }
     hipLaunchKernelGGL(k_heads_count, dim3(n_tiles), dim3(kThreads), 0, s, b, hdr, n, tile_heads);
     hipLaunchKernelGGL(k_heads_scan, dim3(1), dim3(1024), 0, s, tile_heads, n_tiles, hdr, n_unique);
-    hipLaunchKernelGGL(k_emit, dim3(n_tiles), dim3(kThreads), 0, s, b, hdr, n, tile_heads, uniq, inverse, perm, seg);
+    hipLaunchKernelGGL(k_emit, dim3(n_tiles), dim3(kThreads), 0, s, b, hdr, n, tile_heads, uniq, inverse, perm, seg, seg_of);
     MTGR_LAUNCH_CHECK();
     if (counts) {
         hipLaunchKernelGGL(k_counts, dim3((unsigned)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, seg, hdr, counts);

@@ -84,7 +84,7 @@ int launch_copy_rows(const HtView& v, const char* src, const int32_t* index, con
 
 // ---------------------------------------------------------------------------- segment reduce
 // Items are reduced in a fixed order, level by level.  Level 1 items are the positions in sorted
-// order (row = grad[perm[j]], segment = inverse[perm[j]]); a group of LPR lanes folds kSpan
+// order (row = grad[perm[j]], segment = seg_of[j]); a group of LPR lanes folds kSpan
 // consecutive items.  Runs of one segment that lie strictly inside the span are complete and
 // stored to reduced[]; the first and the last run of the span may continue in a neighbour span,
 // so they are handed to the next level as two fp32 partial rows (segment -1 = no item).  The next
@@ -127,7 +127,7 @@ __device__ inline void acc_store(float* row, int sub, const Acc<FPL>& a) {
 struct LevelIn {
     const char* rows;        // level 1: grad matrix; level >= 2: fp32 partial rows
     const int32_t* perm;     // level 1 only
-    const int32_t* seg;      // level 1: inverse[]; level >= 2: segment of each item (-1 = none)
+    const int32_t* seg;      // segment of each item in order (-1 = no item)
     int64_t n_items;
     int in_row_bytes;
 };
@@ -179,14 +179,8 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
             my_seg[u] = -1;
             if (group_on && it < items) {
                 const int64_t j = first + it;
-                if (LEVEL1) {
-                    const int32_t p = in.perm[j];
-                    my_src[u] = p;
-                    my_seg[u] = in.seg[p];
-                } else {
-                    my_src[u] = j;
-                    my_seg[u] = in.seg[j];
-                }
+                my_src[u] = LEVEL1 ? (int64_t)in.perm[j] : j;
+                my_seg[u] = in.seg[j];
             }
         }
 #pragma unroll
@@ -260,7 +254,7 @@ ReduceLayout reduce_layout(int64_t n, int dim) {
 }
 
 template <int LPR, int FPL>
-int launch_reduce(const char* grad, int in_row_bytes, const int32_t* inverse, const int32_t* perm, int64_t n, int dim,
+int launch_reduce(const char* grad, int in_row_bytes, const int32_t* seg_of, const int32_t* perm, int64_t n, int dim,
                   float* reduced, char* ws, const ReduceLayout& L, hipStream_t s) {
     constexpr int kGroups = kWave / LPR;
     constexpr int kSpansPerBlock = (kBlock / kWave) * kGroups;
@@ -270,7 +264,7 @@ int launch_reduce(const char* grad, int in_row_bytes, const int32_t* inverse, co
         float* prow = reinterpret_cast<float*>(ws + L.rows_off[l]);
         int32_t* pseg = reinterpret_cast<int32_t*>(ws + L.seg_off[l]);
         if (l == 0) {
-            LevelIn in{grad, perm, inverse, n, in_row_bytes};
+            LevelIn in{grad, perm, seg_of, n, in_row_bytes};
             hipLaunchKernelGGL((k_seg_reduce<LPR, FPL, true>), dim3(grid), dim3(kBlock), 0, s, in, dim, reduced, prow, pseg, last);
         } else {
             LevelIn in{ws + L.rows_off[l - 1], nullptr, reinterpret_cast<const int32_t*>(ws + L.seg_off[l - 1]), L.items[l],
@@ -396,13 +390,13 @@ size_t grad_segment_reduce_workspace_bytes(int64_t n, int dim) {
     return reduce_layout(n, dim).total;
 }
 
-int grad_segment_reduce(const void* grad, int grad_dtype, const int32_t* inverse, const int32_t* perm, int64_t n,
+int grad_segment_reduce(const void* grad, int grad_dtype, const int32_t* seg_of, const int32_t* perm, int64_t n,
                         int dim, float* reduced, void* workspace, size_t workspace_bytes, void* stream) {
     if (n < 0 || n > 0x7FFFFFFFll || dim <= 0 || (grad_dtype != EMB_F32 && grad_dtype != EMB_BF16)) return EMB_ERR_INVALID_ARG;
     if (n == 0) return EMB_OK;
     const int in_row_bytes = dim * (grad_dtype == EMB_F32 ? 4 : 2);
-    if (in_row_bytes % 16 != 0 || in_row_bytes > 1024) return EMB_ERR_INVALID_ARG;
-    if (!grad || !inverse || !perm || !reduced) return EMB_ERR_INVALID_ARG;
+    if (in_row_bytes % 16 != 0 || dim > 256) return EMB_ERR_INVALID_ARG;
+    if (!grad || !seg_of || !perm || !reduced) return EMB_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(grad) & 15) || (reinterpret_cast<uintptr_t>(reduced) & 15)) return EMB_ERR_INVALID_ARG;
     const ReduceLayout L = reduce_layout(n, dim);
     if (!workspace || workspace_bytes < L.total || (reinterpret_cast<uintptr_t>(workspace) & 255)) return EMB_ERR_WORKSPACE;
@@ -411,8 +405,8 @@ int grad_segment_reduce(const void* grad, int grad_dtype, const int32_t* inverse
     char* ws = static_cast<char*>(workspace);
     const int vecs = in_row_bytes / 16;
 #define MTGR_RED(L_)                                                                                          \
-    (grad_dtype == EMB_F32 ? launch_reduce<L_, 4>(g, in_row_bytes, inverse, perm, n, dim, reduced, ws, L, s) \
-                           : launch_reduce<L_, 8>(g, in_row_bytes, inverse, perm, n, dim, reduced, ws, L, s))
+    (grad_dtype == EMB_F32 ? launch_reduce<L_, 4>(g, in_row_bytes, seg_of, perm, n, dim, reduced, ws, L, s) \
+                           : launch_reduce<L_, 8>(g, in_row_bytes, seg_of, perm, n, dim, reduced, ws, L, s))
     if (vecs <= 1) return MTGR_RED(1);
     if (vecs <= 2) return MTGR_RED(2);
     if (vecs <= 4) return MTGR_RED(4);

@@ -1,9 +1,9 @@
-// Dynamic embedding hash table for gfx950 (Sec. 3.1): decoupled key structure
-// (keys[M] u64 + rows[M] u32) and chunked embedding structure, open addressing over
-// 64-byte lines of 8 slots with a key-dependent odd line stride (Theorem 1 gives full
+// Dynamic embedding hash table for gfx950 (Sec. 3.1): key structure of 16-byte slots
+// (key, row index) decoupled from the chunked embedding structure, open addressing over
+// 128-byte lines of 8 slots with a key-dependent odd line stride (Theorem 1 gives full
 // coverage), sub-wave cooperative probing (8 lanes inspect one line with one coalesced
-// load), CAS insertion into never-used slots only, deleted markers, wave-aggregated
-// row allocation, key-only rehash.
+// 128-byte load), CAS insertion into never-used slots only, deleted markers,
+// wave-aggregated row allocation, key-only rehash.
 #include <cstddef>
 
 #include "common.hpp"
@@ -22,13 +22,11 @@ __device__ inline void* chunk_row_ptr(const HtView& v, uint32_t row) {
 #define CHUNK_FREE(v, pos) ((v).st->free_list[(pos) >> (v).chunk_log2][(pos) & ((1u << (v).chunk_log2) - 1u)])
 
 // --------------------------------------------------------------------------------------------
-__global__ void k_fill_keys(uint64_t* keys, uint32_t* rows, uint64_t n) {
+__global__ void k_fill_slots(Slot* slots, uint64_t n) {
     uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-    for (; i < n; i += stride) {
-        keys[i] = kEmptyKey;
-        rows[i] = kRowInvalid;
-    }
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    const V16 e{0xFFFFFFFFu, 0xFFFFFFFFu, kRowInvalid, 0u};
+    for (; i < n; i += stride) st16(slots + i, e);
 }
 
 __global__ void k_zero_bytes(uint32_t* p, size_t n_words) {
@@ -44,17 +42,25 @@ __global__ void k_set_chunk(HtState* st, int c, void* values, RowMeta* meta, uin
     }
 }
 
+struct ProbeCounters {
+    unsigned probes, cas, cas_fail;
+};
+
 // --------------------------------------------------------------------------------------------
-// Probe for `key` with the 8 lanes of a group.  All 64 lanes of the wave call this together;
-// `active` says whether this lane's group has work.  Returns (group-uniform) the slot of the key,
-// or -1 when absent.  With INSERT, an absent key is claimed in the first never-used slot of the
-// first line on its probe sequence that has one; *created tells whether this call claimed it.
-// Correctness of concurrent inserts: a key is only ever stored by a successful CAS on an EMPTY
-// slot, EMPTY slots of a line are claimed in ascending order, and a line is re-read (bypassing the
-// vector L1) after every failed CAS, so two groups inserting the same key meet in the same slot.
+// Probe for `key` with the 8 lanes of a group, line after line.  All 64 lanes of the wave call
+// this together; `active` says whether this lane's group has work.  Returns (group-uniform) the
+// slot of the key, -1 when absent, -2 when every line was visited without room.  With INSERT, an
+// absent key is claimed in the first never-used slot of the first line on its probe sequence that
+// has one; *created tells whether this call claimed it.
+// Concurrent inserts: a key is only ever stored by a successful CAS on an EMPTY slot, EMPTY slots
+// of a line are claimed in ascending order, and a line is re-read with loads that bypass the
+// non-coherent caches after every failed CAS, so two groups inserting the same key meet in the
+// same slot.  The loop ends: a retry only follows a CAS that lost to a different key, which takes
+// one of the line's at most 8 EMPTY slots away for good; every other iteration finishes the
+// group or moves on to one of the finitely many unvisited lines.
 template <bool INSERT>
 __device__ inline long long probe_group(const HtView& v, uint64_t key, bool active, int lane, bool* created,
-                                        unsigned* n_probes, unsigned* n_cas, unsigned* n_cas_fail) {
+                                        ProbeCounters* pc) {
     const int sub = lane & (kLineSlots - 1);
     const int gbase = lane & ~(kLineSlots - 1);
     const uint64_t h = slot_hash(key);
@@ -65,35 +71,32 @@ __device__ inline long long probe_group(const HtView& v, uint64_t key, bool acti
     bool done = !active;
     *created = false;
     while (__any(!done)) {
-        uint64_t slot = line * kLineSlots + sub;
+        Slot* sp = v.slots + line * kLineSlots + sub;
         uint64_t k = kEmptyKey;
-        if (!done) k = INSERT ? load_fresh(v.keys + slot) : v.keys[slot];
-        uint64_t m_hit = __ballot(!done && k == key);
-        uint64_t m_empty = __ballot(!done && k == kEmptyKey);
-        unsigned hit8 = (unsigned)(m_hit >> gbase) & 0xFFu;
-        unsigned empty8 = (unsigned)(m_empty >> gbase) & 0xFFu;
+        if (!done) k = INSERT ? load_fresh(&sp->key) : sp->key;
+        const uint64_t m_hit = __ballot(!done && k == key);
+        const uint64_t m_empty = __ballot(!done && k == kEmptyKey);
+        const unsigned hit8 = (unsigned)(m_hit >> gbase) & 0xFFu;
+        const unsigned empty8 = (unsigned)(m_empty >> gbase) & 0xFFu;
         bool retry_line = false;
         if (!done) {
-            *n_probes += (sub == 0);
+            pc->probes += (sub == 0);
             if (hit8) {
                 result = (long long)(line * kLineSlots + (__ffs(hit8) - 1));
                 done = true;
-            } else if (empty8) {
-                if (!INSERT) {
-                    done = true; // absent
-                }
+            } else if (empty8 && !INSERT) {
+                done = true; // absent
             }
         }
         if (INSERT) {
             // groups that saw no hit but an EMPTY slot try to claim the first one
-            bool want = !done && !hit8 && empty8;
-            int e = want ? (__ffs(empty8) - 1) : 0;
+            const bool want = !done && !hit8 && empty8;
+            const int e = want ? (__ffs(empty8) - 1) : 0;
             uint64_t old = 0;
             if (want && sub == e) {
-                old = atomicCAS(reinterpret_cast<unsigned long long*>(v.keys + line * kLineSlots + e),
-                                (unsigned long long)kEmptyKey, (unsigned long long)key);
-                *n_cas += 1;
-                if (old != kEmptyKey) *n_cas_fail += 1;
+                old = atomicCAS(&sp->key, (unsigned long long)kEmptyKey, (unsigned long long)key);
+                pc->cas += 1;
+                if (old != kEmptyKey) pc->cas_fail += 1;
             }
             old = shfl64(old, gbase + e);
             if (want) {
@@ -113,15 +116,71 @@ __device__ inline long long probe_group(const HtView& v, uint64_t key, bool acti
             line = (line + stride) & v.line_mask;
             if (--remaining == 0) {
                 done = true;
-                result = -2; // every line visited: table full
+                result = -2;
             }
         }
     }
     return result;
 }
 
-// One wave handles 64 keys: each lane owns one key; the 8 groups of 8 lanes work through the keys
-// of their own lanes one after the other.
+// First lines of the 8 keys of every group, all loads in flight at once: a key found there is
+// settled without entering the line-by-line loop (at the load factors in use that is nearly all
+// present keys).  found_slot stays -1 for the others.
+__device__ inline void first_line_pass(const HtView& v, uint64_t my_key, bool my_ok, int lane, long long* found_slot,
+                                       uint32_t* found_row, ProbeCounters* pc) {
+    const int sub = lane & (kLineSlots - 1);
+    const int gbase = lane & ~(kLineSlots - 1);
+    uint64_t kr[kLineSlots];
+    uint64_t line[kLineSlots];
+    V16 ent[kLineSlots];
+#pragma unroll
+    for (int r = 0; r < kLineSlots; ++r) {
+        kr[r] = shfl64(my_key, gbase + r);
+        line[r] = probe_start(slot_hash(kr[r]), v.line_mask);
+        ent[r] = ld16(v.slots + line[r] * kLineSlots + sub);
+    }
+    *found_slot = -1;
+    *found_row = kRowInvalid;
+#pragma unroll
+    for (int r = 0; r < kLineSlots; ++r) {
+        const bool ok = __shfl((int)my_ok, gbase + r, kWave) != 0;
+        const uint64_t k = ((uint64_t)ent[r].y << 32) | ent[r].x;
+        const uint64_t m = __ballot(ok && k == kr[r]);
+        const unsigned hit8 = (unsigned)(m >> gbase) & 0xFFu;
+        const int hl = hit8 ? (__ffs(hit8) - 1) : 0;
+        const uint32_t row = __shfl(ent[r].z, gbase + hl, kWave);
+        if (sub == r && hit8) {
+            *found_slot = (long long)(line[r] * kLineSlots + hl);
+            *found_row = row;
+        }
+        pc->probes += (sub == r && ok) ? 1u : 0u;
+    }
+}
+
+__device__ inline void flush_counters(const HtView& v, int lane, int64_t cnt, ProbeCounters pc, unsigned alloc_atomics) {
+    unsigned tot_p = pc.probes, tot_c = pc.cas, tot_f = pc.cas_fail;
+    for (int o = 32; o > 0; o >>= 1) {
+        tot_p += __shfl_xor(tot_p, o, kWave);
+        tot_c += __shfl_xor(tot_c, o, kWave);
+        tot_f += __shfl_xor(tot_f, o, kWave);
+    }
+    if (lane == 0) { // one atomic per counter per wave
+        atomicAdd(&v.st->lookups, (unsigned long long)cnt);
+        atomicAdd(&v.st->probes, (unsigned long long)tot_p);
+        if (tot_c) atomicAdd(&v.st->cas_attempts, (unsigned long long)tot_c);
+        if (tot_f) atomicAdd(&v.st->cas_failures, (unsigned long long)tot_f);
+        if (alloc_atomics) atomicAdd(&v.st->alloc_atomics, (unsigned long long)alloc_atomics);
+    }
+}
+
+__device__ inline void touch_row(const HtView& v, uint32_t row, uint32_t step) {
+    RowMeta* m = &CHUNK_META(v, row);
+    atomicAdd(&m->freq, 1u);
+    m->last_seen = step;
+}
+
+// One wave handles 64 keys: each lane owns one key; the 8 groups of 8 lanes first look at the first
+// line of each of their 8 keys, then work through the unsettled keys one after the other.
 template <bool COUNT>
 __global__ __launch_bounds__(kBlock) void k_find_or_insert(HtView v, const uint64_t* __restrict__ key,
                                                            const int64_t* n_dev, int64_t n_max, uint32_t step,
@@ -133,28 +192,36 @@ __global__ __launch_bounds__(kBlock) void k_find_or_insert(HtView v, const uint6
     if (wave_base >= n) return;
     const int64_t i = wave_base + lane;
     const bool valid = i < n;
-    uint64_t my_key = valid ? key[i] : 0ull;
+    const uint64_t my_key = valid ? key[i] : 0ull;
     const bool bad = valid && (my_key >> 63);
+    const bool my_ok = valid && !bad;
     const int sub = lane & (kLineSlots - 1);
     const int gbase = lane & ~(kLineSlots - 1);
 
-    long long my_slot = -1;
+    ProbeCounters pc{0u, 0u, 0u};
+    long long my_slot;
+    uint32_t my_row;
+    first_line_pass(v, my_key, my_ok, lane, &my_slot, &my_row, &pc);
     bool my_created = false;
-    unsigned n_probes = 0, n_cas = 0, n_cas_fail = 0;
-    for (int r = 0; r < kLineSlots; ++r) {
-        uint64_t k = shfl64(my_key, gbase + r);
-        bool act = (__shfl((int)(valid && !bad), gbase + r, kWave) != 0);
-        bool created;
-        long long s = probe_group<true>(v, k, act, lane, &created, &n_probes, &n_cas, &n_cas_fail);
-        if (sub == r) {
-            my_slot = s;
-            my_created = created;
+    // keys not settled by the first-line pass (absent, displaced, or in a line that changed)
+    const bool need_slow = my_ok && my_slot < 0;
+    if (__any(need_slow)) {
+        for (int r = 0; r < kLineSlots; ++r) {
+            const bool act = __shfl((int)need_slow, gbase + r, kWave) != 0;
+            if (!__any(act)) continue;
+            const uint64_t k = shfl64(my_key, gbase + r);
+            bool created;
+            const long long s = probe_group<true>(v, k, act, lane, &created, &pc);
+            if (sub == r && act) {
+                my_slot = s;
+                my_created = created;
+                my_row = kRowInvalid;
+            }
         }
     }
 
     // ---- wave-aggregated row allocation for the lanes that claimed a slot
     const uint64_t m_new = __ballot(my_created);
-    uint32_t my_row = kRowInvalid;
     unsigned n_alloc_atomics = 0;
     if (m_new) {
         const int n_new = __popcll(m_new);
@@ -162,12 +229,14 @@ __global__ __launch_bounds__(kBlock) void k_find_or_insert(HtView v, const uint6
         unsigned bump_base = 0;
         int take = 0;
         if (lane == 0) {
-            old_free = atomicSub(&v.st->free_count, n_new);
-            n_alloc_atomics = 1;
+            if (load_fresh(reinterpret_cast<const uint32_t*>(&v.st->free_count)) != 0u) {
+                old_free = atomicSub(&v.st->free_count, n_new);
+                n_alloc_atomics += 1;
+            }
             take = old_free < 0 ? 0 : (old_free > n_new ? n_new : old_free);
             if (n_new - take > 0) {
                 bump_base = atomicAdd(&v.st->bump, (unsigned)(n_new - take));
-                n_alloc_atomics = 2;
+                n_alloc_atomics += 1;
             }
             atomicAdd(&v.st->live, (unsigned long long)n_new);
         }
@@ -175,17 +244,16 @@ __global__ __launch_bounds__(kBlock) void k_find_or_insert(HtView v, const uint6
         take = __shfl(take, 0, kWave);
         bump_base = __shfl(bump_base, 0, kWave);
         if (my_created) {
-            int r = rank_in(m_new, lane);
+            const int r = rank_in(m_new, lane);
             if (r < take) {
-                unsigned p = (unsigned)(old_free - 1 - r);
-                my_row = CHUNK_FREE(v, p);
+                my_row = CHUNK_FREE(v, (unsigned)(old_free - 1 - r));
             } else {
                 my_row = bump_base + (unsigned)(r - take);
             }
             if (my_row >= v.rows_capacity) {
                 // out of row storage: give the slot up again (as a deleted marker) and report
                 atomicOr(&v.st->status, EMB_DEV_OUT_OF_ROWS);
-                v.keys[my_slot] = kTombKey;
+                v.slots[my_slot].key = kTombKey;
                 atomicAdd(&v.st->tombstones, 1ull);
                 atomicAdd(&v.st->live, ~0ull); // -1
                 my_row = kRowInvalid;
@@ -210,11 +278,15 @@ __global__ __launch_bounds__(kBlock) void k_find_or_insert(HtView v, const uint6
         }
     }
     if (my_created) {
-        CHUNK_META(v, my_row) = RowMeta{0.0f, step, 0u, 0u};
-        v.rows[my_slot] = my_row;
+        // the creating element's own touch is part of the initial record; publish the row index
+        // only after the record is visible device-wide, so that a duplicate of the key that sees
+        // the row may count its touch at once
+        CHUNK_META(v, my_row) = RowMeta{0.0f, step, 1u, 0u};
+        __threadfence();
+        __hip_atomic_store(&v.slots[my_slot].row, my_row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    // ---- results.  A lane that found a key another group is still inserting sees no row yet:
-    // it records the slot (as -(slot+2)) and k_touch resolves it after this kernel.
+    // ---- results.  A lane that found a key whose creator has not published the row yet records
+    // the slot (as -(slot+2)); k_touch resolves it after this kernel.
     if (valid) {
         int32_t out;
         if (bad) {
@@ -228,48 +300,35 @@ __global__ __launch_bounds__(kBlock) void k_find_or_insert(HtView v, const uint6
         } else if (my_created) {
             out = (int32_t)my_row;
         } else {
-            uint32_t r = load_fresh(v.rows + my_slot);
-            out = (r == kRowInvalid) ? (int32_t)(-(my_slot + 2)) : (int32_t)r;
+            if (my_row == kRowInvalid) my_row = load_fresh(&v.slots[my_slot].row);
+            if (my_row == kRowInvalid) {
+                out = (int32_t)(-(my_slot + 2));
+            } else {
+                out = (int32_t)my_row;
+                touch_row(v, my_row, step);
+            }
         }
         row_idx[i] = out;
         if (inserted) inserted[i] = my_created ? 1 : 0;
     }
-    if (COUNT) {
-        // one atomic per counter per wave
-        unsigned tot_p = n_probes, tot_c = n_cas, tot_f = n_cas_fail;
-        for (int o = 32; o > 0; o >>= 1) {
-            tot_p += __shfl_xor(tot_p, o, kWave);
-            tot_c += __shfl_xor(tot_c, o, kWave);
-            tot_f += __shfl_xor(tot_f, o, kWave);
-        }
-        if (lane == 0) {
-            int64_t cnt = n - wave_base < kWave ? n - wave_base : kWave;
-            atomicAdd(&v.st->lookups, (unsigned long long)cnt);
-            atomicAdd(&v.st->probes, (unsigned long long)tot_p);
-            atomicAdd(&v.st->cas_attempts, (unsigned long long)tot_c);
-            atomicAdd(&v.st->cas_failures, (unsigned long long)tot_f);
-            atomicAdd(&v.st->alloc_atomics, (unsigned long long)n_alloc_atomics);
-        }
-    }
+    if (COUNT) flush_counters(v, lane, n - wave_base < kWave ? n - wave_base : kWave, pc, n_alloc_atomics);
 }
 
-// Second half of find-or-insert: resolve deferred rows, then count the touch of every element.
+// Second half of find-or-insert: resolve the deferred elements and count their touch.
 __global__ __launch_bounds__(kBlock) void k_touch(HtView v, const int64_t* n_dev, int64_t n_max, uint32_t step,
                                                   int32_t* __restrict__ row_idx) {
     const int64_t n = read_count(n_dev, n_max);
     const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i == 0 && v.st->free_count < 0) v.st->free_count = 0; // the free list ran dry during the insert
     if (i >= n) return;
-    int32_t r = row_idx[i];
-    if (r <= -2) {
-        uint32_t rr = v.rows[(uint64_t)(-(long long)r - 2)];
-        r = (rr == kRowInvalid) ? -1 : (int32_t)rr;
-        row_idx[i] = r;
-    }
-    if (r >= 0) {
-        RowMeta* m = &CHUNK_META(v, (uint32_t)r);
-        atomicAdd(&m->freq, 1u);
-        m->last_seen = step;
+    const int32_t r = row_idx[i];
+    if (r > -2) return;
+    const uint32_t rr = v.slots[(uint64_t)(-(long long)r - 2)].row;
+    if (rr == kRowInvalid) {
+        row_idx[i] = -1; // the creator ran out of rows
+    } else {
+        row_idx[i] = (int32_t)rr;
+        touch_row(v, rr, step);
     }
 }
 
@@ -282,36 +341,30 @@ __global__ __launch_bounds__(kBlock) void k_find(HtView v, const uint64_t* __res
     if (wave_base >= n) return;
     const int64_t i = wave_base + lane;
     const bool valid = i < n;
-    uint64_t my_key = valid ? key[i] : 0ull;
-    const bool ok = valid && !(my_key >> 63);
+    const uint64_t my_key = valid ? key[i] : 0ull;
+    const bool my_ok = valid && !(my_key >> 63);
     const int sub = lane & (kLineSlots - 1);
     const int gbase = lane & ~(kLineSlots - 1);
-    long long my_slot = -1;
-    unsigned n_probes = 0, d0 = 0, d1 = 0;
-    for (int r = 0; r < kLineSlots; ++r) {
-        uint64_t k = shfl64(my_key, gbase + r);
-        bool act = (__shfl((int)ok, gbase + r, kWave) != 0);
-        bool created;
-        long long s = probe_group<false>(v, k, act, lane, &created, &n_probes, &d0, &d1);
-        if (sub == r) my_slot = s;
-    }
-    if (valid) {
-        int32_t out = -1;
-        if (my_slot >= 0) {
-            uint32_t r = v.rows[my_slot];
-            out = (r == kRowInvalid) ? -1 : (int32_t)r;
-        }
-        row_idx[i] = out;
-    }
-    if (COUNT) {
-        unsigned tot_p = n_probes;
-        for (int o = 32; o > 0; o >>= 1) tot_p += __shfl_xor(tot_p, o, kWave);
-        if (lane == 0) {
-            int64_t cnt = n - wave_base < kWave ? n - wave_base : kWave;
-            atomicAdd(&v.st->lookups, (unsigned long long)cnt);
-            atomicAdd(&v.st->probes, (unsigned long long)tot_p);
+    ProbeCounters pc{0u, 0u, 0u};
+    long long my_slot;
+    uint32_t my_row;
+    first_line_pass(v, my_key, my_ok, lane, &my_slot, &my_row, &pc);
+    const bool need_slow = my_ok && my_slot < 0;
+    if (__any(need_slow)) {
+        for (int r = 0; r < kLineSlots; ++r) {
+            const bool act = __shfl((int)need_slow, gbase + r, kWave) != 0;
+            if (!__any(act)) continue;
+            const uint64_t k = shfl64(my_key, gbase + r);
+            bool created;
+            const long long s = probe_group<false>(v, k, act, lane, &created, &pc);
+            if (sub == r && act) {
+                my_slot = s;
+                my_row = s >= 0 ? v.slots[s].row : kRowInvalid;
+            }
         }
     }
+    if (valid) row_idx[i] = (my_slot >= 0 && my_row != kRowInvalid) ? (int32_t)my_row : -1;
+    if (COUNT) flush_counters(v, lane, n - wave_base < kWave ? n - wave_base : kWave, pc, 0u);
 }
 
 // --------------------------------------------------------------------------------------------
@@ -326,66 +379,60 @@ __global__ __launch_bounds__(kBlock) void k_evict(HtView v, uint64_t n_slots, ui
     uint64_t k = kEmptyKey;
     uint32_t row = kRowInvalid;
     if (slot < n_slots) {
-        k = v.keys[slot];
-        if (k != kEmptyKey && k != kTombKey) {
-            row = v.rows[slot];
-            if (row != kRowInvalid) {
-                const RowMeta m = CHUNK_META(v, row);
-                uint32_t age = now - m.last_seen;
-                uint32_t fq = m.freq;
-                bool stale = ttl > 0 && age >= ttl;
-                bool rare = min_freq > 0 && fq < min_freq && age >= grace;
-                go = stale || rare;
-            }
+        const V16 e = ld16(v.slots + slot);
+        k = ((uint64_t)e.y << 32) | e.x;
+        row = e.z;
+        if (k != kEmptyKey && k != kTombKey && row != kRowInvalid) {
+            const RowMeta m = CHUNK_META(v, row);
+            const uint32_t age = now - m.last_seen;
+            const bool stale = ttl > 0 && age >= ttl;
+            const bool rare = min_freq > 0 && m.freq < min_freq && age >= grace;
+            go = stale || rare;
         }
     }
     const uint64_t m = __ballot(go);
     if (!m) return;
     const int cnt = __popcll(m);
+    const int leader = __ffsll((unsigned long long)m) - 1;
     int free_base = 0;
     unsigned long long out_base = 0;
-    if (lane == __ffsll((unsigned long long)m) - 1) {
+    if (lane == leader) {
         free_base = atomicAdd(&v.st->free_count, cnt);
         out_base = atomicAdd(n_evicted, (unsigned long long)cnt);
         atomicAdd(&v.st->live, ~(unsigned long long)cnt + 1ull);
         atomicAdd(&v.st->tombstones, (unsigned long long)cnt);
     }
-    const int leader = __ffsll((unsigned long long)m) - 1;
     free_base = __shfl(free_base, leader, kWave);
     out_base = shfl64(out_base, leader);
     if (go) {
         const int r = rank_in(m, lane);
-        v.keys[slot] = kTombKey;
-        v.rows[slot] = kRowInvalid;
+        st16(v.slots + slot, V16{0xFFFFFFFEu, 0xFFFFFFFFu, kRowInvalid, 0u});
         CHUNK_FREE(v, (unsigned)(free_base + r)) = row;
         if (evicted_keys && (int64_t)(out_base + r) < evicted_cap) evicted_keys[out_base + r] = k;
     }
 }
 
 // Key-structure migration: one lane per old slot; a live pair is placed in the first never-used
-// slot of the first line with one on its probe sequence in the new arrays.  No key occurs twice,
-// so no match test is needed.  Values are not touched (Sec. 3.1 "Capacity Expansion").
-__global__ __launch_bounds__(kBlock) void k_rehash(const uint64_t* __restrict__ old_keys,
-                                                   const uint32_t* __restrict__ old_rows, uint64_t old_slots,
-                                                   uint64_t* new_keys, uint32_t* new_rows, uint64_t new_line_mask,
-                                                   HtState* st) {
+// slot of the first line with one on its probe sequence in the new structure.  No key occurs
+// twice, so no match test is needed.  Values are not touched (Sec. 3.1 "Capacity Expansion").
+__global__ __launch_bounds__(kBlock) void k_rehash(const Slot* __restrict__ old_slots, uint64_t n_old, Slot* new_slots,
+                                                   uint64_t new_line_mask, HtState* st) {
     const uint64_t s = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (s >= old_slots) return;
-    const uint64_t k = old_keys[s];
-    if (k == kEmptyKey || k == kTombKey) return;
-    const uint32_t row = old_rows[s];
-    if (row == kRowInvalid) return;
+    if (s >= n_old) return;
+    const V16 e = ld16(old_slots + s);
+    const uint64_t k = ((uint64_t)e.y << 32) | e.x;
+    const uint32_t row = e.z;
+    if (k == kEmptyKey || k == kTombKey || row == kRowInvalid) return;
     const uint64_t h = slot_hash(k);
     uint64_t line = probe_start(h, new_line_mask);
     const uint64_t stride = probe_stride(h, new_line_mask);
     for (uint64_t t = 0; t <= new_line_mask; ++t) {
         for (int j = 0; j < kLineSlots; ++j) {
-            uint64_t* p = new_keys + line * kLineSlots + j;
-            if (load_fresh(p) != kEmptyKey) continue;
-            uint64_t old = atomicCAS(reinterpret_cast<unsigned long long*>(p), (unsigned long long)kEmptyKey,
-                                     (unsigned long long)k);
+            Slot* p = new_slots + line * kLineSlots + j;
+            if (load_fresh(&p->key) != kEmptyKey) continue;
+            const uint64_t old = atomicCAS(&p->key, (unsigned long long)kEmptyKey, (unsigned long long)k);
             if (old == kEmptyKey) {
-                new_rows[line * kLineSlots + j] = row;
+                p->row = row;
                 return;
             }
         }
@@ -408,11 +455,10 @@ __global__ __launch_bounds__(kBlock) void k_export(HtView v, uint64_t n_slots, u
     uint64_t k = 0;
     uint32_t row = kRowInvalid;
     if (slot < n_slots) {
-        k = v.keys[slot];
-        if (k != kEmptyKey && k != kTombKey) {
-            row = v.rows[slot];
-            liveslot = row != kRowInvalid;
-        }
+        const V16 e = ld16(v.slots + slot);
+        k = ((uint64_t)e.y << 32) | e.x;
+        row = e.z;
+        liveslot = k != kEmptyKey && k != kTombKey && row != kRowInvalid;
     }
     uint64_t m = __ballot(liveslot);
     if (!m) return;
@@ -423,10 +469,10 @@ __global__ __launch_bounds__(kBlock) void k_export(HtView v, uint64_t n_slots, u
     const unsigned long long pos = base + rank_in(m, lane);
     if (liveslot && (int64_t)pos < cap) {
         keys[pos] = k;
-        const RowMeta m = CHUNK_META(v, row);
-        if (acc) acc[pos] = m.acc;
-        if (last_seen) last_seen[pos] = m.last_seen;
-        if (freq) freq[pos] = m.freq;
+        const RowMeta rm = CHUNK_META(v, row);
+        if (acc) acc[pos] = rm.acc;
+        if (last_seen) last_seen[pos] = rm.last_seen;
+        if (freq) freq[pos] = rm.freq;
     }
     if (!values) return;
     while (m) {
@@ -503,8 +549,7 @@ int emb_table_create(emb_table_t** out, const emb_table_desc_t* desc, void* stat
     if (t->desc.max_load_factor == 0.0f) t->desc.max_load_factor = 0.75f;
     if (t->desc.init_scale == 0.0f) t->desc.init_scale = 0.01f;
     t->st = static_cast<HtState*>(state);
-    t->keys = nullptr;
-    t->rows = nullptr;
+    t->slots = nullptr;
     t->cap_log2 = 0;
     t->n_chunks = 0;
     t->row_bytes = row_bytes;
@@ -548,15 +593,20 @@ int emb_table_destroy(emb_table_t* t) {
     return EMB_OK;
 }
 
-int ht_set_key_storage(emb_table_t* t, uint64_t* keys, uint32_t* rows, int capacity_log2, void* stream) {
-    if (!t || !keys || !rows || capacity_log2 < 6 || capacity_log2 > 30) return EMB_ERR_INVALID_ARG;
-    if (t->keys && t->live_bound() > 0) return EMB_ERR_INVALID_ARG; // non-empty table: use ht_rehash
+static unsigned fill_grid(uint64_t n) {
+    const unsigned g = blocks_for(n, 256 * 8);
+    return g > (1u << 20) ? (1u << 20) : g;
+}
+
+int ht_set_key_storage(emb_table_t* t, void* slots, int capacity_log2, void* stream) {
+    if (!t || !slots || capacity_log2 < 6 || capacity_log2 > 30) return EMB_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(slots) & 127) return EMB_ERR_INVALID_ARG;
+    if (t->slots && t->live_bound() > 0) return EMB_ERR_INVALID_ARG; // non-empty table: use ht_rehash
     const uint64_t n = 1ull << capacity_log2;
-    hipLaunchKernelGGL(k_fill_keys, dim3(blocks_for(n, 256 * 8) > 65535u * 16 ? 65535u * 16 : blocks_for(n, 256 * 8)),
-                       dim3(256), 0, static_cast<hipStream_t>(stream), keys, rows, n);
+    hipLaunchKernelGGL(k_fill_slots, dim3(fill_grid(n)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<Slot*>(slots), n);
     MTGR_LAUNCH_CHECK();
-    t->keys = keys;
-    t->rows = rows;
+    t->slots = static_cast<Slot*>(slots);
     t->cap_log2 = capacity_log2;
     return EMB_OK;
 }
@@ -578,7 +628,7 @@ int ht_plan(emb_table_t* t, int64_t n_incoming, int* new_capacity_log2, int* chu
     t->refresh();
     if (new_capacity_log2) {
         *new_capacity_log2 = 0;
-        if (t->keys) {
+        if (t->slots) {
             const double cap = (double)(1ull << t->cap_log2);
             const double lf = t->desc.max_load_factor;
             if ((double)(t->occupied_bound() + (uint64_t)n_incoming) > lf * cap) {
@@ -598,7 +648,7 @@ int ht_plan(emb_table_t* t, int64_t n_incoming, int* new_capacity_log2, int* chu
 }
 
 static int check_insert_room(emb_table_t* t, int64_t n_max) {
-    if (!t->keys) return EMB_ERR_NO_STORAGE;
+    if (!t->slots) return EMB_ERR_NO_STORAGE;
     t->refresh();
     const double cap = (double)(1ull << t->cap_log2);
     if ((double)(t->occupied_bound() + (uint64_t)n_max) > (double)t->desc.max_load_factor * cap) return EMB_ERR_NEED_REHASH;
@@ -635,7 +685,7 @@ int ht_find(emb_table_t* t, const uint64_t* key, const int64_t* n_dev, int64_t n
     if (!t || n_max < 0 || n_max > 0x7FFFFFFFll) return EMB_ERR_INVALID_ARG;
     if (n_max == 0) return EMB_OK;
     if (!key || !row_idx) return EMB_ERR_INVALID_ARG;
-    if (!t->keys) return EMB_ERR_NO_STORAGE;
+    if (!t->slots) return EMB_ERR_NO_STORAGE;
     HtView v = t->view();
     const unsigned grid = blocks_for((uint64_t)n_max, kBlock);
     if (v.count)
@@ -651,7 +701,7 @@ int ht_find(emb_table_t* t, const uint64_t* key, const int64_t* n_dev, int64_t n
 int ht_evict(emb_table_t* t, uint32_t now, uint32_t ttl, uint32_t min_freq, uint32_t grace,
              uint64_t* evicted_keys, int64_t evicted_cap, int64_t* n_evicted, void* stream) {
     if (!t || !n_evicted || evicted_cap < 0) return EMB_ERR_INVALID_ARG;
-    if (!t->keys) return EMB_ERR_NO_STORAGE;
+    if (!t->slots) return EMB_ERR_NO_STORAGE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipLaunchKernelGGL(k_zero_bytes, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(n_evicted), (size_t)2);
     MTGR_LAUNCH_CHECK();
@@ -663,27 +713,26 @@ int ht_evict(emb_table_t* t, uint32_t now, uint32_t ttl, uint32_t min_freq, uint
     return t->snapshot(s);
 }
 
-int ht_rehash(emb_table_t* t, uint64_t* new_keys, uint32_t* new_rows, int new_capacity_log2, void* stream) {
-    if (!t || !new_keys || !new_rows || new_capacity_log2 < 6 || new_capacity_log2 > 30) return EMB_ERR_INVALID_ARG;
-    if (!t->keys) return EMB_ERR_NO_STORAGE;
-    if (new_keys == t->keys || new_rows == t->rows) return EMB_ERR_INVALID_ARG;
-    // the live keys (last ht_stats count plus inserts issued since) must fit under the limit
+int ht_rehash(emb_table_t* t, void* new_slots, int new_capacity_log2, void* stream) {
+    if (!t || !new_slots || new_capacity_log2 < 6 || new_capacity_log2 > 30) return EMB_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(new_slots) & 127) return EMB_ERR_INVALID_ARG;
+    if (!t->slots) return EMB_ERR_NO_STORAGE;
+    if (new_slots == t->slots) return EMB_ERR_INVALID_ARG;
+    // the live keys (newest counter copy plus inserts issued since) must fit under the limit
     t->refresh();
     if ((double)t->live_bound() > (double)t->desc.max_load_factor * (double)(1ull << new_capacity_log2))
         return EMB_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint64_t n_new = 1ull << new_capacity_log2;
     const uint64_t n_old = 1ull << t->cap_log2;
-    unsigned fill_grid = blocks_for(n_new, 256 * 8);
-    hipLaunchKernelGGL(k_fill_keys, dim3(fill_grid), dim3(256), 0, s, new_keys, new_rows, n_new);
+    hipLaunchKernelGGL(k_fill_slots, dim3(fill_grid(n_new)), dim3(256), 0, s, static_cast<Slot*>(new_slots), n_new);
     MTGR_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_rehash, dim3(blocks_for(n_old, kBlock)), dim3(kBlock), 0, s, t->keys, t->rows, n_old, new_keys,
-                       new_rows, n_new / kLineSlots - 1ull, t->st);
+    hipLaunchKernelGGL(k_rehash, dim3(blocks_for(n_old, kBlock)), dim3(kBlock), 0, s, t->slots, n_old,
+                       static_cast<Slot*>(new_slots), n_new / kLineSlots - 1ull, t->st);
     MTGR_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_after_rehash, dim3(1), dim3(64), 0, s, t->st);
     MTGR_LAUNCH_CHECK();
-    t->keys = new_keys;
-    t->rows = new_rows;
+    t->slots = static_cast<Slot*>(new_slots);
     t->cap_log2 = new_capacity_log2;
     t->n_rehash += 1;
     t->base_tomb = 0;                   // deleted markers are gone;
@@ -701,7 +750,7 @@ int ht_stats(emb_table_t* t, ht_stats_t* out, void* stream) {
     if (hipStreamSynchronize(s) != hipSuccess) return EMB_ERR_HIP;
     out->live = h.live;
     out->tombstones = h.tombstones;
-    out->capacity = t->keys ? (1ull << t->cap_log2) : 0ull;
+    out->capacity = t->slots ? (1ull << t->cap_log2) : 0ull;
     out->rows_used = h.bump;
     out->rows_free = h.free_count > 0 ? (uint64_t)h.free_count : 0ull;
     out->rows_capacity = (uint64_t)t->n_chunks << t->desc.chunk_rows_log2;
@@ -722,7 +771,7 @@ int ht_stats(emb_table_t* t, ht_stats_t* out, void* stream) {
 int ht_export(emb_table_t* t, uint64_t* keys, void* values, float* acc, uint32_t* last_seen, uint32_t* freq,
               int64_t cap, int64_t* n, void* stream) {
     if (!t || !keys || !n || cap < 0) return EMB_ERR_INVALID_ARG;
-    if (!t->keys) return EMB_ERR_NO_STORAGE;
+    if (!t->slots) return EMB_ERR_NO_STORAGE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipLaunchKernelGGL(k_zero_bytes, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(n), (size_t)2);
     MTGR_LAUNCH_CHECK();

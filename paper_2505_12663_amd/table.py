@@ -36,11 +36,9 @@ class EmbeddingTable:
         desc = B.TableDesc(dim, dtype, init_scale, max_load_factor, chunk_rows_log2, int(count_probes))
         self.h = B.emb_table_create(desc, self.state)
         self.capacity_log2 = capacity_log2
-        self.keys = torch.empty(1 << capacity_log2, dtype=torch.int64, device=self.device)
-        self.rows = torch.empty(1 << capacity_log2, dtype=torch.int32, device=self.device)
-        B.ht_set_key_storage(self.h, self.keys, self.rows, capacity_log2)
+        self.slots = torch.empty((1 << capacity_log2, 2), dtype=torch.int64, device=self.device)   # 16 B per slot
+        B.ht_set_key_storage(self.h, self.slots, capacity_log2)
         self.chunks: List[tuple] = []
-        self._retired = []          # old key arrays kept until the stream has passed the rehash
         for _ in range(initial_chunks):
             self.add_chunk()
 
@@ -66,12 +64,11 @@ class EmbeddingTable:
         self.chunks.append((values, meta, free_list))
 
     def rehash(self, new_capacity_log2: int) -> None:
-        new_keys = torch.empty(1 << new_capacity_log2, dtype=torch.int64, device=self.device)
-        new_rows = torch.empty(1 << new_capacity_log2, dtype=torch.int32, device=self.device)
-        B.ht_rehash(self.h, new_keys, new_rows, new_capacity_log2)
-        # torch's caching allocator is stream-ordered: dropping the old arrays here is safe for
+        new_slots = torch.empty((1 << new_capacity_log2, 2), dtype=torch.int64, device=self.device)
+        B.ht_rehash(self.h, new_slots, new_capacity_log2)
+        # torch's caching allocator is stream-ordered: dropping the old array here is safe for
         # work queued on the current stream.
-        self.keys, self.rows, self.capacity_log2 = new_keys, new_rows, new_capacity_log2
+        self.slots, self.capacity_log2 = new_slots, new_capacity_log2
 
     def stats(self) -> dict:
         return B.ht_stats(self.h)
@@ -150,6 +147,7 @@ class StepBuffers:
         self.inverse = torch.empty(n_max, dtype=torch.int32, device=dev)
         self.perm = torch.empty(n_max, dtype=torch.int32, device=dev)
         self.seg_off = torch.empty(n_max + 1, dtype=torch.int32, device=dev)
+        self.seg_of = torch.empty(n_max, dtype=torch.int32, device=dev)
         self.counts = torch.empty(n_max, dtype=torch.int32, device=dev)
         self.n_unique = torch.zeros(1, dtype=torch.int64, device=dev)
         self.err_count = torch.zeros(1, dtype=torch.int64, device=dev)
@@ -167,7 +165,8 @@ def forward(table: EmbeddingTable, buf: StepBuffers, x, field_off, field_tag, ta
     """tag -> dedup -> find-or-insert -> gather -> expand; results in buf.out[:n]."""
     n = x.numel()
     B.emb_tag_keys(x, field_off, field_tag, tag_bits, buf.key, buf.err_count)
-    B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, buf.counts, buf.perm, buf.seg_off, buf.n_unique, buf.dedup_ws)
+    B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, buf.counts, buf.perm, buf.seg_off, buf.seg_of, buf.n_unique,
+                buf.dedup_ws)
     table.find_or_insert(buf.uniq, buf.n_unique, n, step, buf.row_idx, buf.inserted)
     table.gather(buf.row_idx, buf.n_unique, n, buf.uniq_rows)
     B.emb_expand(buf.uniq_rows, buf.inverse, n, table.dim, table.dtype, buf.out)
@@ -175,5 +174,5 @@ def forward(table: EmbeddingTable, buf: StepBuffers, x, field_off, field_tag, ta
 
 def backward(table: EmbeddingTable, buf: StepBuffers, grad, n: int, lr: float, eps: float = 1e-8) -> None:
     """segment-reduce the upstream gradient per distinct key, then row-wise Adagrad."""
-    B.grad_segment_reduce(grad, table.dtype, buf.inverse, buf.perm, n, table.dim, buf.reduced, buf.reduce_ws)
+    B.grad_segment_reduce(grad, table.dtype, buf.seg_of, buf.perm, n, table.dim, buf.reduced, buf.reduce_ws)
     table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, lr, eps)

@@ -54,12 +54,16 @@ def _run_dedup(keys):
     counts = torch.empty(m, dtype=torch.int32, device="cuda")
     perm = torch.empty(m, dtype=torch.int32, device="cuda")
     seg_off = torch.full((m + 1,), -7, dtype=torch.int32, device="cuda")
+    seg_of = torch.full((m,), -7, dtype=torch.int32, device="cuda")
     n_unique = torch.full((1,), -1, dtype=torch.int64, device="cuda")
     ws = torch.empty(B.emb_dedup_workspace_bytes(n), dtype=torch.uint8, device="cuda")
-    B.emb_dedup(d, n, uniq, inverse, counts, perm, seg_off, n_unique, ws)
+    B.emb_dedup(d, n, uniq, inverse, counts, perm, seg_off, seg_of, n_unique, ws)
     U = int(n_unique.item())
-    return (host_keys(uniq[:U]), inverse[:n].cpu().numpy(), counts[:U].cpu().numpy(), perm[:n].cpu().numpy(),
-            seg_off[:U + 1].cpu().numpy())
+    sof = seg_of[:n].cpu().numpy()
+    pm = perm[:n].cpu().numpy()
+    inv = inverse[:n].cpu().numpy()
+    assert np.array_equal(sof, inv[pm])          # seg_of[j] = inverse[perm[j]] by definition
+    return (host_keys(uniq[:U]), inv, counts[:U].cpu().numpy(), pm, seg_off[:U + 1].cpu().numpy())
 
 
 @pytest.mark.parametrize("case", ["empty", "one", "all_equal", "all_distinct", "zipf_small", "zipf_tiles",
@@ -203,10 +207,10 @@ def _reduce_gpu(G_dev, dtype, keys):
     n, dim = G_dev.shape
     uniq, inverse, counts, perm, seg_off = _run_dedup(keys)
     U = len(uniq)
-    d_inv, d_perm = torch.from_numpy(inverse).cuda(), torch.from_numpy(perm).cuda()
+    d_sof, d_perm = torch.from_numpy(inverse[perm]).cuda(), torch.from_numpy(perm).cuda()
     red = torch.full((max(U, 1), dim), 123.0, dtype=torch.float32, device="cuda")
     ws = torch.empty(B.grad_segment_reduce_workspace_bytes(n, dim), dtype=torch.uint8, device="cuda")
-    B.grad_segment_reduce(G_dev, dtype, d_inv, d_perm, n, dim, red, ws)
+    B.grad_segment_reduce(G_dev, dtype, d_sof, d_perm, n, dim, red, ws)
     return red[:U].cpu().numpy(), inverse, U
 
 
