@@ -152,7 +152,8 @@ def main() -> int:
     torch.cuda.synchronize()
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(len(phases) + 1)] for _ in range(args.steps)]
     uniques, news, ids = [], [], 0
-    live_before = table.stats()["live"]
+    st_before = table.stats()
+    live_before = st_before["live"]
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for k in range(args.steps):
@@ -160,7 +161,8 @@ def main() -> int:
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_start
     ms_per_step = wall * 1e3 / args.steps
-    live_after = table.stats()["live"]
+    st_after = table.stats()
+    live_after = st_after["live"]
 
     phase_ms = {p: float(np.mean([events[k][i].elapsed_time(events[k][i + 1]) for k in range(args.steps)]))
                 for i, p in enumerate(phases)}
@@ -209,8 +211,9 @@ def main() -> int:
         "roofline": roofline,
     }
     if args.count_probes:
-        st = table.stats()
-        result["probe_counters"] = {k: st[k] for k in ("lookups", "probes", "cas_attempts", "cas_failures", "alloc_atomics")}
+        pc = {k: st_after[k] - st_before[k] for k in ("lookups", "probes", "cas_attempts", "cas_failures", "alloc_atomics")}
+        pc["lines_per_lookup"] = round(pc["probes"] / max(pc["lookups"], 1), 4)
+        result["probe_counters_timed_region"] = pc
 
     if args.copy_probe_mib > 0:
         nbytes = args.copy_probe_mib << 20

@@ -124,7 +124,8 @@ int ht_set_key_storage(emb_table_t* t, void* slots, int capacity_log2, void* str
  * values [dev, 16-byte aligned]: rows x dim elements of the table dtype;
  * meta [dev, 16-byte aligned]: rows x 16 bytes of per-row auxiliary data (Adagrad accumulator f32,
  *   last-seen step u32, touch count u32, 4 reserved bytes);
- * free_list [dev]: rows x u32 scratch for the row free list.  Contents need no initialisation. */
+ * free_list [dev]: rows x u32 scratch for the row free list.  values and free_list need no
+ * initialisation; meta is zeroed by this call. */
 int ht_add_chunk(emb_table_t* t, void* values, void* meta, uint32_t* free_list, void* stream);
 
 /* Host-side capacity planning from upper bounds of the device counters: the newest copy of the

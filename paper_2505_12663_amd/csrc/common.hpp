@@ -13,6 +13,7 @@ constexpr uint64_t kTombKey = 0xFFFFFFFFFFFFFFFEull;  // deleted slot, reclaimed
 constexpr uint32_t kRowInvalid = 0xFFFFFFFFu;
 constexpr int kLineSlots = 8;                         // one probe = one aligned 128-byte line of 8 slots
 constexpr int kMaxChunks = 256;
+constexpr int kStatStripes = 64;
 
 // One slot of the key structure: the key and the index of its embedding row (Sec. 3.1: the key
 // structure maps keys to pointers into the embedding structure).
@@ -32,28 +33,44 @@ struct __attribute__((aligned(16))) RowMeta {
 };
 
 // Device-resident table state: counters + chunk directory.  Lives in caller memory.
-struct HtState {
-    unsigned long long live;
-    unsigned long long tombstones;
+// Counters that are only ever added to (no return value needed) are striped over 64 cache lines:
+// atomics of concurrently running blocks on one address queue up behind each other (about 25 ns
+// apiece on this part), atomics on different lines do not.
+enum StatSlot { kStatLookups = 0, kStatProbes, kStatCas, kStatCasFail, kStatAlloc, kStatLive, kStatTomb, kStatUnused };
+struct HtHead {
     unsigned int bump;       // rows handed out by the bump allocator
     int free_count;          // entries on the free-row stack (may dip below 0 inside an insert kernel)
     unsigned int status;     // EMB_DEV_* bits
     unsigned int pad0;
-    unsigned long long lookups, probes, cas_attempts, cas_failures, alloc_atomics;
-    unsigned long long pad1[7];
+    unsigned long long pad1[14];
+    unsigned long long stat[kStatStripes][8]; // [stripe][StatSlot]; live / deleted counts are the sums over stripes
+};
+struct HtState {
+    HtHead head;
     void* values[kMaxChunks];
     RowMeta* meta[kMaxChunks];
     uint32_t* free_list[kMaxChunks];
 };
 
-// The first 32 bytes of HtState, as copied to the host.
+// Host view of the counters.
 struct HtCounts {
-    unsigned long long live;
-    unsigned long long tombstones;
+    unsigned long long live, tombstones;
     unsigned int bump;
     int free_count;
     unsigned int status;
-    unsigned int pad0;
+    unsigned long long stat[5];
+    static HtCounts from(const HtHead& h) {
+        HtCounts c{};
+        c.bump = h.bump;
+        c.free_count = h.free_count;
+        c.status = h.status;
+        for (int i = 0; i < kStatStripes; ++i) {
+            c.live += h.stat[i][kStatLive];            // wraps: stripes hold signed deltas
+            c.tombstones += h.stat[i][kStatTomb];
+            for (int k = 0; k < 5; ++k) c.stat[k] += h.stat[i][k];
+        }
+        return c;
+    }
 };
 
 // What a table kernel needs, passed by value.
@@ -169,7 +186,7 @@ struct emb_table {
     // pinned host memory followed by an event, and the newest completed copy is adopted.
     uint64_t base_live, base_tomb, base_rows;
     uint64_t pending;
-    mtgr::HtCounts* snap_host;             // pinned, kSnaps entries
+    mtgr::HtHead* snap_host;               // pinned, kSnaps entries
     hipEvent_t snap_ev[kSnaps];
     uint64_t snap_seq[kSnaps];             // 0 = never recorded
     uint64_t snap_pending_after[kSnaps];   // n_max issued after the snapshot was queued
@@ -196,7 +213,7 @@ struct emb_table {
             if (best >= 0 && snap_seq[i] < snap_seq[best]) continue;
             if (hipEventQuery(snap_ev[i]) == hipSuccess) best = i;
         }
-        if (best >= 0) adopt(snap_host[best], snap_pending_after[best], snap_seq[best]);
+        if (best >= 0) adopt(mtgr::HtCounts::from(snap_host[best]), snap_pending_after[best], snap_seq[best]);
     }
     void issued(uint64_t n_max) {
         pending += n_max;
@@ -205,7 +222,7 @@ struct emb_table {
     int snapshot(hipStream_t s) {
         const int i = snap_next;
         snap_next = (snap_next + 1) % kSnaps;
-        if (hipMemcpyAsync(&snap_host[i], st, sizeof(mtgr::HtCounts), hipMemcpyDeviceToHost, s) != hipSuccess) return EMB_ERR_HIP;
+        if (hipMemcpyAsync(&snap_host[i], st, sizeof(mtgr::HtHead), hipMemcpyDeviceToHost, s) != hipSuccess) return EMB_ERR_HIP;
         if (hipEventRecord(snap_ev[i], s) != hipSuccess) return EMB_ERR_HIP;
         snap_seq[i] = ++seq;
         snap_pending_after[i] = 0;

@@ -12,7 +12,13 @@ using namespace mtgr;
 namespace {
 
 constexpr int kBlock = 256;
-constexpr int kUnroll = 4;
+#ifndef MTGR_RED_UNROLL
+#define MTGR_RED_UNROLL 4
+#endif
+#ifndef MTGR_RED_SPAN
+#define MTGR_RED_SPAN 64
+#endif
+constexpr int kUnroll = MTGR_RED_UNROLL;
 
 __device__ inline const char* chunk_row_cptr(const HtView& v, uint32_t row) {
     const char* base = static_cast<const char*>(v.st->values[row >> v.chunk_log2]);
@@ -21,8 +27,51 @@ __device__ inline const char* chunk_row_cptr(const HtView& v, uint32_t row) {
 
 // ---------------------------------------------------------------------------- gather / expand
 // One wave owns 64 consecutive output rows; lane l reads index l once, the LPR-lane groups then
-// take the rows in turn.  SRC_TABLE: source row = chunked table row (index -1 -> zeros);
-// otherwise source row = base + index * row_bytes.
+// take the rows in turn, kCopyUnroll rows in flight per group.  SRC_TABLE: source row = chunked
+// table row (index -1 -> zeros); otherwise source row = base + index * row_bytes.
+// FULL = all 64 rows present and every lane of a group carries a vector: no per-row branches,
+// so the loads of one batch and the stores of the previous one stay in flight together.
+constexpr int kCopyUnroll = 8;
+
+template <int LPR, bool SRC_TABLE, bool NT_STORE, bool FULL>
+__device__ inline void copy_rows_body(const HtView& v, const char* __restrict__ src_base, int my_index, int rows_here,
+                                      int vecs, int row_bytes, char* __restrict__ out_wave, int lane) {
+    constexpr int kGroups = kWave / LPR;          // rows per wave instruction
+    constexpr int kU = (kGroups * kCopyUnroll > kWave) ? (kWave / kGroups) : kCopyUnroll;
+    const int sub = lane % LPR, grp = lane / LPR;
+    const bool lane_on = FULL || sub < vecs;
+#pragma unroll 1
+    for (int r0 = 0; r0 < kWave; r0 += kGroups * kU) {
+        if (!FULL && r0 >= rows_here) break;
+        V16 val[kU];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int r = r0 + u * kGroups + grp;
+            const int idx = __shfl(my_index, r, kWave);
+            const bool ok = lane_on && (FULL || r < rows_here);
+            const int safe = idx < 0 ? 0 : idx;
+            const char* p = SRC_TABLE ? chunk_row_cptr(v, (uint32_t)safe) : src_base + (size_t)safe * (size_t)row_bytes;
+            if (FULL) {
+                val[u] = ld16(p + sub * 16);
+            } else {
+                val[u] = V16{0u, 0u, 0u, 0u};
+                if (ok) val[u] = ld16(p + sub * 16);
+            }
+            if (SRC_TABLE && idx < 0) val[u] = V16{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int r = r0 + u * kGroups + grp;
+            char* q = out_wave + (size_t)r * (size_t)row_bytes + sub * 16;
+            if (FULL) {
+                if (NT_STORE) st16_nt(q, val[u]); else st16(q, val[u]);
+            } else if (lane_on && r < rows_here) {
+                if (NT_STORE) st16_nt(q, val[u]); else st16(q, val[u]);
+            }
+        }
+    }
+}
+
 template <int LPR, bool SRC_TABLE, bool NT_STORE>
 __global__ __launch_bounds__(kBlock) void k_copy_rows(HtView v, const char* __restrict__ src_base,
                                                       const int32_t* __restrict__ index, const int64_t* n_dev,
@@ -31,35 +80,14 @@ __global__ __launch_bounds__(kBlock) void k_copy_rows(HtView v, const char* __re
     const int lane = lane_id();
     const int64_t wave_base = (int64_t)blockIdx.x * kBlock + (threadIdx.x & ~(kWave - 1));
     if (wave_base >= n) return;
-    constexpr int kGroups = kWave / LPR;          // rows per wave instruction
-    const int sub = lane % LPR, grp = lane / LPR;
     const int vecs = row_bytes / 16;
-    const bool lane_on = sub < vecs;
     const int my_index = (wave_base + lane < n) ? index[wave_base + lane] : -1;
     const int rows_here = (int)((n - wave_base) < kWave ? (n - wave_base) : kWave);
-#pragma unroll 1
-    for (int r0 = 0; r0 < kWave; r0 += kGroups * kUnroll) {
-        if (r0 >= rows_here) break;
-        V16 val[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int r = r0 + u * kGroups + grp;
-            const int idx = __shfl(my_index, r & (kWave - 1), kWave);
-            val[u] = V16{0u, 0u, 0u, 0u};
-            if (lane_on && r < rows_here && idx >= 0) {
-                const char* p = SRC_TABLE ? chunk_row_cptr(v, (uint32_t)idx) : src_base + (size_t)idx * (size_t)row_bytes;
-                val[u] = ld16(p + sub * 16);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int r = r0 + u * kGroups + grp;
-            if (lane_on && r < rows_here) {
-                char* q = out + (size_t)(wave_base + r) * (size_t)row_bytes + sub * 16;
-                if (NT_STORE) st16_nt(q, val[u]); else st16(q, val[u]);
-            }
-        }
-    }
+    char* out_wave = out + (size_t)wave_base * (size_t)row_bytes;
+    if (rows_here == kWave && vecs == LPR)
+        copy_rows_body<LPR, SRC_TABLE, NT_STORE, true>(v, src_base, my_index, rows_here, vecs, row_bytes, out_wave, lane);
+    else
+        copy_rows_body<LPR, SRC_TABLE, NT_STORE, false>(v, src_base, my_index, rows_here, vecs, row_bytes, out_wave, lane);
 }
 
 template <bool SRC_TABLE, bool NT>
@@ -89,8 +117,10 @@ int launch_copy_rows(const HtView& v, const char* src, const int32_t* index, con
 // stored to reduced[]; the first and the last run of the span may continue in a neighbour span,
 // so they are handed to the next level as two fp32 partial rows (segment -1 = no item).  The next
 // level folds kSpan of those, and so on until one span holds everything.  Every sum is a fixed
-// tree, so results are reproducible run to run.
-constexpr int kSpan = 128;
+// tree, so results are reproducible run to run.  Span length trades partial-row traffic (two
+// fp32 rows per span) against parallelism; 64 measured best on the long-sequence workload
+// (0.67 ms against 0.72 ms at 128 and 0.84 ms at 256 for 8.7 M rows of 256 bytes).
+constexpr int kSpan = MTGR_RED_SPAN;
 
 // FPL = floats accumulated per lane (4 for fp32 rows of 16 bytes per lane, 8 for bf16)
 template <int FPL>

@@ -13,6 +13,8 @@ using namespace mtgr;
 namespace {
 
 constexpr int kBlock = 256;
+constexpr int kBigBlock = 1024;            // kernels that aggregate allocator traffic per block
+constexpr int kBigWaves = kBigBlock / kWave;
 
 __device__ inline void* chunk_row_ptr(const HtView& v, uint32_t row) {
     char* base = static_cast<char*>(v.st->values[row >> v.chunk_log2]);
@@ -34,12 +36,16 @@ __global__ void k_zero_bytes(uint32_t* p, size_t n_words) {
     if (i < n_words) p[i] = 0u;
 }
 
-__global__ void k_set_chunk(HtState* st, int c, void* values, RowMeta* meta, uint32_t* free_list) {
+__global__ void k_set_chunk(HtState* st, int c, void* values, RowMeta* meta, uint32_t* free_list, uint64_t rows) {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
         st->values[c] = values;
         st->meta[c] = meta;
         st->free_list[c] = free_list;
     }
+    // unused rows keep freq == 0 (see k_find_or_insert)
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < rows; i += stride)
+        st16(meta + i, V16{0u, 0u, 0u, 0u});
 }
 
 struct ProbeCounters {
@@ -125,9 +131,15 @@ __device__ inline long long probe_group(const HtView& v, uint64_t key, bool acti
 
 // First lines of the 8 keys of every group, all loads in flight at once: a key found there is
 // settled without entering the line-by-line loop (at the load factors in use that is nearly all
-// present keys).  found_slot stays -1 for the others.
+// present keys).  With INSERT, a key whose first line shows no match but a never-used slot is
+// claimed right here, again with the 8 attempts of a group in flight together.  The line was read
+// with ordinary loads and may be out of date, which is harmless: occupied slots never change, so
+// "no match among the occupied slots before the first empty one" stays true, and the CAS itself
+// decides whether that slot was still empty; if it went to another key the element simply takes the
+// line-by-line path.  found_slot stays -1 for unsettled elements.
+template <bool INSERT>
 __device__ inline void first_line_pass(const HtView& v, uint64_t my_key, bool my_ok, int lane, long long* found_slot,
-                                       uint32_t* found_row, ProbeCounters* pc) {
+                                       uint32_t* found_row, bool* created, ProbeCounters* pc) {
     const int sub = lane & (kLineSlots - 1);
     const int gbase = lane & ~(kLineSlots - 1);
     uint64_t kr[kLineSlots];
@@ -141,6 +153,9 @@ __device__ inline void first_line_pass(const HtView& v, uint64_t my_key, bool my
     }
     *found_slot = -1;
     *found_row = kRowInvalid;
+    *created = false;
+    uint64_t cas_old[kLineSlots];
+    unsigned want_mask = 0; // bit r: this lane issued the claim for key r
 #pragma unroll
     for (int r = 0; r < kLineSlots; ++r) {
         const bool ok = __shfl((int)my_ok, gbase + r, kWave) != 0;
@@ -154,22 +169,56 @@ __device__ inline void first_line_pass(const HtView& v, uint64_t my_key, bool my
             *found_row = row;
         }
         pc->probes += (sub == r && ok) ? 1u : 0u;
+        cas_old[r] = 0;
+        if (INSERT) {
+            const uint64_t me = __ballot(ok && k == kEmptyKey);
+            const unsigned empty8 = (unsigned)(me >> gbase) & 0xFFu;
+            if (ok && !hit8 && empty8 && sub == (__ffs(empty8) - 1)) {
+                cas_old[r] = atomicCAS(&(v.slots + line[r] * kLineSlots + sub)->key, (unsigned long long)kEmptyKey,
+                                       (unsigned long long)kr[r]);
+                want_mask |= 1u << r;
+                pc->cas += 1;
+                if (cas_old[r] != kEmptyKey) pc->cas_fail += 1;
+            }
+        }
+    }
+    if (INSERT) {
+#pragma unroll
+        for (int r = 0; r < kLineSlots; ++r) {
+            // which lane of the group (if any) tried to claim a slot for key r, and what came back
+            const uint64_t mw = __ballot((want_mask >> r) & 1u);
+            const unsigned w8 = (unsigned)(mw >> gbase) & 0xFFu;
+            const int wl = w8 ? (__ffs(w8) - 1) : 0;
+            const uint64_t old = shfl64(cas_old[r], gbase + wl);
+            if (sub == r && w8) {
+                if (old == kEmptyKey) {
+                    *found_slot = (long long)(line[r] * kLineSlots + wl);
+                    *created = true;
+                } else if (old == kr[r]) {
+                    *found_slot = (long long)(line[r] * kLineSlots + wl); // a duplicate got there first
+                }
+            }
+        }
     }
 }
 
-__device__ inline void flush_counters(const HtView& v, int lane, int64_t cnt, ProbeCounters pc, unsigned alloc_atomics) {
+__device__ inline unsigned long long* stat_stripe(const HtView& v, unsigned id) {
+    return v.st->head.stat[id & (kStatStripes - 1)];
+}
+
+__device__ inline void flush_counters(const HtView& v, int lane, unsigned wave_no, int64_t cnt, ProbeCounters pc) {
     unsigned tot_p = pc.probes, tot_c = pc.cas, tot_f = pc.cas_fail;
     for (int o = 32; o > 0; o >>= 1) {
         tot_p += __shfl_xor(tot_p, o, kWave);
         tot_c += __shfl_xor(tot_c, o, kWave);
         tot_f += __shfl_xor(tot_f, o, kWave);
     }
-    if (lane == 0) { // one atomic per counter per wave
-        atomicAdd(&v.st->lookups, (unsigned long long)cnt);
-        atomicAdd(&v.st->probes, (unsigned long long)tot_p);
-        if (tot_c) atomicAdd(&v.st->cas_attempts, (unsigned long long)tot_c);
-        if (tot_f) atomicAdd(&v.st->cas_failures, (unsigned long long)tot_f);
-        if (alloc_atomics) atomicAdd(&v.st->alloc_atomics, (unsigned long long)alloc_atomics);
+    if (lane == 0 && cnt > 0) { // one atomic per counter per wave, on the wave's own stripe
+        unsigned long long* c = stat_stripe(v, wave_no);
+        atomicAdd(&c[kStatLookups], (unsigned long long)cnt);
+        atomicAdd(&c[kStatProbes], (unsigned long long)tot_p);
+        if (tot_c) atomicAdd(&c[kStatCas], (unsigned long long)tot_c);
+        if (tot_f) atomicAdd(&c[kStatCasFail], (unsigned long long)tot_f);
     }
 }
 
@@ -180,16 +229,23 @@ __device__ inline void touch_row(const HtView& v, uint32_t row, uint32_t step) {
 }
 
 // One wave handles 64 keys: each lane owns one key; the 8 groups of 8 lanes first look at the first
-// line of each of their 8 keys, then work through the unsettled keys one after the other.
+// line of each of their 8 keys, then work through the unsettled keys one after the other.  Rows
+// for the new keys of all 16 waves of a block are taken from the allocator with one atomic per
+// block (a 4 M-key bulk insert otherwise queues 130 k atomics on the bump pointer).
 template <bool COUNT>
-__global__ __launch_bounds__(kBlock) void k_find_or_insert(HtView v, const uint64_t* __restrict__ key,
-                                                           const int64_t* n_dev, int64_t n_max, uint32_t step,
-                                                           int32_t* __restrict__ row_idx,
-                                                           uint8_t* __restrict__ inserted) {
+__global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const uint64_t* __restrict__ key,
+                                                              const int64_t* n_dev, int64_t n_max, uint32_t step,
+                                                              int32_t* __restrict__ row_idx,
+                                                              uint8_t* __restrict__ inserted) {
+    __shared__ int s_new[kBigWaves];
+    __shared__ int s_old_free, s_take;
+    __shared__ unsigned s_bump;
     const int64_t n = read_count(n_dev, n_max);
+    if ((int64_t)blockIdx.x * kBigBlock >= n) return; // whole block beyond the count
     const int lane = lane_id();
-    const int64_t wave_base = ((int64_t)blockIdx.x * kBlock + (threadIdx.x & ~(kWave - 1)));
-    if (wave_base >= n) return;
+    const int wave = threadIdx.x / kWave;
+    const int64_t wave_base = (int64_t)blockIdx.x * kBigBlock + wave * kWave;
+    const bool wave_on = wave_base < n;
     const int64_t i = wave_base + lane;
     const bool valid = i < n;
     const uint64_t my_key = valid ? key[i] : 0ull;
@@ -199,77 +255,88 @@ __global__ __launch_bounds__(kBlock) void k_find_or_insert(HtView v, const uint6
     const int gbase = lane & ~(kLineSlots - 1);
 
     ProbeCounters pc{0u, 0u, 0u};
-    long long my_slot;
-    uint32_t my_row;
-    first_line_pass(v, my_key, my_ok, lane, &my_slot, &my_row, &pc);
+    long long my_slot = -1;
+    uint32_t my_row = kRowInvalid;
     bool my_created = false;
-    // keys not settled by the first-line pass (absent, displaced, or in a line that changed)
-    const bool need_slow = my_ok && my_slot < 0;
-    if (__any(need_slow)) {
-        for (int r = 0; r < kLineSlots; ++r) {
-            const bool act = __shfl((int)need_slow, gbase + r, kWave) != 0;
-            if (!__any(act)) continue;
-            const uint64_t k = shfl64(my_key, gbase + r);
-            bool created;
-            const long long s = probe_group<true>(v, k, act, lane, &created, &pc);
-            if (sub == r && act) {
-                my_slot = s;
-                my_created = created;
-                my_row = kRowInvalid;
+    if (wave_on) {
+        first_line_pass<true>(v, my_key, my_ok, lane, &my_slot, &my_row, &my_created, &pc);
+        // keys not settled by the first-line pass (first line full, or it changed under us)
+        const bool need_slow = my_ok && my_slot < 0;
+        if (__any(need_slow)) {
+            for (int r = 0; r < kLineSlots; ++r) {
+                const bool act = __shfl((int)need_slow, gbase + r, kWave) != 0;
+                if (!__any(act)) continue;
+                const uint64_t k = shfl64(my_key, gbase + r);
+                bool created;
+                const long long s = probe_group<true>(v, k, act, lane, &created, &pc);
+                if (sub == r && act) {
+                    my_slot = s;
+                    my_created = created;
+                    my_row = kRowInvalid;
+                }
             }
         }
     }
 
-    // ---- wave-aggregated row allocation for the lanes that claimed a slot
+    // ---- block-aggregated row allocation for the lanes that claimed a slot
     const uint64_t m_new = __ballot(my_created);
-    unsigned n_alloc_atomics = 0;
-    if (m_new) {
-        const int n_new = __popcll(m_new);
-        int old_free = 0;
+    if (lane == 0) s_new[wave] = __popcll(m_new);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int total = 0;
+        for (int w = 0; w < kBigWaves; ++w) total += s_new[w];
+        int old_free = 0, take = 0;
         unsigned bump_base = 0;
-        int take = 0;
-        if (lane == 0) {
-            if (load_fresh(reinterpret_cast<const uint32_t*>(&v.st->free_count)) != 0u) {
-                old_free = atomicSub(&v.st->free_count, n_new);
-                n_alloc_atomics += 1;
+        if (total > 0) {
+            unsigned n_atomics = 0;
+            if (load_fresh(reinterpret_cast<const uint32_t*>(&v.st->head.free_count)) != 0u) {
+                old_free = atomicSub(&v.st->head.free_count, total);
+                ++n_atomics;
             }
-            take = old_free < 0 ? 0 : (old_free > n_new ? n_new : old_free);
-            if (n_new - take > 0) {
-                bump_base = atomicAdd(&v.st->bump, (unsigned)(n_new - take));
-                n_alloc_atomics += 1;
+            take = old_free < 0 ? 0 : (old_free > total ? total : old_free);
+            if (total - take > 0) {
+                bump_base = atomicAdd(&v.st->head.bump, (unsigned)(total - take));
+                ++n_atomics;
             }
-            atomicAdd(&v.st->live, (unsigned long long)n_new);
+            unsigned long long* c = stat_stripe(v, blockIdx.x);
+            atomicAdd(&c[kStatLive], (unsigned long long)total);
+            if (COUNT) atomicAdd(&c[kStatAlloc], (unsigned long long)n_atomics);
         }
-        old_free = __shfl(old_free, 0, kWave);
-        take = __shfl(take, 0, kWave);
-        bump_base = __shfl(bump_base, 0, kWave);
-        if (my_created) {
-            const int r = rank_in(m_new, lane);
-            if (r < take) {
-                my_row = CHUNK_FREE(v, (unsigned)(old_free - 1 - r));
-            } else {
-                my_row = bump_base + (unsigned)(r - take);
-            }
-            if (my_row >= v.rows_capacity) {
-                // out of row storage: give the slot up again (as a deleted marker) and report
-                atomicOr(&v.st->status, EMB_DEV_OUT_OF_ROWS);
-                v.slots[my_slot].key = kTombKey;
-                atomicAdd(&v.st->tombstones, 1ull);
-                atomicAdd(&v.st->live, ~0ull); // -1
-                my_row = kRowInvalid;
-                my_created = false;
-                my_slot = -1;
-            }
+        s_old_free = old_free;
+        s_take = take;
+        s_bump = bump_base;
+    }
+    __syncthreads();
+    if (my_created) {
+        int r = rank_in(m_new, lane);
+        for (int w = 0; w < wave; ++w) r += s_new[w];
+        const int take = s_take;
+        if (r < take) {
+            my_row = CHUNK_FREE(v, (unsigned)(s_old_free - 1 - r));
+        } else {
+            my_row = s_bump + (unsigned)(r - take);
+        }
+        if (my_row >= v.rows_capacity) {
+            // out of row storage: give the slot up again (as a deleted marker) and report
+            atomicOr(&v.st->head.status, EMB_DEV_OUT_OF_ROWS);
+            v.slots[my_slot].key = kTombKey;
+            unsigned long long* c = stat_stripe(v, blockIdx.x);
+            atomicAdd(&c[kStatTomb], 1ull);
+            atomicAdd(&c[kStatLive], ~0ull); // -1
+            my_row = kRowInvalid;
+            my_created = false;
+            my_slot = -1;
         }
     }
-    // ---- initialise the new rows, the whole wave writing one row at a time (coalesced)
+    // ---- initialise the new rows, the whole wave writing one row at a time (coalesced).  Every
+    // creating lane resolves its own row address first, so the loop has no dependent loads.
+    const uint64_t my_dst = my_created ? reinterpret_cast<uint64_t>(chunk_row_ptr(v, my_row)) : 0ull;
     uint64_t m_init = __ballot(my_created);
     while (m_init) {
         const int src = __ffsll((unsigned long long)m_init) - 1;
         m_init &= m_init - 1;
         const uint64_t k = shfl64(my_key, src);
-        const uint32_t row = __shfl(my_row, src, kWave);
-        char* dst = static_cast<char*>(chunk_row_ptr(v, row));
+        char* dst = reinterpret_cast<char*>(shfl64(my_dst, src));
         if (v.dtype == EMB_F32) {
             for (int j = lane; j < v.dim; j += kWave) reinterpret_cast<float*>(dst)[j] = init_value(k, j, v.init_c);
         } else {
@@ -278,11 +345,14 @@ __global__ __launch_bounds__(kBlock) void k_find_or_insert(HtView v, const uint6
         }
     }
     if (my_created) {
-        // the creating element's own touch is part of the initial record; publish the row index
-        // only after the record is visible device-wide, so that a duplicate of the key that sees
-        // the row may count its touch at once
-        CHUNK_META(v, my_row) = RowMeta{0.0f, step, 1u, 0u};
-        __threadfence();
+        // A row that is not in use always has freq == 0 (chunks are registered zeroed, eviction
+        // resets it), so creator and duplicates alike count their touch with an atomic add and no
+        // ordering between this record and the publication of the row index is needed - a release
+        // fence here would write the whole L2 back per wave.
+        RowMeta* m = &CHUNK_META(v, my_row);
+        m->acc = 0.0f;
+        m->last_seen = step;
+        atomicAdd(&m->freq, 1u);
         __hip_atomic_store(&v.slots[my_slot].row, my_row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     // ---- results.  A lane that found a key whose creator has not published the row yet records
@@ -290,10 +360,10 @@ __global__ __launch_bounds__(kBlock) void k_find_or_insert(HtView v, const uint6
     if (valid) {
         int32_t out;
         if (bad) {
-            atomicOr(&v.st->status, EMB_DEV_BAD_KEY);
+            atomicOr(&v.st->head.status, EMB_DEV_BAD_KEY);
             out = -1;
         } else if (my_slot == -2) {
-            atomicOr(&v.st->status, EMB_DEV_PROBE_EXHAUSTED);
+            atomicOr(&v.st->head.status, EMB_DEV_PROBE_EXHAUSTED);
             out = -1;
         } else if (my_slot < 0) {
             out = -1;
@@ -311,7 +381,8 @@ __global__ __launch_bounds__(kBlock) void k_find_or_insert(HtView v, const uint6
         row_idx[i] = out;
         if (inserted) inserted[i] = my_created ? 1 : 0;
     }
-    if (COUNT) flush_counters(v, lane, n - wave_base < kWave ? n - wave_base : kWave, pc, n_alloc_atomics);
+    if (COUNT && wave_on)
+        flush_counters(v, lane, blockIdx.x * kBigWaves + wave, n - wave_base < kWave ? n - wave_base : kWave, pc);
 }
 
 // Second half of find-or-insert: resolve the deferred elements and count their touch.
@@ -319,7 +390,7 @@ __global__ __launch_bounds__(kBlock) void k_touch(HtView v, const int64_t* n_dev
                                                   int32_t* __restrict__ row_idx) {
     const int64_t n = read_count(n_dev, n_max);
     const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (i == 0 && v.st->free_count < 0) v.st->free_count = 0; // the free list ran dry during the insert
+    if (i == 0 && v.st->head.free_count < 0) v.st->head.free_count = 0; // the free list ran dry during the insert
     if (i >= n) return;
     const int32_t r = row_idx[i];
     if (r > -2) return;
@@ -348,7 +419,8 @@ __global__ __launch_bounds__(kBlock) void k_find(HtView v, const uint64_t* __res
     ProbeCounters pc{0u, 0u, 0u};
     long long my_slot;
     uint32_t my_row;
-    first_line_pass(v, my_key, my_ok, lane, &my_slot, &my_row, &pc);
+    bool unused_created;
+    first_line_pass<false>(v, my_key, my_ok, lane, &my_slot, &my_row, &unused_created, &pc);
     const bool need_slow = my_ok && my_slot < 0;
     if (__any(need_slow)) {
         for (int r = 0; r < kLineSlots; ++r) {
@@ -364,17 +436,21 @@ __global__ __launch_bounds__(kBlock) void k_find(HtView v, const uint64_t* __res
         }
     }
     if (valid) row_idx[i] = (my_slot >= 0 && my_row != kRowInvalid) ? (int32_t)my_row : -1;
-    if (COUNT) flush_counters(v, lane, n - wave_base < kWave ? n - wave_base : kWave, pc, 0u);
+    if (COUNT) flush_counters(v, lane, blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave, n - wave_base < kWave ? n - wave_base : kWave, pc);
 }
 
 // --------------------------------------------------------------------------------------------
 // Eviction: one lane per slot.  Matching keys become deleted markers; their rows go to the free
-// stack and their keys to the output list, both with one atomic per wave.
-__global__ __launch_bounds__(kBlock) void k_evict(HtView v, uint64_t n_slots, uint32_t now, uint32_t ttl,
-                                                  uint32_t min_freq, uint32_t grace, uint64_t* evicted_keys,
-                                                  int64_t evicted_cap, unsigned long long* n_evicted) {
+// stack and their keys to the output list, with one atomic on each per block of 1024 slots.
+__global__ __launch_bounds__(kBigBlock) void k_evict(HtView v, uint64_t n_slots, uint32_t now, uint32_t ttl,
+                                                     uint32_t min_freq, uint32_t grace, uint64_t* evicted_keys,
+                                                     int64_t evicted_cap, unsigned long long* n_evicted) {
+    __shared__ int s_cnt[kBigWaves];
+    __shared__ int s_free_base;
+    __shared__ unsigned long long s_out_base;
     const int lane = lane_id();
-    const uint64_t slot = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int wave = threadIdx.x / kWave;
+    const uint64_t slot = (uint64_t)blockIdx.x * kBigBlock + threadIdx.x;
     bool go = false;
     uint64_t k = kEmptyKey;
     uint32_t row = kRowInvalid;
@@ -391,24 +467,31 @@ __global__ __launch_bounds__(kBlock) void k_evict(HtView v, uint64_t n_slots, ui
         }
     }
     const uint64_t m = __ballot(go);
-    if (!m) return;
-    const int cnt = __popcll(m);
-    const int leader = __ffsll((unsigned long long)m) - 1;
-    int free_base = 0;
-    unsigned long long out_base = 0;
-    if (lane == leader) {
-        free_base = atomicAdd(&v.st->free_count, cnt);
-        out_base = atomicAdd(n_evicted, (unsigned long long)cnt);
-        atomicAdd(&v.st->live, ~(unsigned long long)cnt + 1ull);
-        atomicAdd(&v.st->tombstones, (unsigned long long)cnt);
+    if (lane == 0) s_cnt[wave] = __popcll(m);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int total = 0;
+        for (int w = 0; w < kBigWaves; ++w) total += s_cnt[w];
+        int free_base = 0;
+        unsigned long long out_base = 0;
+        if (total > 0) {
+            free_base = atomicAdd(&v.st->head.free_count, total);
+            out_base = atomicAdd(n_evicted, (unsigned long long)total);
+            unsigned long long* c = stat_stripe(v, blockIdx.x);
+            atomicAdd(&c[kStatLive], ~(unsigned long long)total + 1ull);
+            atomicAdd(&c[kStatTomb], (unsigned long long)total);
+        }
+        s_free_base = free_base;
+        s_out_base = out_base;
     }
-    free_base = __shfl(free_base, leader, kWave);
-    out_base = shfl64(out_base, leader);
+    __syncthreads();
     if (go) {
-        const int r = rank_in(m, lane);
+        int r = rank_in(m, lane);
+        for (int w = 0; w < wave; ++w) r += s_cnt[w];
         st16(v.slots + slot, V16{0xFFFFFFFEu, 0xFFFFFFFFu, kRowInvalid, 0u});
-        CHUNK_FREE(v, (unsigned)(free_base + r)) = row;
-        if (evicted_keys && (int64_t)(out_base + r) < evicted_cap) evicted_keys[out_base + r] = k;
+        CHUNK_FREE(v, (unsigned)(s_free_base + r)) = row;
+        CHUNK_META(v, row) = RowMeta{0.0f, 0u, 0u, 0u}; // unused rows keep freq == 0
+        if (evicted_keys && (int64_t)(s_out_base + r) < evicted_cap) evicted_keys[s_out_base + r] = k;
     }
 }
 
@@ -438,11 +521,11 @@ __global__ __launch_bounds__(kBlock) void k_rehash(const Slot* __restrict__ old_
         }
         line = (line + stride) & new_line_mask;
     }
-    atomicOr(&st->status, EMB_DEV_PROBE_EXHAUSTED);
+    atomicOr(&st->head.status, EMB_DEV_PROBE_EXHAUSTED);
 }
 
 __global__ void k_after_rehash(HtState* st) {
-    if (threadIdx.x == 0 && blockIdx.x == 0) st->tombstones = 0ull;
+    if (blockIdx.x == 0 && threadIdx.x < kStatStripes) st->head.stat[threadIdx.x][kStatTomb] = 0ull;
 }
 
 // Unordered dump: one lane per slot decides, then the wave copies the rows of its live slots.
@@ -559,7 +642,7 @@ int emb_table_create(emb_table_t** out, const emb_table_desc_t* desc, void* stat
     t->min_valid_seq = 1;
     t->snap_next = 0;
     t->snap_host = nullptr;
-    if (hipHostMalloc(reinterpret_cast<void**>(&t->snap_host), sizeof(HtCounts) * emb_table::kSnaps, hipHostMallocDefault) !=
+    if (hipHostMalloc(reinterpret_cast<void**>(&t->snap_host), sizeof(HtHead) * emb_table::kSnaps, hipHostMallocDefault) !=
         hipSuccess) {
         delete t;
         return EMB_ERR_HIP;
@@ -616,8 +699,9 @@ int ht_add_chunk(emb_table_t* t, void* values, void* meta, uint32_t* free_list, 
     if (t->n_chunks >= kMaxChunks) return EMB_ERR_NO_STORAGE;
     if (((uint64_t)(t->n_chunks + 1) << t->desc.chunk_rows_log2) > 0x7FFFFFFFull) return EMB_ERR_NO_STORAGE;
     if ((reinterpret_cast<uintptr_t>(values) & 15) || (reinterpret_cast<uintptr_t>(meta) & 15)) return EMB_ERR_INVALID_ARG;
-    hipLaunchKernelGGL(k_set_chunk, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), t->st, t->n_chunks, values,
-                       static_cast<RowMeta*>(meta), free_list);
+    const uint64_t rows = 1ull << t->desc.chunk_rows_log2;
+    hipLaunchKernelGGL(k_set_chunk, dim3(fill_grid(rows)), dim3(256), 0, static_cast<hipStream_t>(stream), t->st,
+                       t->n_chunks, values, static_cast<RowMeta*>(meta), free_list, rows);
     MTGR_LAUNCH_CHECK();
     t->n_chunks += 1;
     return EMB_OK;
@@ -666,15 +750,16 @@ int ht_find_or_insert(emb_table_t* t, const uint64_t* key, const int64_t* n_dev,
     if (rc != EMB_OK) return rc;
     HtView v = t->view();
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const unsigned grid = blocks_for((uint64_t)n_max, kBlock);
+    const unsigned grid = blocks_for((uint64_t)n_max, kBigBlock);
     if (v.count)
-        hipLaunchKernelGGL(k_find_or_insert<true>, dim3(grid), dim3(kBlock), 0, s, v, key, n_dev, n_max, step, row_idx,
-                           inserted);
+        hipLaunchKernelGGL(k_find_or_insert<true>, dim3(grid), dim3(kBigBlock), 0, s, v, key, n_dev, n_max, step,
+                           row_idx, inserted);
     else
-        hipLaunchKernelGGL(k_find_or_insert<false>, dim3(grid), dim3(kBlock), 0, s, v, key, n_dev, n_max, step, row_idx,
-                           inserted);
+        hipLaunchKernelGGL(k_find_or_insert<false>, dim3(grid), dim3(kBigBlock), 0, s, v, key, n_dev, n_max, step,
+                           row_idx, inserted);
     MTGR_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_touch, dim3(grid), dim3(kBlock), 0, s, v, n_dev, n_max, step, row_idx);
+    hipLaunchKernelGGL(k_touch, dim3(blocks_for((uint64_t)n_max, kBlock)), dim3(kBlock), 0, s, v, n_dev, n_max, step,
+                       row_idx);
     MTGR_LAUNCH_CHECK();
     t->issued((uint64_t)n_max);
     return t->snapshot(s);
@@ -707,7 +792,7 @@ int ht_evict(emb_table_t* t, uint32_t now, uint32_t ttl, uint32_t min_freq, uint
     MTGR_LAUNCH_CHECK();
     HtView v = t->view();
     const uint64_t n_slots = 1ull << t->cap_log2;
-    hipLaunchKernelGGL(k_evict, dim3(blocks_for(n_slots, kBlock)), dim3(kBlock), 0, s, v, n_slots, now, ttl, min_freq,
+    hipLaunchKernelGGL(k_evict, dim3(blocks_for(n_slots, kBigBlock)), dim3(kBigBlock), 0, s, v, n_slots, now, ttl, min_freq,
                        grace, evicted_keys, evicted_cap, reinterpret_cast<unsigned long long*>(n_evicted));
     MTGR_LAUNCH_CHECK();
     return t->snapshot(s);
@@ -730,7 +815,7 @@ int ht_rehash(emb_table_t* t, void* new_slots, int new_capacity_log2, void* stre
     hipLaunchKernelGGL(k_rehash, dim3(blocks_for(n_old, kBlock)), dim3(kBlock), 0, s, t->slots, n_old,
                        static_cast<Slot*>(new_slots), n_new / kLineSlots - 1ull, t->st);
     MTGR_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_after_rehash, dim3(1), dim3(64), 0, s, t->st);
+    hipLaunchKernelGGL(k_after_rehash, dim3(1), dim3(kStatStripes), 0, s, t->st);
     MTGR_LAUNCH_CHECK();
     t->slots = static_cast<Slot*>(new_slots);
     t->cap_log2 = new_capacity_log2;
@@ -743,11 +828,11 @@ int ht_rehash(emb_table_t* t, void* new_slots, int new_capacity_log2, void* stre
 int ht_stats(emb_table_t* t, ht_stats_t* out, void* stream) {
     if (!t || !out) return EMB_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    HtState full;
-    HtCounts& h = *reinterpret_cast<HtCounts*>(&full);
-    const size_t head_bytes = offsetof(HtState, pad1);
-    if (hipMemcpyAsync(&full, t->st, head_bytes, hipMemcpyDeviceToHost, s) != hipSuccess) return EMB_ERR_HIP;
+    static_assert(offsetof(HtHead, stat) % 128 == 0, "stat stripes must be line aligned");
+    HtHead full;
+    if (hipMemcpyAsync(&full, t->st, sizeof(HtHead), hipMemcpyDeviceToHost, s) != hipSuccess) return EMB_ERR_HIP;
     if (hipStreamSynchronize(s) != hipSuccess) return EMB_ERR_HIP;
+    const HtCounts h = HtCounts::from(full);
     out->live = h.live;
     out->tombstones = h.tombstones;
     out->capacity = t->slots ? (1ull << t->cap_log2) : 0ull;
@@ -757,11 +842,11 @@ int ht_stats(emb_table_t* t, ht_stats_t* out, void* stream) {
     out->n_rehash = t->n_rehash;
     out->n_chunks = (uint64_t)t->n_chunks;
     out->status = h.status;
-    out->lookups = full.lookups;
-    out->probes = full.probes;
-    out->cas_attempts = full.cas_attempts;
-    out->cas_failures = full.cas_failures;
-    out->alloc_atomics = full.alloc_atomics;
+    out->lookups = h.stat[kStatLookups];
+    out->probes = h.stat[kStatProbes];
+    out->cas_attempts = h.stat[kStatCas];
+    out->cas_failures = h.stat[kStatCasFail];
+    out->alloc_atomics = h.stat[kStatAlloc];
     // exact numbers replace the running upper bounds; older counter copies are obsolete
     t->adopt(h, 0, t->seq);
     t->min_valid_seq = t->seq + 1;
