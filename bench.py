@@ -177,11 +177,14 @@ def main() -> int:
     ab = algorithmic_bytes(int(n_avg), int(u_avg), int(u_new), v_row, v_grad, dim)
     achieved = ab["total"] / (ms_per_step * 1e-3) / 1e9
 
-    # dominant kernel: the expand (one kernel = one phase): its own algorithmic bytes over its own time
+    # dominant kernel: the expand (one kernel = one phase): its own algorithmic bytes over its own time,
+    # both measured here; `traffic` = HBM bytes per launch from the committed counter summary (FETCH_SIZE and
+    # WRITE_SIZE runs of this same command, scaled by a 1 GiB copy), valid for the default configuration only
     dom = "expand"
     dom_gbps = ab[dom] / (phase_ms[dom] * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "k_copy_rows (emb_expand)", "achieved": round(dom_gbps, 1),
-                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+    roofline = {"bound": "hbm", "kernel": "k_copy_rows<16,false,true> (emb_expand)", "achieved": round(dom_gbps, 1),
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBPS, 4),
+                "traffic": profiled_traffic("k_copy_rows<16, false, true>") if args.config == 2 else None,
                 "bytes_per_launch": ab[dom], "avg_ms": round(phase_ms[dom], 4)}
 
     result = {
@@ -234,6 +237,19 @@ def main() -> int:
     print(json.dumps(result), flush=True)
     table.close()
     return 0
+
+
+def profiled_traffic(kernel: str):
+    """HBM bytes per dispatch of `kernel` from profiles/hbm_traffic_config2_step.txt (None if absent)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_config2_step.txt")
+    try:
+        for line in open(path):
+            parts = [p.strip() for p in line.split("|")]
+            if len(parts) == 3 and parts[0] == "traffic_bytes_per_dispatch" and parts[1] == kernel:
+                return int(float(parts[2]))
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(w, batch0, tag_bits, dim, dtype, n_keys) -> dict:
