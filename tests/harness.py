@@ -97,3 +97,81 @@ def run_step(pair: Pair, buf: StepBuffers, x: np.ndarray, field_off: np.ndarray,
     g = buf.reduced[:U].cpu().numpy()
     assert close_reduce(g, og.astype(np.float64), osabs, RTOL_F32), "reduced gradients"
     return n, U
+
+
+def small_int_rows(pos: np.ndarray, dim: int, seed: int) -> np.ndarray:
+    """Rows `pos` of workloads.small_int_grads(n, dim, seed) without materialising the whole matrix
+    (same integer formula, evaluated with numpy on the requested rows only)."""
+    i = pos.astype(np.int64)[:, None]
+    j = np.arange(dim, dtype=np.int64)[None, :]
+    h = (i * 2654435761 + j * 40503 + (seed & 0xFFFF) * 97) & 0x7FFFFFFF
+    h = ((h ^ (h >> 13)) * 1274126177) & 0x7FFFFFFF
+    return ((h >> 9) % 17 - 8).astype(np.float32)
+
+
+def tracked_subset(hot_keys: np.ndarray):
+    """Predicate choosing the keys the checker mirrors at full size: a fixed 1/512 of the key space
+    (by a multiplicative hash of the key, so the choice is the same in every step) plus a given set
+    of hot keys.  Because membership depends on the key alone, the checker's table is an exact mirror
+    of the device table restricted to these keys, across any number of steps."""
+    hot = np.sort(np.asarray(hot_keys, dtype=np.uint64))
+
+    def tracked(keys: np.ndarray) -> np.ndarray:
+        h = (keys * np.uint64(0x9E3779B97F4A7C15)) >> np.uint64(55)
+        return (h == 0) | np.isin(keys, hot)
+    return tracked
+
+
+def run_step_sampled(pair: Pair, buf: StepBuffers, x, field_off, field_tag, tag_bits, step, lr, eps, grad_seed,
+                     is_prepopulated, tracked, rng_seed=0):
+    """One full-size forward+backward on the GPU; the checker does the integer work in full (tag, dedup)
+    and the row work on the tracked subset of distinct keys: insert flags, gathered rows, expanded rows,
+    exact integer-valued reduced gradients, updated rows."""
+    from workloads import small_int_grads
+    n = len(x)
+    okey, oerr = oracle.tag_keys(x, field_off, field_tag, tag_bits)
+    ouniq, oinv, ocnt = oracle.dedup(okey)
+    U = len(ouniq)
+    rng = np.random.default_rng(rng_seed + step)
+    pick = np.flatnonzero(tracked(ouniq))
+    skeys = ouniq[pick]
+    pre = is_prepopulated(skeys)
+    pair.orc.prepopulate(skeys[pre])
+    # ---- HIP path, forward
+    dx, doff, dtag = dev_keys(x), torch.from_numpy(field_off).cuda(), torch.from_numpy(field_tag).cuda()
+    forward(pair.gpu, buf, dx, doff, dtag, tag_bits, step)
+    assert int(buf.n_unique.item()) == U and int(buf.err_count.item()) == oerr
+    assert np.array_equal(host_keys(buf.uniq[:U]), ouniq), "unique keys"
+    assert np.array_equal(buf.inverse[:n].cpu().numpy(), oinv), "inverse"
+    assert np.array_equal(buf.counts[:U].cpu().numpy(), ocnt), "counts"
+    ins = buf.inserted[:U].cpu().numpy()
+    oins = pair.orc.find_or_insert(skeys, step)
+    assert np.array_equal(ins[pick], oins), "inserted flags (sample)"
+    dpick = torch.from_numpy(pick).cuda()
+    oE_u = pair.orc.lookup(skeys)
+    _, _, oacc_before, _, _ = pair.orc.peek(skeys)
+    E_u = buf.uniq_rows[dpick].float().cpu().numpy()
+    never = oacc_before == 0
+    assert np.array_equal(E_u[never], oE_u[never]), "rows never updated must be bit-identical"
+    assert close_rows(E_u, oE_u.astype(np.float64), lr, pair.rtol), "gathered rows (sample)"
+    pos = rng.integers(0, n, size=20000)
+    E = buf.out[torch.from_numpy(pos).cuda()].cpu()
+    assert torch.equal(E, buf.uniq_rows[torch.from_numpy(oinv[pos].astype(np.int64)).cuda()].cpu()), "expand (sample)"
+    # ---- backward with integer-valued gradients: exactly one correct fp32 sum per element
+    dG = small_int_grads(n, pair.dim, grad_seed, "cuda")
+    if pair.dtype != B.F32:
+        dG = dG.to(torch.bfloat16)
+    backward(pair.gpu, buf, dG, n, lr, eps)
+    order = np.argsort(oinv, kind="stable")
+    seg_off = np.concatenate([[0], np.cumsum(ocnt)])
+    og = np.zeros((len(pick), pair.dim), dtype=np.float32)
+    for s, u in enumerate(pick):
+        p = order[seg_off[u]:seg_off[u + 1]]
+        og[s] = small_int_rows(p, pair.dim, grad_seed).astype(np.float64).sum(0).astype(np.float32)
+    g = buf.reduced[dpick].cpu().numpy()
+    assert np.array_equal(g, og), "reduced gradients (sample, exact)"
+    pair.orc.apply_adagrad(skeys, og, lr, eps)
+    rows_after = torch.empty((len(pick), pair.dim), dtype=buf.uniq_rows.dtype, device="cuda")
+    pair.gpu.gather(buf.row_idx[dpick].contiguous(), None, len(pick), rows_after)
+    assert close_rows(rows_after.float().cpu().numpy(), pair.orc.lookup(skeys).astype(np.float64), lr, pair.rtol), "updated rows"
+    return n, U, int(ins.sum())

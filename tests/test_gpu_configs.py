@@ -131,14 +131,16 @@ def test_config2_prepopulated_scaled():
     pair.gpu.close()
 
 
-def test_config4_insert_delete_stress_scaled():
-    w = make_config(4, batch=8, vocab_scale=0.01, len_lo=128)      # 4k IDs per step, 4k keys per field
-    w.ttl, w.min_freq, w.grace, w.evict_every = 25, 3, 6, 10
+def test_config4_insert_delete_stress_1000_steps_scaled():
+    """All 1000 streaming steps with the configuration's own eviction policy (ttl 200, freq < 3 after a
+    grace of 20 steps, every 20 steps, load-factor limit 0.85), at a batch the checker keeps up with."""
+    w = make_config(4, batch=8, vocab_scale=0.01, len_lo=128)       # 4096 IDs per step, 4000 keys per field at start
+    assert (w.ttl, w.min_freq, w.grace, w.evict_every, w.max_load_factor) == (200, 3, 20, 20, 0.85)
     merged, n_merged, tag_bits, sig = _plan(w)
-    pair = Pair(64, 0, capacity_log2=12, chunk_rows_log2=11, max_load_factor=0.85)
+    pair = Pair(64, 0, capacity_log2=12, chunk_rows_log2=12, max_load_factor=0.85)
     buf = StepBuffers(8 * 128 * 4, 64)
-    lf_seen, evicted_total = [], 0
-    for step in range(90):
+    lf_seen, evicted_total, caps = [], 0, set()
+    for step in range(w.steps):
         b = w.next_step(step)
         x, off, tags, _ = merged_inputs(w.features, b.ids, merged, 0)
         G = _grads(w, step, len(x), 64, 0, 0)
@@ -146,16 +148,17 @@ def test_config4_insert_delete_stress_scaled():
         if (step + 1) % w.evict_every == 0:
             ev, n_ev = pair.gpu.evict(step, w.ttl, w.min_freq, w.grace)
             oev = pair.orc.evict(step, w.ttl, w.min_freq, w.grace)
-            assert np.array_equal(np.sort(host_keys(ev)), oev)
+            assert np.array_equal(np.sort(host_keys(ev)), oev)          # eviction set, compared as a set
             evicted_total += n_ev
-        st = pair.gpu.stats()
-        lf_seen.append((st["live"] + st["tombstones"]) / st["capacity"])
-        assert st["status"] == 0 and st["live"] == len(pair.orc)
-        if step % 15 == 14:
+            st = pair.gpu.stats()
+            lf_seen.append((st["live"] + st["tombstones"]) / st["capacity"])
+            caps.add(st["capacity"])
+            assert st["status"] == 0 and st["live"] == len(pair.orc)
+        if step % 100 == 99:
             pair.compare_tables(w.lr, exact_rows_when_untouched=True)
     pair.compare_tables(w.lr)
     st = pair.gpu.stats()
-    assert st["n_rehash"] >= 2 and evicted_total > 1000 and max(lf_seen) <= 0.85 + 1e-9
+    assert st["n_rehash"] >= 3 and len(caps) >= 2 and evicted_total > 50000 and max(lf_seen) <= 0.85 + 1e-9
     assert st["rows_free"] + st["live"] == st["rows_used"]          # every allocated row is live or on the free list
     pair.gpu.close()
 
