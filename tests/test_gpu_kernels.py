@@ -200,6 +200,12 @@ def test_expand(dim, dtype, n, u):
     B.emb_expand(d_rows, torch.from_numpy(inverse).cuda(), n, dim, dtype, out)
     ref = oracle.expand(d_rows.float().cpu().numpy(), inverse)
     assert np.array_equal(out.float().cpu().numpy(), ref)
+    # the sorted-order variant must give the same matrix: perm = positions by (index, position), seg_of = index there
+    perm = np.argsort(inverse, kind="stable").astype(np.int32)
+    seg_of = inverse[perm]
+    out2 = torch.full((n, dim), 7.0, dtype=tdt, device="cuda")
+    B.emb_expand_sorted(d_rows, torch.from_numpy(seg_of).cuda(), torch.from_numpy(perm).cuda(), n, dim, dtype, out2)
+    assert np.array_equal(out2.float().cpu().numpy(), ref)
 
 
 # ------------------------------------------------------------------------------------------ reduce
