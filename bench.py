@@ -218,6 +218,31 @@ def main() -> int:
         pc["lines_per_lookup"] = round(pc["probes"] / max(pc["lookups"], 1), 4)
         result["probe_counters_timed_region"] = pc
 
+    # ---- the same step with the fused lookup (no distinct-row matrix), as an extra line
+    def one_step_fused(step: int):
+        dx, doff, dtag, n, _ = batches[step % len(batches)]
+        B.emb_tag_keys(dx, doff, dtag, tag_bits, buf.key, buf.err_count)
+        B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, None, buf.perm, None, buf.seg_of, buf.n_unique, buf.dedup_ws)
+        table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted)
+        B.ht_gather_expand_sorted(table.h, buf.row_idx, buf.seg_of, buf.perm, n, buf.out)
+        B.grad_segment_reduce(grad, dtype, buf.seg_of, buf.perm, n, dim, buf.reduced, buf.reduce_ws)
+        table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps)
+        return n
+
+    base = args.warmup + args.steps + len(batches)
+    for s in range(2):
+        one_step_fused(base + s)
+    torch.cuda.synchronize()
+    t_f = time.perf_counter()
+    ids_f = 0
+    for k in range(args.steps):
+        ids_f += one_step_fused(base + 2 + k)
+    torch.cuda.synchronize()
+    wall_f = time.perf_counter() - t_f
+    result["fused_lookup"] = {"ms_per_step": round(wall_f * 1e3 / args.steps, 4), "ids_per_sec": round(ids_f / wall_f, 1),
+                              "note": "ht_gather_expand_sorted replaces ht_gather + emb_expand_sorted: same result, "
+                                      "2 x rowbytes x unique fewer bytes moved"}
+
     if args.copy_probe_mib > 0:
         nbytes = args.copy_probe_mib << 20
         src = torch.empty(nbytes, dtype=torch.uint8, device=dev).fill_(1)

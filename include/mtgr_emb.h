@@ -218,6 +218,15 @@ int grad_segment_reduce(const void* grad, int grad_dtype, const int32_t* seg_of,
 int ht_apply_adagrad(emb_table_t* t, const int32_t* row_idx, const float* reduced, const int64_t* n_dev,
                      int64_t n_max, float lr, float eps, void* stream);
 
+/* ------------------------------------------------------------------ fused form (no communication between lookup and expand) */
+
+/* ht_gather followed by emb_expand_sorted without materialising the distinct rows:
+ * out[perm[j],:] = values[row_idx[seg_of[j]],:] (zeros where the row index is -1).  Same result,
+ * 2 x rowbytes x n_unique fewer bytes moved.  The unfused calls remain the form to use when the
+ * distinct rows travel between devices (Sec. 3.3). */
+int ht_gather_expand_sorted(emb_table_t* t, const int32_t* row_idx, const int32_t* seg_of, const int32_t* perm,
+                            int64_t n, void* out, void* stream);
+
 /* ------------------------------------------------------------------ maintenance */
 
 /* Delete every key that was not touched for `ttl` steps (rule active when ttl > 0) or that was

@@ -48,7 +48,7 @@ EXPORTS = [
     "emb_table_create", "emb_table_destroy", "ht_set_key_storage", "ht_add_chunk", "ht_plan", "ht_rehash",
     "ht_stats", "emb_tag_keys", "emb_dedup_workspace_bytes", "emb_dedup", "ht_find_or_insert", "ht_find",
     "ht_gather", "emb_expand", "emb_expand_sorted", "grad_segment_reduce_workspace_bytes", "grad_segment_reduce",
-    "ht_apply_adagrad", "ht_evict", "ht_export",
+    "ht_apply_adagrad", "ht_gather_expand_sorted", "ht_evict", "ht_export",
 ]
 
 
@@ -85,6 +85,7 @@ def load():
         "grad_segment_reduce_workspace_bytes": (C.c_size_t, [i64, i32]),
         "grad_segment_reduce": (C.c_int, [vp, i32, vp, vp, i64, i32, vp, vp, C.c_size_t, vp]),
         "ht_apply_adagrad": (C.c_int, [vp, vp, vp, vp, i64, f32, f32, vp]),
+        "ht_gather_expand_sorted": (C.c_int, [vp, vp, vp, vp, i64, vp, vp]),
         "ht_evict": (C.c_int, [vp, u32, u32, u32, u32, vp, i64, vp, vp]),
         "ht_export": (C.c_int, [vp, vp, vp, vp, vp, vp, i64, vp, vp]),
     }
@@ -235,6 +236,11 @@ def grad_segment_reduce(grad, grad_dtype: int, seg_of, perm, n: int, dim: int, r
 def ht_apply_adagrad(h, row_idx, reduced, n_dev, n_max: int, lr: float, eps: float, stream=None) -> None:
     _check(load().ht_apply_adagrad(h, _ptr(row_idx), _ptr(reduced), _ptr(n_dev), n_max, lr, eps, _stream(stream)),
            "ht_apply_adagrad")
+
+
+def ht_gather_expand_sorted(h, row_idx, seg_of, perm, n: int, out, stream=None) -> None:
+    _check(load().ht_gather_expand_sorted(h, _ptr(row_idx), _ptr(seg_of), _ptr(perm), n, _ptr(out), _stream(stream)),
+           "ht_gather_expand_sorted")
 
 
 def ht_evict(h, now: int, ttl: int, min_freq: int, grace: int, evicted_keys, n_evicted, stream=None) -> None:

@@ -77,6 +77,7 @@ __device__ inline void copy_rows_body(const HtView& v, const char* __restrict__ 
 template <int LPR, bool SRC_TABLE, bool NT_STORE, bool DST_IDX>
 __global__ __launch_bounds__(kBlock) void k_copy_rows(HtView v, const char* __restrict__ src_base,
                                                       const int32_t* __restrict__ index,
+                                                      const int32_t* __restrict__ via,
                                                       const int32_t* __restrict__ dst_index, const int64_t* n_dev,
                                                       int64_t n_max, int row_bytes, char* __restrict__ out) {
     const int64_t n = read_count(n_dev, n_max);
@@ -84,7 +85,8 @@ __global__ __launch_bounds__(kBlock) void k_copy_rows(HtView v, const char* __re
     const int64_t wave_base = (int64_t)blockIdx.x * kBlock + (threadIdx.x & ~(kWave - 1));
     if (wave_base >= n) return;
     const int vecs = row_bytes / 16;
-    const int my_index = (wave_base + lane < n) ? index[wave_base + lane] : -1;
+    int my_index = (wave_base + lane < n) ? index[wave_base + lane] : -1;
+    if (via && my_index >= 0) my_index = via[my_index]; // source row = via[index[j]] (fused gather + expand)
     const int my_dst = (DST_IDX && wave_base + lane < n) ? dst_index[wave_base + lane] : 0;
     const int rows_here = (int)((n - wave_base) < kWave ? (n - wave_base) : kWave);
     char* out_wave = DST_IDX ? out : out + (size_t)wave_base * (size_t)row_bytes;
@@ -97,13 +99,13 @@ __global__ __launch_bounds__(kBlock) void k_copy_rows(HtView v, const char* __re
 }
 
 template <bool SRC_TABLE, bool NT, bool DST_IDX>
-int launch_copy_rows(const HtView& v, const char* src, const int32_t* index, const int32_t* dst_index,
+int launch_copy_rows(const HtView& v, const char* src, const int32_t* index, const int32_t* via, const int32_t* dst_index,
                      const int64_t* n_dev, int64_t n_max, int row_bytes, char* out, hipStream_t s) {
     const int vecs = row_bytes / 16;
     const unsigned grid = (unsigned)((n_max + kBlock - 1) / kBlock);
 #define MTGR_CASE(L)                                                                                              \
-    hipLaunchKernelGGL((k_copy_rows<L, SRC_TABLE, NT, DST_IDX>), dim3(grid), dim3(kBlock), 0, s, v, src, index, dst_index, \
-                       n_dev, n_max, row_bytes, out)
+    hipLaunchKernelGGL((k_copy_rows<L, SRC_TABLE, NT, DST_IDX>), dim3(grid), dim3(kBlock), 0, s, v, src, index, via,      \
+                       dst_index, n_dev, n_max, row_bytes, out)
     if (vecs <= 1) MTGR_CASE(1);
     else if (vecs <= 2) MTGR_CASE(2);
     else if (vecs <= 4) MTGR_CASE(4);
@@ -158,6 +160,40 @@ __device__ inline void acc_store(float* row, int sub, const Acc<FPL>& a) {
               __float_as_uint(a.f[4 * q + 3])};
         st16(row + sub * FPL + 4 * q, o);
     }
+}
+
+// Row-wise Adagrad arithmetic, spelled with explicit roundings so that every kernel that applies
+// it produces the same bits: acc' = fma(ss, 1/D, acc); scale = lr / (sqrt(acc') + eps);
+// w' = fma(-scale, g, w).
+__device__ inline float adagrad_acc(float acc_old, float ss, float inv_d) { return __fmaf_rn(ss, inv_d, acc_old); }
+__device__ inline float adagrad_scale(float acc_new, float lr, float eps) {
+    return __fdiv_rn(lr, __fadd_rn(__fsqrt_rn(acc_new), eps));
+}
+__device__ inline float adagrad_w(float w, float g, float scale) { return __fmaf_rn(-scale, g, w); }
+// Sum of squares of a row in a fixed tree that does not depend on how many elements a lane holds:
+// fma chains over aligned quads of elements, then pairwise sums of neighbouring quads, octets, ...
+// (in-lane first, then xor-shuffles with growing distance).
+template <int N>
+__device__ inline float sumsq_lane(const float* g) {
+    float q[N / 4];
+#pragma unroll
+    for (int i = 0; i < N / 4; ++i) {
+        float s = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s = __fmaf_rn(g[4 * i + e], g[4 * i + e], s);
+        q[i] = s;
+    }
+#pragma unroll
+    for (int w = 1; w < N / 4; w <<= 1)
+#pragma unroll
+        for (int i = 0; i + w < N / 4; i += 2 * w) q[i] = __fadd_rn(q[i], q[i + w]);
+    return q[0];
+}
+template <int LPR>
+__device__ inline float sumsq_group(float ss) {
+#pragma unroll
+    for (int o = 1; o < LPR; o <<= 1) ss = __fadd_rn(ss, __shfl_xor(ss, o, kWave));
+    return ss;
 }
 
 struct LevelIn {
@@ -334,7 +370,7 @@ __global__ __launch_bounds__(kBlock) void k_adagrad(HtView v, const int32_t* __r
     const bool lane_on = sub * kF < v.dim;
     const int my_index = (wave_base + lane < n) ? row_idx[wave_base + lane] : -1;
     const int rows_here = (int)((n - wave_base) < kWave ? (n - wave_base) : kWave);
-    const float inv_d = 1.0f / (float)v.dim;
+    const float inv_d = __fdiv_rn(1.0f, (float)v.dim);
 #pragma unroll 1
     for (int r0 = 0; r0 < kWave; r0 += kGroups * 2) {
         if (r0 >= rows_here) break;
@@ -365,29 +401,25 @@ __global__ __launch_bounds__(kBlock) void k_adagrad(HtView v, const int32_t* __r
         }
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            float ss = 0.0f;
-#pragma unroll
-            for (int e = 0; e < kF; ++e) ss = fmaf(gv[u][e], gv[u][e], ss);
-#pragma unroll
-            for (int o = LPR / 2; o > 0; o >>= 1) ss += __shfl_xor(ss, o, kWave);
+            const float ss = sumsq_group<LPR>(sumsq_lane<kF>(gv[u]));
             if (!on[u]) continue;
             const uint32_t row = (uint32_t)idx[u];
             float* accp = &v.st->meta[row >> v.chunk_log2][row & ((1u << v.chunk_log2) - 1u)].acc;
-            const float acc = *accp + ss * inv_d;
-            const float scale = lr / (sqrtf(acc) + eps);
+            const float acc = adagrad_acc(*accp, ss, inv_d);
+            const float scale = adagrad_scale(acc, lr, eps);
             if (lane_on) {
                 char* wp = const_cast<char*>(chunk_row_cptr(v, row)) + sub * 16;
                 V16 o;
                 if (BF16) {
-                    o.x = pack_bf16(bf16lo(wv[u].x) - scale * gv[u][0], bf16hi(wv[u].x) - scale * gv[u][1]);
-                    o.y = pack_bf16(bf16lo(wv[u].y) - scale * gv[u][2], bf16hi(wv[u].y) - scale * gv[u][3]);
-                    o.z = pack_bf16(bf16lo(wv[u].z) - scale * gv[u][4], bf16hi(wv[u].z) - scale * gv[u][5]);
-                    o.w = pack_bf16(bf16lo(wv[u].w) - scale * gv[u][6], bf16hi(wv[u].w) - scale * gv[u][7]);
+                    o.x = pack_bf16(adagrad_w(bf16lo(wv[u].x), gv[u][0], scale), adagrad_w(bf16hi(wv[u].x), gv[u][1], scale));
+                    o.y = pack_bf16(adagrad_w(bf16lo(wv[u].y), gv[u][2], scale), adagrad_w(bf16hi(wv[u].y), gv[u][3], scale));
+                    o.z = pack_bf16(adagrad_w(bf16lo(wv[u].z), gv[u][4], scale), adagrad_w(bf16hi(wv[u].z), gv[u][5], scale));
+                    o.w = pack_bf16(adagrad_w(bf16lo(wv[u].w), gv[u][6], scale), adagrad_w(bf16hi(wv[u].w), gv[u][7], scale));
                 } else {
-                    o.x = __float_as_uint(__uint_as_float(wv[u].x) - scale * gv[u][0]);
-                    o.y = __float_as_uint(__uint_as_float(wv[u].y) - scale * gv[u][1]);
-                    o.z = __float_as_uint(__uint_as_float(wv[u].z) - scale * gv[u][2]);
-                    o.w = __float_as_uint(__uint_as_float(wv[u].w) - scale * gv[u][3]);
+                    o.x = __float_as_uint(adagrad_w(__uint_as_float(wv[u].x), gv[u][0], scale));
+                    o.y = __float_as_uint(adagrad_w(__uint_as_float(wv[u].y), gv[u][1], scale));
+                    o.z = __float_as_uint(adagrad_w(__uint_as_float(wv[u].z), gv[u][2], scale));
+                    o.w = __float_as_uint(adagrad_w(__uint_as_float(wv[u].w), gv[u][3], scale));
                 }
                 st16(wp, o);
             }
@@ -405,7 +437,7 @@ int ht_gather(emb_table_t* t, const int32_t* row_idx, const int64_t* n_dev, int6
     if (n_max == 0) return EMB_OK;
     if (!row_idx || !out || (reinterpret_cast<uintptr_t>(out) & 15)) return EMB_ERR_INVALID_ARG;
     if (t->n_chunks == 0) return EMB_ERR_NO_STORAGE;
-    return launch_copy_rows<true, false, false>(t->view(), nullptr, row_idx, nullptr, n_dev, n_max, t->row_bytes,
+    return launch_copy_rows<true, false, false>(t->view(), nullptr, row_idx, nullptr, nullptr, n_dev, n_max, t->row_bytes,
                                                 static_cast<char*>(out), static_cast<hipStream_t>(stream));
 }
 
@@ -417,7 +449,7 @@ int emb_expand(const void* uniq_rows, const int32_t* inverse, int64_t n, int dim
     if (!uniq_rows || !inverse || !out) return EMB_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(uniq_rows) & 15) || (reinterpret_cast<uintptr_t>(out) & 15)) return EMB_ERR_INVALID_ARG;
     HtView none{};
-    return launch_copy_rows<false, true, false>(none, static_cast<const char*>(uniq_rows), inverse, nullptr, nullptr, n,
+    return launch_copy_rows<false, true, false>(none, static_cast<const char*>(uniq_rows), inverse, nullptr, nullptr, nullptr, n,
                                                 row_bytes, static_cast<char*>(out), static_cast<hipStream_t>(stream));
 }
 
@@ -430,8 +462,18 @@ int emb_expand_sorted(const void* uniq_rows, const int32_t* seg_of, const int32_
     if (!uniq_rows || !seg_of || !perm || !out) return EMB_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(uniq_rows) & 15) || (reinterpret_cast<uintptr_t>(out) & 15)) return EMB_ERR_INVALID_ARG;
     HtView none{};
-    return launch_copy_rows<false, true, true>(none, static_cast<const char*>(uniq_rows), seg_of, perm, nullptr, n,
+    return launch_copy_rows<false, true, true>(none, static_cast<const char*>(uniq_rows), seg_of, nullptr, perm, nullptr, n,
                                                row_bytes, static_cast<char*>(out), static_cast<hipStream_t>(stream));
+}
+
+int ht_gather_expand_sorted(emb_table_t* t, const int32_t* row_idx, const int32_t* seg_of, const int32_t* perm, int64_t n,
+                            void* out, void* stream) {
+    if (!t || n < 0 || n > 0x7FFFFFFFll) return EMB_ERR_INVALID_ARG;
+    if (n == 0) return EMB_OK;
+    if (!row_idx || !seg_of || !perm || !out || (reinterpret_cast<uintptr_t>(out) & 15)) return EMB_ERR_INVALID_ARG;
+    if (t->n_chunks == 0) return EMB_ERR_NO_STORAGE;
+    return launch_copy_rows<true, true, true>(t->view(), nullptr, seg_of, row_idx, perm, nullptr, n, t->row_bytes,
+                                              static_cast<char*>(out), static_cast<hipStream_t>(stream));
 }
 
 size_t grad_segment_reduce_workspace_bytes(int64_t n, int dim) {

@@ -176,3 +176,15 @@ def backward(table: EmbeddingTable, buf: StepBuffers, grad, n: int, lr: float, e
     """segment-reduce the upstream gradient per distinct key, then row-wise Adagrad."""
     B.grad_segment_reduce(grad, table.dtype, buf.seg_of, buf.perm, n, table.dim, buf.reduced, buf.reduce_ws)
     table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, lr, eps)
+
+
+def forward_fused(table: EmbeddingTable, buf: StepBuffers, x, field_off, field_tag, tag_bits: int, step: int) -> None:
+    """tag -> dedup -> find-or-insert -> gather+expand in one kernel; results in buf.out[:n]
+    (buf.uniq_rows is not written)."""
+    n = x.numel()
+    B.emb_tag_keys(x, field_off, field_tag, tag_bits, buf.key, buf.err_count)
+    B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, buf.counts, buf.perm, buf.seg_off, buf.seg_of, buf.n_unique,
+                buf.dedup_ws)
+    table.find_or_insert(buf.uniq, buf.n_unique, n, step, buf.row_idx, buf.inserted)
+    B.ht_gather_expand_sorted(table.h, buf.row_idx, buf.seg_of, buf.perm, n, buf.out)
+

@@ -366,3 +366,40 @@ def test_full_table_up_to_the_load_factor_limit():
     st2 = t.stats()
     assert (st2["probes"] - st["probes"]) / n < 2.5          # lines inspected per successful lookup at LF 0.75
     t.close()
+
+
+# ------------------------------------------------------------------------------------------ fused form
+@pytest.mark.parametrize("dim,dtype", [(64, 0), (32, 0), (128, 0), (128, 1), (16, 0), (8, 1)])
+def test_fused_gather_expand_equals_the_two_calls(dim, dtype):
+    """gather+expand in one kernel is bit-identical to ht_gather followed by emb_expand(_sorted), over
+    several steps with updates in between, and agrees with the checker's direct lookup."""
+    from paper_2505_12663_amd import forward, backward, forward_fused
+    rtol = RTOL_F32 if dtype == 0 else RTOL_BF16
+    n = 64 * 64 * 3 + 77
+    raw = _zipf_keys(n, 2500, 33) & np.uint64((1 << 40) - 1)
+    off, tags = np.array([0, n], dtype=np.int64), np.array([0], dtype=np.uint8)
+    dx, doff, dtag = dev_keys(raw), torch.from_numpy(off).cuda(), torch.from_numpy(tags).cuda()
+    ta = EmbeddingTable(dim, dtype, capacity_log2=14, chunk_rows_log2=12)
+    tb = EmbeddingTable(dim, dtype, capacity_log2=14, chunk_rows_log2=12)
+    ot = oracle.Table(dim, dtype)
+    ba, bb = StepBuffers(n, dim, dtype), StepBuffers(n, dim, dtype)
+    okey, _ = oracle.tag_keys(raw, off, tags, 1)
+    ou, oi, oc = oracle.dedup(okey)
+    for step in range(3):
+        forward(ta, ba, dx, doff, dtag, 1, step)
+        forward_fused(tb, bb, dx, doff, dtag, 1, step)
+        assert torch.equal(ba.out[:n], bb.out[:n])                       # same bits, with and without E_u
+        ot.find_or_insert(ou, step)
+        oE = oracle.expand(ot.lookup(ou), oi)
+        assert close_rows(bb.out[:n].float().cpu().numpy(), oE.astype(np.float64), 0.01, rtol)
+        if step == 0:
+            assert np.array_equal(bb.out[:n].float().cpu().numpy(), oE)  # before any update: bit-exact
+        G = normal_grads(9, step, n, dim)
+        if dtype == 1:
+            G = torch.from_numpy(G).to(torch.bfloat16).float().numpy()
+        dG = torch.from_numpy(G).cuda() if dtype == 0 else torch.from_numpy(G).cuda().to(torch.bfloat16)
+        backward(ta, ba, dG, n, 0.01, 1e-8)
+        backward(tb, bb, dG, n, 0.01, 1e-8)
+        ot.apply_adagrad(ou, oracle.segment_reduce(G, oi, len(ou)), 0.01, 1e-8)
+    ta.close()
+    tb.close()
