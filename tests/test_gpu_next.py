@@ -1,0 +1,100 @@
+"""Compositions of the entry points that the paper describes around the single-device path (needs an MI355X):
+two-stage deduplication over the ID lists of several emulated peers (Sec. 3.3) and sparse gradient
+accumulation over micro-batches (App. C), both checked against the CPU checker's plain definitions."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from workloads import make_config, merged_inputs, normal_grads
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from paper_2505_12663_amd import binding as B
+    from paper_2505_12663_amd import EmbeddingTable, StepBuffers
+    from harness import dev_keys, host_keys, close_reduce, close_rows, RTOL_F32
+
+
+def _dedup(buf, keys_dev, n):
+    B.emb_dedup(keys_dev, n, buf.uniq, buf.inverse, buf.counts, buf.perm, buf.seg_off, buf.seg_of, buf.n_unique, buf.dedup_ws)
+    return int(buf.n_unique.item())
+
+
+def test_two_stage_dedup_over_emulated_peers():
+    """Each of P peers deduplicates its own IDs (stage 1) and sends the distinct ones; the owner
+    deduplicates what it received (stage 2), looks the distinct keys up once, returns one row per
+    received ID, and every peer expands.  The result must equal looking every ID up directly."""
+    P, dim = 4, 32
+    w = make_config(1, batch=128)
+    b = w.next_step(0)
+    x, off, tags, _ = merged_inputs(w.features, b.ids, [0], 0)
+    key, _ = oracle.tag_keys(x, off, tags, 1)
+    parts = np.array_split(key, P)
+    table, ot = EmbeddingTable(dim, 0, capacity_log2=16, chunk_rows_log2=13), oracle.Table(dim)
+    # stage 1 on every peer
+    peer = []
+    for p in range(P):
+        n = len(parts[p])
+        buf = StepBuffers(n, dim, with_grad=False)
+        U = _dedup(buf, dev_keys(parts[p]), n)
+        ou, oi, _ = oracle.dedup(parts[p])
+        assert np.array_equal(host_keys(buf.uniq[:U]), ou) and np.array_equal(buf.inverse[:n].cpu().numpy(), oi)
+        peer.append((buf, n, U))
+    # "all-to-all" of IDs: the owner receives the concatenation of the peers' distinct keys
+    received = torch.cat([buf.uniq[:U] for buf, n, U in peer])
+    R = received.numel()
+    own = StepBuffers(R, dim, with_grad=False)
+    U2 = _dedup(own, received, R)                                   # stage 2: duplicates across peers
+    assert U2 == len(np.unique(key)) and U2 < R
+    table.find_or_insert(own.uniq, own.n_unique, R, 0, own.row_idx)
+    table.gather(own.row_idx, own.n_unique, R, own.uniq_rows)
+    B.emb_expand(own.uniq_rows, own.inverse, R, dim, 0, own.out)     # one row per received ID, in received order
+    # "all-to-all" of rows back, then every peer expands with its stage-1 inverse
+    outs, lo = [], 0
+    for buf, n, U in peer:
+        rows_for_peer = own.out[lo:lo + U].contiguous()
+        lo += U
+        B.emb_expand(rows_for_peer, buf.inverse, n, dim, 0, buf.out)
+        outs.append(buf.out[:n])
+    E = torch.cat(outs).cpu().numpy()
+    assert np.array_equal(E, ot.direct_lookup(key, 0))              # dedup only removes repeated transmission
+    assert table.stats()["live"] == len(ot) == U2
+    table.close()
+
+
+def test_sparse_gradient_accumulation_over_micro_batches():
+    """Gradients of identical IDs across K micro-batches are accumulated and applied once (App. C):
+    recorded (ID, gradient) pairs are concatenated, reduced per ID, and only activated rows are updated."""
+    K, dim = 3, 64
+    w = make_config(1, batch=96)
+    table, ot = EmbeddingTable(dim, 0, capacity_log2=16, chunk_rows_log2=13), oracle.Table(dim)
+    keys, grads = [], []
+    for k in range(K):                                   # forward passes of the micro-batches: lookups only
+        b = w.next_step(k)
+        x, off, tags, _ = merged_inputs(w.features, b.ids, [0], 0)
+        key, _ = oracle.tag_keys(x, off, tags, 1)
+        n = len(key)
+        buf = StepBuffers(n, dim, with_grad=False)
+        U = _dedup(buf, dev_keys(key), n)
+        table.find_or_insert(buf.uniq, buf.n_unique, n, k, buf.row_idx)
+        ot.find_or_insert(np.unique(key), k)
+        keys.append(key)
+        grads.append(normal_grads(77, k, n, dim))
+    allk, allg = np.concatenate(keys), np.concatenate(grads)
+    n = len(allk)
+    buf = StepBuffers(n, dim)
+    U = _dedup(buf, dev_keys(allk), n)                   # merge the recorded IDs
+    ou, oi, _ = oracle.dedup(allk)
+    B.grad_segment_reduce(torch.from_numpy(allg).cuda(), 0, buf.seg_of, buf.perm, n, dim, buf.reduced, buf.reduce_ws)
+    og = oracle.segment_reduce(allg, oi, len(ou))
+    sabs = oracle.segment_reduce(np.abs(allg), oi, len(ou)).astype(np.float64)
+    assert close_reduce(buf.reduced[:U].cpu().numpy(), og.astype(np.float64), sabs, RTOL_F32)
+    table.find(buf.uniq, buf.n_unique, n, buf.row_idx)   # rows of the activated keys (no touch: not a lookup step)
+    table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, 0.01, 1e-8)
+    ot.apply_adagrad(ou, og, 0.01, 1e-8)
+    gk, gv, ga, gl, gf = table.export()
+    ok, ov, oa, ol, of = ot.export()
+    assert np.array_equal(gk, ok) and np.array_equal(gl, ol) and np.array_equal(gf, of)
+    assert close_rows(gv, ov.astype(np.float64), 0.01, RTOL_F32) and np.allclose(ga, oa, rtol=4e-5)
+    table.close()
