@@ -109,6 +109,7 @@ def main() -> int:
 
     # ---- pre-generate the batches and put them in HBM
     batches = []
+    lengths_of = []
     n_max = 0
     for s in range(args.batches):
         b = w.next_step(s)
@@ -116,6 +117,7 @@ def main() -> int:
         batches.append((torch.from_numpy(x.view(np.int64)).to(dev), torch.from_numpy(off).to(dev),
                         torch.from_numpy(tags).to(dev), len(x), (x, off, tags)))
         n_max = max(n_max, len(x))
+        lengths_of.append(b.lengths)
         log(f"batch {s}: N={len(x)} ({time.time() - t0:.1f}s)")
     buf = StepBuffers(n_max, dim, dtype)
     gen = torch.Generator(device=dev)
@@ -242,6 +244,41 @@ def main() -> int:
     result["fused_lookup"] = {"ms_per_step": round(wall_f * 1e3 / args.steps, 4), "ids_per_sec": round(ids_f / wall_f, 1),
                               "note": "ht_gather_expand_sorted replaces ht_gather + emb_expand_sorted: same result, "
                                       "2 x rowbytes x unique fewer bytes moved"}
+
+    # ---- pooled variant (one vector per sample and field instead of one per position), as an extra line
+    if args.config == 2:
+        lens0 = np.concatenate(lengths_of[0]).astype(np.int64)
+        bag_off = torch.from_numpy(np.concatenate([[0], np.cumsum(lens0)]).astype(np.int64)).to(dev)
+        nb = len(lens0)
+        pws = torch.empty(B.emb_pool_workspace_bytes(n_max, nb, dim), dtype=torch.uint8, device=dev)
+        pooled = torch.empty((nb, dim), dtype=torch.float32, device=dev)
+        d_pooled = torch.randn((nb, dim), generator=gen, device=dev, dtype=torch.float32)
+
+        def one_step_pooled(step: int):
+            dx, doff, dtag, n, _ = batches[0]
+            B.emb_tag_keys(dx, doff, dtag, tag_bits, buf.key, buf.err_count)
+            B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, None, buf.perm, None, buf.seg_of, buf.n_unique, buf.dedup_ws)
+            table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted)
+            table.gather(buf.row_idx, buf.n_unique, n, buf.uniq_rows)
+            B.emb_pool_bags(buf.uniq_rows, dtype, buf.inverse, bag_off, n, dim, True, pooled, pws)
+            B.grad_segment_reduce_pooled(d_pooled, bag_off, buf.seg_of, buf.perm, n, dim, True, buf.reduced, pws)
+            table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps)
+            return n
+
+        base = base + 2 + args.steps
+        for s in range(2):
+            one_step_pooled(base + s)
+        torch.cuda.synchronize()
+        t_p = time.perf_counter()
+        ids_p = 0
+        for k in range(args.steps):
+            ids_p += one_step_pooled(base + 2 + k)
+        torch.cuda.synchronize()
+        wall_p = time.perf_counter() - t_p
+        result["pooled_lookup"] = {"ms_per_step": round(wall_p * 1e3 / args.steps, 4), "ids_per_sec": round(ids_p / wall_p, 1),
+                                   "bags": nb, "mode": "mean",
+                                   "note": "emb_pool_bags / grad_segment_reduce_pooled replace expand / reduce: one "
+                                           "fp32 vector per (sample, field) instead of one row per position"}
 
     if args.copy_probe_mib > 0:
         nbytes = args.copy_probe_mib << 20

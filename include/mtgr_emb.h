@@ -227,6 +227,28 @@ int ht_apply_adagrad(emb_table_t* t, const int32_t* row_idx, const float* reduce
 int ht_gather_expand_sorted(emb_table_t* t, const int32_t* row_idx, const int32_t* seg_of, const int32_t* perm,
                             int64_t n, void* out, void* stream);
 
+/* ------------------------------------------------------------------ pooling (Sec. 3.2: "performs pooling computations as needed") */
+
+/* A bag is a run of consecutive positions (the ID list of one sample in one field); bag b covers
+ * positions bag_off[b] .. bag_off[b+1]-1, bag_off [dev, int64, n_bags+1], bag_off[n_bags] == n.
+ *
+ * emb_pool_bags: pooled[b,:] = sum (mean != 0: mean) over the positions i of bag b of
+ * uniq_rows[inverse[i],:], fp32 accumulation in a fixed order, fp32 output [n_bags, dim]; an empty bag
+ * gives zeros.  It replaces emb_expand when the model consumes one vector per bag.
+ *
+ * grad_segment_reduce_pooled: the matching backward pass.  d_pooled [dev, n_bags x dim, f32] is the
+ * gradient of the pooled output; position i receives d_pooled[bag(i),:] (divided by the bag length for
+ * the mean) and these are summed per distinct key exactly like grad_segment_reduce does, into
+ * reduced [*n_unique, dim].  seg_of / perm as written by emb_dedup.
+ *
+ * workspace [dev, 256-byte aligned] of at least emb_pool_workspace_bytes(n, n_bags, dim) for both. */
+size_t emb_pool_workspace_bytes(int64_t n, int n_bags, int dim);
+int emb_pool_bags(const void* uniq_rows, int dtype, const int32_t* inverse, const int64_t* bag_off, int n_bags,
+                  int64_t n, int dim, int mean, float* pooled, void* workspace, size_t workspace_bytes, void* stream);
+int grad_segment_reduce_pooled(const float* d_pooled, const int64_t* bag_off, int n_bags, const int32_t* seg_of,
+                               const int32_t* perm, int64_t n, int dim, int mean, float* reduced, void* workspace,
+                               size_t workspace_bytes, void* stream);
+
 /* ------------------------------------------------------------------ maintenance */
 
 /* Delete every key that was not touched for `ttl` steps (rule active when ttl > 0) or that was

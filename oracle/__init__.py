@@ -116,6 +116,28 @@ def segment_reduce(grad: np.ndarray, inverse: np.ndarray, n_unique: int) -> np.n
     return out
 
 
+def pool_bags(E: np.ndarray, bag_off: np.ndarray, mean: bool) -> np.ndarray:
+    E = np.ascontiguousarray(E, dtype=np.float32)
+    bag_off = np.ascontiguousarray(bag_off, dtype=np.int64)
+    nb, dim = len(bag_off) - 1, E.shape[1]
+    out = np.empty((nb, dim), dtype=np.float32)
+    rc = lib().orc_pool_bags(_p(E, C.c_float), _p(bag_off, C.c_int64), C.c_int64(nb), C.c_int(dim), C.c_int(int(mean)),
+                             _p(out, C.c_float))
+    if rc != 0:
+        raise ValueError("bag offsets must be non-decreasing")
+    return out
+
+
+def pool_bags_backward(d_pooled: np.ndarray, bag_off: np.ndarray, mean: bool) -> np.ndarray:
+    d_pooled = np.ascontiguousarray(d_pooled, dtype=np.float32)
+    bag_off = np.ascontiguousarray(bag_off, dtype=np.int64)
+    nb, dim = d_pooled.shape
+    G = np.empty((int(bag_off[-1]), dim), dtype=np.float32)
+    lib().orc_pool_bags_backward(_p(d_pooled, C.c_float), _p(bag_off, C.c_int64), C.c_int64(nb), C.c_int(dim),
+                                 C.c_int(int(mean)), _p(G, C.c_float))
+    return G
+
+
 def float_to_bf16_bits(a: np.ndarray) -> np.ndarray:
     a = np.ascontiguousarray(a, dtype=np.float32)
     out = np.empty(a.shape, dtype=np.uint16)

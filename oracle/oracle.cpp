@@ -289,6 +289,38 @@ int orc_segment_reduce(const float* grad, const int32_t* inverse, int64_t n, int
     return 0;
 }
 
+// Pooling of bags (Sec. 3.2: the table collection "performs pooling computations as needed").
+// Bag b is the run of positions bag_off[b] .. bag_off[b+1]-1.  pooled[b,:] = sum (or mean) of the
+// rows E[i,:] of its positions, accumulated in double in position order, rounded once.  An empty
+// bag gives zeros.
+int orc_pool_bags(const float* E, const int64_t* bag_off, int64_t n_bags, int dim, int mean, float* pooled) {
+    for (int64_t b = 0; b < n_bags; ++b) {
+        const int64_t len = bag_off[b + 1] - bag_off[b];
+        if (len < 0) return -1;
+        for (int j = 0; j < dim; ++j) {
+            double s = 0.0;
+            for (int64_t i = bag_off[b]; i < bag_off[b + 1]; ++i) s += static_cast<double>(E[i * dim + j]);
+            if (mean && len > 0) s /= static_cast<double>(len);
+            pooled[b * dim + j] = static_cast<float>(s);
+        }
+    }
+    return 0;
+}
+
+// Backward of the pooling: the gradient of position i is the gradient of its bag's pooled vector,
+// divided by the bag length for the mean (one correctly rounded fp32 division).
+int orc_pool_bags_backward(const float* d_pooled, const int64_t* bag_off, int64_t n_bags, int dim, int mean, float* G) {
+    for (int64_t b = 0; b < n_bags; ++b) {
+        const int64_t len = bag_off[b + 1] - bag_off[b];
+        for (int64_t i = bag_off[b]; i < bag_off[b + 1]; ++i)
+            for (int j = 0; j < dim; ++j) {
+                const float g = d_pooled[b * dim + j];
+                G[i * dim + j] = mean ? g / static_cast<float>(len) : g;
+            }
+    }
+    return 0;
+}
+
 // Row-wise Adagrad on the rows of the given keys only:
 //   acc <- acc + (1/D) * sum_j g_j^2 ;  w_j <- w_j - lr * g_j / (sqrt(acc) + eps)
 // evaluated in double from the stored state, each stored value rounded once.

@@ -48,7 +48,8 @@ EXPORTS = [
     "emb_table_create", "emb_table_destroy", "ht_set_key_storage", "ht_add_chunk", "ht_plan", "ht_rehash",
     "ht_stats", "emb_tag_keys", "emb_dedup_workspace_bytes", "emb_dedup", "ht_find_or_insert", "ht_find",
     "ht_gather", "emb_expand", "emb_expand_sorted", "grad_segment_reduce_workspace_bytes", "grad_segment_reduce",
-    "ht_apply_adagrad", "ht_gather_expand_sorted", "ht_evict", "ht_export",
+    "ht_apply_adagrad", "ht_gather_expand_sorted", "emb_pool_workspace_bytes", "emb_pool_bags",
+    "grad_segment_reduce_pooled", "ht_evict", "ht_export",
 ]
 
 
@@ -86,6 +87,9 @@ def load():
         "grad_segment_reduce": (C.c_int, [vp, i32, vp, vp, i64, i32, vp, vp, C.c_size_t, vp]),
         "ht_apply_adagrad": (C.c_int, [vp, vp, vp, vp, i64, f32, f32, vp]),
         "ht_gather_expand_sorted": (C.c_int, [vp, vp, vp, vp, i64, vp, vp]),
+        "emb_pool_workspace_bytes": (C.c_size_t, [i64, i32, i32]),
+        "emb_pool_bags": (C.c_int, [vp, i32, vp, vp, i32, i64, i32, i32, vp, vp, C.c_size_t, vp]),
+        "grad_segment_reduce_pooled": (C.c_int, [vp, vp, i32, vp, vp, i64, i32, i32, vp, vp, C.c_size_t, vp]),
         "ht_evict": (C.c_int, [vp, u32, u32, u32, u32, vp, i64, vp, vp]),
         "ht_export": (C.c_int, [vp, vp, vp, vp, vp, vp, i64, vp, vp]),
     }
@@ -241,6 +245,24 @@ def ht_apply_adagrad(h, row_idx, reduced, n_dev, n_max: int, lr: float, eps: flo
 def ht_gather_expand_sorted(h, row_idx, seg_of, perm, n: int, out, stream=None) -> None:
     _check(load().ht_gather_expand_sorted(h, _ptr(row_idx), _ptr(seg_of), _ptr(perm), n, _ptr(out), _stream(stream)),
            "ht_gather_expand_sorted")
+
+
+def emb_pool_workspace_bytes(n: int, n_bags: int, dim: int) -> int:
+    return int(load().emb_pool_workspace_bytes(n, n_bags, dim))
+
+
+def emb_pool_bags(uniq_rows, dtype: int, inverse, bag_off, n: int, dim: int, mean: bool, pooled, workspace, stream=None) -> None:
+    _check(load().emb_pool_bags(_ptr(uniq_rows), dtype, _ptr(inverse), _ptr(bag_off), bag_off.numel() - 1, n, dim,
+                                int(mean), _ptr(pooled), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                _stream(stream)), "emb_pool_bags")
+
+
+def grad_segment_reduce_pooled(d_pooled, bag_off, seg_of, perm, n: int, dim: int, mean: bool, reduced, workspace,
+                               stream=None) -> None:
+    _check(load().grad_segment_reduce_pooled(_ptr(d_pooled), _ptr(bag_off), bag_off.numel() - 1, _ptr(seg_of), _ptr(perm),
+                                             n, dim, int(mean), _ptr(reduced), _ptr(workspace),
+                                             workspace.numel() * workspace.element_size(), _stream(stream)),
+           "grad_segment_reduce_pooled")
 
 
 def ht_evict(h, now: int, ttl: int, min_freq: int, grace: int, evicted_keys, n_evicted, stream=None) -> None:

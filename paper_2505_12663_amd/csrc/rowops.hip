@@ -198,7 +198,8 @@ __device__ inline float sumsq_group(float ss) {
 
 struct LevelIn {
     const char* rows;        // level 1: grad matrix; level >= 2: fp32 partial rows
-    const int32_t* perm;     // level 1 only
+    const int32_t* perm;     // level 1 only: source row of item j is perm[j] ...
+    const int32_t* via;      // ... or via[perm[j]] when given (pooled gradients: position -> bag)
     const int32_t* seg;      // segment of each item in order (-1 = no item)
     int64_t n_items;
     int in_row_bytes;
@@ -251,7 +252,12 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
             my_seg[u] = -1;
             if (group_on && it < items) {
                 const int64_t j = first + it;
-                my_src[u] = LEVEL1 ? (int64_t)in.perm[j] : j;
+                if (LEVEL1) {
+                    const int32_t p = in.perm[j];
+                    my_src[u] = in.via ? (int64_t)in.via[p] : (int64_t)p;
+                } else {
+                    my_src[u] = j;
+                }
                 my_seg[u] = in.seg[j];
             }
         }
@@ -326,8 +332,8 @@ ReduceLayout reduce_layout(int64_t n, int dim) {
 }
 
 template <int LPR, int FPL>
-int launch_reduce(const char* grad, int in_row_bytes, const int32_t* seg_of, const int32_t* perm, int64_t n, int dim,
-                  float* reduced, char* ws, const ReduceLayout& L, hipStream_t s) {
+int launch_reduce(const char* grad, int in_row_bytes, const int32_t* seg_of, const int32_t* perm, const int32_t* via,
+                  int64_t n, int dim, float* reduced, char* ws, const ReduceLayout& L, hipStream_t s) {
     constexpr int kGroups = kWave / LPR;
     constexpr int kSpansPerBlock = (kBlock / kWave) * kGroups;
     for (int l = 0; l < L.levels; ++l) {
@@ -336,11 +342,11 @@ int launch_reduce(const char* grad, int in_row_bytes, const int32_t* seg_of, con
         float* prow = reinterpret_cast<float*>(ws + L.rows_off[l]);
         int32_t* pseg = reinterpret_cast<int32_t*>(ws + L.seg_off[l]);
         if (l == 0) {
-            LevelIn in{grad, perm, seg_of, n, in_row_bytes};
+            LevelIn in{grad, perm, via, seg_of, n, in_row_bytes};
             hipLaunchKernelGGL((k_seg_reduce<LPR, FPL, true>), dim3(grid), dim3(kBlock), 0, s, in, dim, reduced, prow, pseg, last);
         } else {
-            LevelIn in{ws + L.rows_off[l - 1], nullptr, reinterpret_cast<const int32_t*>(ws + L.seg_off[l - 1]), L.items[l],
-                       dim * 4};
+            LevelIn in{ws + L.rows_off[l - 1], nullptr, nullptr, reinterpret_cast<const int32_t*>(ws + L.seg_off[l - 1]),
+                       L.items[l], dim * 4};
             // partial rows are fp32: dim*4 bytes, dim/4 vectors per row
             constexpr int LPR2 = (FPL == 8) ? (LPR * 2 > 64 ? 64 : LPR * 2) : LPR;
             constexpr int kGroups2 = kWave / LPR2;
@@ -481,23 +487,20 @@ size_t grad_segment_reduce_workspace_bytes(int64_t n, int dim) {
     return reduce_layout(n, dim).total;
 }
 
-int grad_segment_reduce(const void* grad, int grad_dtype, const int32_t* seg_of, const int32_t* perm, int64_t n,
-                        int dim, float* reduced, void* workspace, size_t workspace_bytes, void* stream) {
-    if (n < 0 || n > 0x7FFFFFFFll || dim <= 0 || (grad_dtype != EMB_F32 && grad_dtype != EMB_BF16)) return EMB_ERR_INVALID_ARG;
-    if (n == 0) return EMB_OK;
+static int reduce_dispatch(const void* grad, int grad_dtype, const int32_t* seg_of, const int32_t* perm, const int32_t* via,
+                           int64_t n, int dim, float* reduced, void* workspace, size_t workspace_bytes, hipStream_t s) {
     const int in_row_bytes = dim * (grad_dtype == EMB_F32 ? 4 : 2);
     if (in_row_bytes % 16 != 0 || dim > 256) return EMB_ERR_INVALID_ARG;
     if (!grad || !seg_of || !perm || !reduced) return EMB_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(grad) & 15) || (reinterpret_cast<uintptr_t>(reduced) & 15)) return EMB_ERR_INVALID_ARG;
     const ReduceLayout L = reduce_layout(n, dim);
     if (!workspace || workspace_bytes < L.total || (reinterpret_cast<uintptr_t>(workspace) & 255)) return EMB_ERR_WORKSPACE;
-    hipStream_t s = static_cast<hipStream_t>(stream);
     const char* g = static_cast<const char*>(grad);
     char* ws = static_cast<char*>(workspace);
     const int vecs = in_row_bytes / 16;
-#define MTGR_RED(L_)                                                                                          \
-    (grad_dtype == EMB_F32 ? launch_reduce<L_, 4>(g, in_row_bytes, seg_of, perm, n, dim, reduced, ws, L, s) \
-                           : launch_reduce<L_, 8>(g, in_row_bytes, seg_of, perm, n, dim, reduced, ws, L, s))
+#define MTGR_RED(L_)                                                                                               \
+    (grad_dtype == EMB_F32 ? launch_reduce<L_, 4>(g, in_row_bytes, seg_of, perm, via, n, dim, reduced, ws, L, s) \
+                           : launch_reduce<L_, 8>(g, in_row_bytes, seg_of, perm, via, n, dim, reduced, ws, L, s))
     if (vecs <= 1) return MTGR_RED(1);
     if (vecs <= 2) return MTGR_RED(2);
     if (vecs <= 4) return MTGR_RED(4);
@@ -506,6 +509,115 @@ int grad_segment_reduce(const void* grad, int grad_dtype, const int32_t* seg_of,
     if (vecs <= 32) return MTGR_RED(32);
     return MTGR_RED(64);
 #undef MTGR_RED
+}
+
+int grad_segment_reduce(const void* grad, int grad_dtype, const int32_t* seg_of, const int32_t* perm, int64_t n,
+                        int dim, float* reduced, void* workspace, size_t workspace_bytes, void* stream) {
+    if (n < 0 || n > 0x7FFFFFFFll || dim <= 0 || (grad_dtype != EMB_F32 && grad_dtype != EMB_BF16)) return EMB_ERR_INVALID_ARG;
+    if (n == 0) return EMB_OK;
+    return reduce_dispatch(grad, grad_dtype, seg_of, perm, nullptr, n, dim, reduced, workspace, workspace_bytes,
+                           static_cast<hipStream_t>(stream));
+}
+
+// ---------------------------------------------------------------------------- pooling (Sec. 3.2, HashTableCollection)
+// Bags are runs of consecutive positions (one bag per sample and field).  Pooling the rows of a bag
+// is the same fixed-tree segmented sum as the gradient reduction, with the bag as the segment and
+// uniq_rows[inverse[i]] as the row of position i; its backward pass is the gradient reduction with
+// row dY[bag_of[i]] (scaled by 1/len for the mean) as the gradient of position i.
+namespace {
+__global__ __launch_bounds__(kBlock) void k_bag_of(const int64_t* __restrict__ bag_off, int n_bags, int64_t n,
+                                                   int32_t* __restrict__ bag_of) {
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= n) return;
+    int lo = 0, hi = n_bags; // invariant: bag_off[lo] <= i < bag_off[hi]
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (bag_off[mid] <= i) lo = mid; else hi = mid;
+    }
+    bag_of[i] = lo;
+}
+// out[b,:] = in[b,:] / len(b) for the mean (empty bags give zeros), or a plain copy / zero fill
+__global__ __launch_bounds__(kBlock) void k_bag_rows(const float* __restrict__ in, const int64_t* __restrict__ bag_off,
+                                                     int n_bags, int dim, int mean, int zero_empty_only,
+                                                     float* __restrict__ out) {
+    const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (e >= (int64_t)n_bags * dim) return;
+    const int b = (int)(e / dim);
+    const int64_t len = bag_off[b + 1] - bag_off[b];
+    if (zero_empty_only) {
+        if (len == 0) out[e] = 0.0f;
+        return;
+    }
+    float v = in[e];
+    if (len == 0) v = 0.0f;
+    else if (mean) v = __fdiv_rn(v, (float)len);
+    out[e] = v;
+}
+struct PoolLayout {
+    size_t bag_of, scaled, reduce, total;
+};
+PoolLayout pool_layout(int64_t n, int n_bags, int dim) {
+    PoolLayout L;
+    size_t o = 0;
+    L.bag_of = o; o = align256(o + (size_t)(n > 0 ? n : 1) * 4);
+    L.scaled = o; o = align256(o + (size_t)(n_bags > 0 ? n_bags : 1) * dim * 4);
+    L.reduce = o; o += reduce_layout(n > 0 ? n : 1, dim).total;
+    L.total = o;
+    return L;
+}
+} // namespace
+
+size_t emb_pool_workspace_bytes(int64_t n, int n_bags, int dim) {
+    if (n < 0 || n_bags < 0 || dim <= 0) return 0;
+    return pool_layout(n, n_bags, dim).total;
+}
+
+int emb_pool_bags(const void* uniq_rows, int dtype, const int32_t* inverse, const int64_t* bag_off, int n_bags, int64_t n,
+                  int dim, int mean, float* pooled, void* workspace, size_t workspace_bytes, void* stream) {
+    if (n < 0 || n > 0x7FFFFFFFll || n_bags < 0 || dim <= 0 || (dtype != EMB_F32 && dtype != EMB_BF16)) return EMB_ERR_INVALID_ARG;
+    if (n_bags == 0) return n == 0 ? EMB_OK : EMB_ERR_INVALID_ARG;
+    if (!bag_off || !pooled || (n > 0 && (!uniq_rows || !inverse))) return EMB_ERR_INVALID_ARG;
+    const PoolLayout L = pool_layout(n, n_bags, dim);
+    if (!workspace || workspace_bytes < L.total || (reinterpret_cast<uintptr_t>(workspace) & 255)) return EMB_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(workspace);
+    int32_t* bag_of = reinterpret_cast<int32_t*>(ws + L.bag_of);
+    const unsigned bgrid = (unsigned)(((int64_t)n_bags * dim + kBlock - 1) / kBlock);
+    if (n > 0) {
+        hipLaunchKernelGGL(k_bag_of, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, bag_off, n_bags, n, bag_of);
+        MTGR_LAUNCH_CHECK();
+        // segmented sum: segment = bag, source row of position i = uniq_rows[inverse[i]]
+        int rc = reduce_dispatch(uniq_rows, dtype, bag_of, inverse, nullptr, n, dim, pooled, ws + L.reduce,
+                                 workspace_bytes - L.reduce, s);
+        if (rc != EMB_OK) return rc;
+    }
+    // bags without positions were not written by the sum; the mean divides by the bag length
+    if (mean)
+        hipLaunchKernelGGL(k_bag_rows, dim3(bgrid), dim3(kBlock), 0, s, pooled, bag_off, n_bags, dim, 1, 0, pooled);
+    else
+        hipLaunchKernelGGL(k_bag_rows, dim3(bgrid), dim3(kBlock), 0, s, pooled, bag_off, n_bags, dim, 0, 1, pooled);
+    MTGR_LAUNCH_CHECK();
+    return EMB_OK;
+}
+
+int grad_segment_reduce_pooled(const float* d_pooled, const int64_t* bag_off, int n_bags, const int32_t* seg_of,
+                               const int32_t* perm, int64_t n, int dim, int mean, float* reduced, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+    if (n < 0 || n > 0x7FFFFFFFll || n_bags < 0 || dim <= 0) return EMB_ERR_INVALID_ARG;
+    if (n == 0) return EMB_OK;
+    if (!d_pooled || !bag_off || n_bags == 0) return EMB_ERR_INVALID_ARG;
+    const PoolLayout L = pool_layout(n, n_bags, dim);
+    if (!workspace || workspace_bytes < L.total || (reinterpret_cast<uintptr_t>(workspace) & 255)) return EMB_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(workspace);
+    int32_t* bag_of = reinterpret_cast<int32_t*>(ws + L.bag_of);
+    float* scaled = reinterpret_cast<float*>(ws + L.scaled);
+    hipLaunchKernelGGL(k_bag_of, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, bag_off, n_bags, n, bag_of);
+    const unsigned bgrid = (unsigned)(((int64_t)n_bags * dim + kBlock - 1) / kBlock);
+    hipLaunchKernelGGL(k_bag_rows, dim3(bgrid), dim3(kBlock), 0, s, d_pooled, bag_off, n_bags, dim, mean ? 1 : 0, 0, scaled);
+    MTGR_LAUNCH_CHECK();
+    // gradient of position i = scaled[bag_of[i]]; summed per distinct key in the usual fixed order
+    return reduce_dispatch(scaled, EMB_F32, seg_of, perm, bag_of, n, dim, reduced, ws + L.reduce, workspace_bytes - L.reduce, s);
 }
 
 int ht_apply_adagrad(emb_table_t* t, const int32_t* row_idx, const float* reduced, const int64_t* n_dev,

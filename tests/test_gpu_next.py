@@ -98,3 +98,56 @@ def test_sparse_gradient_accumulation_over_micro_batches():
     assert np.array_equal(gk, ok) and np.array_equal(gl, ol) and np.array_equal(gf, of)
     assert close_rows(gv, ov.astype(np.float64), 0.01, RTOL_F32) and np.allclose(ga, oa, rtol=4e-5)
     table.close()
+
+
+@pytest.mark.parametrize("dim,dtype,mean", [(64, 0, False), (64, 0, True), (32, 0, True), (128, 1, False), (128, 1, True), (16, 0, False)])
+def test_pooled_lookup_forward_and_backward(dim, dtype, mean):
+    """Sum / mean pooling of every (sample, field) bag and its backward pass, against the checker
+    (which is pinned to torch's EmbeddingBag): forward within 1e-5 of the float64 sums, backward with
+    integer-valued output gradients bit-exact for the sum and within 1e-5 for the mean."""
+    w = make_config(1, batch=200)
+    b = w.next_step(0)
+    x, off, tags, _ = merged_inputs(w.features, b.ids, [0], 0)
+    lens = np.concatenate(b.lengths).astype(np.int64)            # field-major, sample-major: one bag per entry
+    lens[5] += lens[6]; lens[6] = 0                              # make one bag empty (positions stay the same)
+    bag_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    n, nb = len(x), len(lens)
+    assert bag_off[-1] == n
+    key, _ = oracle.tag_keys(x, off, tags, 1)
+    ou, oi, oc = oracle.dedup(key)
+    table, ot = EmbeddingTable(dim, dtype, capacity_log2=16, chunk_rows_log2=13), oracle.Table(dim, dtype)
+    buf = StepBuffers(n, dim, dtype)
+    B.emb_dedup(dev_keys(key), n, buf.uniq, buf.inverse, buf.counts, buf.perm, buf.seg_off, buf.seg_of, buf.n_unique, buf.dedup_ws)
+    U = int(buf.n_unique.item())
+    table.find_or_insert(buf.uniq, buf.n_unique, n, 0, buf.row_idx)
+    table.gather(buf.row_idx, buf.n_unique, n, buf.uniq_rows)
+    ot.find_or_insert(ou, 0)
+    oE = oracle.expand(ot.lookup(ou), oi)
+    d_off = torch.from_numpy(bag_off).cuda()
+    ws = torch.empty(B.emb_pool_workspace_bytes(n, nb, dim), dtype=torch.uint8, device="cuda")
+    pooled = torch.full((nb, dim), 5.0, device="cuda")
+    B.emb_pool_bags(buf.uniq_rows, dtype, buf.inverse, d_off, n, dim, mean, pooled, ws)
+    ref = oracle.pool_bags(oE, bag_off, mean).astype(np.float64)
+    sabs = oracle.pool_bags(np.abs(oE), bag_off, mean).astype(np.float64)
+    got = pooled.cpu().numpy()
+    assert close_reduce(got, ref, sabs, RTOL_F32)
+    assert (got[6] == 0).all()
+    # backward
+    rng = np.random.default_rng(4)
+    dY = rng.integers(-4, 5, size=(nb, dim)).astype(np.float32)
+    B.grad_segment_reduce_pooled(torch.from_numpy(dY).cuda(), d_off, buf.seg_of, buf.perm, n, dim, mean, buf.reduced, ws)
+    G = oracle.pool_bags_backward(dY, bag_off, mean)
+    og = oracle.segment_reduce(G, oi, U)
+    g = buf.reduced[:U].cpu().numpy()
+    if not mean:
+        assert np.array_equal(g, og)                                         # integer sums: one correct answer
+    else:
+        sabs_g = oracle.segment_reduce(np.abs(G), oi, U).astype(np.float64)
+        assert close_reduce(g, og.astype(np.float64), sabs_g, RTOL_F32)
+    table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, 0.01, 1e-8)
+    ot.apply_adagrad(ou, og, 0.01, 1e-8)
+    gk, gv, ga, _, _ = table.export()
+    ok, ov, oa, _, _ = ot.export()
+    assert np.array_equal(gk, ok)
+    assert close_rows(gv, ov.astype(np.float64), 0.01, RTOL_F32 if dtype == 0 else 1e-2)
+    table.close()

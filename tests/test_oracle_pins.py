@@ -368,3 +368,33 @@ def test_three_steps_of_tiny_config_conserve_and_stay_finite():
         for k, a in zip(keys.tolist(), acc.tolist()):
             assert a >= prev_acc.get(k, 0.0)
             prev_acc[k] = a
+
+
+# --------------------------------------------------------------------------- #
+# pooling (Sec. 3.2): the library routine for pooled lookups is torch's EmbeddingBag
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("mode", ["sum", "mean"])
+def test_pooling_forward_backward_equal_torch_embedding_bag(mode):
+    rng = np.random.default_rng(21)
+    U, D = 50, 8
+    lens = np.array([3, 0, 1, 7, 2, 0, 5, 4], dtype=np.int64)          # two empty bags
+    bag_off = np.concatenate([[0], np.cumsum(lens)])
+    n = int(bag_off[-1])
+    inverse = rng.integers(0, U, size=n).astype(np.int32)
+    W = rng.standard_normal((U, D)).astype(np.float32)
+    E = oracle.expand(W, inverse)
+    pooled = oracle.pool_bags(E, bag_off, mode == "mean")
+    Wt = torch.from_numpy(W.astype(np.float64)).requires_grad_(True)
+    ref = torch.nn.functional.embedding_bag(torch.from_numpy(inverse.astype(np.int64)), Wt,
+                                            torch.from_numpy(bag_off[:-1]), mode=mode)
+    assert np.array_equal(pooled, ref.detach().float().numpy())                       # float64 sums, one rounding
+    assert (pooled[[1, 5]] == 0).all()                                                 # empty bags
+    # backward: d(loss)/dW from autograd == per-key reduction of the per-position gradients
+    dY = rng.integers(-4, 5, size=(len(lens), D)).astype(np.float32)
+    ref.backward(torch.from_numpy(dY.astype(np.float64)))
+    G = oracle.pool_bags_backward(dY, bag_off, mode == "mean")
+    g = oracle.segment_reduce(G, inverse, U)
+    assert np.allclose(g, Wt.grad.numpy(), rtol=1e-6, atol=1e-6)
+    if mode == "sum":
+        assert np.array_equal(g, Wt.grad.float().numpy())                             # integers: exact
+        assert np.array_equal(G, np.repeat(dY, lens, axis=0))
