@@ -128,6 +128,12 @@ int ht_set_key_storage(emb_table_t* t, void* slots, int capacity_log2, void* str
  * initialisation; meta is zeroed by this call. */
 int ht_add_chunk(emb_table_t* t, void* values, void* meta, uint32_t* free_list, void* stream);
 
+/* Optional optimizer state for ht_apply_adam: fp32 first / second moment rows [2^chunk_rows_log2, dim]
+ * for the oldest chunk that has none yet (chunks get their state in the order they were added).
+ * Register it right after ht_add_chunk, before any key can be placed in the chunk; rows are zeroed
+ * when a key is inserted.  Inserts zero the moments only while every chunk has its state. */
+int ht_add_chunk_adam_state(emb_table_t* t, float* m, float* v, void* stream);
+
 /* Host-side capacity planning from upper bounds of the device counters: the newest copy of the
  * counters that has reached the host (every find-or-insert / evict / rehash queues one, without
  * blocking; ht_stats fetches one synchronously) plus the n_max of every find-or-insert issued since.
@@ -217,6 +223,14 @@ int grad_segment_reduce(const void* grad, int grad_dtype, const int32_t* seg_of,
  * reduced [dev, n x dim, f32]. */
 int ht_apply_adagrad(emb_table_t* t, const int32_t* row_idx, const float* reduced, const int64_t* n_dev,
                      int64_t n_max, float lr, float eps, void* stream);
+
+/* Sparse (lazy) Adam on the listed rows only - the optimizer the paper trains with (Sec. 4.1):
+ *   m = beta1 m + (1-beta1) g;  v = beta2 v + (1-beta2) g^2;
+ *   w -= lr * sqrt(1-beta2^step) / (1-beta1^step) * m / (sqrt(v) + eps),   step >= 1 = optimizer step count.
+ * Needs moment rows for every chunk (ht_add_chunk_adam_state), else EMB_ERR_NO_STORAGE.  row_idx as for
+ * ht_apply_adagrad. */
+int ht_apply_adam(emb_table_t* t, const int32_t* row_idx, const float* reduced, const int64_t* n_dev, int64_t n_max,
+                  float lr, float beta1, float beta2, float eps, int64_t step, void* stream);
 
 /* ------------------------------------------------------------------ fused form (no communication between lookup and expand) */
 

@@ -216,6 +216,16 @@ class Table:
         lib().orc_apply_adagrad(self._h, _p(key, C.c_uint64), C.c_int64(len(key)), _p(g, C.c_float),
                                 C.c_float(lr), C.c_float(eps))
 
+    def apply_adam(self, key, g: np.ndarray, lr: float, step: int, beta1: float = 0.9, beta2: float = 0.999,
+                   eps: float = 1e-8) -> None:
+        key = self._keys(key)
+        g = np.ascontiguousarray(g, dtype=np.float32)
+        assert g.shape == (len(key), self.dim)
+        rc = lib().orc_apply_adam(self._h, _p(key, C.c_uint64), C.c_int64(len(key)), _p(g, C.c_float), C.c_float(lr),
+                                  C.c_float(beta1), C.c_float(beta2), C.c_float(eps), C.c_int64(step))
+        if rc != 0:
+            raise ValueError("step must be >= 1")
+
     def evict(self, now: int, ttl: int, min_freq: int, grace: int) -> np.ndarray:
         out = np.empty(len(self), dtype=np.uint64)
         n = lib().orc_evict(self._h, C.c_uint32(now), C.c_uint32(ttl), C.c_uint32(min_freq), C.c_uint32(grace),

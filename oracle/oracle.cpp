@@ -33,6 +33,7 @@ struct Row {
     float acc = 0.0f;       // row-wise Adagrad accumulator
     uint32_t last_seen = 0; // step of the last find-or-insert that touched the key
     uint32_t freq = 0;      // number of find-or-insert elements that touched the key
+    std::vector<float> m, v; // Adam moments (empty = all zero)
 };
 
 struct Table {
@@ -341,6 +342,39 @@ int orc_apply_adagrad(void* h, const uint64_t* key, int64_t n, const float* g, f
             r.w[j] = (t.dtype == kBF16) ? double_to_bf16_float(w) : static_cast<float>(w);
         }
         r.acc = static_cast<float>(acc);
+    }
+    return 0;
+}
+
+// Sparse (lazy) Adam on the rows of the given keys only, the optimizer of Sec. 4.1:
+//   m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2;
+//   w <- w - lr * sqrt(1-b2^t)/(1-b1^t) * m / (sqrt(v) + eps)
+// evaluated in double from the stored fp32 state; m, v, w each rounded once on store.  Absent keys
+// are skipped.  A new entry starts with zero moments.
+int orc_apply_adam(void* h, const uint64_t* key, int64_t n, const float* g, float lr, float b1, float b2, float eps,
+                   int64_t step) {
+    Table& t = *static_cast<Table*>(h);
+    const int D = t.dim;
+    if (step < 1) return -1;
+    const double B1 = b1, B2 = b2;
+    const double step_size = static_cast<double>(lr) * std::sqrt(1.0 - std::pow(B2, (double)step)) / (1.0 - std::pow(B1, (double)step));
+    for (int64_t u = 0; u < n; ++u) {
+        auto it = t.map.find(key[u]);
+        if (it == t.map.end()) continue;
+        Row& r = it->second;
+        if (r.m.empty()) {
+            r.m.assign(D, 0.0f);
+            r.v.assign(D, 0.0f);
+        }
+        for (int j = 0; j < D; ++j) {
+            const double gg = g[u * D + j];
+            const double m = B1 * (double)r.m[j] + (1.0 - B1) * gg;
+            const double v = B2 * (double)r.v[j] + (1.0 - B2) * gg * gg;
+            const double w = (double)r.w[j] - step_size * m / (std::sqrt(v) + (double)eps);
+            r.m[j] = static_cast<float>(m);
+            r.v[j] = static_cast<float>(v);
+            r.w[j] = (t.dtype == kBF16) ? double_to_bf16_float(w) : static_cast<float>(w);
+        }
     }
     return 0;
 }

@@ -45,10 +45,10 @@ class HtStats(C.Structure):
 
 EXPORTS = [
     "emb_tag_bits", "emb_plan_merge", "ht_probe_line", "emb_status_string", "emb_table_state_bytes",
-    "emb_table_create", "emb_table_destroy", "ht_set_key_storage", "ht_add_chunk", "ht_plan", "ht_rehash",
+    "emb_table_create", "emb_table_destroy", "ht_set_key_storage", "ht_add_chunk", "ht_add_chunk_adam_state", "ht_plan", "ht_rehash",
     "ht_stats", "emb_tag_keys", "emb_dedup_workspace_bytes", "emb_dedup", "ht_find_or_insert", "ht_find",
     "ht_gather", "emb_expand", "emb_expand_sorted", "grad_segment_reduce_workspace_bytes", "grad_segment_reduce",
-    "ht_apply_adagrad", "ht_gather_expand_sorted", "emb_pool_workspace_bytes", "emb_pool_bags",
+    "ht_apply_adagrad", "ht_apply_adam", "ht_gather_expand_sorted", "emb_pool_workspace_bytes", "emb_pool_bags",
     "grad_segment_reduce_pooled", "ht_evict", "ht_export",
 ]
 
@@ -72,6 +72,7 @@ def load():
         "emb_table_destroy": (C.c_int, [vp]),
         "ht_set_key_storage": (C.c_int, [vp, vp, i32, vp]),
         "ht_add_chunk": (C.c_int, [vp, vp, vp, vp, vp]),
+        "ht_add_chunk_adam_state": (C.c_int, [vp, vp, vp, vp]),
         "ht_plan": (C.c_int, [vp, i64, C.POINTER(C.c_int), C.POINTER(C.c_int)]),
         "ht_rehash": (C.c_int, [vp, vp, i32, vp]),
         "ht_stats": (C.c_int, [vp, C.POINTER(HtStats), vp]),
@@ -86,6 +87,7 @@ def load():
         "grad_segment_reduce_workspace_bytes": (C.c_size_t, [i64, i32]),
         "grad_segment_reduce": (C.c_int, [vp, i32, vp, vp, i64, i32, vp, vp, C.c_size_t, vp]),
         "ht_apply_adagrad": (C.c_int, [vp, vp, vp, vp, i64, f32, f32, vp]),
+        "ht_apply_adam": (C.c_int, [vp, vp, vp, vp, i64, f32, f32, f32, f32, i64, vp]),
         "ht_gather_expand_sorted": (C.c_int, [vp, vp, vp, vp, i64, vp, vp]),
         "emb_pool_workspace_bytes": (C.c_size_t, [i64, i32, i32]),
         "emb_pool_bags": (C.c_int, [vp, i32, vp, vp, i32, i64, i32, i32, vp, vp, C.c_size_t, vp]),
@@ -169,6 +171,10 @@ def ht_add_chunk(h, values, meta, free_list, stream=None) -> None:
     _check(load().ht_add_chunk(h, _ptr(values), _ptr(meta), _ptr(free_list), _stream(stream)), "ht_add_chunk")
 
 
+def ht_add_chunk_adam_state(h, m, v, stream=None) -> None:
+    _check(load().ht_add_chunk_adam_state(h, _ptr(m), _ptr(v), _stream(stream)), "ht_add_chunk_adam_state")
+
+
 def ht_plan(h, n_incoming: int):
     cap, chunks = C.c_int(0), C.c_int(0)
     _check(load().ht_plan(h, n_incoming, C.byref(cap), C.byref(chunks)), "ht_plan")
@@ -240,6 +246,12 @@ def grad_segment_reduce(grad, grad_dtype: int, seg_of, perm, n: int, dim: int, r
 def ht_apply_adagrad(h, row_idx, reduced, n_dev, n_max: int, lr: float, eps: float, stream=None) -> None:
     _check(load().ht_apply_adagrad(h, _ptr(row_idx), _ptr(reduced), _ptr(n_dev), n_max, lr, eps, _stream(stream)),
            "ht_apply_adagrad")
+
+
+def ht_apply_adam(h, row_idx, reduced, n_dev, n_max: int, lr: float, beta1: float, beta2: float, eps: float, step: int,
+                  stream=None) -> None:
+    _check(load().ht_apply_adam(h, _ptr(row_idx), _ptr(reduced), _ptr(n_dev), n_max, lr, beta1, beta2, eps, step,
+                                _stream(stream)), "ht_apply_adam")
 
 
 def ht_gather_expand_sorted(h, row_idx, seg_of, perm, n: int, out, stream=None) -> None:

@@ -50,6 +50,8 @@ struct HtState {
     void* values[kMaxChunks];
     RowMeta* meta[kMaxChunks];
     uint32_t* free_list[kMaxChunks];
+    float* adam_m[kMaxChunks];   // optional per-chunk first/second moment rows (fp32 [rows, dim]); null = none
+    float* adam_v[kMaxChunks];
 };
 
 // Host view of the counters.
@@ -85,6 +87,7 @@ struct HtView {
     int row_bytes;
     float init_c;            // init_scale * 2^-23
     int count;               // maintain probe counters
+    int has_adam;            // moment rows are registered for every chunk
 };
 
 // ---- slot hash: the 64-bit finalizer of MurmurHash3 (Sec. 3.1 names MurmurHash3) ----------
@@ -178,6 +181,7 @@ struct emb_table {
     mtgr::Slot* slots;          // device
     int cap_log2;
     int n_chunks;
+    int n_adam_chunks;          // chunks that have moment rows registered (in order)
     int row_bytes;
     uint64_t n_rehash;
     // Host-side upper bounds of the device counters: exact values as of some point of the
@@ -241,6 +245,7 @@ struct emb_table {
         v.row_bytes = row_bytes;
         v.init_c = desc.init_scale * (1.0f / 8388608.0f);
         v.count = desc.count_probes;
+        v.has_adam = (n_chunks > 0 && n_adam_chunks == n_chunks) ? 1 : 0;
         return v;
     }
 };

@@ -5,6 +5,8 @@
 // (LPR = row bytes / 16 rounded up to a power of two), so one wave instruction covers 64/LPR
 // whole rows with fully used 64..128-byte segments, and several rows are in flight per lane
 // group before the first is consumed.
+#include <cmath>
+
 #include "common.hpp"
 
 using namespace mtgr;
@@ -434,6 +436,65 @@ __global__ __launch_bounds__(kBlock) void k_adagrad(HtView v, const int32_t* __r
     }
 }
 
+// ---------------------------------------------------------------------------- sparse Adam
+// The optimizer the paper trains with (Sec. 4.1), in its lazy / sparse form: only the listed rows
+// move.  m = b1 m + (1-b1) g;  v = b2 v + (1-b2) g^2;  w -= step_size * m / (sqrt(v) + eps) with
+// step_size = lr * sqrt(1 - b2^t) / (1 - b1^t) computed on the host.  One lane handles 4 (fp32
+// table) or 8 (bf16 table) elements; the moment rows are fp32.
+template <bool BF16>
+__global__ __launch_bounds__(kBlock) void k_adam(HtView v, const int32_t* __restrict__ row_idx, const float* __restrict__ g,
+                                                 const int64_t* n_dev, int64_t n_max, float step_size, float b1,
+                                                 float b2, float eps) {
+    const int64_t n = read_count(n_dev, n_max);
+    constexpr int kF = BF16 ? 8 : 4;
+    const int per_row = v.dim / kF;                      // lanes' worth of work per row
+    const int64_t item = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t u = item / per_row;
+    const int sub = (int)(item % per_row);
+    if (u >= n) return;
+    const int ri = row_idx[u];
+    if (ri < 0) return;
+    const uint32_t row = (uint32_t)ri;
+    const size_t o = (size_t)(row & ((1u << v.chunk_log2) - 1u)) * (size_t)v.dim + (size_t)sub * kF;
+    float* pm = v.st->adam_m[row >> v.chunk_log2] + o;
+    float* pv = v.st->adam_v[row >> v.chunk_log2] + o;
+    const float* pg = g + (size_t)u * v.dim + (size_t)sub * kF;
+    char* pw = const_cast<char*>(chunk_row_cptr(v, row)) + sub * 16;
+    float w[kF];
+    const V16 wv = ld16(pw);
+    if (BF16) {
+        w[0] = bf16lo(wv.x); w[1] = bf16hi(wv.x); w[2] = bf16lo(wv.y); w[3] = bf16hi(wv.y);
+        w[4 % kF] = bf16lo(wv.z); w[5 % kF] = bf16hi(wv.z); w[6 % kF] = bf16lo(wv.w); w[7 % kF] = bf16hi(wv.w);
+    } else {
+        w[0] = __uint_as_float(wv.x); w[1] = __uint_as_float(wv.y); w[2] = __uint_as_float(wv.z); w[3] = __uint_as_float(wv.w);
+    }
+    const float c1 = __fsub_rn(1.0f, b1), c2 = __fsub_rn(1.0f, b2);
+#pragma unroll
+    for (int q = 0; q < kF / 4; ++q) {
+        V16 gm = ld16(pg + 4 * q), mm = ld16(pm + 4 * q), vv = ld16(pv + 4 * q);
+        uint32_t* gp = &gm.x; uint32_t* mp = &mm.x; uint32_t* vp = &vv.x;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float gg = __uint_as_float(gp[e]);
+            const float m1 = __fmaf_rn(c1, gg, __fmul_rn(b1, __uint_as_float(mp[e])));
+            const float v1 = __fmaf_rn(c2, __fmul_rn(gg, gg), __fmul_rn(b2, __uint_as_float(vp[e])));
+            mp[e] = __float_as_uint(m1);
+            vp[e] = __float_as_uint(v1);
+            w[4 * q + e] = __fmaf_rn(-step_size, __fdiv_rn(m1, __fadd_rn(__fsqrt_rn(v1), eps)), w[4 * q + e]);
+        }
+        st16(pm + 4 * q, mm);
+        st16(pv + 4 * q, vv);
+    }
+    V16 o16;
+    if (BF16) {
+        o16.x = pack_bf16(w[0], w[1]); o16.y = pack_bf16(w[2], w[3]);
+        o16.z = pack_bf16(w[4 % kF], w[5 % kF]); o16.w = pack_bf16(w[6 % kF], w[7 % kF]);
+    } else {
+        o16.x = __float_as_uint(w[0]); o16.y = __float_as_uint(w[1]); o16.z = __float_as_uint(w[2]); o16.w = __float_as_uint(w[3]);
+    }
+    st16(pw, o16);
+}
+
 } // namespace
 
 extern "C" {
@@ -618,6 +679,26 @@ int grad_segment_reduce_pooled(const float* d_pooled, const int64_t* bag_off, in
     MTGR_LAUNCH_CHECK();
     // gradient of position i = scaled[bag_of[i]]; summed per distinct key in the usual fixed order
     return reduce_dispatch(scaled, EMB_F32, seg_of, perm, bag_of, n, dim, reduced, ws + L.reduce, workspace_bytes - L.reduce, s);
+}
+
+int ht_apply_adam(emb_table_t* t, const int32_t* row_idx, const float* reduced, const int64_t* n_dev, int64_t n_max,
+                  float lr, float beta1, float beta2, float eps, int64_t step, void* stream) {
+    if (!t || n_max < 0 || n_max > 0x7FFFFFFFll || step < 1) return EMB_ERR_INVALID_ARG;
+    if (!(beta1 >= 0.0f && beta1 < 1.0f && beta2 >= 0.0f && beta2 < 1.0f)) return EMB_ERR_INVALID_ARG;
+    if (n_max == 0) return EMB_OK;
+    if (!row_idx || !reduced || (reinterpret_cast<uintptr_t>(reduced) & 15)) return EMB_ERR_INVALID_ARG;
+    HtView v = t->view();
+    if (!v.has_adam) return EMB_ERR_NO_STORAGE; // moment rows must be registered for every chunk
+    const double bc1 = 1.0 - std::pow((double)beta1, (double)step), bc2 = 1.0 - std::pow((double)beta2, (double)step);
+    const float step_size = (float)((double)lr * std::sqrt(bc2) / bc1);
+    const bool bf = t->desc.dtype == EMB_BF16;
+    const int per_row = t->desc.dim / (bf ? 8 : 4);
+    const unsigned grid = (unsigned)((n_max * per_row + kBlock - 1) / kBlock);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (bf) hipLaunchKernelGGL(k_adam<true>, dim3(grid), dim3(kBlock), 0, s, v, row_idx, reduced, n_dev, n_max, step_size, beta1, beta2, eps);
+    else hipLaunchKernelGGL(k_adam<false>, dim3(grid), dim3(kBlock), 0, s, v, row_idx, reduced, n_dev, n_max, step_size, beta1, beta2, eps);
+    MTGR_LAUNCH_CHECK();
+    return EMB_OK;
 }
 
 int ht_apply_adagrad(emb_table_t* t, const int32_t* row_idx, const float* reduced, const int64_t* n_dev,

@@ -36,11 +36,20 @@ __global__ void k_zero_bytes(uint32_t* p, size_t n_words) {
     if (i < n_words) p[i] = 0u;
 }
 
+__global__ void k_set_adam(HtState* st, int c, float* m, float* v) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        st->adam_m[c] = m;
+        st->adam_v[c] = v;
+    }
+}
+
 __global__ void k_set_chunk(HtState* st, int c, void* values, RowMeta* meta, uint32_t* free_list, uint64_t rows) {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
         st->values[c] = values;
         st->meta[c] = meta;
         st->free_list[c] = free_list;
+        st->adam_m[c] = nullptr;
+        st->adam_v[c] = nullptr;
     }
     // unused rows keep freq == 0 (see k_find_or_insert)
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
@@ -331,12 +340,26 @@ __global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const ui
     // ---- initialise the new rows, the whole wave writing one row at a time (coalesced).  Every
     // creating lane resolves its own row address first, so the loop has no dependent loads.
     const uint64_t my_dst = my_created ? reinterpret_cast<uint64_t>(chunk_row_ptr(v, my_row)) : 0ull;
+    uint64_t my_m = 0ull, my_v = 0ull; // moment rows of the new row, when an Adam state is registered
+    if (my_created && v.has_adam) {
+        const size_t o = (size_t)(my_row & ((1u << v.chunk_log2) - 1u)) * (size_t)v.dim;
+        my_m = reinterpret_cast<uint64_t>(v.st->adam_m[my_row >> v.chunk_log2] + o);
+        my_v = reinterpret_cast<uint64_t>(v.st->adam_v[my_row >> v.chunk_log2] + o);
+    }
     uint64_t m_init = __ballot(my_created);
     while (m_init) {
         const int src = __ffsll((unsigned long long)m_init) - 1;
         m_init &= m_init - 1;
         const uint64_t k = shfl64(my_key, src);
         char* dst = reinterpret_cast<char*>(shfl64(my_dst, src));
+        if (v.has_adam) {
+            float* pm = reinterpret_cast<float*>(shfl64(my_m, src));
+            float* pv = reinterpret_cast<float*>(shfl64(my_v, src));
+            for (int j = lane; j < v.dim; j += kWave) {
+                pm[j] = 0.0f;
+                pv[j] = 0.0f;
+            }
+        }
         if (v.dtype == EMB_F32) {
             for (int j = lane; j < v.dim; j += kWave) reinterpret_cast<float*>(dst)[j] = init_value(k, j, v.init_c);
         } else {
@@ -635,6 +658,7 @@ int emb_table_create(emb_table_t** out, const emb_table_desc_t* desc, void* stat
     t->slots = nullptr;
     t->cap_log2 = 0;
     t->n_chunks = 0;
+    t->n_adam_chunks = 0;
     t->row_bytes = row_bytes;
     t->n_rehash = 0;
     t->base_live = t->base_tomb = t->base_rows = t->pending = 0;
@@ -704,6 +728,20 @@ int ht_add_chunk(emb_table_t* t, void* values, void* meta, uint32_t* free_list, 
                        t->n_chunks, values, static_cast<RowMeta*>(meta), free_list, rows);
     MTGR_LAUNCH_CHECK();
     t->n_chunks += 1;
+    return EMB_OK;
+}
+
+int ht_add_chunk_adam_state(emb_table_t* t, float* m, float* v, void* stream) {
+    if (!t || !m || !v) return EMB_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(m) & 15) || (reinterpret_cast<uintptr_t>(v) & 15)) return EMB_ERR_INVALID_ARG;
+    if (t->n_adam_chunks >= t->n_chunks) return EMB_ERR_NO_STORAGE; // register the value chunk first
+    // rows already in use in this chunk would start from garbage moments: only allowed while the chunk is unused
+    const uint64_t first_row = (uint64_t)t->n_adam_chunks << t->desc.chunk_rows_log2;
+    t->refresh();
+    if (t->rows_used_bound() > first_row) return EMB_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(k_set_adam, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), t->st, t->n_adam_chunks, m, v);
+    MTGR_LAUNCH_CHECK();
+    t->n_adam_chunks += 1;
     return EMB_OK;
 }
 

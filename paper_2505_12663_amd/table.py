@@ -27,10 +27,11 @@ class EmbeddingTable:
 
     def __init__(self, dim: int, dtype: int = B.F32, capacity_log2: int = 18, chunk_rows_log2: int = 16,
                  init_scale: float = 0.01, max_load_factor: float = 0.75, count_probes: bool = False,
-                 device: str = "cuda:0", initial_chunks: int = 2):
+                 device: str = "cuda:0", initial_chunks: int = 2, adam_state: bool = False):
         self.device = torch.device(device)
         self.dim, self.dtype = dim, dtype
         self.chunk_rows_log2 = chunk_rows_log2
+        self.adam_state = adam_state
         self.torch_dtype = torch.float32 if dtype == B.F32 else torch.bfloat16
         self.state = torch.empty(B.emb_table_state_bytes(), dtype=torch.uint8, device=self.device)
         desc = B.TableDesc(dim, dtype, init_scale, max_load_factor, chunk_rows_log2, int(count_probes))
@@ -61,7 +62,13 @@ class EmbeddingTable:
         meta = torch.empty((n, 4), dtype=torch.int32, device=self.device)        # 16 bytes per row
         free_list = torch.empty(n, dtype=torch.int32, device=self.device)
         B.ht_add_chunk(self.h, values, meta, free_list)
-        self.chunks.append((values, meta, free_list))
+        chunk = (values, meta, free_list)
+        if self.adam_state:
+            m = torch.empty((n, self.dim), dtype=torch.float32, device=self.device)
+            v = torch.empty((n, self.dim), dtype=torch.float32, device=self.device)
+            B.ht_add_chunk_adam_state(self.h, m, v)
+            chunk += (m, v)
+        self.chunks.append(chunk)
 
     def rehash(self, new_capacity_log2: int) -> None:
         new_slots = torch.empty((1 << new_capacity_log2, 2), dtype=torch.int64, device=self.device)
@@ -105,6 +112,10 @@ class EmbeddingTable:
 
     def apply_adagrad(self, row_idx, reduced, n_dev, n_max: int, lr: float, eps: float = 1e-8) -> None:
         B.ht_apply_adagrad(self.h, row_idx, reduced, n_dev, n_max, lr, eps)
+
+    def apply_adam(self, row_idx, reduced, n_dev, n_max: int, lr: float, step: int, beta1: float = 0.9,
+                   beta2: float = 0.999, eps: float = 1e-8) -> None:
+        B.ht_apply_adam(self.h, row_idx, reduced, n_dev, n_max, lr, beta1, beta2, eps, step)
 
     def evict(self, now: int, ttl: int, min_freq: int, grace: int, want_keys: bool = True):
         live = self.stats()["live"]

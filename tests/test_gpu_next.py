@@ -151,3 +151,40 @@ def test_pooled_lookup_forward_and_backward(dim, dtype, mean):
     assert np.array_equal(gk, ok)
     assert close_rows(gv, ov.astype(np.float64), 0.01, RTOL_F32 if dtype == 0 else 1e-2)
     table.close()
+
+
+@pytest.mark.parametrize("dim,dtype", [(64, 0), (32, 0), (128, 1), (16, 0)])
+def test_sparse_adam_matches_checker(dim, dtype):
+    """Lazy Adam on the activated rows only, several steps with new keys arriving and an eviction in
+    between (moment rows of recycled rows must restart from zero)."""
+    rtol = RTOL_F32 if dtype == 0 else 1e-2
+    table = EmbeddingTable(dim, dtype, capacity_log2=13, chunk_rows_log2=10, adam_state=True, initial_chunks=2)
+    ot = oracle.Table(dim, dtype)
+    rng = np.random.default_rng(dim)
+    pool = np.arange(1, 3001, dtype=np.uint64) * np.uint64(104729)
+    for step in range(1, 9):
+        ks = np.unique(pool[rng.integers(0, 300 * step, size=500)])
+        n = len(ks)
+        row_idx = torch.empty(n, dtype=torch.int32, device="cuda")
+        table.find_or_insert(dev_keys(ks), None, n, step, row_idx)
+        ot.find_or_insert(ks, step)
+        g = normal_grads(3, step, n, dim)
+        table.apply_adam(row_idx, torch.from_numpy(g).cuda(), None, n, 1e-3, step)
+        ot.apply_adam(ks, g, 1e-3, step)
+        if step == 5:
+            ev, n_ev = table.evict(step, 3, 0, 0)            # drop keys unseen for 3 steps; their rows get reused
+            oev = ot.evict(step, 3, 0, 0)
+            assert np.array_equal(np.sort(host_keys(ev)), oev) and n_ev > 0
+        gk, gv, ga, gl, gf = table.export()
+        ok, ov, oa, ol, of = ot.export()
+        assert np.array_equal(gk, ok) and np.array_equal(gl, ol) and np.array_equal(gf, of)
+        assert close_rows(gv, ov.astype(np.float64), 1e-3, rtol), float(np.abs(gv - ov).max())
+    st = table.stats()
+    assert st["status"] == 0 and st["n_chunks"] >= 2
+    table.close()
+    # without moment rows the call is refused
+    plain = EmbeddingTable(dim, dtype, capacity_log2=10, chunk_rows_log2=8)
+    r = torch.zeros(4, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.EmbError):
+        plain.apply_adam(r, torch.zeros((4, dim), device="cuda"), None, 4, 1e-3, 1)
+    plain.close()

@@ -398,3 +398,45 @@ def test_pooling_forward_backward_equal_torch_embedding_bag(mode):
     if mode == "sum":
         assert np.array_equal(g, Wt.grad.float().numpy())                             # integers: exact
         assert np.array_equal(G, np.repeat(dY, lens, axis=0))
+
+
+# --------------------------------------------------------------------------- #
+# sparse Adam (Sec. 4.1 trains with Adam): the library routine is torch.optim.SparseAdam
+# --------------------------------------------------------------------------- #
+def test_sparse_adam_equals_torch_sparse_adam():
+    D, n_keys = 6, 30
+    keys = np.arange(100, 100 + n_keys, dtype=np.uint64)
+    t = oracle.Table(D)
+    t.find_or_insert(keys, 0)
+    W0 = t.lookup(keys).astype(np.float64)
+    p = torch.nn.Parameter(torch.from_numpy(W0).clone())
+    lr, b1, b2, eps = float(np.float32(1e-3)), float(np.float32(0.9)), float(np.float32(0.999)), float(np.float32(1e-8))
+    opt = torch.optim.SparseAdam([p], lr=lr, betas=(b1, b2), eps=eps)
+    rng = np.random.default_rng(8)
+    for step in range(1, 7):
+        rows = np.sort(rng.choice(n_keys, size=11, replace=False))            # only these rows are activated
+        g = rng.standard_normal((len(rows), D)).astype(np.float32)
+        t.apply_adam(keys[rows], g, lr, step, b1, b2, eps)
+        p.grad = torch.sparse_coo_tensor(torch.from_numpy(rows[None, :]), torch.from_numpy(g.astype(np.float64)),
+                                         size=(n_keys, D))
+        opt.step()
+        # float64 library result vs checker (float64 math, fp32 state between steps)
+        assert np.allclose(t.lookup(keys), p.detach().numpy(), rtol=3e-6, atol=1e-9)
+    untouched_row = oracle.Table(D)
+    untouched_row.find_or_insert(np.array([7], dtype=np.uint64), 0)
+    untouched_row.apply_adam(np.array([9], dtype=np.uint64), np.ones((1, D), dtype=np.float32), lr, 1)   # absent key: skipped
+    assert np.array_equal(untouched_row.lookup(np.array([7], dtype=np.uint64))[0], oracle.init_row(7, D))
+    with pytest.raises(ValueError):
+        t.apply_adam(keys[:1], np.ones((1, D), dtype=np.float32), lr, 0)
+
+
+def test_sparse_adam_first_step_closed_form():
+    # t = 1: m = (1-b1) g, v = (1-b2) g^2  =>  w -= lr * g / (|g| + eps * sqrt(1-b2)) ~ lr * sign(g)
+    D = 4
+    t = oracle.Table(D)
+    k = np.array([5], dtype=np.uint64)
+    t.find_or_insert(k, 0)
+    w0 = t.lookup(k).astype(np.float64)
+    g = np.array([[2.0, -3.0, 0.5, -0.25]], dtype=np.float32)
+    t.apply_adam(k, g, 0.01, 1)
+    assert np.allclose(t.lookup(k), w0 - 0.01 * np.sign(g), rtol=0, atol=2e-8)
