@@ -279,6 +279,14 @@ int ht_evict(emb_table_t* t, uint32_t now, uint32_t ttl, uint32_t min_freq, uint
 int ht_export(emb_table_t* t, uint64_t* keys, void* values, float* acc, uint32_t* last_seen, uint32_t* freq,
               int64_t cap, int64_t* n, void* stream);
 
+/* Overwrite the contents of existing rows: values[row_idx[u],:] = values_in[u,:] (table dtype) and the
+ * row's accumulator / last-seen step / touch count; any of the four sources may be NULL (left as is),
+ * row index -1 is skipped.  Together with ht_find_or_insert this restores an ht_export dump
+ * (App. C "Checkpoint Resuming": every device saves its own shard; a device of a resized job reads
+ * the dump of rank r mod old_world and keeps the keys it owns). */
+int ht_put(emb_table_t* t, const int32_t* row_idx, const void* values_in, const float* acc, const uint32_t* last_seen,
+           const uint32_t* freq, int64_t n, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

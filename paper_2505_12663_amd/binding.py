@@ -49,7 +49,7 @@ EXPORTS = [
     "ht_stats", "emb_tag_keys", "emb_dedup_workspace_bytes", "emb_dedup", "ht_find_or_insert", "ht_find",
     "ht_gather", "emb_expand", "emb_expand_sorted", "grad_segment_reduce_workspace_bytes", "grad_segment_reduce",
     "ht_apply_adagrad", "ht_apply_adam", "ht_gather_expand_sorted", "emb_pool_workspace_bytes", "emb_pool_bags",
-    "grad_segment_reduce_pooled", "ht_evict", "ht_export",
+    "grad_segment_reduce_pooled", "ht_evict", "ht_export", "ht_put",
 ]
 
 
@@ -94,6 +94,7 @@ def load():
         "grad_segment_reduce_pooled": (C.c_int, [vp, vp, i32, vp, vp, i64, i32, i32, vp, vp, C.c_size_t, vp]),
         "ht_evict": (C.c_int, [vp, u32, u32, u32, u32, vp, i64, vp, vp]),
         "ht_export": (C.c_int, [vp, vp, vp, vp, vp, vp, i64, vp, vp]),
+        "ht_put": (C.c_int, [vp, vp, vp, vp, vp, vp, i64, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -286,3 +287,8 @@ def ht_evict(h, now: int, ttl: int, min_freq: int, grace: int, evicted_keys, n_e
 def ht_export(h, keys, values, acc, last_seen, freq, n, stream=None) -> None:
     _check(load().ht_export(h, _ptr(keys), _ptr(values), _ptr(acc), _ptr(last_seen), _ptr(freq), keys.numel(), _ptr(n),
                             _stream(stream)), "ht_export")
+
+
+def ht_put(h, row_idx, values, acc, last_seen, freq, n: int, stream=None) -> None:
+    _check(load().ht_put(h, _ptr(row_idx), _ptr(values), _ptr(acc), _ptr(last_seen), _ptr(freq), n, _stream(stream)),
+           "ht_put")

@@ -436,6 +436,31 @@ __global__ __launch_bounds__(kBlock) void k_adagrad(HtView v, const int32_t* __r
     }
 }
 
+// ---------------------------------------------------------------------------- put rows (checkpoint import)
+// values[row_idx[u],:] = src[u,:] and the row record = (acc[u], last_seen[u], freq[u]): the inverse of
+// gather + export, used to restore a dump into a table.  16-byte vectors, one lane per vector.
+__global__ __launch_bounds__(kBlock) void k_put_rows(HtView v, const int32_t* __restrict__ row_idx,
+                                                     const char* __restrict__ src, const float* __restrict__ acc,
+                                                     const uint32_t* __restrict__ last_seen,
+                                                     const uint32_t* __restrict__ freq, int64_t n) {
+    const int vecs = v.row_bytes / 16;
+    const int64_t item = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t u = item / vecs;
+    const int sub = (int)(item % vecs);
+    if (u >= n) return;
+    const int ri = row_idx[u];
+    if (ri < 0) return;
+    const uint32_t row = (uint32_t)ri;
+    char* dst = const_cast<char*>(chunk_row_cptr(v, row));
+    if (src) st16(dst + sub * 16, ld16(src + (size_t)u * v.row_bytes + sub * 16));
+    if (sub == 0) {
+        RowMeta* m = &v.st->meta[row >> v.chunk_log2][row & ((1u << v.chunk_log2) - 1u)];
+        if (acc) m->acc = acc[u];
+        if (last_seen) m->last_seen = last_seen[u];
+        if (freq) m->freq = freq[u];
+    }
+}
+
 // ---------------------------------------------------------------------------- sparse Adam
 // The optimizer the paper trains with (Sec. 4.1), in its lazy / sparse form: only the listed rows
 // move.  m = b1 m + (1-b1) g;  v = b2 v + (1-b2) g^2;  w -= step_size * m / (sqrt(v) + eps) with
@@ -679,6 +704,21 @@ int grad_segment_reduce_pooled(const float* d_pooled, const int64_t* bag_off, in
     MTGR_LAUNCH_CHECK();
     // gradient of position i = scaled[bag_of[i]]; summed per distinct key in the usual fixed order
     return reduce_dispatch(scaled, EMB_F32, seg_of, perm, bag_of, n, dim, reduced, ws + L.reduce, workspace_bytes - L.reduce, s);
+}
+
+int ht_put(emb_table_t* t, const int32_t* row_idx, const void* values, const float* acc, const uint32_t* last_seen,
+           const uint32_t* freq, int64_t n, void* stream) {
+    if (!t || n < 0 || n > 0x7FFFFFFFll) return EMB_ERR_INVALID_ARG;
+    if (n == 0) return EMB_OK;
+    if (!row_idx || (values && (reinterpret_cast<uintptr_t>(values) & 15))) return EMB_ERR_INVALID_ARG;
+    if (t->n_chunks == 0) return EMB_ERR_NO_STORAGE;
+    HtView v = t->view();
+    const int vecs = t->row_bytes / 16;
+    const unsigned grid = (unsigned)((n * vecs + kBlock - 1) / kBlock);
+    hipLaunchKernelGGL(k_put_rows, dim3(grid), dim3(kBlock), 0, static_cast<hipStream_t>(stream), v, row_idx,
+                       static_cast<const char*>(values), acc, last_seen, freq, n);
+    MTGR_LAUNCH_CHECK();
+    return EMB_OK;
 }
 
 int ht_apply_adam(emb_table_t* t, const int32_t* row_idx, const float* reduced, const int64_t* n_dev, int64_t n_max,

@@ -146,6 +146,30 @@ class EmbeddingTable:
                 last_seen[:cnt].cpu().numpy().view(np.uint32)[order], freq[:cnt].cpu().numpy().view(np.uint32)[order])
 
 
+    def export_device(self):
+        """Unordered dump as device tensors (keys int64, values, acc, last_seen, freq), trimmed to the live count."""
+        live = self.stats()["live"]
+        cap = max(live, 1)
+        keys = torch.empty(cap, dtype=torch.int64, device=self.device)
+        values = torch.empty((cap, self.dim), dtype=self.torch_dtype, device=self.device)
+        acc = torch.empty(cap, dtype=torch.float32, device=self.device)
+        last_seen = torch.empty(cap, dtype=torch.int32, device=self.device)
+        freq = torch.empty(cap, dtype=torch.int32, device=self.device)
+        n = torch.zeros(1, dtype=torch.int64, device=self.device)
+        B.ht_export(self.h, keys, values, acc, last_seen, freq, n)
+        cnt = int(n.item())
+        return keys[:cnt], values[:cnt], acc[:cnt], last_seen[:cnt], freq[:cnt]
+
+    def import_rows(self, keys, values, acc, last_seen, freq, step: int = 0) -> None:
+        """Restore dumped entries: create the keys, then overwrite row contents and records."""
+        n = keys.numel()
+        if n == 0:
+            return
+        row_idx = torch.empty(n, dtype=torch.int32, device=self.device)
+        self.find_or_insert(keys.contiguous(), None, n, step, row_idx)
+        B.ht_put(self.h, row_idx, values.contiguous(), acc.contiguous(), last_seen.contiguous(), freq.contiguous(), n)
+
+
 class StepBuffers:
     """Device buffers of one forward+backward step over at most n_max IDs of one merged table."""
 
