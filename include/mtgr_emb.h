@@ -84,6 +84,10 @@ typedef struct {
     uint64_t cas_attempts;
     uint64_t cas_failures;
     uint64_t alloc_atomics; /* atomics issued by the wave-aggregated row allocator */
+    /* hot store (ht_set_hot_storage); all zero without one */
+    uint64_t hot_rows_used;     /* high-water mark of the hot store's allocator */
+    uint64_t hot_rows_free;     /* hot rows returned by evictions */
+    uint64_t hot_rows_capacity;
 } ht_stats_t;
 
 /* ------------------------------------------------------------------ host-only planning */
@@ -286,6 +290,34 @@ int ht_export(emb_table_t* t, uint64_t* keys, void* values, float* acc, uint32_t
  * the dump of rank r mod old_world and keeps the keys it owns). */
 int ht_put(emb_table_t* t, const int32_t* row_idx, const void* values_in, const float* acc, const uint32_t* last_seen,
            const uint32_t* freq, int64_t n, void* stream);
+
+/* ---- hot / cold rows (App. C "Mixed Precision Training"): a 16-bit table whose frequently used keys
+ * keep an fp32 master row, so that many small updates of a hot row are not lost to 16-bit rounding,
+ * while the bulk of the table stays at 2 bytes per element.
+ *
+ * ht_set_hot_storage attaches the hot store, once, to a table of dtype EMB_BF16: hot_values
+ * [hot_rows, dim] fp32 (16-byte aligned) and hot_free [hot_rows] u32 scratch, both owned by the caller
+ * for the table's lifetime.  With a hot store attached:
+ *   ht_gather / ht_gather_expand_sorted deliver every row in the table dtype, a hot row as its master
+ *     rounded to nearest even;
+ *   ht_apply_adagrad updates a hot row's master in fp32 and a cold row in place as before (the 16-bit
+ *     copy of a hot row is stale from then on and never read);
+ *   ht_evict returns the hot rows of evicted keys to the hot store; ht_export dumps a hot row as its
+ *     rounded master; ht_put refreshes the master of a hot row it overwrites;
+ *   ht_apply_adam is refused (EMB_ERR_INVALID_ARG). */
+int ht_set_hot_storage(emb_table_t* t, float* hot_values, uint32_t* hot_free, int64_t hot_rows, void* stream);
+
+/* Promote by access frequency: every row of row_idx [device; distinct rows, -1 skipped; count as for
+ * ht_gather] that has been touched at least min_freq times and has no master yet gets one (a copy of
+ * its current 16-bit values, which is exact), as long as the hot store has room; the rest stay cold.
+ * *n_promoted [device, optional] receives the number promoted by this call.  Which rows win when the
+ * store runs out is not specified.  EMB_ERR_NO_STORAGE without a hot store. */
+int ht_promote(emb_table_t* t, const int32_t* row_idx, const int64_t* n_dev, int64_t n_max, uint32_t min_freq,
+               int64_t* n_promoted, void* stream);
+
+/* Unordered dump of the masters: keys[cap], values[cap, dim] fp32 (optional); *n [device] = number of
+ * hot rows (may exceed cap; only the first cap are written). */
+int ht_export_hot(emb_table_t* t, uint64_t* keys, float* values, int64_t cap, int64_t* n, void* stream);
 
 #ifdef __cplusplus
 }

@@ -48,6 +48,8 @@ def lib():
         L.orc_dedup.restype = C.c_int64
         L.orc_evict.restype = C.c_int64
         L.orc_export.restype = C.c_int64
+        L.orc_promote.restype = C.c_int64
+        L.orc_export_hot.restype = C.c_int64
         _lib = L
     return _lib
 
@@ -225,6 +227,22 @@ class Table:
                                   C.c_float(beta1), C.c_float(beta2), C.c_float(eps), C.c_int64(step))
         if rc != 0:
             raise ValueError("step must be >= 1")
+
+    def set_hot(self, capacity: int) -> None:
+        """Give a 16-bit table a hot store of `capacity` fp32 masters (App. C, mixed precision)."""
+        if lib().orc_set_hot(self._h, C.c_int64(capacity)) != 0:
+            raise ValueError("hot rows need a bf16 table and a positive capacity")
+
+    def promote(self, key, min_freq: int) -> int:
+        key = self._keys(key)
+        return int(lib().orc_promote(self._h, _p(key, C.c_uint64), C.c_int64(len(key)), C.c_uint32(min_freq)))
+
+    def export_hot(self):
+        n = int(lib().orc_export_hot(self._h, None, None))
+        keys = np.empty(n, dtype=np.uint64)
+        values = np.empty((n, self.dim), dtype=np.float32)
+        lib().orc_export_hot(self._h, _p(keys, C.c_uint64), _p(values, C.c_float))
+        return keys, values
 
     def evict(self, now: int, ttl: int, min_freq: int, grace: int) -> np.ndarray:
         out = np.empty(len(self), dtype=np.uint64)

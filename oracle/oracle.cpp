@@ -34,6 +34,7 @@ struct Row {
     uint32_t last_seen = 0; // step of the last find-or-insert that touched the key
     uint32_t freq = 0;      // number of find-or-insert elements that touched the key
     std::vector<float> m, v; // Adam moments (empty = all zero)
+    bool hot = false;        // 16-bit table only: w holds an fp32 master instead of 16-bit values
 };
 
 struct Table {
@@ -41,6 +42,8 @@ struct Table {
     int dtype;
     float init_scale;
     std::unordered_map<uint64_t, Row> map;
+    int64_t hot_capacity = 0; // masters the hot store can hold (0 = no hot store)
+    int64_t hot_used = 0;
 };
 
 // ---- bf16 <-> float, written out (round to nearest, ties to even) ---------
@@ -97,6 +100,12 @@ Row fresh_row(const Table& t, uint64_t key) {
 }
 
 inline bool key_ok(uint64_t k) { return (k >> 63) == 0; }
+
+// What a lookup delivers for element j of a row: the stored value, a hot row's fp32 master
+// rounded to the table's 16-bit type (App. C "Mixed Precision Training").
+inline float delivered(const Row& r, int j) {
+    return r.hot ? bf16_bits_to_float(float_to_bf16_bits(r.w[j])) : r.w[j];
+}
 
 } // namespace
 
@@ -244,7 +253,7 @@ int orc_lookup(void* h, const uint64_t* key, int64_t n, float* out) {
         if (it == t.map.end()) {
             for (int j = 0; j < t.dim; ++j) o[j] = 0.0f;
         } else {
-            for (int j = 0; j < t.dim; ++j) o[j] = it->second.w[j];
+            for (int j = 0; j < t.dim; ++j) o[j] = delivered(it->second, j);
         }
     }
     return 0;
@@ -263,7 +272,7 @@ int orc_direct_lookup(void* h, const uint64_t* key, int64_t n, uint32_t step, fl
             r.last_seen = step;
             it = t.map.emplace(key[i], std::move(r)).first;
         }
-        for (int j = 0; j < t.dim; ++j) out[i * t.dim + j] = it->second.w[j];
+        for (int j = 0; j < t.dim; ++j) out[i * t.dim + j] = delivered(it->second, j);
     }
     return 0;
 }
@@ -339,7 +348,7 @@ int orc_apply_adagrad(void* h, const uint64_t* key, int64_t n, const float* g, f
         double denom = std::sqrt(acc) + static_cast<double>(eps);
         for (int j = 0; j < D; ++j) {
             double w = static_cast<double>(r.w[j]) - static_cast<double>(lr) * static_cast<double>(g[u * D + j]) / denom;
-            r.w[j] = (t.dtype == kBF16) ? double_to_bf16_float(w) : static_cast<float>(w);
+            r.w[j] = (t.dtype == kBF16 && !r.hot) ? double_to_bf16_float(w) : static_cast<float>(w);
         }
         r.acc = static_cast<float>(acc);
     }
@@ -394,7 +403,10 @@ int64_t orc_evict(void* h, uint32_t now, uint32_t ttl, uint32_t min_freq, uint32
         if (stale || rare) gone.push_back(kv.first);
     }
     std::sort(gone.begin(), gone.end());
-    for (uint64_t k : gone) t.map.erase(k);
+    for (uint64_t k : gone) {
+        if (t.map.at(k).hot) t.hot_used -= 1; // its master goes back to the hot store
+        t.map.erase(k);
+    }
     if (evicted) std::copy(gone.begin(), gone.end(), evicted);
     return static_cast<int64_t>(gone.size());
 }
@@ -410,7 +422,7 @@ int64_t orc_export(void* h, uint64_t* keys, float* values, float* acc, uint32_t*
     for (size_t i = 0; i < ks.size(); ++i) {
         const Row& r = t.map.at(ks[i]);
         if (keys) keys[i] = ks[i];
-        if (values) std::copy(r.w.begin(), r.w.end(), values + i * t.dim);
+        if (values) for (int j = 0; j < t.dim; ++j) values[i * t.dim + j] = delivered(r, j);
         if (acc) acc[i] = r.acc;
         if (last_seen) last_seen[i] = r.last_seen;
         if (freq) freq[i] = r.freq;
@@ -428,12 +440,51 @@ int orc_peek(void* h, const uint64_t* key, int64_t n, uint8_t* present, float* v
         present[i] = it != t.map.end();
         if (!present[i]) continue;
         const Row& r = it->second;
-        if (values) std::copy(r.w.begin(), r.w.end(), values + i * t.dim);
+        if (values) for (int j = 0; j < t.dim; ++j) values[i * t.dim + j] = delivered(r, j);
         if (acc) acc[i] = r.acc;
         if (last_seen) last_seen[i] = r.last_seen;
         if (freq) freq[i] = r.freq;
     }
     return 0;
+}
+
+// ---- hot / cold rows (App. C "Mixed Precision Training") --------------------
+// Frequently used keys of a 16-bit table keep their vector in fp32; the rest stay 16-bit.
+// The hot store holds at most `capacity` masters.
+int orc_set_hot(void* h, int64_t capacity) {
+    Table& t = *static_cast<Table*>(h);
+    if (t.dtype != kBF16 || capacity <= 0) return -1;
+    t.hot_capacity = capacity;
+    return 0;
+}
+// Promote, in the order given, every present key touched at least min_freq times that is not
+// hot yet, while the hot store has room.  The master starts as the row's current 16-bit values.
+// Returns how many were promoted.
+int64_t orc_promote(void* h, const uint64_t* key, int64_t n, uint32_t min_freq) {
+    Table& t = *static_cast<Table*>(h);
+    int64_t done = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        auto it = t.map.find(key[i]);
+        if (it == t.map.end()) continue;
+        Row& r = it->second;
+        if (r.hot || r.freq < min_freq || t.hot_used >= t.hot_capacity) continue;
+        r.hot = true;
+        t.hot_used += 1;
+        done += 1;
+    }
+    return done;
+}
+// Masters ordered by key: keys[n_hot], values[n_hot, dim] (either may be null).  Returns n_hot.
+int64_t orc_export_hot(void* h, uint64_t* keys, float* values) {
+    Table& t = *static_cast<Table*>(h);
+    std::vector<uint64_t> ks;
+    for (const auto& kv : t.map) if (kv.second.hot) ks.push_back(kv.first);
+    std::sort(ks.begin(), ks.end());
+    for (size_t i = 0; i < ks.size(); ++i) {
+        if (keys) keys[i] = ks[i];
+        if (values) std::copy(t.map.at(ks[i]).w.begin(), t.map.at(ks[i]).w.end(), values + i * t.dim);
+    }
+    return static_cast<int64_t>(ks.size());
 }
 
 // bf16 helpers exposed for the tests' own cross-checks.

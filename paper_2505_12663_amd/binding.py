@@ -37,7 +37,8 @@ class TableDesc(C.Structure):
 class HtStats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in
                 ("live", "tombstones", "capacity", "rows_used", "rows_free", "rows_capacity", "n_rehash",
-                 "n_chunks", "status", "lookups", "probes", "cas_attempts", "cas_failures", "alloc_atomics")]
+                 "n_chunks", "status", "lookups", "probes", "cas_attempts", "cas_failures", "alloc_atomics",
+                 "hot_rows_used", "hot_rows_free", "hot_rows_capacity")]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
@@ -49,7 +50,7 @@ EXPORTS = [
     "ht_stats", "emb_tag_keys", "emb_dedup_workspace_bytes", "emb_dedup", "ht_find_or_insert", "ht_find",
     "ht_gather", "emb_expand", "emb_expand_sorted", "grad_segment_reduce_workspace_bytes", "grad_segment_reduce",
     "ht_apply_adagrad", "ht_apply_adam", "ht_gather_expand_sorted", "emb_pool_workspace_bytes", "emb_pool_bags",
-    "grad_segment_reduce_pooled", "ht_evict", "ht_export", "ht_put",
+    "grad_segment_reduce_pooled", "ht_evict", "ht_export", "ht_put", "ht_set_hot_storage", "ht_promote", "ht_export_hot",
 ]
 
 
@@ -95,6 +96,9 @@ def load():
         "ht_evict": (C.c_int, [vp, u32, u32, u32, u32, vp, i64, vp, vp]),
         "ht_export": (C.c_int, [vp, vp, vp, vp, vp, vp, i64, vp, vp]),
         "ht_put": (C.c_int, [vp, vp, vp, vp, vp, vp, i64, vp]),
+        "ht_set_hot_storage": (C.c_int, [vp, vp, vp, i64, vp]),
+        "ht_promote": (C.c_int, [vp, vp, vp, i64, u32, vp, vp]),
+        "ht_export_hot": (C.c_int, [vp, vp, vp, i64, vp, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -292,3 +296,16 @@ def ht_export(h, keys, values, acc, last_seen, freq, n, stream=None) -> None:
 def ht_put(h, row_idx, values, acc, last_seen, freq, n: int, stream=None) -> None:
     _check(load().ht_put(h, _ptr(row_idx), _ptr(values), _ptr(acc), _ptr(last_seen), _ptr(freq), n, _stream(stream)),
            "ht_put")
+
+
+def ht_set_hot_storage(h, hot_values, hot_free, hot_rows: int, stream=None) -> None:
+    _check(load().ht_set_hot_storage(h, _ptr(hot_values), _ptr(hot_free), hot_rows, _stream(stream)), "ht_set_hot_storage")
+
+
+def ht_promote(h, row_idx, n_dev, n_max: int, min_freq: int, n_promoted=None, stream=None) -> None:
+    _check(load().ht_promote(h, _ptr(row_idx), _ptr(n_dev), n_max, min_freq, _ptr(n_promoted), _stream(stream)),
+           "ht_promote")
+
+
+def ht_export_hot(h, keys, values, n, stream=None) -> None:
+    _check(load().ht_export_hot(h, _ptr(keys), _ptr(values), keys.numel(), _ptr(n), _stream(stream)), "ht_export_hot")

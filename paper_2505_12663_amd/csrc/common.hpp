@@ -29,7 +29,7 @@ struct __attribute__((aligned(16))) RowMeta {
     float acc;           // row-wise Adagrad accumulator
     uint32_t last_seen;  // step of the last find-or-insert touch
     uint32_t freq;       // number of touches
-    uint32_t reserved;
+    uint32_t hot;        // 0 = the row lives in its chunk only; h+1 = fp32 master copy in row h of the hot store
 };
 
 // Device-resident table state: counters + chunk directory.  Lives in caller memory.
@@ -41,8 +41,10 @@ struct HtHead {
     unsigned int bump;       // rows handed out by the bump allocator
     int free_count;          // entries on the free-row stack (may dip below 0 inside an insert kernel)
     unsigned int status;     // EMB_DEV_* bits
+    unsigned int hot_bump;   // rows handed out from the hot store
+    int hot_free_count;      // entries on the hot store's free stack
     unsigned int pad0;
-    unsigned long long pad1[14];
+    unsigned long long pad1[13];
     unsigned long long stat[kStatStripes][8]; // [stripe][StatSlot]; live / deleted counts are the sums over stripes
 };
 struct HtState {
@@ -60,9 +62,13 @@ struct HtCounts {
     unsigned int bump;
     int free_count;
     unsigned int status;
+    unsigned int hot_bump;
+    int hot_free_count;
     unsigned long long stat[5];
     static HtCounts from(const HtHead& h) {
         HtCounts c{};
+        c.hot_bump = h.hot_bump;
+        c.hot_free_count = h.hot_free_count;
         c.bump = h.bump;
         c.free_count = h.free_count;
         c.status = h.status;
@@ -88,6 +94,9 @@ struct HtView {
     float init_c;            // init_scale * 2^-23
     int count;               // maintain probe counters
     int has_adam;            // moment rows are registered for every chunk
+    float* hot_values;       // optional fp32 master rows of frequently used keys [hot_capacity, dim]; null = none
+    uint32_t* hot_free;      // free stack of the hot store [hot_capacity]
+    uint32_t hot_capacity;
 };
 
 // ---- slot hash: the 64-bit finalizer of MurmurHash3 (Sec. 3.1 names MurmurHash3) ----------
@@ -182,6 +191,9 @@ struct emb_table {
     int cap_log2;
     int n_chunks;
     int n_adam_chunks;          // chunks that have moment rows registered (in order)
+    float* hot_values;          // device, optional hot store
+    uint32_t* hot_free;
+    uint32_t hot_capacity;
     int row_bytes;
     uint64_t n_rehash;
     // Host-side upper bounds of the device counters: exact values as of some point of the
@@ -246,6 +258,9 @@ struct emb_table {
         v.init_c = desc.init_scale * (1.0f / 8388608.0f);
         v.count = desc.count_probes;
         v.has_adam = (n_chunks > 0 && n_adam_chunks == n_chunks) ? 1 : 0;
+        v.hot_values = hot_values;
+        v.hot_free = hot_free;
+        v.hot_capacity = hot_capacity;
         return v;
     }
 };

@@ -436,6 +436,150 @@ __global__ __launch_bounds__(kBlock) void k_adagrad(HtView v, const int32_t* __r
     }
 }
 
+// ---------------------------------------------------------------------------- hot / cold rows (App. C "Mixed Precision Training")
+// A 16-bit table may keep an fp32 master copy of its frequently used rows in a separate hot
+// store (RowMeta::hot = index + 1).  Lookups deliver every row in the table dtype (hot rows
+// rounded on the way out); the optimizer updates a hot row's master in fp32, so that many small
+// updates are not lost to 16-bit rounding, and a cold row in place as before.  These kernels
+// use one group of LPR lanes per row, 8 elements per lane.
+
+// row -> pointer to its 16-byte record
+__device__ inline RowMeta* meta_ptr(const HtView& v, uint32_t row) {
+    return &v.st->meta[row >> v.chunk_log2][row & ((1u << v.chunk_log2) - 1u)];
+}
+__device__ inline void hot_load8(const float* hp, float* w) {
+    const V16 a = ld16(hp), b = ld16(hp + 4);
+    w[0] = __uint_as_float(a.x); w[1] = __uint_as_float(a.y); w[2] = __uint_as_float(a.z); w[3] = __uint_as_float(a.w);
+    w[4] = __uint_as_float(b.x); w[5] = __uint_as_float(b.y); w[6] = __uint_as_float(b.z); w[7] = __uint_as_float(b.w);
+}
+__device__ inline void hot_store8(float* hp, const float* w) {
+    st16(hp, V16{__float_as_uint(w[0]), __float_as_uint(w[1]), __float_as_uint(w[2]), __float_as_uint(w[3])});
+    st16(hp + 4, V16{__float_as_uint(w[4]), __float_as_uint(w[5]), __float_as_uint(w[6]), __float_as_uint(w[7])});
+}
+__device__ inline void unpack8(const V16& c, float* w) {
+    w[0] = bf16lo(c.x); w[1] = bf16hi(c.x); w[2] = bf16lo(c.y); w[3] = bf16hi(c.y);
+    w[4] = bf16lo(c.z); w[5] = bf16hi(c.z); w[6] = bf16lo(c.w); w[7] = bf16hi(c.w);
+}
+__device__ inline V16 pack8(const float* w) {
+    return V16{pack_bf16(w[0], w[1]), pack_bf16(w[2], w[3]), pack_bf16(w[4], w[5]), pack_bf16(w[6], w[7])};
+}
+__global__ void k_zero_words(uint32_t* p, int n) {
+    if ((int)threadIdx.x < n) p[threadIdx.x] = 0u;
+}
+template <int LPR>
+__device__ inline int64_t group_item() {
+    constexpr int kGroups = kWave / LPR;
+    return ((int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave) * kGroups + lane_id() / LPR;
+}
+template <int LPR>
+constexpr int rows_per_block() { return (kBlock / kWave) * (kWave / LPR); }
+
+// Give the rows of row_idx that were touched at least min_freq times and have no master yet one
+// from the hot store (free stack first, then the bump pointer); rows stay cold when it is full.
+template <int LPR>
+__global__ __launch_bounds__(kBlock) void k_promote(HtView v, const int32_t* __restrict__ row_idx, const int64_t* n_dev,
+                                                    int64_t n_max, uint32_t min_freq, unsigned long long* n_promoted) {
+    const int64_t n = read_count(n_dev, n_max);
+    const int lane = lane_id(), sub = lane % LPR;
+    const int64_t u = group_item<LPR>();
+    const int idx = u < n ? row_idx[u] : -1;
+    int h = -1;
+    if (sub == 0 && idx >= 0) {
+        const RowMeta* m = meta_ptr(v, (uint32_t)idx);
+        if (m->freq >= min_freq && m->hot == 0) {
+            HtHead* hd = &v.st->head;
+            const int f = atomicSub(&hd->hot_free_count, 1); // an entry is taken only by who sees a positive count
+            if (f > 0) {
+                h = (int)v.hot_free[f - 1];
+            } else {
+                atomicAdd(&hd->hot_free_count, 1);
+                const unsigned b = atomicAdd(&hd->hot_bump, 1u);
+                if (b < v.hot_capacity) h = (int)b;
+                else atomicSub(&hd->hot_bump, 1u);
+            }
+        }
+    }
+    h = __shfl(h, lane - sub, kWave);
+    if (h < 0) return;
+    if (sub * 8 < v.dim) {
+        float w[8];
+        unpack8(ld16(chunk_row_cptr(v, (uint32_t)idx) + sub * 16), w);
+        hot_store8(v.hot_values + (size_t)h * v.dim + sub * 8, w);
+    }
+    if (sub == 0) {
+        meta_ptr(v, (uint32_t)idx)->hot = (uint32_t)h + 1u;
+        if (n_promoted) atomicAdd(n_promoted, 1ull);
+    }
+}
+
+// out[dst,:] = row (source index = via ? via[index[j]] : index[j]; dst = dst_index ? dst_index[j] : j);
+// index -1 gives a zero row.
+template <int LPR>
+__global__ __launch_bounds__(kBlock) void k_gather_mixed(HtView v, const int32_t* __restrict__ index,
+                                                         const int32_t* __restrict__ via,
+                                                         const int32_t* __restrict__ dst_index, const int64_t* n_dev,
+                                                         int64_t n_max, char* __restrict__ out) {
+    const int64_t n = read_count(n_dev, n_max);
+    const int sub = lane_id() % LPR;
+    const int64_t j = group_item<LPR>();
+    if (j >= n || sub * 8 >= v.dim) return;
+    int idx = index[j];
+    if (via && idx >= 0) idx = via[idx];
+    const int64_t dst = dst_index ? (int64_t)dst_index[j] : j;
+    char* o = out + (size_t)dst * v.row_bytes + sub * 16;
+    if (idx < 0) {
+        st16(o, V16{0u, 0u, 0u, 0u});
+        return;
+    }
+    const uint32_t hot = meta_ptr(v, (uint32_t)idx)->hot;
+    if (hot != 0) {
+        float w[8];
+        hot_load8(v.hot_values + (size_t)(hot - 1u) * v.dim + sub * 8, w);
+        st16(o, pack8(w));
+    } else {
+        st16(o, ld16(chunk_row_cptr(v, (uint32_t)idx) + sub * 16));
+    }
+}
+
+// Row-wise Adagrad with the arithmetic of k_adagrad; a hot row's master stays in fp32.
+template <int LPR>
+__global__ __launch_bounds__(kBlock) void k_adagrad_mixed(HtView v, const int32_t* __restrict__ row_idx,
+                                                          const float* __restrict__ g, const int64_t* n_dev,
+                                                          int64_t n_max, float lr, float eps) {
+    const int64_t n = read_count(n_dev, n_max);
+    const int sub = lane_id() % LPR;
+    const int64_t u = group_item<LPR>();
+    const bool lane_on = sub * 8 < v.dim;
+    const int idx = u < n ? row_idx[u] : -1;
+    float gv[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) gv[e] = 0.0f;
+    if (idx >= 0 && lane_on) hot_load8(g + (size_t)u * v.dim + sub * 8, gv);
+    const float ss = sumsq_group<LPR>(sumsq_lane<8>(gv));
+    if (idx < 0) return;
+    RowMeta* m = meta_ptr(v, (uint32_t)idx);
+    const uint32_t hot = m->hot;
+    const float acc = adagrad_acc(m->acc, ss, __fdiv_rn(1.0f, (float)v.dim));
+    const float scale = adagrad_scale(acc, lr, eps);
+    if (lane_on) {
+        float w[8];
+        if (hot != 0) {
+            float* hp = v.hot_values + (size_t)(hot - 1u) * v.dim + sub * 8;
+            hot_load8(hp, w);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) w[e] = adagrad_w(w[e], gv[e], scale);
+            hot_store8(hp, w);
+        } else {
+            char* wp = const_cast<char*>(chunk_row_cptr(v, (uint32_t)idx)) + sub * 16;
+            unpack8(ld16(wp), w);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) w[e] = adagrad_w(w[e], gv[e], scale);
+            st16(wp, pack8(w));
+        }
+    }
+    if (sub == 0) m->acc = acc;
+}
+
 // ---------------------------------------------------------------------------- put rows (checkpoint import)
 // values[row_idx[u],:] = src[u,:] and the row record = (acc[u], last_seen[u], freq[u]): the inverse of
 // gather + export, used to restore a dump into a table.  16-byte vectors, one lane per vector.
@@ -452,9 +596,18 @@ __global__ __launch_bounds__(kBlock) void k_put_rows(HtView v, const int32_t* __
     if (ri < 0) return;
     const uint32_t row = (uint32_t)ri;
     char* dst = const_cast<char*>(chunk_row_cptr(v, row));
-    if (src) st16(dst + sub * 16, ld16(src + (size_t)u * v.row_bytes + sub * 16));
+    RowMeta* m = &v.st->meta[row >> v.chunk_log2][row & ((1u << v.chunk_log2) - 1u)];
+    if (src) {
+        const V16 x = ld16(src + (size_t)u * v.row_bytes + sub * 16);
+        st16(dst + sub * 16, x);
+        const uint32_t hot = v.hot_values ? m->hot : 0u;
+        if (hot != 0) { // a row with an fp32 master: the master follows
+            float w[8];
+            unpack8(x, w);
+            hot_store8(v.hot_values + (size_t)(hot - 1u) * v.dim + sub * 8, w);
+        }
+    }
     if (sub == 0) {
-        RowMeta* m = &v.st->meta[row >> v.chunk_log2][row & ((1u << v.chunk_log2) - 1u)];
         if (acc) m->acc = acc[u];
         if (last_seen) m->last_seen = last_seen[u];
         if (freq) m->freq = freq[u];
@@ -524,11 +677,47 @@ __global__ __launch_bounds__(kBlock) void k_adam(HtView v, const int32_t* __rest
 
 extern "C" {
 
+// launch K<LPR> for the smallest power-of-two group that covers `vecs` 16-byte vectors of a 16-bit row
+#define MTGR_MIXED_LAUNCH(K, vecs, n_rows, s, ...)                                                                     \
+    do {                                                                                                               \
+        if ((vecs) <= 1) hipLaunchKernelGGL((K<1>), dim3((unsigned)(((n_rows) + rows_per_block<1>() - 1) / rows_per_block<1>())), dim3(kBlock), 0, s, __VA_ARGS__);       \
+        else if ((vecs) <= 2) hipLaunchKernelGGL((K<2>), dim3((unsigned)(((n_rows) + rows_per_block<2>() - 1) / rows_per_block<2>())), dim3(kBlock), 0, s, __VA_ARGS__);  \
+        else if ((vecs) <= 4) hipLaunchKernelGGL((K<4>), dim3((unsigned)(((n_rows) + rows_per_block<4>() - 1) / rows_per_block<4>())), dim3(kBlock), 0, s, __VA_ARGS__);  \
+        else if ((vecs) <= 8) hipLaunchKernelGGL((K<8>), dim3((unsigned)(((n_rows) + rows_per_block<8>() - 1) / rows_per_block<8>())), dim3(kBlock), 0, s, __VA_ARGS__);  \
+        else if ((vecs) <= 16) hipLaunchKernelGGL((K<16>), dim3((unsigned)(((n_rows) + rows_per_block<16>() - 1) / rows_per_block<16>())), dim3(kBlock), 0, s, __VA_ARGS__); \
+        else hipLaunchKernelGGL((K<32>), dim3((unsigned)(((n_rows) + rows_per_block<32>() - 1) / rows_per_block<32>())), dim3(kBlock), 0, s, __VA_ARGS__);                \
+    } while (0)
+
+int ht_promote(emb_table_t* t, const int32_t* row_idx, const int64_t* n_dev, int64_t n_max, uint32_t min_freq,
+               int64_t* n_promoted, void* stream) {
+    if (!t || n_max < 0 || n_max > 0x7FFFFFFFll) return EMB_ERR_INVALID_ARG;
+    if (!t->hot_values) return EMB_ERR_NO_STORAGE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (n_promoted) {
+        hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(n_promoted), 2);
+        MTGR_LAUNCH_CHECK();
+    }
+    if (n_max == 0) return EMB_OK;
+    if (!row_idx) return EMB_ERR_INVALID_ARG;
+    HtView v = t->view();
+    MTGR_MIXED_LAUNCH(k_promote, t->row_bytes / 16, n_max, s, v, row_idx, n_dev, n_max, min_freq,
+                      reinterpret_cast<unsigned long long*>(n_promoted));
+    MTGR_LAUNCH_CHECK();
+    return t->snapshot(s);
+}
+
 int ht_gather(emb_table_t* t, const int32_t* row_idx, const int64_t* n_dev, int64_t n_max, void* out, void* stream) {
     if (!t || n_max < 0 || n_max > 0x7FFFFFFFll) return EMB_ERR_INVALID_ARG;
     if (n_max == 0) return EMB_OK;
     if (!row_idx || !out || (reinterpret_cast<uintptr_t>(out) & 15)) return EMB_ERR_INVALID_ARG;
     if (t->n_chunks == 0) return EMB_ERR_NO_STORAGE;
+    if (t->hot_values) {
+        HtView v = t->view();
+        MTGR_MIXED_LAUNCH(k_gather_mixed, t->row_bytes / 16, n_max, static_cast<hipStream_t>(stream), v, row_idx,
+                          (const int32_t*)nullptr, (const int32_t*)nullptr, n_dev, n_max, static_cast<char*>(out));
+        MTGR_LAUNCH_CHECK();
+        return EMB_OK;
+    }
     return launch_copy_rows<true, false, false>(t->view(), nullptr, row_idx, nullptr, nullptr, n_dev, n_max, t->row_bytes,
                                                 static_cast<char*>(out), static_cast<hipStream_t>(stream));
 }
@@ -564,6 +753,13 @@ int ht_gather_expand_sorted(emb_table_t* t, const int32_t* row_idx, const int32_
     if (n == 0) return EMB_OK;
     if (!row_idx || !seg_of || !perm || !out || (reinterpret_cast<uintptr_t>(out) & 15)) return EMB_ERR_INVALID_ARG;
     if (t->n_chunks == 0) return EMB_ERR_NO_STORAGE;
+    if (t->hot_values) {
+        HtView v = t->view();
+        MTGR_MIXED_LAUNCH(k_gather_mixed, t->row_bytes / 16, n, static_cast<hipStream_t>(stream), v, seg_of, row_idx, perm,
+                          (const int64_t*)nullptr, n, static_cast<char*>(out));
+        MTGR_LAUNCH_CHECK();
+        return EMB_OK;
+    }
     return launch_copy_rows<true, true, true>(t->view(), nullptr, seg_of, row_idx, perm, nullptr, n, t->row_bytes,
                                               static_cast<char*>(out), static_cast<hipStream_t>(stream));
 }
@@ -729,6 +925,7 @@ int ht_apply_adam(emb_table_t* t, const int32_t* row_idx, const float* reduced, 
     if (!row_idx || !reduced || (reinterpret_cast<uintptr_t>(reduced) & 15)) return EMB_ERR_INVALID_ARG;
     HtView v = t->view();
     if (!v.has_adam) return EMB_ERR_NO_STORAGE; // moment rows must be registered for every chunk
+    if (t->hot_values) return EMB_ERR_INVALID_ARG; // fp32 masters are kept for Adagrad only
     const double bc1 = 1.0 - std::pow((double)beta1, (double)step), bc2 = 1.0 - std::pow((double)beta2, (double)step);
     const float step_size = (float)((double)lr * std::sqrt(bc2) / bc1);
     const bool bf = t->desc.dtype == EMB_BF16;
@@ -752,6 +949,11 @@ int ht_apply_adagrad(emb_table_t* t, const int32_t* row_idx, const float* reduce
     const unsigned grid = (unsigned)((n_max + kBlock - 1) / kBlock);
     const int vecs = t->row_bytes / 16;
     const bool bf = t->desc.dtype == EMB_BF16;
+    if (t->hot_values) {
+        MTGR_MIXED_LAUNCH(k_adagrad_mixed, vecs, n_max, s, v, row_idx, reduced, n_dev, n_max, lr, eps);
+        MTGR_LAUNCH_CHECK();
+        return EMB_OK;
+    }
 #define MTGR_ADA(L_)                                                                                                     \
     do {                                                                                                                 \
         if (bf) hipLaunchKernelGGL((k_adagrad<L_, true>), dim3(grid), dim3(kBlock), 0, s, v, row_idx, reduced, n_dev, n_max, lr, eps); \

@@ -477,12 +477,14 @@ __global__ __launch_bounds__(kBigBlock) void k_evict(HtView v, uint64_t n_slots,
     bool go = false;
     uint64_t k = kEmptyKey;
     uint32_t row = kRowInvalid;
+    uint32_t hot = 0;
     if (slot < n_slots) {
         const V16 e = ld16(v.slots + slot);
         k = ((uint64_t)e.y << 32) | e.x;
         row = e.z;
         if (k != kEmptyKey && k != kTombKey && row != kRowInvalid) {
             const RowMeta m = CHUNK_META(v, row);
+            hot = m.hot;
             const uint32_t age = now - m.last_seen;
             const bool stale = ttl > 0 && age >= ttl;
             const bool rare = min_freq > 0 && m.freq < min_freq && age >= grace;
@@ -514,6 +516,8 @@ __global__ __launch_bounds__(kBigBlock) void k_evict(HtView v, uint64_t n_slots,
         st16(v.slots + slot, V16{0xFFFFFFFEu, 0xFFFFFFFFu, kRowInvalid, 0u});
         CHUNK_FREE(v, (unsigned)(s_free_base + r)) = row;
         CHUNK_META(v, row) = RowMeta{0.0f, 0u, 0u, 0u}; // unused rows keep freq == 0
+        if (hot != 0 && v.hot_free) // hot rows are few: one atomic each
+            v.hot_free[atomicAdd(&v.st->head.hot_free_count, 1)] = hot - 1u;
         if (evicted_keys && (int64_t)(s_out_base + r) < evicted_cap) evicted_keys[s_out_base + r] = k;
     }
 }
@@ -589,11 +593,49 @@ __global__ __launch_bounds__(kBlock) void k_export(HtView v, uint64_t n_slots, u
         if ((int64_t)p >= cap) continue;
         const uint32_t* s32 = static_cast<const uint32_t*>(chunk_row_ptr(v, r));
         uint32_t* d32 = reinterpret_cast<uint32_t*>(values + (size_t)p * v.row_bytes);
-        for (int w = lane; w < v.row_bytes / 4; w += kWave) d32[w] = s32[w];
+        const uint32_t hot_r = v.hot_values ? CHUNK_META(v, r).hot : 0u;
+        if (hot_r != 0) { // 16-bit table with an fp32 master for this row: dump the master, rounded
+            const float* hp = v.hot_values + (size_t)(hot_r - 1u) * v.dim;
+            for (int w = lane; w < v.dim / 2; w += kWave) d32[w] = pack_bf16(hp[2 * w], hp[2 * w + 1]);
+        } else {
+            for (int w = lane; w < v.row_bytes / 4; w += kWave) d32[w] = s32[w];
+        }
     }
 }
 
 inline unsigned blocks_for(uint64_t n, int per_block) { return (unsigned)((n + per_block - 1) / per_block); }
+
+// Dump of the fp32 master rows: one lane per slot decides, the wave copies.
+__global__ __launch_bounds__(kBlock) void k_export_hot(HtView v, uint64_t n_slots, uint64_t* keys, float* values,
+                                                       int64_t cap, unsigned long long* n_out) {
+    const int lane = lane_id();
+    const uint64_t slot = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    uint64_t k = 0;
+    uint32_t hot = 0;
+    if (slot < n_slots) {
+        const V16 e = ld16(v.slots + slot);
+        k = ((uint64_t)e.y << 32) | e.x;
+        if (k != kEmptyKey && k != kTombKey && e.z != kRowInvalid) hot = CHUNK_META(v, e.z).hot;
+    }
+    uint64_t m = __ballot(hot != 0);
+    if (!m) return;
+    const int leader = __ffsll((unsigned long long)m) - 1;
+    unsigned long long base = 0;
+    if (lane == leader) base = atomicAdd(n_out, (unsigned long long)__popcll(m));
+    base = shfl64(base, leader);
+    const unsigned long long pos = base + rank_in(m, lane);
+    if (hot != 0 && (int64_t)pos < cap) keys[pos] = k;
+    if (!values) return;
+    while (m) {
+        const int src = __ffsll((unsigned long long)m) - 1;
+        m &= m - 1;
+        const uint32_t h = __shfl(hot, src, kWave) - 1u;
+        const unsigned long long p = shfl64(pos, src);
+        if ((int64_t)p >= cap) continue;
+        const float* hp = v.hot_values + (size_t)h * v.dim;
+        for (int w = lane; w < v.dim; w += kWave) values[(size_t)p * v.dim + w] = hp[w];
+    }
+}
 
 } // namespace
 
@@ -863,6 +905,31 @@ int ht_rehash(emb_table_t* t, void* new_slots, int new_capacity_log2, void* stre
     return t->snapshot(s);
 }
 
+int ht_set_hot_storage(emb_table_t* t, float* hot_values, uint32_t* hot_free, int64_t hot_rows, void* stream) {
+    if (!t || !hot_values || !hot_free || hot_rows <= 0 || hot_rows > 0x7FFFFFFFll) return EMB_ERR_INVALID_ARG;
+    if (t->desc.dtype != EMB_BF16) return EMB_ERR_INVALID_ARG; // fp32 tables have nothing to gain
+    if (reinterpret_cast<uintptr_t>(hot_values) & 15) return EMB_ERR_INVALID_ARG;
+    if (t->hot_values) return EMB_ERR_INVALID_ARG;              // one hot store per table, for its lifetime
+    (void)stream; // counters were zeroed with the state block
+    t->hot_values = hot_values;
+    t->hot_free = hot_free;
+    t->hot_capacity = (uint32_t)hot_rows;
+    return EMB_OK;
+}
+
+int ht_export_hot(emb_table_t* t, uint64_t* keys, float* values, int64_t cap, int64_t* n, void* stream) {
+    if (!t || !keys || !n || cap < 0) return EMB_ERR_INVALID_ARG;
+    if (!t->slots || !t->hot_values) return EMB_ERR_NO_STORAGE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(k_zero_bytes, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(n), (size_t)2);
+    MTGR_LAUNCH_CHECK();
+    const uint64_t n_slots = 1ull << t->cap_log2;
+    hipLaunchKernelGGL(k_export_hot, dim3(blocks_for(n_slots, kBlock)), dim3(kBlock), 0, s, t->view(), n_slots, keys, values, cap,
+                       reinterpret_cast<unsigned long long*>(n));
+    MTGR_LAUNCH_CHECK();
+    return EMB_OK;
+}
+
 int ht_stats(emb_table_t* t, ht_stats_t* out, void* stream) {
     if (!t || !out) return EMB_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -885,6 +952,9 @@ int ht_stats(emb_table_t* t, ht_stats_t* out, void* stream) {
     out->cas_attempts = h.stat[kStatCas];
     out->cas_failures = h.stat[kStatCasFail];
     out->alloc_atomics = h.stat[kStatAlloc];
+    out->hot_rows_used = h.hot_bump;
+    out->hot_rows_free = h.hot_free_count > 0 ? (uint64_t)h.hot_free_count : 0ull;
+    out->hot_rows_capacity = t->hot_capacity;
     // exact numbers replace the running upper bounds; older counter copies are obsolete
     t->adopt(h, 0, t->seq);
     t->min_valid_seq = t->seq + 1;

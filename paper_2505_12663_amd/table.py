@@ -27,7 +27,7 @@ class EmbeddingTable:
 
     def __init__(self, dim: int, dtype: int = B.F32, capacity_log2: int = 18, chunk_rows_log2: int = 16,
                  init_scale: float = 0.01, max_load_factor: float = 0.75, count_probes: bool = False,
-                 device: str = "cuda:0", initial_chunks: int = 2, adam_state: bool = False):
+                 device: str = "cuda:0", initial_chunks: int = 2, adam_state: bool = False, hot_rows: int = 0):
         self.device = torch.device(device)
         self.dim, self.dtype = dim, dtype
         self.chunk_rows_log2 = chunk_rows_log2
@@ -42,6 +42,11 @@ class EmbeddingTable:
         self.chunks: List[tuple] = []
         for _ in range(initial_chunks):
             self.add_chunk()
+        self.hot_rows = hot_rows
+        if hot_rows > 0:   # fp32 masters for frequently used keys of a 16-bit table
+            self.hot_values = torch.empty((hot_rows, dim), dtype=torch.float32, device=self.device)
+            self.hot_free = torch.empty(hot_rows, dtype=torch.int32, device=self.device)
+            B.ht_set_hot_storage(self.h, self.hot_values, self.hot_free, hot_rows)
 
     def close(self) -> None:
         if self.h is not None:
@@ -145,6 +150,20 @@ class EmbeddingTable:
         return (k[order], vals[order], acc[:cnt].cpu().numpy()[order],
                 last_seen[:cnt].cpu().numpy().view(np.uint32)[order], freq[:cnt].cpu().numpy().view(np.uint32)[order])
 
+    def promote(self, row_idx, n_dev, n_max: int, min_freq: int, n_promoted=None) -> None:
+        B.ht_promote(self.h, row_idx, n_dev, n_max, min_freq, n_promoted)
+
+    def export_hot(self):
+        """Host copy of the fp32 masters, sorted by key: (keys uint64, values float32 [n, dim])."""
+        cap = max(self.hot_rows, 1)
+        keys = torch.empty(cap, dtype=torch.int64, device=self.device)
+        values = torch.empty((cap, self.dim), dtype=torch.float32, device=self.device)
+        n = torch.zeros(1, dtype=torch.int64, device=self.device)
+        B.ht_export_hot(self.h, keys, values, n)
+        cnt = int(n.item())
+        k = keys[:cnt].cpu().numpy().view(np.uint64)
+        order = np.argsort(k, kind="stable")
+        return k[order], values[:cnt].cpu().numpy()[order]
 
     def export_device(self):
         """Unordered dump as device tensors (keys int64, values, acc, last_seen, freq), trimmed to the live count."""

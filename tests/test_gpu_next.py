@@ -233,3 +233,179 @@ def test_checkpoint_dump_restores_and_reshards_by_modulo():
     assert close_rows(ref[1], ov.astype(np.float64), 0.01, RTOL_F32)
     for t in [src, same] + shards:
         t.close()
+
+
+# --------------------------------------------------------------------------- hot / cold rows
+def _bf16_rows(t: torch.Tensor) -> np.ndarray:
+    return t.float().cpu().numpy()
+
+
+def _mixed_pair(dim, hot_rows, cap_log2=14):
+    from harness import RTOL_BF16  # noqa: F401
+    table = EmbeddingTable(dim, B.BF16, capacity_log2=cap_log2, chunk_rows_log2=11, hot_rows=hot_rows)
+    ot = oracle.Table(dim, oracle.BF16)
+    ot.set_hot(hot_rows)
+    return table, ot
+
+
+def _insert(table, ot, ks, step):
+    row_idx = torch.empty(len(ks), dtype=torch.int32, device="cuda")
+    table.find_or_insert(dev_keys(ks), None, len(ks), step, row_idx)
+    ot.find_or_insert(ks, step)
+    return row_idx
+
+
+@pytest.mark.parametrize("dim", [64, 24, 256])
+def test_hot_cold_rows_match_checker(dim):
+    """App. C mixed precision: keys touched often get an fp32 master, the rest stay 16-bit.  Promotion set, masters,
+    delivered rows and the store's bookkeeping must follow the checker; a hot row's master to fp32 accuracy."""
+    from harness import RTOL_BF16
+    lr, eps = 0.05, 1e-8
+    table, ot = _mixed_pair(dim, hot_rows=3000)
+    rng = np.random.default_rng(dim)
+    pool = (np.arange(1, 3001, dtype=np.uint64) * np.uint64(0x9E3779B1)) & np.uint64((1 << 40) - 1)
+    # popularity: key i is drawn with weight 1/(i+1)
+    wts = 1.0 / np.arange(1, 3001)
+    wts /= wts.sum()
+    for step in range(6):
+        ks = np.unique(pool[rng.choice(3000, size=900, p=wts)])
+        _insert(table, ot, ks, step)
+    allk = np.sort(pool)
+    row_idx = torch.empty(len(allk), dtype=torch.int32, device="cuda")
+    table.find(dev_keys(allk), None, len(allk), row_idx)
+    present = row_idx.cpu().numpy() >= 0
+    n_prom = torch.zeros(1, dtype=torch.int64, device="cuda")
+    table.promote(row_idx, None, len(allk), 4, n_prom)
+    want = ot.promote(allk[present], 4)
+    assert 0 < want < 3000 and int(n_prom.item()) == want
+    hk, hv = table.export_hot()
+    ok, ov = ot.export_hot()
+    assert np.array_equal(hk, ok) and np.array_equal(hv, ov)          # a fresh master is the 16-bit row, exactly
+    table.promote(row_idx, None, len(allk), 4, n_prom)
+    assert int(n_prom.item()) == 0                                     # nothing is promoted twice
+    st = table.stats()
+    assert st["hot_rows_used"] == want and st["hot_rows_capacity"] == 3000
+    # optimizer steps on random subsets, hot and cold rows mixed
+    for step in range(6, 14):
+        ks = np.unique(pool[rng.choice(3000, size=700, p=wts)])
+        ri = _insert(table, ot, ks, step)
+        g = normal_grads(3, step, len(ks), dim)
+        table.apply_adagrad(ri, torch.from_numpy(g).cuda(), None, len(ks), lr, eps)
+        ot.apply_adagrad(ks, g, lr, eps)
+    hk, hv = table.export_hot()
+    ok, ov = ot.export_hot()
+    assert np.array_equal(hk, ok)
+    assert close_rows(hv, ov.astype(np.float64), lr, RTOL_F32)        # masters: fp32 accuracy
+    # delivered rows: gather and the fused lookup agree with each other and with the checker
+    keys_now, vals_now, acc_now, _, freq_now = ot.export()
+    row_idx = torch.empty(len(keys_now), dtype=torch.int32, device="cuda")
+    table.find(dev_keys(keys_now), None, len(keys_now), row_idx)
+    out = torch.empty((len(keys_now), dim), dtype=torch.bfloat16, device="cuda")
+    table.gather(row_idx, None, len(keys_now), out)
+    got = _bf16_rows(out)
+    assert close_rows(got, vals_now.astype(np.float64), lr, RTOL_BF16)
+    never = acc_now == 0
+    assert never.any() and np.array_equal(got[never], vals_now[never])
+    ident = torch.arange(len(keys_now), dtype=torch.int32, device="cuda")
+    fused = torch.empty_like(out)
+    B.ht_gather_expand_sorted(table.h, row_idx, ident, ident, len(keys_now), fused)
+    assert torch.equal(fused.view(torch.int16), out.view(torch.int16))
+    ek, ev, ea, _, ef = table.export()
+    assert np.array_equal(ek, keys_now) and np.array_equal(ef, freq_now)
+    assert np.array_equal(ev, got)                                      # the dump delivers what a lookup delivers
+    # eviction returns masters to the store; re-promotion reuses them before taking new ones
+    gone, n_gone = table.evict(14, 6, 0, 0)
+    assert n_gone > 0 and np.array_equal(np.sort(host_keys(gone)), ot.evict(14, 6, 0, 0))
+    hk2, _ = table.export_hot()
+    ok2, _ = ot.export_hot()
+    assert np.array_equal(hk2, ok2)
+    st = table.stats()
+    assert st["hot_rows_free"] == len(ok) - len(ok2) and st["hot_rows_used"] == want
+    keys_now = ot.export()[0]
+    row_idx = torch.empty(len(keys_now), dtype=torch.int32, device="cuda")
+    table.find(dev_keys(keys_now), None, len(keys_now), row_idx)
+    table.promote(row_idx, None, len(keys_now), 2, n_prom)
+    want2 = ot.promote(keys_now, 2)
+    assert int(n_prom.item()) == want2
+    st = table.stats()
+    reused = min(want2, len(ok) - len(ok2))
+    assert st["hot_rows_free"] == len(ok) - len(ok2) - reused and st["hot_rows_used"] == want + want2 - reused
+    assert np.array_equal(table.export_hot()[0], ot.export_hot()[0])
+    assert st["status"] == 0
+    table.close()
+
+
+def test_hot_store_full_keeps_the_rest_cold():
+    dim = 32
+    table, ot = _mixed_pair(dim, hot_rows=5)
+    ks = np.arange(1, 41, dtype=np.uint64) * np.uint64(1000003)
+    for step in range(3):
+        ri = _insert(table, ot, ks, step)
+    n_prom = torch.zeros(1, dtype=torch.int64, device="cuda")
+    table.promote(ri, None, len(ks), 3, n_prom)
+    assert int(n_prom.item()) == 5 == ot.promote(ks, 3)                # which five is not specified
+    hk, hv = table.export_hot()
+    assert len(hk) == 5 and np.all(np.isin(hk, ks))
+    st = table.stats()
+    assert st["hot_rows_used"] == 5 and st["hot_rows_free"] == 0
+    # every row still updates: the hot ones in fp32, the others in 16-bit
+    g = normal_grads(4, 0, len(ks), dim)
+    w0 = torch.empty((len(ks), dim), dtype=torch.bfloat16, device="cuda")
+    table.gather(ri, None, len(ks), w0)
+    table.apply_adagrad(ri, torch.from_numpy(g).cuda(), None, len(ks), 0.05, 1e-8)
+    w1 = torch.empty_like(w0)
+    table.gather(ri, None, len(ks), w1)
+    ss = (g.astype(np.float64) ** 2).mean(axis=1)
+    want = _bf16_rows(w0).astype(np.float64) - 0.05 * g / (np.sqrt(ss) + 1e-8)[:, None]
+    from harness import RTOL_BF16
+    assert close_rows(_bf16_rows(w1), want, 0.05, RTOL_BF16)
+    hk1, hv1 = table.export_hot()
+    sel = np.searchsorted(ks, hk1)
+    assert close_rows(hv1, want[sel], 0.05, RTOL_F32)
+    table.close()
+
+
+def test_hot_rows_keep_small_updates_on_device():
+    """The property the hot store exists for: a stream of updates, each below half a 16-bit spacing, moves a hot
+    row by their sum and leaves a cold row where it was."""
+    dim, T, lr = 64, 400, 1e-4
+    table = EmbeddingTable(dim, B.BF16, capacity_log2=10, chunk_rows_log2=6, init_scale=1.0, hot_rows=4)
+    ks = np.array([21, 22], dtype=np.uint64)
+    ri = torch.empty(2, dtype=torch.int32, device="cuda")
+    table.find_or_insert(dev_keys(ks), None, 2, 0, ri)
+    table.find_or_insert(dev_keys(ks[:1]), None, 1, 1, ri[:1].clone())
+    table.promote(ri, None, 2, 2)
+    w0 = torch.empty((2, dim), dtype=torch.bfloat16, device="cuda")
+    table.gather(ri, None, 2, w0)
+    g = torch.ones((2, dim), dtype=torch.float32, device="cuda")
+    for _ in range(T):
+        table.apply_adagrad(ri, g, None, 2, lr, 0.0)
+    w1 = torch.empty_like(w0)
+    table.gather(ri, None, 2, w1)
+    a, b = _bf16_rows(w0).astype(np.float64), _bf16_rows(w1).astype(np.float64)
+    shift = lr * np.sum(1.0 / np.sqrt(np.arange(1, T + 1, dtype=np.float64)))      # acc after s steps is s
+    big = np.abs(a) > 0.25
+    assert np.array_equal(b[1][big[1]], a[1][big[1]])                               # cold: unchanged
+    _, hv = table.export_hot()
+    assert np.allclose(hv[0], a[0] - shift, rtol=0, atol=T * 2.0 ** -24)            # hot: the full sum arrived
+    assert np.all(np.abs(b[0] - (a[0] - shift)) <= 2.0 ** -8)
+    table.close()
+
+
+def test_hot_store_argument_checks():
+    t32 = EmbeddingTable(32, B.F32, capacity_log2=10, chunk_rows_log2=6)
+    hv = torch.empty((4, 32), dtype=torch.float32, device="cuda")
+    hf = torch.empty(4, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.EmbError):
+        B.ht_set_hot_storage(t32.h, hv, hf, 4)                     # fp32 tables have no 16-bit form
+    ri = torch.zeros(1, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.EmbError):
+        B.ht_promote(t32.h, ri, None, 1, 1)                        # no hot store
+    tb = EmbeddingTable(32, B.BF16, capacity_log2=10, chunk_rows_log2=6, hot_rows=4, adam_state=True)
+    with pytest.raises(B.EmbError):
+        B.ht_set_hot_storage(tb.h, hv, hf, 4)                      # only once
+    g = torch.zeros((1, 32), dtype=torch.float32, device="cuda")
+    with pytest.raises(B.EmbError):
+        tb.apply_adam(ri, g, None, 1, 1e-3, 1)                     # masters are kept for Adagrad only
+    t32.close()
+    tb.close()

@@ -440,3 +440,75 @@ def test_sparse_adam_first_step_closed_form():
     g = np.array([[2.0, -3.0, 0.5, -0.25]], dtype=np.float32)
     t.apply_adam(k, g, 0.01, 1)
     assert np.allclose(t.lookup(k), w0 - 0.01 * np.sign(g), rtol=0, atol=2e-8)
+
+
+# --------------------------------------------------------------------------- #
+# hot / cold rows (App. C "Mixed Precision Training"): frequently used keys of a 16-bit table keep an
+# fp32 vector so that repeated small updates are not lost to 16-bit rounding
+# --------------------------------------------------------------------------- #
+def test_hot_rows_keep_small_updates_that_cold_rows_lose():
+    D, T, lr = 8, 1000, 1e-4      # total shift 6.2e-3, more than one 16-bit spacing below 1 (3.9e-3)
+    t = oracle.Table(D, oracle.BF16, init_scale=1.0)
+    keys = np.array([11, 12], dtype=np.uint64)
+    t.find_or_insert(keys, 0)
+    t.find_or_insert(keys[:1], 1)                      # key 11 touched twice, key 12 once
+    t.set_hot(4)
+    assert t.promote(keys, 2) == 1                     # only key 11 qualifies
+    assert np.array_equal(t.export_hot()[0], keys[:1])
+    w0 = t.lookup(keys).astype(np.float64)
+    assert np.array_equal(t.export_hot()[1][0], w0[0].astype(np.float32))   # the master starts as the 16-bit values
+    g = np.ones((2, D), dtype=np.float32)
+    for _ in range(T):
+        t.apply_adagrad(keys, g, lr, 0.0)
+    # constant unit gradient: acc after s steps = s, so the total shift is lr * sum_s 1/sqrt(s)
+    shift = lr * np.sum(1.0 / np.sqrt(np.arange(1, T + 1, dtype=np.float64)))
+    master = t.export_hot()[1][0].astype(np.float64)
+    assert np.allclose(master, w0[0] - shift, rtol=0, atol=T * 2.0 ** -25)  # T fp32 roundings of values below 1
+    got = t.lookup(keys).astype(np.float64)
+    big = np.abs(w0) > 0.25                             # there a step of at most 1e-4 is below half a 16-bit spacing
+    assert big[0].any() and big[1].any()
+    assert np.array_equal(got[1][big[1]], w0[1][big[1]])                    # cold: every single update rounds away
+    assert np.all(np.abs(got[0][big[0]] - (w0[0][big[0]] - shift)) <= 2.0 ** -9)   # hot: delivered = rounded master
+    assert np.all(got[0][big[0]] != w0[0][big[0]])
+    assert np.array_equal(got[0], torch.from_numpy(master.astype(np.float32)).to(torch.bfloat16).float().numpy())
+
+
+def test_hot_and_cold_updates_equal_torch_casts():
+    D, n_keys, lr, eps = 16, 12, 0.05, 1e-8
+    keys = np.arange(1, n_keys + 1, dtype=np.uint64) * np.uint64(7919)
+    t = oracle.Table(D, oracle.BF16)
+    t.find_or_insert(keys, 0)
+    t.find_or_insert(keys[::2], 1)
+    t.set_hot(n_keys)
+    assert t.promote(keys, 2) == n_keys // 2
+    hot = np.zeros(n_keys, dtype=bool)
+    hot[::2] = True
+    w = torch.from_numpy(t.lookup(keys)).double()
+    acc = torch.zeros(n_keys, dtype=torch.float64)
+    rng = np.random.default_rng(5)
+    for _ in range(6):
+        g = rng.standard_normal((n_keys, D)).astype(np.float32)
+        t.apply_adagrad(keys, g, lr, eps)
+        gd = torch.from_numpy(g).double()
+        acc_new = acc + (gd * gd).mean(dim=1)             # used unrounded within the step, stored as fp32
+        new = w - float(np.float32(lr)) * gd / (acc_new.sqrt() + float(np.float32(eps)))[:, None]
+        acc = acc_new.float().double()
+        as_f32 = new.float()
+        w = torch.where(torch.from_numpy(hot)[:, None], as_f32.double(), new.to(torch.bfloat16).double())
+    assert np.array_equal(t.export_hot()[1], w[torch.from_numpy(hot)].float().numpy())
+    assert np.array_equal(t.lookup(keys), w.float().to(torch.bfloat16).float().numpy())
+
+
+def test_hot_store_capacity_and_release_on_eviction():
+    t = oracle.Table(4, oracle.BF16)
+    keys = np.arange(1, 9, dtype=np.uint64)
+    t.find_or_insert(keys, 0)
+    t.find_or_insert(keys, 1)
+    t.set_hot(3)
+    assert t.promote(keys, 2) == 3 and np.array_equal(t.export_hot()[0], keys[:3])   # in the order given
+    assert t.promote(keys, 2) == 0                                                    # full
+    t.find_or_insert(keys[1:], 50)
+    assert np.array_equal(t.evict(60, 20, 0, 0), keys[:1])                            # key 1 is stale; its master is released
+    assert t.promote(keys, 2) == 1 and np.array_equal(t.export_hot()[0], keys[1:4])
+    with pytest.raises(ValueError):
+        oracle.Table(4).set_hot(3)                                                    # fp32 tables have no cold form
