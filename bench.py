@@ -53,6 +53,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, choices=[2, 5])
     ap.add_argument("--batches", type=int, default=4, help="distinct pre-generated batches cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the fused-lookup and pooled-lookup extra lines (profiling runs: only the step's own kernels)")
     ap.add_argument("--count-probes", action="store_true", help="maintain probe/CAS counters (small overhead)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run plain device-to-device copies of this many MiB (reference kernel of known "
@@ -232,21 +234,22 @@ def main() -> int:
         return n
 
     base = args.warmup + args.steps + len(batches)
-    for s in range(2):
-        one_step_fused(base + s)
-    torch.cuda.synchronize()
-    t_f = time.perf_counter()
-    ids_f = 0
-    for k in range(args.steps):
-        ids_f += one_step_fused(base + 2 + k)
-    torch.cuda.synchronize()
-    wall_f = time.perf_counter() - t_f
-    result["fused_lookup"] = {"ms_per_step": round(wall_f * 1e3 / args.steps, 4), "ids_per_sec": round(ids_f / wall_f, 1),
-                              "note": "ht_gather_expand_sorted replaces ht_gather + emb_expand_sorted: same result, "
-                                      "2 x rowbytes x unique fewer bytes moved"}
+    if not args.no_extras:
+        for s in range(2):
+            one_step_fused(base + s)
+        torch.cuda.synchronize()
+        t_f = time.perf_counter()
+        ids_f = 0
+        for k in range(args.steps):
+            ids_f += one_step_fused(base + 2 + k)
+        torch.cuda.synchronize()
+        wall_f = time.perf_counter() - t_f
+        result["fused_lookup"] = {"ms_per_step": round(wall_f * 1e3 / args.steps, 4), "ids_per_sec": round(ids_f / wall_f, 1),
+                                  "note": "ht_gather_expand_sorted replaces ht_gather + emb_expand_sorted: same result, "
+                                          "2 x rowbytes x unique fewer bytes moved"}
 
     # ---- pooled variant (one vector per sample and field instead of one per position), as an extra line
-    if args.config == 2:
+    if args.config == 2 and not args.no_extras:
         lens0 = np.concatenate(lengths_of[0]).astype(np.int64)
         bag_off = torch.from_numpy(np.concatenate([[0], np.cumsum(lens0)]).astype(np.int64)).to(dev)
         nb = len(lens0)
