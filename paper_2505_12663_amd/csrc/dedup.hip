@@ -9,6 +9,10 @@
 // LDS and writes runs of equal digit contiguously.
 #include "common.hpp"
 
+#ifndef MTGR_SC_THREADS
+#define MTGR_SC_THREADS 512
+#endif
+
 using namespace mtgr;
 
 namespace {
@@ -19,6 +23,9 @@ constexpr int kTile = kThreads * kItems;      // 4096 keys per block
 constexpr int kWaves = kThreads / kWave;      // 4
 constexpr int kRadix = 256;
 constexpr int kPasses = 8;
+constexpr int kScThreads = MTGR_SC_THREADS;    // scatter kernel: same tile, more and lighter threads
+constexpr int kScItems = kTile / kScThreads;
+constexpr int kScWaves = kScThreads / kWave;
 
 struct DdHeader {
     unsigned long long or_mask, and_mask;
@@ -158,10 +165,26 @@ __global__ __launch_bounds__(kThreads) void k_rs_hist(DdBuffers b, const DdHeade
     __syncthreads();
     const uint64_t* keys = sel_keys(b, h->src[pass]);
     const int64_t base = (int64_t)blockIdx.x * kTile + (threadIdx.x / kWave) * (kWave * kItems) + (threadIdx.x % kWave);
+    // From the second pass on equal keys sit next to each other, and a popular key fills whole
+    // tiles: 64 lanes adding to one LDS counter would be served one after the other.  Neighbouring
+    // lanes with the same digit are therefore counted as one run and added once by the run's first lane.
+    const int lane = lane_id();
+    unsigned d[kItems];
 #pragma unroll
     for (int it = 0; it < kItems; ++it) {
-        int64_t e = base + it * kWave;
-        if (e < n) atomicAdd(&s_hist[digit_of(keys[e], pass)], 1u);
+        const int64_t e = base + it * kWave;
+        d[it] = e < n ? digit_of(keys[e], pass) : kRadix; // kRadix = no key
+    }
+#pragma unroll
+    for (int it = 0; it < kItems; ++it) {
+        const unsigned prev = __shfl_up(d[it], 1, kWave);
+        const bool head = lane == 0 || d[it] != prev;
+        const uint64_t heads = __ballot(head);
+        if (head && d[it] < (unsigned)kRadix) {
+            const uint64_t rest = (heads >> lane) >> 1;
+            const unsigned len = rest ? (unsigned)__ffsll((unsigned long long)rest) : (unsigned)(kWave - lane);
+            atomicAdd(&s_hist[d[it]], len);
+        }
     }
     __syncthreads();
     tile_hist[(size_t)threadIdx.x * n_tiles + blockIdx.x] = s_hist[threadIdx.x];
@@ -199,16 +222,22 @@ __global__ __launch_bounds__(kThreads) void k_rs_scan(const DdHeader* __restrict
     if (threadIdx.x == 0) digit_total[blockIdx.x] = s_carry;
 }
 
-__global__ __launch_bounds__(kThreads) void k_rs_scatter(DdBuffers b, const DdHeader* __restrict__ h, int pass,
+// tile element e = wave*(64*kScItems) + item*64 + lane
+__global__ __launch_bounds__(kScThreads) void k_rs_scatter(DdBuffers b, const DdHeader* __restrict__ h, int pass,
                                                         int64_t n, unsigned n_tiles,
                                                         const unsigned* __restrict__ tile_hist,
                                                         const unsigned* __restrict__ digit_total) {
     if (!h->active[pass]) return;
-    __shared__ uint64_t s_key[kTile];
-    __shared__ uint32_t s_idx[kTile];
-    __shared__ unsigned s_cnt[kWaves][kRadix];   // per wave: keys seen per digit, then exclusive offsets
-    __shared__ unsigned s_start[kRadix];         // first position of digit d in the sorted tile
-    __shared__ long long s_delta[kRadix];        // global position - tile position for digit d
+    // LDS: the reordered tile (48 KB) and, before it is filled, the counters in the same memory;
+    // only the per-digit output offsets live apart.  49 KB per block lets three blocks share a CU.
+    __shared__ __attribute__((aligned(16))) unsigned char s_raw[kTile * 12];
+    __shared__ unsigned s_delta[kRadix];         // global position - tile position for digit d (mod 2^32)
+    uint64_t* s_key = reinterpret_cast<uint64_t*>(s_raw);
+    uint32_t* s_idx = reinterpret_cast<uint32_t*>(s_raw + (size_t)kTile * 8);
+    unsigned (*s_cnt)[kRadix] = reinterpret_cast<unsigned (*)[kRadix]>(s_raw);            // [kScWaves][kRadix]
+    unsigned* s_start = reinterpret_cast<unsigned*>(s_raw) + kScWaves * kRadix;             // [kRadix]
+    unsigned* s_wt = s_start + kRadix;                                                    // [kWaves]
+    unsigned* s_wg = s_wt + kScWaves;                                                       // [kWaves]
 
     const int src = h->src[pass], dst = h->dst[pass];
     const uint64_t* in_k = sel_keys(b, src);
@@ -219,15 +248,15 @@ __global__ __launch_bounds__(kThreads) void k_rs_scatter(DdBuffers b, const DdHe
     const int lane = lane_id(), wave = threadIdx.x / kWave;
     const int64_t tile_base = (int64_t)blockIdx.x * kTile;
     const int tile_n = (int)((n - tile_base) < kTile ? (n - tile_base) : kTile);
-    for (int w = 0; w < kWaves; ++w) s_cnt[w][threadIdx.x] = 0u;
+    for (int i = threadIdx.x; i < kScWaves * kRadix; i += kScThreads) s_cnt[0][i] = 0u;
     __syncthreads();
 
-    uint64_t key[kItems];
-    uint32_t idx[kItems];
-    unsigned rnk[kItems];
-    const int e0 = wave * (kWave * kItems) + lane;
+    uint64_t key[kScItems];
+    uint32_t idx[kScItems];
+    unsigned rnk[kScItems];
+    const int e0 = wave * (kWave * kScItems) + lane;
 #pragma unroll
-    for (int it = 0; it < kItems; ++it) {
+    for (int it = 0; it < kScItems; ++it) {
         const int e = e0 + it * kWave;
         const bool ok = e < tile_n;
         key[it] = ok ? in_k[tile_base + e] : ~0ull;
@@ -235,7 +264,7 @@ __global__ __launch_bounds__(kThreads) void k_rs_scatter(DdBuffers b, const DdHe
     }
     // rank of every key among the keys of equal digit that precede it in this wave's 1024
 #pragma unroll
-    for (int it = 0; it < kItems; ++it) {
+    for (int it = 0; it < kScItems; ++it) {
         const unsigned d = digit_of(key[it], pass); // padding keys are all ones: digit 255, at the tile's end
         uint64_t peers = ~0ull;
 #pragma unroll
@@ -248,18 +277,18 @@ __global__ __launch_bounds__(kThreads) void k_rs_scatter(DdBuffers b, const DdHe
         if (rank_in(peers, lane) == 0) s_cnt[wave][d] = before + (unsigned)__popcll(peers);
     }
     __syncthreads();
-    // thread d: per-wave exclusive offsets of digit d, tile total, global base
-    {
+    // thread d < 256: per-wave exclusive offsets of digit d, tile total, global base
+    unsigned run = 0, incl_t = 0, incl_g = 0, tot_g = 0;
+    if (threadIdx.x < kRadix) {
         const unsigned d = threadIdx.x;
-        unsigned run = 0;
-        for (int w = 0; w < kWaves; ++w) {
+        for (int w = 0; w < kScWaves; ++w) {
             const unsigned c = s_cnt[w][d];
             s_cnt[w][d] = run;
             run += c;
         }
         // exclusive scans over the 256 digits: tile totals (-> s_start) and global totals
-        unsigned incl_t = run, incl_g = digit_total[d];
-        const unsigned tot_g = incl_g;
+        incl_t = run;
+        incl_g = tot_g = digit_total[d];
         for (int o = 1; o < kWave; o <<= 1) {
             unsigned a = __shfl_up(incl_t, o, kWave), g = __shfl_up(incl_g, o, kWave);
             if (lane >= o) {
@@ -267,12 +296,14 @@ __global__ __launch_bounds__(kThreads) void k_rs_scatter(DdBuffers b, const DdHe
                 incl_g += g;
             }
         }
-        __shared__ unsigned s_wt[kWaves], s_wg[kWaves];
         if (lane == kWave - 1) {
             s_wt[wave] = incl_t;
             s_wg[wave] = incl_g;
         }
-        __syncthreads();
+    }
+    __syncthreads();
+    if (threadIdx.x < kRadix) {
+        const unsigned d = threadIdx.x;
         unsigned off_t = 0, off_g = 0;
         for (int w = 0; w < wave; ++w) {
             off_t += s_wt[w];
@@ -281,20 +312,25 @@ __global__ __launch_bounds__(kThreads) void k_rs_scatter(DdBuffers b, const DdHe
         const unsigned start = off_t + incl_t - run;
         const unsigned gbase = off_g + incl_g - tot_g;
         s_start[d] = start;
-        s_delta[d] = (long long)gbase + (long long)tile_hist[(size_t)d * n_tiles + blockIdx.x] - (long long)start;
+        s_delta[d] = gbase + tile_hist[(size_t)d * n_tiles + blockIdx.x] - start;
+    }
+    __syncthreads();
+    // position of every key in the sorted tile, taken before the tile overwrites the counters
+#pragma unroll
+    for (int it = 0; it < kScItems; ++it) {
+        const unsigned d = digit_of(key[it], pass);
+        rnk[it] += s_start[d] + s_cnt[wave][d];
     }
     __syncthreads();
 #pragma unroll
-    for (int it = 0; it < kItems; ++it) {
-        const unsigned d = digit_of(key[it], pass);
-        const unsigned pos = s_start[d] + s_cnt[wave][d] + rnk[it];
-        s_key[pos] = key[it];
-        s_idx[pos] = idx[it];
+    for (int it = 0; it < kScItems; ++it) {
+        s_key[rnk[it]] = key[it];
+        s_idx[rnk[it]] = idx[it];
     }
     __syncthreads();
-    for (int e = threadIdx.x; e < tile_n; e += kThreads) {
+    for (int e = threadIdx.x; e < tile_n; e += kScThreads) {
         const uint64_t k = s_key[e];
-        const long long g = s_delta[digit_of(k, pass)] + e;
+        const unsigned g = s_delta[digit_of(k, pass)] + (unsigned)e;   // < n < 2^31
         out_k[g] = k;
         out_i[g] = s_idx[e];
     }
@@ -501,7 +537,7 @@ int emb_dedup(const uint64_t* key, int64_t n, uint64_t* uniq, int32_t* inverse, 
     for (int p = 0; p < kPasses; ++p) {
         hipLaunchKernelGGL(k_rs_hist, dim3(n_tiles), dim3(kThreads), 0, s, b, hdr, p, n, n_tiles, tile_hist);
         hipLaunchKernelGGL(k_rs_scan, dim3(kRadix), dim3(kThreads), 0, s, hdr, p, n_tiles, tile_hist, digit_total);
-        hipLaunchKernelGGL(k_rs_scatter, dim3(n_tiles), dim3(kThreads), 0, s, b, hdr, p, n, n_tiles, tile_hist, digit_total);
+        hipLaunchKernelGGL(k_rs_scatter, dim3(n_tiles), dim3(kScThreads), 0, s, b, hdr, p, n, n_tiles, tile_hist, digit_total);
         MTGR_LAUNCH_CHECK();
     }
     hipLaunchKernelGGL(k_heads_count, dim3(n_tiles), dim3(kThreads), 0, s, b, hdr, n, tile_heads);
