@@ -53,6 +53,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, choices=[2, 5])
     ap.add_argument("--batches", type=int, default=4, help="distinct pre-generated batches cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--touch-in-lookup", action="store_true",
+                    help="ht_find_or_insert + ht_apply_adagrad (two updates of every row record per step) instead of "
+                         "ht_find_or_insert_notouch + ht_apply_adagrad_touch (one)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the fused-lookup and pooled-lookup extra lines (profiling runs: only the step's own kernels)")
     ap.add_argument("--count-probes", action="store_true", help="maintain probe/CAS counters (small overhead)")
@@ -130,6 +133,7 @@ def main() -> int:
     v_grad = v_row
 
     phases = ["tag", "dedup", "find_or_insert", "gather", "expand", "reduce", "adagrad"]
+    touch = args.touch_in_lookup   # False: the update writes the row record once per step (touch + accumulator)
 
     def one_step(step: int, ev=None):
         dx, doff, dtag, n, _ = batches[step % len(batches)]
@@ -139,7 +143,7 @@ def main() -> int:
         rec(1)
         B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, None, buf.perm, None, buf.seg_of, buf.n_unique, buf.dedup_ws)
         rec(2)
-        table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted)
+        table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted, touch=touch)
         rec(3)
         table.gather(buf.row_idx, buf.n_unique, n, buf.uniq_rows)
         rec(4)
@@ -147,7 +151,7 @@ def main() -> int:
         rec(5)
         B.grad_segment_reduce(grad, dtype, buf.seg_of, buf.perm, n, dim, buf.reduced, buf.reduce_ws)
         rec(6)
-        table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps)
+        table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps, None if touch else step + 1)
         rec(7)
         return n
 
@@ -206,7 +210,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"config{args.config}:{w.name}", "batch": w.batch, "fields": len(w.features), "dim": dim,
                    "table_keys": n_keys, "capacity_log2": cap_log2, "ids_per_step": int(n_avg),
-                   "unique_per_step": int(u_avg), "new_keys_per_step": round(u_new, 1)},
+                   "unique_per_step": int(u_avg), "new_keys_per_step": round(u_new, 1),
+                   "row_record_updates_per_step": 2 if touch else 1},
         "unique_ids_per_sec": round(u_avg * args.steps / wall, 1),
         "algorithmic_bytes_per_step": ab["total"],
         "achieved_hbm_gbps": round(achieved, 1),
@@ -227,10 +232,10 @@ def main() -> int:
         dx, doff, dtag, n, _ = batches[step % len(batches)]
         B.emb_tag_keys(dx, doff, dtag, tag_bits, buf.key, buf.err_count)
         B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, None, buf.perm, None, buf.seg_of, buf.n_unique, buf.dedup_ws)
-        table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted)
+        table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted, touch=touch)
         B.ht_gather_expand_sorted(table.h, buf.row_idx, buf.seg_of, buf.perm, n, buf.out)
         B.grad_segment_reduce(grad, dtype, buf.seg_of, buf.perm, n, dim, buf.reduced, buf.reduce_ws)
-        table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps)
+        table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps, None if touch else step + 1)
         return n
 
     base = args.warmup + args.steps + len(batches)
@@ -261,11 +266,11 @@ def main() -> int:
             dx, doff, dtag, n, _ = batches[0]
             B.emb_tag_keys(dx, doff, dtag, tag_bits, buf.key, buf.err_count)
             B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, None, buf.perm, None, buf.seg_of, buf.n_unique, buf.dedup_ws)
-            table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted)
+            table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted, touch=touch)
             table.gather(buf.row_idx, buf.n_unique, n, buf.uniq_rows)
             B.emb_pool_bags(buf.uniq_rows, dtype, buf.inverse, bag_off, n, dim, True, pooled, pws)
             B.grad_segment_reduce_pooled(d_pooled, bag_off, buf.seg_of, buf.perm, n, dim, True, buf.reduced, pws)
-            table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps)
+            table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps, None if touch else step + 1)
             return n
 
         base = base + 2 + args.steps

@@ -291,6 +291,21 @@ int ht_export(emb_table_t* t, uint64_t* keys, void* values, float* acc, uint32_t
 int ht_put(emb_table_t* t, const int32_t* row_idx, const void* values_in, const float* acc, const uint32_t* last_seen,
            const uint32_t* freq, int64_t n, void* stream);
 
+/* ---- one record update per training step.
+ * A row's 16-byte record (accumulator, last-seen step, touch count) is a random small access; memory
+ * serves it as a read-modify-write, about as dear as reading the whole row.  A training step that
+ * looks a key up and later updates it can pay this once instead of twice:
+ *   ht_find_or_insert_notouch  = ht_find_or_insert, except that existing keys are not touched and a
+ *     created row starts with last_seen = step and touch count 0;
+ *   ht_apply_adagrad_touch     = ht_apply_adagrad, and every updated row also gets last_seen = step and
+ *     touch count + 1, written together with the accumulator (row_idx must hold distinct rows).
+ * After both calls on the distinct keys of a step the table is in the state that ht_find_or_insert +
+ * ht_apply_adagrad leave.  Keys that are looked up but get no update keep their old record. */
+int ht_find_or_insert_notouch(emb_table_t* t, const uint64_t* key, const int64_t* n_dev, int64_t n_max, uint32_t step,
+                              int32_t* row_idx, uint8_t* inserted, void* stream);
+int ht_apply_adagrad_touch(emb_table_t* t, const int32_t* row_idx, const float* reduced, const int64_t* n_dev,
+                           int64_t n_max, float lr, float eps, uint32_t step, void* stream);
+
 /* ---- hot / cold rows (App. C "Mixed Precision Training"): a 16-bit table whose frequently used keys
  * keep an fp32 master row, so that many small updates of a hot row are not lost to 16-bit rounding,
  * while the bulk of the table stays at 2 bytes per element.

@@ -51,6 +51,7 @@ EXPORTS = [
     "ht_gather", "emb_expand", "emb_expand_sorted", "grad_segment_reduce_workspace_bytes", "grad_segment_reduce",
     "ht_apply_adagrad", "ht_apply_adam", "ht_gather_expand_sorted", "emb_pool_workspace_bytes", "emb_pool_bags",
     "grad_segment_reduce_pooled", "ht_evict", "ht_export", "ht_put", "ht_set_hot_storage", "ht_promote", "ht_export_hot",
+    "ht_find_or_insert_notouch", "ht_apply_adagrad_touch",
 ]
 
 
@@ -81,6 +82,8 @@ def load():
         "emb_dedup_workspace_bytes": (C.c_size_t, [i64]),
         "emb_dedup": (C.c_int, [vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]),
         "ht_find_or_insert": (C.c_int, [vp, vp, vp, i64, u32, vp, vp, vp]),
+        "ht_find_or_insert_notouch": (C.c_int, [vp, vp, vp, i64, u32, vp, vp, vp]),
+        "ht_apply_adagrad_touch": (C.c_int, [vp, vp, vp, vp, i64, f32, f32, u32, vp]),
         "ht_find": (C.c_int, [vp, vp, vp, i64, vp, vp]),
         "ht_gather": (C.c_int, [vp, vp, vp, i64, vp, vp]),
         "emb_expand": (C.c_int, [vp, vp, i64, i32, i32, vp, vp]),
@@ -212,12 +215,14 @@ def emb_dedup(key, n: int, uniq, inverse, counts, perm, seg_off, seg_of, n_uniqu
                             _stream(stream)), "emb_dedup")
 
 
-def ht_find_or_insert(h, key, n_dev, n_max: int, step: int, row_idx, inserted=None, stream=None) -> int:
-    """Returns the status instead of raising for the two "make room first" codes."""
-    rc = load().ht_find_or_insert(h, _ptr(key), _ptr(n_dev), n_max, step, _ptr(row_idx), _ptr(inserted), _stream(stream))
+def ht_find_or_insert(h, key, n_dev, n_max: int, step: int, row_idx, inserted=None, stream=None, touch: bool = True) -> int:
+    """Returns the status instead of raising for the two "make room first" codes.
+    touch=False calls ht_find_or_insert_notouch."""
+    fn = load().ht_find_or_insert if touch else load().ht_find_or_insert_notouch
+    rc = fn(h, _ptr(key), _ptr(n_dev), n_max, step, _ptr(row_idx), _ptr(inserted), _stream(stream))
     if rc in (EMB_ERR_NEED_REHASH, EMB_ERR_NO_STORAGE):
         return rc
-    _check(rc, "ht_find_or_insert")
+    _check(rc, "ht_find_or_insert" if touch else "ht_find_or_insert_notouch")
     return rc
 
 
@@ -251,6 +256,11 @@ def grad_segment_reduce(grad, grad_dtype: int, seg_of, perm, n: int, dim: int, r
 def ht_apply_adagrad(h, row_idx, reduced, n_dev, n_max: int, lr: float, eps: float, stream=None) -> None:
     _check(load().ht_apply_adagrad(h, _ptr(row_idx), _ptr(reduced), _ptr(n_dev), n_max, lr, eps, _stream(stream)),
            "ht_apply_adagrad")
+
+
+def ht_apply_adagrad_touch(h, row_idx, reduced, n_dev, n_max: int, lr: float, eps: float, step: int, stream=None) -> None:
+    _check(load().ht_apply_adagrad_touch(h, _ptr(row_idx), _ptr(reduced), _ptr(n_dev), n_max, lr, eps, step,
+                                         _stream(stream)), "ht_apply_adagrad_touch")
 
 
 def ht_apply_adam(h, row_idx, reduced, n_dev, n_max: int, lr: float, beta1: float, beta2: float, eps: float, step: int,

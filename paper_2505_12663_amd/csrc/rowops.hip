@@ -9,6 +9,10 @@
 
 #include "common.hpp"
 
+#ifndef MTGR_ADA_ROWS
+#define MTGR_ADA_ROWS 2
+#endif
+
 using namespace mtgr;
 
 namespace {
@@ -364,10 +368,13 @@ int launch_reduce(const char* grad, int in_row_bytes, const int32_t* seg_of, con
 // ---------------------------------------------------------------------------- row-wise Adagrad
 // One wave owns 64 consecutive entries of row_idx; an LPR-lane group updates one row:
 // sum of squares by xor-shuffles inside the group, then w -= lr * g / (sqrt(acc) + eps).
-template <int LPR, bool BF16>
+// TOUCH: the row record is rewritten whole - new accumulator, last_seen = step, touch count + 1 -
+// so that a training step updates the record once instead of once per lookup and once per update
+// (a random 16-byte record costs a read-modify-write in memory either way).
+template <int LPR, bool BF16, bool TOUCH>
 __global__ __launch_bounds__(kBlock) void k_adagrad(HtView v, const int32_t* __restrict__ row_idx,
                                                     const float* __restrict__ g, const int64_t* n_dev, int64_t n_max,
-                                                    float lr, float eps) {
+                                                    float lr, float eps, uint32_t step) {
     const int64_t n = read_count(n_dev, n_max);
     const int lane = lane_id();
     const int64_t wave_base = (int64_t)blockIdx.x * kBlock + (threadIdx.x & ~(kWave - 1));
@@ -379,21 +386,40 @@ __global__ __launch_bounds__(kBlock) void k_adagrad(HtView v, const int32_t* __r
     const int my_index = (wave_base + lane < n) ? row_idx[wave_base + lane] : -1;
     const int rows_here = (int)((n - wave_base) < kWave ? (n - wave_base) : kWave);
     const float inv_d = __fdiv_rn(1.0f, (float)v.dim);
+    constexpr int kRows = MTGR_ADA_ROWS;          // rows in flight per group
 #pragma unroll 1
-    for (int r0 = 0; r0 < kWave; r0 += kGroups * 2) {
+    for (int r0 = 0; r0 < kWave; r0 += kGroups * kRows) {
         if (r0 >= rows_here) break;
-        float gv[2][kF];
-        V16 wv[2];
-        int idx[2];
-        bool on[2];
+        float gv[kRows][kF];
+        V16 wv[kRows];
+        int idx[kRows];
+        bool on[kRows];
+        float acc_old[kRows];
+        uint32_t freq_old[kRows], hot_old[kRows];
+        // all loads of the batch go out before anything waits: gradient row, weight row and the
+        // row's accumulator (its own cache line) are independent
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+        for (int u = 0; u < kRows; ++u) {
             const int r = r0 + u * kGroups + grp;
             idx[u] = __shfl(my_index, r & (kWave - 1), kWave);
             on[u] = r < rows_here && idx[u] >= 0;
 #pragma unroll
             for (int e = 0; e < kF; ++e) gv[u][e] = 0.0f;
             wv[u] = V16{0u, 0u, 0u, 0u};
+            acc_old[u] = 0.0f;
+            freq_old[u] = hot_old[u] = 0u;
+            if (on[u]) {
+                const uint32_t row = (uint32_t)idx[u];
+                const RowMeta* m = &v.st->meta[row >> v.chunk_log2][row & ((1u << v.chunk_log2) - 1u)];
+                if (TOUCH) {
+                    const V16 rec = ld16(m);
+                    acc_old[u] = __uint_as_float(rec.x);
+                    freq_old[u] = rec.z;
+                    hot_old[u] = rec.w;
+                } else {
+                    acc_old[u] = m->acc;
+                }
+            }
             if (on[u] && lane_on) {
                 const float* gp = g + (size_t)(wave_base + r) * v.dim + sub * kF;
 #pragma unroll
@@ -408,12 +434,11 @@ __global__ __launch_bounds__(kBlock) void k_adagrad(HtView v, const int32_t* __r
             }
         }
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+        for (int u = 0; u < kRows; ++u) {
             const float ss = sumsq_group<LPR>(sumsq_lane<kF>(gv[u]));
             if (!on[u]) continue;
             const uint32_t row = (uint32_t)idx[u];
-            float* accp = &v.st->meta[row >> v.chunk_log2][row & ((1u << v.chunk_log2) - 1u)].acc;
-            const float acc = adagrad_acc(*accp, ss, inv_d);
+            const float acc = adagrad_acc(acc_old[u], ss, inv_d);
             const float scale = adagrad_scale(acc, lr, eps);
             if (lane_on) {
                 char* wp = const_cast<char*>(chunk_row_cptr(v, row)) + sub * 16;
@@ -431,7 +456,11 @@ __global__ __launch_bounds__(kBlock) void k_adagrad(HtView v, const int32_t* __r
                 }
                 st16(wp, o);
             }
-            if (sub == 0) *accp = acc;
+            if (sub == 0) {
+                RowMeta* m = &v.st->meta[row >> v.chunk_log2][row & ((1u << v.chunk_log2) - 1u)];
+                if (TOUCH) st16(m, V16{__float_as_uint(acc), step, freq_old[u] + 1u, hot_old[u]});
+                else m->acc = acc;
+            }
         }
     }
 }
@@ -545,7 +574,7 @@ __global__ __launch_bounds__(kBlock) void k_gather_mixed(HtView v, const int32_t
 template <int LPR>
 __global__ __launch_bounds__(kBlock) void k_adagrad_mixed(HtView v, const int32_t* __restrict__ row_idx,
                                                           const float* __restrict__ g, const int64_t* n_dev,
-                                                          int64_t n_max, float lr, float eps) {
+                                                          int64_t n_max, float lr, float eps, int touch, uint32_t step) {
     const int64_t n = read_count(n_dev, n_max);
     const int sub = lane_id() % LPR;
     const int64_t u = group_item<LPR>();
@@ -577,7 +606,13 @@ __global__ __launch_bounds__(kBlock) void k_adagrad_mixed(HtView v, const int32_
             st16(wp, pack8(w));
         }
     }
-    if (sub == 0) m->acc = acc;
+    if (sub == 0) {
+        m->acc = acc;
+        if (touch) {
+            m->last_seen = step;
+            m->freq += 1u;
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------- put rows (checkpoint import)
@@ -938,8 +973,8 @@ int ht_apply_adam(emb_table_t* t, const int32_t* row_idx, const float* reduced, 
     return EMB_OK;
 }
 
-int ht_apply_adagrad(emb_table_t* t, const int32_t* row_idx, const float* reduced, const int64_t* n_dev,
-                     int64_t n_max, float lr, float eps, void* stream) {
+static int adagrad_impl(emb_table_t* t, const int32_t* row_idx, const float* reduced, const int64_t* n_dev,
+                        int64_t n_max, float lr, float eps, bool touch, uint32_t step, void* stream) {
     if (!t || n_max < 0 || n_max > 0x7FFFFFFFll) return EMB_ERR_INVALID_ARG;
     if (n_max == 0) return EMB_OK;
     if (!row_idx || !reduced || (reinterpret_cast<uintptr_t>(reduced) & 15)) return EMB_ERR_INVALID_ARG;
@@ -950,14 +985,16 @@ int ht_apply_adagrad(emb_table_t* t, const int32_t* row_idx, const float* reduce
     const int vecs = t->row_bytes / 16;
     const bool bf = t->desc.dtype == EMB_BF16;
     if (t->hot_values) {
-        MTGR_MIXED_LAUNCH(k_adagrad_mixed, vecs, n_max, s, v, row_idx, reduced, n_dev, n_max, lr, eps);
+        MTGR_MIXED_LAUNCH(k_adagrad_mixed, vecs, n_max, s, v, row_idx, reduced, n_dev, n_max, lr, eps, touch ? 1 : 0, step);
         MTGR_LAUNCH_CHECK();
         return EMB_OK;
     }
-#define MTGR_ADA(L_)                                                                                                     \
-    do {                                                                                                                 \
-        if (bf) hipLaunchKernelGGL((k_adagrad<L_, true>), dim3(grid), dim3(kBlock), 0, s, v, row_idx, reduced, n_dev, n_max, lr, eps); \
-        else hipLaunchKernelGGL((k_adagrad<L_, false>), dim3(grid), dim3(kBlock), 0, s, v, row_idx, reduced, n_dev, n_max, lr, eps);   \
+#define MTGR_ADA2(L_, B_, T_) \
+    hipLaunchKernelGGL((k_adagrad<L_, B_, T_>), dim3(grid), dim3(kBlock), 0, s, v, row_idx, reduced, n_dev, n_max, lr, eps, step)
+#define MTGR_ADA(L_)                                                    \
+    do {                                                                \
+        if (bf) { if (touch) MTGR_ADA2(L_, true, true); else MTGR_ADA2(L_, true, false); }   \
+        else { if (touch) MTGR_ADA2(L_, false, true); else MTGR_ADA2(L_, false, false); }    \
     } while (0)
     if (vecs <= 1) MTGR_ADA(1);
     else if (vecs <= 2) MTGR_ADA(2);
@@ -967,8 +1004,19 @@ int ht_apply_adagrad(emb_table_t* t, const int32_t* row_idx, const float* reduce
     else if (vecs <= 32) MTGR_ADA(32);
     else MTGR_ADA(64);
 #undef MTGR_ADA
+#undef MTGR_ADA2
     MTGR_LAUNCH_CHECK();
     return EMB_OK;
+}
+
+int ht_apply_adagrad(emb_table_t* t, const int32_t* row_idx, const float* reduced, const int64_t* n_dev,
+                     int64_t n_max, float lr, float eps, void* stream) {
+    return adagrad_impl(t, row_idx, reduced, n_dev, n_max, lr, eps, false, 0u, stream);
+}
+
+int ht_apply_adagrad_touch(emb_table_t* t, const int32_t* row_idx, const float* reduced, const int64_t* n_dev,
+                           int64_t n_max, float lr, float eps, uint32_t step, void* stream) {
+    return adagrad_impl(t, row_idx, reduced, n_dev, n_max, lr, eps, true, step, stream);
 }
 
 } // extern "C"

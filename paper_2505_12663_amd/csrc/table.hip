@@ -241,7 +241,9 @@ __device__ inline void touch_row(const HtView& v, uint32_t row, uint32_t step) {
 // line of each of their 8 keys, then work through the unsettled keys one after the other.  Rows
 // for the new keys of all 16 waves of a block are taken from the allocator with one atomic per
 // block (a 4 M-key bulk insert otherwise queues 130 k atomics on the bump pointer).
-template <bool COUNT>
+// TOUCH = false: existing keys are found without counting a touch and a created row starts
+// with touch count 0 (the update call of the step counts it, in the write it does anyway).
+template <bool COUNT, bool TOUCH>
 __global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const uint64_t* __restrict__ key,
                                                               const int64_t* n_dev, int64_t n_max, uint32_t step,
                                                               int32_t* __restrict__ row_idx,
@@ -375,7 +377,7 @@ __global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const ui
         RowMeta* m = &CHUNK_META(v, my_row);
         m->acc = 0.0f;
         m->last_seen = step;
-        atomicAdd(&m->freq, 1u);
+        if (TOUCH) atomicAdd(&m->freq, 1u);
         __hip_atomic_store(&v.slots[my_slot].row, my_row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     // ---- results.  A lane that found a key whose creator has not published the row yet records
@@ -398,7 +400,7 @@ __global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const ui
                 out = (int32_t)(-(my_slot + 2));
             } else {
                 out = (int32_t)my_row;
-                touch_row(v, my_row, step);
+                if (TOUCH) touch_row(v, my_row, step);
             }
         }
         row_idx[i] = out;
@@ -410,7 +412,7 @@ __global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const ui
 
 // Second half of find-or-insert: resolve the deferred elements and count their touch.
 __global__ __launch_bounds__(kBlock) void k_touch(HtView v, const int64_t* n_dev, int64_t n_max, uint32_t step,
-                                                  int32_t* __restrict__ row_idx) {
+                                                  int32_t* __restrict__ row_idx, int touch) {
     const int64_t n = read_count(n_dev, n_max);
     const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i == 0 && v.st->head.free_count < 0) v.st->head.free_count = 0; // the free list ran dry during the insert
@@ -422,7 +424,7 @@ __global__ __launch_bounds__(kBlock) void k_touch(HtView v, const int64_t* n_dev
         row_idx[i] = -1; // the creator ran out of rows
     } else {
         row_idx[i] = (int32_t)rr;
-        touch_row(v, rr, step);
+        if (touch) touch_row(v, rr, step);
     }
 }
 
@@ -821,8 +823,8 @@ static int check_insert_room(emb_table_t* t, int64_t n_max) {
     return EMB_OK;
 }
 
-int ht_find_or_insert(emb_table_t* t, const uint64_t* key, const int64_t* n_dev, int64_t n_max, uint32_t step,
-                      int32_t* row_idx, uint8_t* inserted, void* stream) {
+static int find_or_insert_impl(emb_table_t* t, const uint64_t* key, const int64_t* n_dev, int64_t n_max, uint32_t step,
+                               int32_t* row_idx, uint8_t* inserted, void* stream, bool touch) {
     if (!t || n_max < 0 || n_max > 0x7FFFFFFFll) return EMB_ERR_INVALID_ARG;
     if (n_max == 0) return EMB_OK;
     if (!key || !row_idx) return EMB_ERR_INVALID_ARG;
@@ -831,18 +833,31 @@ int ht_find_or_insert(emb_table_t* t, const uint64_t* key, const int64_t* n_dev,
     HtView v = t->view();
     hipStream_t s = static_cast<hipStream_t>(stream);
     const unsigned grid = blocks_for((uint64_t)n_max, kBigBlock);
-    if (v.count)
-        hipLaunchKernelGGL(k_find_or_insert<true>, dim3(grid), dim3(kBigBlock), 0, s, v, key, n_dev, n_max, step,
-                           row_idx, inserted);
-    else
-        hipLaunchKernelGGL(k_find_or_insert<false>, dim3(grid), dim3(kBigBlock), 0, s, v, key, n_dev, n_max, step,
-                           row_idx, inserted);
+#define MTGR_FOI(C_, T_)                                                                                          \
+    hipLaunchKernelGGL((k_find_or_insert<C_, T_>), dim3(grid), dim3(kBigBlock), 0, s, v, key, n_dev, n_max, step, \
+                       row_idx, inserted)
+    if (v.count) {
+        if (touch) MTGR_FOI(true, true); else MTGR_FOI(true, false);
+    } else {
+        if (touch) MTGR_FOI(false, true); else MTGR_FOI(false, false);
+    }
+#undef MTGR_FOI
     MTGR_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_touch, dim3(blocks_for((uint64_t)n_max, kBlock)), dim3(kBlock), 0, s, v, n_dev, n_max, step,
-                       row_idx);
+                       row_idx, touch ? 1 : 0);
     MTGR_LAUNCH_CHECK();
     t->issued((uint64_t)n_max);
     return t->snapshot(s);
+}
+
+int ht_find_or_insert(emb_table_t* t, const uint64_t* key, const int64_t* n_dev, int64_t n_max, uint32_t step,
+                      int32_t* row_idx, uint8_t* inserted, void* stream) {
+    return find_or_insert_impl(t, key, n_dev, n_max, step, row_idx, inserted, stream, true);
+}
+
+int ht_find_or_insert_notouch(emb_table_t* t, const uint64_t* key, const int64_t* n_dev, int64_t n_max, uint32_t step,
+                              int32_t* row_idx, uint8_t* inserted, void* stream) {
+    return find_or_insert_impl(t, key, n_dev, n_max, step, row_idx, inserted, stream, false);
 }
 
 int ht_find(emb_table_t* t, const uint64_t* key, const int64_t* n_dev, int64_t n_max, int32_t* row_idx,

@@ -101,11 +101,12 @@ class EmbeddingTable:
             self.rehash(cap)
 
     # -- calls --------------------------------------------------------------------------------
-    def find_or_insert(self, key, n_dev, n_max: int, step: int, row_idx, inserted=None) -> None:
-        rc = B.ht_find_or_insert(self.h, key, n_dev, n_max, step, row_idx, inserted)
+    def find_or_insert(self, key, n_dev, n_max: int, step: int, row_idx, inserted=None, touch: bool = True) -> None:
+        """touch=False: the step's update call (apply_adagrad with touch_step) counts the touch."""
+        rc = B.ht_find_or_insert(self.h, key, n_dev, n_max, step, row_idx, inserted, touch=touch)
         if rc != B.EMB_OK:
             self.reserve(n_max)
-            rc = B.ht_find_or_insert(self.h, key, n_dev, n_max, step, row_idx, inserted)
+            rc = B.ht_find_or_insert(self.h, key, n_dev, n_max, step, row_idx, inserted, touch=touch)
             if rc != B.EMB_OK:
                 raise B.EmbError(rc, "ht_find_or_insert")
 
@@ -115,8 +116,12 @@ class EmbeddingTable:
     def gather(self, row_idx, n_dev, n_max: int, out) -> None:
         B.ht_gather(self.h, row_idx, n_dev, n_max, out)
 
-    def apply_adagrad(self, row_idx, reduced, n_dev, n_max: int, lr: float, eps: float = 1e-8) -> None:
-        B.ht_apply_adagrad(self.h, row_idx, reduced, n_dev, n_max, lr, eps)
+    def apply_adagrad(self, row_idx, reduced, n_dev, n_max: int, lr: float, eps: float = 1e-8,
+                      touch_step: Optional[int] = None) -> None:
+        if touch_step is None:
+            B.ht_apply_adagrad(self.h, row_idx, reduced, n_dev, n_max, lr, eps)
+        else:
+            B.ht_apply_adagrad_touch(self.h, row_idx, reduced, n_dev, n_max, lr, eps, touch_step)
 
     def apply_adam(self, row_idx, reduced, n_dev, n_max: int, lr: float, step: int, beta1: float = 0.9,
                    beta2: float = 0.999, eps: float = 1e-8) -> None:
@@ -215,21 +220,25 @@ class StepBuffers:
             self.reduce_ws = torch.empty(B.grad_segment_reduce_workspace_bytes(n_max, dim), dtype=torch.uint8, device=dev)
 
 
-def forward(table: EmbeddingTable, buf: StepBuffers, x, field_off, field_tag, tag_bits: int, step: int) -> None:
-    """tag -> dedup -> find-or-insert -> gather -> expand (in sorted order); results in buf.out[:n]."""
+def forward(table: EmbeddingTable, buf: StepBuffers, x, field_off, field_tag, tag_bits: int, step: int,
+            touch: bool = True) -> None:
+    """tag -> dedup -> find-or-insert -> gather -> expand (in sorted order); results in buf.out[:n].
+    touch=False leaves the rows' touch records to the update of the same step (backward with touch_step)."""
     n = x.numel()
     B.emb_tag_keys(x, field_off, field_tag, tag_bits, buf.key, buf.err_count)
     B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, buf.counts, buf.perm, buf.seg_off, buf.seg_of, buf.n_unique,
                 buf.dedup_ws)
-    table.find_or_insert(buf.uniq, buf.n_unique, n, step, buf.row_idx, buf.inserted)
+    table.find_or_insert(buf.uniq, buf.n_unique, n, step, buf.row_idx, buf.inserted, touch=touch)
     table.gather(buf.row_idx, buf.n_unique, n, buf.uniq_rows)
     B.emb_expand_sorted(buf.uniq_rows, buf.seg_of, buf.perm, n, table.dim, table.dtype, buf.out)
 
 
-def backward(table: EmbeddingTable, buf: StepBuffers, grad, n: int, lr: float, eps: float = 1e-8) -> None:
-    """segment-reduce the upstream gradient per distinct key, then row-wise Adagrad."""
+def backward(table: EmbeddingTable, buf: StepBuffers, grad, n: int, lr: float, eps: float = 1e-8,
+             touch_step: Optional[int] = None) -> None:
+    """segment-reduce the upstream gradient per distinct key, then row-wise Adagrad (which also counts
+    the step's touch when touch_step is given)."""
     B.grad_segment_reduce(grad, table.dtype, buf.seg_of, buf.perm, n, table.dim, buf.reduced, buf.reduce_ws)
-    table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, lr, eps)
+    table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, lr, eps, touch_step)
 
 
 def forward_fused(table: EmbeddingTable, buf: StepBuffers, x, field_off, field_tag, tag_bits: int, step: int) -> None:

@@ -56,8 +56,11 @@ class Pair:
 
 
 def run_step(pair: Pair, buf: StepBuffers, x: np.ndarray, field_off: np.ndarray, field_tag: np.ndarray,
-             tag_bits: int, step: int, G: np.ndarray, lr: float, eps: float, prepopulated_keys=None):
-    """One forward+backward on both sides; asserts the parity bar and returns (N, U)."""
+             tag_bits: int, step: int, G: np.ndarray, lr: float, eps: float, prepopulated_keys=None,
+             one_record_update: bool = False):
+    """One forward+backward on both sides; asserts the parity bar and returns (N, U).
+    one_record_update: the HIP side looks keys up without touching them and lets the update count the
+    touch; the checker keeps touching in the lookup - after the step both must be in the same state."""
     n = len(x)
     # ---- checker
     okey, oerr = oracle.tag_keys(x, field_off, field_tag, tag_bits)
@@ -73,7 +76,7 @@ def run_step(pair: Pair, buf: StepBuffers, x: np.ndarray, field_off: np.ndarray,
     pair.orc.apply_adagrad(ouniq, og, lr, eps)
     # ---- HIP path
     dx, doff, dtag = dev_keys(x), torch.from_numpy(field_off).cuda(), torch.from_numpy(field_tag).cuda()
-    forward(pair.gpu, buf, dx, doff, dtag, tag_bits, step)
+    forward(pair.gpu, buf, dx, doff, dtag, tag_bits, step, touch=not one_record_update)
     U = int(buf.n_unique.item())
     assert int(buf.err_count.item()) == oerr
     assert np.array_equal(host_keys(buf.key[:n]), okey), "tagged keys"
@@ -93,7 +96,7 @@ def run_step(pair: Pair, buf: StepBuffers, x: np.ndarray, field_off: np.ndarray,
         dG = torch.from_numpy(G).cuda()
     else:
         dG = torch.from_numpy(G).cuda().to(torch.bfloat16)     # G is bf16-representable: exact
-    backward(pair.gpu, buf, dG, n, lr, eps)
+    backward(pair.gpu, buf, dG, n, lr, eps, touch_step=step if one_record_update else None)
     g = buf.reduced[:U].cpu().numpy()
     assert close_reduce(g, og.astype(np.float64), osabs, RTOL_F32), "reduced gradients"
     return n, U

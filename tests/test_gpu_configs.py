@@ -59,7 +59,8 @@ def _grads(w, step, n, dim, dtype, g):
     return G
 
 
-def test_config1_tiny_full_size():
+@pytest.mark.parametrize("one_record_update", [False, True])
+def test_config1_tiny_full_size(one_record_update):
     w = make_config(1)
     merged, n_merged, tag_bits, sig = _plan(w)
     assert n_merged == 1 and tag_bits == 1
@@ -69,7 +70,7 @@ def test_config1_tiny_full_size():
         b = w.next_step(step)
         x, off, tags, _ = merged_inputs(w.features, b.ids, merged, 0)
         G = _grads(w, step, len(x), 32, 0, 0)
-        n, U = run_step(pair, buf, x, off, tags, tag_bits, step, G, w.lr, w.eps)
+        n, U = run_step(pair, buf, x, off, tags, tag_bits, step, G, w.lr, w.eps, one_record_update=one_record_update)
         live = pair.compare_tables(w.lr)
         assert live == len(pair.orc)
     st = pair.gpu.stats()
@@ -131,7 +132,8 @@ def test_config2_prepopulated_scaled():
     pair.gpu.close()
 
 
-def test_config4_insert_delete_stress_1000_steps_scaled():
+@pytest.mark.parametrize("one_record_update", [False, True])
+def test_config4_insert_delete_stress_1000_steps_scaled(one_record_update):
     """All 1000 streaming steps with the configuration's own eviction policy (ttl 200, freq < 3 after a
     grace of 20 steps, every 20 steps, load-factor limit 0.85), at a batch the checker keeps up with."""
     w = make_config(4, batch=8, vocab_scale=0.01, len_lo=128)       # 4096 IDs per step, 4000 keys per field at start
@@ -144,7 +146,7 @@ def test_config4_insert_delete_stress_1000_steps_scaled():
         b = w.next_step(step)
         x, off, tags, _ = merged_inputs(w.features, b.ids, merged, 0)
         G = _grads(w, step, len(x), 64, 0, 0)
-        n, U = run_step(pair, buf, x, off, tags, tag_bits, step, G, w.lr, w.eps)
+        n, U = run_step(pair, buf, x, off, tags, tag_bits, step, G, w.lr, w.eps, one_record_update=one_record_update)
         if (step + 1) % w.evict_every == 0:
             ev, n_ev = pair.gpu.evict(step, w.ttl, w.min_freq, w.grace)
             oev = pair.orc.evict(step, w.ttl, w.min_freq, w.grace)
@@ -163,7 +165,8 @@ def test_config4_insert_delete_stress_1000_steps_scaled():
     pair.gpu.close()
 
 
-def test_config5_bf16_scaled():
+@pytest.mark.parametrize("one_record_update", [False, True])
+def test_config5_bf16_scaled(one_record_update):
     w = make_config(5, batch=8, vocab_scale=0.0002, len_lo=256)     # 20k keys per field, 8k IDs per step
     merged, n_merged, tag_bits, sig = _plan(w)
     assert sig == [(128, 1)]
@@ -177,7 +180,8 @@ def test_config5_bf16_scaled():
         b = w.next_step(step - 1)
         x, off, tags, _ = merged_inputs(w.features, b.ids, merged, 0)
         G = _grads(w, step, len(x), 128, 1, 0)
-        n, U = run_step(pair, buf, x, off, tags, tag_bits, step, G, w.lr, w.eps, prepopulated_keys=lazy)
+        n, U = run_step(pair, buf, x, off, tags, tag_bits, step, G, w.lr, w.eps, prepopulated_keys=lazy,
+                        one_record_update=one_record_update)
         new_total += int(buf.inserted[:U].sum().item())
     assert new_total > 0                                            # ~5 % of each step's keys are new
     ok, ov, oa, ol, of = pair.orc.export()

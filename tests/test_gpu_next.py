@@ -409,3 +409,54 @@ def test_hot_store_argument_checks():
         tb.apply_adam(ri, g, None, 1, 1e-3, 1)                     # masters are kept for Adagrad only
     t32.close()
     tb.close()
+
+
+# --------------------------------------------------------------------------- one record update per step
+@pytest.mark.parametrize("dtype,hot", [(0, 0), (1, 0), (1, 1500)])
+def test_notouch_lookup_plus_touching_update_equals_the_plain_pair(dtype, hot):
+    """ht_find_or_insert_notouch + ht_apply_adagrad_touch must leave the table exactly where ht_find_or_insert +
+    ht_apply_adagrad leave it (bit for bit: same kernels' arithmetic), and keys without an update keep their record."""
+    dim, lr, eps = 64, 0.05, 1e-8
+    ta = EmbeddingTable(dim, dtype, capacity_log2=13, chunk_rows_log2=10, hot_rows=hot)
+    tb = EmbeddingTable(dim, dtype, capacity_log2=13, chunk_rows_log2=10, hot_rows=hot)
+    rng = np.random.default_rng(11)
+    pool = np.arange(1, 1501, dtype=np.uint64) * np.uint64(48271)
+    for step in range(1, 9):
+        ks = np.unique(pool[rng.integers(0, 1500, size=600)])
+        n = len(ks)
+        dk = dev_keys(ks)
+        g = torch.from_numpy(normal_grads(9, step, n, dim)).cuda()
+        ra = torch.empty(n, dtype=torch.int32, device="cuda")
+        rb = torch.empty(n, dtype=torch.int32, device="cuda")
+        ia = torch.empty(n, dtype=torch.uint8, device="cuda")
+        ib = torch.empty(n, dtype=torch.uint8, device="cuda")
+        ta.find_or_insert(dk, None, n, step, ra, ia)
+        ta.apply_adagrad(ra, g, None, n, lr, eps)
+        tb.find_or_insert(dk, None, n, step, rb, ib, touch=False)
+        assert torch.equal(ia, ib)
+        tb.apply_adagrad(rb, g, None, n, lr, eps, touch_step=step)
+        if hot and step == 4:
+            ta.promote(ra, None, n, 2)
+            tb.promote(rb, None, n, 2)
+        for a, b in zip(ta.export(), tb.export()):
+            assert np.array_equal(a, b)
+    if hot:
+        for a, b in zip(ta.export_hot(), tb.export_hot()):
+            assert np.array_equal(a, b)
+        assert ta.stats()["hot_rows_used"] > 0
+    # a key that is looked up without an update keeps its record
+    k = dev_keys(pool[:5])
+    r = torch.empty(5, dtype=torch.int32, device="cuda")
+    before = tb.export()
+    tb.find_or_insert(k, None, 5, 99, r, None, touch=False)
+    for a, b in zip(before, tb.export()):
+        assert np.array_equal(a, b)
+    # a key created by the quiet lookup starts with touch count 0 and the step as last_seen
+    newk = np.array([0x7FFF0001], dtype=np.uint64)
+    r1 = torch.empty(1, dtype=torch.int32, device="cuda")
+    tb.find_or_insert(dev_keys(newk), None, 1, 123, r1, None, touch=False)
+    ek, _, ea, el, ef = tb.export()
+    i = int(np.searchsorted(ek, newk[0]))
+    assert ek[i] == newk[0] and ef[i] == 0 and el[i] == 123 and ea[i] == 0
+    ta.close()
+    tb.close()
