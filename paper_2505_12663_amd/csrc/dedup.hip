@@ -82,28 +82,60 @@ __global__ void k_zero64(unsigned long long* p) {
 }
 
 // ---------------------------------------------------------------------------- which digits vary
-constexpr int kMaskBlocks = 1024;
+__device__ inline unsigned digit_of(uint64_t k, int pass) { return (unsigned)(k >> (8 * pass)) & 0xFFu; }
 
-// every block ORs / ANDs its share of the keys and leaves one pair in `partial` (no atomics)
-__global__ __launch_bounds__(kThreads) void k_dd_masks(const uint64_t* __restrict__ key, int64_t n,
-                                                      unsigned long long* __restrict__ partial) {
+// Add a wave's 64 digits to an LDS histogram.  From the second pass on equal keys sit next to
+// each other, and a popular key fills whole tiles: 64 lanes adding to one counter would be served
+// one after the other.  Neighbouring lanes with the same digit are therefore counted as one run
+// and added once, by the run's first lane.  d >= kRadix means "no key".
+__device__ inline void hist_add_runs(unsigned* s_hist, unsigned d, int lane) {
+    const unsigned prev = __shfl_up(d, 1, kWave);
+    const bool head = lane == 0 || d != prev;
+    const uint64_t heads = __ballot(head);
+    if (head && d < (unsigned)kRadix) {
+        const uint64_t rest = (heads >> lane) >> 1;
+        const unsigned len = rest ? (unsigned)__ffsll((unsigned long long)rest) : (unsigned)(kWave - lane);
+        atomicAdd(&s_hist[d], len);
+    }
+}
+
+// One block per tile: OR / AND of the tile's keys -> partial[2*tile], partial[2*tile+1] (no atomics),
+// and, since the keys are in registers anyway, the tile's histogram of the lowest digit in the
+// layout the first radix pass expects (that pass then needs no histogram kernel of its own).
+__global__ __launch_bounds__(kThreads) void k_dd_masks(const uint64_t* __restrict__ key, int64_t n, unsigned n_tiles,
+                                                      unsigned long long* __restrict__ partial,
+                                                      unsigned* __restrict__ tile_hist) {
     __shared__ unsigned long long s_o[kWaves], s_a[kWaves];
+    __shared__ unsigned s_hist[kRadix];
+    s_hist[threadIdx.x] = 0u;
+    __syncthreads();
+    const int lane = lane_id();
     uint64_t o = 0ull, a = ~0ull;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
-        uint64_t k = key[i];
-        o |= k;
-        a &= k;
+    const int64_t base = (int64_t)blockIdx.x * kTile + (threadIdx.x / kWave) * (kWave * kItems) + lane;
+    unsigned d[kItems];
+#pragma unroll
+    for (int it = 0; it < kItems; ++it) {
+        const int64_t e = base + it * kWave;
+        d[it] = kRadix;
+        if (e < n) {
+            const uint64_t k = key[e];
+            o |= k;
+            a &= k;
+            d[it] = digit_of(k, 0);
+        }
     }
+#pragma unroll
+    for (int it = 0; it < kItems; ++it) hist_add_runs(s_hist, d[it], lane);
     for (int s = 32; s > 0; s >>= 1) {
-        o |= shfl64(o, lane_id() ^ s);
-        a &= shfl64(a, lane_id() ^ s);
+        o |= shfl64(o, lane ^ s);
+        a &= shfl64(a, lane ^ s);
     }
-    if (lane_id() == 0) {
+    if (lane == 0) {
         s_o[threadIdx.x / kWave] = o;
         s_a[threadIdx.x / kWave] = a;
     }
     __syncthreads();
+    tile_hist[(size_t)threadIdx.x * n_tiles + blockIdx.x] = s_hist[threadIdx.x];
     if (threadIdx.x == 0) {
         for (int w = 1; w < kWaves; ++w) {
             o |= s_o[w];
@@ -154,7 +186,6 @@ __global__ __launch_bounds__(kThreads) void k_dd_plan(DdHeader* h, const unsigne
 }
 
 // ---------------------------------------------------------------------------- radix pass
-__device__ inline unsigned digit_of(uint64_t k, int pass) { return (unsigned)(k >> (8 * pass)) & 0xFFu; }
 
 // tile element e = wave*1024 + item*64 + lane
 __global__ __launch_bounds__(kThreads) void k_rs_hist(DdBuffers b, const DdHeader* __restrict__ h, int pass, int64_t n,
@@ -165,9 +196,6 @@ __global__ __launch_bounds__(kThreads) void k_rs_hist(DdBuffers b, const DdHeade
     __syncthreads();
     const uint64_t* keys = sel_keys(b, h->src[pass]);
     const int64_t base = (int64_t)blockIdx.x * kTile + (threadIdx.x / kWave) * (kWave * kItems) + (threadIdx.x % kWave);
-    // From the second pass on equal keys sit next to each other, and a popular key fills whole
-    // tiles: 64 lanes adding to one LDS counter would be served one after the other.  Neighbouring
-    // lanes with the same digit are therefore counted as one run and added once by the run's first lane.
     const int lane = lane_id();
     unsigned d[kItems];
 #pragma unroll
@@ -176,50 +204,40 @@ __global__ __launch_bounds__(kThreads) void k_rs_hist(DdBuffers b, const DdHeade
         d[it] = e < n ? digit_of(keys[e], pass) : kRadix; // kRadix = no key
     }
 #pragma unroll
-    for (int it = 0; it < kItems; ++it) {
-        const unsigned prev = __shfl_up(d[it], 1, kWave);
-        const bool head = lane == 0 || d[it] != prev;
-        const uint64_t heads = __ballot(head);
-        if (head && d[it] < (unsigned)kRadix) {
-            const uint64_t rest = (heads >> lane) >> 1;
-            const unsigned len = rest ? (unsigned)__ffsll((unsigned long long)rest) : (unsigned)(kWave - lane);
-            atomicAdd(&s_hist[d[it]], len);
-        }
-    }
+    for (int it = 0; it < kItems; ++it) hist_add_runs(s_hist, d[it], lane);
     __syncthreads();
     tile_hist[(size_t)threadIdx.x * n_tiles + blockIdx.x] = s_hist[threadIdx.x];
 }
 
-// block d: exclusive scan of digit d's counts over the tiles; total -> digit_total[d]
+// block d: exclusive scan of digit d's counts over the tiles; total -> digit_total[d].
+// Every thread owns a run of consecutive tiles, so the block-wide scan happens once.
 __global__ __launch_bounds__(kThreads) void k_rs_scan(const DdHeader* __restrict__ h, int pass, unsigned n_tiles,
                                                      unsigned* __restrict__ tile_hist,
                                                      unsigned* __restrict__ digit_total) {
     if (!h->active[pass]) return;
     __shared__ unsigned s_wave[kWaves];
-    __shared__ unsigned s_carry;
     unsigned* row = tile_hist + (size_t)blockIdx.x * n_tiles;
     const int lane = lane_id(), wave = threadIdx.x / kWave;
-    if (threadIdx.x == 0) s_carry = 0u;
-    __syncthreads();
-    for (unsigned base = 0; base < n_tiles; base += kThreads) {
-        const unsigned i = base + threadIdx.x;
-        const unsigned v = i < n_tiles ? row[i] : 0u;
-        unsigned incl = v;
-        for (int o = 1; o < kWave; o <<= 1) {
-            unsigned t = __shfl_up(incl, o, kWave);
-            if (lane >= o) incl += t;
-        }
-        if (lane == kWave - 1) s_wave[wave] = incl;
-        __syncthreads();
-        unsigned woff = 0;
-        for (int w = 0; w < wave; ++w) woff += s_wave[w];
-        const unsigned carry = s_carry;
-        if (i < n_tiles) row[i] = carry + woff + incl - v;
-        __syncthreads();
-        if (threadIdx.x == kThreads - 1) s_carry = carry + woff + incl;
-        __syncthreads();
+    const unsigned per = (n_tiles + kThreads - 1) / kThreads;
+    const unsigned lo = threadIdx.x * per;
+    const unsigned hi = lo + per < n_tiles ? lo + per : n_tiles;
+    unsigned sum = 0;
+    for (unsigned i = lo; i < hi; ++i) sum += row[i];
+    unsigned incl = sum;
+    for (int o = 1; o < kWave; o <<= 1) {
+        unsigned t = __shfl_up(incl, o, kWave);
+        if (lane >= o) incl += t;
     }
-    if (threadIdx.x == 0) digit_total[blockIdx.x] = s_carry;
+    if (lane == kWave - 1) s_wave[wave] = incl;
+    __syncthreads();
+    unsigned run = incl - sum;
+    for (int w = 0; w < wave; ++w) run += s_wave[w];
+    for (unsigned i = lo; i < hi; ++i) {
+        const unsigned v = row[i];
+        row[i] = run;
+        run += v;
+    }
+    if (threadIdx.x == kThreads - 1) digit_total[blockIdx.x] = run;
 }
 
 // tile element e = wave*(64*kScItems) + item*64 + lane
@@ -464,7 +482,7 @@ DdLayout dd_layout(int64_t n) {
     L.n_tiles = (unsigned)((n + kTile - 1) / kTile);
     size_t o = 0;
     L.header = o; o = align_up(o + sizeof(DdHeader), 256);
-    L.masks = o; o = align_up(o + (size_t)kMaskBlocks * 16, 256);
+    L.masks = o; o = align_up(o + (size_t)L.n_tiles * 16, 256);
     L.ka = o; o = align_up(o + (size_t)n * 8, 256);
     L.kb = o; o = align_up(o + (size_t)n * 8, 256);
     L.ia = o; o = align_up(o + (size_t)n * 4, 256);
@@ -530,12 +548,12 @@ int emb_dedup(const uint64_t* key, int64_t n, uint64_t* uniq, int32_t* inverse, 
     const unsigned n_tiles = L.n_tiles;
 
     unsigned long long* masks = reinterpret_cast<unsigned long long*>(w + L.masks);
-    const unsigned mgrid = n_tiles < (unsigned)kMaskBlocks ? n_tiles : (unsigned)kMaskBlocks;
-    hipLaunchKernelGGL(k_dd_masks, dim3(mgrid), dim3(kThreads), 0, s, key, n, masks);
-    hipLaunchKernelGGL(k_dd_plan, dim3(1), dim3(kThreads), 0, s, hdr, masks, (int)mgrid);
+    hipLaunchKernelGGL(k_dd_masks, dim3(n_tiles), dim3(kThreads), 0, s, key, n, n_tiles, masks, tile_hist);
+    hipLaunchKernelGGL(k_dd_plan, dim3(1), dim3(kThreads), 0, s, hdr, masks, (int)n_tiles);
     MTGR_LAUNCH_CHECK();
     for (int p = 0; p < kPasses; ++p) {
-        hipLaunchKernelGGL(k_rs_hist, dim3(n_tiles), dim3(kThreads), 0, s, b, hdr, p, n, n_tiles, tile_hist);
+        if (p > 0) // the lowest digit's histogram came with the mask reduction
+            hipLaunchKernelGGL(k_rs_hist, dim3(n_tiles), dim3(kThreads), 0, s, b, hdr, p, n, n_tiles, tile_hist);
         hipLaunchKernelGGL(k_rs_scan, dim3(kRadix), dim3(kThreads), 0, s, hdr, p, n_tiles, tile_hist, digit_total);
         hipLaunchKernelGGL(k_rs_scatter, dim3(n_tiles), dim3(kScThreads), 0, s, b, hdr, p, n, n_tiles, tile_hist, digit_total);
         MTGR_LAUNCH_CHECK();
