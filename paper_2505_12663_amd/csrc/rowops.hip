@@ -267,28 +267,47 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
                 my_seg[u] = in.seg[j];
             }
         }
+        // The chunk's rows are fetched in batches of kUnroll per group; the loads of batch b+1 are
+        // issued before batch b is folded, so that a wave always has loads in flight.
+        constexpr int kBpu = (LPR + kUnroll - 1) / kUnroll;   // batches per preloaded item slot u
+        constexpr int kBatches = kUnroll * kBpu;
+        V16 val[2][kUnroll];
+        int seg[2][kUnroll];
+        auto issue = [&](int u, int s0, V16* v_, int* sg_) {
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
+            for (int k = 0; k < kUnroll; ++k) {
+                const int sl = gbase + ((s0 + k) & (LPR - 1));
+                const long long src = (long long)shfl64((uint64_t)my_src[u], sl);
+                sg_[k] = (s0 + k < LPR) ? __shfl(my_seg[u], sl, kWave) : -1;
+                v_[k] = V16{0u, 0u, 0u, 0u};
+                if (lane_on && sg_[k] >= 0) v_[k] = ld16(in.rows + (size_t)src * (size_t)in.in_row_bytes + sub * 16);
+            }
+        };
+        auto fold = [&](const V16* v_, const int* sg_) {
+#pragma unroll
+            for (int k = 0; k < kUnroll; ++k) {
+                if (sg_[k] < 0) continue;
+                if (have && sg_[k] != cur_seg) flush_mid();
+                cur_seg = sg_[k];
+                have = true;
+                acc_add(acc, v_[k], false);
+            }
+        };
+        if constexpr (kBatches <= 16) {
+            issue(0, 0, val[0], seg[0]);
+#pragma unroll
+            for (int b = 0; b < kBatches; ++b) {
+                if (b + 1 < kBatches)
+                    issue((b + 1) / kBpu, ((b + 1) % kBpu) * kUnroll, val[(b + 1) & 1], seg[(b + 1) & 1]);
+                fold(val[b & 1], seg[b & 1]);
+            }
+        } else { // wide rows: too many batches to unroll, fetch and fold one batch at a time
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
 #pragma unroll 1
-            for (int s0 = 0; s0 < LPR; s0 += kUnroll) {
-                V16 val[kUnroll];
-                int seg[kUnroll];
-#pragma unroll
-                for (int k = 0; k < kUnroll; ++k) {
-                    const int sl = gbase + ((s0 + k) & (LPR - 1));
-                    const long long src = (long long)shfl64((uint64_t)my_src[u], sl);
-                    seg[k] = __shfl(my_seg[u], sl, kWave);
-                    val[k] = V16{0u, 0u, 0u, 0u};
-                    if (s0 + k < LPR && lane_on && seg[k] >= 0)
-                        val[k] = ld16(in.rows + (size_t)src * (size_t)in.in_row_bytes + sub * 16);
-                }
-#pragma unroll
-                for (int k = 0; k < kUnroll; ++k) {
-                    if (s0 + k >= LPR || seg[k] < 0) continue;
-                    if (have && seg[k] != cur_seg) flush_mid();
-                    cur_seg = seg[k];
-                    have = true;
-                    acc_add(acc, val[k], false);
+                for (int s0 = 0; s0 < LPR; s0 += kUnroll) {
+                    issue(u, s0, val[0], seg[0]);
+                    fold(val[0], seg[0]);
                 }
             }
         }
