@@ -18,13 +18,17 @@ using namespace mtgr;
 namespace {
 
 constexpr int kBlock = 256;
+#ifndef MTGR_RED_UNROLL_UPPER
+#define MTGR_RED_UNROLL_UPPER 16
+#endif
 #ifndef MTGR_RED_UNROLL
 #define MTGR_RED_UNROLL 4
 #endif
 #ifndef MTGR_RED_SPAN
 #define MTGR_RED_SPAN 64
 #endif
-constexpr int kUnroll = MTGR_RED_UNROLL;
+constexpr int kUnroll = MTGR_RED_UNROLL;          // first level
+constexpr int kUnrollUpper = MTGR_RED_UNROLL_UPPER;
 
 __device__ inline const char* chunk_row_cptr(const HtView& v, uint32_t row) {
     const char* base = static_cast<const char*>(v.st->values[row >> v.chunk_log2]);
@@ -211,7 +215,9 @@ struct LevelIn {
     int in_row_bytes;
 };
 
-template <int LPR, int FPL, bool LEVEL1>
+// UNR = rows a group keeps in flight per batch: 4 with the next batch prefetched for the large
+// first level; 16 for the small upper levels, which are chains of dependent round trips.
+template <int LPR, int FPL, bool LEVEL1, int UNR>
 __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, float* __restrict__ reduced,
                                                        float* __restrict__ part_rows, int32_t* __restrict__ part_seg,
                                                        int last_level) {
@@ -247,12 +253,14 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
     };
 
     // each lane of the group preloads the source row index / segment of items sub, sub+LPR, ...
-    for (int c = 0; c < kSpan; c += LPR * kUnroll) {
-        // chunk of LPR*kUnroll items: lane holds kUnroll of them (item c + u*LPR + sub)
-        int64_t my_src[kUnroll];
-        int my_seg[kUnroll];
+    constexpr int kPre = (kSpan / LPR) < 1 ? 1 : ((kSpan / LPR) > 4 ? 4 : (kSpan / LPR)); // items a lane holds per chunk
+    constexpr int kChunk = LPR * kPre;                        // items per chunk (flat index f = u*LPR + lane-in-group)
+    constexpr int kBatches = (kChunk + UNR - 1) / UNR;
+    for (int c = 0; c < kSpan; c += kChunk) {
+        int64_t my_src[kPre];
+        int my_seg[kPre];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
+        for (int u = 0; u < kPre; ++u) {
             const int it = c + u * LPR + sub;
             my_src[u] = -1;
             my_seg[u] = -1;
@@ -267,25 +275,24 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
                 my_seg[u] = in.seg[j];
             }
         }
-        // The chunk's rows are fetched in batches of kUnroll per group; the loads of batch b+1 are
-        // issued before batch b is folded, so that a wave always has loads in flight.
-        constexpr int kBpu = (LPR + kUnroll - 1) / kUnroll;   // batches per preloaded item slot u
-        constexpr int kBatches = kUnroll * kBpu;
-        V16 val[2][kUnroll];
-        int seg[2][kUnroll];
-        auto issue = [&](int u, int s0, V16* v_, int* sg_) {
+        // batch b fetches the rows of flat items b*UNR .. b*UNR+UNR-1 of the chunk
+        auto issue = [&](int b, V16* v_, int* sg_) {
 #pragma unroll
-            for (int k = 0; k < kUnroll; ++k) {
-                const int sl = gbase + ((s0 + k) & (LPR - 1));
-                const long long src = (long long)shfl64((uint64_t)my_src[u], sl);
-                sg_[k] = (s0 + k < LPR) ? __shfl(my_seg[u], sl, kWave) : -1;
+            for (int k = 0; k < UNR; ++k) {
+                const int f = b * UNR + k;
+                sg_[k] = -1;
                 v_[k] = V16{0u, 0u, 0u, 0u};
-                if (lane_on && sg_[k] >= 0) v_[k] = ld16(in.rows + (size_t)src * (size_t)in.in_row_bytes + sub * 16);
+                if (f < kChunk) {
+                    const int sl = gbase + f % LPR;
+                    const long long src = (long long)shfl64((uint64_t)my_src[f / LPR], sl);
+                    sg_[k] = __shfl(my_seg[f / LPR], sl, kWave);
+                    if (lane_on && sg_[k] >= 0) v_[k] = ld16(in.rows + (size_t)src * (size_t)in.in_row_bytes + sub * 16);
+                }
             }
         };
         auto fold = [&](const V16* v_, const int* sg_) {
 #pragma unroll
-            for (int k = 0; k < kUnroll; ++k) {
+            for (int k = 0; k < UNR; ++k) {
                 if (sg_[k] < 0) continue;
                 if (have && sg_[k] != cur_seg) flush_mid();
                 cur_seg = sg_[k];
@@ -293,22 +300,23 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
                 acc_add(acc, v_[k], false);
             }
         };
-        if constexpr (kBatches <= 16) {
-            issue(0, 0, val[0], seg[0]);
+        if constexpr (UNR <= 4) {
+            // the loads of batch b+1 are issued before batch b is folded, so that a wave always has loads in flight
+            V16 val[2][UNR];
+            int seg[2][UNR];
+            issue(0, val[0], seg[0]);
 #pragma unroll
             for (int b = 0; b < kBatches; ++b) {
-                if (b + 1 < kBatches)
-                    issue((b + 1) / kBpu, ((b + 1) % kBpu) * kUnroll, val[(b + 1) & 1], seg[(b + 1) & 1]);
+                if (b + 1 < kBatches) issue(b + 1, val[(b + 1) & 1], seg[(b + 1) & 1]);
                 fold(val[b & 1], seg[b & 1]);
             }
-        } else { // wide rows: too many batches to unroll, fetch and fold one batch at a time
+        } else {
+            V16 val[UNR];
+            int seg[UNR];
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-#pragma unroll 1
-                for (int s0 = 0; s0 < LPR; s0 += kUnroll) {
-                    issue(u, s0, val[0], seg[0]);
-                    fold(val[0], seg[0]);
-                }
+            for (int b = 0; b < kBatches; ++b) {
+                issue(b, val, seg);
+                fold(val, seg);
             }
         }
     }
@@ -368,7 +376,7 @@ int launch_reduce(const char* grad, int in_row_bytes, const int32_t* seg_of, con
         int32_t* pseg = reinterpret_cast<int32_t*>(ws + L.seg_off[l]);
         if (l == 0) {
             LevelIn in{grad, perm, via, seg_of, n, in_row_bytes};
-            hipLaunchKernelGGL((k_seg_reduce<LPR, FPL, true>), dim3(grid), dim3(kBlock), 0, s, in, dim, reduced, prow, pseg, last);
+            hipLaunchKernelGGL((k_seg_reduce<LPR, FPL, true, kUnroll>), dim3(grid), dim3(kBlock), 0, s, in, dim, reduced, prow, pseg, last);
         } else {
             LevelIn in{ws + L.rows_off[l - 1], nullptr, nullptr, reinterpret_cast<const int32_t*>(ws + L.seg_off[l - 1]),
                        L.items[l], dim * 4};
@@ -377,7 +385,7 @@ int launch_reduce(const char* grad, int in_row_bytes, const int32_t* seg_of, con
             constexpr int kGroups2 = kWave / LPR2;
             constexpr int kSpb2 = (kBlock / kWave) * kGroups2;
             const unsigned grid2 = (unsigned)((L.spans[l] + kSpb2 - 1) / kSpb2);
-            hipLaunchKernelGGL((k_seg_reduce<LPR2, 4, false>), dim3(grid2), dim3(kBlock), 0, s, in, dim, reduced, prow, pseg, last);
+            hipLaunchKernelGGL((k_seg_reduce<LPR2, 4, false, kUnrollUpper>), dim3(grid2), dim3(kBlock), 0, s, in, dim, reduced, prow, pseg, last);
         }
         MTGR_LAUNCH_CHECK();
     }
