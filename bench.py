@@ -288,6 +288,39 @@ def main() -> int:
                                    "note": "emb_pool_bags / grad_segment_reduce_pooled replace expand / reduce: one "
                                            "fp32 vector per (sample, field) instead of one row per position"}
 
+    # ---- same shape with realistic per-field vocabularies (a few fields with a handful of values): segments of
+    # 10^5..10^6 positions; table-free phases only (dedup, expand, reduce), as an extra line
+    if args.config == 2 and not args.no_extras:
+        wl = make_config(2, field_vocab=[6_250_000, 20_000, 6_250_000, 500_000, 100, 24, 8, 50])
+        bl = wl.next_step(0)
+        xl, offl, tagl, _ = merged_inputs(wl.features, bl.ids, merged, 0)
+        nl = len(xl)
+        if nl <= n_max:
+            dxl = torch.from_numpy(xl.view(np.int64)).to(dev)
+            B.emb_tag_keys(dxl, torch.from_numpy(offl).to(dev), torch.from_numpy(tagl).to(dev), tag_bits, buf.key, buf.err_count)
+
+            def timed(fn, reps=10):
+                fn()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(reps):
+                    fn()
+                e1.record()
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1) / reps
+
+            t_d = timed(lambda: B.emb_dedup(buf.key, nl, buf.uniq, buf.inverse, buf.counts, buf.perm, None, buf.seg_of,
+                                            buf.n_unique, buf.dedup_ws))
+            ul = int(buf.n_unique.item())
+            longest = int(buf.counts[:ul].max().item())
+            t_e = timed(lambda: B.emb_expand_sorted(buf.uniq_rows, buf.seg_of, buf.perm, nl, dim, dtype, buf.out))
+            t_r = timed(lambda: B.grad_segment_reduce(grad, dtype, buf.seg_of, buf.perm, nl, dim, buf.reduced, buf.reduce_ws))
+            result["low_cardinality_fields"] = {
+                "ids": nl, "unique": ul, "longest_segment": longest, "dedup_ms": round(t_d, 4),
+                "expand_ms": round(t_e, 4), "reduce_ms": round(t_r, 4),
+                "note": "field vocabularies 6.25M, 20k, 6.25M, 500k, 100, 24, 8, 50: worst case for the segmented "
+                        "reduction (one segment spans thousands of spans)"}
+
     if args.copy_probe_mib > 0:
         nbytes = args.copy_probe_mib << 20
         src = torch.empty(nbytes, dtype=torch.uint8, device=dev).fill_(1)

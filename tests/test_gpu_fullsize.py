@@ -84,6 +84,47 @@ def test_config2_full_size_two_steps():
     pair.gpu.close()
 
 
+def test_config2_low_cardinality_fields_segments_of_hundreds_of_thousands():
+    """The long-sequence shape with realistic per-field vocabularies: action, scene, hour fields with a handful of
+    values give segments of 10^5..10^6 positions, the worst case for the segmented reduction (many levels of
+    partial rows for one segment) and the best case for the sorted expand.  Dedup, expand and reduce are compared
+    with the checker in full (integer-valued gradients: one correct fp32 answer)."""
+    from workloads import small_int_grads
+    w = make_config(2, field_vocab=[6_250_000, 20_000, 6_250_000, 500_000, 100, 24, 8, 50])
+    merged, n_merged = B.emb_plan_merge([64] * 8, [0] * 8)
+    tag_bits = B.emb_tag_bits(8)
+    b = w.next_step(0)
+    x, off, tags, _ = merged_inputs(w.features, b.ids, merged, 0)
+    n, dim = len(x), 64
+    okey, _ = oracle.tag_keys(x, off, tags, tag_bits)
+    ouniq, oinv, ocnt = oracle.dedup(okey)
+    U = len(ouniq)
+    assert ocnt.max() > 300_000 and U < n // 8
+    buf = StepBuffers(n, dim)
+    B.emb_tag_keys(dev_keys(x), torch.from_numpy(off).cuda(), torch.from_numpy(tags).cuda(), tag_bits, buf.key, buf.err_count)
+    B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, buf.counts, buf.perm, buf.seg_off, buf.seg_of, buf.n_unique, buf.dedup_ws)
+    assert int(buf.n_unique.item()) == U
+    assert np.array_equal(host_keys(buf.uniq[:U]), ouniq)
+    assert np.array_equal(buf.inverse[:n].cpu().numpy(), oinv)
+    assert np.array_equal(buf.counts[:U].cpu().numpy(), ocnt)
+    print(f"  dedup: N={n} U={U} longest segment {int(ocnt.max())}", flush=True)
+    # expand, both forms, against the definition
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    buf.uniq_rows[:U].normal_(generator=gen)
+    inv_dev = buf.inverse[:n].long()
+    B.emb_expand_sorted(buf.uniq_rows, buf.seg_of, buf.perm, n, dim, 0, buf.out)
+    assert torch.equal(buf.out[:n], buf.uniq_rows[:U][inv_dev])
+    buf.out.zero_()
+    B.emb_expand(buf.uniq_rows, buf.inverse, n, dim, 0, buf.out)
+    assert torch.equal(buf.out[:n], buf.uniq_rows[:U][inv_dev])
+    # reduce: integers in [-8, 8]; the longest segment sums 4e5 of them, exact in fp32 in any order
+    G = small_int_grads(n, dim, 21, "cuda")
+    B.grad_segment_reduce(G, 0, buf.seg_of, buf.perm, n, dim, buf.reduced, buf.reduce_ws)
+    og = oracle.segment_reduce(G.cpu().numpy(), oinv, U)
+    assert np.array_equal(buf.reduced[:U].cpu().numpy(), og)
+    print("  expand and reduce exact", flush=True)
+
+
 def test_config3_full_size_merged_tables():
     w = make_config(3)
     dims = [w.table_dim(t) for t in range(w.n_tables)]

@@ -233,9 +233,11 @@ _FIELDS8 = ["item", "category", "shop", "brand", "price_bucket", "time_bucket", 
 
 def make_config(config_id: int, *, batch: Optional[int] = None, vocab_scale: float = 1.0,
                 len_hi: Optional[int] = None, len_lo: Optional[int] = None,
-                steps: Optional[int] = None) -> Workload:
+                steps: Optional[int] = None, field_vocab: Optional[Sequence[int]] = None) -> Workload:
     """Build configuration 1..5.  ``batch``/``vocab_scale``/``len_*`` shrink a
-    configuration for quick checks; defaults give the full published shape."""
+    configuration for quick checks; defaults give the full published shape.
+    ``field_vocab`` (configuration 2 only) replaces the per-field vocabulary sizes, e.g. a few
+    fields with under a thousand values (action, scene, hour) next to item-like ones."""
     vs = lambda v: max(16, int(v * vocab_scale))
     if config_id == 1:
         feats = [FeatureDecl(f"f{i}", 0, vs(100_000), 32) for i in range(4)]
@@ -244,7 +246,9 @@ def make_config(config_id: int, *, batch: Optional[int] = None, vocab_scale: flo
                      steps=steps or 3)
         return w
     if config_id == 2:
-        feats = [FeatureDecl(n, i, vs(6_250_000), 64) for i, n in enumerate(_FIELDS8)]
+        fv = list(field_vocab) if field_vocab is not None else [vs(6_250_000)] * len(_FIELDS8)
+        assert len(fv) == len(_FIELDS8)
+        feats = [FeatureDecl(n, i, int(fv[i]), 64) for i, n in enumerate(_FIELDS8)]
         w = Workload("grm_seq_lookup", 2, feats, batch or 512, 1.05, 40, "per_sample_uniform",
                      len_lo or 256, len_hi or 4096, steps=steps or 3)
         w.prepopulated = [f.vocab for f in feats]
