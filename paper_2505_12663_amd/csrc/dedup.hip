@@ -49,6 +49,18 @@ __device__ inline const uint64_t* sel_keys(const DdBuffers& b, int s) { return s
 __device__ inline const uint32_t* sel_idx(const DdBuffers& b, int s) { return s == 1 ? b.ia : (s == 2 ? b.ib : nullptr); }
 
 // ---------------------------------------------------------------------------- tagging
+// last field whose start is <= e (s_off[0] <= e < s_off[n_fields])
+__device__ inline int field_of(const int64_t* s_off, int n_fields, int64_t e) {
+    int lo = 0, hi = n_fields;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (s_off[mid] <= e) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// A wave tags 256 consecutive IDs per round (4 coalesced loads).  Almost every such range lies
+// inside one field, so two searches per wave (first and last element) replace one per element.
 __global__ __launch_bounds__(kThreads) void k_tag(const uint64_t* __restrict__ x, const int64_t* __restrict__ field_off,
                                                  const uint8_t* __restrict__ field_tag, int n_fields, int64_t n,
                                                  int shift, uint64_t* __restrict__ key_out,
@@ -56,25 +68,38 @@ __global__ __launch_bounds__(kThreads) void k_tag(const uint64_t* __restrict__ x
     extern __shared__ int64_t s_off[]; // n_fields + 1 offsets
     for (int f = threadIdx.x; f <= n_fields; f += kThreads) s_off[f] = field_off[f];
     __syncthreads();
+    constexpr int kPer = 4;
     const uint64_t low_mask = (1ull << shift) - 1ull;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    const int lane = lane_id();
+    const int64_t wave_stride = (int64_t)gridDim.x * kWaves * (kWave * kPer);
     unsigned errs = 0;
-    for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < n; e += stride) {
-        // last field whose start is <= e
-        int lo = 0, hi = n_fields; // invariant: s_off[lo] <= e < s_off[hi]
-        while (hi - lo > 1) {
-            int mid = (lo + hi) >> 1;
-            if (s_off[mid] <= e) lo = mid; else hi = mid;
+    for (int64_t base = ((int64_t)blockIdx.x * kWaves + threadIdx.x / kWave) * (kWave * kPer); base < n; base += wave_stride) {
+        const int64_t last = base + kWave * kPer - 1 < n ? base + kWave * kPer - 1 : n - 1;
+        int f_edge = 0;
+        if (lane == 0) f_edge = field_of(s_off, n_fields, base);
+        if (lane == kWave - 1) f_edge = field_of(s_off, n_fields, last);
+        const int f_first = __shfl(f_edge, 0, kWave), f_last = __shfl(f_edge, kWave - 1, kWave);
+        uint64_t v[kPer];
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int64_t e = base + u * kWave + lane;
+            v[u] = e < n ? x[e] : 0ull;
         }
-        uint64_t v = x[e];
-        if (v > low_mask) {
-            ++errs;
-            v &= low_mask;
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int64_t e = base + u * kWave + lane;
+            if (e >= n) continue;
+            const int f = (f_first == f_last) ? f_first : field_of(s_off, n_fields, e);
+            uint64_t val = v[u];
+            if (val > low_mask) {
+                ++errs;
+                val &= low_mask;
+            }
+            key_out[e] = ((uint64_t)field_tag[f] << shift) | val;
         }
-        key_out[e] = ((uint64_t)field_tag[lo] << shift) | v;
     }
     for (int o = 32; o > 0; o >>= 1) errs += __shfl_xor(errs, o, kWave);
-    if (errs && lane_id() == 0) atomicAdd(err_count, (unsigned long long)errs);
+    if (errs && lane == 0) atomicAdd(err_count, (unsigned long long)errs);
 }
 
 __global__ void k_zero64(unsigned long long* p) {

@@ -460,3 +460,25 @@ def test_notouch_lookup_plus_touching_update_equals_the_plain_pair(dtype, hot):
     assert ek[i] == newk[0] and ef[i] == 0 and el[i] == 123 and ea[i] == 0
     ta.close()
     tb.close()
+
+
+def test_notouch_lookup_with_duplicate_new_keys_resolves_every_element():
+    """Duplicates of a key that is being created in the same call meet an unpublished row and are resolved by the
+    follow-up kernel; in the quiet form that kernel must still hand out the row, only without counting."""
+    dim = 32
+    t = EmbeddingTable(dim, 0, capacity_log2=12, chunk_rows_log2=10)
+    rng = np.random.default_rng(3)
+    distinct = np.arange(1, 301, dtype=np.uint64) * np.uint64(7919)
+    ks = distinct[rng.integers(0, 300, size=20000)]                 # ~67 copies of each key, all new
+    r = torch.empty(len(ks), dtype=torch.int32, device="cuda")
+    t.find_or_insert(dev_keys(ks), None, len(ks), 5, r, None, touch=False)
+    rows = r.cpu().numpy()
+    assert (rows >= 0).all()
+    first = {}
+    for k, row in zip(ks.tolist(), rows.tolist()):
+        assert first.setdefault(k, row) == row                       # one row per key
+    assert len(set(first.values())) == len(first) == len(np.unique(ks))
+    ek, _, _, el, ef = t.export()
+    assert np.array_equal(ek, np.unique(ks)) and (ef == 0).all() and (el == 5).all()
+    assert t.stats()["status"] == 0
+    t.close()
