@@ -14,8 +14,9 @@
 // the GPU library.
 //
 // Parity pins live in tests/test_oracle_*.py.  Parts whose definition the paper
-// leaves open (row initialisation, the optimizer, the eviction predicate) follow
-// the readings listed in DESIGN.md; no function here is "parity unpinned".
+// leaves open (row initialisation, the optimizer, the eviction predicate, pooling,
+// hot rows) follow the reading stated at each function; no function here is
+// "parity unpinned".
 #include <algorithm>
 #include <cmath>
 #include <cstdint>

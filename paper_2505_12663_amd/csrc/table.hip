@@ -3,7 +3,7 @@
 // 128-byte lines of 8 slots with a key-dependent odd line stride (Theorem 1 gives full
 // coverage), sub-wave cooperative probing (8 lanes inspect one line with one coalesced
 // 128-byte load), CAS insertion into never-used slots only, deleted markers,
-// wave-aggregated row allocation, key-only rehash.
+// block-aggregated row allocation, key-only rehash.
 #include <cstddef>
 
 #include "common.hpp"
