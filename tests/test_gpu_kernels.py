@@ -99,7 +99,7 @@ def test_dedup_matches_checker(case):
 
 
 # ------------------------------------------------------------------------------------------ table
-@pytest.mark.parametrize("dim,dtype", [(32, 0), (64, 0), (16, 0), (128, 0), (128, 1), (8, 1)])
+@pytest.mark.parametrize("dim,dtype", [(32, 0), (64, 0), (16, 0), (128, 0), (128, 1), (8, 1), (256, 0), (4, 0), (24, 0), (256, 1), (40, 1)])
 def test_find_or_insert_gather_roundtrip(dim, dtype):
     keys = _zipf_keys(20_000, 6000, 5)                         # with duplicates inside one call
     keys[:64] = keys[0]                                          # a whole wave of the same new key
@@ -189,7 +189,8 @@ def test_bad_key_and_capacity_errors_are_reported():
 
 # ------------------------------------------------------------------------------------------ expand
 @pytest.mark.parametrize("dim,dtype,n,u", [(64, 0, 10_000, 3000), (32, 0, 4097, 1), (128, 1, 5000, 5000),
-                                            (16, 0, 63, 10), (128, 0, 2000, 300), (4, 0, 1000, 17)])
+                                            (16, 0, 63, 10), (128, 0, 2000, 300), (4, 0, 1000, 17), (256, 0, 3000, 500), (24, 0, 3000, 500),
+                                            (256, 1, 3000, 500), (40, 1, 3000, 40)])
 def test_expand(dim, dtype, n, u):
     rng = np.random.default_rng(n)
     rows = rng.standard_normal((u, dim)).astype(np.float32)
@@ -220,7 +221,7 @@ def _reduce_gpu(G_dev, dtype, keys):
     return red[:U].cpu().numpy(), inverse, U
 
 
-@pytest.mark.parametrize("dim,dtype", [(64, 0), (32, 0), (16, 0), (128, 0), (128, 1), (8, 1)])
+@pytest.mark.parametrize("dim,dtype", [(64, 0), (32, 0), (16, 0), (128, 0), (128, 1), (8, 1), (256, 0), (4, 0), (24, 0), (256, 1), (40, 1)])
 @pytest.mark.parametrize("shape", ["zipf", "one_giant_segment", "all_distinct", "tiny"])
 def test_segment_reduce(dim, dtype, shape):
     n = {"zipf": 128 * 128 * 2 + 300, "one_giant_segment": 40_000, "all_distinct": 5000, "tiny": 3}[shape]
@@ -255,7 +256,7 @@ def test_segment_reduce(dim, dtype, shape):
 
 
 # ------------------------------------------------------------------------------------------ adagrad
-@pytest.mark.parametrize("dim,dtype", [(32, 0), (64, 0), (128, 0), (16, 0), (128, 1), (8, 1)])
+@pytest.mark.parametrize("dim,dtype", [(32, 0), (64, 0), (128, 0), (16, 0), (128, 1), (8, 1), (256, 0), (4, 0), (24, 0), (256, 1), (40, 1)])
 def test_adagrad_matches_checker(dim, dtype):
     rtol = RTOL_F32 if dtype == 0 else RTOL_BF16
     keys = np.unique(_zipf_keys(6000, 4000, 21))
@@ -369,7 +370,7 @@ def test_full_table_up_to_the_load_factor_limit():
 
 
 # ------------------------------------------------------------------------------------------ fused form
-@pytest.mark.parametrize("dim,dtype", [(64, 0), (32, 0), (128, 0), (128, 1), (16, 0), (8, 1)])
+@pytest.mark.parametrize("dim,dtype", [(64, 0), (32, 0), (128, 0), (128, 1), (16, 0), (8, 1), (256, 0), (4, 0), (24, 0), (256, 1), (40, 1)])
 def test_fused_gather_expand_equals_the_two_calls(dim, dtype):
     """gather+expand in one kernel is bit-identical to ht_gather followed by emb_expand(_sorted), over
     several steps with updates in between, and agrees with the checker's direct lookup."""
