@@ -100,7 +100,8 @@ def test_sparse_gradient_accumulation_over_micro_batches():
     table.close()
 
 
-@pytest.mark.parametrize("dim,dtype,mean", [(64, 0, False), (64, 0, True), (32, 0, True), (128, 1, False), (128, 1, True), (16, 0, False)])
+@pytest.mark.parametrize("dim,dtype,mean", [(64, 0, False), (64, 0, True), (32, 0, True), (128, 1, False), (128, 1, True), (16, 0, False),
+                                            (256, 0, True), (24, 0, False), (4, 0, True), (40, 1, True), (256, 1, False)])
 def test_pooled_lookup_forward_and_backward(dim, dtype, mean):
     """Sum / mean pooling of every (sample, field) bag and its backward pass, against the checker
     (which is pinned to torch's EmbeddingBag): forward within 1e-5 of the float64 sums, backward with
@@ -153,7 +154,7 @@ def test_pooled_lookup_forward_and_backward(dim, dtype, mean):
     table.close()
 
 
-@pytest.mark.parametrize("dim,dtype", [(64, 0), (32, 0), (128, 1), (16, 0)])
+@pytest.mark.parametrize("dim,dtype", [(64, 0), (32, 0), (128, 1), (16, 0), (256, 0), (24, 0), (4, 0), (40, 1)])
 def test_sparse_adam_matches_checker(dim, dtype):
     """Lazy Adam on the activated rows only, several steps with new keys arriving and an eviction in
     between (moment rows of recycled rows must restart from zero)."""
