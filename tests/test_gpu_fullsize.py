@@ -218,3 +218,48 @@ def test_config5_full_size_bf16_400m_keys():
     assert st["live"] == 400_000_000 + n_new and st["status"] == 0
     assert st["n_rehash"] == 1 and st["capacity"] == 1 << 30          # 0.745 load + incoming bound crossed 0.75
     pair.gpu.close()
+
+
+def test_dedup_beyond_2_pow_30_keys():
+    """Largest sizes: n just above 2^30 (the entry point takes n < 2^31).  Checked by properties that hold at any
+    size: distinct keys strictly ascending, uniq[inverse] == key, the sorted order is a stable sort of the keys,
+    segment offsets and counts agree with it."""
+    n = (1 << 30) + 12345
+    g = torch.Generator(device="cuda").manual_seed(7)
+    key = torch.randint(0, 1 << 40, (n,), generator=g, device="cuda", dtype=torch.int64)
+    key[: n // 2] &= (1 << 22) - 1                       # half of the keys from a 4 M-key vocabulary: long segments
+    key |= torch.randint(0, 26, (n,), generator=g, device="cuda", dtype=torch.int64) << 55
+    key[-5:] = key[0].clone()
+    uniq = torch.empty(n, dtype=torch.int64, device="cuda")
+    inverse = torch.empty(n, dtype=torch.int32, device="cuda")
+    perm = torch.empty(n, dtype=torch.int32, device="cuda")
+    seg_off = torch.empty(n + 1, dtype=torch.int32, device="cuda")
+    seg_of = torch.empty(n, dtype=torch.int32, device="cuda")
+    n_unique = torch.zeros(1, dtype=torch.int64, device="cuda")
+    ws = torch.empty(B.emb_dedup_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    print(f"  n={n}, workspace {ws.numel() / 2**30:.1f} GiB", flush=True)
+    B.emb_dedup(key, n, uniq, inverse, None, perm, seg_off, seg_of, n_unique, ws)
+    U = int(n_unique.item())
+    del ws
+    print(f"  U={U}", flush=True)
+    assert 0 < U < n
+    u = uniq[:U]
+    assert bool((u[1:] > u[:-1]).all())                                   # strictly ascending, hence distinct
+    assert bool((inverse >= 0).all()) and int(inverse.max().item()) == U - 1
+    step = 1 << 28                                                        # check in slices to bound temporaries
+    for lo in range(0, n, step):
+        hi = min(n, lo + step)
+        assert torch.equal(u[inverse[lo:hi].long()], key[lo:hi])          # every key maps to its own distinct key
+        p = perm[lo:hi].long()
+        sk = key[p]
+        assert torch.equal(u[seg_of[lo:hi].long()], sk)                   # sorted order carries the right segment
+        assert bool((sk[1:] >= sk[:-1]).all())
+        assert bool(((sk[1:] != sk[:-1]) | (p[1:] > p[:-1])).all())       # equal keys keep their input order
+    assert int(seg_off[0].item()) == 0 and int(seg_off[U].item()) == n
+    so = seg_off[: U + 1].long()
+    assert bool((so[1:] > so[:-1]).all())
+    assert torch.equal(seg_of[so[:-1]].long(), torch.arange(U, device="cuda"))   # a segment starts where seg_off says
+    # perm is a permutation: every position appears once
+    seen = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    seen[perm.long()] = 1
+    assert bool(seen.all())
