@@ -381,7 +381,6 @@ __global__ __launch_bounds__(kScThreads) void k_rs_scatter(DdBuffers b, const Dd
 
 // ---------------------------------------------------------------------------- heads -> unique
 // head(j) = key differs from its predecessor in sorted order
-__device__ inline uint64_t sorted_key(const uint64_t* keys, int64_t j) { return keys[j]; }
 
 __global__ __launch_bounds__(kThreads) void k_heads_count(DdBuffers b, const DdHeader* __restrict__ h, int64_t n,
                                                          unsigned* __restrict__ tile_heads) {
