@@ -253,6 +253,42 @@ def main() -> int:
                                   "note": "ht_gather_expand_sorted replaces ht_gather + emb_expand_sorted: same result, "
                                           "2 x rowbytes x unique fewer bytes moved"}
 
+    # ---- both fusions of the no-communication case: fused lookup and fused backward (no distinct-row matrix, no
+    # reduced-gradient matrix), as an extra line
+    if not args.no_extras:
+        def one_step_fused2(step: int):
+            dx, doff, dtag, n, _ = batches[step % len(batches)]
+            B.emb_tag_keys(dx, doff, dtag, tag_bits, buf.key, buf.err_count)
+            B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, None, buf.perm, None, buf.seg_of, buf.n_unique, buf.dedup_ws)
+            table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted, touch=touch)
+            B.ht_gather_expand_sorted(table.h, buf.row_idx, buf.seg_of, buf.perm, n, buf.out)
+            B.grad_reduce_apply_adagrad(table.h, grad, buf.seg_of, buf.perm, n, buf.row_idx, w.lr, w.eps,
+                                        None if touch else step + 1, buf.reduce_ws)
+            return n
+
+        base2 = base + 2 + args.steps
+        for s in range(2):
+            one_step_fused2(base2 + s)
+        torch.cuda.synchronize()
+        ev0, ev1, ev2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        t_f2 = time.perf_counter()
+        ids_f2 = 0
+        for k in range(args.steps):
+            ids_f2 += one_step_fused2(base2 + 2 + k)
+        torch.cuda.synchronize()
+        wall_f2 = time.perf_counter() - t_f2
+        # the fused backward alone
+        ev0.record()
+        for k in range(5):
+            B.grad_reduce_apply_adagrad(table.h, grad, buf.seg_of, buf.perm, batches[0][3], buf.row_idx, w.lr, w.eps, None,
+                                        buf.reduce_ws)
+        ev1.record()
+        torch.cuda.synchronize()
+        result["fused_step"] = {"ms_per_step": round(wall_f2 * 1e3 / args.steps, 4), "ids_per_sec": round(ids_f2 / wall_f2, 1),
+                                "fused_backward_ms": round(ev0.elapsed_time(ev1) / 5, 4),
+                                "note": "ht_gather_expand_sorted + grad_reduce_apply_adagrad: neither the distinct-row "
+                                        "matrix nor the reduced-gradient matrix is written"}
+
     # ---- pooled variant (one vector per sample and field instead of one per position), as an extra line
     if args.config == 2 and not args.no_extras:
         lens0 = np.concatenate(lengths_of[0]).astype(np.int64)
@@ -273,7 +309,7 @@ def main() -> int:
             table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps, None if touch else step + 1)
             return n
 
-        base = base + 2 + args.steps
+        base = base + 2 * (2 + args.steps)
         for s in range(2):
             one_step_pooled(base + s)
         torch.cuda.synchronize()

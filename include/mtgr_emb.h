@@ -306,6 +306,20 @@ int ht_find_or_insert_notouch(emb_table_t* t, const uint64_t* key, const int64_t
 int ht_apply_adagrad_touch(emb_table_t* t, const int32_t* row_idx, const float* reduced, const int64_t* n_dev,
                            int64_t n_max, float lr, float eps, uint32_t step, void* stream);
 
+/* Backward pass in one call for the case without communication between aggregation and update
+ * (Sec. 2 "Backward Update"): grad_segment_reduce followed by ht_apply_adagrad (touch == 0) or
+ * ht_apply_adagrad_touch (touch != 0), without materialising the reduced matrix.  grad [n, dim] is in
+ * the table's dtype; seg_of / perm as for grad_segment_reduce; row_idx [n_unique] gives the row of
+ * every segment (-1 = skip).  The segment sums and the update arithmetic are those of the two calls, so
+ * the table ends up bit-identical.  workspace: grad_segment_reduce_workspace_bytes(n, dim) bytes.
+ * What it saves is the reduced matrix (n_max x dim x 4 bytes of caller memory), not time: every completed
+ * sum needs its row from memory before the next one can be parked, and with a few positions per distinct ID
+ * that wait is exposed (about 1.5x the time of the two calls on long-sequence batches).
+ * Not available for tables with a hot store (EMB_ERR_INVALID_ARG). */
+int grad_reduce_apply_adagrad(emb_table_t* t, const void* grad, const int32_t* seg_of, const int32_t* perm, int64_t n,
+                              const int32_t* row_idx, float lr, float eps, int touch, uint32_t step, void* workspace,
+                              size_t workspace_bytes, void* stream);
+
 /* ---- hot / cold rows (App. C "Mixed Precision Training"): a 16-bit table whose frequently used keys
  * keep an fp32 master row, so that many small updates of a hot row are not lost to 16-bit rounding,
  * while the bulk of the table stays at 2 bytes per element.

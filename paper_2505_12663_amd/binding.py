@@ -51,7 +51,7 @@ EXPORTS = [
     "ht_gather", "emb_expand", "emb_expand_sorted", "grad_segment_reduce_workspace_bytes", "grad_segment_reduce",
     "ht_apply_adagrad", "ht_apply_adam", "ht_gather_expand_sorted", "emb_pool_workspace_bytes", "emb_pool_bags",
     "grad_segment_reduce_pooled", "ht_evict", "ht_export", "ht_put", "ht_set_hot_storage", "ht_promote", "ht_export_hot",
-    "ht_find_or_insert_notouch", "ht_apply_adagrad_touch",
+    "ht_find_or_insert_notouch", "ht_apply_adagrad_touch", "grad_reduce_apply_adagrad",
 ]
 
 
@@ -84,6 +84,7 @@ def load():
         "ht_find_or_insert": (C.c_int, [vp, vp, vp, i64, u32, vp, vp, vp]),
         "ht_find_or_insert_notouch": (C.c_int, [vp, vp, vp, i64, u32, vp, vp, vp]),
         "ht_apply_adagrad_touch": (C.c_int, [vp, vp, vp, vp, i64, f32, f32, u32, vp]),
+        "grad_reduce_apply_adagrad": (C.c_int, [vp, vp, vp, vp, i64, vp, f32, f32, i32, u32, vp, C.c_size_t, vp]),
         "ht_find": (C.c_int, [vp, vp, vp, i64, vp, vp]),
         "ht_gather": (C.c_int, [vp, vp, vp, i64, vp, vp]),
         "emb_expand": (C.c_int, [vp, vp, i64, i32, i32, vp, vp]),
@@ -319,3 +320,10 @@ def ht_promote(h, row_idx, n_dev, n_max: int, min_freq: int, n_promoted=None, st
 
 def ht_export_hot(h, keys, values, n, stream=None) -> None:
     _check(load().ht_export_hot(h, _ptr(keys), _ptr(values), keys.numel(), _ptr(n), _stream(stream)), "ht_export_hot")
+
+
+def grad_reduce_apply_adagrad(h, grad, seg_of, perm, n: int, row_idx, lr: float, eps: float, touch_step, ws, stream=None) -> None:
+    """touch_step None: plain update; an int: the update also stamps last_seen = touch_step and counts a touch."""
+    _check(load().grad_reduce_apply_adagrad(h, _ptr(grad), _ptr(seg_of), _ptr(perm), n, _ptr(row_idx), lr, eps,
+                                            0 if touch_step is None else 1, 0 if touch_step is None else touch_step,
+                                            _ptr(ws), ws.numel(), _stream(stream)), "grad_reduce_apply_adagrad")

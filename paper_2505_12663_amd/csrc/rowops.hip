@@ -215,12 +215,25 @@ struct LevelIn {
     int in_row_bytes;
 };
 
+// Fused form (no reduced matrix): a completed segment sum goes straight into the row-wise Adagrad
+// update of row row_idx[segment].  The update needs the row and its record from memory; so that
+// the reduction's loads are not held up, a completed sum is parked, its loads are issued, and the
+// update is finished when the next sum completes (or at the end of the span).
+struct FuseArgs {
+    HtView v;
+    const int32_t* row_idx;   // row of every segment (-1 = none)
+    float lr, eps;
+    uint32_t step;
+    int touch;                // also set last_seen = step and count one touch
+};
+
 // UNR = rows a group keeps in flight per batch: 4 with the next batch prefetched for the large
 // first level; 16 for the small upper levels, which are chains of dependent round trips.
-template <int LPR, int FPL, bool LEVEL1, int UNR>
+// FUSE = 1: apply Adagrad to completed sums (table dtype TBL_BF16) instead of storing them.
+template <int LPR, int FPL, bool LEVEL1, int UNR, int FUSE, bool TBL_BF16>
 __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, float* __restrict__ reduced,
                                                        float* __restrict__ part_rows, int32_t* __restrict__ part_seg,
-                                                       int last_level) {
+                                                       int last_level, FuseArgs fz) {
     constexpr int kGroups = kWave / LPR;
     const int lane = lane_id();
     const int sub = lane % LPR, grp = lane / LPR;
@@ -235,15 +248,76 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
     Acc<FPL> acc;
     acc.zero();
     int cur_seg = -1;
+    int cur_row = -1;        // fused form: table row of cur_seg
     int runs_closed = 0;     // runs already flushed in this span
     bool have = false;
 
-    // flush the current run: first run of the span -> partial slot 0, otherwise complete -> reduced[]
+    // ---- fused form: one parked update per group
+    constexpr int kWB = FPL * (TBL_BF16 ? 2 : 4);   // bytes of the table row a lane owns (16, or 8 for bf16 rows at upper levels)
+    bool p_on = false;
+    int p_row = -1;
+    Acc<FPL> p_g;
+    V16 p_w{0u, 0u, 0u, 0u}, p_rec{0u, 0u, 0u, 0u};
+    auto finish_update = [&](void) {
+        if (!FUSE || !p_on) return;
+        p_on = false;
+        const float ss = sumsq_group<LPR>(sumsq_lane<FPL>(p_g.f));
+        const float acc_new = adagrad_acc(__uint_as_float(p_rec.x), ss, __fdiv_rn(1.0f, (float)dim));
+        const float scale = adagrad_scale(acc_new, fz.lr, fz.eps);
+        const uint32_t row = (uint32_t)p_row;
+        if (lane_on) {
+            char* wp = const_cast<char*>(chunk_row_cptr(fz.v, row)) + sub * kWB;
+            if (!TBL_BF16) {
+                st16(wp, V16{__float_as_uint(adagrad_w(__uint_as_float(p_w.x), p_g.f[0], scale)),
+                             __float_as_uint(adagrad_w(__uint_as_float(p_w.y), p_g.f[1], scale)),
+                             __float_as_uint(adagrad_w(__uint_as_float(p_w.z), p_g.f[2], scale)),
+                             __float_as_uint(adagrad_w(__uint_as_float(p_w.w), p_g.f[3], scale))});
+            } else {
+                const uint32_t o0 = pack_bf16(adagrad_w(bf16lo(p_w.x), p_g.f[0], scale), adagrad_w(bf16hi(p_w.x), p_g.f[1], scale));
+                const uint32_t o1 = pack_bf16(adagrad_w(bf16lo(p_w.y), p_g.f[2], scale), adagrad_w(bf16hi(p_w.y), p_g.f[3], scale));
+                if constexpr (FPL == 8) {
+                    const uint32_t o2 = pack_bf16(adagrad_w(bf16lo(p_w.z), p_g.f[4], scale), adagrad_w(bf16hi(p_w.z), p_g.f[5], scale));
+                    const uint32_t o3 = pack_bf16(adagrad_w(bf16lo(p_w.w), p_g.f[6], scale), adagrad_w(bf16hi(p_w.w), p_g.f[7], scale));
+                    st16(wp, V16{o0, o1, o2, o3});
+                } else {
+                    *reinterpret_cast<uint2*>(wp) = make_uint2(o0, o1);
+                }
+            }
+        }
+        if (sub == 0) {
+            RowMeta* m = &fz.v.st->meta[row >> fz.v.chunk_log2][row & ((1u << fz.v.chunk_log2) - 1u)];
+            if (fz.touch) st16(m, V16{__float_as_uint(acc_new), fz.step, p_rec.z + 1u, p_rec.w});
+            else m->acc = acc_new;
+        }
+    };
+    // the sum in `acc` is complete for the segment whose row is `row`: park it and fetch what the update needs
+    auto start_update = [&](int row) {
+        finish_update();
+        if (row < 0) return;
+        p_on = true;
+        p_row = row;
+        p_g = acc;
+        const uint32_t r = (uint32_t)row;
+        p_rec = ld16(&fz.v.st->meta[r >> fz.v.chunk_log2][r & ((1u << fz.v.chunk_log2) - 1u)]);
+        if (lane_on) {
+            const char* wp = chunk_row_cptr(fz.v, r) + sub * kWB;
+            if (kWB == 16) p_w = ld16(wp);
+            else {
+                const uint2 t = *reinterpret_cast<const uint2*>(wp);
+                p_w.x = t.x;
+                p_w.y = t.y;
+            }
+        }
+    };
+
+    // flush the current run: first run of the span -> partial slot 0, otherwise complete -> reduced[] (or the update)
     auto flush_mid = [&](void) {
         if (!have) return;
         if (runs_closed == 0 && !last_level) {
             if (lane_on) acc_store<FPL>(part_rows + (size_t)(2 * span) * dim, sub, acc);
             if (sub == 0) part_seg[2 * span] = cur_seg;
+        } else if (FUSE) {
+            start_update(cur_row);
         } else {
             if (lane_on) acc_store<FPL>(reduced + (size_t)cur_seg * dim, sub, acc);
         }
@@ -259,11 +333,13 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
     for (int c = 0; c < kSpan; c += kChunk) {
         int64_t my_src[kPre];
         int my_seg[kPre];
+        int my_row[kPre];
 #pragma unroll
         for (int u = 0; u < kPre; ++u) {
             const int it = c + u * LPR + sub;
             my_src[u] = -1;
             my_seg[u] = -1;
+            my_row[u] = -1;
             if (group_on && it < items) {
                 const int64_t j = first + it;
                 if (LEVEL1) {
@@ -273,29 +349,33 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
                     my_src[u] = j;
                 }
                 my_seg[u] = in.seg[j];
+                if (FUSE && my_seg[u] >= 0) my_row[u] = fz.row_idx[my_seg[u]];
             }
         }
         // batch b fetches the rows of flat items b*UNR .. b*UNR+UNR-1 of the chunk
-        auto issue = [&](int b, V16* v_, int* sg_) {
+        auto issue = [&](int b, V16* v_, int* sg_, int* rw_) {
 #pragma unroll
             for (int k = 0; k < UNR; ++k) {
                 const int f = b * UNR + k;
                 sg_[k] = -1;
+                rw_[k] = -1;
                 v_[k] = V16{0u, 0u, 0u, 0u};
                 if (f < kChunk) {
                     const int sl = gbase + f % LPR;
                     const long long src = (long long)shfl64((uint64_t)my_src[f / LPR], sl);
                     sg_[k] = __shfl(my_seg[f / LPR], sl, kWave);
+                    if (FUSE) rw_[k] = __shfl(my_row[f / LPR], sl, kWave);
                     if (lane_on && sg_[k] >= 0) v_[k] = ld16(in.rows + (size_t)src * (size_t)in.in_row_bytes + sub * 16);
                 }
             }
         };
-        auto fold = [&](const V16* v_, const int* sg_) {
+        auto fold = [&](const V16* v_, const int* sg_, const int* rw_) {
 #pragma unroll
             for (int k = 0; k < UNR; ++k) {
                 if (sg_[k] < 0) continue;
                 if (have && sg_[k] != cur_seg) flush_mid();
                 cur_seg = sg_[k];
+                cur_row = rw_[k];
                 have = true;
                 acc_add(acc, v_[k], false);
             }
@@ -303,27 +383,31 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
         if constexpr (UNR <= 4) {
             // the loads of batch b+1 are issued before batch b is folded, so that a wave always has loads in flight
             V16 val[2][UNR];
-            int seg[2][UNR];
-            issue(0, val[0], seg[0]);
+            int seg[2][UNR], rw[2][UNR];
+            issue(0, val[0], seg[0], rw[0]);
 #pragma unroll
             for (int b = 0; b < kBatches; ++b) {
-                if (b + 1 < kBatches) issue(b + 1, val[(b + 1) & 1], seg[(b + 1) & 1]);
-                fold(val[b & 1], seg[b & 1]);
+                if (b + 1 < kBatches) issue(b + 1, val[(b + 1) & 1], seg[(b + 1) & 1], rw[(b + 1) & 1]);
+                fold(val[b & 1], seg[b & 1], rw[b & 1]);
             }
         } else {
             V16 val[UNR];
-            int seg[UNR];
+            int seg[UNR], rw[UNR];
 #pragma unroll
             for (int b = 0; b < kBatches; ++b) {
-                issue(b, val, seg);
-                fold(val, seg);
+                issue(b, val, seg, rw);
+                fold(val, seg, rw);
             }
         }
     }
     // last run of the span
     if (group_on) {
         if (last_level) {
-            if (have && lane_on) acc_store<FPL>(reduced + (size_t)cur_seg * dim, sub, acc);
+            if (FUSE) {
+                if (have) start_update(cur_row);
+            } else if (have && lane_on) {
+                acc_store<FPL>(reduced + (size_t)cur_seg * dim, sub, acc);
+            }
         } else {
             // a span with a single run has already nothing in slot 0: put the run there, slot 1 empty
             const int slot = (runs_closed == 0) ? 0 : 1;
@@ -334,6 +418,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
             }
         }
     }
+    finish_update();
 }
 
 struct ReduceLayout {
@@ -364,9 +449,11 @@ ReduceLayout reduce_layout(int64_t n, int dim) {
     return L;
 }
 
-template <int LPR, int FPL>
+template <int LPR, int FPL, int FUSE>
 int launch_reduce(const char* grad, int in_row_bytes, const int32_t* seg_of, const int32_t* perm, const int32_t* via,
-                  int64_t n, int dim, float* reduced, char* ws, const ReduceLayout& L, hipStream_t s) {
+                  int64_t n, int dim, float* reduced, char* ws, const ReduceLayout& L, hipStream_t s,
+                  const FuseArgs& fz = FuseArgs{}) {
+    constexpr bool kTblBf16 = FUSE && FPL == 8;   // the fused form takes gradients in the table dtype
     constexpr int kGroups = kWave / LPR;
     constexpr int kSpansPerBlock = (kBlock / kWave) * kGroups;
     for (int l = 0; l < L.levels; ++l) {
@@ -376,7 +463,7 @@ int launch_reduce(const char* grad, int in_row_bytes, const int32_t* seg_of, con
         int32_t* pseg = reinterpret_cast<int32_t*>(ws + L.seg_off[l]);
         if (l == 0) {
             LevelIn in{grad, perm, via, seg_of, n, in_row_bytes};
-            hipLaunchKernelGGL((k_seg_reduce<LPR, FPL, true, kUnroll>), dim3(grid), dim3(kBlock), 0, s, in, dim, reduced, prow, pseg, last);
+            hipLaunchKernelGGL((k_seg_reduce<LPR, FPL, true, kUnroll, FUSE, kTblBf16>), dim3(grid), dim3(kBlock), 0, s, in, dim, reduced, prow, pseg, last, fz);
         } else {
             LevelIn in{ws + L.rows_off[l - 1], nullptr, nullptr, reinterpret_cast<const int32_t*>(ws + L.seg_off[l - 1]),
                        L.items[l], dim * 4};
@@ -385,7 +472,7 @@ int launch_reduce(const char* grad, int in_row_bytes, const int32_t* seg_of, con
             constexpr int kGroups2 = kWave / LPR2;
             constexpr int kSpb2 = (kBlock / kWave) * kGroups2;
             const unsigned grid2 = (unsigned)((L.spans[l] + kSpb2 - 1) / kSpb2);
-            hipLaunchKernelGGL((k_seg_reduce<LPR2, 4, false, kUnrollUpper>), dim3(grid2), dim3(kBlock), 0, s, in, dim, reduced, prow, pseg, last);
+            hipLaunchKernelGGL((k_seg_reduce<LPR2, 4, false, kUnrollUpper, FUSE, kTblBf16>), dim3(grid2), dim3(kBlock), 0, s, in, dim, reduced, prow, pseg, last, fz);
         }
         MTGR_LAUNCH_CHECK();
     }
@@ -832,19 +919,22 @@ size_t grad_segment_reduce_workspace_bytes(int64_t n, int dim) {
 }
 
 static int reduce_dispatch(const void* grad, int grad_dtype, const int32_t* seg_of, const int32_t* perm, const int32_t* via,
-                           int64_t n, int dim, float* reduced, void* workspace, size_t workspace_bytes, hipStream_t s) {
+                           int64_t n, int dim, float* reduced, void* workspace, size_t workspace_bytes, hipStream_t s,
+                           const FuseArgs* fz = nullptr) {
     const int in_row_bytes = dim * (grad_dtype == EMB_F32 ? 4 : 2);
     if (in_row_bytes % 16 != 0 || dim > 256) return EMB_ERR_INVALID_ARG;
-    if (!grad || !seg_of || !perm || !reduced) return EMB_ERR_INVALID_ARG;
+    if (!grad || !seg_of || !perm || (!reduced && !fz)) return EMB_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(grad) & 15) || (reinterpret_cast<uintptr_t>(reduced) & 15)) return EMB_ERR_INVALID_ARG;
     const ReduceLayout L = reduce_layout(n, dim);
     if (!workspace || workspace_bytes < L.total || (reinterpret_cast<uintptr_t>(workspace) & 255)) return EMB_ERR_WORKSPACE;
     const char* g = static_cast<const char*>(grad);
     char* ws = static_cast<char*>(workspace);
     const int vecs = in_row_bytes / 16;
-#define MTGR_RED(L_)                                                                                               \
-    (grad_dtype == EMB_F32 ? launch_reduce<L_, 4>(g, in_row_bytes, seg_of, perm, via, n, dim, reduced, ws, L, s) \
-                           : launch_reduce<L_, 8>(g, in_row_bytes, seg_of, perm, via, n, dim, reduced, ws, L, s))
+#define MTGR_RED(L_)                                                                                                      \
+    (fz ? (grad_dtype == EMB_F32 ? launch_reduce<L_, 4, 1>(g, in_row_bytes, seg_of, perm, via, n, dim, reduced, ws, L, s, *fz) \
+                                 : launch_reduce<L_, 8, 1>(g, in_row_bytes, seg_of, perm, via, n, dim, reduced, ws, L, s, *fz)) \
+        : (grad_dtype == EMB_F32 ? launch_reduce<L_, 4, 0>(g, in_row_bytes, seg_of, perm, via, n, dim, reduced, ws, L, s)      \
+                                 : launch_reduce<L_, 8, 0>(g, in_row_bytes, seg_of, perm, via, n, dim, reduced, ws, L, s)))
     if (vecs <= 1) return MTGR_RED(1);
     if (vecs <= 2) return MTGR_RED(2);
     if (vecs <= 4) return MTGR_RED(4);
@@ -861,6 +951,19 @@ int grad_segment_reduce(const void* grad, int grad_dtype, const int32_t* seg_of,
     if (n == 0) return EMB_OK;
     return reduce_dispatch(grad, grad_dtype, seg_of, perm, nullptr, n, dim, reduced, workspace, workspace_bytes,
                            static_cast<hipStream_t>(stream));
+}
+
+int grad_reduce_apply_adagrad(emb_table_t* t, const void* grad, const int32_t* seg_of, const int32_t* perm, int64_t n,
+                              const int32_t* row_idx, float lr, float eps, int touch, uint32_t step, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+    if (!t || n < 0 || n > 0x7FFFFFFFll) return EMB_ERR_INVALID_ARG;
+    if (n == 0) return EMB_OK;
+    if (!row_idx) return EMB_ERR_INVALID_ARG;
+    if (t->n_chunks == 0) return EMB_ERR_NO_STORAGE;
+    if (t->hot_values) return EMB_ERR_INVALID_ARG; // rows with fp32 masters take the two-call form
+    FuseArgs fz{t->view(), row_idx, lr, eps, step, touch ? 1 : 0};
+    return reduce_dispatch(grad, t->desc.dtype, seg_of, perm, nullptr, n, t->desc.dim, nullptr, workspace, workspace_bytes,
+                           static_cast<hipStream_t>(stream), &fz);
 }
 
 // ---------------------------------------------------------------------------- pooling (Sec. 3.2, HashTableCollection)

@@ -241,6 +241,12 @@ def backward(table: EmbeddingTable, buf: StepBuffers, grad, n: int, lr: float, e
     table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, lr, eps, touch_step)
 
 
+def backward_fused(table: EmbeddingTable, buf: StepBuffers, grad, n: int, lr: float, eps: float = 1e-8,
+                   touch_step: Optional[int] = None) -> None:
+    """segment-reduce and row-wise Adagrad in one pass (buf.reduced is not written)."""
+    B.grad_reduce_apply_adagrad(table.h, grad, buf.seg_of, buf.perm, n, buf.row_idx, lr, eps, touch_step, buf.reduce_ws)
+
+
 def forward_fused(table: EmbeddingTable, buf: StepBuffers, x, field_off, field_tag, tag_bits: int, step: int) -> None:
     """tag -> dedup -> find-or-insert -> gather+expand in one kernel; results in buf.out[:n]
     (buf.uniq_rows is not written)."""

@@ -483,3 +483,47 @@ def test_notouch_lookup_with_duplicate_new_keys_resolves_every_element():
     assert np.array_equal(ek, np.unique(ks)) and (ef == 0).all() and (el == 5).all()
     assert t.stats()["status"] == 0
     t.close()
+
+
+# --------------------------------------------------------------------------- fused backward
+@pytest.mark.parametrize("dim,dtype", [(64, 0), (128, 1), (32, 0), (16, 0), (256, 0), (24, 0), (4, 0), (40, 1), (8, 1)])
+@pytest.mark.parametrize("touch", [False, True])
+def test_fused_backward_equals_reduce_then_adagrad(dim, dtype, touch):
+    """grad_reduce_apply_adagrad must leave the table bit-identical to grad_segment_reduce + ht_apply_adagrad(_touch):
+    same summation tree, same update arithmetic; long segments (several levels), single rows and skipped rows included."""
+    from paper_2505_12663_amd import backward, backward_fused
+    lr, eps = 0.05, 1e-8
+    ta = EmbeddingTable(dim, dtype, capacity_log2=14, chunk_rows_log2=11)
+    tb = EmbeddingTable(dim, dtype, capacity_log2=14, chunk_rows_log2=11)
+    rng = np.random.default_rng(dim + 7 * dtype)
+    vocab = np.arange(1, 4001, dtype=np.uint64) * np.uint64(2654435761)
+    n = 64 * 64 * 3 + 77
+    bufa, bufb = StepBuffers(n, dim, dtype), StepBuffers(n, dim, dtype)
+    for step in range(1, 5):
+        wts = 1.0 / np.arange(1, 4001) ** 1.2
+        ks = vocab[rng.choice(4000, size=n, p=wts / wts.sum())]
+        ks[: n // 3] = vocab[0]                                     # one segment of thousands of positions
+        dk = dev_keys(ks)
+        G = torch.from_numpy(normal_grads(5, step, n, dim)).cuda()
+        if dtype == 1:
+            G = G.to(torch.bfloat16)
+        for t, buf in ((ta, bufa), (tb, bufb)):
+            B.emb_dedup(dk, n, buf.uniq, buf.inverse, buf.counts, buf.perm, buf.seg_off, buf.seg_of, buf.n_unique, buf.dedup_ws)
+            t.find_or_insert(buf.uniq, buf.n_unique, n, step, buf.row_idx, buf.inserted, touch=not touch)
+        U = int(bufa.n_unique.item())
+        if step == 3:                                               # a segment without a row is skipped by both forms
+            bufa.row_idx[5] = -1
+            bufb.row_idx[5] = -1
+        backward(ta, bufa, G, n, lr, eps, touch_step=step if touch else None)
+        backward_fused(tb, bufb, G, n, lr, eps, touch_step=step if touch else None)
+        for a, b in zip(ta.export(), tb.export()):
+            assert np.array_equal(a, b)
+    assert ta.stats()["status"] == 0 and tb.stats()["status"] == 0
+    # hot-store tables take the two-call form
+    if dtype == 1:
+        th = EmbeddingTable(dim, dtype, capacity_log2=10, chunk_rows_log2=6, hot_rows=4)
+        with pytest.raises(B.EmbError):
+            backward_fused(th, bufb, G, n, lr, eps)
+        th.close()
+    ta.close()
+    tb.close()
