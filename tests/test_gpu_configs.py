@@ -192,3 +192,50 @@ def test_config5_bf16_scaled(one_record_update):
     assert np.allclose(ga[pos], oa, rtol=1e-4)
     assert pair.gpu.stats()["live"] == len(all_keys) + new_total
     pair.gpu.close()
+
+
+@pytest.mark.parametrize("seed", list(range(12)))
+def test_random_shapes_whole_steps(seed):
+    """Whole steps at randomly drawn shapes (row width, dtype, list lengths, vocabulary, number of fields and tables,
+    share of fresh keys), three steps each with an eviction in between, against the checker."""
+    rng = np.random.default_rng(1000 + seed)
+    dim = int(rng.choice([4, 8, 16, 24, 32, 64, 128, 256]))
+    dtype = int(rng.integers(0, 2))
+    if dtype == 1 and (dim * 2) % 16 != 0:
+        dim = 8 * ((dim + 7) // 8)
+    n_tables = int(rng.integers(1, 6))
+    n_fields = int(rng.integers(n_tables, n_tables + 4))
+    owner = list(range(n_tables)) + [int(t) for t in rng.integers(0, n_tables, size=n_fields - n_tables)]
+    tag_bits = max(1, int(np.ceil(np.log2(n_tables + 1))))
+    vocab = [int(v) for v in rng.integers(5, 5000, size=n_tables)]
+    pair = Pair(dim, dtype, capacity_log2=12, chunk_rows_log2=9, max_load_factor=float(rng.choice([0.5, 0.75, 0.85])))
+    n_max = 40_000
+    buf = StepBuffers(n_max, dim, dtype)
+    lr, eps = 0.05, 1e-8
+    one_record = bool(rng.integers(0, 2))
+    for step in range(1, 4):
+        lens = rng.integers(0, 3000, size=n_fields)
+        lens[rng.integers(0, n_fields)] = 0                              # an empty field
+        xs = []
+        for f in range(n_fields):
+            t = owner[f]
+            ids = rng.zipf(1.3, size=int(lens[f])) % vocab[t]
+            fresh = rng.random(int(lens[f])) < 0.1
+            ids = np.where(fresh, vocab[t] + step * 100000 + rng.integers(0, 50, size=int(lens[f])), ids)
+            xs.append(ids.astype(np.uint64))
+        x = np.concatenate(xs) if sum(lens) else np.zeros(0, dtype=np.uint64)
+        if len(x) == 0:
+            continue
+        off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+        tags = np.array(owner, dtype=np.uint8)
+        G = normal_grads(77 + seed, step, len(x), dim)
+        if dtype == 1:
+            G = torch.from_numpy(G).to(torch.bfloat16).float().numpy()
+        run_step(pair, buf, x, off, tags, tag_bits, step, G, lr, eps, one_record_update=one_record)
+        pair.compare_tables(lr)
+        if step == 2:
+            ev, n_ev = pair.gpu.evict(step, 1, 2, 0)
+            assert np.array_equal(np.sort(host_keys(ev)), pair.orc.evict(step, 1, 2, 0))
+    st = pair.gpu.stats()
+    assert st["status"] == 0 and st["live"] == len(pair.orc)
+    pair.gpu.close()
