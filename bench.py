@@ -253,6 +253,33 @@ def main() -> int:
                                   "note": "ht_gather_expand_sorted replaces ht_gather + emb_expand_sorted: same result, "
                                           "2 x rowbytes x unique fewer bytes moved"}
 
+    # ---- the leanest form that still delivers every output of the step on one GPU: no position-ordered inverse
+    # (the sorted-order pair perm / seg_of carries the mapping) and the fused lookup, as an extra line
+    if not args.no_extras:
+        def one_step_lean(step: int):
+            dx, doff, dtag, n, _ = batches[step % len(batches)]
+            B.emb_tag_keys(dx, doff, dtag, tag_bits, buf.key, buf.err_count)
+            B.emb_dedup(buf.key, n, buf.uniq, None, None, buf.perm, None, buf.seg_of, buf.n_unique, buf.dedup_ws)
+            table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted, touch=touch)
+            B.ht_gather_expand_sorted(table.h, buf.row_idx, buf.seg_of, buf.perm, n, buf.out)
+            B.grad_segment_reduce(grad, dtype, buf.seg_of, buf.perm, n, dim, buf.reduced, buf.reduce_ws)
+            table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps, None if touch else step + 1)
+            return n
+
+        base_l = base + 3 * (2 + args.steps)
+        for s in range(2):
+            one_step_lean(base_l + s)
+        torch.cuda.synchronize()
+        t_l = time.perf_counter()
+        ids_l = 0
+        for k in range(args.steps):
+            ids_l += one_step_lean(base_l + 2 + k)
+        torch.cuda.synchronize()
+        wall_l = time.perf_counter() - t_l
+        result["lean_step"] = {"ms_per_step": round(wall_l * 1e3 / args.steps, 4), "ids_per_sec": round(ids_l / wall_l, 1),
+                               "note": "emb_dedup without the position-ordered inverse array + ht_gather_expand_sorted: "
+                                       "same embeddings out, same table after the step"}
+
     # ---- both fusions of the no-communication case: fused lookup and fused backward (no distinct-row matrix, no
     # reduced-gradient matrix), as an extra line
     if not args.no_extras:

@@ -169,7 +169,10 @@ int emb_tag_keys(const uint64_t* x, const int64_t* field_off, const uint8_t* fie
 
 /* Stage-1 deduplication (Sec. 3.3).  key [dev, n] ->
  *   uniq [dev, n]: distinct keys ascending, first *n_unique entries valid;
- *   inverse [dev, n, int32]: uniq[inverse[i]] == key[i];
+ *   inverse [dev, n, int32, optional]: uniq[inverse[i]] == key[i].  The same mapping is delivered in
+ *     sorted order by (perm, seg_of), which is what emb_expand_sorted, ht_gather_expand_sorted and
+ *     grad_segment_reduce consume; the position-ordered array is a scatter of n random 4-byte writes
+ *     (about a sixth of the call's time on long-sequence batches), so pass NULL when nothing reads it;
  *   counts [dev, n, int32, optional]: occurrences of uniq[u];
  *   perm [dev, n, int32, optional]: positions ordered by (key, position); the positions of
  *     uniq[u] are perm[seg_off[u] .. seg_off[u+1]);

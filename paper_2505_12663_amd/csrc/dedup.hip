@@ -470,7 +470,7 @@ __global__ __launch_bounds__(kThreads) void k_emit(DdBuffers b, const DdHeader* 
         running += (unsigned)__popcll(m);
         if (j < n) {
             const uint32_t p = idxs ? idxs[j] : (uint32_t)j;
-            inverse[p] = (int32_t)seg;
+            if (inverse) inverse[p] = (int32_t)seg;
             if (perm) perm[j] = (int32_t)p;
             if (seg_of) seg_of[j] = (int32_t)seg;
             if (head) {
@@ -554,7 +554,7 @@ int emb_dedup(const uint64_t* key, int64_t n, uint64_t* uniq, int32_t* inverse, 
         MTGR_LAUNCH_CHECK();
         return EMB_OK;
     }
-    if (!key || !uniq || !inverse) return EMB_ERR_INVALID_ARG;
+    if (!key || !uniq) return EMB_ERR_INVALID_ARG;
     const DdLayout L = dd_layout(n);
     if (!workspace || workspace_bytes < L.total || (reinterpret_cast<uintptr_t>(workspace) & 255)) return EMB_ERR_WORKSPACE;
     char* w = static_cast<char*>(workspace);

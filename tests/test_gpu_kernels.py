@@ -404,3 +404,25 @@ def test_fused_gather_expand_equals_the_two_calls(dim, dtype):
         ot.apply_adagrad(ou, oracle.segment_reduce(G, oi, len(ou)), 0.01, 1e-8)
     ta.close()
     tb.close()
+
+
+def test_dedup_without_position_ordered_inverse():
+    """inverse is optional: with NULL every other output is unchanged, and (perm, seg_of) carry the same mapping."""
+    keys = _zipf_keys(50_000, 7000, 3)
+    n = len(keys)
+    a, b = StepBuffers(n, 16, with_grad=False), StepBuffers(n, 16, with_grad=False)
+    dk = dev_keys(keys)
+    B.emb_dedup(dk, n, a.uniq, a.inverse, a.counts, a.perm, a.seg_off, a.seg_of, a.n_unique, a.dedup_ws)
+    b.inverse.fill_(-7)
+    B.emb_dedup(dk, n, b.uniq, None, b.counts, b.perm, b.seg_off, b.seg_of, b.n_unique, b.dedup_ws)
+    U = int(a.n_unique.item())
+    assert int(b.n_unique.item()) == U
+    for x, y, m in ((a.uniq, b.uniq, U), (a.counts, b.counts, U), (a.perm, b.perm, n), (a.seg_of, b.seg_of, n),
+                    (a.seg_off, b.seg_off, U + 1)):
+        assert torch.equal(x[:m], y[:m])
+    assert bool((b.inverse == -7).all())                                   # untouched
+    rebuilt = torch.empty(n, dtype=torch.int32, device="cuda")
+    rebuilt[b.perm[:n].long()] = b.seg_of[:n]
+    assert torch.equal(rebuilt, a.inverse[:n])                             # inverse[perm[j]] == seg_of[j]
+    ou, oi, oc = oracle.dedup(keys)
+    assert np.array_equal(rebuilt.cpu().numpy(), oi) and np.array_equal(host_keys(b.uniq[:U]), ou)
