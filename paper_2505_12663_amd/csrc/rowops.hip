@@ -18,8 +18,11 @@ using namespace mtgr;
 namespace {
 
 constexpr int kBlock = 256;
+#ifndef MTGR_RED_PIPE_MAX
+#define MTGR_RED_PIPE_MAX 8
+#endif
 #ifndef MTGR_RED_UNROLL_UPPER
-#define MTGR_RED_UNROLL_UPPER 16
+#define MTGR_RED_UNROLL_UPPER 8
 #endif
 #ifndef MTGR_RED_UNROLL
 #define MTGR_RED_UNROLL 4
@@ -227,8 +230,9 @@ struct FuseArgs {
     int touch;                // also set last_seen = step and count one touch
 };
 
-// UNR = rows a group keeps in flight per batch: 4 with the next batch prefetched for the large
-// first level; 16 for the small upper levels, which are chains of dependent round trips.
+// UNR = rows a group fetches per batch, the next batch being fetched while the current one is
+// folded: 4 at the large first level, 8 at the small upper levels, which are chains of dependent
+// round trips (their stores would otherwise sit between a batch's loads and their use).
 // FUSE = 1: apply Adagrad to completed sums (table dtype TBL_BF16) instead of storing them.
 template <int LPR, int FPL, bool LEVEL1, int UNR, int FUSE, bool TBL_BF16>
 __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, float* __restrict__ reduced,
@@ -380,7 +384,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
                 acc_add(acc, v_[k], false);
             }
         };
-        if constexpr (UNR <= 4) {
+        if constexpr (UNR <= MTGR_RED_PIPE_MAX) {
             // the loads of batch b+1 are issued before batch b is folded, so that a wave always has loads in flight
             V16 val[2][UNR];
             int seg[2][UNR], rw[2][UNR];
