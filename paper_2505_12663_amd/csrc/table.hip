@@ -146,6 +146,8 @@ __device__ inline long long probe_group(const HtView& v, uint64_t key, bool acti
 // "no match among the occupied slots before the first empty one" stays true, and the CAS itself
 // decides whether that slot was still empty; if it went to another key the element simply takes the
 // line-by-line path.  found_slot stays -1 for unsettled elements.
+constexpr long long kSlotAbsent = -3;   // first_line_pass<false>: settled, the key is not in the table
+
 template <bool INSERT>
 __device__ inline void first_line_pass(const HtView& v, uint64_t my_key, bool my_ok, int lane, long long* found_slot,
                                        uint32_t* found_row, bool* created, ProbeCounters* pc) {
@@ -179,6 +181,12 @@ __device__ inline void first_line_pass(const HtView& v, uint64_t my_key, bool my
         }
         pc->probes += (sub == r && ok) ? 1u : 0u;
         cas_old[r] = 0;
+        if (!INSERT) {
+            // read-only lookup: a never-used slot in the first line and no match means the key is absent
+            const uint64_t me = __ballot(ok && k == kEmptyKey);
+            const unsigned empty8 = (unsigned)(me >> gbase) & 0xFFu;
+            if (sub == r && !hit8 && empty8) *found_slot = kSlotAbsent;
+        }
         if (INSERT) {
             const uint64_t me = __ballot(ok && k == kEmptyKey);
             const unsigned empty8 = (unsigned)(me >> gbase) & 0xFFu;
@@ -446,7 +454,7 @@ __global__ __launch_bounds__(kBlock) void k_find(HtView v, const uint64_t* __res
     uint32_t my_row;
     bool unused_created;
     first_line_pass<false>(v, my_key, my_ok, lane, &my_slot, &my_row, &unused_created, &pc);
-    const bool need_slow = my_ok && my_slot < 0;
+    const bool need_slow = my_ok && my_slot == -1;
     if (__any(need_slow)) {
         for (int r = 0; r < kLineSlots; ++r) {
             const bool act = __shfl((int)need_slow, gbase + r, kWave) != 0;
