@@ -56,6 +56,10 @@ def main() -> int:
     ap.add_argument("--touch-in-lookup", action="store_true",
                     help="ht_find_or_insert + ht_apply_adagrad (two updates of every row record per step) instead of "
                          "ht_find_or_insert_notouch + ht_apply_adagrad_touch (one)")
+    ap.add_argument("--literal-zipf", action="store_true",
+                    help="extra line: config 2 with ranks Zipf-distributed over the whole 2^40 key space (about a quarter "
+                         "of the IDs miss the pre-populated table, so it grows by ~2 M keys per step); runs last, "
+                         "takes ~30 s more")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the fused-lookup and pooled-lookup extra lines (profiling runs: only the step's own kernels)")
     ap.add_argument("--count-probes", action="store_true", help="maintain probe/CAS counters (small overhead)")
@@ -383,6 +387,51 @@ def main() -> int:
                 "expand_ms": round(t_e, 4), "reduce_ms": round(t_r, 4),
                 "note": "field vocabularies 6.25M, 20k, 6.25M, 500k, 100, 24, 8, 50: worst case for the segmented "
                         "reduction (one segment spans thousands of spans)"}
+
+    # ---- literal reading of "Zipf over a 2^40 key space": the table keeps growing (inserts, new chunks, rehash)
+    if args.config == 2 and args.literal_zipf:
+        wz = make_config(2, field_vocab=[2 ** 40] * 8)
+        wz.prepopulated = list(w.prepopulated)
+        k_steps = min(args.steps, 10)
+        zb = []
+        for s_ in range(k_steps + 1):
+            bz = wz.next_step(s_)
+            xz, offz, tagz, _ = merged_inputs(wz.features, bz.ids, merged, 0)
+            if len(xz) <= n_max:
+                zb.append((torch.from_numpy(xz.view(np.int64)).to(dev), torch.from_numpy(offz).to(dev),
+                           torch.from_numpy(tagz).to(dev), len(xz)))
+        st0 = table.stats()
+
+        def one_step_z(i: int, step: int):
+            dx, doff, dtag, n = zb[i]
+            B.emb_tag_keys(dx, doff, dtag, tag_bits, buf.key, buf.err_count)
+            B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, None, buf.perm, None, buf.seg_of, buf.n_unique, buf.dedup_ws)
+            table.find_or_insert(buf.uniq, buf.n_unique, n, step, buf.row_idx, buf.inserted, touch=touch)
+            table.gather(buf.row_idx, buf.n_unique, n, buf.uniq_rows)
+            B.emb_expand_sorted(buf.uniq_rows, buf.seg_of, buf.perm, n, dim, dtype, buf.out)
+            B.grad_segment_reduce(grad, dtype, buf.seg_of, buf.perm, n, dim, buf.reduced, buf.reduce_ws)
+            table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps, None if touch else step)
+            return n
+
+        base_z = 10_000
+        one_step_z(0, base_z)                       # warm-up on a batch of its own
+        torch.cuda.synchronize()
+        st1 = table.stats()
+        t_z = time.perf_counter()
+        ids_z = 0
+        for k in range(1, len(zb)):
+            ids_z += one_step_z(k, base_z + k)
+        torch.cuda.synchronize()
+        wall_z = time.perf_counter() - t_z
+        st2 = table.stats()
+        nz = len(zb) - 1
+        result["literal_zipf"] = {
+            "steps": nz, "ms_per_step": round(wall_z * 1e3 / nz, 4), "ids_per_sec": round(ids_z / wall_z, 1),
+            "new_keys_per_step": round((st2["live"] - st1["live"]) / nz, 1), "live_after": st2["live"],
+            "chunks_added": st2["n_chunks"] - st0["n_chunks"], "rehashes": st2["n_rehash"] - st0["n_rehash"],
+            "status": st2["status"],
+            "note": "ranks Zipf(1.05) over 2^40, top 6.25 M ranks per field pre-populated: every step creates rows "
+                    "for about a quarter of its IDs; host-side capacity planning (chunk registration, rehash) included"}
 
     if args.copy_probe_mib > 0:
         nbytes = args.copy_probe_mib << 20
