@@ -335,7 +335,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
     constexpr int kChunk = LPR * kPre;                        // items per chunk (flat index f = u*LPR + lane-in-group)
     constexpr int kBatches = (kChunk + UNR - 1) / UNR;
     for (int c = 0; c < kSpan; c += kChunk) {
-        int64_t my_src[kPre];
+        int my_src[kPre];          // source row of the item (< 2^31)
         int my_seg[kPre];
         int my_row[kPre];
 #pragma unroll
@@ -348,9 +348,9 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
                 const int64_t j = first + it;
                 if (LEVEL1) {
                     const int32_t p = in.perm[j];
-                    my_src[u] = in.via ? (int64_t)in.via[p] : (int64_t)p;
+                    my_src[u] = in.via ? in.via[p] : p;
                 } else {
-                    my_src[u] = j;
+                    my_src[u] = (int)j;
                 }
                 my_seg[u] = in.seg[j];
                 if (FUSE && my_seg[u] >= 0) my_row[u] = fz.row_idx[my_seg[u]];
@@ -366,7 +366,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
                 v_[k] = V16{0u, 0u, 0u, 0u};
                 if (f < kChunk) {
                     const int sl = gbase + f % LPR;
-                    const long long src = (long long)shfl64((uint64_t)my_src[f / LPR], sl);
+                    const int src = __shfl(my_src[f / LPR], sl, kWave);
                     sg_[k] = __shfl(my_seg[f / LPR], sl, kWave);
                     if (FUSE) rw_[k] = __shfl(my_row[f / LPR], sl, kWave);
                     if (lane_on && sg_[k] >= 0) v_[k] = ld16(in.rows + (size_t)src * (size_t)in.in_row_bytes + sub * 16);
