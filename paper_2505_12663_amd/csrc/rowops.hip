@@ -384,7 +384,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
                 acc_add(acc, v_[k], false);
             }
         };
-        if constexpr (UNR <= MTGR_RED_PIPE_MAX) {
+        if constexpr (UNR <= MTGR_RED_PIPE_MAX && !(FUSE && FPL == 8)) {   // (the parked update of 8-float lanes leaves no registers for a second batch)
             // the loads of batch b+1 are issued before batch b is folded, so that a wave always has loads in flight
             V16 val[2][UNR];
             int seg[2][UNR], rw[2][UNR];
