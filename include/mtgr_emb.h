@@ -21,10 +21,11 @@
  *     the n_unique written by emb_dedup.  Kernels are launched over `n_max` and
  *     read the count on the device, so no host read-back sits on the path.  NULL
  *     means "exactly n_max elements".
- *   - Return value: EMB_OK (0) or a negative emb_status.  Conditions that only the
- *     device can see (probe sequence exhausted, out of row storage) set sticky bits
- *     in the table's device status word, reported by ht_stats; the affected
- *     elements get row index -1 and nothing is left half-inserted.
+ *   - Return value: EMB_OK (0) or a negative emb_status (ht_find_or_insert may also
+ *     return the positive EMB_CHECK_STATUS).  Conditions that only the device can
+ *     see (load-factor limit reached, out of row storage, probe sequence exhausted)
+ *     set sticky bits in the table's device status word, reported by ht_stats; the
+ *     affected elements get row index -1 and nothing is left half-inserted.
  *   - Calls on the same table must be ordered (one stream, or events).  Two calls
  *     that overlap on one table race.
  *   - Valid keys have bit 63 clear (Eq. 8 keeps the top bit zero).  2^64-1 and
@@ -51,19 +52,26 @@ typedef enum {
     EMB_ERR_WORKSPACE = -3,   /* workspace too small or misaligned */
     EMB_ERR_NO_STORAGE = -4,  /* no key storage / not enough row chunks registered for n_max inserts */
     EMB_ERR_HIP = -5,         /* a HIP runtime call failed */
-    EMB_ERR_NEED_REHASH = -6  /* n_max inserts could push the load factor over the limit: ht_rehash first */
+    EMB_ERR_NEED_REHASH = -6, /* ht_rehash: the live keys do not fit under the limit of the new structure */
+    /* Positive, ht_find_or_insert only: the kernels were launched, but the host-side upper bounds could not prove
+     * that n_max new keys fit.  The device admits new keys only while live + deleted slots stay within
+     * floor(max_load_factor * capacity) and rows remain; compare ht_stats().refused before and after to learn
+     * whether any were turned away. */
+    EMB_CHECK_STATUS = 1
 } emb_status_t;
 
-/* bits of ht_stats_t.status (sticky, device-side) */
-#define EMB_DEV_PROBE_EXHAUSTED 1u
-#define EMB_DEV_OUT_OF_ROWS 2u
-#define EMB_DEV_BAD_KEY 4u /* a key with bit 63 set was passed; it got row index -1 */
+/* bits of ht_stats_t.status (sticky, device-side; cleared by ht_clear_status) */
+#define EMB_DEV_PROBE_EXHAUSTED 1u /* every line of a key's probe sequence was visited without finding room */
+#define EMB_DEV_OUT_OF_ROWS 2u     /* new keys were turned away because the registered chunks are full */
+#define EMB_DEV_BAD_KEY 4u         /* a key with bit 63 set was passed; it got row index -1 */
+#define EMB_DEV_NEED_REHASH 8u     /* new keys were turned away at the load-factor limit (Sec. 3.1 "Capacity Expansion") */
 
 typedef struct {
     int32_t dim;             /* elements per embedding row; row bytes must be a multiple of 16 */
     int32_t dtype;           /* emb_dtype_t of the stored rows */
     float init_scale;        /* new rows are uniform on [-init_scale, init_scale) */
-    float max_load_factor;   /* expansion trigger, (live+deleted)/capacity; 0 -> 0.75 (Sec. 3.1) */
+    float max_load_factor;   /* expansion trigger, (live+deleted)/capacity; 0 -> 0.75 (Sec. 3.1).  At most 1.0;
+                                values above 0.95 let probe sequences grow very long and serve tests only */
     int32_t chunk_rows_log2; /* every value chunk holds 2^this rows */
     int32_t count_probes;    /* nonzero: maintain the probe/CAS/allocation counters of ht_stats_t */
 } emb_table_desc_t;
@@ -88,6 +96,7 @@ typedef struct {
     uint64_t hot_rows_used;     /* high-water mark of the hot store's allocator */
     uint64_t hot_rows_free;     /* hot rows returned by evictions */
     uint64_t hot_rows_capacity;
+    uint64_t refused;       /* new keys turned away so far by find-or-insert (limit reached or out of rows); each got -1 */
 } ht_stats_t;
 
 /* ------------------------------------------------------------------ host-only planning */
@@ -138,19 +147,21 @@ int ht_add_chunk(emb_table_t* t, void* values, void* meta, uint32_t* free_list, 
  * when a key is inserted.  Inserts zero the moments only while every chunk has its state. */
 int ht_add_chunk_adam_state(emb_table_t* t, float* m, float* v, void* stream);
 
-/* Host-side capacity planning from upper bounds of the device counters: the newest copy of the
+/* Host-side capacity planning (Sec. 3.1 "Capacity Expansion": expand when the load factor passes the limit,
+ * doubling; keys only) from upper bounds of the device counters: the newest copy of the
  * counters that has reached the host (every find-or-insert / evict / rehash queues one, without
  * blocking; ht_stats fetches one synchronously) plus the n_max of every find-or-insert issued since.
- * n_incoming = upper bound of keys the next find-or-insert may add.
- * *new_capacity_log2 = 0 if the key structure is fine, else the size to rehash to: the same size
- * when purging deleted slots is enough, otherwise doubled until (live+n_incoming)/capacity is at
- * most half the load-factor limit.  *chunks_needed = chunks to add so that n_incoming rows fit. */
+ * n_incoming = keys still to be added (after a refusal: the number turned away).
+ * *new_capacity_log2 = 0 if live + deleted + n_incoming slots stay within floor(max_load_factor * capacity),
+ * else the size to rehash to: the same size when purging deleted slots is enough, otherwise doubled until
+ * (live+n_incoming)/capacity is at most half the load-factor limit.  *chunks_needed = chunks to add so that
+ * n_incoming rows fit. */
 int ht_plan(emb_table_t* t, int64_t n_incoming, int* new_capacity_log2, int* chunks_needed);
 
 /* Capacity expansion (Sec. 3.1): move every live (key,row) pair into new key storage of
  * 2^new_capacity_log2 slots (same layout and alignment as above), dropping deleted slots.
  * Embedding rows do not move.  The old array is no longer referenced once this call's work on
- * `stream` has finished.  Fails with EMB_ERR_INVALID_ARG if the live keys would exceed the
+ * `stream` has finished.  Fails with EMB_ERR_NEED_REHASH if the live keys would exceed the
  * load-factor limit of the new structure. */
 int ht_rehash(emb_table_t* t, void* new_slots, int new_capacity_log2, void* stream);
 
@@ -186,14 +197,29 @@ int emb_dedup(const uint64_t* key, int64_t n, uint64_t* uniq, int32_t* inverse, 
               int32_t* perm, int32_t* seg_off, int32_t* seg_of, int64_t* n_unique, void* workspace,
               size_t workspace_bytes, void* stream);
 
-/* Find each key; insert the absent ones (claim a slot, allocate a row, initialise the row from
- * the key, acc = 0).  Every element counts one touch: freq += 1, last_seen = step.
- * key [dev], row_idx [dev, int32] <- row of each key (-1 on a device-side failure),
+/* Sec. 3.1 (real-time insertion; open addressing with cooperative probing; "Capacity Expansion"):
+ * find each key; insert the absent ones (claim a never-used slot by compare-and-swap, allocate a row,
+ * initialise the row from the key, acc = 0).  Every element counts one touch: freq += 1, last_seen = step.
+ * key [dev], row_idx [dev, int32] <- row of each key (-1: see below),
  * inserted [dev, u8, optional] <- 1 for the element that created its entry.  Duplicate keys in
- * one call are allowed and share one row.  Fails with EMB_ERR_NEED_REHASH / EMB_ERR_NO_STORAGE
- * (nothing launched) when n_max inserts might not fit: see ht_plan. */
+ * one call are allowed and share one row.
+ * Capacity: new keys are admitted on the device while live + deleted slots stay within
+ * floor(max_load_factor * capacity) and registered rows remain.  A key that is turned away gets -1, is counted
+ * in ht_stats_t.refused and sets EMB_DEV_NEED_REHASH / EMB_DEV_OUT_OF_ROWS; nothing of it remains in the table
+ * (a key that got a slot but no row leaves a deleted marker in that slot).  Returns EMB_OK when the host-side bounds (see ht_plan) prove that n_max
+ * new keys fit, EMB_CHECK_STATUS when they do not (the caller then reads ht_stats, makes room with ht_rehash /
+ * ht_add_chunk and calls ht_find_or_insert_retry), EMB_ERR_NO_STORAGE without key storage or chunks. */
 int ht_find_or_insert(emb_table_t* t, const uint64_t* key, const int64_t* n_dev, int64_t n_max, uint32_t step,
                       int32_t* row_idx, uint8_t* inserted, void* stream);
+
+/* Second attempt after room was made: the same call restricted to the elements whose row_idx[i] is negative
+ * on entry (the ones turned away); all others, their touch counts and their `inserted` flags are left as the
+ * first call wrote them.  touch != 0: as ht_find_or_insert, touch == 0: as ht_find_or_insert_notouch. */
+int ht_find_or_insert_retry(emb_table_t* t, const uint64_t* key, const int64_t* n_dev, int64_t n_max, uint32_t step,
+                            int32_t* row_idx, uint8_t* inserted, int touch, void* stream);
+
+/* Clear the given EMB_DEV_* bits of the device status word (asynchronously on `stream`). */
+int ht_clear_status(emb_table_t* t, uint32_t bits, void* stream);
 
 /* Read-only lookup: row_idx[i] = row of key[i], or -1 if absent. */
 int ht_find(emb_table_t* t, const uint64_t* key, const int64_t* n_dev, int64_t n_max, int32_t* row_idx,

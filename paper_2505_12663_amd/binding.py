@@ -16,7 +16,8 @@ F32, BF16 = 0, 1
 EMB_OK = 0
 EMB_ERR_NO_STORAGE = -4
 EMB_ERR_NEED_REHASH = -6
-DEV_PROBE_EXHAUSTED, DEV_OUT_OF_ROWS, DEV_BAD_KEY = 1, 2, 4
+EMB_CHECK_STATUS = 1
+DEV_PROBE_EXHAUSTED, DEV_OUT_OF_ROWS, DEV_BAD_KEY, DEV_NEED_REHASH = 1, 2, 4, 8
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmtgr_emb.so")
@@ -38,7 +39,7 @@ class HtStats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in
                 ("live", "tombstones", "capacity", "rows_used", "rows_free", "rows_capacity", "n_rehash",
                  "n_chunks", "status", "lookups", "probes", "cas_attempts", "cas_failures", "alloc_atomics",
-                 "hot_rows_used", "hot_rows_free", "hot_rows_capacity")]
+                 "hot_rows_used", "hot_rows_free", "hot_rows_capacity", "refused")]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
@@ -52,6 +53,7 @@ EXPORTS = [
     "ht_apply_adagrad", "ht_apply_adam", "ht_gather_expand_sorted", "emb_pool_workspace_bytes", "emb_pool_bags",
     "grad_segment_reduce_pooled", "ht_evict", "ht_export", "ht_put", "ht_set_hot_storage", "ht_promote", "ht_export_hot",
     "ht_find_or_insert_notouch", "ht_apply_adagrad_touch", "grad_reduce_apply_adagrad",
+    "ht_find_or_insert_retry", "ht_clear_status",
 ]
 
 
@@ -83,6 +85,8 @@ def load():
         "emb_dedup": (C.c_int, [vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]),
         "ht_find_or_insert": (C.c_int, [vp, vp, vp, i64, u32, vp, vp, vp]),
         "ht_find_or_insert_notouch": (C.c_int, [vp, vp, vp, i64, u32, vp, vp, vp]),
+        "ht_find_or_insert_retry": (C.c_int, [vp, vp, vp, i64, u32, vp, vp, i32, vp]),
+        "ht_clear_status": (C.c_int, [vp, u32, vp]),
         "ht_apply_adagrad_touch": (C.c_int, [vp, vp, vp, vp, i64, f32, f32, u32, vp]),
         "grad_reduce_apply_adagrad": (C.c_int, [vp, vp, vp, vp, i64, vp, f32, f32, i32, u32, vp, C.c_size_t, vp]),
         "ht_find": (C.c_int, [vp, vp, vp, i64, vp, vp]),
@@ -217,14 +221,25 @@ def emb_dedup(key, n: int, uniq, inverse, counts, perm, seg_off, seg_of, n_uniqu
 
 
 def ht_find_or_insert(h, key, n_dev, n_max: int, step: int, row_idx, inserted=None, stream=None, touch: bool = True) -> int:
-    """Returns the status instead of raising for the two "make room first" codes.
+    """Returns EMB_OK or EMB_CHECK_STATUS (launched, but new keys may have been turned away); raises on errors.
     touch=False calls ht_find_or_insert_notouch."""
     fn = load().ht_find_or_insert if touch else load().ht_find_or_insert_notouch
     rc = fn(h, _ptr(key), _ptr(n_dev), n_max, step, _ptr(row_idx), _ptr(inserted), _stream(stream))
-    if rc in (EMB_ERR_NEED_REHASH, EMB_ERR_NO_STORAGE):
-        return rc
-    _check(rc, "ht_find_or_insert" if touch else "ht_find_or_insert_notouch")
+    if rc < 0:
+        raise EmbError(rc, "ht_find_or_insert" if touch else "ht_find_or_insert_notouch")
     return rc
+
+
+def ht_find_or_insert_retry(h, key, n_dev, n_max: int, step: int, row_idx, inserted=None, touch: bool = True, stream=None) -> int:
+    rc = load().ht_find_or_insert_retry(h, _ptr(key), _ptr(n_dev), n_max, step, _ptr(row_idx), _ptr(inserted), int(touch),
+                                        _stream(stream))
+    if rc < 0:
+        raise EmbError(rc, "ht_find_or_insert_retry")
+    return rc
+
+
+def ht_clear_status(h, bits: int, stream=None) -> None:
+    _check(load().ht_clear_status(h, bits, _stream(stream)), "ht_clear_status")
 
 
 def ht_find(h, key, n_dev, n_max: int, row_idx, stream=None) -> None:

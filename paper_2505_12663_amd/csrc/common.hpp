@@ -43,8 +43,9 @@ struct HtHead {
     unsigned int status;     // EMB_DEV_* bits
     unsigned int hot_bump;   // rows handed out from the hot store
     int hot_free_count;      // entries on the hot store's free stack
-    unsigned int pad0;
-    unsigned long long pad1[13];
+    unsigned int occupied;   // slots that are not never-used (live + deleted): inserts are admitted against the load-factor limit here
+    unsigned long long refused; // new keys turned away so far (limit reached or out of rows)
+    unsigned long long pad1[12];
     unsigned long long stat[kStatStripes][8]; // [stripe][StatSlot]; live / deleted counts are the sums over stripes
 };
 struct HtState {
@@ -64,9 +65,11 @@ struct HtCounts {
     unsigned int status;
     unsigned int hot_bump;
     int hot_free_count;
+    unsigned long long refused;
     unsigned long long stat[5];
     static HtCounts from(const HtHead& h) {
         HtCounts c{};
+        c.refused = h.refused;
         c.hot_bump = h.hot_bump;
         c.hot_free_count = h.hot_free_count;
         c.bump = h.bump;
@@ -86,6 +89,7 @@ struct HtView {
     Slot* slots;
     HtState* st;
     uint64_t line_mask;      // (capacity / kLineSlots) - 1
+    uint32_t slot_limit;     // floor(max_load_factor * capacity): live + deleted slots never exceed it
     uint32_t rows_capacity;  // rows in registered chunks
     int chunk_log2;
     int dim;
@@ -209,6 +213,8 @@ struct emb_table {
     uint64_t seq, min_valid_seq, base_seq;
     int snap_next;
 
+    // live + deleted slots the key structure may hold: floor(max_load_factor * capacity)
+    uint32_t slot_limit() const { return (uint32_t)((double)desc.max_load_factor * (double)(1ull << cap_log2)); }
     uint64_t live_bound() const { return base_live + pending; }
     uint64_t occupied_bound() const { return base_live + base_tomb + pending; }
     uint64_t rows_used_bound() const { return base_rows + pending; }
@@ -250,6 +256,7 @@ struct emb_table {
         v.slots = slots;
         v.st = st;
         v.line_mask = slots ? ((1ull << cap_log2) / mtgr::kLineSlots - 1ull) : 0ull;
+        v.slot_limit = slots ? slot_limit() : 0u;
         v.rows_capacity = (uint32_t)((uint64_t)n_chunks << desc.chunk_rows_log2);
         v.chunk_log2 = desc.chunk_rows_log2;
         v.dim = desc.dim;

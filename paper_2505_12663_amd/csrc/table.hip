@@ -73,6 +73,8 @@ struct ProbeCounters {
 // same slot.  The loop ends: a retry only follows a CAS that lost to a different key, which takes
 // one of the line's at most 8 EMPTY slots away for good; every other iteration finishes the
 // group or moves on to one of the finitely many unvisited lines.
+constexpr long long kSlotAbsent = -3;    // read-only lookup, settled: the key is not in the table
+
 template <bool INSERT>
 __device__ inline long long probe_group(const HtView& v, uint64_t key, bool active, int lane, bool* created,
                                         ProbeCounters* pc) {
@@ -146,8 +148,6 @@ __device__ inline long long probe_group(const HtView& v, uint64_t key, bool acti
 // "no match among the occupied slots before the first empty one" stays true, and the CAS itself
 // decides whether that slot was still empty; if it went to another key the element simply takes the
 // line-by-line path.  found_slot stays -1 for unsettled elements.
-constexpr long long kSlotAbsent = -3;   // first_line_pass<false>: settled, the key is not in the table
-
 template <bool INSERT>
 __device__ inline void first_line_pass(const HtView& v, uint64_t my_key, bool my_ok, int lane, long long* found_slot,
                                        uint32_t* found_row, bool* created, ProbeCounters* pc) {
@@ -246,18 +246,33 @@ __device__ inline void touch_row(const HtView& v, uint32_t row, uint32_t step) {
 }
 
 // One wave handles 64 keys: each lane owns one key; the 8 groups of 8 lanes first look at the first
-// line of each of their 8 keys, then work through the unsettled keys one after the other.  Rows
-// for the new keys of all 16 waves of a block are taken from the allocator with one atomic per
-// block (a 4 M-key bulk insert otherwise queues 130 k atomics on the bump pointer).
+// line of each of their 8 keys, then work through the unsettled keys one after the other.
+//
+// The call runs in two rounds so that the load-factor limit holds exactly (Sec. 3.1 "Capacity
+// Expansion": the key structure is expanded when the load factor passes the limit).
+//   Round 1 looks every key up without writing.  Keys that are present are settled here - the whole
+//   call, when the batch brings no new keys.
+//   Admission: the block adds the number of its absent keys to the count of occupied slots; what would
+//   exceed floor(max_load_factor * capacity) is given back, and those elements are turned away
+//   (row -1, counted in head.refused, status bit) without having claimed anything.  Live + deleted
+//   slots therefore never exceed the limit.
+//   Round 2 claims a never-used slot for every admitted key by compare-and-swap.  A key that a
+//   duplicate in another wave has inserted meanwhile is simply found; its reservation is returned.
+// Rows for the new keys of all 16 waves of a block are taken from the allocator with one atomic per
+// block (a 4 M-key bulk insert otherwise queues 130 k atomics on the bump pointer): free stack first,
+// then the bump pointer, which never passes the registered rows; a claim that gets no row leaves a
+// deleted marker in its slot and its element is turned away too.
 // TOUCH = false: existing keys are found without counting a touch and a created row starts
 // with touch count 0 (the update call of the step counts it, in the write it does anyway).
+// retry: only the elements an earlier call left at -1 are processed, the others keep their results.
 template <bool COUNT, bool TOUCH>
 __global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const uint64_t* __restrict__ key,
                                                               const int64_t* n_dev, int64_t n_max, uint32_t step,
                                                               int32_t* __restrict__ row_idx,
-                                                              uint8_t* __restrict__ inserted) {
-    __shared__ int s_new[kBigWaves];
-    __shared__ int s_old_free, s_take;
+                                                              uint8_t* __restrict__ inserted, int retry) {
+    __shared__ int s_absent[kBigWaves], s_new[kBigWaves], s_surplus[kBigWaves];
+    __shared__ unsigned s_bits[kBigWaves];
+    __shared__ int s_admitted, s_old_free, s_take, s_got;
     __shared__ unsigned s_bump;
     const int64_t n = read_count(n_dev, n_max);
     if ((int64_t)blockIdx.x * kBigBlock >= n) return; // whole block beyond the count
@@ -266,7 +281,7 @@ __global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const ui
     const int64_t wave_base = (int64_t)blockIdx.x * kBigBlock + wave * kWave;
     const bool wave_on = wave_base < n;
     const int64_t i = wave_base + lane;
-    const bool valid = i < n;
+    const bool valid = i < n && !(retry && row_idx[i] >= 0);
     const uint64_t my_key = valid ? key[i] : 0ull;
     const bool bad = valid && (my_key >> 63);
     const bool my_ok = valid && !bad;
@@ -277,128 +292,215 @@ __global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const ui
     long long my_slot = -1;
     uint32_t my_row = kRowInvalid;
     bool my_created = false;
+    // ---- round 1: read-only lookup
     if (wave_on) {
-        first_line_pass<true>(v, my_key, my_ok, lane, &my_slot, &my_row, &my_created, &pc);
-        // keys not settled by the first-line pass (first line full, or it changed under us)
-        const bool need_slow = my_ok && my_slot < 0;
+        bool unused;
+        first_line_pass<false>(v, my_key, my_ok, lane, &my_slot, &my_row, &unused, &pc);
+        const bool need_slow = my_ok && my_slot == -1;   // first line full without a match
         if (__any(need_slow)) {
             for (int r = 0; r < kLineSlots; ++r) {
                 const bool act = __shfl((int)need_slow, gbase + r, kWave) != 0;
                 if (!__any(act)) continue;
                 const uint64_t k = shfl64(my_key, gbase + r);
-                bool created;
-                const long long s = probe_group<true>(v, k, act, lane, &created, &pc);
+                const long long s = probe_group<false>(v, k, act, lane, &unused, &pc);
                 if (sub == r && act) {
-                    my_slot = s;
-                    my_created = created;
+                    my_slot = s == -1 ? kSlotAbsent : s;   // -2: every line visited, no match, no room
                     my_row = kRowInvalid;
                 }
             }
         }
     }
-
-    // ---- block-aggregated row allocation for the lanes that claimed a slot
-    const uint64_t m_new = __ballot(my_created);
-    if (lane == 0) s_new[wave] = __popcll(m_new);
+    // ---- admission of the absent keys against the load-factor limit
+    const bool absent = my_ok && my_slot == kSlotAbsent;
+    const uint64_t m_absent = __ballot(absent);
+    unsigned wave_bits = 0;   // status bits raised by this wave: one atomic per block, not one per element
+    if (__any(bad)) wave_bits |= EMB_DEV_BAD_KEY;
+    const uint64_t m_full = __ballot(my_ok && my_slot == -2);   // no match and not one never-used slot in the table
+    if (m_full) wave_bits |= EMB_DEV_PROBE_EXHAUSTED;
+    if (lane == 0) {
+        s_absent[wave] = __popcll(m_absent);
+        s_surplus[wave] = __popcll(m_full);
+        s_bits[wave] = wave_bits;
+    }
     __syncthreads();
     if (threadIdx.x == 0) {
-        int total = 0;
-        for (int w = 0; w < kBigWaves; ++w) total += s_new[w];
-        int old_free = 0, take = 0;
-        unsigned bump_base = 0;
-        if (total > 0) {
-            unsigned n_atomics = 0;
-            if (load_fresh(reinterpret_cast<const uint32_t*>(&v.st->head.free_count)) != 0u) {
-                old_free = atomicSub(&v.st->head.free_count, total);
-                ++n_atomics;
-            }
-            take = old_free < 0 ? 0 : (old_free > total ? total : old_free);
-            if (total - take > 0) {
-                bump_base = atomicAdd(&v.st->head.bump, (unsigned)(total - take));
-                ++n_atomics;
-            }
-            unsigned long long* c = stat_stripe(v, blockIdx.x);
-            atomicAdd(&c[kStatLive], (unsigned long long)total);
-            if (COUNT) atomicAdd(&c[kStatAlloc], (unsigned long long)n_atomics);
+        int total = 0, no_room = 0;
+        unsigned bits = 0;
+        for (int w = 0; w < kBigWaves; ++w) {
+            total += s_absent[w];
+            no_room += s_surplus[w];
+            bits |= s_bits[w];
         }
-        s_old_free = old_free;
-        s_take = take;
-        s_bump = bump_base;
+        if (no_room > 0) atomicAdd(&v.st->head.refused, (unsigned long long)no_room);
+        int admitted = 0;
+        if (total > 0) {
+            const unsigned old_occ = atomicAdd(&v.st->head.occupied, (unsigned)total);
+            admitted = old_occ >= v.slot_limit ? 0 : (int)(v.slot_limit - old_occ);
+            if (admitted > total) admitted = total;
+            if (admitted < total) {
+                atomicSub(&v.st->head.occupied, (unsigned)(total - admitted));
+                atomicAdd(&v.st->head.refused, (unsigned long long)(total - admitted));
+                bits |= EMB_DEV_NEED_REHASH;
+            }
+            if (COUNT) atomicAdd(&stat_stripe(v, blockIdx.x)[kStatAlloc], 1ull);
+        }
+        if (bits) atomicOr(&v.st->head.status, bits);
+        s_admitted = admitted;
     }
     __syncthreads();
-    if (my_created) {
-        int r = rank_in(m_new, lane);
-        for (int w = 0; w < wave; ++w) r += s_new[w];
-        const int take = s_take;
-        if (r < take) {
-            my_row = CHUNK_FREE(v, (unsigned)(s_old_free - 1 - r));
-        } else {
-            my_row = s_bump + (unsigned)(r - take);
-        }
-        if (my_row >= v.rows_capacity) {
-            // out of row storage: give the slot up again (as a deleted marker) and report
-            atomicOr(&v.st->head.status, EMB_DEV_OUT_OF_ROWS);
-            v.slots[my_slot].key = kTombKey;
-            unsigned long long* c = stat_stripe(v, blockIdx.x);
-            atomicAdd(&c[kStatTomb], 1ull);
-            atomicAdd(&c[kStatLive], ~0ull); // -1
-            my_row = kRowInvalid;
-            my_created = false;
-            my_slot = -1;
-        }
-    }
-    // ---- initialise the new rows, the whole wave writing one row at a time (coalesced).  Every
-    // creating lane resolves its own row address first, so the loop has no dependent loads.
-    const uint64_t my_dst = my_created ? reinterpret_cast<uint64_t>(chunk_row_ptr(v, my_row)) : 0ull;
-    uint64_t my_m = 0ull, my_v = 0ull; // moment rows of the new row, when an Adam state is registered
-    if (my_created && v.has_adam) {
-        const size_t o = (size_t)(my_row & ((1u << v.chunk_log2) - 1u)) * (size_t)v.dim;
-        my_m = reinterpret_cast<uint64_t>(v.st->adam_m[my_row >> v.chunk_log2] + o);
-        my_v = reinterpret_cast<uint64_t>(v.st->adam_v[my_row >> v.chunk_log2] + o);
-    }
-    uint64_t m_init = __ballot(my_created);
-    while (m_init) {
-        const int src = __ffsll((unsigned long long)m_init) - 1;
-        m_init &= m_init - 1;
-        const uint64_t k = shfl64(my_key, src);
-        char* dst = reinterpret_cast<char*>(shfl64(my_dst, src));
-        if (v.has_adam) {
-            float* pm = reinterpret_cast<float*>(shfl64(my_m, src));
-            float* pv = reinterpret_cast<float*>(shfl64(my_v, src));
-            for (int j = lane; j < v.dim; j += kWave) {
-                pm[j] = 0.0f;
-                pv[j] = 0.0f;
+    int absent_rank = rank_in(m_absent, lane);
+    for (int w = 0; w < wave; ++w) absent_rank += s_absent[w];
+    const bool claim = absent && absent_rank < s_admitted;
+    // ---- round 2: the admitted keys claim a slot (block-uniform branch: most blocks of a step bring no new key)
+    if (s_admitted > 0) {
+        if (wave_on && __any(claim)) {
+            long long slot2;
+            uint32_t row2;
+            bool created2;
+            first_line_pass<true>(v, my_key, claim, lane, &slot2, &row2, &created2, &pc);
+            if (claim) {
+                my_slot = slot2;
+                my_row = row2;
+                my_created = created2;
+            }
+            const bool need_slow = claim && my_slot == -1;   // first line full, or it changed under us
+            if (__any(need_slow)) {
+                for (int r = 0; r < kLineSlots; ++r) {
+                    const bool act = __shfl((int)need_slow, gbase + r, kWave) != 0;
+                    if (!__any(act)) continue;
+                    const uint64_t k = shfl64(my_key, gbase + r);
+                    bool created;
+                    const long long s = probe_group<true>(v, k, act, lane, &created, &pc);
+                    if (sub == r && act) {
+                        my_slot = s;
+                        my_created = created;
+                        my_row = kRowInvalid;
+                    }
+                }
             }
         }
-        if (v.dtype == EMB_F32) {
-            for (int j = lane; j < v.dim; j += kWave) reinterpret_cast<float*>(dst)[j] = init_value(k, j, v.init_c);
-        } else {
-            for (int j = lane; j < v.dim; j += kWave)
-                reinterpret_cast<uint16_t*>(dst)[j] = f32_to_bf16(init_value(k, j, v.init_c));
+        // ---- block-aggregated row allocation for the lanes that claimed a slot; reservations of admitted
+        // keys that turned out to be present (or found no slot) are returned
+        const uint64_t m_new = __ballot(my_created);
+        const uint64_t m_surplus = __ballot(claim && !my_created);
+        const uint64_t m_lost = __ballot(claim && my_slot == -2);   // cannot happen while reservations hold; counted all the same
+        if (lane == 0) {
+            s_new[wave] = __popcll(m_new);
+            s_surplus[wave] = __popcll(m_surplus);
+            s_bits[wave] = (unsigned)__popcll(m_lost);
         }
-    }
-    if (my_created) {
-        // A row that is not in use always has freq == 0 (chunks are registered zeroed, eviction
-        // resets it), so creator and duplicates alike count their touch with an atomic add and no
-        // ordering between this record and the publication of the row index is needed - a release
-        // fence here would write the whole L2 back per wave.
-        RowMeta* m = &CHUNK_META(v, my_row);
-        m->acc = 0.0f;
-        m->last_seen = step;
-        if (TOUCH) atomicAdd(&m->freq, 1u);
-        __hip_atomic_store(&v.slots[my_slot].row, my_row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int total = 0, surplus = 0;
+            unsigned lost = 0;
+            for (int w = 0; w < kBigWaves; ++w) {
+                total += s_new[w];
+                surplus += s_surplus[w];
+                lost += s_bits[w];
+            }
+            if (surplus > 0) atomicSub(&v.st->head.occupied, (unsigned)surplus);
+            if (lost > 0) {
+                atomicAdd(&v.st->head.refused, (unsigned long long)lost);
+                atomicOr(&v.st->head.status, EMB_DEV_PROBE_EXHAUSTED);
+            }
+            int old_free = 0, take = 0, got = 0;
+            unsigned bump_base = 0;
+            if (total > 0) {
+                unsigned n_atomics = 0;
+                if (load_fresh(reinterpret_cast<const uint32_t*>(&v.st->head.free_count)) != 0u) {
+                    old_free = atomicSub(&v.st->head.free_count, total);
+                    ++n_atomics;
+                }
+                take = old_free < 0 ? 0 : (old_free > total ? total : old_free);
+                got = take;
+                const int need = total - take;
+                if (need > 0) {
+                    bump_base = atomicAdd(&v.st->head.bump, (unsigned)need);
+                    ++n_atomics;
+                    int avail = bump_base >= v.rows_capacity ? 0 : (int)(v.rows_capacity - bump_base);
+                    if (avail > need) avail = need;
+                    if (avail < need)   // give the overshoot back: the pointer ends at the registered rows
+                        atomicSub(&v.st->head.bump, (unsigned)(need - avail));
+                    got += avail;
+                }
+                unsigned long long* c = stat_stripe(v, blockIdx.x);
+                if (got > 0) atomicAdd(&c[kStatLive], (unsigned long long)got);
+                if (got < total) {
+                    atomicAdd(&c[kStatTomb], (unsigned long long)(total - got));
+                    atomicAdd(&v.st->head.refused, (unsigned long long)(total - got));
+                    atomicOr(&v.st->head.status, EMB_DEV_OUT_OF_ROWS);
+                }
+                if (COUNT) atomicAdd(&c[kStatAlloc], (unsigned long long)n_atomics);
+            }
+            s_old_free = old_free;
+            s_take = take;
+            s_got = got;
+            s_bump = bump_base;
+        }
+        __syncthreads();
+        if (my_created) {
+            int r = rank_in(m_new, lane);
+            for (int w = 0; w < wave; ++w) r += s_new[w];
+            const int take = s_take;
+            if (r < take) {
+                my_row = CHUNK_FREE(v, (unsigned)(s_old_free - 1 - r));
+            } else if (r < s_got) {
+                my_row = s_bump + (unsigned)(r - take);
+            } else {
+                // no row left: give the slot up again (as a deleted marker); the element reports -1
+                v.slots[my_slot].key = kTombKey;
+                my_row = kRowInvalid;
+                my_created = false;
+                my_slot = -1;
+            }
+        }
+        // ---- initialise the new rows, the whole wave writing one row at a time (coalesced).  Every
+        // creating lane resolves its own row address first, so the loop has no dependent loads.
+        const uint64_t my_dst = my_created ? reinterpret_cast<uint64_t>(chunk_row_ptr(v, my_row)) : 0ull;
+        uint64_t my_m = 0ull, my_v = 0ull; // moment rows of the new row, when an Adam state is registered
+        if (my_created && v.has_adam) {
+            const size_t o = (size_t)(my_row & ((1u << v.chunk_log2) - 1u)) * (size_t)v.dim;
+            my_m = reinterpret_cast<uint64_t>(v.st->adam_m[my_row >> v.chunk_log2] + o);
+            my_v = reinterpret_cast<uint64_t>(v.st->adam_v[my_row >> v.chunk_log2] + o);
+        }
+        uint64_t m_init = __ballot(my_created);
+        while (m_init) {
+            const int src = __ffsll((unsigned long long)m_init) - 1;
+            m_init &= m_init - 1;
+            const uint64_t k = shfl64(my_key, src);
+            char* dst = reinterpret_cast<char*>(shfl64(my_dst, src));
+            if (v.has_adam) {
+                float* pm = reinterpret_cast<float*>(shfl64(my_m, src));
+                float* pv = reinterpret_cast<float*>(shfl64(my_v, src));
+                for (int j = lane; j < v.dim; j += kWave) {
+                    pm[j] = 0.0f;
+                    pv[j] = 0.0f;
+                }
+            }
+            if (v.dtype == EMB_F32) {
+                for (int j = lane; j < v.dim; j += kWave) reinterpret_cast<float*>(dst)[j] = init_value(k, j, v.init_c);
+            } else {
+                for (int j = lane; j < v.dim; j += kWave)
+                    reinterpret_cast<uint16_t*>(dst)[j] = f32_to_bf16(init_value(k, j, v.init_c));
+            }
+        }
+        if (my_created) {
+            // A row that is not in use always has freq == 0 (chunks are registered zeroed, eviction
+            // resets it), so creator and duplicates alike count their touch with an atomic add and no
+            // ordering between this record and the publication of the row index is needed - a release
+            // fence here would write the whole L2 back per wave.
+            RowMeta* m = &CHUNK_META(v, my_row);
+            m->acc = 0.0f;
+            m->last_seen = step;
+            if (TOUCH) atomicAdd(&m->freq, 1u);
+            __hip_atomic_store(&v.slots[my_slot].row, my_row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
     // ---- results.  A lane that found a key whose creator has not published the row yet records
     // the slot (as -(slot+2)); k_touch resolves it after this kernel.
     if (valid) {
         int32_t out;
-        if (bad) {
-            atomicOr(&v.st->head.status, EMB_DEV_BAD_KEY);
-            out = -1;
-        } else if (my_slot == -2) {
-            atomicOr(&v.st->head.status, EMB_DEV_PROBE_EXHAUSTED);
-            out = -1;
-        } else if (my_slot < 0) {
+        if (bad || my_slot < 0) {     // bad key, turned away, no row, probe sequence exhausted
             out = -1;
         } else if (my_created) {
             out = (int32_t)my_row;
@@ -561,8 +663,18 @@ __global__ __launch_bounds__(kBlock) void k_rehash(const Slot* __restrict__ old_
     atomicOr(&st->head.status, EMB_DEV_PROBE_EXHAUSTED);
 }
 
+// After a rehash (or on fresh key storage) no deleted markers are left: occupied = live.  One wave.
 __global__ void k_after_rehash(HtState* st) {
-    if (blockIdx.x == 0 && threadIdx.x < kStatStripes) st->head.stat[threadIdx.x][kStatTomb] = 0ull;
+    static_assert(kStatStripes == kWave, "one lane per stripe");
+    const int lane = lane_id();
+    uint64_t live = st->head.stat[lane][kStatLive];   // stripes hold signed deltas: the sum wraps to the count
+    st->head.stat[lane][kStatTomb] = 0ull;
+    for (int o = 32; o > 0; o >>= 1) live += shfl64(live, lane ^ o);
+    if (lane == 0) st->head.occupied = (unsigned)live;
+}
+
+__global__ void k_clear_status(HtState* st, unsigned bits) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) st->head.status &= ~bits;
 }
 
 // Unordered dump: one lane per slot decides, then the wave copies the rows of its live slots.
@@ -686,7 +798,8 @@ const char* emb_status_string(int s) {
         case EMB_ERR_WORKSPACE: return "workspace too small or misaligned";
         case EMB_ERR_NO_STORAGE: return "no key storage or not enough row chunks";
         case EMB_ERR_HIP: return "HIP runtime error";
-        case EMB_ERR_NEED_REHASH: return "load factor limit: rehash first";
+        case EMB_ERR_NEED_REHASH: return "load factor limit: rehash to a larger key structure";
+        case EMB_CHECK_STATUS: return "launched; new keys may have been turned away: compare ht_stats().refused";
         default: return "unknown status";
     }
 }
@@ -701,7 +814,7 @@ int emb_table_create(emb_table_t** out, const emb_table_desc_t* desc, void* stat
     const int row_bytes = desc->dim * (desc->dtype == EMB_F32 ? 4 : 2);
     if (row_bytes % 16 != 0 || desc->dim > 256) return EMB_ERR_INVALID_ARG;
     if (desc->chunk_rows_log2 < 4 || desc->chunk_rows_log2 > 30) return EMB_ERR_INVALID_ARG;
-    if (desc->max_load_factor < 0.0f || desc->max_load_factor > 0.95f) return EMB_ERR_INVALID_ARG;
+    if (desc->max_load_factor < 0.0f || desc->max_load_factor > 1.0f) return EMB_ERR_INVALID_ARG;
     emb_table* t = new emb_table();
     t->desc = *desc;
     if (t->desc.max_load_factor == 0.0f) t->desc.max_load_factor = 0.75f;
@@ -765,8 +878,13 @@ int ht_set_key_storage(emb_table_t* t, void* slots, int capacity_log2, void* str
     hipLaunchKernelGGL(k_fill_slots, dim3(fill_grid(n)), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<Slot*>(slots), n);
     MTGR_LAUNCH_CHECK();
+    // an emptied table may still count deleted markers of its old key structure: they are gone with it
+    hipLaunchKernelGGL(k_after_rehash, dim3(1), dim3(kWave), 0, static_cast<hipStream_t>(stream), t->st);
+    MTGR_LAUNCH_CHECK();
     t->slots = static_cast<Slot*>(slots);
     t->cap_log2 = capacity_log2;
+    t->base_tomb = 0;
+    t->min_valid_seq = t->seq + 1;
     return EMB_OK;
 }
 
@@ -803,9 +921,8 @@ int ht_plan(emb_table_t* t, int64_t n_incoming, int* new_capacity_log2, int* chu
     if (new_capacity_log2) {
         *new_capacity_log2 = 0;
         if (t->slots) {
-            const double cap = (double)(1ull << t->cap_log2);
             const double lf = t->desc.max_load_factor;
-            if ((double)(t->occupied_bound() + (uint64_t)n_incoming) > lf * cap) {
+            if (t->occupied_bound() + (uint64_t)n_incoming > (uint64_t)t->slot_limit()) {
                 int c = t->cap_log2;
                 while ((double)(t->live_bound() + (uint64_t)n_incoming) > 0.5 * lf * (double)(1ull << c) && c < 30) ++c;
                 *new_capacity_log2 = c;
@@ -821,29 +938,31 @@ int ht_plan(emb_table_t* t, int64_t n_incoming, int* new_capacity_log2, int* chu
     return EMB_OK;
 }
 
+// EMB_OK: the host-side upper bounds prove that n_max new keys fit under the load-factor limit and
+// into the registered rows.  EMB_CHECK_STATUS: they do not - the device admits what fits and turns
+// the rest away.
 static int check_insert_room(emb_table_t* t, int64_t n_max) {
-    if (!t->slots) return EMB_ERR_NO_STORAGE;
+    if (!t->slots || t->n_chunks == 0) return EMB_ERR_NO_STORAGE;
     t->refresh();
-    const double cap = (double)(1ull << t->cap_log2);
-    if ((double)(t->occupied_bound() + (uint64_t)n_max) > (double)t->desc.max_load_factor * cap) return EMB_ERR_NEED_REHASH;
+    if (t->occupied_bound() + (uint64_t)n_max > (uint64_t)t->slot_limit()) return EMB_CHECK_STATUS;
     const uint64_t have = (uint64_t)t->n_chunks << t->desc.chunk_rows_log2;
-    if (t->rows_used_bound() + (uint64_t)n_max > have) return EMB_ERR_NO_STORAGE;
+    if (t->rows_used_bound() + (uint64_t)n_max > have) return EMB_CHECK_STATUS;
     return EMB_OK;
 }
 
 static int find_or_insert_impl(emb_table_t* t, const uint64_t* key, const int64_t* n_dev, int64_t n_max, uint32_t step,
-                               int32_t* row_idx, uint8_t* inserted, void* stream, bool touch) {
+                               int32_t* row_idx, uint8_t* inserted, void* stream, bool touch, bool retry) {
     if (!t || n_max < 0 || n_max > 0x7FFFFFFFll) return EMB_ERR_INVALID_ARG;
     if (n_max == 0) return EMB_OK;
     if (!key || !row_idx) return EMB_ERR_INVALID_ARG;
-    int rc = check_insert_room(t, n_max);
-    if (rc != EMB_OK) return rc;
+    const int room = check_insert_room(t, n_max);
+    if (room < 0) return room;
     HtView v = t->view();
     hipStream_t s = static_cast<hipStream_t>(stream);
     const unsigned grid = blocks_for((uint64_t)n_max, kBigBlock);
 #define MTGR_FOI(C_, T_)                                                                                          \
     hipLaunchKernelGGL((k_find_or_insert<C_, T_>), dim3(grid), dim3(kBigBlock), 0, s, v, key, n_dev, n_max, step, \
-                       row_idx, inserted)
+                       row_idx, inserted, retry ? 1 : 0)
     if (v.count) {
         if (touch) MTGR_FOI(true, true); else MTGR_FOI(true, false);
     } else {
@@ -855,17 +974,30 @@ static int find_or_insert_impl(emb_table_t* t, const uint64_t* key, const int64_
                        row_idx, touch ? 1 : 0);
     MTGR_LAUNCH_CHECK();
     t->issued((uint64_t)n_max);
-    return t->snapshot(s);
+    const int rc = t->snapshot(s);
+    return rc != EMB_OK ? rc : room;
 }
 
 int ht_find_or_insert(emb_table_t* t, const uint64_t* key, const int64_t* n_dev, int64_t n_max, uint32_t step,
                       int32_t* row_idx, uint8_t* inserted, void* stream) {
-    return find_or_insert_impl(t, key, n_dev, n_max, step, row_idx, inserted, stream, true);
+    return find_or_insert_impl(t, key, n_dev, n_max, step, row_idx, inserted, stream, true, false);
 }
 
 int ht_find_or_insert_notouch(emb_table_t* t, const uint64_t* key, const int64_t* n_dev, int64_t n_max, uint32_t step,
                               int32_t* row_idx, uint8_t* inserted, void* stream) {
-    return find_or_insert_impl(t, key, n_dev, n_max, step, row_idx, inserted, stream, false);
+    return find_or_insert_impl(t, key, n_dev, n_max, step, row_idx, inserted, stream, false, false);
+}
+
+int ht_find_or_insert_retry(emb_table_t* t, const uint64_t* key, const int64_t* n_dev, int64_t n_max, uint32_t step,
+                            int32_t* row_idx, uint8_t* inserted, int touch, void* stream) {
+    return find_or_insert_impl(t, key, n_dev, n_max, step, row_idx, inserted, stream, touch != 0, true);
+}
+
+int ht_clear_status(emb_table_t* t, uint32_t bits, void* stream) {
+    if (!t) return EMB_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(k_clear_status, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), t->st, bits);
+    MTGR_LAUNCH_CHECK();
+    return EMB_OK;
 }
 
 int ht_find(emb_table_t* t, const uint64_t* key, const int64_t* n_dev, int64_t n_max, int32_t* row_idx,
@@ -909,7 +1041,7 @@ int ht_rehash(emb_table_t* t, void* new_slots, int new_capacity_log2, void* stre
     // the live keys (newest counter copy plus inserts issued since) must fit under the limit
     t->refresh();
     if ((double)t->live_bound() > (double)t->desc.max_load_factor * (double)(1ull << new_capacity_log2))
-        return EMB_ERR_INVALID_ARG;
+        return EMB_ERR_NEED_REHASH;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint64_t n_new = 1ull << new_capacity_log2;
     const uint64_t n_old = 1ull << t->cap_log2;
@@ -918,7 +1050,7 @@ int ht_rehash(emb_table_t* t, void* new_slots, int new_capacity_log2, void* stre
     hipLaunchKernelGGL(k_rehash, dim3(blocks_for(n_old, kBlock)), dim3(kBlock), 0, s, t->slots, n_old,
                        static_cast<Slot*>(new_slots), n_new / kLineSlots - 1ull, t->st);
     MTGR_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_after_rehash, dim3(1), dim3(kStatStripes), 0, s, t->st);
+    hipLaunchKernelGGL(k_after_rehash, dim3(1), dim3(kWave), 0, s, t->st);
     MTGR_LAUNCH_CHECK();
     t->slots = static_cast<Slot*>(new_slots);
     t->cap_log2 = new_capacity_log2;
@@ -978,6 +1110,7 @@ int ht_stats(emb_table_t* t, ht_stats_t* out, void* stream) {
     out->hot_rows_used = h.hot_bump;
     out->hot_rows_free = h.hot_free_count > 0 ? (uint64_t)h.hot_free_count : 0ull;
     out->hot_rows_capacity = t->hot_capacity;
+    out->refused = h.refused;
     // exact numbers replace the running upper bounds; older counter copies are obsolete
     t->adopt(h, 0, t->seq);
     t->min_valid_seq = t->seq + 1;

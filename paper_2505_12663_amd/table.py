@@ -2,8 +2,8 @@
 
 The C library allocates nothing; this module keeps the torch tensors that back the key
 structure, the value chunks and the per-step buffers alive, and applies the capacity policy the
-library plans (``ht_plan``): rehash the key structure when the load-factor limit would be crossed,
-keep a spare value chunk registered (dual-chunk rule of Sec. 3.1).  All arithmetic of the path
+library plans (``ht_plan``): rehash the key structure when the device turned new keys away at the
+load-factor limit, keep a spare value chunk registered (dual-chunk rule of Sec. 3.1).  All arithmetic of the path
 runs in the library's kernels.
 """
 from __future__ import annotations
@@ -36,6 +36,8 @@ class EmbeddingTable:
         self.state = torch.empty(B.emb_table_state_bytes(), dtype=torch.uint8, device=self.device)
         desc = B.TableDesc(dim, dtype, init_scale, max_load_factor, chunk_rows_log2, int(count_probes))
         self.h = B.emb_table_create(desc, self.state)
+        self._refused_seen = 0
+        self.peak_load = 0.0          # highest (live + deleted) / capacity any counter read-back has shown
         self.capacity_log2 = capacity_log2
         self.slots = torch.empty((1 << capacity_log2, 2), dtype=torch.int64, device=self.device)   # 16 B per slot
         B.ht_set_key_storage(self.h, self.slots, capacity_log2)
@@ -83,32 +85,50 @@ class EmbeddingTable:
         self.slots, self.capacity_log2 = new_slots, new_capacity_log2
 
     def stats(self) -> dict:
-        return B.ht_stats(self.h)
+        st = B.ht_stats(self.h)
+        self.peak_load = max(self.peak_load, (st["live"] + st["tombstones"]) / max(st["capacity"], 1))
+        return st
 
-    def reserve(self, n_incoming: int) -> None:
-        """Make room for up to n_incoming new keys.  Syncs only when the library's running upper
-        bounds (exact counts at the last ht_stats plus everything issued since) say it may not fit."""
-        cap, chunks = B.ht_plan(self.h, n_incoming)
-        if cap == 0 and chunks == 0:
-            return
+    def make_room(self, n_incoming: int) -> None:
+        """Room for n_incoming more keys, from the exact counters (synchronises): add value chunks, and expand or
+        clean the key structure if live + deleted + n_incoming slots would pass the load-factor limit."""
         self.stats()                       # exact counts replace the running upper bounds
-        cap, _ = B.ht_plan(self.h, n_incoming)
-        # dual-chunk rule: besides the rows needed now, keep one whole spare chunk registered
-        _, chunks = B.ht_plan(self.h, n_incoming + (1 << self.chunk_rows_log2))
+        cap, chunks = B.ht_plan(self.h, n_incoming)
         for _ in range(chunks):
             self.add_chunk()
         if cap:
             self.rehash(cap)
 
+    def _keep_spare_chunk(self, st: dict, n_next: int) -> None:
+        """Dual-chunk rule of Sec. 3.1: besides the rows the next call may need, one whole chunk stays unused."""
+        free_rows = st["rows_capacity"] - (st["rows_used"] - st["rows_free"])
+        per = 1 << self.chunk_rows_log2
+        while free_rows < n_next + per:
+            self.add_chunk()
+            free_rows += per
+
     # -- calls --------------------------------------------------------------------------------
     def find_or_insert(self, key, n_dev, n_max: int, step: int, row_idx, inserted=None, touch: bool = True) -> None:
-        """touch=False: the step's update call (apply_adagrad with touch_step) counts the touch."""
+        """touch=False: the step's update call (apply_adagrad with touch_step) counts the touch.
+        The library admits new keys on the device up to the load-factor limit.  While its host-side bounds prove
+        that everything fits, nothing here waits for the GPU; otherwise the counters are read back after the
+        call and, if keys were turned away, room is made (rehash, chunks) and the call is issued again for them."""
         rc = B.ht_find_or_insert(self.h, key, n_dev, n_max, step, row_idx, inserted, touch=touch)
-        if rc != B.EMB_OK:
-            self.reserve(n_max)
-            rc = B.ht_find_or_insert(self.h, key, n_dev, n_max, step, row_idx, inserted, touch=touch)
-            if rc != B.EMB_OK:
-                raise B.EmbError(rc, "ht_find_or_insert")
+        if rc == B.EMB_OK:
+            return
+        for _ in range(4):
+            st = self.stats()
+            turned_away = st["refused"] - self._refused_seen
+            self._refused_seen = st["refused"]
+            if turned_away == 0:
+                self._keep_spare_chunk(st, n_max)
+                return
+            # the bits the turned-away elements raised (a table filled to its last slot by claims that were
+            # still being counted shows as an exhausted probe sequence); the retry must end with none of them
+            B.ht_clear_status(self.h, B.DEV_NEED_REHASH | B.DEV_OUT_OF_ROWS | B.DEV_PROBE_EXHAUSTED)
+            self.make_room(turned_away)
+            B.ht_find_or_insert_retry(self.h, key, n_dev, n_max, step, row_idx, inserted, touch=touch)
+        raise B.EmbError(B.EMB_ERR_NEED_REHASH, "ht_find_or_insert: keys still turned away after making room")
 
     def find(self, key, n_dev, n_max: int, row_idx) -> None:
         B.ht_find(self.h, key, n_dev, n_max, row_idx)
@@ -170,19 +190,19 @@ class EmbeddingTable:
         order = np.argsort(k, kind="stable")
         return k[order], values[:cnt].cpu().numpy()[order]
 
-    def export_device(self):
-        """Unordered dump as device tensors (keys int64, values, acc, last_seen, freq), trimmed to the live count."""
+    def export_device(self, values: bool = True):
+        """Unordered dump as device tensors (keys int64, values or None, acc, last_seen, freq), trimmed to the live count."""
         live = self.stats()["live"]
         cap = max(live, 1)
         keys = torch.empty(cap, dtype=torch.int64, device=self.device)
-        values = torch.empty((cap, self.dim), dtype=self.torch_dtype, device=self.device)
+        values = torch.empty((cap, self.dim), dtype=self.torch_dtype, device=self.device) if values else None
         acc = torch.empty(cap, dtype=torch.float32, device=self.device)
         last_seen = torch.empty(cap, dtype=torch.int32, device=self.device)
         freq = torch.empty(cap, dtype=torch.int32, device=self.device)
         n = torch.zeros(1, dtype=torch.int64, device=self.device)
         B.ht_export(self.h, keys, values, acc, last_seen, freq, n)
         cnt = int(n.item())
-        return keys[:cnt], values[:cnt], acc[:cnt], last_seen[:cnt], freq[:cnt]
+        return keys[:cnt], (values[:cnt] if values is not None else None), acc[:cnt], last_seen[:cnt], freq[:cnt]
 
     def import_rows(self, keys, values, acc, last_seen, freq, step: int = 0) -> None:
         """Restore dumped entries: create the keys, then overwrite row contents and records."""

@@ -123,7 +123,7 @@ def test_config2_prepopulated_scaled():
     assert len(gk) == n_all
     pos = np.searchsorted(gk, ok)
     assert np.array_equal(gk[pos], ok) and np.array_equal(gl[pos], ol) and np.array_equal(gf[pos], of)
-    assert np.allclose(gv[pos], ov, rtol=1e-5, atol=1e-7) and np.allclose(ga[pos], oa, rtol=4e-5)
+    assert np.allclose(gv[pos], ov, rtol=1e-5, atol=1e-7) and np.allclose(ga[pos], oa, rtol=1e-5)
     untouched = np.ones(n_all, dtype=bool)
     untouched[pos] = False
     sample = np.flatnonzero(untouched)[:: max(1, untouched.sum() // 500)]
@@ -160,7 +160,9 @@ def test_config4_insert_delete_stress_1000_steps_scaled(one_record_update):
             pair.compare_tables(w.lr, exact_rows_when_untouched=True)
     pair.compare_tables(w.lr)
     st = pair.gpu.stats()
-    assert st["n_rehash"] >= 3 and len(caps) >= 2 and evicted_total > 50000 and max(lf_seen) <= 0.85 + 1e-9
+    assert st["n_rehash"] >= 3 and len(caps) >= 2 and evicted_total > 50000 and max(lf_seen) <= float(np.float32(0.85))
+    # the key structure is expanded only when the device turned keys away at the limit: the load factor touches it
+    assert 0.84 <= pair.gpu.peak_load <= float(np.float32(0.85)) and st["refused"] > 0
     assert st["rows_free"] + st["live"] == st["rows_used"]          # every allocated row is live or on the free list
     pair.gpu.close()
 
@@ -189,7 +191,7 @@ def test_config5_bf16_scaled(one_record_update):
     pos = np.searchsorted(gk, ok)
     assert np.array_equal(gk[pos], ok) and np.array_equal(gl[pos], ol) and np.array_equal(gf[pos], of)
     assert (np.abs(gv[pos] - ov) <= 1e-2 * np.maximum(np.abs(ov), w.lr)).all()
-    assert np.allclose(ga[pos], oa, rtol=1e-4)
+    assert np.allclose(ga[pos], oa, rtol=1e-5)
     assert pair.gpu.stats()["live"] == len(all_keys) + new_total
     pair.gpu.close()
 

@@ -153,45 +153,108 @@ def test_config3_full_size_merged_tables():
 
 
 def test_config4_full_batch_insert_evict_rehash():
-    """Full batch (512 x 1024 x 4), a window of the 1000-step stream with the eviction clock scaled to it."""
+    """Full batch (512 x 1024 x 4 = 2.1 M IDs per step) with the configuration's own eviction clock (unseen for 200
+    steps, or touched fewer than 3 times and unseen for 20; every 20 steps; load-factor limit 0.85), for the first
+    260 of the 1000 streaming steps: long enough for several limit-driven rehashes and for the 200-step rule to fire.
+    The checker mirrors the tracked subset of keys (a fixed 1/512 of the key space plus the hottest keys) exactly
+    through every step and every eviction: insert flags, touch records, exact integer-valued reduced gradients,
+    updated rows, eviction sets.  On all keys: the distinct keys and inverse indices (in full against the checker
+    every tenth step, by properties otherwise), the eviction predicate on a dump of the records, the counters."""
+    from harness import small_int_rows, close_rows
+    from paper_2505_12663_amd import forward, backward
+    from workloads import small_int_grads
     w = make_config(4)
+    assert (w.ttl, w.min_freq, w.grace, w.evict_every, w.max_load_factor) == (200, 3, 20, 20, 0.85)
     merged, _ = B.emb_plan_merge([64] * 4, [0] * 4)
     tag_bits = B.emb_tag_bits(4)
-    pair = Pair(64, 0, capacity_log2=22, chunk_rows_log2=21, max_load_factor=0.85)
-    buf = StepBuffers(512 * 1024 * 4, 64)
-    nobody = lambda keys: np.zeros(len(keys), dtype=bool)
-    ttl, min_freq, grace, every = 8, 3, 3, 4
-    lf = []
-    # the sampled checker follows only sampled keys, so its table is not a full mirror here: eviction
-    # sets are checked by the predicate on the device dump instead
-    for step in range(16):
+    dim, steps = 64, 260
+    pair = Pair(dim, 0, capacity_log2=22, chunk_rows_log2=21, max_load_factor=w.max_load_factor, count_probes=True)
+    buf = StepBuffers(512 * 1024 * 4, dim)
+    tracked = tracked_subset(_hot_keys(w, tag_bits))
+    rehash_at, lf_at_refusal, evicted_total = [], [], 0
+    for step in range(steps):
         b = w.next_step(step)
         x, off, tags, _ = merged_inputs(w.features, b.ids, merged, 0)
+        n = len(x)
         okey, _ = oracle.tag_keys(x, off, tags, tag_bits)
-        dx = dev_keys(x)
-        from paper_2505_12663_amd import forward, backward
-        from workloads import small_int_grads
-        forward(pair.gpu, buf, dx, torch.from_numpy(off).cuda(), torch.from_numpy(tags).cuda(), tag_bits, step)
+        refused_before, rehash_before = pair.gpu._refused_seen, pair.gpu.stats()["n_rehash"]
+        pair.gpu.peak_load = 0.0
+        forward(pair.gpu, buf, dev_keys(x), torch.from_numpy(off).cuda(), torch.from_numpy(tags).cuda(), tag_bits, step)
         U = int(buf.n_unique.item())
-        ou, oi, oc = oracle.dedup(okey)
-        assert U == len(ou) and np.array_equal(host_keys(buf.uniq[:U]), ou)
-        assert np.array_equal(buf.inverse[:len(x)].cpu().numpy(), oi)
-        backward(pair.gpu, buf, small_int_grads(len(x), 64, step, "cuda"), len(x), w.lr, w.eps)
-        if (step + 1) % every == 0:
-            gk, gv, ga, gl, gf = pair.gpu.export()
-            expect = np.sort(gk[((step - gl.astype(np.int64)) >= ttl) |
-                                ((gf < min_freq) & ((step - gl.astype(np.int64)) >= grace))])
-            ev, n_ev = pair.gpu.evict(step, ttl, min_freq, grace)
-            assert np.array_equal(np.sort(host_keys(ev)), expect) and n_ev > 0
-            found = torch.empty(n_ev, dtype=torch.int32, device="cuda")
-            pair.gpu.find(ev.contiguous(), None, n_ev, found)
-            assert (found == -1).all()
+        if pair.gpu._refused_seen > refused_before:
+            lf_at_refusal.append(pair.gpu.peak_load)       # what the counters showed when keys were turned away
+        # ---- all keys: distinct keys and inverse
+        assert np.array_equal(host_keys(buf.key[:n]), okey)
+        if step % 10 == 0:
+            ou, oi, oc = oracle.dedup(okey)
+            assert U == len(ou) and np.array_equal(host_keys(buf.uniq[:U]), ou)
+            assert np.array_equal(buf.inverse[:n].cpu().numpy(), oi) and np.array_equal(buf.counts[:U].cpu().numpy(), oc)
+        else:
+            u = buf.uniq[:U]
+            assert bool((u[1:] > u[:-1]).all()) and torch.equal(u[buf.inverse[:n].long()], buf.key[:n])
+        assert bool((buf.row_idx[:U] >= 0).all())
+        # ---- tracked subset through the checker
+        pos = np.flatnonzero(tracked(okey))
+        skeys, sinv = np.unique(okey[pos], return_inverse=True)
+        oins = pair.orc.find_or_insert(skeys, step)
+        sidx = torch.from_numpy(np.searchsorted(host_keys(buf.uniq[:U]), skeys)).cuda()
+        assert np.array_equal(host_keys(buf.uniq[sidx]), skeys)
+        assert np.array_equal(buf.inserted[sidx].cpu().numpy(), oins), "insert flags (tracked keys)"
+        E_u = buf.uniq_rows[sidx].cpu().numpy()
+        oE_u = pair.orc.lookup(skeys)
+        never = pair.orc.peek(skeys)[2] == 0
+        assert np.array_equal(E_u[never], oE_u[never]) and close_rows(E_u, oE_u.astype(np.float64), w.lr, pair.rtol)
+        assert torch.equal(buf.out[torch.from_numpy(pos).cuda()], buf.uniq_rows[sidx][torch.from_numpy(sinv).cuda()])
+        backward(pair.gpu, buf, small_int_grads(n, dim, step, "cuda"), n, w.lr, w.eps)
+        og = np.zeros((len(skeys), dim), dtype=np.float64)
+        np.add.at(og, sinv, small_int_rows(pos, dim, step).astype(np.float64))
+        og = og.astype(np.float32)
+        assert np.array_equal(buf.reduced[sidx].cpu().numpy(), og), "reduced gradients (tracked keys, exact)"
+        pair.orc.apply_adagrad(skeys, og, w.lr, w.eps)
+        rows_after = torch.empty((len(skeys), dim), dtype=torch.float32, device="cuda")
+        pair.gpu.gather(buf.row_idx[sidx].contiguous(), None, len(skeys), rows_after)
+        assert close_rows(rows_after.cpu().numpy(), pair.orc.lookup(skeys).astype(np.float64), w.lr, pair.rtol)
+        # ---- eviction
+        if (step + 1) % w.evict_every == 0:
+            gk, _, ga, gl, gf = pair.gpu.export_device(values=False)
+            age = step - gl.long()
+            go = (age >= w.ttl) | ((gf < w.min_freq) & (age >= w.grace))
+            expect = torch.sort(gk[go]).values
+            # the tracked keys' records against the checker's, bit for bit (accumulators within the bound)
+            hk = host_keys(gk)
+            sel = np.flatnonzero(tracked(hk))
+            order = sel[np.argsort(hk[sel], kind="stable")]
+            ok, ov, oa, ol, of = pair.orc.export()
+            assert np.array_equal(hk[order], ok), "tracked key set"
+            d_order = torch.from_numpy(order).cuda()
+            assert np.array_equal(gl[d_order].cpu().numpy().view(np.uint32), ol)
+            assert np.array_equal(gf[d_order].cpu().numpy().view(np.uint32), of)
+            assert np.allclose(ga[d_order].cpu().numpy(), oa, rtol=1e-5, atol=1e-12)
+            ev, n_ev = pair.gpu.evict(step, w.ttl, w.min_freq, w.grace)
+            assert n_ev == expect.numel() and torch.equal(torch.sort(ev).values, expect)
+            oev = pair.orc.evict(step, w.ttl, w.min_freq, w.grace)
+            hev = host_keys(ev)
+            assert np.array_equal(np.sort(hev[tracked(hev)]), oev), "eviction set (tracked keys)"
+            if n_ev:
+                found = torch.empty(n_ev, dtype=torch.int32, device="cuda")
+                pair.gpu.find(ev.contiguous(), None, n_ev, found)
+                assert bool((found == -1).all())
+            evicted_total += n_ev
         st = pair.gpu.stats()
-        lf.append((st["live"] + st["tombstones"]) / st["capacity"])
-        assert st["status"] == 0 and st["rows_free"] + st["live"] == st["rows_used"]
-        print(f"  step {step}: U={U} live={st['live']} deleted={st['tombstones']} cap=2^{int(np.log2(st['capacity']))} "
-              f"load={lf[-1]:.3f} rehash={st['n_rehash']}", flush=True)
-    assert pair.gpu.stats()["n_rehash"] >= 1 and max(lf) <= 0.85 + 1e-9
+        lf = (st["live"] + st["tombstones"]) / st["capacity"]
+        assert st["status"] == 0 and st["rows_free"] + st["live"] == st["rows_used"] and lf <= float(np.float32(w.max_load_factor))
+        if st["n_rehash"] > rehash_before:
+            rehash_at.append(step)
+        if step % 10 == 9 or st["n_rehash"] > rehash_before:
+            print(f"  step {step}: U={U} live={st['live']} deleted={st['tombstones']} cap=2^{int(np.log2(st['capacity']))} "
+                  f"load={lf:.3f} rehash={st['n_rehash']} turned away so far={st['refused']} evicted so far={evicted_total}", flush=True)
+    st = pair.gpu.stats()
+    print(f"  rehashes at steps {rehash_at}; load factor when keys were turned away: {[round(v, 4) for v in lf_at_refusal]}; "
+          f"lines per lookup {st['probes'] / st['lookups']:.3f}, CAS failures {st['cas_failures']} of {st['cas_attempts']}", flush=True)
+    # the key structure was expanded only when the device had turned keys away at the limit (Sec. 3.1)
+    assert len(rehash_at) >= 2 and len(lf_at_refusal) == len(rehash_at)
+    assert all(0.84 <= v <= float(np.float32(w.max_load_factor)) for v in lf_at_refusal)      # the limit is a float32
+    assert evicted_total > 1_000_000
     pair.gpu.close()
 
 
@@ -216,7 +279,22 @@ def test_config5_full_size_bf16_400m_keys():
     st = pair.gpu.stats()
     assert n == 2048 * 2048 * 4 and 0.02 < n_new / U < 0.09          # ~5 % of the distinct keys are new
     assert st["live"] == 400_000_000 + n_new and st["status"] == 0
-    assert st["n_rehash"] == 1 and st["capacity"] == 1 << 30          # 0.745 load + incoming bound crossed 0.75
+    assert st["n_rehash"] == 0 and st["capacity"] == 1 << 29 and st["refused"] == 0   # 0.7458 < 0.75: still fits
+    # 3 M keys never issued before push the table over the limit: the device admits keys up to
+    # floor(0.75 * 2^29) slots, the owner expands the key structure (values do not move) and re-issues the call
+    fresh = w.raw_ids_of_ranks(0, np.arange(w._issued[0], w._issued[0] + 3_000_000, dtype=np.uint64))
+    rows = torch.empty(len(fresh), dtype=torch.int32, device="cuda")
+    pair.gpu.peak_load = 0.0
+    pair.gpu.find_or_insert(dev_keys(fresh), None, len(fresh), 2, rows)       # tag 0: the raw ID is the key
+    st = pair.gpu.stats()
+    print(f"  +3 M keys: turned away at load {pair.gpu.peak_load:.4f}: {st['refused']}, capacity 2^{int(np.log2(st['capacity']))}", flush=True)
+    assert st["live"] == 400_000_000 + n_new + 3_000_000 and st["status"] == 0 and bool((rows >= 0).all())
+    assert st["n_rehash"] == 1 and st["capacity"] == 1 << 30 and st["refused"] > 0 and 0.7499 < pair.gpu.peak_load <= 0.75
+    pick = np.arange(0, len(fresh), 300_007)
+    got = torch.empty((len(pick), 128), dtype=torch.bfloat16, device="cuda")
+    pair.gpu.gather(rows[torch.from_numpy(pick).cuda()].contiguous(), None, len(pick), got)
+    ref = np.stack([oracle.init_row(int(k), 128, dtype=1) for k in fresh[pick]])
+    assert np.array_equal(got.float().cpu().numpy(), ref)             # new rows are the key-seeded initial rows
     pair.gpu.close()
 
 
