@@ -52,6 +52,7 @@ typedef enum {
     EMB_ERR_WORKSPACE = -3,   /* workspace too small or misaligned */
     EMB_ERR_NO_STORAGE = -4,  /* no key storage / not enough row chunks registered for n_max inserts */
     EMB_ERR_HIP = -5,         /* a HIP runtime call failed */
+    EMB_ERR_TOO_LARGE = -7,   /* emb_dedup_noalloc: n beyond EMB_DEDUP_NOALLOC_MAX_KEYS */
     EMB_ERR_NEED_REHASH = -6, /* ht_rehash: the live keys do not fit under the limit of the new structure */
     /* Positive, ht_find_or_insert only: the kernels were launched, but the host-side upper bounds could not prove
      * that n_max new keys fit.  The device admits new keys only while live + deleted slots stay within
@@ -196,6 +197,19 @@ size_t emb_dedup_workspace_bytes(int64_t n);
 int emb_dedup(const uint64_t* key, int64_t n, uint64_t* uniq, int32_t* inverse, int32_t* counts,
               int32_t* perm, int32_t* seg_off, int32_t* seg_of, int64_t* n_unique, void* workspace,
               size_t workspace_bytes, void* stream);
+
+/* For callers that cannot allocate device memory or hand in a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  emb_dedup with the same arguments and results, minus the
+ * workspace: its scratch is a fixed array in the library's device image (about 24.3 bytes per key of
+ * EMB_DEDUP_NOALLOC_MAX_KEYS, i.e. 25 MB, held on every GPU the library runs on until the process ends).
+ * Calls no hipMalloc / hipFree or any allocating routine.  n > EMB_DEDUP_NOALLOC_MAX_KEYS -> EMB_ERR_TOO_LARGE
+ * (nothing launched).  The first call on a device resolves the array's address (hipGetSymbolAddress) with
+ * that device current: make it outside stream capture.  Every call on a GPU shares that GPU's array: calls that
+ * overlap on one GPU (different streams without ordering) race; calls ordered on one stream do not.  Nothing
+ * in the scratch needs clearing between calls (every word that is read is written earlier in the same call). */
+#define EMB_DEDUP_NOALLOC_MAX_KEYS (1 << 20)
+int emb_dedup_noalloc(const uint64_t* key, int64_t n, uint64_t* uniq, int32_t* inverse, int32_t* counts,
+                      int32_t* perm, int32_t* seg_off, int32_t* seg_of, int64_t* n_unique, void* stream);
 
 /* Sec. 3.1 (real-time insertion; open addressing with cooperative probing; "Capacity Expansion"):
  * find each key; insert the absent ones (claim a never-used slot by compare-and-swap, allocate a row,

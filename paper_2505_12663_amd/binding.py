@@ -17,6 +17,8 @@ EMB_OK = 0
 EMB_ERR_NO_STORAGE = -4
 EMB_ERR_NEED_REHASH = -6
 EMB_CHECK_STATUS = 1
+EMB_ERR_TOO_LARGE = -7
+EMB_DEDUP_NOALLOC_MAX_KEYS = 1 << 20
 DEV_PROBE_EXHAUSTED, DEV_OUT_OF_ROWS, DEV_BAD_KEY, DEV_NEED_REHASH = 1, 2, 4, 8
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -53,7 +55,7 @@ EXPORTS = [
     "ht_apply_adagrad", "ht_apply_adam", "ht_gather_expand_sorted", "emb_pool_workspace_bytes", "emb_pool_bags",
     "grad_segment_reduce_pooled", "ht_evict", "ht_export", "ht_put", "ht_set_hot_storage", "ht_promote", "ht_export_hot",
     "ht_find_or_insert_notouch", "ht_apply_adagrad_touch", "grad_reduce_apply_adagrad",
-    "ht_find_or_insert_retry", "ht_clear_status",
+    "ht_find_or_insert_retry", "ht_clear_status", "emb_dedup_noalloc",
 ]
 
 
@@ -83,6 +85,7 @@ def load():
         "emb_tag_keys": (C.c_int, [vp, vp, vp, i32, i64, i32, vp, vp, vp]),
         "emb_dedup_workspace_bytes": (C.c_size_t, [i64]),
         "emb_dedup": (C.c_int, [vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]),
+        "emb_dedup_noalloc": (C.c_int, [vp, i64, vp, vp, vp, vp, vp, vp, vp, vp]),
         "ht_find_or_insert": (C.c_int, [vp, vp, vp, i64, u32, vp, vp, vp]),
         "ht_find_or_insert_notouch": (C.c_int, [vp, vp, vp, i64, u32, vp, vp, vp]),
         "ht_find_or_insert_retry": (C.c_int, [vp, vp, vp, i64, u32, vp, vp, i32, vp]),
@@ -218,6 +221,11 @@ def emb_dedup(key, n: int, uniq, inverse, counts, perm, seg_off, seg_of, n_uniqu
     _check(load().emb_dedup(_ptr(key), n, _ptr(uniq), _ptr(inverse), _ptr(counts), _ptr(perm), _ptr(seg_off),
                             _ptr(seg_of), _ptr(n_unique), _ptr(workspace), workspace.numel() * workspace.element_size(),
                             _stream(stream)), "emb_dedup")
+
+
+def emb_dedup_noalloc(key, n: int, uniq, inverse, counts, perm, seg_off, seg_of, n_unique, stream=None) -> None:
+    _check(load().emb_dedup_noalloc(_ptr(key), n, _ptr(uniq), _ptr(inverse), _ptr(counts), _ptr(perm), _ptr(seg_off),
+                                    _ptr(seg_of), _ptr(n_unique), _stream(stream)), "emb_dedup_noalloc")
 
 
 def ht_find_or_insert(h, key, n_dev, n_max: int, step: int, row_idx, inserted=None, stream=None, touch: bool = True) -> int:

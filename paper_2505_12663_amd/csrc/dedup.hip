@@ -7,11 +7,9 @@
 // (per-tile histogram, per-digit scan over tiles, scatter) - no kernel waits on another block.
 // The scatter ranks a tile's keys with wave-wide ballots (no LDS atomics), reorders the tile in
 // LDS and writes runs of equal digit contiguously.
-#include "common.hpp"
+#include <mutex>
 
-#ifndef MTGR_SC_THREADS
-#define MTGR_SC_THREADS 512
-#endif
+#include "common.hpp"
 
 using namespace mtgr;
 
@@ -23,7 +21,7 @@ constexpr int kTile = kThreads * kItems;      // 4096 keys per block
 constexpr int kWaves = kThreads / kWave;      // 4
 constexpr int kRadix = 256;
 constexpr int kPasses = 8;
-constexpr int kScThreads = MTGR_SC_THREADS;    // scatter kernel: same tile, more and lighter threads
+constexpr int kScThreads = 512;               // scatter kernel: same tile, more and lighter threads
 constexpr int kScItems = kTile / kScThreads;
 constexpr int kScWaves = kScThreads / kWave;
 
@@ -495,14 +493,14 @@ __global__ void k_empty_result(int64_t* n_unique, int32_t* seg_off) {
     }
 }
 
-inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+constexpr size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct DdLayout {
     size_t header, masks, ka, kb, ia, ib, tile_hist, digit_total, tile_heads, seg_off, total;
     unsigned n_tiles;
 };
-DdLayout dd_layout(int64_t n) {
-    DdLayout L;
+constexpr DdLayout dd_layout(int64_t n) {
+    DdLayout L{};
     L.n_tiles = (unsigned)((n + kTile - 1) / kTile);
     size_t o = 0;
     L.header = o; o = align_up(o + sizeof(DdHeader), 256);
@@ -517,6 +515,30 @@ DdLayout dd_layout(int64_t n) {
     L.seg_off = o; o = align_up(o + (size_t)(n + 1) * 4, 256);
     L.total = o;
     return L;
+}
+
+// Scratch of the allocation-free entry point: the workspace of a deduplication of up to
+// EMB_DEDUP_NOALLOC_MAX_KEYS keys, resident on every device the library runs on until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress; kernels get the resolved address.
+constexpr size_t kScratchBytes = dd_layout(EMB_DEDUP_NOALLOC_MAX_KEYS).total;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mu;
+
+// address of `scratch` on the current device, resolved once per device
+int scratch_of_current_device(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return EMB_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return EMB_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return EMB_OK;
 }
 
 } // namespace
@@ -542,6 +564,15 @@ int emb_tag_keys(const uint64_t* x, const int64_t* field_off, const uint8_t* fie
 size_t emb_dedup_workspace_bytes(int64_t n) {
     if (n < 0) return 0;
     return dd_layout(n < 1 ? 1 : n).total;
+}
+
+int emb_dedup_noalloc(const uint64_t* key, int64_t n, uint64_t* uniq, int32_t* inverse, int32_t* counts,
+                      int32_t* perm, int32_t* seg_off, int32_t* seg_of, int64_t* n_unique, void* stream) {
+    if (n > EMB_DEDUP_NOALLOC_MAX_KEYS) return EMB_ERR_TOO_LARGE;
+    void* ws = nullptr;
+    const int rc = scratch_of_current_device(&ws);
+    if (rc != EMB_OK) return rc;
+    return emb_dedup(key, n, uniq, inverse, counts, perm, seg_off, seg_of, n_unique, ws, kScratchBytes, stream);
 }
 
 int emb_dedup(const uint64_t* key, int64_t n, uint64_t* uniq, int32_t* inverse, int32_t* counts,

@@ -799,6 +799,7 @@ const char* emb_status_string(int s) {
         case EMB_ERR_NO_STORAGE: return "no key storage or not enough row chunks";
         case EMB_ERR_HIP: return "HIP runtime error";
         case EMB_ERR_NEED_REHASH: return "load factor limit: rehash to a larger key structure";
+        case EMB_ERR_TOO_LARGE: return "size beyond the fixed scratch of the allocation-free entry point";
         case EMB_CHECK_STATUS: return "launched; new keys may have been turned away: compare ht_stats().refused";
         default: return "unknown status";
     }
