@@ -1,10 +1,11 @@
 #!/usr/bin/env python3
 """Benchmark of the sparse-embedding step on one MI355X.
 
-A step = tag -> dedup -> find-or-insert -> gather -> expand -> (upstream gradient already in HBM)
+A step = tag + dedup -> find-or-insert -> gather -> expand -> (upstream gradient already in HBM)
 -> gradient segment-reduce -> row-wise Adagrad over one batch of the long-sequence lookup
 configuration (batch 512, lengths U{256..4096}, 8 fields, dim 64 fp32, 50 M-key table, Zipf 1.05).
-Inputs are resident in HBM when the timed region starts.  Prints ONE JSON line on stdout.
+Every output of the step is materialised (distinct keys, inverse, distinct rows, expanded rows, reduced
+gradients).  Inputs are resident in HBM when the timed region starts.  Prints ONE JSON line on stdout.
 
     python bench.py [--gpus 1] [--steps 20] [--warmup 3] [--config 2] [--no-cpu-baseline]
 """
@@ -45,27 +46,42 @@ def algorithmic_bytes(n: int, u: int, u_new: int, v_row: int, v_grad: int, dim: 
     return b
 
 
+def timed_loop(step_fn, first_step: int, steps: int, warmup: int = 2):
+    """warmup untimed calls, then `steps` calls bracketed by synchronisations; (wall seconds, total IDs)."""
+    for s in range(warmup):
+        step_fn(first_step + s)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ids = 0
+    for k in range(steps):
+        ids += step_fn(first_step + warmup + k)
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0, ids
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, choices=[2, 5])
-    ap.add_argument("--batches", type=int, default=4, help="distinct pre-generated batches cycled through")
+    ap.add_argument("--batches", type=int, default=0,
+                    help="distinct pre-generated batches cycled through (default: 4 for the long-sequence configuration, "
+                         "which brings no new keys; warmup + steps for the large one, so that every step brings its "
+                         "share of keys never seen before)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--touch-in-lookup", action="store_true",
-                    help="ht_find_or_insert + ht_apply_adagrad (two updates of every row record per step) instead of "
-                         "ht_find_or_insert_notouch + ht_apply_adagrad_touch (one)")
     ap.add_argument("--literal-zipf", action="store_true",
                     help="extra line: config 2 with ranks Zipf-distributed over the whole 2^40 key space (about a quarter "
                          "of the IDs miss the pre-populated table, so it grows by ~2 M keys per step); runs last, "
                          "takes ~30 s more")
     ap.add_argument("--no-extras", action="store_true",
-                    help="skip the fused-lookup and pooled-lookup extra lines (profiling runs: only the step's own kernels)")
-    ap.add_argument("--count-probes", action="store_true", help="maintain probe/CAS counters (small overhead)")
+                    help="skip the extra lines (profiling runs: only the step's own kernels)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run plain device-to-device copies of this many MiB (reference kernel of known "
                          "size for scaling hardware counters; reports the copy rate)")
+    ap.add_argument("--ceiling-probes", action="store_true",
+                    help="extra line: what the memory system delivers to streaming and random-row kernels of this "
+                         "library's access shapes (2 GiB buffers): the yardstick next to the nominal 8 TB/s")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU's share of the embedding path; run it with --gpus 1 "
@@ -87,16 +103,18 @@ def main() -> int:
     merged, n_merged = B.emb_plan_merge(dims, dtypes)
     assert n_merged == 1
     tag_bits = B.emb_tag_bits(w.n_tables)
+    id_bits = w.id_bits
     dim, dtype = dims[0], dtypes[0]
     v_row = dim * (4 if dtype == 0 else 2)
     n_keys = sum(w.prepopulated)
     cap_log2 = 27 if args.config == 2 else 29
     chunk_log2 = 24 if args.config == 2 else 26
     n_chunks = (n_keys >> chunk_log2) + 2
+    n_batches = args.batches or (4 if args.config == 2 else args.warmup + args.steps)
 
     t0 = time.time()
     table = EmbeddingTable(dim, dtype, capacity_log2=cap_log2, chunk_rows_log2=chunk_log2, max_load_factor=0.75,
-                           count_probes=args.count_probes, initial_chunks=n_chunks)
+                           count_probes=False, initial_chunks=n_chunks)
     # ---- bulk load of the pre-existing keys (step 0), in slices
     slice_n = 1 << 22
     dk = torch.empty(slice_n, dtype=torch.int64, device=dev)
@@ -120,13 +138,14 @@ def main() -> int:
     batches = []
     lengths_of = []
     n_max = 0
-    for s in range(args.batches):
+    for s in range(n_batches):
         b = w.next_step(s)
         x, off, tags, _ = merged_inputs(w.features, b.ids, merged, 0)
+        keep_host = (x, off, tags) if s == 0 else None
         batches.append((torch.from_numpy(x.view(np.int64)).to(dev), torch.from_numpy(off).to(dev),
-                        torch.from_numpy(tags).to(dev), len(x), (x, off, tags)))
+                        torch.from_numpy(tags).to(dev), len(x), keep_host))
         n_max = max(n_max, len(x))
-        lengths_of.append(b.lengths)
+        lengths_of.append(b.lengths if s == 0 else None)
         log(f"batch {s}: N={len(x)} ({time.time() - t0:.1f}s)")
     buf = StepBuffers(n_max, dim, dtype)
     gen = torch.Generator(device=dev)
@@ -136,36 +155,36 @@ def main() -> int:
         grad = grad.to(torch.bfloat16)
     v_grad = v_row
 
-    phases = ["tag", "dedup", "find_or_insert", "gather", "expand", "reduce", "adagrad"]
-    touch = args.touch_in_lookup   # False: the update writes the row record once per step (touch + accumulator)
+    phases = ["tag_dedup", "find_or_insert", "gather", "expand", "reduce", "adagrad"]
 
+    # The step this library recommends for one GPU: tag + dedup in one call (8-byte sort records, no tagged-key
+    # array), one row-record update per step (the lookup leaves the touch to the update).  Same outputs and the same
+    # table afterwards as the step of the named calls below.
     def one_step(step: int, ev=None):
         dx, doff, dtag, n, _ = batches[step % len(batches)]
         rec = (lambda i: ev[i].record()) if ev is not None else (lambda i: None)
         rec(0)
-        B.emb_tag_keys(dx, doff, dtag, tag_bits, buf.key, buf.err_count)
+        B.emb_tag_dedup(dx, doff, dtag, tag_bits, id_bits, None, buf.uniq, buf.inverse, None, buf.perm, None, buf.seg_of,
+                        buf.n_unique, buf.err_count, buf.tag_dedup_ws)
         rec(1)
-        B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, None, buf.perm, None, buf.seg_of, buf.n_unique, buf.dedup_ws)
+        table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted, touch=False)
         rec(2)
-        table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted, touch=touch)
-        rec(3)
         table.gather(buf.row_idx, buf.n_unique, n, buf.uniq_rows)
-        rec(4)
+        rec(3)
         B.emb_expand_sorted(buf.uniq_rows, buf.seg_of, buf.perm, n, dim, dtype, buf.out)
-        rec(5)
+        rec(4)
         B.grad_segment_reduce(grad, dtype, buf.seg_of, buf.perm, n, dim, buf.reduced, buf.reduce_ws)
+        rec(5)
+        table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps, step + 1)
         rec(6)
-        table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps, None if touch else step + 1)
-        rec(7)
         return n
 
     for s in range(args.warmup):
         one_step(s)
     torch.cuda.synchronize()
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(len(phases) + 1)] for _ in range(args.steps)]
-    uniques, news, ids = [], [], 0
-    st_before = table.stats()
-    live_before = st_before["live"]
+    ids = 0
+    live_before = table.stats()["live"]
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for k in range(args.steps):
@@ -175,13 +194,16 @@ def main() -> int:
     ms_per_step = wall * 1e3 / args.steps
     st_after = table.stats()
     live_after = st_after["live"]
+    next_step = args.warmup + args.steps
 
     phase_ms = {p: float(np.mean([events[k][i].elapsed_time(events[k][i + 1]) for k in range(args.steps)]))
                 for i, p in enumerate(phases)}
-    # U per batch (not on the timed path)
+    # U of the timed batches (read back outside the timed region)
     u_of = {}
-    for s in range(len(batches)):
-        one_step(s)
+    for s in sorted({(args.warmup + k) % len(batches) for k in range(args.steps)}):
+        dx, doff, dtag, n, _ = batches[s]
+        B.emb_tag_dedup(dx, doff, dtag, tag_bits, id_bits, None, buf.uniq, None, None, buf.perm, None, buf.seg_of,
+                        buf.n_unique, buf.err_count, buf.tag_dedup_ws)
         u_of[s] = int(buf.n_unique.item())
     n_avg = ids / args.steps
     u_avg = float(np.mean([u_of[(args.warmup + k) % len(batches)] for k in range(args.steps)]))
@@ -191,13 +213,17 @@ def main() -> int:
 
     # dominant kernel: the expand (one kernel = one phase): its own algorithmic bytes over its own time,
     # both measured here; `traffic` = HBM bytes per launch from the committed counter summary (FETCH_SIZE and
-    # WRITE_SIZE runs of this same command, scaled by a 1 GiB copy), valid for the default configuration only
+    # WRITE_SIZE runs of this same command, scaled by a 1 GiB copy) of the configuration
     dom = "expand"
     dom_gbps = ab[dom] / (phase_ms[dom] * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "k_copy_rows<16,false,true,true> (emb_expand_sorted)", "achieved": round(dom_gbps, 1),
+    lpr = max(1, v_row // 16)
+    kname = f"k_copy_rows<{lpr}, false, true, true>"
+    roofline = {"bound": "hbm", "kernel": f"{kname} (emb_expand_sorted)", "achieved": round(dom_gbps, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBPS, 4),
-                "traffic": profiled_traffic("k_copy_rows<16, false, true, true>") if args.config == 2 else None,
-                "bytes_per_launch": ab[dom], "avg_ms": round(phase_ms[dom], 4)}
+                "traffic": profiled_traffic(kname, args.config),
+                "bytes_per_launch": ab[dom], "avg_ms": round(phase_ms[dom], 4),
+                "whole_step": {"algorithmic_bytes": ab["total"], "achieved": round(achieved, 1),
+                               "frac": round(achieved / HBM_PEAK_GBPS, 4)}}
 
     result = {
         "metric": "embedding IDs/sec fwd+bwd",
@@ -214,114 +240,98 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"config{args.config}:{w.name}", "batch": w.batch, "fields": len(w.features), "dim": dim,
                    "table_keys": n_keys, "capacity_log2": cap_log2, "ids_per_step": int(n_avg),
-                   "unique_per_step": int(u_avg), "new_keys_per_step": round(u_new, 1),
-                   "row_record_updates_per_step": 2 if touch else 1},
+                   "unique_per_step": int(u_avg), "new_keys_per_step": round(u_new, 1), "distinct_batches": len(batches),
+                   "calls": "emb_tag_dedup, ht_find_or_insert_notouch, ht_gather, emb_expand_sorted, grad_segment_reduce, "
+                            "ht_apply_adagrad_touch"},
         "unique_ids_per_sec": round(u_avg * args.steps / wall, 1),
         "algorithmic_bytes_per_step": ab["total"],
         "achieved_hbm_gbps": round(achieved, 1),
         "hbm_frac_of_8TBps": round(achieved / HBM_PEAK_GBPS, 4),
         "phase_ms": {k: round(v, 4) for k, v in phase_ms.items()},
-        "phase_gbps": {p: round(ab[q] / (phase_ms[p] * 1e-3) / 1e9, 1) for p, q in
-                       [("dedup", "tag_dedup"), ("find_or_insert", "find_or_insert"), ("gather", "gather"),
-                        ("expand", "expand"), ("reduce", "reduce"), ("adagrad", "adagrad")]},
+        "phase_gbps": {p: round(ab[p] / (phase_ms[p] * 1e-3) / 1e9, 1) for p in phases},
         "roofline": roofline,
     }
-    if args.count_probes:
-        pc = {k: st_after[k] - st_before[k] for k in ("lookups", "probes", "cas_attempts", "cas_failures", "alloc_atomics")}
-        pc["lines_per_lookup"] = round(pc["probes"] / max(pc["lookups"], 1), 4)
-        result["probe_counters_timed_region"] = pc
+    if st_after["n_rehash"] or st_after["refused"]:
+        result["config"]["rehashes_in_run"] = st_after["n_rehash"]
+        result["config"]["keys_turned_away_at_the_limit"] = st_after["refused"]
+        result["config"]["capacity_log2_after"] = int(np.log2(st_after["capacity"]))
+
+    # ---- the step spelled with the calls the problem statement names, as an extra line: emb_tag_keys + emb_dedup,
+    # ht_find_or_insert (touches every row record), ht_gather, emb_expand by `inverse`, grad_segment_reduce,
+    # ht_apply_adagrad (updates the record again)
+    def one_step_named(step: int):
+        dx, doff, dtag, n, _ = batches[step % len(batches)]
+        B.emb_tag_keys(dx, doff, dtag, tag_bits, buf.key, buf.err_count)
+        B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, None, buf.perm, None, buf.seg_of, buf.n_unique, buf.dedup_ws)
+        table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted, touch=True)
+        table.gather(buf.row_idx, buf.n_unique, n, buf.uniq_rows)
+        B.emb_expand(buf.uniq_rows, buf.inverse, n, dim, dtype, buf.out)
+        B.grad_segment_reduce(grad, dtype, buf.seg_of, buf.perm, n, dim, buf.reduced, buf.reduce_ws)
+        table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps, None)
+        return n
+
+    extras_ok = not args.no_extras and args.config == 2      # the extra lines reuse batches; only where no step brings new keys
+    if extras_ok:
+        wall_n, ids_n = timed_loop(one_step_named, next_step, args.steps)
+        next_step += args.steps + 2
+        result["named_calls_step"] = {
+            "ms_per_step": round(wall_n * 1e3 / args.steps, 4), "ids_per_sec": round(ids_n / wall_n, 1),
+            "hbm_frac_of_8TBps": round(ab["total"] * args.steps / wall_n / 1e9 / HBM_PEAK_GBPS, 4),
+            "calls": "emb_tag_keys, emb_dedup, ht_find_or_insert, ht_gather, emb_expand, grad_segment_reduce, ht_apply_adagrad"}
+
+    # ---- probe and atomic counts of the lookup, from a counted pass outside the timed region
+    if not args.no_extras:
+        result["probe_counts"] = probe_counts(B, table, batches, buf, tag_bits, id_bits, dim, dtype, cap_log2, chunk_log2)
 
     # ---- the same step with the fused lookup (no distinct-row matrix), as an extra line
     def one_step_fused(step: int):
         dx, doff, dtag, n, _ = batches[step % len(batches)]
-        B.emb_tag_keys(dx, doff, dtag, tag_bits, buf.key, buf.err_count)
-        B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, None, buf.perm, None, buf.seg_of, buf.n_unique, buf.dedup_ws)
-        table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted, touch=touch)
+        B.emb_tag_dedup(dx, doff, dtag, tag_bits, id_bits, None, buf.uniq, buf.inverse, None, buf.perm, None, buf.seg_of,
+                        buf.n_unique, buf.err_count, buf.tag_dedup_ws)
+        table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted, touch=False)
         B.ht_gather_expand_sorted(table.h, buf.row_idx, buf.seg_of, buf.perm, n, buf.out)
         B.grad_segment_reduce(grad, dtype, buf.seg_of, buf.perm, n, dim, buf.reduced, buf.reduce_ws)
-        table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps, None if touch else step + 1)
+        table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps, step + 1)
         return n
 
-    base = args.warmup + args.steps + len(batches)
-    if not args.no_extras:
-        for s in range(2):
-            one_step_fused(base + s)
-        torch.cuda.synchronize()
-        t_f = time.perf_counter()
-        ids_f = 0
-        for k in range(args.steps):
-            ids_f += one_step_fused(base + 2 + k)
-        torch.cuda.synchronize()
-        wall_f = time.perf_counter() - t_f
+    if extras_ok:
+        wall_f, ids_f = timed_loop(one_step_fused, next_step, args.steps)
+        next_step += args.steps + 2
         result["fused_lookup"] = {"ms_per_step": round(wall_f * 1e3 / args.steps, 4), "ids_per_sec": round(ids_f / wall_f, 1),
                                   "note": "ht_gather_expand_sorted replaces ht_gather + emb_expand_sorted: same result, "
                                           "2 x rowbytes x unique fewer bytes moved"}
 
-    # ---- the leanest form that still delivers every output of the step on one GPU: no position-ordered inverse
-    # (the sorted-order pair perm / seg_of carries the mapping) and the fused lookup, as an extra line
-    if not args.no_extras:
-        def one_step_lean(step: int):
-            dx, doff, dtag, n, _ = batches[step % len(batches)]
-            B.emb_tag_keys(dx, doff, dtag, tag_bits, buf.key, buf.err_count)
-            B.emb_dedup(buf.key, n, buf.uniq, None, None, buf.perm, None, buf.seg_of, buf.n_unique, buf.dedup_ws)
-            table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted, touch=touch)
-            B.ht_gather_expand_sorted(table.h, buf.row_idx, buf.seg_of, buf.perm, n, buf.out)
-            B.grad_segment_reduce(grad, dtype, buf.seg_of, buf.perm, n, dim, buf.reduced, buf.reduce_ws)
-            table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps, None if touch else step + 1)
-            return n
+    # ---- no position-ordered inverse (the sorted-order pair perm / seg_of carries the mapping), fused lookup and
+    # fused backward: nothing is written that one GPU does not read again, as an extra line
+    def one_step_lean(step: int):
+        dx, doff, dtag, n, _ = batches[step % len(batches)]
+        B.emb_tag_dedup(dx, doff, dtag, tag_bits, id_bits, None, buf.uniq, None, None, buf.perm, None, buf.seg_of,
+                        buf.n_unique, buf.err_count, buf.tag_dedup_ws)
+        table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted, touch=False)
+        B.ht_gather_expand_sorted(table.h, buf.row_idx, buf.seg_of, buf.perm, n, buf.out)
+        B.grad_reduce_apply_adagrad(table.h, grad, buf.seg_of, buf.perm, n, buf.row_idx, w.lr, w.eps, step + 1, buf.reduce_ws)
+        return n
 
-        base_l = base + 3 * (2 + args.steps)
-        for s in range(2):
-            one_step_lean(base_l + s)
-        torch.cuda.synchronize()
-        t_l = time.perf_counter()
-        ids_l = 0
-        for k in range(args.steps):
-            ids_l += one_step_lean(base_l + 2 + k)
-        torch.cuda.synchronize()
-        wall_l = time.perf_counter() - t_l
-        result["lean_step"] = {"ms_per_step": round(wall_l * 1e3 / args.steps, 4), "ids_per_sec": round(ids_l / wall_l, 1),
-                               "note": "emb_dedup without the position-ordered inverse array + ht_gather_expand_sorted: "
-                                       "same embeddings out, same table after the step"}
-
-    # ---- both fusions of the no-communication case: fused lookup and fused backward (no distinct-row matrix, no
-    # reduced-gradient matrix), as an extra line
-    if not args.no_extras:
-        def one_step_fused2(step: int):
-            dx, doff, dtag, n, _ = batches[step % len(batches)]
-            B.emb_tag_keys(dx, doff, dtag, tag_bits, buf.key, buf.err_count)
-            B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, None, buf.perm, None, buf.seg_of, buf.n_unique, buf.dedup_ws)
-            table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted, touch=touch)
-            B.ht_gather_expand_sorted(table.h, buf.row_idx, buf.seg_of, buf.perm, n, buf.out)
-            B.grad_reduce_apply_adagrad(table.h, grad, buf.seg_of, buf.perm, n, buf.row_idx, w.lr, w.eps,
-                                        None if touch else step + 1, buf.reduce_ws)
-            return n
-
-        base2 = base + 2 + args.steps
-        for s in range(2):
-            one_step_fused2(base2 + s)
-        torch.cuda.synchronize()
-        ev0, ev1, ev2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
-        t_f2 = time.perf_counter()
-        ids_f2 = 0
-        for k in range(args.steps):
-            ids_f2 += one_step_fused2(base2 + 2 + k)
-        torch.cuda.synchronize()
-        wall_f2 = time.perf_counter() - t_f2
-        # the fused backward alone
+    if extras_ok:
+        wall_l, ids_l = timed_loop(one_step_lean, next_step, args.steps)
+        next_step += args.steps + 2
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         ev0.record()
         for k in range(5):
             B.grad_reduce_apply_adagrad(table.h, grad, buf.seg_of, buf.perm, batches[0][3], buf.row_idx, w.lr, w.eps, None,
                                         buf.reduce_ws)
         ev1.record()
         torch.cuda.synchronize()
-        result["fused_step"] = {"ms_per_step": round(wall_f2 * 1e3 / args.steps, 4), "ids_per_sec": round(ids_f2 / wall_f2, 1),
-                                "fused_backward_ms": round(ev0.elapsed_time(ev1) / 5, 4),
-                                "note": "ht_gather_expand_sorted + grad_reduce_apply_adagrad: neither the distinct-row "
-                                        "matrix nor the reduced-gradient matrix is written"}
+        result["no_intermediates_step"] = {
+            "ms_per_step": round(wall_l * 1e3 / args.steps, 4), "ids_per_sec": round(ids_l / wall_l, 1),
+            "hbm_frac_of_8TBps_by_the_unfused_byte_count": round(ab["total"] * args.steps / wall_l / 1e9 / HBM_PEAK_GBPS, 4),
+            "fused_backward_ms": round(ev0.elapsed_time(ev1) / 5, 4),
+            "note": "emb_tag_dedup without inverse + ht_gather_expand_sorted + grad_reduce_apply_adagrad: same embeddings "
+                    "out, same table after the step; distinct-row matrix, reduced-gradient matrix and inverse are not "
+                    "written"}
 
     # ---- pooled variant (one vector per sample and field instead of one per position), as an extra line
-    if args.config == 2 and not args.no_extras:
+    if extras_ok:
         lens0 = np.concatenate(lengths_of[0]).astype(np.int64)
         bag_off = torch.from_numpy(np.concatenate([[0], np.cumsum(lens0)]).astype(np.int64)).to(dev)
         nb = len(lens0)
@@ -331,59 +341,49 @@ def main() -> int:
 
         def one_step_pooled(step: int):
             dx, doff, dtag, n, _ = batches[0]
-            B.emb_tag_keys(dx, doff, dtag, tag_bits, buf.key, buf.err_count)
-            B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, None, buf.perm, None, buf.seg_of, buf.n_unique, buf.dedup_ws)
-            table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted, touch=touch)
+            B.emb_tag_dedup(dx, doff, dtag, tag_bits, id_bits, None, buf.uniq, buf.inverse, None, buf.perm, None, buf.seg_of,
+                            buf.n_unique, buf.err_count, buf.tag_dedup_ws)
+            table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted, touch=False)
             table.gather(buf.row_idx, buf.n_unique, n, buf.uniq_rows)
             B.emb_pool_bags(buf.uniq_rows, dtype, buf.inverse, bag_off, n, dim, True, pooled, pws)
             B.grad_segment_reduce_pooled(d_pooled, bag_off, buf.seg_of, buf.perm, n, dim, True, buf.reduced, pws)
-            table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps, None if touch else step + 1)
+            table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps, step + 1)
             return n
 
-        base = base + 2 * (2 + args.steps)
-        for s in range(2):
-            one_step_pooled(base + s)
-        torch.cuda.synchronize()
-        t_p = time.perf_counter()
-        ids_p = 0
-        for k in range(args.steps):
-            ids_p += one_step_pooled(base + 2 + k)
-        torch.cuda.synchronize()
-        wall_p = time.perf_counter() - t_p
+        wall_p, ids_p = timed_loop(one_step_pooled, next_step, args.steps)
+        next_step += args.steps + 2
         result["pooled_lookup"] = {"ms_per_step": round(wall_p * 1e3 / args.steps, 4), "ids_per_sec": round(ids_p / wall_p, 1),
                                    "bags": nb, "mode": "mean",
                                    "note": "emb_pool_bags / grad_segment_reduce_pooled replace expand / reduce: one "
                                            "fp32 vector per (sample, field) instead of one row per position"}
 
+    def timed(fn, reps=10):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
     # ---- same shape with realistic per-field vocabularies (a few fields with a handful of values): segments of
     # 10^5..10^6 positions; table-free phases only (dedup, expand, reduce), as an extra line
-    if args.config == 2 and not args.no_extras:
+    if extras_ok:
         wl = make_config(2, field_vocab=[6_250_000, 20_000, 6_250_000, 500_000, 100, 24, 8, 50])
         bl = wl.next_step(0)
         xl, offl, tagl, _ = merged_inputs(wl.features, bl.ids, merged, 0)
         nl = len(xl)
         if nl <= n_max:
-            dxl = torch.from_numpy(xl.view(np.int64)).to(dev)
-            B.emb_tag_keys(dxl, torch.from_numpy(offl).to(dev), torch.from_numpy(tagl).to(dev), tag_bits, buf.key, buf.err_count)
-
-            def timed(fn, reps=10):
-                fn()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                for _ in range(reps):
-                    fn()
-                e1.record()
-                torch.cuda.synchronize()
-                return e0.elapsed_time(e1) / reps
-
-            t_d = timed(lambda: B.emb_dedup(buf.key, nl, buf.uniq, buf.inverse, buf.counts, buf.perm, None, buf.seg_of,
-                                            buf.n_unique, buf.dedup_ws))
+            dxl, doffl, dtagl = torch.from_numpy(xl.view(np.int64)).to(dev), torch.from_numpy(offl).to(dev), torch.from_numpy(tagl).to(dev)
+            t_d = timed(lambda: B.emb_tag_dedup(dxl, doffl, dtagl, tag_bits, id_bits, None, buf.uniq, buf.inverse, buf.counts,
+                                                buf.perm, buf.seg_off, buf.seg_of, buf.n_unique, buf.err_count, buf.tag_dedup_ws))
             ul = int(buf.n_unique.item())
             longest = int(buf.counts[:ul].max().item())
             t_e = timed(lambda: B.emb_expand_sorted(buf.uniq_rows, buf.seg_of, buf.perm, nl, dim, dtype, buf.out))
             t_r = timed(lambda: B.grad_segment_reduce(grad, dtype, buf.seg_of, buf.perm, nl, dim, buf.reduced, buf.reduce_ws))
             result["low_cardinality_fields"] = {
-                "ids": nl, "unique": ul, "longest_segment": longest, "dedup_ms": round(t_d, 4),
+                "ids": nl, "unique": ul, "longest_segment": longest, "tag_dedup_ms": round(t_d, 4),
                 "expand_ms": round(t_e, 4), "reduce_ms": round(t_r, 4),
                 "note": "field vocabularies 6.25M, 20k, 6.25M, 500k, 100, 24, 8, 50: worst case for the segmented "
                         "reduction (one segment spans thousands of spans)"}
@@ -404,13 +404,13 @@ def main() -> int:
 
         def one_step_z(i: int, step: int):
             dx, doff, dtag, n = zb[i]
-            B.emb_tag_keys(dx, doff, dtag, tag_bits, buf.key, buf.err_count)
-            B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, None, buf.perm, None, buf.seg_of, buf.n_unique, buf.dedup_ws)
-            table.find_or_insert(buf.uniq, buf.n_unique, n, step, buf.row_idx, buf.inserted, touch=touch)
+            B.emb_tag_dedup(dx, doff, dtag, tag_bits, id_bits, None, buf.uniq, buf.inverse, None, buf.perm, None, buf.seg_of,
+                            buf.n_unique, buf.err_count, buf.tag_dedup_ws)
+            table.find_or_insert(buf.uniq, buf.n_unique, n, step, buf.row_idx, buf.inserted, touch=False)
             table.gather(buf.row_idx, buf.n_unique, n, buf.uniq_rows)
             B.emb_expand_sorted(buf.uniq_rows, buf.seg_of, buf.perm, n, dim, dtype, buf.out)
             B.grad_segment_reduce(grad, dtype, buf.seg_of, buf.perm, n, dim, buf.reduced, buf.reduce_ws)
-            table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps, None if touch else step)
+            table.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps, step)
             return n
 
         base_z = 10_000
@@ -437,16 +437,12 @@ def main() -> int:
         nbytes = args.copy_probe_mib << 20
         src = torch.empty(nbytes, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        dst.copy_(src)
-        e0.record()
-        for _ in range(10):
-            dst.copy_(src)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / 10
+        ms = timed(lambda: dst.copy_(src))
         result["copy_probe"] = {"bytes_read": nbytes, "bytes_written": nbytes, "avg_ms": round(ms, 4),
                                 "gbps_read_plus_write": round(2 * nbytes / (ms * 1e-3) / 1e9, 1)}
+        del src, dst
+    if args.ceiling_probes:
+        result["ceiling_probes"] = ceiling_probes(B, timed, dev)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, batches[0][4], tag_bits, dim, dtype, n_keys)
     print(json.dumps(result), flush=True)
@@ -454,9 +450,92 @@ def main() -> int:
     return 0
 
 
-def profiled_traffic(kernel: str):
-    """HBM bytes per dispatch of `kernel` from profiles/hbm_traffic_config2_step.txt (None if absent)."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_config2_step.txt")
+def probe_counts(B, table, batches, buf, tag_bits, id_bits, dim, dtype, cap_log2, chunk_log2) -> dict:
+    """Probe and atomic counts of the hash table from instrumented calls outside the timed region (the counters
+    cost a few atomics per wave, so the timed table runs without them): a 3.9 M-key bulk insert into a fresh table
+    of 2^23 slots (load factor 0 -> 0.47) with its compare-and-swap, admission and allocator counts, then a lookup
+    of the same keys and a lookup of as many absent keys at that load, each with its histogram of distinct slot
+    lines inspected per key."""
+    from paper_2505_12663_amd import EmbeddingTable
+    dx, doff, dtag, n, _ = batches[0]
+    B.emb_tag_dedup(dx, doff, dtag, tag_bits, id_bits, None, buf.uniq, None, None, buf.perm, None, buf.seg_of,
+                    buf.n_unique, buf.err_count, buf.tag_dedup_ws)
+    u = int(buf.n_unique.item())
+    out = {}
+    dev = buf.uniq.device
+    t2 = EmbeddingTable(dim, dtype, capacity_log2=23, chunk_rows_log2=22, max_load_factor=0.75, count_probes=True,
+                        initial_chunks=2)
+    g = torch.Generator(device=dev).manual_seed(3)
+    keys = torch.randint(0, 1 << 40, (1 << 22,), generator=g, device=dev, dtype=torch.int64)
+    keys = torch.unique(keys)[: (1 << 22) - (1 << 18)].contiguous()             # distinct, a little under 4 M
+    k = keys.numel()
+    rows = torch.empty(k, dtype=torch.int32, device=dev)
+    s0 = t2.stats()
+    table_ms = time.perf_counter()
+    t2.find_or_insert(keys, None, k, 1, rows)
+    torch.cuda.synchronize()
+    table_ms = (time.perf_counter() - table_ms) * 1e3
+    s1 = t2.stats()
+    d = lambda a, b, f: b[f] - a[f]
+    out["bulk_insert"] = {
+        "keys": k, "load_factor_after": round(s1["live"] / s1["capacity"], 3),
+        "lines_per_key": round(d(s0, s1, "probes") / max(d(s0, s1, "lookups"), 1), 4),
+        "distinct_lines_per_key_histogram_1_to_8plus": [b - a for a, b in zip(s0["probe_hist"], s1["probe_hist"])],
+        "cas_attempts": d(s0, s1, "cas_attempts"), "cas_failures": d(s0, s1, "cas_failures"),
+        "admission_and_allocator_atomics": d(s0, s1, "alloc_atomics"), "wall_ms_with_sync": round(table_ms, 3)}
+    B.ht_find(t2.h, keys, None, k, rows)
+    s2 = t2.stats()
+    out["lookup_at_load_0.5"] = {
+        "keys": k, "lines_per_key": round(d(s1, s2, "probes") / max(d(s1, s2, "lookups"), 1), 4),
+        "distinct_lines_per_key_histogram_1_to_8plus": [b - a for a, b in zip(s1["probe_hist"], s2["probe_hist"])]}
+    # absent keys at that load (a miss ends at the first line with a never-used slot)
+    miss = keys + (1 << 41)
+    B.ht_find(t2.h, miss, None, k, rows)
+    s3 = t2.stats()
+    out["miss_at_load_0.5"] = {
+        "keys": k, "lines_per_key": round(d(s2, s3, "probes") / max(d(s2, s3, "lookups"), 1), 4),
+        "distinct_lines_per_key_histogram_1_to_8plus": [b - a for a, b in zip(s2["probe_hist"], s3["probe_hist"])]}
+    t2.close()
+    stb = table.stats()
+    out["benchmark_table"] = {"load_factor": round((stb["live"] + stb["tombstones"]) / stb["capacity"], 4),
+                              "distinct_keys_looked_up_per_step": u,
+                              "atomics_per_lookup_step": "none for keys that are present (admission and allocation "
+                                                         "atomics are per block of 1024 keys that brings new keys)"}
+    return out
+
+
+def ceiling_probes(B, timed, dev) -> dict:
+    """What the part delivers to kernels of this library's access shapes, measured with the library's own row
+    movers on synthetic indices (2 GiB of 256-byte rows) and with the runtime's fill / copy for comparison."""
+    rows = 1 << 23                                     # 8 M rows x 256 B = 2 GiB
+    dim = 64
+    src = torch.empty((rows, dim), dtype=torch.float32, device=dev).fill_(1.0)
+    dst = torch.empty_like(src)
+    nbytes = src.numel() * 4
+    ident = torch.arange(rows, dtype=torch.int32, device=dev)
+    g = torch.Generator(device=dev).manual_seed(1)
+    rnd = torch.randperm(rows, generator=g, device=dev).to(torch.int32)
+    quarter = (ident // 4).contiguous()
+    out = {"buffer_bytes": nbytes}
+    ms = timed(lambda: dst.fill_(2.0))
+    out["runtime_fill_write_gbps"] = round(nbytes / (ms * 1e-3) / 1e9, 1)
+    ms = timed(lambda: dst.copy_(src))
+    out["runtime_copy_read_plus_write_gbps"] = round(2 * nbytes / (ms * 1e-3) / 1e9, 1)
+    ms = timed(lambda: B.emb_expand(src, ident, rows, dim, 0, dst))
+    out["row_copy_sequential_read_plus_write_gbps"] = round((2 * nbytes + 4 * rows) / (ms * 1e-3) / 1e9, 1)
+    ms = timed(lambda: B.emb_expand(src, rnd, rows, dim, 0, dst))
+    out["random_row_read_sequential_write_gbps"] = round((2 * nbytes + 4 * rows) / (ms * 1e-3) / 1e9, 1)
+    ms = timed(lambda: B.emb_expand_sorted(src, quarter, rnd, rows, dim, 0, dst))
+    out["quarter_read_random_row_write_gbps"] = round((nbytes // 4 + nbytes + 8 * rows) / (ms * 1e-3) / 1e9, 1)
+    out["note"] = ("row movers of this library on synthetic indices: identity (streaming copy), a random permutation as "
+                   "source index (the gather's shape), one source row per four positions with a random destination "
+                   "permutation (the sorted expand's shape)")
+    return out
+
+
+def profiled_traffic(kernel: str, config: int):
+    """HBM bytes per dispatch of `kernel` from profiles/hbm_traffic_config<config>_step.txt (None if absent)."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_config{config}_step.txt")
     try:
         for line in open(path):
             parts = [p.strip() for p in line.split("|")]
@@ -467,32 +546,52 @@ def profiled_traffic(kernel: str):
     return None
 
 
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(w, batch0, tag_bits, dim, dtype, n_keys) -> dict:
-    """The CPU checker as it stands, one thread, timed on one full step of the first batch.
-    Pre-existing keys the step touches are materialised first (untimed), as the lazy checker does."""
+    """The CPU checker as it stands, one thread, timed on one whole step of the first batch, three repetitions,
+    median (about 15 s of CPU work).  Pre-existing keys the step touches are materialised first (untimed), as the
+    lazy checker does."""
     import oracle
     x, off, tags = batch0
+    n_fields = len(tags)
+    n = int(off[n_fields])
+    x, off, tags = x[:n], off[:n_fields + 1], tags[:n_fields]
     log("cpu baseline: preparing (untimed)")
     key, _ = oracle.tag_keys(x, off, tags, tag_bits)
     uniq, _, _ = oracle.dedup(key)
-    t = oracle.Table(dim, dtype)
-    t.prepopulate(uniq)
     rng = np.random.Generator(np.random.Philox(key=1234))
     G = rng.standard_normal((len(x), dim), dtype=np.float32)
-    log("cpu baseline: timing one step")
-    t0 = time.perf_counter()
-    key, _ = oracle.tag_keys(x, off, tags, tag_bits)
-    uniq, inverse, _ = oracle.dedup(key)
-    t.find_or_insert(uniq, 1)
-    E_u = t.lookup(uniq)
-    E = oracle.expand(E_u, inverse)
-    g = oracle.segment_reduce(G, inverse, len(uniq))
-    t.apply_adagrad(uniq, g, w.lr, w.eps)
-    dt = time.perf_counter() - t0
-    assert E.shape == (len(x), dim)
+    times = []
+    for rep in range(3):
+        t = oracle.Table(dim, dtype)
+        t.prepopulate(uniq)
+        log(f"cpu baseline: timing repetition {rep + 1} of 3")
+        t0 = time.perf_counter()
+        key, _ = oracle.tag_keys(x, off, tags, tag_bits)
+        uniq, inverse, _ = oracle.dedup(key)
+        t.find_or_insert(uniq, 1)
+        E_u = t.lookup(uniq)
+        E = oracle.expand(E_u, inverse)
+        g = oracle.segment_reduce(G, inverse, len(uniq))
+        t.apply_adagrad(uniq, g, w.lr, w.eps)
+        times.append(time.perf_counter() - t0)
+        assert E.shape == (len(x), dim)
+        del t, E, E_u, g
+    dt = float(np.median(times))
     return {"value": round(len(x) / dt, 1), "unit": "IDs/s", "cores": 1, "kind": "oracle",
-            "sample": f"one full step of batch 0 ({len(x)} IDs, {len(uniq)} unique), touched keys pre-materialised",
-            "seconds": round(dt, 2), "host_cpus": os.cpu_count()}
+            "sample": f"one full step over the first {n_fields} of {len(batch0[2])} fields of batch 0 ({len(x)} IDs, "
+                      f"{len(uniq)} unique), touched keys pre-materialised, median of 3 repetitions",
+            "seconds": round(dt, 2), "seconds_all": [round(v, 2) for v in times], "host_cpus": os.cpu_count(),
+            "cpu_model": cpu_model()}
 
 
 if __name__ == "__main__":

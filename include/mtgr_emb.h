@@ -92,11 +92,12 @@ typedef struct {
     uint64_t probes;        /* 128-byte slot lines inspected for them */
     uint64_t cas_attempts;
     uint64_t cas_failures;
-    uint64_t alloc_atomics; /* atomics issued by the row allocator (one per block of 1024 keys that creates rows) */
+    uint64_t alloc_atomics; /* atomics issued by admission and the row allocator (per block of 1024 keys that brings new keys) */
     /* hot store (ht_set_hot_storage); all zero without one */
     uint64_t hot_rows_used;     /* high-water mark of the hot store's allocator */
     uint64_t hot_rows_free;     /* hot rows returned by evictions */
     uint64_t hot_rows_capacity;
+    uint64_t probe_hist[8]; /* count_probes != 0: keys that inspected 1, 2, .. 7, and 8 or more slot lines */
     uint64_t refused;       /* new keys turned away so far by find-or-insert (limit reached or out of rows); each got -1 */
 } ht_stats_t;
 
@@ -197,6 +198,22 @@ size_t emb_dedup_workspace_bytes(int64_t n);
 int emb_dedup(const uint64_t* key, int64_t n, uint64_t* uniq, int32_t* inverse, int32_t* counts,
               int32_t* perm, int32_t* seg_off, int32_t* seg_of, int64_t* n_unique, void* workspace,
               size_t workspace_bytes, void* stream);
+
+/* Eq. 8 and Sec. 3.3 in one call: the results of emb_tag_keys followed by emb_dedup on the tagged keys, without
+ * writing the tagged keys (unless key_out is given) and with fewer, narrower sort passes.
+ * id_bits: declared width of the raw IDs, 1 <= id_bits <= 63 - tag_bits (e.g. 40 for IDs drawn from a 2^40
+ *   space).  A raw ID that needs more bits is counted in *err_count and its excess bits are dropped - the
+ *   same treatment emb_tag_keys gives IDs beyond Eq. 8's 63 - tag_bits bits.
+ * key_out [dev, n, optional]: the tagged keys, as emb_tag_keys writes them.  All other outputs as emb_dedup.
+ * The table identifier is a function of the position (IDs arrive field by field), so the sort carries 8-byte
+ * records (ID, position) whenever id_bits + ceil(log2 n) <= 64 and n_fields <= 1024, and ceil((id_bits +
+ * tag_bits) / 9) radix passes are planned on the host; otherwise the call runs emb_tag_keys and emb_dedup
+ * internally.  workspace [dev, 256-byte aligned] of at least emb_tag_dedup_workspace_bytes(...) bytes. */
+size_t emb_tag_dedup_workspace_bytes(int64_t n, int n_fields, int tag_bits, int id_bits);
+int emb_tag_dedup(const uint64_t* x, const int64_t* field_off, const uint8_t* field_tag, int n_fields, int64_t n,
+                  int tag_bits, int id_bits, uint64_t* key_out, uint64_t* uniq, int32_t* inverse, int32_t* counts,
+                  int32_t* perm, int32_t* seg_off, int32_t* seg_of, int64_t* n_unique, int64_t* err_count,
+                  void* workspace, size_t workspace_bytes, void* stream);
 
 /* For callers that cannot allocate device memory or hand in a workspace: code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc.  emb_dedup with the same arguments and results, minus the

@@ -6,6 +6,6 @@ gfx950); importing this package without the built library raises.
 """
 from . import binding  # noqa: F401
 from .binding import F32, BF16, EmbError, load  # noqa: F401
-from .table import EmbeddingTable, StepBuffers, forward, backward, forward_fused, backward_fused  # noqa: F401
+from .table import EmbeddingTable, StepBuffers, forward, forward_two_call, backward, forward_fused, backward_fused  # noqa: F401
 
 load()

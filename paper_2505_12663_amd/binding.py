@@ -38,13 +38,16 @@ class TableDesc(C.Structure):
 
 
 class HtStats(C.Structure):
-    _fields_ = [(n, C.c_uint64) for n in
-                ("live", "tombstones", "capacity", "rows_used", "rows_free", "rows_capacity", "n_rehash",
-                 "n_chunks", "status", "lookups", "probes", "cas_attempts", "cas_failures", "alloc_atomics",
-                 "hot_rows_used", "hot_rows_free", "hot_rows_capacity", "refused")]
+    _fields_ = ([(n, C.c_uint64) for n in
+                 ("live", "tombstones", "capacity", "rows_used", "rows_free", "rows_capacity", "n_rehash",
+                  "n_chunks", "status", "lookups", "probes", "cas_attempts", "cas_failures", "alloc_atomics",
+                  "hot_rows_used", "hot_rows_free", "hot_rows_capacity")]
+                + [("probe_hist", C.c_uint64 * 8), ("refused", C.c_uint64)])
 
     def as_dict(self):
-        return {n: int(getattr(self, n)) for n, _ in self._fields_}
+        d = {n: int(getattr(self, n)) for n, _ in self._fields_ if n != "probe_hist"}
+        d["probe_hist"] = [int(v) for v in self.probe_hist]
+        return d
 
 
 EXPORTS = [
@@ -56,6 +59,7 @@ EXPORTS = [
     "grad_segment_reduce_pooled", "ht_evict", "ht_export", "ht_put", "ht_set_hot_storage", "ht_promote", "ht_export_hot",
     "ht_find_or_insert_notouch", "ht_apply_adagrad_touch", "grad_reduce_apply_adagrad",
     "ht_find_or_insert_retry", "ht_clear_status", "emb_dedup_noalloc",
+    "emb_tag_dedup_workspace_bytes", "emb_tag_dedup",
 ]
 
 
@@ -85,6 +89,8 @@ def load():
         "emb_tag_keys": (C.c_int, [vp, vp, vp, i32, i64, i32, vp, vp, vp]),
         "emb_dedup_workspace_bytes": (C.c_size_t, [i64]),
         "emb_dedup": (C.c_int, [vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]),
+        "emb_tag_dedup_workspace_bytes": (C.c_size_t, [i64, i32, i32, i32]),
+        "emb_tag_dedup": (C.c_int, [vp, vp, vp, i32, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]),
         "emb_dedup_noalloc": (C.c_int, [vp, i64, vp, vp, vp, vp, vp, vp, vp, vp]),
         "ht_find_or_insert": (C.c_int, [vp, vp, vp, i64, u32, vp, vp, vp]),
         "ht_find_or_insert_notouch": (C.c_int, [vp, vp, vp, i64, u32, vp, vp, vp]),
@@ -221,6 +227,18 @@ def emb_dedup(key, n: int, uniq, inverse, counts, perm, seg_off, seg_of, n_uniqu
     _check(load().emb_dedup(_ptr(key), n, _ptr(uniq), _ptr(inverse), _ptr(counts), _ptr(perm), _ptr(seg_off),
                             _ptr(seg_of), _ptr(n_unique), _ptr(workspace), workspace.numel() * workspace.element_size(),
                             _stream(stream)), "emb_dedup")
+
+
+def emb_tag_dedup_workspace_bytes(n: int, n_fields: int, tag_bits: int, id_bits: int) -> int:
+    return int(load().emb_tag_dedup_workspace_bytes(n, n_fields, tag_bits, id_bits))
+
+
+def emb_tag_dedup(x, field_off, field_tag, tag_bits: int, id_bits: int, key_out, uniq, inverse, counts, perm, seg_off, seg_of,
+                  n_unique, err_count, workspace, stream=None) -> None:
+    _check(load().emb_tag_dedup(_ptr(x), _ptr(field_off), _ptr(field_tag), field_tag.numel(), x.numel(), tag_bits, id_bits,
+                                _ptr(key_out), _ptr(uniq), _ptr(inverse), _ptr(counts), _ptr(perm), _ptr(seg_off), _ptr(seg_of),
+                                _ptr(n_unique), _ptr(err_count), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                _stream(stream)), "emb_tag_dedup")
 
 
 def emb_dedup_noalloc(key, n: int, uniq, inverse, counts, perm, seg_off, seg_of, n_unique, stream=None) -> None:

@@ -36,7 +36,9 @@ struct __attribute__((aligned(16))) RowMeta {
 // Counters that are only ever added to (no return value needed) are striped over 64 cache lines:
 // atomics of concurrently running blocks on one address queue up behind each other (about 25 ns
 // apiece on this part), atomics on different lines do not.
-enum StatSlot { kStatLookups = 0, kStatProbes, kStatCas, kStatCasFail, kStatAlloc, kStatLive, kStatTomb, kStatUnused };
+enum StatSlot { kStatLookups = 0, kStatProbes, kStatCas, kStatCasFail, kStatAlloc, kStatLive, kStatTomb, kStatUnused,
+                kStatHist0 /* .. kStatHist0 + 7: keys that inspected 1, 2, .. 7, 8 or more slot lines */ };
+constexpr int kStatSlots = 16;
 struct HtHead {
     unsigned int bump;       // rows handed out by the bump allocator
     int free_count;          // entries on the free-row stack (may dip below 0 inside an insert kernel)
@@ -46,7 +48,7 @@ struct HtHead {
     unsigned int occupied;   // slots that are not never-used (live + deleted): inserts are admitted against the load-factor limit here
     unsigned long long refused; // new keys turned away so far (limit reached or out of rows)
     unsigned long long pad1[12];
-    unsigned long long stat[kStatStripes][8]; // [stripe][StatSlot]; live / deleted counts are the sums over stripes
+    unsigned long long stat[kStatStripes][kStatSlots]; // [stripe][StatSlot]; live / deleted counts are the sums over stripes
 };
 struct HtState {
     HtHead head;
@@ -67,6 +69,7 @@ struct HtCounts {
     int hot_free_count;
     unsigned long long refused;
     unsigned long long stat[5];
+    unsigned long long probe_hist[8];
     static HtCounts from(const HtHead& h) {
         HtCounts c{};
         c.refused = h.refused;
@@ -79,6 +82,7 @@ struct HtCounts {
             c.live += h.stat[i][kStatLive];            // wraps: stripes hold signed deltas
             c.tombstones += h.stat[i][kStatTomb];
             for (int k = 0; k < 5; ++k) c.stat[k] += h.stat[i][k];
+            for (int k = 0; k < 8; ++k) c.probe_hist[k] += h.stat[i][kStatHist0 + k];
         }
         return c;
     }
@@ -183,6 +187,11 @@ inline int check_hip(hipError_t e) { return e == hipSuccess ? EMB_OK : EMB_ERR_H
     do {                                            \
         if (hipGetLastError() != hipSuccess) return EMB_ERR_HIP; \
     } while (0)
+
+// emb_tag_keys with a declared ID width: raw IDs that need more than min(id_bits, 63 - tag_bits) bits are
+// counted and wrapped (dedup.hip; also the first half of emb_tag_dedup's two-call form).
+int tag_keys_limited(const uint64_t* x, const int64_t* field_off, const uint8_t* field_tag, int n_fields, int64_t n,
+                     int tag_bits, int id_bits, uint64_t* key_out, int64_t* err_count, void* stream);
 
 } // namespace mtgr
 

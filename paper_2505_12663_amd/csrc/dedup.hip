@@ -61,13 +61,13 @@ __device__ inline int field_of(const int64_t* s_off, int n_fields, int64_t e) {
 // inside one field, so two searches per wave (first and last element) replace one per element.
 __global__ __launch_bounds__(kThreads) void k_tag(const uint64_t* __restrict__ x, const int64_t* __restrict__ field_off,
                                                  const uint8_t* __restrict__ field_tag, int n_fields, int64_t n,
-                                                 int shift, uint64_t* __restrict__ key_out,
+                                                 int shift, int id_bits, uint64_t* __restrict__ key_out,
                                                  unsigned long long* err_count) {
     extern __shared__ int64_t s_off[]; // n_fields + 1 offsets
     for (int f = threadIdx.x; f <= n_fields; f += kThreads) s_off[f] = field_off[f];
     __syncthreads();
     constexpr int kPer = 4;
-    const uint64_t low_mask = (1ull << shift) - 1ull;
+    const uint64_t low_mask = (1ull << (id_bits < shift ? id_bits : shift)) - 1ull;   // IDs beyond it are counted and wrapped
     const int lane = lane_id();
     const int64_t wave_stride = (int64_t)gridDim.x * kWaves * (kWave * kPer);
     unsigned errs = 0;
@@ -547,7 +547,14 @@ extern "C" {
 
 int emb_tag_keys(const uint64_t* x, const int64_t* field_off, const uint8_t* field_tag, int n_fields,
                  int64_t n, int tag_bits, uint64_t* key_out, int64_t* err_count, void* stream) {
-    if (n < 0 || n_fields < 0 || n_fields > 4096 || tag_bits < 0 || tag_bits > 16 || !err_count) return EMB_ERR_INVALID_ARG;
+    return mtgr::tag_keys_limited(x, field_off, field_tag, n_fields, n, tag_bits, 63, key_out, err_count, stream);
+}
+
+} // extern "C"
+
+int mtgr::tag_keys_limited(const uint64_t* x, const int64_t* field_off, const uint8_t* field_tag, int n_fields,
+                           int64_t n, int tag_bits, int id_bits, uint64_t* key_out, int64_t* err_count, void* stream) {
+    if (n < 0 || n_fields < 0 || n_fields > 4096 || tag_bits < 0 || tag_bits > 16 || id_bits < 1 || !err_count) return EMB_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipLaunchKernelGGL(k_zero64, dim3(1), dim3(64), 0, s, reinterpret_cast<unsigned long long*>(err_count));
     MTGR_LAUNCH_CHECK();
@@ -556,10 +563,12 @@ int emb_tag_keys(const uint64_t* x, const int64_t* field_off, const uint8_t* fie
     unsigned grid = (unsigned)((n + kThreads * 4 - 1) / (kThreads * 4));
     if (grid > 65536u) grid = 65536u;
     hipLaunchKernelGGL(k_tag, dim3(grid), dim3(kThreads), (size_t)(n_fields + 1) * sizeof(int64_t), s, x, field_off,
-                       field_tag, n_fields, n, 63 - tag_bits, key_out, reinterpret_cast<unsigned long long*>(err_count));
+                       field_tag, n_fields, n, 63 - tag_bits, id_bits, key_out, reinterpret_cast<unsigned long long*>(err_count));
     MTGR_LAUNCH_CHECK();
     return EMB_OK;
 }
+
+extern "C" {
 
 size_t emb_dedup_workspace_bytes(int64_t n) {
     if (n < 0) return 0;

@@ -9,33 +9,36 @@
 
 #include "common.hpp"
 
-#ifndef MTGR_ADA_ROWS
-#define MTGR_ADA_ROWS 2
-#endif
-
 using namespace mtgr;
 
 namespace {
 
 constexpr int kBlock = 256;
-#ifndef MTGR_RED_PIPE_MAX
-#define MTGR_RED_PIPE_MAX 8
-#endif
-#ifndef MTGR_RED_UNROLL_UPPER
-#define MTGR_RED_UNROLL_UPPER 8
-#endif
-#ifndef MTGR_RED_UNROLL
-#define MTGR_RED_UNROLL 4
-#endif
-#ifndef MTGR_RED_SPAN
-#define MTGR_RED_SPAN 64
-#endif
-constexpr int kUnroll = MTGR_RED_UNROLL;          // first level
-constexpr int kUnrollUpper = MTGR_RED_UNROLL_UPPER;
+constexpr int kUnroll = 4;            // segment reduce: rows a lane group fetches per batch at the first level
+constexpr int kUnrollUpper = 8;       // ... and at the upper levels
+constexpr int kPipeMax = 8;           // batches up to this size are double-buffered
 
 __device__ inline const char* chunk_row_cptr(const HtView& v, uint32_t row) {
     const char* base = static_cast<const char*>(v.st->values[row >> v.chunk_log2]);
     return base + (size_t)(row & ((1u << v.chunk_log2) - 1u)) * (size_t)v.row_bytes;
+}
+
+// Base pointers of the value chunks and their row records, copied to LDS once per block: a row's address then
+// depends on its index only, not on a load from the chunk directory in HBM (which would put a second memory
+// round trip in front of every batch of row loads).
+__device__ inline void stage_chunks(const HtView& v, char** s_values, RowMeta** s_meta) {
+    const int nc = (int)(v.rows_capacity >> v.chunk_log2);
+    for (int c = threadIdx.x; c < nc; c += kBlock) {
+        s_values[c] = static_cast<char*>(v.st->values[c]);
+        if (s_meta) s_meta[c] = v.st->meta[c];
+    }
+    __syncthreads();
+}
+__device__ inline char* staged_row(const HtView& v, char* const* s_values, uint32_t row) {
+    return s_values[row >> v.chunk_log2] + (size_t)(row & ((1u << v.chunk_log2) - 1u)) * (size_t)v.row_bytes;
+}
+__device__ inline RowMeta* staged_meta(const HtView& v, RowMeta* const* s_meta, uint32_t row) {
+    return s_meta[row >> v.chunk_log2] + (row & ((1u << v.chunk_log2) - 1u));
 }
 
 // ---------------------------------------------------------------------------- gather / expand
@@ -47,8 +50,8 @@ __device__ inline const char* chunk_row_cptr(const HtView& v, uint32_t row) {
 constexpr int kCopyUnroll = 8;
 
 template <int LPR, bool SRC_TABLE, bool NT_STORE, bool FULL, bool DST_IDX>
-__device__ inline void copy_rows_body(const HtView& v, const char* __restrict__ src_base, int my_index, int my_dst,
-                                      int rows_here, int vecs, int row_bytes, char* __restrict__ out_wave, int lane) {
+__device__ inline void copy_rows_body(const HtView& v, char* const* s_values, const char* __restrict__ src_base, int my_index,
+                                      int my_dst, int rows_here, int vecs, int row_bytes, char* __restrict__ out_wave, int lane) {
     constexpr int kGroups = kWave / LPR;          // rows per wave instruction
     constexpr int kU = (kGroups * kCopyUnroll > kWave) ? (kWave / kGroups) : kCopyUnroll;
     const int sub = lane % LPR, grp = lane / LPR;
@@ -63,7 +66,7 @@ __device__ inline void copy_rows_body(const HtView& v, const char* __restrict__ 
             const int idx = __shfl(my_index, r, kWave);
             const bool ok = lane_on && (FULL || r < rows_here);
             const int safe = idx < 0 ? 0 : idx;
-            const char* p = SRC_TABLE ? chunk_row_cptr(v, (uint32_t)safe) : src_base + (size_t)safe * (size_t)row_bytes;
+            const char* p = SRC_TABLE ? staged_row(v, s_values, (uint32_t)safe) : src_base + (size_t)safe * (size_t)row_bytes;
             if (FULL) {
                 val[u] = ld16(p + sub * 16);
             } else {
@@ -93,6 +96,8 @@ __global__ __launch_bounds__(kBlock) void k_copy_rows(HtView v, const char* __re
                                                       const int32_t* __restrict__ via,
                                                       const int32_t* __restrict__ dst_index, const int64_t* n_dev,
                                                       int64_t n_max, int row_bytes, char* __restrict__ out) {
+    __shared__ char* s_values[SRC_TABLE ? kMaxChunks : 1];
+    if (SRC_TABLE) stage_chunks(v, s_values, nullptr);
     const int64_t n = read_count(n_dev, n_max);
     const int lane = lane_id();
     const int64_t wave_base = (int64_t)blockIdx.x * kBlock + (threadIdx.x & ~(kWave - 1));
@@ -104,11 +109,11 @@ __global__ __launch_bounds__(kBlock) void k_copy_rows(HtView v, const char* __re
     const int rows_here = (int)((n - wave_base) < kWave ? (n - wave_base) : kWave);
     char* out_wave = DST_IDX ? out : out + (size_t)wave_base * (size_t)row_bytes;
     if (rows_here == kWave && vecs == LPR)
-        copy_rows_body<LPR, SRC_TABLE, NT_STORE, true, DST_IDX>(v, src_base, my_index, my_dst, rows_here, vecs, row_bytes,
-                                                                out_wave, lane);
+        copy_rows_body<LPR, SRC_TABLE, NT_STORE, true, DST_IDX>(v, s_values, src_base, my_index, my_dst, rows_here, vecs,
+                                                                row_bytes, out_wave, lane);
     else
-        copy_rows_body<LPR, SRC_TABLE, NT_STORE, false, DST_IDX>(v, src_base, my_index, my_dst, rows_here, vecs, row_bytes,
-                                                                 out_wave, lane);
+        copy_rows_body<LPR, SRC_TABLE, NT_STORE, false, DST_IDX>(v, s_values, src_base, my_index, my_dst, rows_here, vecs,
+                                                                 row_bytes, out_wave, lane);
 }
 
 template <bool SRC_TABLE, bool NT, bool DST_IDX>
@@ -141,7 +146,7 @@ int launch_copy_rows(const HtView& v, const char* src, const int32_t* index, con
 // tree, so results are reproducible run to run.  Span length trades partial-row traffic (two
 // fp32 rows per span) against parallelism; 64 measured best on the long-sequence workload
 // (0.67 ms against 0.72 ms at 128 and 0.84 ms at 256 for 8.7 M rows of 256 bytes).
-constexpr int kSpan = MTGR_RED_SPAN;
+constexpr int kSpan = 64;
 
 // FPL = floats accumulated per lane (4 for fp32 rows of 16 bytes per lane, 8 for bf16)
 template <int FPL>
@@ -218,26 +223,13 @@ struct LevelIn {
     int in_row_bytes;
 };
 
-// Fused form (no reduced matrix): a completed segment sum goes straight into the row-wise Adagrad
-// update of row row_idx[segment].  The update needs the row and its record from memory; so that
-// the reduction's loads are not held up, a completed sum is parked, its loads are issued, and the
-// update is finished when the next sum completes (or at the end of the span).
-struct FuseArgs {
-    HtView v;
-    const int32_t* row_idx;   // row of every segment (-1 = none)
-    float lr, eps;
-    uint32_t step;
-    int touch;                // also set last_seen = step and count one touch
-};
-
 // UNR = rows a group fetches per batch, the next batch being fetched while the current one is
 // folded: 4 at the large first level, 8 at the small upper levels, which are chains of dependent
 // round trips (their stores would otherwise sit between a batch's loads and their use).
-// FUSE = 1: apply Adagrad to completed sums (table dtype TBL_BF16) instead of storing them.
-template <int LPR, int FPL, bool LEVEL1, int UNR, int FUSE, bool TBL_BF16>
+template <int LPR, int FPL, bool LEVEL1, int UNR>
 __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, float* __restrict__ reduced,
                                                        float* __restrict__ part_rows, int32_t* __restrict__ part_seg,
-                                                       int last_level, FuseArgs fz) {
+                                                       int last_level) {
     constexpr int kGroups = kWave / LPR;
     const int lane = lane_id();
     const int sub = lane % LPR, grp = lane / LPR;
@@ -252,76 +244,15 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
     Acc<FPL> acc;
     acc.zero();
     int cur_seg = -1;
-    int cur_row = -1;        // fused form: table row of cur_seg
     int runs_closed = 0;     // runs already flushed in this span
     bool have = false;
 
-    // ---- fused form: one parked update per group
-    constexpr int kWB = FPL * (TBL_BF16 ? 2 : 4);   // bytes of the table row a lane owns (16, or 8 for bf16 rows at upper levels)
-    bool p_on = false;
-    int p_row = -1;
-    Acc<FPL> p_g;
-    V16 p_w{0u, 0u, 0u, 0u}, p_rec{0u, 0u, 0u, 0u};
-    auto finish_update = [&](void) {
-        if (!FUSE || !p_on) return;
-        p_on = false;
-        const float ss = sumsq_group<LPR>(sumsq_lane<FPL>(p_g.f));
-        const float acc_new = adagrad_acc(__uint_as_float(p_rec.x), ss, __fdiv_rn(1.0f, (float)dim));
-        const float scale = adagrad_scale(acc_new, fz.lr, fz.eps);
-        const uint32_t row = (uint32_t)p_row;
-        if (lane_on) {
-            char* wp = const_cast<char*>(chunk_row_cptr(fz.v, row)) + sub * kWB;
-            if (!TBL_BF16) {
-                st16(wp, V16{__float_as_uint(adagrad_w(__uint_as_float(p_w.x), p_g.f[0], scale)),
-                             __float_as_uint(adagrad_w(__uint_as_float(p_w.y), p_g.f[1], scale)),
-                             __float_as_uint(adagrad_w(__uint_as_float(p_w.z), p_g.f[2], scale)),
-                             __float_as_uint(adagrad_w(__uint_as_float(p_w.w), p_g.f[3], scale))});
-            } else {
-                const uint32_t o0 = pack_bf16(adagrad_w(bf16lo(p_w.x), p_g.f[0], scale), adagrad_w(bf16hi(p_w.x), p_g.f[1], scale));
-                const uint32_t o1 = pack_bf16(adagrad_w(bf16lo(p_w.y), p_g.f[2], scale), adagrad_w(bf16hi(p_w.y), p_g.f[3], scale));
-                if constexpr (FPL == 8) {
-                    const uint32_t o2 = pack_bf16(adagrad_w(bf16lo(p_w.z), p_g.f[4], scale), adagrad_w(bf16hi(p_w.z), p_g.f[5], scale));
-                    const uint32_t o3 = pack_bf16(adagrad_w(bf16lo(p_w.w), p_g.f[6], scale), adagrad_w(bf16hi(p_w.w), p_g.f[7], scale));
-                    st16(wp, V16{o0, o1, o2, o3});
-                } else {
-                    *reinterpret_cast<uint2*>(wp) = make_uint2(o0, o1);
-                }
-            }
-        }
-        if (sub == 0) {
-            RowMeta* m = &fz.v.st->meta[row >> fz.v.chunk_log2][row & ((1u << fz.v.chunk_log2) - 1u)];
-            if (fz.touch) st16(m, V16{__float_as_uint(acc_new), fz.step, p_rec.z + 1u, p_rec.w});
-            else m->acc = acc_new;
-        }
-    };
-    // the sum in `acc` is complete for the segment whose row is `row`: park it and fetch what the update needs
-    auto start_update = [&](int row) {
-        finish_update();
-        if (row < 0) return;
-        p_on = true;
-        p_row = row;
-        p_g = acc;
-        const uint32_t r = (uint32_t)row;
-        p_rec = ld16(&fz.v.st->meta[r >> fz.v.chunk_log2][r & ((1u << fz.v.chunk_log2) - 1u)]);
-        if (lane_on) {
-            const char* wp = chunk_row_cptr(fz.v, r) + sub * kWB;
-            if (kWB == 16) p_w = ld16(wp);
-            else {
-                const uint2 t = *reinterpret_cast<const uint2*>(wp);
-                p_w.x = t.x;
-                p_w.y = t.y;
-            }
-        }
-    };
-
-    // flush the current run: first run of the span -> partial slot 0, otherwise complete -> reduced[] (or the update)
+    // flush the current run: first run of the span -> partial slot 0, otherwise complete -> reduced[]
     auto flush_mid = [&](void) {
         if (!have) return;
         if (runs_closed == 0 && !last_level) {
             if (lane_on) acc_store<FPL>(part_rows + (size_t)(2 * span) * dim, sub, acc);
             if (sub == 0) part_seg[2 * span] = cur_seg;
-        } else if (FUSE) {
-            start_update(cur_row);
         } else {
             if (lane_on) acc_store<FPL>(reduced + (size_t)cur_seg * dim, sub, acc);
         }
@@ -337,13 +268,11 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
     for (int c = 0; c < kSpan; c += kChunk) {
         int my_src[kPre];          // source row of the item (< 2^31)
         int my_seg[kPre];
-        int my_row[kPre];
 #pragma unroll
         for (int u = 0; u < kPre; ++u) {
             const int it = c + u * LPR + sub;
             my_src[u] = -1;
             my_seg[u] = -1;
-            my_row[u] = -1;
             if (group_on && it < items) {
                 const int64_t j = first + it;
                 if (LEVEL1) {
@@ -353,65 +282,57 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
                     my_src[u] = (int)j;
                 }
                 my_seg[u] = in.seg[j];
-                if (FUSE && my_seg[u] >= 0) my_row[u] = fz.row_idx[my_seg[u]];
             }
         }
         // batch b fetches the rows of flat items b*UNR .. b*UNR+UNR-1 of the chunk
-        auto issue = [&](int b, V16* v_, int* sg_, int* rw_) {
+        auto issue = [&](int b, V16* v_, int* sg_) {
 #pragma unroll
             for (int k = 0; k < UNR; ++k) {
                 const int f = b * UNR + k;
                 sg_[k] = -1;
-                rw_[k] = -1;
                 v_[k] = V16{0u, 0u, 0u, 0u};
                 if (f < kChunk) {
                     const int sl = gbase + f % LPR;
                     const int src = __shfl(my_src[f / LPR], sl, kWave);
                     sg_[k] = __shfl(my_seg[f / LPR], sl, kWave);
-                    if (FUSE) rw_[k] = __shfl(my_row[f / LPR], sl, kWave);
                     if (lane_on && sg_[k] >= 0) v_[k] = ld16(in.rows + (size_t)src * (size_t)in.in_row_bytes + sub * 16);
                 }
             }
         };
-        auto fold = [&](const V16* v_, const int* sg_, const int* rw_) {
+        auto fold = [&](const V16* v_, const int* sg_) {
 #pragma unroll
             for (int k = 0; k < UNR; ++k) {
                 if (sg_[k] < 0) continue;
                 if (have && sg_[k] != cur_seg) flush_mid();
                 cur_seg = sg_[k];
-                cur_row = rw_[k];
                 have = true;
                 acc_add(acc, v_[k], false);
             }
         };
-        if constexpr (UNR <= MTGR_RED_PIPE_MAX && !(FUSE && FPL == 8)) {   // (the parked update of 8-float lanes leaves no registers for a second batch)
+        if constexpr (UNR <= kPipeMax) {
             // the loads of batch b+1 are issued before batch b is folded, so that a wave always has loads in flight
             V16 val[2][UNR];
-            int seg[2][UNR], rw[2][UNR];
-            issue(0, val[0], seg[0], rw[0]);
+            int seg[2][UNR];
+            issue(0, val[0], seg[0]);
 #pragma unroll
             for (int b = 0; b < kBatches; ++b) {
-                if (b + 1 < kBatches) issue(b + 1, val[(b + 1) & 1], seg[(b + 1) & 1], rw[(b + 1) & 1]);
-                fold(val[b & 1], seg[b & 1], rw[b & 1]);
+                if (b + 1 < kBatches) issue(b + 1, val[(b + 1) & 1], seg[(b + 1) & 1]);
+                fold(val[b & 1], seg[b & 1]);
             }
         } else {
             V16 val[UNR];
-            int seg[UNR], rw[UNR];
+            int seg[UNR];
 #pragma unroll
             for (int b = 0; b < kBatches; ++b) {
-                issue(b, val, seg, rw);
-                fold(val, seg, rw);
+                issue(b, val, seg);
+                fold(val, seg);
             }
         }
     }
     // last run of the span
     if (group_on) {
         if (last_level) {
-            if (FUSE) {
-                if (have) start_update(cur_row);
-            } else if (have && lane_on) {
-                acc_store<FPL>(reduced + (size_t)cur_seg * dim, sub, acc);
-            }
+            if (have && lane_on) acc_store<FPL>(reduced + (size_t)cur_seg * dim, sub, acc);
         } else {
             // a span with a single run has already nothing in slot 0: put the run there, slot 1 empty
             const int slot = (runs_closed == 0) ? 0 : 1;
@@ -422,7 +343,224 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
             }
         }
     }
-    finish_update();
+}
+
+// ---------------------------------------------------------------------------- segment reduce + update in one pass
+// Same spans, same order of additions and the same partial rows as k_seg_reduce, but a run that
+// completes inside a span goes straight into the row-wise Adagrad update of row row_idx[segment]
+// instead of the reduced matrix.  Which items end such a run is known as soon as the span's segment
+// numbers are (they are loaded first), so the table row and the row record a completed sum will need
+// are fetched together with the gradient rows of its batch, one batch ahead of their use: the update
+// never waits on a load of its own.  The base pointers of the value chunks are staged in LDS, so no
+// address depends on a load from the chunk directory in HBM.
+struct FuseArgs {
+    HtView v;
+    const int32_t* row_idx;   // row of every segment (-1 = none)
+    float lr, eps;
+    uint32_t step;
+    int touch;                // also set last_seen = step and count one touch
+    int n_chunks;
+};
+
+template <int LPR, int FPL, bool LEVEL1, int UNR, bool TBL_BF16>
+__global__ __launch_bounds__(kBlock) void k_seg_reduce_apply(LevelIn in, int dim, float* __restrict__ part_rows,
+                                                             int32_t* __restrict__ part_seg, int last_level, FuseArgs fz) {
+    __shared__ char* s_values[kMaxChunks];
+    __shared__ RowMeta* s_meta[kMaxChunks];
+    for (int c = threadIdx.x; c < fz.n_chunks; c += kBlock) {
+        s_values[c] = static_cast<char*>(fz.v.st->values[c]);
+        s_meta[c] = fz.v.st->meta[c];
+    }
+    __syncthreads();
+    constexpr int kGroups = kWave / LPR;
+    constexpr int kWB = FPL * (TBL_BF16 ? 2 : 4);   // bytes of the table row a lane owns (16, or 8 for bf16 rows at upper levels)
+    const int lane = lane_id();
+    const int sub = lane % LPR, grp = lane / LPR;
+    const int gbase = lane - sub;
+    const int64_t span = ((int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave) * kGroups + grp;
+    const int64_t first = span * kSpan;
+    const bool group_on = first < in.n_items;
+    const int vecs = in.in_row_bytes / 16;
+    const bool lane_on = group_on && sub < vecs;
+    const int items = group_on ? (int)((in.n_items - first) < kSpan ? (in.n_items - first) : kSpan) : 0;
+    const uint32_t chunk_mask = (1u << fz.v.chunk_log2) - 1u;
+    const float inv_d = __fdiv_rn(1.0f, (float)dim);
+
+    Acc<FPL> acc;
+    acc.zero();
+    int cur_seg = -1;
+    int runs_closed = 0;
+    bool have = false;
+
+    // the run in `acc` is complete and its row (w_) and record (rec_) are here: update the row
+    auto apply = [&](int row, const V16& w_, const V16& rec_) {
+        const float ss = sumsq_group<LPR>(sumsq_lane<FPL>(acc.f));
+        const uint32_t rec_acc = __shfl(rec_.x, gbase, kWave), rec_freq = __shfl(rec_.z, gbase, kWave),
+                       rec_hot = __shfl(rec_.w, gbase, kWave);
+        if (row >= 0) {
+            const float acc_new = adagrad_acc(__uint_as_float(rec_acc), ss, inv_d);
+            const float scale = adagrad_scale(acc_new, fz.lr, fz.eps);
+            const uint32_t r = (uint32_t)row;
+            if (lane_on) {
+                char* wp = s_values[r >> fz.v.chunk_log2] + (size_t)(r & chunk_mask) * (size_t)fz.v.row_bytes + sub * kWB;
+                if (!TBL_BF16) {
+                    st16(wp, V16{__float_as_uint(adagrad_w(__uint_as_float(w_.x), acc.f[0], scale)),
+                                 __float_as_uint(adagrad_w(__uint_as_float(w_.y), acc.f[1], scale)),
+                                 __float_as_uint(adagrad_w(__uint_as_float(w_.z), acc.f[2], scale)),
+                                 __float_as_uint(adagrad_w(__uint_as_float(w_.w), acc.f[3], scale))});
+                } else {
+                    const uint32_t o0 = pack_bf16(adagrad_w(bf16lo(w_.x), acc.f[0], scale), adagrad_w(bf16hi(w_.x), acc.f[1], scale));
+                    const uint32_t o1 = pack_bf16(adagrad_w(bf16lo(w_.y), acc.f[2], scale), adagrad_w(bf16hi(w_.y), acc.f[3], scale));
+                    if constexpr (FPL == 8) {
+                        const uint32_t o2 = pack_bf16(adagrad_w(bf16lo(w_.z), acc.f[4], scale), adagrad_w(bf16hi(w_.z), acc.f[5], scale));
+                        const uint32_t o3 = pack_bf16(adagrad_w(bf16lo(w_.w), acc.f[6], scale), adagrad_w(bf16hi(w_.w), acc.f[7], scale));
+                        st16(wp, V16{o0, o1, o2, o3});
+                    } else {
+                        *reinterpret_cast<uint2*>(wp) = make_uint2(o0, o1);
+                    }
+                }
+            }
+            if (sub == 0) {
+                RowMeta* m = s_meta[r >> fz.v.chunk_log2] + (r & chunk_mask);
+                if (fz.touch) st16(m, V16{__float_as_uint(acc_new), fz.step, rec_freq + 1u, rec_hot});
+                else m->acc = acc_new;
+            }
+        }
+        runs_closed++;
+        acc.zero();
+        have = false;
+    };
+
+    constexpr int kPre = (kSpan / LPR) < 1 ? 1 : ((kSpan / LPR) > 4 ? 4 : (kSpan / LPR));
+    constexpr int kChunk = LPR * kPre;
+    constexpr int kBatches = (kChunk + UNR - 1) / UNR;
+    // segment of the first item of the span: its run continues from the span before (unless this is the last level)
+    int seg_first = -1;
+    if (group_on) seg_first = in.seg[first];
+    for (int c = 0; c < kSpan; c += kChunk) {
+        int my_src[kPre], my_seg[kPre], my_row[kPre], my_next[kPre];
+#pragma unroll
+        for (int u = 0; u < kPre; ++u) {
+            const int it = c + u * LPR + sub;
+            my_src[u] = -1;
+            my_seg[u] = -1;
+            my_row[u] = -1;
+            my_next[u] = -2;       // segment of the item after this one (-2: there is none in this span)
+            if (group_on && it < items) {
+                const int64_t j = first + it;
+                if (LEVEL1) {
+                    const int32_t p = in.perm[j];
+                    my_src[u] = in.via ? in.via[p] : p;
+                } else {
+                    my_src[u] = (int)j;
+                }
+                my_seg[u] = in.seg[j];
+                // segment of the next item; at the upper levels the second slot of a span may be empty (-1) and
+                // the run goes on with the first slot of the span after it, which never is
+                if (it + 1 < items) {
+                    int nx = in.seg[j + 1];
+                    if (!LEVEL1 && nx < 0) nx = it + 2 < items ? in.seg[j + 2] : -2;
+                    my_next[u] = nx;
+                }
+            }
+        }
+        // does item (u, lane) end a run that is applied here?  Not the run that came in from the span before,
+        // not the run that goes on into the next span (both travel to the next level as partial rows), unless
+        // this is the last level, where every run ends here.  Segment -1 = no item (upper levels).
+#pragma unroll
+        for (int u = 0; u < kPre; ++u) {
+            const bool ends = my_seg[u] >= 0 && my_next[u] != my_seg[u];
+            const bool applied = last_level ? ends : (ends && my_next[u] != -2 && my_seg[u] != seg_first);
+            my_row[u] = applied ? fz.row_idx[my_seg[u]] : -2;     // -2: nothing to apply at this item; -1: segment without a row
+        }
+        // element `idx` of a small per-lane array without dynamic register indexing
+        auto pick = [&](const int* arr, int idx) {
+            int r = arr[0];
+#pragma unroll
+            for (int u = 1; u < kPre; ++u) r = idx == u ? arr[u] : r;
+            return r;
+        };
+        auto issue = [&](int b, V16* v_, int* sg_, int* rw_, V16* w_, V16* rec_) {
+#pragma unroll
+            for (int k = 0; k < UNR; ++k) {
+                const int f = b * UNR + k;
+                sg_[k] = -1;
+                rw_[k] = -2;
+                v_[k] = V16{0u, 0u, 0u, 0u};
+                w_[k] = V16{0u, 0u, 0u, 0u};
+                rec_[k] = V16{0u, 0u, 0u, 0u};
+                if (f < kChunk) {
+                    const int sl = gbase + f % LPR;
+                    const int u = f / LPR;
+                    const int src = __shfl(pick(my_src, u), sl, kWave);
+                    sg_[k] = __shfl(pick(my_seg, u), sl, kWave);
+                    rw_[k] = __shfl(pick(my_row, u), sl, kWave);
+                    if (lane_on && sg_[k] >= 0) v_[k] = ld16(in.rows + (size_t)src * (size_t)in.in_row_bytes + sub * 16);
+                    if (rw_[k] >= 0) {
+                        const uint32_t r = (uint32_t)rw_[k];
+                        if (lane_on) {
+                            const char* wp = s_values[r >> fz.v.chunk_log2] + (size_t)(r & chunk_mask) * (size_t)fz.v.row_bytes + sub * kWB;
+                            if (kWB == 16) w_[k] = ld16(wp);
+                            else {
+                                const uint2 t = *reinterpret_cast<const uint2*>(wp);
+                                w_[k].x = t.x;
+                                w_[k].y = t.y;
+                            }
+                        }
+                        if (sub == 0) rec_[k] = ld16(s_meta[r >> fz.v.chunk_log2] + (r & chunk_mask));
+                    }
+                }
+            }
+        };
+        auto fold = [&](const V16* v_, const int* sg_, const int* rw_, const V16* w_, const V16* rec_) {
+#pragma unroll
+            for (int k = 0; k < UNR; ++k) {
+                if (sg_[k] < 0) continue;
+                if (have && sg_[k] != cur_seg) {
+                    // the run that came in from the span before ends here: partial slot 0
+                    if (lane_on) acc_store<FPL>(part_rows + (size_t)(2 * span) * dim, sub, acc);
+                    if (sub == 0) part_seg[2 * span] = cur_seg;
+                    runs_closed++;
+                    acc.zero();
+                }
+                cur_seg = sg_[k];
+                have = true;
+                acc_add(acc, v_[k], false);
+                if (rw_[k] != -2) apply(rw_[k], w_[k], rec_[k]);
+            }
+        };
+        if constexpr (UNR <= 4 && FPL == 4) {
+            // two named buffers, two batches per trip: the loads of the next batch are issued before the current
+            // one is folded, and no buffer is ever indexed by a run-time value
+            V16 val_a[UNR], wv_a[UNR], rec_a[UNR], val_b[UNR], wv_b[UNR], rec_b[UNR];
+            int seg_a[UNR], rw_a[UNR], seg_b[UNR], rw_b[UNR];
+            issue(0, val_a, seg_a, rw_a, wv_a, rec_a);
+#pragma unroll 1
+            for (int b = 0; b < kBatches; b += 2) {
+                if (b + 1 < kBatches) issue(b + 1, val_b, seg_b, rw_b, wv_b, rec_b);
+                fold(val_a, seg_a, rw_a, wv_a, rec_a);
+                if (b + 2 < kBatches) issue(b + 2, val_a, seg_a, rw_a, wv_a, rec_a);
+                if (b + 1 < kBatches) fold(val_b, seg_b, rw_b, wv_b, rec_b);
+            }
+        } else {
+            V16 val[UNR], wv[UNR], rec[UNR];
+            int seg[UNR], rw[UNR];
+#pragma unroll 1
+            for (int b = 0; b < kBatches; ++b) {
+                issue(b, val, seg, rw, wv, rec);
+                fold(val, seg, rw, wv, rec);
+            }
+        }
+    }
+    // the run that goes on into the next span (at the last level every run has been applied above)
+    if (group_on && !last_level) {
+        const int slot = (runs_closed == 0) ? 0 : 1;
+        if (have && lane_on) acc_store<FPL>(part_rows + (size_t)(2 * span + slot) * dim, sub, acc);
+        if (sub == 0) {
+            part_seg[2 * span + slot] = have ? cur_seg : -1;
+            if (slot == 0) part_seg[2 * span + 1] = -1;
+        }
+    }
 }
 
 struct ReduceLayout {
@@ -453,11 +591,9 @@ ReduceLayout reduce_layout(int64_t n, int dim) {
     return L;
 }
 
-template <int LPR, int FPL, int FUSE>
+template <int LPR, int FPL>
 int launch_reduce(const char* grad, int in_row_bytes, const int32_t* seg_of, const int32_t* perm, const int32_t* via,
-                  int64_t n, int dim, float* reduced, char* ws, const ReduceLayout& L, hipStream_t s,
-                  const FuseArgs& fz = FuseArgs{}) {
-    constexpr bool kTblBf16 = FUSE && FPL == 8;   // the fused form takes gradients in the table dtype
+                  int64_t n, int dim, float* reduced, char* ws, const ReduceLayout& L, hipStream_t s) {
     constexpr int kGroups = kWave / LPR;
     constexpr int kSpansPerBlock = (kBlock / kWave) * kGroups;
     for (int l = 0; l < L.levels; ++l) {
@@ -467,7 +603,7 @@ int launch_reduce(const char* grad, int in_row_bytes, const int32_t* seg_of, con
         int32_t* pseg = reinterpret_cast<int32_t*>(ws + L.seg_off[l]);
         if (l == 0) {
             LevelIn in{grad, perm, via, seg_of, n, in_row_bytes};
-            hipLaunchKernelGGL((k_seg_reduce<LPR, FPL, true, kUnroll, FUSE, kTblBf16>), dim3(grid), dim3(kBlock), 0, s, in, dim, reduced, prow, pseg, last, fz);
+            hipLaunchKernelGGL((k_seg_reduce<LPR, FPL, true, kUnroll>), dim3(grid), dim3(kBlock), 0, s, in, dim, reduced, prow, pseg, last);
         } else {
             LevelIn in{ws + L.rows_off[l - 1], nullptr, nullptr, reinterpret_cast<const int32_t*>(ws + L.seg_off[l - 1]),
                        L.items[l], dim * 4};
@@ -476,7 +612,36 @@ int launch_reduce(const char* grad, int in_row_bytes, const int32_t* seg_of, con
             constexpr int kGroups2 = kWave / LPR2;
             constexpr int kSpb2 = (kBlock / kWave) * kGroups2;
             const unsigned grid2 = (unsigned)((L.spans[l] + kSpb2 - 1) / kSpb2);
-            hipLaunchKernelGGL((k_seg_reduce<LPR2, 4, false, kUnrollUpper, FUSE, kTblBf16>), dim3(grid2), dim3(kBlock), 0, s, in, dim, reduced, prow, pseg, last, fz);
+            hipLaunchKernelGGL((k_seg_reduce<LPR2, 4, false, kUnrollUpper>), dim3(grid2), dim3(kBlock), 0, s, in, dim, reduced, prow, pseg, last);
+        }
+        MTGR_LAUNCH_CHECK();
+    }
+    return EMB_OK;
+}
+
+// the same levels with k_seg_reduce_apply; gradients come in the table dtype (FPL = 8: bf16 table)
+template <int LPR, int FPL>
+int launch_reduce_apply(const char* grad, int in_row_bytes, const int32_t* seg_of, const int32_t* perm, int64_t n, int dim,
+                        char* ws, const ReduceLayout& L, hipStream_t s, const FuseArgs& fz) {
+    constexpr bool kTblBf16 = FPL == 8;
+    constexpr int kGroups = kWave / LPR;
+    constexpr int kSpansPerBlock = (kBlock / kWave) * kGroups;
+    for (int l = 0; l < L.levels; ++l) {
+        const int last = (l == L.levels - 1) ? 1 : 0;
+        const unsigned grid = (unsigned)((L.spans[l] + kSpansPerBlock - 1) / kSpansPerBlock);
+        float* prow = reinterpret_cast<float*>(ws + L.rows_off[l]);
+        int32_t* pseg = reinterpret_cast<int32_t*>(ws + L.seg_off[l]);
+        if (l == 0) {
+            LevelIn in{grad, perm, nullptr, seg_of, n, in_row_bytes};
+            hipLaunchKernelGGL((k_seg_reduce_apply<LPR, FPL, true, kUnroll, kTblBf16>), dim3(grid), dim3(kBlock), 0, s, in, dim, prow, pseg, last, fz);
+        } else {
+            LevelIn in{ws + L.rows_off[l - 1], nullptr, nullptr, reinterpret_cast<const int32_t*>(ws + L.seg_off[l - 1]),
+                       L.items[l], dim * 4};
+            constexpr int LPR2 = (FPL == 8) ? (LPR * 2 > 64 ? 64 : LPR * 2) : LPR;
+            constexpr int kGroups2 = kWave / LPR2;
+            constexpr int kSpb2 = (kBlock / kWave) * kGroups2;
+            const unsigned grid2 = (unsigned)((L.spans[l] + kSpb2 - 1) / kSpb2);
+            hipLaunchKernelGGL((k_seg_reduce_apply<LPR2, 4, false, kUnrollUpper, kTblBf16>), dim3(grid2), dim3(kBlock), 0, s, in, dim, prow, pseg, last, fz);
         }
         MTGR_LAUNCH_CHECK();
     }
@@ -493,6 +658,9 @@ template <int LPR, bool BF16, bool TOUCH>
 __global__ __launch_bounds__(kBlock) void k_adagrad(HtView v, const int32_t* __restrict__ row_idx,
                                                     const float* __restrict__ g, const int64_t* n_dev, int64_t n_max,
                                                     float lr, float eps, uint32_t step) {
+    __shared__ char* s_values[kMaxChunks];
+    __shared__ RowMeta* s_meta[kMaxChunks];
+    stage_chunks(v, s_values, s_meta);
     const int64_t n = read_count(n_dev, n_max);
     const int lane = lane_id();
     const int64_t wave_base = (int64_t)blockIdx.x * kBlock + (threadIdx.x & ~(kWave - 1));
@@ -504,7 +672,7 @@ __global__ __launch_bounds__(kBlock) void k_adagrad(HtView v, const int32_t* __r
     const int my_index = (wave_base + lane < n) ? row_idx[wave_base + lane] : -1;
     const int rows_here = (int)((n - wave_base) < kWave ? (n - wave_base) : kWave);
     const float inv_d = __fdiv_rn(1.0f, (float)v.dim);
-    constexpr int kRows = MTGR_ADA_ROWS;          // rows in flight per group
+    constexpr int kRows = 2;                      // rows in flight per group (4 measured no faster)
 #pragma unroll 1
     for (int r0 = 0; r0 < kWave; r0 += kGroups * kRows) {
         if (r0 >= rows_here) break;
@@ -528,7 +696,7 @@ __global__ __launch_bounds__(kBlock) void k_adagrad(HtView v, const int32_t* __r
             freq_old[u] = hot_old[u] = 0u;
             if (on[u]) {
                 const uint32_t row = (uint32_t)idx[u];
-                const RowMeta* m = &v.st->meta[row >> v.chunk_log2][row & ((1u << v.chunk_log2) - 1u)];
+                const RowMeta* m = staged_meta(v, s_meta, row);
                 if (TOUCH) {
                     const V16 rec = ld16(m);
                     acc_old[u] = __uint_as_float(rec.x);
@@ -548,7 +716,7 @@ __global__ __launch_bounds__(kBlock) void k_adagrad(HtView v, const int32_t* __r
                     gv[u][4 * q + 2] = __uint_as_float(t.z);
                     gv[u][4 * q + 3] = __uint_as_float(t.w);
                 }
-                wv[u] = ld16(chunk_row_cptr(v, (uint32_t)idx[u]) + sub * 16);
+                wv[u] = ld16(staged_row(v, s_values, (uint32_t)idx[u]) + sub * 16);
             }
         }
 #pragma unroll
@@ -559,7 +727,7 @@ __global__ __launch_bounds__(kBlock) void k_adagrad(HtView v, const int32_t* __r
             const float acc = adagrad_acc(acc_old[u], ss, inv_d);
             const float scale = adagrad_scale(acc, lr, eps);
             if (lane_on) {
-                char* wp = const_cast<char*>(chunk_row_cptr(v, row)) + sub * 16;
+                char* wp = staged_row(v, s_values, row) + sub * 16;
                 V16 o;
                 if (BF16) {
                     o.x = pack_bf16(adagrad_w(bf16lo(wv[u].x), gv[u][0], scale), adagrad_w(bf16hi(wv[u].x), gv[u][1], scale));
@@ -575,7 +743,7 @@ __global__ __launch_bounds__(kBlock) void k_adagrad(HtView v, const int32_t* __r
                 st16(wp, o);
             }
             if (sub == 0) {
-                RowMeta* m = &v.st->meta[row >> v.chunk_log2][row & ((1u << v.chunk_log2) - 1u)];
+                RowMeta* m = staged_meta(v, s_meta, row);
                 if (TOUCH) st16(m, V16{__float_as_uint(acc), step, freq_old[u] + 1u, hot_old[u]});
                 else m->acc = acc;
             }
@@ -935,10 +1103,10 @@ static int reduce_dispatch(const void* grad, int grad_dtype, const int32_t* seg_
     char* ws = static_cast<char*>(workspace);
     const int vecs = in_row_bytes / 16;
 #define MTGR_RED(L_)                                                                                                      \
-    (fz ? (grad_dtype == EMB_F32 ? launch_reduce<L_, 4, 1>(g, in_row_bytes, seg_of, perm, via, n, dim, reduced, ws, L, s, *fz) \
-                                 : launch_reduce<L_, 8, 1>(g, in_row_bytes, seg_of, perm, via, n, dim, reduced, ws, L, s, *fz)) \
-        : (grad_dtype == EMB_F32 ? launch_reduce<L_, 4, 0>(g, in_row_bytes, seg_of, perm, via, n, dim, reduced, ws, L, s)      \
-                                 : launch_reduce<L_, 8, 0>(g, in_row_bytes, seg_of, perm, via, n, dim, reduced, ws, L, s)))
+    (fz ? (grad_dtype == EMB_F32 ? launch_reduce_apply<L_, 4>(g, in_row_bytes, seg_of, perm, n, dim, ws, L, s, *fz)       \
+                                 : launch_reduce_apply<L_, 8>(g, in_row_bytes, seg_of, perm, n, dim, ws, L, s, *fz))      \
+        : (grad_dtype == EMB_F32 ? launch_reduce<L_, 4>(g, in_row_bytes, seg_of, perm, via, n, dim, reduced, ws, L, s)    \
+                                 : launch_reduce<L_, 8>(g, in_row_bytes, seg_of, perm, via, n, dim, reduced, ws, L, s)))
     if (vecs <= 1) return MTGR_RED(1);
     if (vecs <= 2) return MTGR_RED(2);
     if (vecs <= 4) return MTGR_RED(4);
@@ -965,7 +1133,7 @@ int grad_reduce_apply_adagrad(emb_table_t* t, const void* grad, const int32_t* s
     if (!row_idx) return EMB_ERR_INVALID_ARG;
     if (t->n_chunks == 0) return EMB_ERR_NO_STORAGE;
     if (t->hot_values) return EMB_ERR_INVALID_ARG; // rows with fp32 masters take the two-call form
-    FuseArgs fz{t->view(), row_idx, lr, eps, step, touch ? 1 : 0};
+    FuseArgs fz{t->view(), row_idx, lr, eps, step, touch ? 1 : 0, t->n_chunks};
     return reduce_dispatch(grad, t->desc.dtype, seg_of, perm, nullptr, n, t->desc.dim, nullptr, workspace, workspace_bytes,
                            static_cast<hipStream_t>(stream), &fz);
 }

@@ -59,6 +59,7 @@ __global__ void k_set_chunk(HtState* st, int c, void* values, RowMeta* meta, uin
 
 struct ProbeCounters {
     unsigned probes, cas, cas_fail;
+    unsigned my_lines;   // slot lines inspected for this lane's own key (probe histogram)
 };
 
 // --------------------------------------------------------------------------------------------
@@ -87,6 +88,7 @@ __device__ inline long long probe_group(const HtView& v, uint64_t key, bool acti
     long long result = -1;
     bool done = !active;
     *created = false;
+    unsigned lines = 0;
     while (__any(!done)) {
         Slot* sp = v.slots + line * kLineSlots + sub;
         uint64_t k = kEmptyKey;
@@ -98,6 +100,7 @@ __device__ inline long long probe_group(const HtView& v, uint64_t key, bool acti
         bool retry_line = false;
         if (!done) {
             pc->probes += (sub == 0);
+            ++lines;
             if (hit8) {
                 result = (long long)(line * kLineSlots + (__ffs(hit8) - 1));
                 done = true;
@@ -137,6 +140,7 @@ __device__ inline long long probe_group(const HtView& v, uint64_t key, bool acti
             }
         }
     }
+    pc->my_lines = lines;   // group-uniform; the caller credits it to the lane that owns the key
     return result;
 }
 
@@ -223,8 +227,16 @@ __device__ inline unsigned long long* stat_stripe(const HtView& v, unsigned id) 
     return v.st->head.stat[id & (kStatStripes - 1)];
 }
 
-__device__ inline void flush_counters(const HtView& v, int lane, unsigned wave_no, int64_t cnt, ProbeCounters pc) {
+// key_lines: slot lines inspected for this lane's key (0 = the lane had no key)
+__device__ inline void flush_counters(const HtView& v, int lane, unsigned wave_no, int64_t cnt, ProbeCounters pc,
+                                      unsigned key_lines) {
     unsigned tot_p = pc.probes, tot_c = pc.cas, tot_f = pc.cas_fail;
+    unsigned long long* hc = stat_stripe(v, wave_no);
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+        const uint64_t m = __ballot(b < 7 ? key_lines == (unsigned)(b + 1) : key_lines >= 8u);
+        if (lane == 0 && m) atomicAdd(&hc[kStatHist0 + b], (unsigned long long)__popcll(m));
+    }
     for (int o = 32; o > 0; o >>= 1) {
         tot_p += __shfl_xor(tot_p, o, kWave);
         tot_c += __shfl_xor(tot_c, o, kWave);
@@ -288,7 +300,8 @@ __global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const ui
     const int sub = lane & (kLineSlots - 1);
     const int gbase = lane & ~(kLineSlots - 1);
 
-    ProbeCounters pc{0u, 0u, 0u};
+    ProbeCounters pc{0u, 0u, 0u, 0u};
+    unsigned key_lines = my_ok ? 1u : 0u;   // distinct slot lines of its probe sequence inspected for this lane's key
     long long my_slot = -1;
     uint32_t my_row = kRowInvalid;
     bool my_created = false;
@@ -306,6 +319,7 @@ __global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const ui
                 if (sub == r && act) {
                     my_slot = s == -1 ? kSlotAbsent : s;   // -2: every line visited, no match, no room
                     my_row = kRowInvalid;
+                    key_lines = pc.my_lines;        // the line-by-line walk starts over at the first line
                 }
             }
         }
@@ -375,6 +389,7 @@ __global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const ui
                         my_slot = s;
                         my_created = created;
                         my_row = kRowInvalid;
+                        key_lines = key_lines > pc.my_lines ? key_lines : pc.my_lines;   // distinct lines of the key's sequence
                     }
                 }
             }
@@ -517,7 +532,7 @@ __global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const ui
         if (inserted) inserted[i] = my_created ? 1 : 0;
     }
     if (COUNT && wave_on)
-        flush_counters(v, lane, blockIdx.x * kBigWaves + wave, n - wave_base < kWave ? n - wave_base : kWave, pc);
+        flush_counters(v, lane, blockIdx.x * kBigWaves + wave, n - wave_base < kWave ? n - wave_base : kWave, pc, key_lines);
 }
 
 // Second half of find-or-insert: resolve the deferred elements and count their touch.
@@ -551,7 +566,8 @@ __global__ __launch_bounds__(kBlock) void k_find(HtView v, const uint64_t* __res
     const bool my_ok = valid && !(my_key >> 63);
     const int sub = lane & (kLineSlots - 1);
     const int gbase = lane & ~(kLineSlots - 1);
-    ProbeCounters pc{0u, 0u, 0u};
+    ProbeCounters pc{0u, 0u, 0u, 0u};
+    unsigned key_lines = my_ok ? 1u : 0u;
     long long my_slot;
     uint32_t my_row;
     bool unused_created;
@@ -567,11 +583,12 @@ __global__ __launch_bounds__(kBlock) void k_find(HtView v, const uint64_t* __res
             if (sub == r && act) {
                 my_slot = s;
                 my_row = s >= 0 ? v.slots[s].row : kRowInvalid;
+                key_lines = pc.my_lines;
             }
         }
     }
     if (valid) row_idx[i] = (my_slot >= 0 && my_row != kRowInvalid) ? (int32_t)my_row : -1;
-    if (COUNT) flush_counters(v, lane, blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave, n - wave_base < kWave ? n - wave_base : kWave, pc);
+    if (COUNT) flush_counters(v, lane, blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave, n - wave_base < kWave ? n - wave_base : kWave, pc, key_lines);
 }
 
 // --------------------------------------------------------------------------------------------
@@ -1108,6 +1125,7 @@ int ht_stats(emb_table_t* t, ht_stats_t* out, void* stream) {
     out->cas_attempts = h.stat[kStatCas];
     out->cas_failures = h.stat[kStatCasFail];
     out->alloc_atomics = h.stat[kStatAlloc];
+    for (int b = 0; b < 8; ++b) out->probe_hist[b] = h.probe_hist[b];
     out->hot_rows_used = h.hot_bump;
     out->hot_rows_free = h.hot_free_count > 0 ? (uint64_t)h.hot_free_count : 0ull;
     out->hot_rows_capacity = t->hot_capacity;

@@ -233,6 +233,9 @@ class StepBuffers:
         self.row_idx = torch.empty(n_max, dtype=torch.int32, device=dev)
         self.inserted = torch.empty(n_max, dtype=torch.uint8, device=dev)
         self.dedup_ws = torch.empty(B.emb_dedup_workspace_bytes(n_max), dtype=torch.uint8, device=dev)
+        # emb_tag_dedup: the larger of its two internal forms (8-byte records / tag, then deduplicate)
+        self.tag_dedup_ws = torch.empty(max(B.emb_tag_dedup_workspace_bytes(n_max, 1, 0, 32),
+                                            B.emb_tag_dedup_workspace_bytes(n_max, 1, 0, 63)), dtype=torch.uint8, device=dev)
         self.uniq_rows = torch.empty((n_max, dim), dtype=tdt, device=dev)
         self.out = torch.empty((n_max, dim), dtype=tdt, device=dev)
         if with_grad:
@@ -241,9 +244,23 @@ class StepBuffers:
 
 
 def forward(table: EmbeddingTable, buf: StepBuffers, x, field_off, field_tag, tag_bits: int, step: int,
-            touch: bool = True) -> None:
-    """tag -> dedup -> find-or-insert -> gather -> expand (in sorted order); results in buf.out[:n].
+            touch: bool = True, id_bits: Optional[int] = None, want_keys: bool = True) -> None:
+    """tag + dedup (one call) -> find-or-insert -> gather -> expand (in sorted order); results in buf.out[:n].
+    id_bits: declared width of the raw IDs (default: everything Eq. 8 leaves, 63 - tag_bits).
+    want_keys: also write the tagged keys to buf.key.
     touch=False leaves the rows' touch records to the update of the same step (backward with touch_step)."""
+    n = x.numel()
+    B.emb_tag_dedup(x, field_off, field_tag, tag_bits, (63 - tag_bits) if id_bits is None else id_bits,
+                    buf.key if want_keys else None, buf.uniq, buf.inverse, buf.counts, buf.perm, buf.seg_off, buf.seg_of,
+                    buf.n_unique, buf.err_count, buf.tag_dedup_ws)
+    table.find_or_insert(buf.uniq, buf.n_unique, n, step, buf.row_idx, buf.inserted, touch=touch)
+    table.gather(buf.row_idx, buf.n_unique, n, buf.uniq_rows)
+    B.emb_expand_sorted(buf.uniq_rows, buf.seg_of, buf.perm, n, table.dim, table.dtype, buf.out)
+
+
+def forward_two_call(table: EmbeddingTable, buf: StepBuffers, x, field_off, field_tag, tag_bits: int, step: int,
+                     touch: bool = True) -> None:
+    """The same with emb_tag_keys and emb_dedup as separate calls (the tagged keys are materialised)."""
     n = x.numel()
     B.emb_tag_keys(x, field_off, field_tag, tag_bits, buf.key, buf.err_count)
     B.emb_dedup(buf.key, n, buf.uniq, buf.inverse, buf.counts, buf.perm, buf.seg_off, buf.seg_of, buf.n_unique,

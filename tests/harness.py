@@ -6,7 +6,7 @@ import torch
 
 import oracle
 from paper_2505_12663_amd import binding as B
-from paper_2505_12663_amd import EmbeddingTable, StepBuffers, forward, backward
+from paper_2505_12663_amd import EmbeddingTable, StepBuffers, forward, forward_two_call, backward
 
 RTOL_F32 = 1e-5     # reduced gradients and updated rows, fp32 tables
 RTOL_BF16 = 1e-2    # bf16 tables
@@ -57,7 +57,7 @@ class Pair:
 
 def run_step(pair: Pair, buf: StepBuffers, x: np.ndarray, field_off: np.ndarray, field_tag: np.ndarray,
              tag_bits: int, step: int, G: np.ndarray, lr: float, eps: float, prepopulated_keys=None,
-             one_record_update: bool = False):
+             one_record_update: bool = False, id_bits=None, two_call: bool = False):
     """One forward+backward on both sides; asserts the parity bar and returns (N, U).
     one_record_update: the HIP side looks keys up without touching them and lets the update count the
     touch; the checker keeps touching in the lookup - after the step both must be in the same state."""
@@ -76,7 +76,10 @@ def run_step(pair: Pair, buf: StepBuffers, x: np.ndarray, field_off: np.ndarray,
     pair.orc.apply_adagrad(ouniq, og, lr, eps)
     # ---- HIP path
     dx, doff, dtag = dev_keys(x), torch.from_numpy(field_off).cuda(), torch.from_numpy(field_tag).cuda()
-    forward(pair.gpu, buf, dx, doff, dtag, tag_bits, step, touch=not one_record_update)
+    if two_call:
+        forward_two_call(pair.gpu, buf, dx, doff, dtag, tag_bits, step, touch=not one_record_update)
+    else:
+        forward(pair.gpu, buf, dx, doff, dtag, tag_bits, step, touch=not one_record_update, id_bits=id_bits)
     U = int(buf.n_unique.item())
     assert int(buf.err_count.item()) == oerr
     assert np.array_equal(host_keys(buf.key[:n]), okey), "tagged keys"
@@ -126,7 +129,7 @@ def tracked_subset(hot_keys: np.ndarray):
 
 
 def run_step_sampled(pair: Pair, buf: StepBuffers, x, field_off, field_tag, tag_bits, step, lr, eps, grad_seed,
-                     is_prepopulated, tracked, rng_seed=0):
+                     is_prepopulated, tracked, rng_seed=0, id_bits=None):
     """One full-size forward+backward on the GPU; the checker does the integer work in full (tag, dedup)
     and the row work on the tracked subset of distinct keys: insert flags, gathered rows, expanded rows,
     exact integer-valued reduced gradients, updated rows."""
@@ -142,7 +145,7 @@ def run_step_sampled(pair: Pair, buf: StepBuffers, x, field_off, field_tag, tag_
     pair.orc.prepopulate(skeys[pre])
     # ---- HIP path, forward
     dx, doff, dtag = dev_keys(x), torch.from_numpy(field_off).cuda(), torch.from_numpy(field_tag).cuda()
-    forward(pair.gpu, buf, dx, doff, dtag, tag_bits, step)
+    forward(pair.gpu, buf, dx, doff, dtag, tag_bits, step, id_bits=id_bits)
     assert int(buf.n_unique.item()) == U and int(buf.err_count.item()) == oerr
     assert np.array_equal(host_keys(buf.uniq[:U]), ouniq), "unique keys"
     assert np.array_equal(buf.inverse[:n].cpu().numpy(), oinv), "inverse"
@@ -178,3 +181,26 @@ def run_step_sampled(pair: Pair, buf: StepBuffers, x, field_off, field_tag, tag_
     pair.gpu.gather(buf.row_idx[dpick].contiguous(), None, len(pick), rows_after)
     assert close_rows(rows_after.float().cpu().numpy(), pair.orc.lookup(skeys).astype(np.float64), lr, pair.rtol), "updated rows"
     return n, U, int(ins.sum())
+
+
+def check_reduce_normal_sampled(buf: StepBuffers, okey: np.ndarray, dim: int, dtype: int, tracked, seed: int) -> int:
+    """Full-size gradient reduction of N(0,1) gradients (rounded to bf16 for bf16 tables) over the segments that
+    buf.seg_of / buf.perm describe, compared on the tracked distinct keys with the checker's fp64 sums in input
+    order, within the bound for reductions (1e-5 of |sum| plus 1e-5 of the sum of |addends|).  Returns the number
+    of segments compared.  The gradient matrix is drawn on the device (an input, not part of the method)."""
+    n = len(okey)
+    gen = torch.Generator(device="cuda").manual_seed(seed)
+    G = torch.randn((n, dim), generator=gen, device="cuda", dtype=torch.float32)
+    if dtype != B.F32:
+        G = G.to(torch.bfloat16)
+    B.grad_segment_reduce(G, dtype, buf.seg_of, buf.perm, n, dim, buf.reduced, buf.reduce_ws)
+    U = int(buf.n_unique.item())
+    pos = np.flatnonzero(tracked(okey))
+    skeys, sinv = np.unique(okey[pos], return_inverse=True)
+    sidx = np.searchsorted(host_keys(buf.uniq[:U]), skeys)
+    Gs = G[torch.from_numpy(pos).cuda()].float().cpu().numpy()
+    ref = oracle.segment_reduce(Gs, sinv.astype(np.int32), len(skeys))
+    sabs = oracle.segment_reduce(np.abs(Gs), sinv.astype(np.int32), len(skeys)).astype(np.float64)
+    got = buf.reduced[torch.from_numpy(sidx).cuda()].cpu().numpy()
+    assert close_reduce(got, ref.astype(np.float64), sabs, RTOL_F32), "reduced N(0,1) gradients (tracked segments)"
+    return len(skeys)

@@ -70,7 +70,8 @@ def test_config1_tiny_full_size(one_record_update):
         b = w.next_step(step)
         x, off, tags, _ = merged_inputs(w.features, b.ids, merged, 0)
         G = _grads(w, step, len(x), 32, 0, 0)
-        n, U = run_step(pair, buf, x, off, tags, tag_bits, step, G, w.lr, w.eps, one_record_update=one_record_update)
+        n, U = run_step(pair, buf, x, off, tags, tag_bits, step, G, w.lr, w.eps, one_record_update=one_record_update,
+                        id_bits=w.id_bits, two_call=(step % 7 == 3))
         live = pair.compare_tables(w.lr)
         assert live == len(pair.orc)
     st = pair.gpu.stats()
@@ -91,7 +92,7 @@ def test_config3_table_merging_scaled():
             x, off, tags, sel = merged_inputs(w.features, b.ids, merged, g)
             assert len(sel) > 0
             G = _grads(w, step, len(x), sig[g][0], sig[g][1], g)
-            run_step(pairs[g], bufs[g], x, off, tags, tag_bits, step, G, w.lr, w.eps)
+            run_step(pairs[g], bufs[g], x, off, tags, tag_bits, step, G, w.lr, w.eps, id_bits=w.id_bits)
     for p in pairs:
         p.compare_tables(w.lr)
         # keys of different logical tables never collide: the tag is part of the key
@@ -115,7 +116,7 @@ def test_config2_prepopulated_scaled():
         b = w.next_step(step - 1)
         x, off, tags, _ = merged_inputs(w.features, b.ids, merged, 0)
         G = _grads(w, step, len(x), 64, 0, 0)
-        n, U = run_step(pair, buf, x, off, tags, tag_bits, step, G, w.lr, w.eps, prepopulated_keys=lazy)
+        n, U = run_step(pair, buf, x, off, tags, tag_bits, step, G, w.lr, w.eps, prepopulated_keys=lazy, id_bits=w.id_bits)
         assert int(buf.inserted[:U].sum().item()) == 0                # nothing is new in this configuration
     # touched keys agree in full; untouched pre-populated rows are a pure function of their key
     ok, ov, oa, ol, of = pair.orc.export()
@@ -146,7 +147,8 @@ def test_config4_insert_delete_stress_1000_steps_scaled(one_record_update):
         b = w.next_step(step)
         x, off, tags, _ = merged_inputs(w.features, b.ids, merged, 0)
         G = _grads(w, step, len(x), 64, 0, 0)
-        n, U = run_step(pair, buf, x, off, tags, tag_bits, step, G, w.lr, w.eps, one_record_update=one_record_update)
+        n, U = run_step(pair, buf, x, off, tags, tag_bits, step, G, w.lr, w.eps, one_record_update=one_record_update,
+                        id_bits=w.id_bits, two_call=(step % 7 == 3))
         if (step + 1) % w.evict_every == 0:
             ev, n_ev = pair.gpu.evict(step, w.ttl, w.min_freq, w.grace)
             oev = pair.orc.evict(step, w.ttl, w.min_freq, w.grace)
@@ -182,7 +184,7 @@ def test_config5_bf16_scaled(one_record_update):
         b = w.next_step(step - 1)
         x, off, tags, _ = merged_inputs(w.features, b.ids, merged, 0)
         G = _grads(w, step, len(x), 128, 1, 0)
-        n, U = run_step(pair, buf, x, off, tags, tag_bits, step, G, w.lr, w.eps, prepopulated_keys=lazy,
+        n, U = run_step(pair, buf, x, off, tags, tag_bits, step, G, w.lr, w.eps, prepopulated_keys=lazy, id_bits=w.id_bits,
                         one_record_update=one_record_update)
         new_total += int(buf.inserted[:U].sum().item())
     assert new_total > 0                                            # ~5 % of each step's keys are new
@@ -233,7 +235,8 @@ def test_random_shapes_whole_steps(seed):
         G = normal_grads(77 + seed, step, len(x), dim)
         if dtype == 1:
             G = torch.from_numpy(G).to(torch.bfloat16).float().numpy()
-        run_step(pair, buf, x, off, tags, tag_bits, step, G, lr, eps, one_record_update=one_record)
+        run_step(pair, buf, x, off, tags, tag_bits, step, G, lr, eps, one_record_update=one_record,
+                 id_bits=[None, 40, 20][seed % 3], two_call=(seed % 4 == 3))
         pair.compare_tables(lr)
         if step == 2:
             ev, n_ev = pair.gpu.evict(step, 1, 2, 0)

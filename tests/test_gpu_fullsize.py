@@ -17,7 +17,7 @@ pytestmark = pytest.mark.gpu
 if torch.cuda.is_available():
     from paper_2505_12663_amd import binding as B
     from paper_2505_12663_amd import EmbeddingTable, StepBuffers
-    from harness import Pair, run_step_sampled, tracked_subset, dev_keys, host_keys
+    from harness import Pair, run_step_sampled, tracked_subset, dev_keys, host_keys, check_reduce_normal_sampled
 
 
 def _bulk_load(pair, w, tag_bits, slice_n=1 << 23):
@@ -76,9 +76,15 @@ def test_config2_full_size_two_steps():
     for step in (1, 2):
         b = w.next_step(step - 1)
         x, off, tags, _ = merged_inputs(w.features, b.ids, merged, 0)
-        n, U, n_new = run_step_sampled(pair, buf, x, off, tags, tag_bits, step, w.lr, w.eps, 11 + step, is_pre, tracked)
+        n, U, n_new = run_step_sampled(pair, buf, x, off, tags, tag_bits, step, w.lr, w.eps, 11 + step, is_pre, tracked,
+                                       id_bits=w.id_bits)
         print(f"  step {step}: N={n} U={U} new={n_new}", flush=True)
         assert n_new == 0 and 0.15 < U / n < 0.35
+    # the same segments with N(0,1) gradients: fp32 sums in the kernel's fixed order against fp64 sums in input order
+    okey, _ = oracle.tag_keys(x, off, tags, tag_bits)
+    n_seg = check_reduce_normal_sampled(buf, okey, 64, 0, tracked, 99)
+    print(f"  N(0,1) reduce: {n_seg} tracked segments within 1e-5", flush=True)
+    assert n_seg > 3000
     st = pair.gpu.stats()
     assert st["live"] == 50_000_000 and st["status"] == 0 and st["n_rehash"] == 0
     pair.gpu.close()
@@ -143,7 +149,7 @@ def test_config3_full_size_merged_tables():
             x, off, tags, sel = merged_inputs(w.features, b.ids, merged, g)
             assert len(x) <= bufs[g].n_max
             n, U, n_new = run_step_sampled(pairs[g], bufs[g], x, off, tags, 8, step, w.lr, w.eps, 5 + g, nobody,
-                                           tracked)
+                                           tracked, id_bits=w.id_bits)
             tot += n
         print(f"  step {step}: total IDs {tot}", flush=True)
         assert 3_000_000 < tot < 5_500_000
@@ -179,7 +185,8 @@ def test_config4_full_batch_insert_evict_rehash():
         okey, _ = oracle.tag_keys(x, off, tags, tag_bits)
         refused_before, rehash_before = pair.gpu._refused_seen, pair.gpu.stats()["n_rehash"]
         pair.gpu.peak_load = 0.0
-        forward(pair.gpu, buf, dev_keys(x), torch.from_numpy(off).cuda(), torch.from_numpy(tags).cuda(), tag_bits, step)
+        forward(pair.gpu, buf, dev_keys(x), torch.from_numpy(off).cuda(), torch.from_numpy(tags).cuda(), tag_bits, step,
+                id_bits=w.id_bits)
         U = int(buf.n_unique.item())
         if pair.gpu._refused_seen > refused_before:
             lf_at_refusal.append(pair.gpu.peak_load)       # what the counters showed when keys were turned away
@@ -274,8 +281,11 @@ def test_config5_full_size_bf16_400m_keys():
     b = w.next_step(0)
     x, off, tags, _ = merged_inputs(w.features, b.ids, merged, 0)
     n, U, n_new = run_step_sampled(pair, buf, x, off, tags, tag_bits, 1, w.lr, w.eps, 3, is_pre,
-                                   tracked_subset(_hot_keys(w, tag_bits)))
+                                   tracked_subset(_hot_keys(w, tag_bits)), id_bits=w.id_bits)
     print(f"  step 1: N={n} U={U} new={n_new}", flush=True)
+    okey, _ = oracle.tag_keys(x, off, tags, tag_bits)
+    n_seg = check_reduce_normal_sampled(buf, okey, 128, 1, tracked_subset(_hot_keys(w, tag_bits)), 98)   # bf16 N(0,1) gradients
+    print(f"  N(0,1) bf16 reduce: {n_seg} tracked segments within 1e-5", flush=True)
     st = pair.gpu.stats()
     assert n == 2048 * 2048 * 4 and 0.02 < n_new / U < 0.09          # ~5 % of the distinct keys are new
     assert st["live"] == 400_000_000 + n_new and st["status"] == 0

@@ -98,6 +98,93 @@ def test_dedup_matches_checker(case):
         assert (np.diff(perm)[same] > 0).all()
 
 
+# ------------------------------------------------------------------------------------------ tag + dedup in one call
+@pytest.mark.parametrize("case", ["config2_like", "one_field", "empty", "one", "shared_and_unordered_tags", "empty_fields",
+                                  "id_bits_exceeded", "all_equal", "all_distinct", "narrow_ids_wide_tags", "many_fields",
+                                  "two_call_form"])
+def test_tag_dedup_matches_tag_then_dedup(case):
+    """emb_tag_dedup against the checker's tag (Eq. 8) followed by its sort-based dedup: tagged keys, error count,
+    distinct keys, inverse, counts bit-exact; perm / seg_off / seg_of by what is unique about them."""
+    rng = np.random.default_rng(5)
+    tag_bits, id_bits = 4, 40
+    if case == "config2_like":          # 8 fields, one identifier each, several tiles and a ragged tail
+        lens, tags = [4096 * 3 + 11] * 8, list(range(8))
+        xs = [_zipf_keys(l, 20_000, 10 + f) for f, l in enumerate(lens)]
+    elif case == "one_field":
+        lens, tags, tag_bits = [70_001], [0], 0
+        xs = [_zipf_keys(lens[0], 9000, 3)]
+    elif case == "empty":
+        lens, tags, xs = [0, 0], [1, 2], [np.zeros(0, np.uint64)] * 2
+    elif case == "one":
+        lens, tags, xs = [0, 1], [3, 2], [np.zeros(0, np.uint64), np.array([77], np.uint64)]
+    elif case == "shared_and_unordered_tags":   # two fields feed identifier 5; identifiers not in field order
+        lens, tags = [5000, 3000, 7000, 100, 6000], [5, 2, 9, 5, 0]
+        xs = [_zipf_keys(l, 800, 20 + f) for f, l in enumerate(lens)]       # the same IDs under several identifiers
+        xs[3] = xs[0][:100].copy()
+    elif case == "empty_fields":
+        lens, tags = [0, 4097, 0, 0, 5], [1, 2, 3, 4, 15]
+        xs = [_zipf_keys(l, 500, 30 + f) if l else np.zeros(0, np.uint64) for f, l in enumerate(lens)]
+    elif case == "id_bits_exceeded":    # IDs beyond the declared width are counted and wrapped
+        lens, tags, id_bits = [9000, 9000], [0, 1], 12
+        xs = [rng.integers(0, 1 << 14, size=l, dtype=np.uint64) for l in lens]
+    elif case == "all_equal":
+        lens, tags = [6000, 6000], [1, 1]
+        xs = [np.full(l, 123456789, np.uint64) for l in lens]
+    elif case == "all_distinct":
+        lens, tags = [10_001], [7]
+        xs = [rng.permutation(np.arange(10_001, dtype=np.uint64) * np.uint64(48271)) & np.uint64((1 << 40) - 1)]
+    elif case == "narrow_ids_wide_tags":      # the identifier spans more than one radix pass
+        lens, tags, tag_bits, id_bits = [3000] * 6, [0, 255, 4097, 65535, 300, 255], 16, 5
+        xs = [rng.integers(0, 32, size=l, dtype=np.uint64) for l in lens]
+    elif case == "many_fields":
+        nf = 700
+        lens, tags, tag_bits = list(rng.integers(0, 60, size=nf)), list(rng.integers(0, 200, size=nf)), 8
+        xs = [rng.integers(0, 50, size=int(l), dtype=np.uint64) for l in lens]
+    else:                                # records of ID and position do not fit 64 bits: tag, then dedup, inside the call
+        lens, tags, id_bits = [20_000, 20_000], [0, 3], 59
+        xs = [rng.integers(0, 1 << 59, size=l, dtype=np.uint64) for l in lens]
+        xs[1][:5000] = xs[0][:5000]
+    if case == "narrow_ids_wide_tags":
+        tags = [t & 0xFF for t in tags]  # identifiers are bytes at this boundary
+    x = np.concatenate(xs) if sum(lens) else np.zeros(0, np.uint64)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    tg = np.array(tags, dtype=np.uint8)
+    n = len(x)
+    wrapped = x & np.uint64((1 << id_bits) - 1)
+    okey, oerr = oracle.tag_keys(wrapped, off, tg, tag_bits)
+    oerr += int((x != wrapped).sum())
+    ou, oi, oc = oracle.dedup(okey)
+    U = len(ou)
+    m = max(n, 1)
+    key = torch.full((m,), -1, dtype=torch.int64, device="cuda")
+    uniq = torch.full((m,), -1, dtype=torch.int64, device="cuda")
+    inverse, counts, perm, seg_of = (torch.full((m,), -7, dtype=torch.int32, device="cuda") for _ in range(4))
+    seg_off = torch.full((m + 1,), -7, dtype=torch.int32, device="cuda")
+    n_unique = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    err = torch.full((1,), 99, dtype=torch.int64, device="cuda")
+    ws = torch.empty(B.emb_tag_dedup_workspace_bytes(n, len(tags), tag_bits, id_bits), dtype=torch.uint8, device="cuda")
+    dx = dev_keys(x) if n else torch.empty(0, dtype=torch.int64, device="cuda")
+    B.emb_tag_dedup(dx, torch.from_numpy(off).cuda(), torch.from_numpy(tg).cuda(), tag_bits, id_bits, key, uniq, inverse,
+                    counts, perm, seg_off, seg_of, n_unique, err, ws)
+    assert int(n_unique.item()) == U and int(err.item()) == oerr
+    assert np.array_equal(host_keys(key[:n]), okey), "tagged keys"
+    assert np.array_equal(host_keys(uniq[:U]), ou) and np.array_equal(inverse[:n].cpu().numpy(), oi)
+    assert np.array_equal(counts[:U].cpu().numpy(), oc)
+    so, pm, sf = seg_off[:U + 1].cpu().numpy(), perm[:n].cpu().numpy(), seg_of[:n].cpu().numpy()
+    assert so[0] == 0
+    if n:
+        assert so[-1] == n and np.array_equal(np.diff(so), oc)
+        assert np.array_equal(pm, np.argsort(okey, kind="stable"))       # positions by (key, position)
+        assert np.array_equal(sf, oi[pm])
+    # without the optional outputs
+    uniq2 = torch.full((m,), -1, dtype=torch.int64, device="cuda")
+    B.emb_tag_dedup(dx, torch.from_numpy(off).cuda(), torch.from_numpy(tg).cuda(), tag_bits, id_bits, None, uniq2, None,
+                    None, perm, None, seg_of, n_unique, err, ws)
+    assert int(n_unique.item()) == U and torch.equal(uniq2[:U], uniq[:U])
+    if n:
+        assert np.array_equal(perm[:n].cpu().numpy(), pm) and np.array_equal(seg_of[:n].cpu().numpy(), sf)
+
+
 # ------------------------------------------------------------------------------------------ table
 @pytest.mark.parametrize("dim,dtype", [(32, 0), (64, 0), (16, 0), (128, 0), (128, 1), (8, 1), (256, 0), (4, 0), (24, 0), (256, 1), (40, 1)])
 def test_find_or_insert_gather_roundtrip(dim, dtype):
