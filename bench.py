@@ -196,8 +196,9 @@ def main() -> int:
     live_after = st_after["live"]
     next_step = args.warmup + args.steps
 
-    phase_ms = {p: float(np.mean([events[k][i].elapsed_time(events[k][i + 1]) for k in range(args.steps)]))
-                for i, p in enumerate(phases)}
+    per_step = {p: [events[k][i].elapsed_time(events[k][i + 1]) for k in range(args.steps)] for i, p in enumerate(phases)}
+    phase_ms = {p: float(np.mean(v)) for p, v in per_step.items()}
+    step_ms = [events[k][0].elapsed_time(events[k][len(phases)]) for k in range(args.steps)]
     # U of the timed batches (read back outside the timed region)
     u_of = {}
     for s in sorted({(args.warmup + k) % len(batches) for k in range(args.steps)}):
@@ -252,9 +253,17 @@ def main() -> int:
         "roofline": roofline,
     }
     if st_after["n_rehash"] or st_after["refused"]:
-        result["config"]["rehashes_in_run"] = st_after["n_rehash"]
-        result["config"]["keys_turned_away_at_the_limit"] = st_after["refused"]
-        result["config"]["capacity_log2_after"] = int(np.log2(st_after["capacity"]))
+        # the table crossed its load-factor limit inside the timed region: the step that expands the key structure
+        # is in ms_per_step (and in the mean phase times); the medians show the ordinary step
+        slow = int(np.argmax(step_ms))
+        result["capacity_expansion"] = {
+            "rehashes_in_run": st_after["n_rehash"], "keys_turned_away_at_the_limit": st_after["refused"],
+            "capacity_log2_after": int(np.log2(st_after["capacity"])),
+            "slowest_step_ms": round(step_ms[slow], 3), "slowest_step_find_or_insert_ms": round(per_step["find_or_insert"][slow], 3),
+            "median_step_ms": round(float(np.median(step_ms)), 4),
+            "phase_ms_median": {p: round(float(np.median(v)), 4) for p, v in per_step.items()},
+            "note": "find_or_insert of the slowest step includes reading the counters back, the key-only rehash into a "
+                    "structure of twice the size and the second attempt for the keys that had been turned away"}
 
     # ---- the step spelled with the calls the problem statement names, as an extra line: emb_tag_keys + emb_dedup,
     # ht_find_or_insert (touches every row record), ht_gather, emb_expand by `inverse`, grad_segment_reduce,
@@ -496,6 +505,32 @@ def probe_counts(B, table, batches, buf, tag_bits, id_bits, dim, dtype, cap_log2
         "keys": k, "lines_per_key": round(d(s2, s3, "probes") / max(d(s2, s3, "lookups"), 1), 4),
         "distinct_lines_per_key_histogram_1_to_8plus": [b - a for a, b in zip(s2["probe_hist"], s3["probe_hist"])]}
     t2.close()
+    # the same at the stress configuration's load-factor limit: a table filled to floor(0.85 * 2^22) slots
+    t3 = EmbeddingTable(dim, dtype, capacity_log2=22, chunk_rows_log2=22, max_load_factor=0.85, count_probes=True,
+                        initial_chunks=1)
+    k3 = int(np.float32(0.85) * (1 << 22))
+    keys3 = keys[:k3].contiguous()
+    rows3 = torch.empty(k3, dtype=torch.int32, device=dev)
+    a0 = t3.stats()
+    t3.find_or_insert(keys3, None, k3, 1, rows3)
+    a1 = t3.stats()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    B.ht_find(t3.h, keys3, None, k3, rows3)
+    e1.record()
+    a2 = t3.stats()
+    B.ht_find(t3.h, miss[:k3].contiguous(), None, k3, rows3)
+    a3 = t3.stats()
+    out["at_load_0.85"] = {
+        "keys": k3, "load_factor": round((a1["live"] + a1["tombstones"]) / a1["capacity"], 4), "turned_away": a1["refused"],
+        "insert_lines_per_key": round(d(a0, a1, "probes") / max(d(a0, a1, "lookups"), 1), 4),
+        "insert_cas_attempts": d(a0, a1, "cas_attempts"), "insert_cas_failures": d(a0, a1, "cas_failures"),
+        "hit_lines_per_key": round(d(a1, a2, "probes") / max(d(a1, a2, "lookups"), 1), 4),
+        "hit_distinct_lines_histogram_1_to_8plus": [b - a for a, b in zip(a1["probe_hist"], a2["probe_hist"])],
+        "hit_lookup_ms": round(e0.elapsed_time(e1), 4),
+        "miss_lines_per_key": round(d(a2, a3, "probes") / max(d(a2, a3, "lookups"), 1), 4),
+        "miss_distinct_lines_histogram_1_to_8plus": [b - a for a, b in zip(a2["probe_hist"], a3["probe_hist"])]}
+    t3.close()
     stb = table.stats()
     out["benchmark_table"] = {"load_factor": round((stb["live"] + stb["tombstones"]) / stb["capacity"], 4),
                               "distinct_keys_looked_up_per_step": u,
@@ -527,9 +562,18 @@ def ceiling_probes(B, timed, dev) -> dict:
     out["random_row_read_sequential_write_gbps"] = round((2 * nbytes + 4 * rows) / (ms * 1e-3) / 1e9, 1)
     ms = timed(lambda: B.emb_expand_sorted(src, quarter, rnd, rows, dim, 0, dst))
     out["quarter_read_random_row_write_gbps"] = round((nbytes // 4 + nbytes + 8 * rows) / (ms * 1e-3) / 1e9, 1)
-    out["note"] = ("row movers of this library on synthetic indices: identity (streaming copy), a random permutation as "
-                   "source index (the gather's shape), one source row per four positions with a random destination "
-                   "permutation (the sorted expand's shape)")
+    # reads only: the segment reduction over one giant segment (every row is read once, one row is written)
+    zeros = torch.zeros(rows, dtype=torch.int32, device=dev)
+    red = torch.empty((1, dim), dtype=torch.float32, device=dev)
+    rws = torch.empty(B.grad_segment_reduce_workspace_bytes(rows, dim), dtype=torch.uint8, device=dev)
+    ms = timed(lambda: B.grad_segment_reduce(src, 0, zeros, ident, rows, dim, red, rws))
+    out["row_read_sequential_gbps"] = round((nbytes + 8 * rows) / (ms * 1e-3) / 1e9, 1)
+    ms = timed(lambda: B.grad_segment_reduce(src, 0, zeros, rnd, rows, dim, red, rws))
+    out["row_read_random_gbps"] = round((nbytes + 8 * rows) / (ms * 1e-3) / 1e9, 1)
+    out["note"] = ("kernels of this library on synthetic indices: row mover with identity index (streaming copy), with a "
+                   "random permutation as source index (the gather's shape), with one source row per four positions and a "
+                   "random destination permutation (the sorted expand's shape); segment reduction of all rows into one "
+                   "segment in sequential and in random row order (the reduce's shape: reads only)")
     return out
 
 

@@ -104,6 +104,17 @@ __global__ void k_zero64(unsigned long long* p) {
     if (threadIdx.x == 0 && blockIdx.x == 0) *p = 0ull;
 }
 
+// Tile handled by a block: workgroups are handed to the 8 XCDs (each with its own L2) in turn; giving every XCD
+// a contiguous range of tiles lets its L2 merge the partial-sector accesses that neighbouring tiles make to the
+// rows of tile_hist and to the ends of their digit runs in the scatter's output.  The grid is
+// 8 * ceil(n_tiles / 8) blocks; a block whose tile does not exist leaves at once.
+constexpr unsigned kXcds = 8;
+__device__ inline unsigned tile_of_block(unsigned n_tiles) {
+    const unsigned per = (n_tiles + kXcds - 1) / kXcds;
+    return (blockIdx.x % kXcds) * per + blockIdx.x / kXcds;
+}
+inline unsigned xcd_grid(unsigned n_tiles) { return kXcds * ((n_tiles + kXcds - 1) / kXcds); }
+
 // ---------------------------------------------------------------------------- which digits vary
 __device__ inline unsigned digit_of(uint64_t k, int pass) { return (unsigned)(k >> (8 * pass)) & 0xFFu; }
 
@@ -130,11 +141,13 @@ __global__ __launch_bounds__(kThreads) void k_dd_masks(const uint64_t* __restric
                                                       unsigned* __restrict__ tile_hist) {
     __shared__ unsigned long long s_o[kWaves], s_a[kWaves];
     __shared__ unsigned s_hist[kRadix];
+    const unsigned tile = tile_of_block(n_tiles);
+    if (tile >= n_tiles) return;
     s_hist[threadIdx.x] = 0u;
     __syncthreads();
     const int lane = lane_id();
     uint64_t o = 0ull, a = ~0ull;
-    const int64_t base = (int64_t)blockIdx.x * kTile + (threadIdx.x / kWave) * (kWave * kItems) + lane;
+    const int64_t base = (int64_t)tile * kTile + (threadIdx.x / kWave) * (kWave * kItems) + lane;
     unsigned d[kItems];
 #pragma unroll
     for (int it = 0; it < kItems; ++it) {
@@ -158,14 +171,14 @@ __global__ __launch_bounds__(kThreads) void k_dd_masks(const uint64_t* __restric
         s_a[threadIdx.x / kWave] = a;
     }
     __syncthreads();
-    tile_hist[(size_t)threadIdx.x * n_tiles + blockIdx.x] = s_hist[threadIdx.x];
+    tile_hist[(size_t)threadIdx.x * n_tiles + tile] = s_hist[threadIdx.x];
     if (threadIdx.x == 0) {
         for (int w = 1; w < kWaves; ++w) {
             o |= s_o[w];
             a &= s_a[w];
         }
-        partial[2 * blockIdx.x] = o;
-        partial[2 * blockIdx.x + 1] = a;
+        partial[2 * tile] = o;
+        partial[2 * tile + 1] = a;
     }
 }
 
@@ -215,10 +228,12 @@ __global__ __launch_bounds__(kThreads) void k_rs_hist(DdBuffers b, const DdHeade
                                                      unsigned n_tiles, unsigned* __restrict__ tile_hist) {
     if (!h->active[pass]) return;
     __shared__ unsigned s_hist[kRadix];
+    const unsigned tile = tile_of_block(n_tiles);
+    if (tile >= n_tiles) return;
     s_hist[threadIdx.x] = 0u;
     __syncthreads();
     const uint64_t* keys = sel_keys(b, h->src[pass]);
-    const int64_t base = (int64_t)blockIdx.x * kTile + (threadIdx.x / kWave) * (kWave * kItems) + (threadIdx.x % kWave);
+    const int64_t base = (int64_t)tile * kTile + (threadIdx.x / kWave) * (kWave * kItems) + (threadIdx.x % kWave);
     const int lane = lane_id();
     unsigned d[kItems];
 #pragma unroll
@@ -229,7 +244,7 @@ __global__ __launch_bounds__(kThreads) void k_rs_hist(DdBuffers b, const DdHeade
 #pragma unroll
     for (int it = 0; it < kItems; ++it) hist_add_runs(s_hist, d[it], lane);
     __syncthreads();
-    tile_hist[(size_t)threadIdx.x * n_tiles + blockIdx.x] = s_hist[threadIdx.x];
+    tile_hist[(size_t)threadIdx.x * n_tiles + tile] = s_hist[threadIdx.x];
 }
 
 // block d: exclusive scan of digit d's counts over the tiles; total -> digit_total[d].
@@ -286,8 +301,10 @@ __global__ __launch_bounds__(kScThreads) void k_rs_scatter(DdBuffers b, const Dd
     uint64_t* out_k = dst == 1 ? b.ka : b.kb;
     uint32_t* out_i = dst == 1 ? b.ia : b.ib;
 
+    const unsigned tile = tile_of_block(n_tiles);
+    if (tile >= n_tiles) return;
     const int lane = lane_id(), wave = threadIdx.x / kWave;
-    const int64_t tile_base = (int64_t)blockIdx.x * kTile;
+    const int64_t tile_base = (int64_t)tile * kTile;
     const int tile_n = (int)((n - tile_base) < kTile ? (n - tile_base) : kTile);
     for (int i = threadIdx.x; i < kScWaves * kRadix; i += kScThreads) s_cnt[0][i] = 0u;
     __syncthreads();
@@ -353,7 +370,7 @@ __global__ __launch_bounds__(kScThreads) void k_rs_scatter(DdBuffers b, const Dd
         const unsigned start = off_t + incl_t - run;
         const unsigned gbase = off_g + incl_g - tot_g;
         s_start[d] = start;
-        s_delta[d] = gbase + tile_hist[(size_t)d * n_tiles + blockIdx.x] - start;
+        s_delta[d] = gbase + tile_hist[(size_t)d * n_tiles + tile] - start;
     }
     __syncthreads();
     // position of every key in the sorted tile, taken before the tile overwrites the counters
@@ -612,14 +629,14 @@ int emb_dedup(const uint64_t* key, int64_t n, uint64_t* uniq, int32_t* inverse, 
     const unsigned n_tiles = L.n_tiles;
 
     unsigned long long* masks = reinterpret_cast<unsigned long long*>(w + L.masks);
-    hipLaunchKernelGGL(k_dd_masks, dim3(n_tiles), dim3(kThreads), 0, s, key, n, n_tiles, masks, tile_hist);
+    hipLaunchKernelGGL(k_dd_masks, dim3(xcd_grid(n_tiles)), dim3(kThreads), 0, s, key, n, n_tiles, masks, tile_hist);
     hipLaunchKernelGGL(k_dd_plan, dim3(1), dim3(kThreads), 0, s, hdr, masks, (int)n_tiles);
     MTGR_LAUNCH_CHECK();
     for (int p = 0; p < kPasses; ++p) {
         if (p > 0) // the lowest digit's histogram came with the mask reduction
-            hipLaunchKernelGGL(k_rs_hist, dim3(n_tiles), dim3(kThreads), 0, s, b, hdr, p, n, n_tiles, tile_hist);
+            hipLaunchKernelGGL(k_rs_hist, dim3(xcd_grid(n_tiles)), dim3(kThreads), 0, s, b, hdr, p, n, n_tiles, tile_hist);
         hipLaunchKernelGGL(k_rs_scan, dim3(kRadix), dim3(kThreads), 0, s, hdr, p, n_tiles, tile_hist, digit_total);
-        hipLaunchKernelGGL(k_rs_scatter, dim3(n_tiles), dim3(kScThreads), 0, s, b, hdr, p, n, n_tiles, tile_hist, digit_total);
+        hipLaunchKernelGGL(k_rs_scatter, dim3(xcd_grid(n_tiles)), dim3(kScThreads), 0, s, b, hdr, p, n, n_tiles, tile_hist, digit_total);
         MTGR_LAUNCH_CHECK();
     }
     hipLaunchKernelGGL(k_heads_count, dim3(n_tiles), dim3(kThreads), 0, s, b, hdr, n, tile_heads);
