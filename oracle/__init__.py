@@ -21,10 +21,16 @@ _lib = None
 
 
 def build(force: bool = False) -> str:
-    """Compile oracle.cpp with the host compiler (plain -O2, one thread)."""
+    """Compile oracle.cpp with the host compiler (plain -O2, one thread).
+    ORACLE_SANITIZE=1 in the environment builds and loads an AddressSanitizer + UBSan variant instead
+    (run the tests with libasan preloaded: LD_PRELOAD=$(g++ -print-file-name=libasan.so):$LD_PRELOAD)."""
+    global _LIB
+    flags = ["-O2"]
+    if os.environ.get("ORACLE_SANITIZE"):
+        _LIB = os.path.join(_HERE, "liboracle_san.so")
+        flags = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"]
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
-                               "-o", _LIB, _SRC])
+        subprocess.check_call(["g++", *flags, "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off", "-o", _LIB, _SRC])
     return _LIB
 
 

@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <cstddef>
 
 #include "mtgr_emb.h"
 
@@ -40,16 +41,24 @@ enum StatSlot { kStatLookups = 0, kStatProbes, kStatCas, kStatCasFail, kStatAllo
                 kStatHist0 /* .. kStatHist0 + 7: keys that inspected 1, 2, .. 7, 8 or more slot lines */ };
 constexpr int kStatSlots = 16;
 struct HtHead {
+    // line 0: the row allocator
     unsigned int bump;       // rows handed out by the bump allocator
     int free_count;          // entries on the free-row stack (may dip below 0 inside an insert kernel)
     unsigned int status;     // EMB_DEV_* bits
     unsigned int hot_bump;   // rows handed out from the hot store
     int hot_free_count;      // entries on the hot store's free stack
+    unsigned int pad0;
+    unsigned long long pad1[13];
+    // line 1: admission.  Every block that brings new keys does one returning atomic here and one on `bump`;
+    // atomics on one 128-byte line queue up behind each other (about 25 ns apiece), so the two counters
+    // live on lines of their own.
     unsigned int occupied;   // slots that are not never-used (live + deleted): inserts are admitted against the load-factor limit here
-    unsigned long long refused; // new keys turned away so far (limit reached or out of rows)
-    unsigned long long pad1[12];
+    unsigned int pad2;
+    unsigned long long refused; // new keys turned away so far (limit reached, out of rows, probe sequence exhausted)
+    unsigned long long pad3[14];
     unsigned long long stat[kStatStripes][kStatSlots]; // [stripe][StatSlot]; live / deleted counts are the sums over stripes
 };
+static_assert(offsetof(HtHead, occupied) == 128 && offsetof(HtHead, stat) == 256, "counter lines");
 struct HtState {
     HtHead head;
     void* values[kMaxChunks];

@@ -78,7 +78,7 @@ constexpr long long kSlotAbsent = -3;    // read-only lookup, settled: the key i
 
 template <bool INSERT>
 __device__ inline long long probe_group(const HtView& v, uint64_t key, bool active, int lane, bool* created,
-                                        ProbeCounters* pc) {
+                                        ProbeCounters* pc, uint32_t* row_out = nullptr) {
     const int sub = lane & (kLineSlots - 1);
     const int gbase = lane & ~(kLineSlots - 1);
     const uint64_t h = slot_hash(key);
@@ -92,7 +92,16 @@ __device__ inline long long probe_group(const HtView& v, uint64_t key, bool acti
     while (__any(!done)) {
         Slot* sp = v.slots + line * kLineSlots + sub;
         uint64_t k = kEmptyKey;
-        if (!done) k = INSERT ? load_fresh(&sp->key) : sp->key;
+        uint32_t slot_row = kRowInvalid;
+        if (!done) {
+            if (INSERT) {
+                k = load_fresh(&sp->key);
+            } else {       // read-only: the whole slot in one load, so that a hit brings its row index along
+                const V16 e = ld16(sp);
+                k = ((uint64_t)e.y << 32) | e.x;
+                slot_row = e.z;
+            }
+        }
         const uint64_t m_hit = __ballot(!done && k == key);
         const uint64_t m_empty = __ballot(!done && k == kEmptyKey);
         const unsigned hit8 = (unsigned)(m_hit >> gbase) & 0xFFu;
@@ -103,6 +112,7 @@ __device__ inline long long probe_group(const HtView& v, uint64_t key, bool acti
             ++lines;
             if (hit8) {
                 result = (long long)(line * kLineSlots + (__ffs(hit8) - 1));
+                if (!INSERT && row_out) *row_out = __shfl(slot_row, gbase + (__ffs(hit8) - 1), kWave);
                 done = true;
             } else if (empty8 && !INSERT) {
                 done = true; // absent
@@ -144,17 +154,16 @@ __device__ inline long long probe_group(const HtView& v, uint64_t key, bool acti
     return result;
 }
 
-// First lines of the 8 keys of every group, all loads in flight at once: a key found there is
+// First lines of the 8 keys of every group, all loads in flight at once, read-only: a key found there is
 // settled without entering the line-by-line loop (at the load factors in use that is nearly all
-// present keys).  With INSERT, a key whose first line shows no match but a never-used slot is
-// claimed right here, again with the 8 attempts of a group in flight together.  The line was read
-// with ordinary loads and may be out of date, which is harmless: occupied slots never change, so
-// "no match among the occupied slots before the first empty one" stays true, and the CAS itself
-// decides whether that slot was still empty; if it went to another key the element simply takes the
-// line-by-line path.  found_slot stays -1 for unsettled elements.
-template <bool INSERT>
+// present keys).  A first line that shows no match but a never-used slot settles the key as absent;
+// *empty_slot then names the first such slot, which is where an insert will try its claim.  The line
+// is read with ordinary loads and may be out of date, which is harmless: occupied slots never change,
+// so "no match among the occupied slots before the first empty one" stays true, and the claim itself
+// (a compare-and-swap) decides whether that slot was still empty.  found_slot stays -1 for unsettled
+// elements (first line full without a match).
 __device__ inline void first_line_pass(const HtView& v, uint64_t my_key, bool my_ok, int lane, long long* found_slot,
-                                       uint32_t* found_row, bool* created, ProbeCounters* pc) {
+                                       uint32_t* found_row, long long* empty_slot, ProbeCounters* pc) {
     const int sub = lane & (kLineSlots - 1);
     const int gbase = lane & ~(kLineSlots - 1);
     uint64_t kr[kLineSlots];
@@ -168,9 +177,7 @@ __device__ inline void first_line_pass(const HtView& v, uint64_t my_key, bool my
     }
     *found_slot = -1;
     *found_row = kRowInvalid;
-    *created = false;
-    uint64_t cas_old[kLineSlots];
-    unsigned want_mask = 0; // bit r: this lane issued the claim for key r
+    *empty_slot = -1;
 #pragma unroll
     for (int r = 0; r < kLineSlots; ++r) {
         const bool ok = __shfl((int)my_ok, gbase + r, kWave) != 0;
@@ -184,41 +191,12 @@ __device__ inline void first_line_pass(const HtView& v, uint64_t my_key, bool my
             *found_row = row;
         }
         pc->probes += (sub == r && ok) ? 1u : 0u;
-        cas_old[r] = 0;
-        if (!INSERT) {
-            // read-only lookup: a never-used slot in the first line and no match means the key is absent
-            const uint64_t me = __ballot(ok && k == kEmptyKey);
-            const unsigned empty8 = (unsigned)(me >> gbase) & 0xFFu;
-            if (sub == r && !hit8 && empty8) *found_slot = kSlotAbsent;
-        }
-        if (INSERT) {
-            const uint64_t me = __ballot(ok && k == kEmptyKey);
-            const unsigned empty8 = (unsigned)(me >> gbase) & 0xFFu;
-            if (ok && !hit8 && empty8 && sub == (__ffs(empty8) - 1)) {
-                cas_old[r] = atomicCAS(&(v.slots + line[r] * kLineSlots + sub)->key, (unsigned long long)kEmptyKey,
-                                       (unsigned long long)kr[r]);
-                want_mask |= 1u << r;
-                pc->cas += 1;
-                if (cas_old[r] != kEmptyKey) pc->cas_fail += 1;
-            }
-        }
-    }
-    if (INSERT) {
-#pragma unroll
-        for (int r = 0; r < kLineSlots; ++r) {
-            // which lane of the group (if any) tried to claim a slot for key r, and what came back
-            const uint64_t mw = __ballot((want_mask >> r) & 1u);
-            const unsigned w8 = (unsigned)(mw >> gbase) & 0xFFu;
-            const int wl = w8 ? (__ffs(w8) - 1) : 0;
-            const uint64_t old = shfl64(cas_old[r], gbase + wl);
-            if (sub == r && w8) {
-                if (old == kEmptyKey) {
-                    *found_slot = (long long)(line[r] * kLineSlots + wl);
-                    *created = true;
-                } else if (old == kr[r]) {
-                    *found_slot = (long long)(line[r] * kLineSlots + wl); // a duplicate got there first
-                }
-            }
+        // a never-used slot in the first line and no match means the key is absent
+        const uint64_t me = __ballot(ok && k == kEmptyKey);
+        const unsigned empty8 = (unsigned)(me >> gbase) & 0xFFu;
+        if (sub == r && !hit8 && empty8) {
+            *found_slot = kSlotAbsent;
+            *empty_slot = (long long)(line[r] * kLineSlots + (__ffs(empty8) - 1));
         }
     }
 }
@@ -302,23 +280,24 @@ __global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const ui
 
     ProbeCounters pc{0u, 0u, 0u, 0u};
     unsigned key_lines = my_ok ? 1u : 0u;   // distinct slot lines of its probe sequence inspected for this lane's key
-    long long my_slot = -1;
+    long long my_slot = -1, my_empty = -1;
     uint32_t my_row = kRowInvalid;
     bool my_created = false;
     // ---- round 1: read-only lookup
     if (wave_on) {
         bool unused;
-        first_line_pass<false>(v, my_key, my_ok, lane, &my_slot, &my_row, &unused, &pc);
+        first_line_pass(v, my_key, my_ok, lane, &my_slot, &my_row, &my_empty, &pc);
         const bool need_slow = my_ok && my_slot == -1;   // first line full without a match
         if (__any(need_slow)) {
             for (int r = 0; r < kLineSlots; ++r) {
                 const bool act = __shfl((int)need_slow, gbase + r, kWave) != 0;
                 if (!__any(act)) continue;
                 const uint64_t k = shfl64(my_key, gbase + r);
-                const long long s = probe_group<false>(v, k, act, lane, &unused, &pc);
+                uint32_t row = kRowInvalid;
+                const long long s = probe_group<false>(v, k, act, lane, &unused, &pc, &row);
                 if (sub == r && act) {
                     my_slot = s == -1 ? kSlotAbsent : s;   // -2: every line visited, no match, no room
-                    my_row = kRowInvalid;
+                    my_row = row;
                     key_lines = pc.my_lines;        // the line-by-line walk starts over at the first line
                 }
             }
@@ -368,16 +347,27 @@ __global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const ui
     // ---- round 2: the admitted keys claim a slot (block-uniform branch: most blocks of a step bring no new key)
     if (s_admitted > 0) {
         if (wave_on && __any(claim)) {
-            long long slot2;
-            uint32_t row2;
-            bool created2;
-            first_line_pass<true>(v, my_key, claim, lane, &slot2, &row2, &created2, &pc);
-            if (claim) {
-                my_slot = slot2;
-                my_row = row2;
-                my_created = created2;
+            // a key whose first line showed a never-used slot tries that slot at once, every lane for itself: the
+            // compare-and-swap tells whether it was still free (claimed), holds the key by now (a duplicate in
+            // another wave was faster: found) or went to another key (then, as for keys whose first line was full,
+            // the line-by-line walk with fresh loads takes over)
+            bool need_slow = claim;
+            if (claim && my_empty >= 0) {
+                const uint64_t old = atomicCAS(&v.slots[my_empty].key, (unsigned long long)kEmptyKey, (unsigned long long)my_key);
+                pc.cas += 1;
+                if (old == kEmptyKey) {
+                    my_slot = my_empty;
+                    my_created = true;
+                    need_slow = false;
+                } else {
+                    pc.cas_fail += 1;
+                    if (old == my_key) {
+                        my_slot = my_empty;
+                        my_row = kRowInvalid;      // resolved below, or by k_touch if the creator has not published it yet
+                        need_slow = false;
+                    }
+                }
             }
-            const bool need_slow = claim && my_slot == -1;   // first line full, or it changed under us
             if (__any(need_slow)) {
                 for (int r = 0; r < kLineSlots; ++r) {
                     const bool act = __shfl((int)need_slow, gbase + r, kWave) != 0;
@@ -571,7 +561,8 @@ __global__ __launch_bounds__(kBlock) void k_find(HtView v, const uint64_t* __res
     long long my_slot;
     uint32_t my_row;
     bool unused_created;
-    first_line_pass<false>(v, my_key, my_ok, lane, &my_slot, &my_row, &unused_created, &pc);
+    long long unused_empty;
+    first_line_pass(v, my_key, my_ok, lane, &my_slot, &my_row, &unused_empty, &pc);
     const bool need_slow = my_ok && my_slot == -1;
     if (__any(need_slow)) {
         for (int r = 0; r < kLineSlots; ++r) {
@@ -579,10 +570,11 @@ __global__ __launch_bounds__(kBlock) void k_find(HtView v, const uint64_t* __res
             if (!__any(act)) continue;
             const uint64_t k = shfl64(my_key, gbase + r);
             bool created;
-            const long long s = probe_group<false>(v, k, act, lane, &created, &pc);
+            uint32_t row = kRowInvalid;
+            const long long s = probe_group<false>(v, k, act, lane, &created, &pc, &row);
             if (sub == r && act) {
                 my_slot = s;
-                my_row = s >= 0 ? v.slots[s].row : kRowInvalid;
+                my_row = row;
                 key_lines = pc.my_lines;
             }
         }
