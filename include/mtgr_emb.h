@@ -252,15 +252,19 @@ int ht_find_or_insert_retry(emb_table_t* t, const uint64_t* key, const int64_t* 
 /* Clear the given EMB_DEV_* bits of the device status word (asynchronously on `stream`). */
 int ht_clear_status(emb_table_t* t, uint32_t bits, void* stream);
 
-/* Read-only lookup: row_idx[i] = row of key[i], or -1 if absent. */
+/* Sec. 3.1 (hash lookup by cooperative probing, Theorem 1 for the probe sequence), read-only:
+ * row_idx[i] = row of key[i], or -1 if absent (static tables fall back to a default embedding there; here the
+ * caller decides: ht_gather turns -1 into a zero row). */
 int ht_find(emb_table_t* t, const uint64_t* key, const int64_t* n_dev, int64_t n_max, int32_t* row_idx,
             void* stream);
 
-/* out[u,:] = values[row_idx[u],:] in the table dtype, row-major [n, dim]; row -1 reads as zeros. */
+/* Sec. 3.1 "Table Lookup" (Eq. 7: the key structure yields the position of the row in the chunked embedding
+ * structure): out[u,:] = values[row_idx[u],:] in the table dtype, row-major [n, dim]; row -1 reads as zeros. */
 int ht_gather(emb_table_t* t, const int32_t* row_idx, const int64_t* n_dev, int64_t n_max, void* out,
               void* stream);
 
-/* out[i,:] = uniq_rows[inverse[i],:]  (undo the deduplication).  dtype: element type of both. */
+/* Sec. 3.3 (after the embeddings of the distinct IDs have come back, every position gets the row of its ID;
+ * Fig. 6): out[i,:] = uniq_rows[inverse[i],:].  dtype: element type of both. */
 int emb_expand(const void* uniq_rows, const int32_t* inverse, int64_t n, int dim, int dtype, void* out,
                void* stream);
 
@@ -273,7 +277,8 @@ int emb_expand_sorted(const void* uniq_rows, const int32_t* seg_of, const int32_
 
 /* ------------------------------------------------------------------ backward */
 
-/* reduced[u,:] = sum over positions i with inverse[i] == u of grad[i,:], fp32 accumulation,
+/* Sec. 2 "Backward Update" and App. C "Gradient Accumulation" (gradients of one ID are aggregated before the
+ * owner updates the row): reduced[u,:] = sum over positions i with inverse[i] == u of grad[i,:], fp32 accumulation,
  * fp32 output [*n_unique, dim].  grad [dev, n x dim] of grad_dtype, dim <= 256.  perm and seg_of as
  * written by emb_dedup for the same keys (the sum for u runs over grad[perm[j]] for the j with
  * seg_of[j] == u).  The order of additions is fixed, so results are reproducible run to run. */
@@ -281,7 +286,8 @@ size_t grad_segment_reduce_workspace_bytes(int64_t n, int dim);
 int grad_segment_reduce(const void* grad, int grad_dtype, const int32_t* seg_of, const int32_t* perm, int64_t n,
                         int dim, float* reduced, void* workspace, size_t workspace_bytes, void* stream);
 
-/* Row-wise Adagrad on the listed rows only:
+/* Sec. 2 "Backward Update", App. C (only the activated rows are updated; the benchmark fixes the sparse optimizer:
+ * row-wise Adagrad with one fp32 accumulator per row).  On the listed rows only:
  *   acc += mean_j(g_j^2);  w_j -= lr * g_j / (sqrt(acc) + eps).
  * row_idx [dev]: distinct rows (as returned for deduplicated keys); -1 entries are skipped.
  * reduced [dev, n x dim, f32]. */
@@ -329,7 +335,8 @@ int grad_segment_reduce_pooled(const float* d_pooled, const int64_t* bag_off, in
 
 /* ------------------------------------------------------------------ maintenance */
 
-/* Delete every key that was not touched for `ttl` steps (rule active when ttl > 0) or that was
+/* Sec. 3.1 (real-time deletion of entries; the embedding structure keeps timestamps as auxiliary data).
+ * Delete every key that was not touched for `ttl` steps (rule active when ttl > 0) or that was
  * touched fewer than `min_freq` times and not within the last `grace` steps (active when
  * min_freq > 0).  Slots become deleted markers, rows return to the free list.
  * evicted_keys [dev, evicted_cap, optional]: the deleted keys in no particular order (at most
