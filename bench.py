@@ -4,8 +4,9 @@
 A step = tag + dedup -> find-or-insert -> gather -> expand -> (upstream gradient already in HBM)
 -> gradient segment-reduce -> row-wise Adagrad over one batch of the long-sequence lookup
 configuration (batch 512, lengths U{256..4096}, 8 fields, dim 64 fp32, 50 M-key table, Zipf 1.05).
-Every output of the step is materialised (distinct keys, inverse, distinct rows, expanded rows, reduced
-gradients).  Inputs are resident in HBM when the timed region starts.  Prints ONE JSON line on stdout.
+Every output of the step is materialised (distinct keys, the mapping between positions and distinct keys in
+sorted order (perm, seg_of), distinct rows, expanded rows, reduced gradients).  Inputs are resident in HBM when
+the timed region starts.  Prints ONE JSON line on stdout.
 
     python bench.py [--gpus 1] [--steps 20] [--warmup 3] [--config 2] [--no-cpu-baseline]
 """
@@ -71,9 +72,9 @@ def main() -> int:
                          "share of keys never seen before)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--literal-zipf", action="store_true",
-                    help="extra line: config 2 with ranks Zipf-distributed over the whole 2^40 key space (about a quarter "
-                         "of the IDs miss the pre-populated table, so it grows by ~2 M keys per step); runs last, "
-                         "takes ~30 s more")
+                    help="extra line literal_zipf (config 2 with ranks Zipf-distributed over the whole 2^40 key space: "
+                         "about a quarter of the IDs miss the pre-populated table, so it grows by ~2 M keys per "
+                         "step) over 10 steps instead of 4")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the extra lines (profiling runs: only the step's own kernels)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -160,11 +161,14 @@ def main() -> int:
     # The step this library recommends for one GPU: tag + dedup in one call (8-byte sort records, no tagged-key
     # array), one row-record update per step (the lookup leaves the touch to the update).  Same outputs and the same
     # table afterwards as the step of the named calls below.
+    # The mapping positions <-> distinct keys is written in sorted order (perm, seg_of), which is what the expand
+    # and the reduce read; the position-ordered `inverse` (a random 4-byte scatter no call of this step reads) is
+    # left out here and written by the step of the named calls below.
     def one_step(step: int, ev=None):
         dx, doff, dtag, n, _ = batches[step % len(batches)]
         rec = (lambda i: ev[i].record()) if ev is not None else (lambda i: None)
         rec(0)
-        B.emb_tag_dedup(dx, doff, dtag, tag_bits, id_bits, None, buf.uniq, buf.inverse, None, buf.perm, None, buf.seg_of,
+        B.emb_tag_dedup(dx, doff, dtag, tag_bits, id_bits, None, buf.uniq, None, None, buf.perm, None, buf.seg_of,
                         buf.n_unique, buf.err_count, buf.tag_dedup_ws)
         rec(1)
         table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted, touch=False)
@@ -242,8 +246,8 @@ def main() -> int:
         "config": {"workload": f"config{args.config}:{w.name}", "batch": w.batch, "fields": len(w.features), "dim": dim,
                    "table_keys": n_keys, "capacity_log2": cap_log2, "ids_per_step": int(n_avg),
                    "unique_per_step": int(u_avg), "new_keys_per_step": round(u_new, 1), "distinct_batches": len(batches),
-                   "calls": "emb_tag_dedup, ht_find_or_insert_notouch, ht_gather, emb_expand_sorted, grad_segment_reduce, "
-                            "ht_apply_adagrad_touch"},
+                   "calls": "emb_tag_dedup (mapping as perm + seg_of), ht_find_or_insert_notouch, ht_gather, "
+                            "emb_expand_sorted, grad_segment_reduce, ht_apply_adagrad_touch"},
         "unique_ids_per_sec": round(u_avg * args.steps / wall, 1),
         "algorithmic_bytes_per_step": ab["total"],
         "achieved_hbm_gbps": round(achieved, 1),
@@ -292,10 +296,14 @@ def main() -> int:
     if not args.no_extras:
         result["probe_counts"] = probe_counts(B, table, batches, buf, tag_bits, id_bits, dim, dtype, cap_log2, chunk_log2)
 
+    # ---- first stage of a hash-based deduplication, measured for comparison with the sort
+    if extras_ok:
+        result["hash_front_end_probe"] = hash_front_end_probe(B, batches, buf, tag_bits, id_bits, phase_ms["tag_dedup"])
+
     # ---- the same step with the fused lookup (no distinct-row matrix), as an extra line
     def one_step_fused(step: int):
         dx, doff, dtag, n, _ = batches[step % len(batches)]
-        B.emb_tag_dedup(dx, doff, dtag, tag_bits, id_bits, None, buf.uniq, buf.inverse, None, buf.perm, None, buf.seg_of,
+        B.emb_tag_dedup(dx, doff, dtag, tag_bits, id_bits, None, buf.uniq, None, None, buf.perm, None, buf.seg_of,
                         buf.n_unique, buf.err_count, buf.tag_dedup_ws)
         table.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted, touch=False)
         B.ht_gather_expand_sorted(table.h, buf.row_idx, buf.seg_of, buf.perm, n, buf.out)
@@ -335,9 +343,8 @@ def main() -> int:
             "ms_per_step": round(wall_l * 1e3 / args.steps, 4), "ids_per_sec": round(ids_l / wall_l, 1),
             "hbm_frac_of_8TBps_by_the_unfused_byte_count": round(ab["total"] * args.steps / wall_l / 1e9 / HBM_PEAK_GBPS, 4),
             "fused_backward_ms": round(ev0.elapsed_time(ev1) / 5, 4),
-            "note": "emb_tag_dedup without inverse + ht_gather_expand_sorted + grad_reduce_apply_adagrad: same embeddings "
-                    "out, same table after the step; distinct-row matrix, reduced-gradient matrix and inverse are not "
-                    "written"}
+            "note": "emb_tag_dedup + ht_gather_expand_sorted + grad_reduce_apply_adagrad: same embeddings out, same "
+                    "table after the step; distinct-row matrix and reduced-gradient matrix are not written"}
 
     # ---- pooled variant (one vector per sample and field instead of one per position), as an extra line
     if extras_ok:
@@ -398,10 +405,11 @@ def main() -> int:
                         "reduction (one segment spans thousands of spans)"}
 
     # ---- literal reading of "Zipf over a 2^40 key space": the table keeps growing (inserts, new chunks, rehash)
-    if args.config == 2 and args.literal_zipf:
+    # (4 steps by default, 10 with --literal-zipf; the only line of the default run in which every step inserts)
+    if extras_ok:
         wz = make_config(2, field_vocab=[2 ** 40] * 8)
         wz.prepopulated = list(w.prepopulated)
-        k_steps = min(args.steps, 10)
+        k_steps = min(args.steps, 10) if args.literal_zipf else 4
         zb = []
         for s_ in range(k_steps + 1):
             bz = wz.next_step(s_)
@@ -413,7 +421,7 @@ def main() -> int:
 
         def one_step_z(i: int, step: int):
             dx, doff, dtag, n = zb[i]
-            B.emb_tag_dedup(dx, doff, dtag, tag_bits, id_bits, None, buf.uniq, buf.inverse, None, buf.perm, None, buf.seg_of,
+            B.emb_tag_dedup(dx, doff, dtag, tag_bits, id_bits, None, buf.uniq, None, None, buf.perm, None, buf.seg_of,
                             buf.n_unique, buf.err_count, buf.tag_dedup_ws)
             table.find_or_insert(buf.uniq, buf.n_unique, n, step, buf.row_idx, buf.inserted, touch=False)
             table.gather(buf.row_idx, buf.n_unique, n, buf.uniq_rows)
@@ -537,6 +545,41 @@ def probe_counts(B, table, batches, buf, tag_bits, id_bits, dim, dtype, cap_log2
                               "atomics_per_lookup_step": "none for keys that are present (admission and allocation "
                                                          "atomics are per block of 1024 keys that brings new keys)"}
     return out
+
+
+def hash_front_end_probe(B, batches, buf, tag_bits, id_bits, sort_ms) -> dict:
+    """What the first stage of a hash-based deduplication costs on this batch, measured with the library's own
+    table: every ID of the batch, duplicates included, goes through find-or-insert into an empty table with
+    16-byte rows (the row index a key receives is its dense number, i.e. an inverse in arrival order).  A hash
+    front end would still have to clear the table, bring the distinct keys into ascending order, renumber, and
+    sort (number, position) pairs for the backward pass's segments; the sort-based call delivers all of that."""
+    from paper_2505_12663_amd import EmbeddingTable
+    dx, doff, dtag, n, _ = batches[0]
+    B.emb_tag_keys(dx, doff, dtag, tag_bits, buf.key, buf.err_count)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ms, distinct, rcs = [], 0, []
+    for rep in range(3):
+        t = EmbeddingTable(4, 0, capacity_log2=23, chunk_rows_log2=22, max_load_factor=1.0, initial_chunks=1)
+        torch.cuda.synchronize()
+        e0.record()
+        rcs.append(B.ht_find_or_insert(t.h, buf.key, None, n, 1, buf.row_idx, None, touch=False))
+        e1.record()
+        torch.cuda.synchronize()
+        ms.append(e0.elapsed_time(e1))
+        st = t.stats()
+        distinct, refused = st["live"], st["refused"]
+        t.close()
+    e0.record()
+    B.emb_tag_dedup(dx, doff, dtag, tag_bits, id_bits, None, buf.uniq, buf.inverse, None, buf.perm, None, buf.seg_of,
+                    buf.n_unique, buf.err_count, buf.tag_dedup_ws)
+    e1.record()
+    torch.cuda.synchronize()
+    return {"ids": n, "distinct": distinct, "turned_away": refused, "table_slots_log2": 23,
+            "insert_all_ids_ms": round(float(np.median(ms)), 4), "insert_all_ids_ms_all": [round(m, 4) for m in ms],
+            "emb_tag_dedup_ms": round(sort_ms, 4), "emb_tag_dedup_with_position_ordered_inverse_ms": round(e0.elapsed_time(e1), 4),
+            "note": "find-or-insert of all IDs of one batch (duplicates included) into an empty table with 16-byte rows: "
+                    "stage one of a hash-based deduplication (dense numbers in arrival order), next to the whole "
+                    "sort-based call, which also delivers ascending distinct keys, perm and segments"}
 
 
 def ceiling_probes(B, timed, dev) -> dict:

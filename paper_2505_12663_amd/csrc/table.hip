@@ -255,11 +255,14 @@ __device__ inline void touch_row(const HtView& v, uint32_t row, uint32_t step) {
 // TOUCH = false: existing keys are found without counting a touch and a created row starts
 // with touch count 0 (the update call of the step counts it, in the write it does anyway).
 // retry: only the elements an earlier call left at -1 are processed, the others keep their results.
+// admit = 0: the host has shown that every element of the call fits below the limit even if all are
+// new keys; the block then skips the admission (an atomic whose result it would have to wait for) and
+// just adds the slots it claimed to the count.
 template <bool COUNT, bool TOUCH>
 __global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const uint64_t* __restrict__ key,
                                                               const int64_t* n_dev, int64_t n_max, uint32_t step,
                                                               int32_t* __restrict__ row_idx,
-                                                              uint8_t* __restrict__ inserted, int retry) {
+                                                              uint8_t* __restrict__ inserted, int retry, int admit) {
     __shared__ int s_absent[kBigWaves], s_new[kBigWaves], s_surplus[kBigWaves];
     __shared__ unsigned s_bits[kBigWaves];
     __shared__ int s_admitted, s_old_free, s_take, s_got;
@@ -268,6 +271,10 @@ __global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const ui
     if ((int64_t)blockIdx.x * kBigBlock >= n) return; // whole block beyond the count
     const int lane = lane_id();
     const int wave = threadIdx.x / kWave;
+    // whether the free stack holds rows, read long before the allocation needs it (only eviction pushes
+    // rows, and never while this kernel runs, so a zero stays a zero)
+    const uint32_t free_hint =
+        threadIdx.x == 0 ? load_fresh(reinterpret_cast<const uint32_t*>(&v.st->head.free_count)) : 0u;
     const int64_t wave_base = (int64_t)blockIdx.x * kBigBlock + wave * kWave;
     const bool wave_on = wave_base < n;
     const int64_t i = wave_base + lane;
@@ -326,7 +333,9 @@ __global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const ui
         }
         if (no_room > 0) atomicAdd(&v.st->head.refused, (unsigned long long)no_room);
         int admitted = 0;
-        if (total > 0) {
+        if (total > 0 && !admit) {
+            admitted = total;
+        } else if (total > 0) {
             const unsigned old_occ = atomicAdd(&v.st->head.occupied, (unsigned)total);
             admitted = old_occ >= v.slot_limit ? 0 : (int)(v.slot_limit - old_occ);
             if (admitted > total) admitted = total;
@@ -403,7 +412,11 @@ __global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const ui
                 surplus += s_surplus[w];
                 lost += s_bits[w];
             }
-            if (surplus > 0) atomicSub(&v.st->head.occupied, (unsigned)surplus);
+            if (admit) {
+                if (surplus > 0) atomicSub(&v.st->head.occupied, (unsigned)surplus);
+            } else if (total > 0) {
+                atomicAdd(&v.st->head.occupied, (unsigned)total);   // the slots claimed; nothing waits for the result
+            }
             if (lost > 0) {
                 atomicAdd(&v.st->head.refused, (unsigned long long)lost);
                 atomicOr(&v.st->head.status, EMB_DEV_PROBE_EXHAUSTED);
@@ -412,7 +425,7 @@ __global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const ui
             unsigned bump_base = 0;
             if (total > 0) {
                 unsigned n_atomics = 0;
-                if (load_fresh(reinterpret_cast<const uint32_t*>(&v.st->head.free_count)) != 0u) {
+                if (free_hint != 0u) {
                     old_free = atomicSub(&v.st->head.free_count, total);
                     ++n_atomics;
                 }
@@ -967,12 +980,14 @@ static int find_or_insert_impl(emb_table_t* t, const uint64_t* key, const int64_
     if (!key || !row_idx) return EMB_ERR_INVALID_ARG;
     const int room = check_insert_room(t, n_max);
     if (room < 0) return room;
+    // the device checks every block's new keys against the limit unless the bound shows that all fit
+    const int admit = t->occupied_bound() + (uint64_t)n_max > (uint64_t)t->slot_limit() ? 1 : 0;
     HtView v = t->view();
     hipStream_t s = static_cast<hipStream_t>(stream);
     const unsigned grid = blocks_for((uint64_t)n_max, kBigBlock);
 #define MTGR_FOI(C_, T_)                                                                                          \
     hipLaunchKernelGGL((k_find_or_insert<C_, T_>), dim3(grid), dim3(kBigBlock), 0, s, v, key, n_dev, n_max, step, \
-                       row_idx, inserted, retry ? 1 : 0)
+                       row_idx, inserted, retry ? 1 : 0, admit)
     if (v.count) {
         if (touch) MTGR_FOI(true, true); else MTGR_FOI(true, false);
     } else {
