@@ -346,6 +346,30 @@ def main() -> int:
             "note": "emb_tag_dedup + ht_gather_expand_sorted + grad_reduce_apply_adagrad: same embeddings out, same "
                     "table after the step; distinct-row matrix and reduced-gradient matrix are not written"}
 
+    # ---- the fused calls on their own (any configuration): the buffers still hold the last timed step's batch
+    if not args.no_extras and not extras_ok:
+        dx, doff, dtag, n_last, _ = batches[(args.warmup + args.steps - 1) % len(batches)]
+        B.emb_tag_dedup(dx, doff, dtag, tag_bits, id_bits, None, buf.uniq, None, None, buf.perm, None, buf.seg_of,
+                        buf.n_unique, buf.err_count, buf.tag_dedup_ws)
+        table.find_or_insert(buf.uniq, buf.n_unique, n_last, next_step, buf.row_idx, buf.inserted, touch=False)
+        e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        reps = 3
+        e0.record()
+        for _ in range(reps):
+            B.ht_gather_expand_sorted(table.h, buf.row_idx, buf.seg_of, buf.perm, n_last, buf.out)
+        e1.record()
+        for _ in range(reps):
+            B.grad_reduce_apply_adagrad(table.h, grad, buf.seg_of, buf.perm, n_last, buf.row_idx, w.lr, w.eps, None, buf.reduce_ws)
+        e2.record()
+        torch.cuda.synchronize()
+        result["fused_calls"] = {
+            "ht_gather_expand_sorted_ms": round(e0.elapsed_time(e1) / reps, 4),
+            "against_gather_plus_expand_ms": round(phase_ms["gather"] + phase_ms["expand"], 4),
+            "grad_reduce_apply_adagrad_ms": round(e1.elapsed_time(e2) / reps, 4),
+            "against_reduce_plus_adagrad_ms": round(phase_ms["reduce"] + phase_ms["adagrad"], 4),
+            "note": "same results without the distinct-row matrix / the reduced-gradient matrix (which, with fp32 sums of "
+                    "bf16 gradients, is twice the size of the rows it updates)"}
+
     # ---- pooled variant (one vector per sample and field instead of one per position), as an extra line
     if extras_ok:
         lens0 = np.concatenate(lengths_of[0]).astype(np.int64)
