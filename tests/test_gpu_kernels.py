@@ -146,6 +146,38 @@ def test_tag_dedup_matches_tag_then_dedup(case):
         xs[1][:5000] = xs[0][:5000]
     if case == "narrow_ids_wide_tags":
         tags = [t & 0xFF for t in tags]  # identifiers are bytes at this boundary
+    _check_tag_dedup(xs, lens, tags, tag_bits, id_bits)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_tag_dedup_random_shapes(seed):
+    """Random field counts, lengths (empty fields included), identifier assignments, widths and duplicate rates;
+    sizes from one record to a dozen tiles, with and without the packed records fitting 64 bits."""
+    rng = np.random.default_rng(1000 + seed)
+    nf = int(rng.integers(1, 41))
+    tag_bits = int(rng.integers(0, 9)) if nf > 1 or seed % 2 else 0
+    id_bits = int(rng.choice([3, 9, 17, 18, 27, 36, 40, 45, 50, 55]))
+    id_bits = min(id_bits, 63 - tag_bits)
+    scale = int(rng.choice([1, 40, 700, 4096, 13_000]))
+    lens = [int(l) for l in rng.integers(0, scale + 1, size=nf)]
+    if sum(lens) == 0:
+        lens[int(rng.integers(0, nf))] = 1
+    tags = [int(t) for t in rng.integers(0, 1 << tag_bits, size=nf)]
+    vocab = int(rng.choice([1, 7, 300, 50_000, 1 << 40]))
+    xs = []
+    for l in lens:
+        v = rng.integers(0, min(vocab, 1 << id_bits), size=l, dtype=np.uint64)
+        if seed % 3 == 0 and l:            # spread the values over the whole declared width
+            v = (v * np.uint64(0x9E3779B97F4A7C15)) & np.uint64((1 << id_bits) - 1)
+        xs.append(v)
+    if seed % 5 == 0:                      # some IDs beyond the declared width: counted and wrapped
+        for v in xs:
+            if len(v):
+                v[:: 7] |= np.uint64(1 << id_bits) if id_bits < 62 - tag_bits else np.uint64(0)
+    _check_tag_dedup(xs, lens, tags, tag_bits, id_bits)
+
+
+def _check_tag_dedup(xs, lens, tags, tag_bits, id_bits):
     x = np.concatenate(xs) if sum(lens) else np.zeros(0, np.uint64)
     off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
     tg = np.array(tags, dtype=np.uint8)
