@@ -99,6 +99,8 @@ typedef struct {
     uint64_t hot_rows_capacity;
     uint64_t probe_hist[8]; /* count_probes != 0: keys that inspected 1, 2, .. 7, and 8 or more slot lines */
     uint64_t refused;       /* new keys turned away so far by find-or-insert (limit reached or out of rows); each got -1 */
+    uint64_t occupied;      /* the device's own count of live + deleted slots, the figure its load-factor limit bounds
+                               (equal to live + tombstones whenever no call is in flight) */
 } ht_stats_t;
 
 /* ------------------------------------------------------------------ host-only planning */

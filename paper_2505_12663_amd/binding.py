@@ -42,7 +42,7 @@ class HtStats(C.Structure):
                  ("live", "tombstones", "capacity", "rows_used", "rows_free", "rows_capacity", "n_rehash",
                   "n_chunks", "status", "lookups", "probes", "cas_attempts", "cas_failures", "alloc_atomics",
                   "hot_rows_used", "hot_rows_free", "hot_rows_capacity")]
-                + [("probe_hist", C.c_uint64 * 8), ("refused", C.c_uint64)])
+                + [("probe_hist", C.c_uint64 * 8), ("refused", C.c_uint64), ("occupied", C.c_uint64)])
 
     def as_dict(self):
         d = {n: int(getattr(self, n)) for n, _ in self._fields_ if n != "probe_hist"}

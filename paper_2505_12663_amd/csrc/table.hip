@@ -1137,6 +1137,7 @@ int ht_stats(emb_table_t* t, ht_stats_t* out, void* stream) {
     out->hot_rows_free = h.hot_free_count > 0 ? (uint64_t)h.hot_free_count : 0ull;
     out->hot_rows_capacity = t->hot_capacity;
     out->refused = h.refused;
+    out->occupied = full.occupied;
     // exact numbers replace the running upper bounds; older counter copies are obsolete
     t->adopt(h, 0, t->seq);
     t->min_valid_seq = t->seq + 1;
