@@ -659,6 +659,8 @@ __global__ __launch_bounds__(kBigBlock) void k_evict(HtView v, uint64_t n_slots,
 // Key-structure migration: one lane per old slot; a live pair is placed in the first never-used
 // slot of the first line with one on its probe sequence in the new structure.  No key occurs
 // twice, so no match test is needed.  Values are not touched (Sec. 3.1 "Capacity Expansion").
+// DISPLACED_ONLY: second pass of the streaming migration - only keys that did not sit in their home line.
+template <bool DISPLACED_ONLY>
 __global__ __launch_bounds__(kBlock) void k_rehash(const Slot* __restrict__ old_slots, uint64_t n_old, Slot* new_slots,
                                                    uint64_t new_line_mask, HtState* st) {
     const uint64_t s = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
@@ -668,6 +670,7 @@ __global__ __launch_bounds__(kBlock) void k_rehash(const Slot* __restrict__ old_
     const uint32_t row = e.z;
     if (k == kEmptyKey || k == kTombKey || row == kRowInvalid) return;
     const uint64_t h = slot_hash(k);
+    if (DISPLACED_ONLY && probe_start(h, n_old / kLineSlots - 1ull) == s / kLineSlots) return;   // placed by the first pass
     uint64_t line = probe_start(h, new_line_mask);
     const uint64_t stride = probe_stride(h, new_line_mask);
     for (uint64_t t = 0; t <= new_line_mask; ++t) {
@@ -683,6 +686,45 @@ __global__ __launch_bounds__(kBlock) void k_rehash(const Slot* __restrict__ old_
         line = (line + stride) & new_line_mask;
     }
     atomicOr(&st->head.status, EMB_DEV_PROBE_EXHAUSTED);
+}
+
+// Migration into a structure of 2^k times the size (k >= 0), in two streaming passes instead of one
+// random insert per key.  The home line of a key is the low bits of its hash, so the keys whose home
+// is old line l have home l + j * L_old (j < 2^k) in the new structure, and nobody else has.
+// Pass 1: the 8 lanes that hold old line l write those 2^k new lines completely - the keys that sat
+// in their home line, packed to the front, then never-used slots.  Every new line is written exactly
+// once, in whole 128-byte lines (no separate fill, no compare-and-swap, no reads of the new memory).
+// Pass 2 (k_rehash with DISPLACED_ONLY): the keys that were not in their home line (it had been full
+// when they arrived) are inserted by probing, as in the general migration.  A key in its home line is
+// found by the first probe; the others are placed by the ordinary insert rule, so lookups see a table
+// like any other.
+__global__ __launch_bounds__(kBlock) void k_rehash_split(const Slot* __restrict__ old_slots, uint64_t n_old,
+                                                         Slot* __restrict__ new_slots, int old_line_bits, int k) {
+    const uint64_t slot = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (slot >= n_old) return;            // n_old is a multiple of the wave size: whole waves leave
+    const int lane = lane_id();
+    const int sub = lane & (kLineSlots - 1);
+    const int gbase = lane & ~(kLineSlots - 1);
+    const uint64_t line = slot / kLineSlots;
+    const uint64_t old_lines = 1ull << old_line_bits;
+    const V16 e = ld16(old_slots + slot);
+    const uint64_t key = ((uint64_t)e.y << 32) | e.x;
+    const uint32_t row = e.z;
+    const bool live = key != kEmptyKey && key != kTombKey && row != kRowInvalid;
+    const uint64_t h = slot_hash(key);
+    const bool at_home = live && probe_start(h, old_lines - 1ull) == line;
+    const unsigned target = (unsigned)((h >> old_line_bits) & ((1ull << k) - 1ull));   // which of the 2^k new lines
+    const V16 never_used{0xFFFFFFFFu, 0xFFFFFFFFu, kRowInvalid, 0u};
+    for (unsigned j = 0; j < (1u << k); ++j) {
+        const uint64_t m = __ballot(at_home && target == j);
+        unsigned m8 = (unsigned)(m >> gbase) & 0xFFu;
+        for (int i = 0; i < sub; ++i) m8 &= m8 - 1u;          // drop the `sub` lowest members: the next one is this lane's
+        const int src = m8 ? (__ffs(m8) - 1) : 0;
+        const uint64_t kk = shfl64(key, gbase + src);
+        const uint32_t rr = __shfl(row, gbase + src, kWave);
+        const V16 out = m8 ? V16{(uint32_t)kk, (uint32_t)(kk >> 32), rr, 0u} : never_used;
+        st16(new_slots + (line + (uint64_t)j * old_lines) * kLineSlots + sub, out);
+    }
 }
 
 // After a rehash (or on fresh key storage) no deleted markers are left: occupied = live.  One wave.
@@ -1070,11 +1112,22 @@ int ht_rehash(emb_table_t* t, void* new_slots, int new_capacity_log2, void* stre
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint64_t n_new = 1ull << new_capacity_log2;
     const uint64_t n_old = 1ull << t->cap_log2;
-    hipLaunchKernelGGL(k_fill_slots, dim3(fill_grid(n_new)), dim3(256), 0, s, static_cast<Slot*>(new_slots), n_new);
-    MTGR_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_rehash, dim3(blocks_for(n_old, kBlock)), dim3(kBlock), 0, s, t->slots, n_old,
-                       static_cast<Slot*>(new_slots), n_new / kLineSlots - 1ull, t->st);
-    MTGR_LAUNCH_CHECK();
+    if (new_capacity_log2 >= t->cap_log2 && new_capacity_log2 - t->cap_log2 <= 3) {
+        // same size (purge of deleted markers) or 2, 4, 8 times larger: two streaming passes (a lane of the first
+        // pass writes 2^k slots, so a jump from a tiny structure to a huge one is left to the general path)
+        hipLaunchKernelGGL(k_rehash_split, dim3(blocks_for(n_old, kBlock)), dim3(kBlock), 0, s, t->slots, n_old,
+                           static_cast<Slot*>(new_slots), t->cap_log2 - 3, new_capacity_log2 - t->cap_log2);
+        MTGR_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_rehash<true>, dim3(blocks_for(n_old, kBlock)), dim3(kBlock), 0, s, t->slots, n_old,
+                           static_cast<Slot*>(new_slots), n_new / kLineSlots - 1ull, t->st);
+        MTGR_LAUNCH_CHECK();
+    } else {
+        hipLaunchKernelGGL(k_fill_slots, dim3(fill_grid(n_new)), dim3(256), 0, s, static_cast<Slot*>(new_slots), n_new);
+        MTGR_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_rehash<false>, dim3(blocks_for(n_old, kBlock)), dim3(kBlock), 0, s, t->slots, n_old,
+                           static_cast<Slot*>(new_slots), n_new / kLineSlots - 1ull, t->st);
+        MTGR_LAUNCH_CHECK();
+    }
     hipLaunchKernelGGL(k_after_rehash, dim3(1), dim3(kWave), 0, s, t->st);
     MTGR_LAUNCH_CHECK();
     t->slots = static_cast<Slot*>(new_slots);

@@ -571,6 +571,51 @@ def test_evict_and_rehash_against_checker():
     t.close()
 
 
+@pytest.mark.parametrize("grow", [0, 1, 2, 3, 4, -1])
+def test_rehash_keeps_every_pair_at_high_load(grow):
+    """Key-structure migration from a table at load 0.85 with deleted markers (a good part of the keys sits away
+    from its home line): same size, 2, 4, 8 times larger (two streaming passes), 16 times larger and smaller (general
+    path).  Every live key keeps its row, deleted keys stay absent, no marker survives, the lookup still ends within a
+    few lines, and inserts work afterwards."""
+    cap_log2 = 14
+    n = int(np.float32(0.85) * (1 << cap_log2))
+    keys = scramble_bits(np.arange(n, dtype=np.uint64), 44, 21)
+    t = EmbeddingTable(8, 0, capacity_log2=cap_log2, chunk_rows_log2=cap_log2, max_load_factor=0.85, count_probes=True,
+                       initial_chunks=2)
+    rows = torch.empty(n, dtype=torch.int32, device="cuda")
+    # two halves at steps 1 and 2, then everything of step 1 is evicted: markers all over the probe sequences
+    h = n // 2 if grow >= 0 else (n * 3) // 4
+    t.find_or_insert(dev_keys(keys[:h]), None, h, 1, rows[:h])
+    t.find_or_insert(dev_keys(keys[h:]), None, n - h, 2, rows[h:])
+    assert t.stats()["live"] == n
+    ev, n_ev = t.evict(3, 2, 0, 0)                    # last seen at step 1 -> age 2 -> out
+    assert n_ev == h
+    keep = keys[h:]
+    before = torch.empty(len(keep), dtype=torch.int32, device="cuda")
+    t.find(dev_keys(keep), None, len(keep), before)
+    assert (before >= 0).all()
+    t.rehash(cap_log2 + grow)
+    st = t.stats()
+    assert st["live"] == len(keep) and st["tombstones"] == 0 and st["status"] == 0 and st["capacity"] == 1 << (cap_log2 + grow)
+    after = torch.empty_like(before)
+    p0 = st["probes"]
+    t.find(dev_keys(keep), None, len(keep), after)
+    assert torch.equal(before, after)
+    lines = (t.stats()["probes"] - p0) / len(keep)
+    assert lines < (1.6 if grow <= 0 else 1.2), lines
+    gone = torch.empty(h, dtype=torch.int32, device="cuda")
+    t.find(dev_keys(keys[:h]), None, h, gone)
+    assert (gone == -1).all()
+    # the migrated structure takes inserts like any other: the evicted keys come back as new rows
+    back = min(h, int(0.85 * (1 << (cap_log2 + grow))) - len(keep))
+    t.find_or_insert(dev_keys(keys[:back]), None, back, 4, gone[:back])
+    st = t.stats()
+    assert (gone[:back] >= 0).all() and st["live"] == len(keep) + back and st["status"] == 0
+    t.find(dev_keys(keep), None, len(keep), after)
+    assert torch.equal(before, after)
+    t.close()
+
+
 def test_full_table_up_to_the_load_factor_limit():
     # exactly capacity * max_load_factor keys fit without a rehash and are all found again
     cap_log2 = 13
