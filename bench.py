@@ -567,7 +567,7 @@ def probe_counts(B, table, batches, buf, tag_bits, id_bits, dim, dtype, cap_log2
     out["benchmark_table"] = {"load_factor": round((stb["live"] + stb["tombstones"]) / stb["capacity"], 4),
                               "distinct_keys_looked_up_per_step": u,
                               "atomics_per_lookup_step": "none for keys that are present (admission and allocation "
-                                                         "atomics are per block of 1024 keys that brings new keys)"}
+                                                         "atomics are per block of 512 keys that brings new keys)"}
     return out
 
 

@@ -92,7 +92,7 @@ typedef struct {
     uint64_t probes;        /* 128-byte slot lines inspected for them */
     uint64_t cas_attempts;
     uint64_t cas_failures;
-    uint64_t alloc_atomics; /* atomics issued by admission and the row allocator (per block of 1024 keys that brings new keys) */
+    uint64_t alloc_atomics; /* atomics issued by admission and the row allocator (per block of 512 keys that brings new keys) */
     /* hot store (ht_set_hot_storage); all zero without one */
     uint64_t hot_rows_used;     /* high-water mark of the hot store's allocator */
     uint64_t hot_rows_free;     /* hot rows returned by evictions */

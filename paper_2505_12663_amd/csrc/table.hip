@@ -13,8 +13,15 @@ using namespace mtgr;
 namespace {
 
 constexpr int kBlock = 256;
-constexpr int kBigBlock = 1024;            // kernels that aggregate allocator traffic per block
+constexpr int kBigBlock = 1024;            // eviction: aggregates its pushes per block
 constexpr int kBigWaves = kBigBlock / kWave;
+// find-or-insert aggregates admission and row allocation per block and has block-wide barriers between its
+// rounds, so every wave waits for the block's slowest key.  512 keys per block measured best: against 1024,
+// a lookup of 5.7 M present keys at load 0.73 takes 188 us instead of 250, the same with 5 % new keys 260 us
+// instead of 360, a 4 M-key bulk insert 735 us instead of 860; 256 helps the sparse case a little more
+// (243 us) but costs the bulk insert its aggregation (1150 us).
+constexpr int kFoiBlock = 512;
+constexpr int kFoiWaves = kFoiBlock / kWave;
 
 __device__ inline void* chunk_row_ptr(const HtView& v, uint32_t row) {
     char* base = static_cast<char*>(v.st->values[row >> v.chunk_log2]);
@@ -248,7 +255,7 @@ __device__ inline void touch_row(const HtView& v, uint32_t row, uint32_t step) {
 //   slots therefore never exceed the limit.
 //   Round 2 claims a never-used slot for every admitted key by compare-and-swap.  A key that a
 //   duplicate in another wave has inserted meanwhile is simply found; its reservation is returned.
-// Rows for the new keys of all 16 waves of a block are taken from the allocator with one atomic per
+// Rows for the new keys of all waves of a block are taken from the allocator with one atomic per
 // block (a 4 M-key bulk insert otherwise queues 130 k atomics on the bump pointer): free stack first,
 // then the bump pointer, which never passes the registered rows; a claim that gets no row leaves a
 // deleted marker in its slot and its element is turned away too.
@@ -259,23 +266,23 @@ __device__ inline void touch_row(const HtView& v, uint32_t row, uint32_t step) {
 // new keys; the block then skips the admission (an atomic whose result it would have to wait for) and
 // just adds the slots it claimed to the count.
 template <bool COUNT, bool TOUCH>
-__global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const uint64_t* __restrict__ key,
+__global__ __launch_bounds__(kFoiBlock) void k_find_or_insert(HtView v, const uint64_t* __restrict__ key,
                                                               const int64_t* n_dev, int64_t n_max, uint32_t step,
                                                               int32_t* __restrict__ row_idx,
                                                               uint8_t* __restrict__ inserted, int retry, int admit) {
-    __shared__ int s_absent[kBigWaves], s_new[kBigWaves], s_surplus[kBigWaves];
-    __shared__ unsigned s_bits[kBigWaves];
+    __shared__ int s_absent[kFoiWaves], s_new[kFoiWaves], s_surplus[kFoiWaves];
+    __shared__ unsigned s_bits[kFoiWaves];
     __shared__ int s_admitted, s_old_free, s_take, s_got;
     __shared__ unsigned s_bump;
     const int64_t n = read_count(n_dev, n_max);
-    if ((int64_t)blockIdx.x * kBigBlock >= n) return; // whole block beyond the count
+    if ((int64_t)blockIdx.x * kFoiBlock >= n) return; // whole block beyond the count
     const int lane = lane_id();
     const int wave = threadIdx.x / kWave;
     // whether the free stack holds rows, read long before the allocation needs it (only eviction pushes
     // rows, and never while this kernel runs, so a zero stays a zero)
     const uint32_t free_hint =
         threadIdx.x == 0 ? load_fresh(reinterpret_cast<const uint32_t*>(&v.st->head.free_count)) : 0u;
-    const int64_t wave_base = (int64_t)blockIdx.x * kBigBlock + wave * kWave;
+    const int64_t wave_base = (int64_t)blockIdx.x * kFoiBlock + wave * kWave;
     const bool wave_on = wave_base < n;
     const int64_t i = wave_base + lane;
     const bool valid = i < n && !(retry && row_idx[i] >= 0);
@@ -326,7 +333,7 @@ __global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const ui
     if (threadIdx.x == 0) {
         int total = 0, no_room = 0;
         unsigned bits = 0;
-        for (int w = 0; w < kBigWaves; ++w) {
+        for (int w = 0; w < kFoiWaves; ++w) {
             total += s_absent[w];
             no_room += s_surplus[w];
             bits |= s_bits[w];
@@ -407,7 +414,7 @@ __global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const ui
         if (threadIdx.x == 0) {
             int total = 0, surplus = 0;
             unsigned lost = 0;
-            for (int w = 0; w < kBigWaves; ++w) {
+            for (int w = 0; w < kFoiWaves; ++w) {
                 total += s_new[w];
                 surplus += s_surplus[w];
                 lost += s_bits[w];
@@ -535,7 +542,7 @@ __global__ __launch_bounds__(kBigBlock) void k_find_or_insert(HtView v, const ui
         if (inserted) inserted[i] = my_created ? 1 : 0;
     }
     if (COUNT && wave_on)
-        flush_counters(v, lane, blockIdx.x * kBigWaves + wave, n - wave_base < kWave ? n - wave_base : kWave, pc, key_lines);
+        flush_counters(v, lane, blockIdx.x * kFoiWaves + wave, n - wave_base < kWave ? n - wave_base : kWave, pc, key_lines);
 }
 
 // Second half of find-or-insert: resolve the deferred elements and count their touch.
@@ -1026,9 +1033,9 @@ static int find_or_insert_impl(emb_table_t* t, const uint64_t* key, const int64_
     const int admit = t->occupied_bound() + (uint64_t)n_max > (uint64_t)t->slot_limit() ? 1 : 0;
     HtView v = t->view();
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const unsigned grid = blocks_for((uint64_t)n_max, kBigBlock);
+    const unsigned grid = blocks_for((uint64_t)n_max, kFoiBlock);
 #define MTGR_FOI(C_, T_)                                                                                          \
-    hipLaunchKernelGGL((k_find_or_insert<C_, T_>), dim3(grid), dim3(kBigBlock), 0, s, v, key, n_dev, n_max, step, \
+    hipLaunchKernelGGL((k_find_or_insert<C_, T_>), dim3(grid), dim3(kFoiBlock), 0, s, v, key, n_dev, n_max, step, \
                        row_idx, inserted, retry ? 1 : 0, admit)
     if (v.count) {
         if (touch) MTGR_FOI(true, true); else MTGR_FOI(true, false);
