@@ -474,6 +474,10 @@ def main() -> int:
             "note": "ranks Zipf(1.05) over 2^40, top 6.25 M ranks per field pre-populated: every step creates rows "
                     "for about a quarter of its IDs; host-side capacity planning (chunk registration, rehash) included"}
 
+    # ---- eviction scan and key-structure migration on the benchmark's own table (last GPU work of the run)
+    if extras_ok:
+        result["table_maintenance"] = table_maintenance(B, table, next_step + 20_000)
+
     if args.copy_probe_mib > 0:
         nbytes = args.copy_probe_mib << 20
         src = torch.empty(nbytes, dtype=torch.uint8, device=dev).fill_(1)
@@ -568,6 +572,52 @@ def probe_counts(B, table, batches, buf, tag_bits, id_bits, dim, dtype, cap_log2
                               "distinct_keys_looked_up_per_step": u,
                               "atomics_per_lookup_step": "none for keys that are present (admission and allocation "
                                                          "atomics are per block of 512 keys that brings new keys)"}
+    return out
+
+
+def table_maintenance(B, table, now: int) -> dict:
+    """Eviction and rehash timed on the table the benchmark has just used (HIP events, one call each): a scan that
+    evicts nothing, the migration into a key structure of twice the size, an eviction of every key no step has
+    touched since the bulk load, and the same-size migration that purges the deleted markers.  GB/s = the bytes the
+    operation must move (16 per slot read, 16 per slot of the new structure written, 16 per live key's record) over
+    its time."""
+    dev = table.device
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def once(fn):
+        torch.cuda.synchronize()
+        e0.record()
+        fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1)
+
+    out = {}
+    n_ev = torch.zeros(1, dtype=torch.int64, device=dev)
+    st = table.stats()
+    cap, live = st["capacity"], st["live"]
+    ms = once(lambda: B.ht_evict(table.h, now, 1 << 30, 0, 0, None, n_ev))
+    out["evict_scan_nothing_evicted"] = {"slots": cap, "live": live, "ms": round(ms, 3),
+                                         "gbps": round((16 * cap + 16 * live) / ms / 1e6, 1)}
+    log2 = table.capacity_log2
+    new_slots = torch.empty((1 << (log2 + 1), 2), dtype=torch.int64, device=dev)
+    ms = once(lambda: B.ht_rehash(table.h, new_slots, log2 + 1))
+    table.slots, table.capacity_log2 = new_slots, log2 + 1
+    out["rehash_to_twice_the_size"] = {"slots_before": cap, "live": live, "ms": round(ms, 3),
+                                       "gbps": round((16 * cap + 32 * cap) / ms / 1e6, 1)}
+    cap *= 2
+    ms = once(lambda: B.ht_evict(table.h, now, now, 0, 0, None, n_ev))      # last seen at step 0 = never touched since the load
+    gone = int(n_ev.item())
+    out["evict_untouched_keys"] = {"slots": cap, "live_before": live, "evicted": gone, "ms": round(ms, 3)}
+    st = table.stats()
+    purge = torch.empty((1 << (log2 + 1), 2), dtype=torch.int64, device=dev)
+    ms = once(lambda: B.ht_rehash(table.h, purge, log2 + 1))
+    table.slots = purge
+    st2 = table.stats()
+    out["rehash_same_size_purge"] = {"slots": cap, "live": st2["live"], "deleted_markers_before": st["tombstones"],
+                                     "deleted_markers_after": st2["tombstones"], "ms": round(ms, 3),
+                                     "gbps": round((16 * cap + 16 * cap) / ms / 1e6, 1)}
+    out["status"] = st2["status"]
     return out
 
 
