@@ -616,6 +616,53 @@ def test_rehash_keeps_every_pair_at_high_load(grow):
     t.close()
 
 
+def test_evict_and_export_respect_the_capacity_of_their_output_lists():
+    """ht_evict and ht_export store at most `cap` entries, report the full count, and write nothing beyond the
+    list's end; what they store is a subset of the right answer."""
+    n, dim = 5000, 8
+    keys = scramble_bits(np.arange(n, dtype=np.uint64), 40, 31)
+    t = EmbeddingTable(dim, 0, capacity_log2=14, chunk_rows_log2=13, initial_chunks=1)
+    rows = torch.empty(n, dtype=torch.int32, device="cuda")
+    t.find_or_insert(dev_keys(keys[:3000]), None, 3000, 1, rows[:3000])
+    t.find_or_insert(dev_keys(keys[3000:]), None, 2000, 5, rows[3000:])
+    # export into lists shorter than the table
+    cap = 1200
+    guard = -12345
+    ek = torch.full((cap + 64,), guard, dtype=torch.int64, device="cuda")
+    ev = torch.full((cap + 64, dim), 7.5, dtype=torch.float32, device="cuda")
+    ea = torch.full((cap + 64,), 7.5, dtype=torch.float32, device="cuda")
+    el = torch.full((cap + 64,), guard, dtype=torch.int32, device="cuda")
+    ef = torch.full((cap + 64,), guard, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
+    B.ht_export(t.h, ek[:cap], ev[:cap], ea[:cap], el[:cap], ef[:cap], cnt)
+    assert int(cnt.item()) == n
+    assert (ek[cap:] == guard).all() and (ev[cap:] == 7.5).all() and (ea[cap:] == 7.5).all()
+    assert (el[cap:] == guard).all() and (ef[cap:] == guard).all()
+    got = host_keys(ek[:cap])
+    assert len(np.unique(got)) == cap and np.isin(got, keys).all()
+    first = np.isin(got, keys[:3000])
+    assert np.array_equal(el[:cap].cpu().numpy(), np.where(first, 1, 5)) and (ef[:cap] == 1).all() and (ea[:cap] == 0).all()
+    want = np.stack([oracle.init_row(int(k), dim) for k in got[:50]])
+    assert np.array_equal(ev[:50].cpu().numpy(), want)
+    # evict the 3000 keys of step 1 into a list of 1000
+    cap = 1000
+    kk = torch.full((cap + 64,), guard, dtype=torch.int64, device="cuda")
+    n_ev = torch.zeros(1, dtype=torch.int64, device="cuda")
+    B.ht_evict(t.h, 6, 3, 0, 0, kk[:cap], n_ev)                  # age >= 3: the keys last seen at step 1
+    assert int(n_ev.item()) == 3000 and (kk[cap:] == guard).all()
+    listed = host_keys(kk[:cap])
+    assert len(np.unique(listed)) == cap and np.isin(listed, keys[:3000]).all()
+    st = t.stats()
+    assert st["live"] == 2000 and st["tombstones"] == 3000 and st["rows_free"] == 3000 and st["status"] == 0
+    found = torch.empty(n, dtype=torch.int32, device="cuda")
+    t.find(dev_keys(keys), None, n, found)
+    assert (found[:3000] == -1).all() and torch.equal(found[3000:], rows[3000:])
+    # without a list at all
+    B.ht_evict(t.h, 9, 3, 0, 0, None, n_ev)
+    assert int(n_ev.item()) == 2000 and t.stats()["live"] == 0
+    t.close()
+
+
 def test_full_table_up_to_the_load_factor_limit():
     # exactly capacity * max_load_factor keys fit without a rehash and are all found again
     cap_log2 = 13
