@@ -252,6 +252,7 @@ def main() -> int:
         "algorithmic_bytes_per_step": ab["total"],
         "achieved_hbm_gbps": round(achieved, 1),
         "hbm_frac_of_8TBps": round(achieved / HBM_PEAK_GBPS, 4),
+        "step_ms_median": round(float(np.median(step_ms)), 4),
         "phase_ms": {k: round(v, 4) for k, v in phase_ms.items()},
         "phase_gbps": {p: round(ab[p] / (phase_ms[p] * 1e-3) / 1e9, 1) for p in phases},
         "roofline": roofline,
