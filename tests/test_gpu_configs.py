@@ -244,3 +244,66 @@ def test_random_shapes_whole_steps(seed):
     st = pair.gpu.stats()
     assert st["status"] == 0 and st["live"] == len(pair.orc)
     pair.gpu.close()
+
+
+def test_dedup_of_next_batch_on_a_second_stream_equals_serial_steps():
+    """The training pipeline overlaps the ID dispatch of batch i+1 with the work on batch i: emb_tag_dedup of the next
+    batch on a second stream (two sets of outputs, events both ways) while the current batch looks up, gathers,
+    expands, reduces and updates on the first.  Same calls, same order per table, so the table must end bit-identical
+    to the one the serial steps leave (which run_step checks against the checker)."""
+    w = make_config(4, batch=8, vocab_scale=0.01, len_lo=128)
+    merged, n_merged, tag_bits, sig = _plan(w)
+    n_max = 8 * 128 * 4
+    pair = Pair(64, 0, capacity_log2=12, chunk_rows_log2=12, max_load_factor=0.85)
+    buf = StepBuffers(n_max, 64)
+    steps = 24
+    inputs = []
+    for step in range(steps):
+        b = w.next_step(step)
+        x, off, tags, _ = merged_inputs(w.features, b.ids, merged, 0)
+        G = _grads(w, step, len(x), 64, 0, 0)
+        inputs.append((x, off, tags, G))
+        run_step(pair, buf, x, off, tags, tag_bits, step, G, w.lr, w.eps, one_record_update=True, id_bits=w.id_bits)
+    serial = pair.gpu.export()
+
+    from paper_2505_12663_amd import EmbeddingTable
+    table = EmbeddingTable(64, 0, capacity_log2=12, chunk_rows_log2=12, max_load_factor=0.85)
+    main_s, side_s = torch.cuda.current_stream(), torch.cuda.Stream()
+    sets = [StepBuffers(n_max, 64, with_grad=False), StepBuffers(n_max, 64, with_grad=False)]
+    ev_dedup, ev_free = [torch.cuda.Event(), torch.cuda.Event()], [torch.cuda.Event(), torch.cuda.Event()]
+    dev_in = [(dev_keys(x), torch.from_numpy(off).cuda(), torch.from_numpy(tags).cuda(), torch.from_numpy(G).cuda())
+              for x, off, tags, G in inputs]
+    torch.cuda.synchronize()
+    for e in ev_free:
+        e.record(main_s)
+
+    def dedup_ahead(step):
+        if step >= steps:
+            return
+        dx, doff, dtag, _ = dev_in[step]
+        s = sets[step & 1]
+        side_s.wait_event(ev_free[step & 1])
+        B.emb_tag_dedup(dx, doff, dtag, tag_bits, w.id_bits, None, s.uniq, None, None, s.perm, None, s.seg_of, s.n_unique,
+                        s.err_count, s.tag_dedup_ws, stream=side_s)
+        ev_dedup[step & 1].record(side_s)
+
+    dedup_ahead(0)
+    for step in range(steps):
+        dedup_ahead(step + 1)
+        dx, _, _, dG = dev_in[step]
+        n = dx.numel()
+        s = sets[step & 1]
+        main_s.wait_event(ev_dedup[step & 1])
+        table.find_or_insert(s.uniq, s.n_unique, n, step, buf.row_idx, buf.inserted, touch=False)
+        table.gather(buf.row_idx, s.n_unique, n, buf.uniq_rows)
+        B.emb_expand_sorted(buf.uniq_rows, s.seg_of, s.perm, n, 64, 0, buf.out)
+        B.grad_segment_reduce(dG, 0, s.seg_of, s.perm, n, 64, buf.reduced, buf.reduce_ws)
+        table.apply_adagrad(buf.row_idx, buf.reduced, s.n_unique, n, w.lr, w.eps, step)
+        ev_free[step & 1].record(main_s)
+    side_s.synchronize()
+    piped = table.export()
+    for a, b, what in zip(serial, piped, ("keys", "rows", "accumulators", "last_seen", "touch counts")):
+        assert np.array_equal(a, b), what
+    assert table.stats()["status"] == 0
+    table.close()
+    pair.gpu.close()
