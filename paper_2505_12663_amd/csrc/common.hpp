@@ -157,6 +157,29 @@ __device__ inline uint32_t pack_bf16(float lo, float hi) { return (uint32_t)f32_
 __device__ inline int lane_id() { return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)); }
 __device__ inline uint64_t lanes_below(int lane) { return (1ull << lane) - 1ull; }
 __device__ inline int rank_in(uint64_t mask, int lane) { return __popcll(mask & lanes_below(lane)); }
+// The lanes of the wave whose BITS-wide digit equals this lane's, as the two halves of a 64-lane mask, and from
+// them the lane's rank among those peers and their number.  One ballot per digit bit; the mask is kept in 32-bit
+// halves and narrowed with (mask xnor bit) so that a bit costs four vector instructions (bit extract, compare,
+// two three-input logic ops) - a 64-bit select between the ballot and its complement costs nine.
+struct Peers {
+    uint32_t lo, hi;
+    __device__ inline unsigned rank() const { return __builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, 0u)); }
+    __device__ inline unsigned count() const { return (unsigned)(__popc(lo) + __popc(hi)); }
+};
+template <int BITS>
+__device__ inline Peers match_digit(unsigned d) {
+    Peers p{~0u, ~0u};
+#pragma unroll
+    for (int bit = 0; bit < BITS; ++bit) {
+        uint32_t sel = (uint32_t)__builtin_amdgcn_sbfe((int)d, bit, 1);   // all ones when the bit is set
+        asm("" : "+v"(sel));     // keeps the compare on `sel` itself (otherwise it is re-derived from d with a shift)
+        const uint64_t m = __ballot((int)sel);
+        // p &= ~(m ^ sel): one three-input logic instruction per half (truth table 0x90 = a & (b xnor c))
+        p.lo = __builtin_amdgcn_bitop3_b32(p.lo, (uint32_t)m, sel, 0x90);
+        p.hi = __builtin_amdgcn_bitop3_b32(p.hi, (uint32_t)(m >> 32), sel, 0x90);
+    }
+    return p;
+}
 template <typename T>
 __device__ inline T wave_bcast(T v, int src) { return __shfl(v, src, kWave); }
 __device__ inline uint64_t shfl64(uint64_t v, int src) {

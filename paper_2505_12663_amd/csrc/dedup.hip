@@ -324,15 +324,10 @@ __global__ __launch_bounds__(kScThreads) void k_rs_scatter(DdBuffers b, const Dd
 #pragma unroll
     for (int it = 0; it < kScItems; ++it) {
         const unsigned d = digit_of(key[it], pass); // padding keys are all ones: digit 255, at the tile's end
-        uint64_t peers = ~0ull;
-#pragma unroll
-        for (int bit = 0; bit < 8; ++bit) {
-            const uint64_t m = __ballot((d >> bit) & 1u);
-            peers &= ((d >> bit) & 1u) ? m : ~m;
-        }
-        const unsigned before = s_cnt[wave][d];
-        rnk[it] = before + (unsigned)rank_in(peers, lane);
-        if (rank_in(peers, lane) == 0) s_cnt[wave][d] = before + (unsigned)__popcll(peers);
+        const Peers peers = match_digit<8>(d);
+        const unsigned before = s_cnt[wave][d], r = peers.rank();
+        rnk[it] = before + r;
+        if (r == 0) s_cnt[wave][d] = before + peers.count();
     }
     __syncthreads();
     // thread d < 256: per-wave exclusive offsets of digit d, tile total, global base

@@ -301,15 +301,10 @@ __global__ __launch_bounds__(kScThreads) void k_pk_scatter(PkArgs a, PassPlan p,
         // padding records take the highest digit and sit at the tile's end
         const unsigned d = e < tile_n ? digit_of<WITH_TAG>(rec[it], a, p, ft) : (unsigned)(kRadix - 1);
         dig[it] = d;
-        uint64_t peers = ~0ull;
-#pragma unroll
-        for (int bit = 0; bit < BITS; ++bit) {
-            const uint64_t m = __ballot((d >> bit) & 1u);
-            peers &= ((d >> bit) & 1u) ? m : ~m;
-        }
-        const unsigned before = s_cnt[wave][d];
-        rnk[it] = before + (unsigned)rank_in(peers, lane);
-        if (rank_in(peers, lane) == 0) s_cnt[wave][d] = before + (unsigned)__popcll(peers);
+        const Peers peers = match_digit<BITS>(d);
+        const unsigned before = s_cnt[wave][d], r = peers.rank();
+        rnk[it] = before + r;
+        if (r == 0) s_cnt[wave][d] = before + peers.count();
     }
     __syncthreads();
     // thread d < kRadix: per-wave exclusive offsets of digit d, tile total, global base
