@@ -155,8 +155,11 @@ __device__ inline uint32_t pack_bf16(float lo, float hi) { return (uint32_t)f32_
 
 // ---- wave64 primitives ------------------------------------------------------------------------
 __device__ inline int lane_id() { return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)); }
-__device__ inline uint64_t lanes_below(int lane) { return (1ull << lane) - 1ull; }
-__device__ inline int rank_in(uint64_t mask, int lane) { return __popcll(mask & lanes_below(lane)); }
+// members of `mask` among the lanes below the calling lane (`lane` must be the caller's own lane: the count is two
+// mbcnt instructions instead of a 64-bit shift, two ands and two population counts)
+__device__ inline int rank_in(uint64_t mask, int /*lane*/) {
+    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
 // The lanes of the wave whose BITS-wide digit equals this lane's, as the two halves of a 64-lane mask, and from
 // them the lane's rank among those peers and their number.  One ballot per digit bit; the mask is kept in 32-bit
 // halves and narrowed with (mask xnor bit) so that a bit costs four vector instructions (bit extract, compare,

@@ -167,30 +167,33 @@ __global__ __launch_bounds__(kThreads) void k_pk_hist0(PkArgs a, PassPlan p, uin
         f_last = field_of(ft.off, ft.n_fields, last);
     }
     unsigned errs = 0;
-    unsigned d[kItems];
-    uint64_t raw[kItems];
+    // Two batches of eight IDs per lane: all loads of a batch go out before anything waits, and a digit goes to the
+    // histogram as soon as it is known.  (Sixteen IDs and sixteen digits held at once cost the kernel a quarter of
+    // its resident waves - 74 registers - and with them a second round of blocks.)
+    constexpr int kHalf = kItems / 2;
+#pragma unroll 1
+    for (int h = 0; h < 2; ++h) {
+        const int64_t e0 = wave_base + h * (kHalf * kWave) + lane;
+        uint64_t raw[kHalf];
 #pragma unroll
-    for (int it = 0; it < kItems; ++it) {   // all loads of the thread go out before anything waits
-        const int64_t e = wave_base + it * kWave + lane;
-        raw[it] = e < a.n ? a.x[e] : 0ull;
-    }
+        for (int it = 0; it < kHalf; ++it) raw[it] = e0 + it * kWave < a.n ? a.x[e0 + it * kWave] : 0ull;
 #pragma unroll
-    for (int it = 0; it < kItems; ++it) {
-        const int64_t e = wave_base + it * kWave + lane;
-        d[it] = kMaxRadix;
-        if (e < a.n) {
-            const uint64_t id = checked_id(raw[it], a, &errs);
-            uint64_t k = id;
-            if (need_tag) {
-                const unsigned tag = ft.tag[f_first == f_last ? f_first : field_of(ft.off, ft.n_fields, e)];
-                if (key_out) key_out[e] = ((uint64_t)tag << a.tag_shift) | id;
-                if (WITH_TAG) k |= (uint64_t)tag << a.id_bits;
+        for (int it = 0; it < kHalf; ++it) {
+            const int64_t e = e0 + it * kWave;
+            unsigned d = kMaxRadix;
+            if (e < a.n) {
+                const uint64_t id = checked_id(raw[it], a, &errs);
+                uint64_t k = id;
+                if (need_tag) {
+                    const unsigned tag = ft.tag[f_first == f_last ? f_first : field_of(ft.off, ft.n_fields, e)];
+                    if (key_out) key_out[e] = ((uint64_t)tag << a.tag_shift) | id;
+                    if (WITH_TAG) k |= (uint64_t)tag << a.id_bits;
+                }
+                d = (unsigned)(k >> p.shift) & ((1u << p.bits) - 1u);
             }
-            d[it] = (unsigned)(k >> p.shift) & ((1u << p.bits) - 1u);
+            hist_add_runs(s_hist, d, lane);
         }
     }
-#pragma unroll
-    for (int it = 0; it < kItems; ++it) hist_add_runs(s_hist, d[it], lane);
     for (int o = 32; o > 0; o >>= 1) errs += __shfl_xor(errs, o, kWave);
     if (errs && lane == 0) atomicAdd(err_count, (unsigned long long)errs);
     __syncthreads();
