@@ -209,6 +209,11 @@ __device__ inline int64_t read_count(const int64_t* n_dev, int64_t n_max) {
 // 16-byte vector moves
 struct __attribute__((aligned(16))) V16 { uint32_t x, y, z, w; };
 __device__ inline V16 ld16(const void* p) { return *reinterpret_cast<const V16*>(p); }
+__device__ inline V16 ld16_nt(const void* p) {
+    const uint32_t* q = reinterpret_cast<const uint32_t*>(p);
+    return V16{__builtin_nontemporal_load(q), __builtin_nontemporal_load(q + 1), __builtin_nontemporal_load(q + 2),
+               __builtin_nontemporal_load(q + 3)};
+}
 __device__ inline void st16(void* p, V16 v) { *reinterpret_cast<V16*>(p) = v; }
 __device__ inline void st16_nt(void* p, V16 v) {
     __builtin_nontemporal_store(v.x, reinterpret_cast<uint32_t*>(p) + 0);

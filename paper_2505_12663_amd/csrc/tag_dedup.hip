@@ -484,8 +484,9 @@ __global__ __launch_bounds__(kThreads) void k_pk_emit(PkArgs a, const uint64_t* 
         if (j < a.n) {
             const uint32_t p = (uint32_t)(r[it] & pos_mask);
             if (inverse) inverse[p] = (int32_t)seg;
-            if (perm) perm[j] = (int32_t)p;
-            if (seg_of) seg_of[j] = (int32_t)seg;
+            // the mapping is read again a gigabyte of traffic later (expand, reduce): no cache allocation
+            if (perm) __builtin_nontemporal_store((int32_t)p, &perm[j]);
+            if (seg_of) __builtin_nontemporal_store((int32_t)seg, &seg_of[j]);
             if (head) {
                 // identifier of sorted position j: the last t with tag_start[t] <= j
                 int lo = 0, hi = 256;
