@@ -481,8 +481,9 @@ __global__ __launch_bounds__(kThreads) void k_emit(DdBuffers b, const DdHeader* 
         if (j < n) {
             const uint32_t p = idxs ? idxs[j] : (uint32_t)j;
             if (inverse) inverse[p] = (int32_t)seg;
-            if (perm) perm[j] = (int32_t)p;
-            if (seg_of) seg_of[j] = (int32_t)seg;
+            // the mapping is read again a gigabyte of traffic later (expand, reduce): no cache allocation
+            if (perm) __builtin_nontemporal_store((int32_t)p, &perm[j]);
+            if (seg_of) __builtin_nontemporal_store((int32_t)seg, &seg_of[j]);
             if (head) {
                 uniq[seg] = key[it];
                 if (seg_off) seg_off[seg] = (int32_t)j;

@@ -86,7 +86,7 @@ __device__ inline void copy_rows_body(const HtView& v, char* const* s_values, co
             const int safe = idx < 0 ? 0 : idx;
             const char* p = SRC_TABLE ? staged_row(v, s_values, (uint32_t)safe) : src_base + (size_t)safe * (size_t)row_bytes;
             if (FULL) {
-                val[u] = SRC_TABLE ? ld16_nt(p + sub * 16) : ld16(p + sub * 16);   // table rows are read once: no cache allocation
+                val[u] = (SRC_TABLE && !DST_IDX) ? ld16_nt(p + sub * 16) : ld16(p + sub * 16);   // gather: a table row is read once
             } else {
                 val[u] = V16{0u, 0u, 0u, 0u};
                 if (ok) val[u] = ld16(p + sub * 16);
@@ -425,7 +425,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce_apply(LevelIn in, int dim
             if (lane_on) {
                 char* wp = s_values[r >> fz.v.chunk_log2] + (size_t)(r & chunk_mask) * (size_t)fz.v.row_bytes + sub * kWB;
                 if (!TBL_BF16) {
-                    st16(wp, V16{__float_as_uint(adagrad_w(__uint_as_float(w_.x), acc.f[0], scale)),
+                    st16_nt(wp, V16{__float_as_uint(adagrad_w(__uint_as_float(w_.x), acc.f[0], scale)),
                                  __float_as_uint(adagrad_w(__uint_as_float(w_.y), acc.f[1], scale)),
                                  __float_as_uint(adagrad_w(__uint_as_float(w_.z), acc.f[2], scale)),
                                  __float_as_uint(adagrad_w(__uint_as_float(w_.w), acc.f[3], scale))});
@@ -435,7 +435,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce_apply(LevelIn in, int dim
                     if constexpr (FPL == 8) {
                         const uint32_t o2 = pack_bf16(adagrad_w(bf16lo(w_.z), acc.f[4], scale), adagrad_w(bf16hi(w_.z), acc.f[5], scale));
                         const uint32_t o3 = pack_bf16(adagrad_w(bf16lo(w_.w), acc.f[6], scale), adagrad_w(bf16hi(w_.w), acc.f[7], scale));
-                        st16(wp, V16{o0, o1, o2, o3});
+                        st16_nt(wp, V16{o0, o1, o2, o3});
                     } else {
                         *reinterpret_cast<uint2*>(wp) = make_uint2(o0, o1);
                     }
@@ -470,7 +470,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce_apply(LevelIn in, int dim
             if (group_on && it < items) {
                 const int64_t j = first + it;
                 if (LEVEL1) {
-                    const int32_t p = in.perm[j];
+                    const int32_t p = __builtin_nontemporal_load(&in.perm[j]);
                     my_src[u] = in.via ? in.via[p] : p;
                 } else {
                     my_src[u] = (int)j;
@@ -516,12 +516,12 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce_apply(LevelIn in, int dim
                     const int src = __shfl(pick(my_src, u), sl, kWave);
                     sg_[k] = __shfl(pick(my_seg, u), sl, kWave);
                     rw_[k] = __shfl(pick(my_row, u), sl, kWave);
-                    if (lane_on && sg_[k] >= 0) v_[k] = ld16(in.rows + (size_t)src * (size_t)in.in_row_bytes + sub * 16);
+                    if (lane_on && sg_[k] >= 0) v_[k] = (LEVEL1 ? ld16_nt : ld16)(in.rows + (size_t)src * (size_t)in.in_row_bytes + sub * 16);
                     if (rw_[k] >= 0) {
                         const uint32_t r = (uint32_t)rw_[k];
                         if (lane_on) {
                             const char* wp = s_values[r >> fz.v.chunk_log2] + (size_t)(r & chunk_mask) * (size_t)fz.v.row_bytes + sub * kWB;
-                            if (kWB == 16) w_[k] = ld16(wp);
+                            if (kWB == 16) w_[k] = ld16_nt(wp);
                             else {
                                 const uint2 t = *reinterpret_cast<const uint2*>(wp);
                                 w_[k].x = t.x;
