@@ -252,6 +252,9 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
                                                        float* __restrict__ part_rows, int32_t* __restrict__ part_seg,
                                                        int last_level) {
     constexpr int kGroups = kWave / LPR;
+    // fp32 gradient rows are loaded non-temporally (long-sequence step: reduce -36 us, whole step -17 us); for bf16
+    // gradients, whose fp32 sums are twice the size of the rows read, the same hint cost 0.1 ms per step
+    constexpr bool kNtGrad = LEVEL1 && FPL == 4;
     const int lane = lane_id();
     const int sub = lane % LPR, grp = lane / LPR;
     const int gbase = lane - sub;
@@ -316,7 +319,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
                     const int sl = gbase + f % LPR;
                     const int src = __shfl(my_src[f / LPR], sl, kWave);
                     sg_[k] = __shfl(my_seg[f / LPR], sl, kWave);
-                    if (lane_on && sg_[k] >= 0) v_[k] = (LEVEL1 ? ld16_nt : ld16)(in.rows + (size_t)src * (size_t)in.in_row_bytes + sub * 16);
+                    if (lane_on && sg_[k] >= 0) v_[k] = (kNtGrad ? ld16_nt : ld16)(in.rows + (size_t)src * (size_t)in.in_row_bytes + sub * 16);
                 }
             }
         };
@@ -394,6 +397,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce_apply(LevelIn in, int dim
     }
     __syncthreads();
     constexpr int kGroups = kWave / LPR;
+    constexpr bool kNtGrad = LEVEL1 && FPL == 4;    // as in k_seg_reduce
     constexpr int kWB = FPL * (TBL_BF16 ? 2 : 4);   // bytes of the table row a lane owns (16, or 8 for bf16 rows at upper levels)
     const int lane = lane_id();
     const int sub = lane % LPR, grp = lane / LPR;
@@ -516,7 +520,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce_apply(LevelIn in, int dim
                     const int src = __shfl(pick(my_src, u), sl, kWave);
                     sg_[k] = __shfl(pick(my_seg, u), sl, kWave);
                     rw_[k] = __shfl(pick(my_row, u), sl, kWave);
-                    if (lane_on && sg_[k] >= 0) v_[k] = (LEVEL1 ? ld16_nt : ld16)(in.rows + (size_t)src * (size_t)in.in_row_bytes + sub * 16);
+                    if (lane_on && sg_[k] >= 0) v_[k] = (kNtGrad ? ld16_nt : ld16)(in.rows + (size_t)src * (size_t)in.in_row_bytes + sub * 16);
                     if (rw_[k] >= 0) {
                         const uint32_t r = (uint32_t)rw_[k];
                         if (lane_on) {
