@@ -180,7 +180,7 @@ __device__ inline void first_line_pass(const HtView& v, uint64_t my_key, bool my
     for (int r = 0; r < kLineSlots; ++r) {
         kr[r] = shfl64(my_key, gbase + r);
         line[r] = probe_start(slot_hash(kr[r]), v.line_mask);
-        ent[r] = ld16_nt(v.slots + line[r] * kLineSlots + sub);   // a slot line is read once per step: no cache allocation
+        ent[r] = ld16(v.slots + line[r] * kLineSlots + sub);
     }
     *found_slot = -1;
     *found_row = kRowInvalid;
