@@ -413,6 +413,14 @@ int ht_set_hot_storage(emb_table_t* t, float* hot_values, uint32_t* hot_free, in
 int ht_promote(emb_table_t* t, const int32_t* row_idx, const int64_t* n_dev, int64_t n_max, uint32_t min_freq,
                int64_t* n_promoted, void* stream);
 
+/* Demote by idle time (App. C: the hot set is partitioned dynamically, so it follows the access pattern both ways;
+ * the criterion is this library's): every hot row whose key no find-or-insert has touched for `idle` steps
+ * (now - last_seen >= idle, as in ht_evict) gives its master back to the hot store; its 16-bit row becomes the
+ * master rounded to nearest even - the values lookups delivered for it anyway - and later updates round like any
+ * cold row's.  *n_demoted [device, optional] receives the number demoted by this call.  Scans the key structure
+ * (one pass over all slots).  EMB_ERR_NO_STORAGE without a hot store. */
+int ht_demote(emb_table_t* t, uint32_t now, uint32_t idle, int64_t* n_demoted, void* stream);
+
 /* Unordered dump of the masters: keys[cap], values[cap, dim] fp32 (optional); *n [device] = number of
  * hot rows (may exceed cap; only the first cap are written). */
 int ht_export_hot(emb_table_t* t, uint64_t* keys, float* values, int64_t cap, int64_t* n, void* stream);

@@ -56,6 +56,7 @@ def lib():
         L.orc_export.restype = C.c_int64
         L.orc_promote.restype = C.c_int64
         L.orc_export_hot.restype = C.c_int64
+        L.orc_demote.restype = C.c_int64
         _lib = L
     return _lib
 
@@ -242,6 +243,10 @@ class Table:
     def promote(self, key, min_freq: int) -> int:
         key = self._keys(key)
         return int(lib().orc_promote(self._h, _p(key, C.c_uint64), C.c_int64(len(key)), C.c_uint32(min_freq)))
+
+    def demote(self, now: int, idle: int) -> int:
+        """Hot rows untouched for `idle` steps become cold again (master rounded into the 16-bit row); how many."""
+        return int(lib().orc_demote(self._h, C.c_uint32(now), C.c_uint32(idle)))
 
     def export_hot(self):
         n = int(lib().orc_export_hot(self._h, None, None))

@@ -475,6 +475,23 @@ int64_t orc_promote(void* h, const uint64_t* key, int64_t n, uint32_t min_freq) 
     }
     return done;
 }
+// Demote: the partition into hot and cold keys follows the access pattern both ways (App. C: hot sets are
+// partitioned dynamically).  Every hot row that no lookup has touched for `idle` steps (now - last_seen >= idle)
+// gives its master back to the hot store: the 16-bit row becomes the master rounded to nearest even - which is
+// what lookups delivered for it anyway - and later updates round as for any cold row.  Returns how many.
+int64_t orc_demote(void* h, uint32_t now, uint32_t idle) {
+    Table& t = *static_cast<Table*>(h);
+    int64_t done = 0;
+    for (auto& kv : t.map) {
+        Row& r = kv.second;
+        if (!r.hot || now - r.last_seen < idle) continue;
+        for (int j = 0; j < t.dim; ++j) r.w[j] = bf16_bits_to_float(float_to_bf16_bits(r.w[j]));
+        r.hot = false;
+        t.hot_used -= 1;
+        done += 1;
+    }
+    return done;
+}
 // Masters ordered by key: keys[n_hot], values[n_hot, dim] (either may be null).  Returns n_hot.
 int64_t orc_export_hot(void* h, uint64_t* keys, float* values) {
     Table& t = *static_cast<Table*>(h);

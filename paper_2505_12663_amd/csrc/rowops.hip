@@ -854,6 +854,43 @@ __global__ __launch_bounds__(kBlock) void k_promote(HtView v, const int32_t* __r
     }
 }
 
+// Demotion: one lane per slot decides (a live key whose row has a master and has not been looked up for `idle`
+// steps); the slot of the master goes back on the hot store's free stack and the record's hot field is cleared;
+// the wave then takes its demoting rows in turn and writes the master, rounded to nearest even, into the 16-bit
+// row - the values lookups delivered for the row anyway.
+__global__ __launch_bounds__(kBlock) void k_demote(HtView v, uint64_t n_slots, uint32_t now, uint32_t idle,
+                                                   unsigned long long* n_demoted) {
+    const int lane = lane_id();
+    const uint64_t slot = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    uint32_t row = kRowInvalid, hot = 0;
+    if (slot < n_slots) {
+        const V16 e = ld16(v.slots + slot);
+        const uint64_t k = ((uint64_t)e.y << 32) | e.x;
+        if (k != kEmptyKey && k != kTombKey && e.z != kRowInvalid) {
+            const RowMeta m = *meta_ptr(v, e.z);
+            if (m.hot != 0 && now - m.last_seen >= idle) {
+                row = e.z;
+                hot = m.hot;
+            }
+        }
+    }
+    uint64_t m = __ballot(hot != 0);
+    if (!m) return;
+    if (n_demoted && lane == __ffsll((unsigned long long)m) - 1) atomicAdd(n_demoted, (unsigned long long)__popcll(m));
+    if (hot != 0) { // hot rows are few: one atomic each
+        v.hot_free[atomicAdd(&v.st->head.hot_free_count, 1)] = hot - 1u;
+        meta_ptr(v, row)->hot = 0u;
+    }
+    while (m) {
+        const int src = __ffsll((unsigned long long)m) - 1;
+        m &= m - 1;
+        const uint32_t r = __shfl(row, src, kWave);
+        const float* hp = v.hot_values + (size_t)(__shfl(hot, src, kWave) - 1u) * v.dim;
+        uint32_t* d32 = reinterpret_cast<uint32_t*>(const_cast<char*>(chunk_row_cptr(v, r)));
+        for (int w = lane; w < v.dim / 2; w += kWave) d32[w] = pack_bf16(hp[2 * w], hp[2 * w + 1]);
+    }
+}
+
 // out[dst,:] = row (source index = via ? via[index[j]] : index[j]; dst = dst_index ? dst_index[j] : j);
 // index -1 gives a zero row.
 template <int LPR>
@@ -1050,6 +1087,21 @@ int ht_promote(emb_table_t* t, const int32_t* row_idx, const int64_t* n_dev, int
     HtView v = t->view();
     MTGR_MIXED_LAUNCH(k_promote, t->row_bytes / 16, n_max, s, v, row_idx, n_dev, n_max, min_freq,
                       reinterpret_cast<unsigned long long*>(n_promoted));
+    MTGR_LAUNCH_CHECK();
+    return t->snapshot(s);
+}
+
+int ht_demote(emb_table_t* t, uint32_t now, uint32_t idle, int64_t* n_demoted, void* stream) {
+    if (!t) return EMB_ERR_INVALID_ARG;
+    if (!t->hot_values || !t->slots) return EMB_ERR_NO_STORAGE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (n_demoted) {
+        hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(n_demoted), 2);
+        MTGR_LAUNCH_CHECK();
+    }
+    const uint64_t n_slots = 1ull << t->cap_log2;
+    hipLaunchKernelGGL(k_demote, dim3((unsigned)((n_slots + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, t->view(), n_slots, now,
+                       idle, reinterpret_cast<unsigned long long*>(n_demoted));
     MTGR_LAUNCH_CHECK();
     return t->snapshot(s);
 }

@@ -178,6 +178,9 @@ class EmbeddingTable:
     def promote(self, row_idx, n_dev, n_max: int, min_freq: int, n_promoted=None) -> None:
         B.ht_promote(self.h, row_idx, n_dev, n_max, min_freq, n_promoted)
 
+    def demote(self, now: int, idle: int, n_demoted=None) -> None:
+        B.ht_demote(self.h, now, idle, n_demoted)
+
     def export_hot(self):
         """Host copy of the fp32 masters, sorted by key: (keys uint64, values float32 [n, dim])."""
         cap = max(self.hot_rows, 1)

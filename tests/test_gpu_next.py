@@ -336,6 +336,73 @@ def test_hot_cold_rows_match_checker(dim):
     table.close()
 
 
+@pytest.mark.parametrize("dim", [64, 24, 256])
+def test_demotion_by_idle_time_matches_checker(dim):
+    """The hot set follows the access pattern both ways: hot rows no lookup has touched for `idle` steps become cold
+    again.  The demoted key set, the remaining masters, the delivered rows (unchanged by a demotion, bit for bit), the
+    store's bookkeeping and a further update of hot, demoted and cold rows must follow the checker."""
+    from harness import RTOL_BF16
+    lr, eps = 0.05, 1e-8
+    table, ot = _mixed_pair(dim, hot_rows=600)
+    rng = np.random.default_rng(100 + dim)
+    pool = (np.arange(1, 2001, dtype=np.uint64) * np.uint64(0x9E3779B1)) & np.uint64((1 << 40) - 1)
+    for step in range(3):
+        _insert(table, ot, pool, step)
+    _insert(table, ot, pool[:600], 3)                            # 600 keys reach four touches: exactly the store's size
+    allk = np.sort(pool)
+    row_idx = torch.empty(len(allk), dtype=torch.int32, device="cuda")
+    table.find(dev_keys(allk), None, len(allk), row_idx)
+    n_dev = torch.zeros(1, dtype=torch.int64, device="cuda")
+    table.promote(row_idx, None, len(allk), 4, n_dev)
+    assert int(n_dev.item()) == 600 and ot.promote(allk, 4) == 600
+    hot_keys = table.export_hot()[0]
+    assert np.array_equal(hot_keys, ot.export_hot()[0]) and np.array_equal(hot_keys, np.sort(pool[:600]))
+    # a drifting working set: keys 300 .. 1499 of the pool stay in use, so half of the hot keys fall idle
+    for step in range(4, 12):
+        ks = np.unique(pool[rng.integers(300, 1500, size=900)])
+        ri = _insert(table, ot, ks, step)
+        g = normal_grads(9, step, len(ks), dim)
+        table.apply_adagrad(ri, torch.from_numpy(g).cuda(), None, len(ks), lr, eps)
+        ot.apply_adagrad(ks, g, lr, eps)
+    out = torch.empty((len(allk), dim), dtype=torch.bfloat16, device="cuda")
+    table.gather(row_idx, None, len(allk), out)
+    before = out.clone()
+    table.demote(12, 6, n_dev)
+    want = ot.demote(12, 6)
+    assert 0 < want < 600 and int(n_dev.item()) == want
+    hk, hv = table.export_hot()
+    ok, ov = ot.export_hot()
+    assert np.array_equal(hk, ok)                                 # who stays hot is unique
+    assert close_rows(hv, ov.astype(np.float64), lr, RTOL_F32)
+    table.gather(row_idx, None, len(allk), out)
+    assert torch.equal(out.view(torch.int16), before.view(torch.int16))   # a demotion changes no delivered bit
+    st = table.stats()
+    assert st["hot_rows_free"] == want and st["hot_rows_used"] == 600 and st["status"] == 0
+    table.demote(12, 6, n_dev)
+    assert int(n_dev.item()) == 0                                 # nothing is demoted twice
+    # hot, demoted and never-hot rows take one more update each; the freed masters serve other keys
+    ri = _insert(table, ot, allk, 12)
+    g = normal_grads(9, 12, len(allk), dim)
+    table.apply_adagrad(ri, torch.from_numpy(g).cuda(), None, len(allk), lr, eps)
+    ot.apply_adagrad(allk, g, lr, eps)
+    ek, ev, ea, el, ef = table.export()
+    kk, kv, ka, kl, kf = ot.export()
+    assert np.array_equal(ek, kk) and np.array_equal(el, kl) and np.array_equal(ef, kf)
+    # A demoted row has been rounded to 16 bits twice since its master was last compared (once by the demotion, once by
+    # this update), each time from values that agree with the checker's only to fp32 accuracy: two 16-bit roundings can
+    # differ by two spacings, so these rows get twice the 16-bit tolerance; all other rows the usual one.
+    was_demoted = np.isin(ek, np.setdiff1d(hot_keys, hk))
+    assert was_demoted.sum() == want
+    assert close_rows(ev[~was_demoted], kv[~was_demoted].astype(np.float64), lr, RTOL_BF16)
+    assert close_rows(ev[was_demoted], kv[was_demoted].astype(np.float64), lr, 2 * RTOL_BF16)
+    assert np.allclose(ea, ka, rtol=RTOL_F32, atol=1e-12)
+    table.promote(ri, None, len(allk), 5, n_dev)
+    assert int(n_dev.item()) == want                              # exactly the freed masters are handed out again
+    st = table.stats()
+    assert st["hot_rows_free"] == 0 and st["hot_rows_used"] == 600
+    table.close()
+
+
 def test_hot_store_full_keeps_the_rest_cold():
     dim = 32
     table, ot = _mixed_pair(dim, hot_rows=5)

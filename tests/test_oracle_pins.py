@@ -512,3 +512,41 @@ def test_hot_store_capacity_and_release_on_eviction():
     assert t.promote(keys, 2) == 1 and np.array_equal(t.export_hot()[0], keys[1:4])
     with pytest.raises(ValueError):
         oracle.Table(4).set_hot(3)                                                    # fp32 tables have no cold form
+
+
+def test_demotion_keeps_what_lookups_deliver_and_frees_the_master():
+    """Demotion by idle time (App. C: the hot set follows the access pattern).  Pins: the demoted set is the brute-force
+    predicate over the dump; a lookup delivers the same bits before and after (a hot row is delivered as its rounded
+    master, which is exactly what the 16-bit row becomes); the master returns to the store; and from then on the row
+    rounds like any cold row - one more update equals torch's bf16 arithmetic on the delivered values."""
+    D, lr, eps = 16, 0.05, 1e-8
+    keys = np.arange(1, 13, dtype=np.uint64) * np.uint64(104729)
+    t = oracle.Table(D, oracle.BF16, init_scale=1.0)
+    for s in range(3):
+        t.find_or_insert(keys, s)
+    t.set_hot(8)
+    assert t.promote(keys, 3) == 8                       # the first eight, in the order given
+    rng = np.random.default_rng(5)
+    for s in range(3, 9):                                # keys[::2] stay in use, the others fall idle after step 2
+        t.find_or_insert(keys[::2], s)
+        t.apply_adagrad(keys, rng.standard_normal((len(keys), D)).astype(np.float32), lr, eps)
+    hot_before = t.export_hot()[0]
+    assert np.array_equal(hot_before, keys[:8])
+    _, _, _, last_seen, _ = t.export()
+    before = t.lookup(keys)
+    now, idle = 9, 5
+    want = np.array([k for k, ls in zip(np.sort(keys), last_seen) if k in set(hot_before) and now - int(ls) >= idle])
+    assert t.demote(now, idle) == len(want) == 4         # keys[1], [3], [5], [7]
+    assert np.array_equal(t.export_hot()[0], np.setdiff1d(hot_before, want))
+    assert np.array_equal(t.lookup(keys), before)        # delivered bits unchanged
+    assert t.demote(now, idle) == 0                      # nothing is demoted twice
+    assert t.promote(keys[8:], 3) == 4                   # the freed masters serve other keys
+    # a demoted row now updates in 16-bit arithmetic: torch casts as the independent statement
+    k = want[:1]
+    w = torch.from_numpy(t.lookup(k)[0].copy())
+    _, _, acc0, _, _ = t.peek(k)
+    g = rng.standard_normal((1, D)).astype(np.float32)
+    t.apply_adagrad(k, g, lr, eps)
+    acc = np.float64(acc0[0]) + np.mean(g[0].astype(np.float64) ** 2)
+    ref = (w.double() - lr * torch.from_numpy(g[0]).double() / (np.sqrt(np.float32(acc).astype(np.float64)) + eps))
+    assert torch.equal(torch.from_numpy(t.lookup(k)[0]), ref.float().to(torch.bfloat16).float())
