@@ -421,6 +421,14 @@ int ht_promote(emb_table_t* t, const int32_t* row_idx, const int64_t* n_dev, int
  * (one pass over all slots).  EMB_ERR_NO_STORAGE without a hot store. */
 int ht_demote(emb_table_t* t, uint32_t now, uint32_t idle, int64_t* n_demoted, void* stream);
 
+/* Restore masters from a dump (App. C "Checkpoint Resuming" for a table with hot rows): for every u < n
+ * whose row row_idx[u] [device; -1 skipped] has a master, the master becomes masters[u,:] [device, fp32,
+ * row-major, 16-byte aligned], e.g. what ht_export_hot wrote; rows without a master are skipped (promote them
+ * first: ht_promote with min_freq 0 gives every listed row a master).  The 16-bit row is left as it is (it is
+ * stale while a master exists).  *n_written [device, optional] receives the number of masters written.
+ * EMB_ERR_NO_STORAGE without a hot store. */
+int ht_put_hot(emb_table_t* t, const int32_t* row_idx, const float* masters, int64_t n, int64_t* n_written, void* stream);
+
 /* Unordered dump of the masters: keys[cap], values[cap, dim] fp32 (optional); *n [device] = number of
  * hot rows (may exceed cap; only the first cap are written). */
 int ht_export_hot(emb_table_t* t, uint64_t* keys, float* values, int64_t cap, int64_t* n, void* stream);

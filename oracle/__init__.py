@@ -57,6 +57,8 @@ def lib():
         L.orc_promote.restype = C.c_int64
         L.orc_export_hot.restype = C.c_int64
         L.orc_demote.restype = C.c_int64
+        L.orc_put_hot.restype = C.c_int64
+        L.orc_put.restype = C.c_int64
         _lib = L
     return _lib
 
@@ -247,6 +249,24 @@ class Table:
     def demote(self, now: int, idle: int) -> int:
         """Hot rows untouched for `idle` steps become cold again (master rounded into the 16-bit row); how many."""
         return int(lib().orc_demote(self._h, C.c_uint32(now), C.c_uint32(idle)))
+
+    def put(self, key, values, acc, last_seen, freq) -> int:
+        """Restore dumped entries of keys that are present (rows as delivered, accumulators, last-seen steps, touch counts)."""
+        key = self._keys(key)
+        values = np.ascontiguousarray(values, dtype=np.float32)
+        acc = np.ascontiguousarray(acc, dtype=np.float32)
+        last_seen = np.ascontiguousarray(last_seen, dtype=np.uint32)
+        freq = np.ascontiguousarray(freq, dtype=np.uint32)
+        assert values.shape == (len(key), self.dim) and len(acc) == len(last_seen) == len(freq) == len(key)
+        return int(lib().orc_put(self._h, _p(key, C.c_uint64), C.c_int64(len(key)), _p(values, C.c_float), _p(acc, C.c_float),
+                                 _p(last_seen, C.c_uint32), _p(freq, C.c_uint32)))
+
+    def put_hot(self, key, values) -> int:
+        """Masters of the listed hot keys := values (fp32 [n, dim]); absent or cold keys are skipped; how many written."""
+        key = self._keys(key)
+        values = np.ascontiguousarray(values, dtype=np.float32)
+        assert values.shape == (len(key), self.dim)
+        return int(lib().orc_put_hot(self._h, _p(key, C.c_uint64), C.c_int64(len(key)), _p(values, C.c_float)))
 
     def export_hot(self):
         n = int(lib().orc_export_hot(self._h, None, None))

@@ -492,6 +492,39 @@ int64_t orc_demote(void* h, uint32_t now, uint32_t idle) {
     }
     return done;
 }
+// Restore dumped entries (App. C "Checkpoint Resuming"): every listed key that is present takes the dumped row
+// (values[i,:] as a lookup delivered it; exact for a 16-bit table since the dump holds 16-bit values), accumulator,
+// last-seen step and touch count.  A hot row's master follows the row.  Returns how many keys were present.
+int64_t orc_put(void* h, const uint64_t* key, int64_t n, const float* values, const float* acc,
+                const uint32_t* last_seen, const uint32_t* freq) {
+    Table& t = *static_cast<Table*>(h);
+    int64_t done = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        auto it = t.map.find(key[i]);
+        if (it == t.map.end()) continue;
+        Row& r = it->second;
+        if (values) for (int j = 0; j < t.dim; ++j) r.w[j] = values[i * t.dim + j];
+        if (acc) r.acc = acc[i];
+        if (last_seen) r.last_seen = last_seen[i];
+        if (freq) r.freq = freq[i];
+        done += 1;
+    }
+    return done;
+}
+// Restore masters from a dump (App. C "Checkpoint Resuming" for a table with hot rows): the master of every listed
+// key that is present and hot becomes values[i,:] (fp32, as ht_export_hot / orc_export_hot wrote it); keys that are
+// absent or cold are skipped.  Returns how many masters were written.
+int64_t orc_put_hot(void* h, const uint64_t* key, int64_t n, const float* values) {
+    Table& t = *static_cast<Table*>(h);
+    int64_t done = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        auto it = t.map.find(key[i]);
+        if (it == t.map.end() || !it->second.hot) continue;
+        for (int j = 0; j < t.dim; ++j) it->second.w[j] = values[i * t.dim + j];
+        done += 1;
+    }
+    return done;
+}
 // Masters ordered by key: keys[n_hot], values[n_hot, dim] (either may be null).  Returns n_hot.
 int64_t orc_export_hot(void* h, uint64_t* keys, float* values) {
     Table& t = *static_cast<Table*>(h);

@@ -56,7 +56,7 @@ EXPORTS = [
     "ht_stats", "emb_tag_keys", "emb_dedup_workspace_bytes", "emb_dedup", "ht_find_or_insert", "ht_find",
     "ht_gather", "emb_expand", "emb_expand_sorted", "grad_segment_reduce_workspace_bytes", "grad_segment_reduce",
     "ht_apply_adagrad", "ht_apply_adam", "ht_gather_expand_sorted", "emb_pool_workspace_bytes", "emb_pool_bags",
-    "grad_segment_reduce_pooled", "ht_evict", "ht_export", "ht_put", "ht_set_hot_storage", "ht_promote", "ht_demote", "ht_export_hot",
+    "grad_segment_reduce_pooled", "ht_evict", "ht_export", "ht_put", "ht_set_hot_storage", "ht_promote", "ht_demote", "ht_put_hot", "ht_export_hot",
     "ht_find_or_insert_notouch", "ht_apply_adagrad_touch", "grad_reduce_apply_adagrad",
     "ht_find_or_insert_retry", "ht_clear_status", "emb_dedup_noalloc",
     "emb_tag_dedup_workspace_bytes", "emb_tag_dedup",
@@ -116,6 +116,7 @@ def load():
         "ht_set_hot_storage": (C.c_int, [vp, vp, vp, i64, vp]),
         "ht_promote": (C.c_int, [vp, vp, vp, i64, u32, vp, vp]),
         "ht_demote": (C.c_int, [vp, u32, u32, vp, vp]),
+        "ht_put_hot": (C.c_int, [vp, vp, vp, i64, vp, vp]),
         "ht_export_hot": (C.c_int, [vp, vp, vp, i64, vp, vp]),
     }
     for name, (res, args) in sig.items():
@@ -362,6 +363,10 @@ def ht_promote(h, row_idx, n_dev, n_max: int, min_freq: int, n_promoted=None, st
 
 def ht_demote(h, now: int, idle: int, n_demoted=None, stream=None) -> None:
     _check(load().ht_demote(h, now, idle, _ptr(n_demoted), _stream(stream)), "ht_demote")
+
+
+def ht_put_hot(h, row_idx, masters, n: int, n_written=None, stream=None) -> None:
+    _check(load().ht_put_hot(h, _ptr(row_idx), _ptr(masters), n, _ptr(n_written), _stream(stream)), "ht_put_hot")
 
 
 def ht_export_hot(h, keys, values, n, stream=None) -> None:

@@ -999,6 +999,24 @@ __global__ __launch_bounds__(kBlock) void k_put_rows(HtView v, const int32_t* __
     }
 }
 
+// masters[hot(row_idx[u]) - 1, :] = src[u,:] for the rows that have a master (checkpoint import of the fp32 copies
+// ht_export_hot dumped); one lane per 16-byte vector of four floats.
+__global__ __launch_bounds__(kBlock) void k_put_hot(HtView v, const int32_t* __restrict__ row_idx,
+                                                    const float* __restrict__ src, int64_t n,
+                                                    unsigned long long* n_written) {
+    const int vecs = v.dim / 4;
+    const int64_t item = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t u = item / vecs;
+    const int sub = (int)(item % vecs);
+    if (u >= n) return;
+    const int ri = row_idx[u];
+    if (ri < 0) return;
+    const uint32_t hot = meta_ptr(v, (uint32_t)ri)->hot;
+    if (hot == 0) return;
+    st16(v.hot_values + (size_t)(hot - 1u) * v.dim + sub * 4, ld16(src + (size_t)u * v.dim + sub * 4));
+    if (sub == 0 && n_written) atomicAdd(n_written, 1ull);
+}
+
 // ---------------------------------------------------------------------------- sparse Adam
 // The optimizer the paper trains with (Sec. 4.1), in its lazy / sparse form: only the listed rows
 // move.  m = b1 m + (1-b1) g;  v = b2 v + (1-b2) g^2;  w -= step_size * m / (sqrt(v) + eps) with
@@ -1329,6 +1347,24 @@ int ht_put(emb_table_t* t, const int32_t* row_idx, const void* values, const flo
     const unsigned grid = (unsigned)((n * vecs + kBlock - 1) / kBlock);
     hipLaunchKernelGGL(k_put_rows, dim3(grid), dim3(kBlock), 0, static_cast<hipStream_t>(stream), v, row_idx,
                        static_cast<const char*>(values), acc, last_seen, freq, n);
+    MTGR_LAUNCH_CHECK();
+    return EMB_OK;
+}
+
+int ht_put_hot(emb_table_t* t, const int32_t* row_idx, const float* masters, int64_t n, int64_t* n_written, void* stream) {
+    if (!t || n < 0 || n > 0x7FFFFFFFll) return EMB_ERR_INVALID_ARG;
+    if (!t->hot_values) return EMB_ERR_NO_STORAGE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (n_written) {
+        hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(n_written), 2);
+        MTGR_LAUNCH_CHECK();
+    }
+    if (n == 0) return EMB_OK;
+    if (!row_idx || !masters || (reinterpret_cast<uintptr_t>(masters) & 15)) return EMB_ERR_INVALID_ARG;
+    HtView v = t->view();
+    const int vecs = v.dim / 4;
+    hipLaunchKernelGGL(k_put_hot, dim3((unsigned)((n * vecs + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, v, row_idx, masters, n,
+                       reinterpret_cast<unsigned long long*>(n_written));
     MTGR_LAUNCH_CHECK();
     return EMB_OK;
 }

@@ -181,6 +181,19 @@ class EmbeddingTable:
     def demote(self, now: int, idle: int, n_demoted=None) -> None:
         B.ht_demote(self.h, now, idle, n_demoted)
 
+    def import_hot(self, keys, masters) -> int:
+        """Restore dumped masters (keys int64 device tensor, masters fp32 [n, dim]): the keys must be in the table; each
+        gets a master (while the store has room) holding the dumped values.  Returns how many masters were written."""
+        n = keys.numel()
+        if n == 0:
+            return 0
+        row_idx = torch.empty(n, dtype=torch.int32, device=self.device)
+        self.find(keys.contiguous(), None, n, row_idx)
+        self.promote(row_idx, None, n, 0)
+        cnt = torch.zeros(1, dtype=torch.int64, device=self.device)
+        B.ht_put_hot(self.h, row_idx, masters.contiguous(), n, cnt)
+        return int(cnt.item())
+
     def export_hot(self):
         """Host copy of the fp32 masters, sorted by key: (keys uint64, values float32 [n, dim])."""
         cap = max(self.hot_rows, 1)

@@ -403,6 +403,68 @@ def test_demotion_by_idle_time_matches_checker(dim):
     table.close()
 
 
+def test_checkpoint_of_a_table_with_hot_rows_restores_its_masters():
+    """Dump = the 16-bit view of every row (ht_export) plus the fp32 masters (ht_export_hot).  A table restored from both
+    (ht_put, then ht_promote with min_freq 0 and ht_put_hot for the dumped masters) holds the dumped state bit for bit,
+    agrees with the checker restored the same way, and keeps following the original through further updates."""
+    from harness import RTOL_BF16
+    dim, lr, eps = 64, 0.05, 1e-8
+    table, ot = _mixed_pair(dim, hot_rows=400)
+    rng = np.random.default_rng(77)
+    pool = (np.arange(1, 1201, dtype=np.uint64) * np.uint64(0x9E3779B1)) & np.uint64((1 << 40) - 1)
+    for step in range(3):
+        _insert(table, ot, pool, step)
+    ri = _insert(table, ot, pool[:300], 3)
+    n_dev = torch.zeros(1, dtype=torch.int64, device="cuda")
+    table.promote(ri, None, 300, 4, n_dev)
+    assert int(n_dev.item()) == 300 and ot.promote(pool[:300], 4) == 300
+    for step in range(4, 9):
+        ks = np.unique(pool[rng.integers(0, 1200, size=700)])
+        ri = _insert(table, ot, ks, step)
+        g = normal_grads(21, step, len(ks), dim)
+        table.apply_adagrad(ri, torch.from_numpy(g).cuda(), None, len(ks), lr, eps)
+        ot.apply_adagrad(ks, g, lr, eps)
+    dump = table.export_device()
+    ref = table.export()
+    hk, hv = table.export_hot()
+    # ---- restore on both sides
+    t2 = EmbeddingTable(dim, B.BF16, capacity_log2=13, chunk_rows_log2=10, hot_rows=400)
+    t2.import_rows(*dump)
+    assert t2.import_hot(dev_keys(hk), torch.from_numpy(hv).cuda()) == len(hk)
+    o2 = oracle.Table(dim, oracle.BF16)
+    ok_, ov_, oa_, ol_, of_ = ot.export()
+    o2.find_or_insert(ok_, 0)
+    assert o2.put(ok_, ov_, oa_, ol_, of_) == len(ok_)
+    o2.set_hot(400)
+    ohk, ohv = ot.export_hot()
+    assert o2.promote(ohk, 0) == len(ohk) and o2.put_hot(ohk, ohv) == len(ohk)
+    for a, b in zip(ref, t2.export()):
+        assert np.array_equal(a, b)                                     # rows as delivered, accumulators, counters
+    hk2, hv2 = t2.export_hot()
+    assert np.array_equal(hk2, hk) and np.array_equal(hv2, hv)          # masters bit for bit
+    assert np.array_equal(hk2, o2.export_hot()[0])
+    st = t2.stats()
+    assert st["hot_rows_used"] == len(hk) and st["status"] == 0
+    # ---- original and restored table take the same further updates
+    for step in range(9, 12):
+        ks = np.unique(pool[rng.integers(0, 1200, size=700)])
+        g = torch.from_numpy(normal_grads(21, step, len(ks), dim)).cuda()
+        for t in (table, t2):
+            r = torch.empty(len(ks), dtype=torch.int32, device="cuda")
+            t.find_or_insert(dev_keys(ks), None, len(ks), step, r)
+            t.apply_adagrad(r, g, None, len(ks), lr, eps)
+        for o in (ot, o2):
+            o.find_or_insert(ks, step)
+            o.apply_adagrad(ks, g.cpu().numpy(), lr, eps)
+    for a, b in zip(table.export(), t2.export()):
+        assert np.array_equal(a, b)
+    assert np.array_equal(table.export_hot()[1], t2.export_hot()[1])
+    assert close_rows(t2.export_hot()[1], o2.export_hot()[1].astype(np.float64), lr, RTOL_F32)
+    assert close_rows(t2.export()[1], o2.export()[1].astype(np.float64), lr, RTOL_BF16)
+    table.close()
+    t2.close()
+
+
 def test_hot_store_full_keeps_the_rest_cold():
     dim = 32
     table, ot = _mixed_pair(dim, hot_rows=5)

@@ -550,3 +550,46 @@ def test_demotion_keeps_what_lookups_deliver_and_frees_the_master():
     acc = np.float64(acc0[0]) + np.mean(g[0].astype(np.float64) ** 2)
     ref = (w.double() - lr * torch.from_numpy(g[0]).double() / (np.sqrt(np.float32(acc).astype(np.float64)) + eps))
     assert torch.equal(torch.from_numpy(t.lookup(k)[0]), ref.float().to(torch.bfloat16).float())
+
+
+def test_restored_masters_continue_where_the_dump_left_off():
+    """Checkpoint of a table with hot rows (App. C): the dump holds the 16-bit view of every row and the fp32 masters.
+    Pins: a table restored with its masters delivers the same bits and then follows the original bit for bit through
+    many small updates; restored without them (all rows cold) it loses those updates to 16-bit rounding, which is the
+    closed form of the hot/cold pin above (constant unit gradient: shift = lr * sum 1/sqrt(s))."""
+    D, T, lr = 8, 400, 1e-4
+    keys = np.array([21, 22, 23], dtype=np.uint64)
+    a = oracle.Table(D, oracle.BF16, init_scale=1.0)
+    a.find_or_insert(keys, 0)
+    a.find_or_insert(keys[:2], 1)
+    a.set_hot(4)
+    assert a.promote(keys, 2) == 2
+    g = np.ones((3, D), dtype=np.float32)
+    for _ in range(T):
+        a.apply_adagrad(keys, g, lr, 0.0)
+    dk, dv, dacc, dls, dfq = a.export()
+    hk, hv = a.export_hot()
+
+    def restore(with_masters: bool):
+        b = oracle.Table(D, oracle.BF16, init_scale=1.0)
+        b.find_or_insert(dk, 0)
+        b.put(dk, dv, dacc, dls, dfq)
+        b.set_hot(4)
+        if with_masters:
+            assert b.promote(hk, 0) == len(hk) and b.put_hot(hk, hv) == len(hk)
+            assert b.put_hot(keys[2:], hv[:1]) == 0          # a cold key is skipped
+        return b
+
+    full, cold = restore(True), restore(False)
+    assert np.array_equal(full.export_hot()[1], hv) and np.array_equal(full.lookup(keys), a.lookup(keys))
+    assert np.array_equal(cold.lookup(keys), a.lookup(keys))  # the 16-bit view is what the dump delivered
+    for _ in range(T):
+        for t in (a, full, cold):
+            t.apply_adagrad(keys, g, lr, 0.0)
+    assert np.array_equal(full.export_hot()[1], a.export_hot()[1]) and np.array_equal(full.lookup(keys), a.lookup(keys))
+    steps = np.arange(T + 1, 2 * T + 1, dtype=np.float64)
+    shift = lr * np.sum(1.0 / np.sqrt(steps))                # what the second T steps move a value by
+    w_mid = hv.astype(np.float64)
+    assert np.allclose(a.export_hot()[1], w_mid - shift, rtol=0, atol=T * 2.0 ** -25)
+    big = np.abs(dv[:2]) > 0.25                              # there every single step is below half a 16-bit spacing
+    assert big.any() and np.array_equal(cold.lookup(keys[:2])[big], dv[:2][big])   # without masters nothing moves
