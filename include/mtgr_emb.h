@@ -402,7 +402,7 @@ int grad_reduce_apply_adagrad(emb_table_t* t, const void* grad, const int32_t* s
  *     copy of a hot row is stale from then on and never read);
  *   ht_evict returns the hot rows of evicted keys to the hot store; ht_export dumps a hot row as its
  *     rounded master; ht_put refreshes the master of a hot row it overwrites;
- *   ht_apply_adam is refused (EMB_ERR_INVALID_ARG). */
+ *   ht_apply_adam, like ht_apply_adagrad, updates a hot row's master in fp32. */
 int ht_set_hot_storage(emb_table_t* t, float* hot_values, uint32_t* hot_free, int64_t hot_rows, void* stream);
 
 /* Promote by access frequency: every row of row_idx [device; distinct rows, -1 skipped; count as for

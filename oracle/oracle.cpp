@@ -383,7 +383,7 @@ int orc_apply_adam(void* h, const uint64_t* key, int64_t n, const float* g, floa
             const double w = (double)r.w[j] - step_size * m / (std::sqrt(v) + (double)eps);
             r.m[j] = static_cast<float>(m);
             r.v[j] = static_cast<float>(v);
-            r.w[j] = (t.dtype == kBF16) ? double_to_bf16_float(w) : static_cast<float>(w);
+            r.w[j] = (t.dtype == kBF16 && !r.hot) ? double_to_bf16_float(w) : static_cast<float>(w);   // a master stays fp32
         }
     }
     return 0;

@@ -1042,8 +1042,20 @@ __global__ __launch_bounds__(kBlock) void k_adam(HtView v, const int32_t* __rest
     const float* pg = g + (size_t)u * v.dim + (size_t)sub * kF;
     char* pw = const_cast<char*>(chunk_row_cptr(v, row)) + sub * 16;
     float w[kF];
-    const V16 wv = ld16(pw);
-    if (BF16) {
+    // a row of a 16-bit table that has an fp32 master: the master is what moves (and is not rounded)
+    float* master = nullptr;
+    if constexpr (BF16) {
+        if (v.hot_values) {
+            const uint32_t hot = meta_ptr(v, row)->hot;
+            if (hot != 0) master = v.hot_values + (size_t)(hot - 1u) * v.dim + (size_t)sub * kF;
+        }
+    }
+    const V16 wv = master ? V16{0u, 0u, 0u, 0u} : ld16(pw);
+    if constexpr (BF16) {
+        if (master) hot_load8(master, w);
+    }
+    if (master) {
+    } else if (BF16) {
         w[0] = bf16lo(wv.x); w[1] = bf16hi(wv.x); w[2] = bf16lo(wv.y); w[3] = bf16hi(wv.y);
         w[4 % kF] = bf16lo(wv.z); w[5 % kF] = bf16hi(wv.z); w[6 % kF] = bf16lo(wv.w); w[7 % kF] = bf16hi(wv.w);
     } else {
@@ -1065,6 +1077,12 @@ __global__ __launch_bounds__(kBlock) void k_adam(HtView v, const int32_t* __rest
         }
         st16(pm + 4 * q, mm);
         st16(pv + 4 * q, vv);
+    }
+    if constexpr (BF16) {
+        if (master) {
+            hot_store8(master, w);
+            return;
+        }
     }
     V16 o16;
     if (BF16) {
@@ -1377,7 +1395,6 @@ int ht_apply_adam(emb_table_t* t, const int32_t* row_idx, const float* reduced, 
     if (!row_idx || !reduced || (reinterpret_cast<uintptr_t>(reduced) & 15)) return EMB_ERR_INVALID_ARG;
     HtView v = t->view();
     if (!v.has_adam) return EMB_ERR_NO_STORAGE; // moment rows must be registered for every chunk
-    if (t->hot_values) return EMB_ERR_INVALID_ARG; // fp32 masters are kept for Adagrad only
     const double bc1 = 1.0 - std::pow((double)beta1, (double)step), bc2 = 1.0 - std::pow((double)beta2, (double)step);
     const float step_size = (float)((double)lr * std::sqrt(bc2) / bc1);
     const bool bf = t->desc.dtype == EMB_BF16;

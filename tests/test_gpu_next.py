@@ -534,11 +534,44 @@ def test_hot_store_argument_checks():
     tb = EmbeddingTable(32, B.BF16, capacity_log2=10, chunk_rows_log2=6, hot_rows=4, adam_state=True)
     with pytest.raises(B.EmbError):
         B.ht_set_hot_storage(tb.h, hv, hf, 4)                      # only once
-    g = torch.zeros((1, 32), dtype=torch.float32, device="cuda")
-    with pytest.raises(B.EmbError):
-        tb.apply_adam(ri, g, None, 1, 1e-3, 1)                     # masters are kept for Adagrad only
     t32.close()
     tb.close()
+
+
+def test_sparse_adam_moves_the_masters_of_hot_rows():
+    """Adam on a 16-bit table with hot rows: a hot row's master takes the update in fp32, a cold row rounds as before.
+    Masters to fp32 accuracy against the checker, delivered rows to 16-bit accuracy; moments identical for both kinds."""
+    from harness import RTOL_BF16
+    dim, lr = 64, 1e-3
+    table = EmbeddingTable(dim, B.BF16, capacity_log2=13, chunk_rows_log2=10, adam_state=True, initial_chunks=2, hot_rows=500)
+    ot = oracle.Table(dim, oracle.BF16)
+    ot.set_hot(500)
+    rng = np.random.default_rng(31)
+    pool = (np.arange(1, 1501, dtype=np.uint64) * np.uint64(0x9E3779B1)) & np.uint64((1 << 40) - 1)
+    for step in range(3):
+        _insert(table, ot, pool, step)
+    ri = _insert(table, ot, pool[:400], 3)
+    n_dev = torch.zeros(1, dtype=torch.int64, device="cuda")
+    table.promote(ri, None, 400, 4, n_dev)
+    assert int(n_dev.item()) == 400 and ot.promote(pool[:400], 4) == 400
+    for step in range(1, 7):
+        ks = np.unique(pool[rng.integers(0, 1500, size=800)])
+        r = _insert(table, ot, ks, 3 + step)
+        g = normal_grads(17, step, len(ks), dim)
+        table.apply_adam(r, torch.from_numpy(g).cuda(), None, len(ks), lr, step)
+        ot.apply_adam(ks, g, lr, step)
+    hk, hv = table.export_hot()
+    ok, ov = ot.export_hot()
+    assert np.array_equal(hk, ok) and len(hk) == 400
+    assert close_rows(hv, ov.astype(np.float64), lr, RTOL_F32)                 # masters: fp32 accuracy
+    moved = np.abs(hv - np.float32(torch.from_numpy(hv).to(torch.bfloat16).float().numpy())) > 0
+    assert moved.mean() > 0.5                                                  # masters really hold more than 16 bits
+    gk, gv, _, _, gf = table.export()
+    kk, kv, _, _, kf = ot.export()
+    assert np.array_equal(gk, kk) and np.array_equal(gf, kf)
+    assert close_rows(gv, kv.astype(np.float64), lr, RTOL_BF16)
+    assert table.stats()["status"] == 0
+    table.close()
 
 
 # --------------------------------------------------------------------------- one record update per step

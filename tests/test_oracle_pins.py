@@ -593,3 +593,30 @@ def test_restored_masters_continue_where_the_dump_left_off():
     assert np.allclose(a.export_hot()[1], w_mid - shift, rtol=0, atol=T * 2.0 ** -25)
     big = np.abs(dv[:2]) > 0.25                              # there every single step is below half a 16-bit spacing
     assert big.any() and np.array_equal(cold.lookup(keys[:2])[big], dv[:2][big])   # without masters nothing moves
+
+
+def test_adam_on_a_hot_row_is_the_fp32_update():
+    """A hot row of a 16-bit table under Adam: its master must move exactly like the row of an fp32 table that starts
+    from the same (16-bit representable) values - the fp32 table's Adam is pinned to torch.optim.SparseAdam above -
+    while a cold row of the same table ends on 16-bit values."""
+    D, lr = 16, 1e-2
+    keys = np.array([5, 6], dtype=np.uint64)
+    tb = oracle.Table(D, oracle.BF16, init_scale=1.0)
+    tb.find_or_insert(keys, 0)
+    tb.find_or_insert(keys[:1], 1)
+    tb.set_hot(2)
+    assert tb.promote(keys, 2) == 1                                  # key 5 hot, key 6 cold
+    start = tb.lookup(keys)
+    t32 = oracle.Table(D, oracle.F32, init_scale=1.0)
+    t32.find_or_insert(keys, 0)
+    _, _, acc, ls, fq = t32.export()
+    assert t32.put(np.sort(keys), start[np.argsort(keys)], acc, ls, fq) == 2
+    rng = np.random.default_rng(8)
+    for step in range(1, 6):
+        g = rng.standard_normal((2, D)).astype(np.float32)
+        tb.apply_adam(keys, g, lr, step)
+        t32.apply_adam(keys, g, lr, step)
+    assert np.array_equal(tb.export_hot()[1][0], t32.lookup(keys[:1])[0])          # master == fp32 row, bit for bit
+    cold = tb.lookup(keys[1:])[0]
+    assert np.array_equal(cold, torch.from_numpy(cold).to(torch.bfloat16).float().numpy())   # cold row: 16-bit values
+    assert not np.array_equal(cold, t32.lookup(keys[1:])[0])                        # and it did round on the way
