@@ -5,6 +5,8 @@ contents, exact integer-valued reduced gradients, updated rows and insert flags 
 sample of distinct keys that always contains the longest segments.  Pre-existing keys are
 materialised in the checker only when touched (an untouched row is a pure function of its key).
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -173,7 +175,8 @@ def test_config4_full_batch_insert_evict_rehash():
     assert (w.ttl, w.min_freq, w.grace, w.evict_every, w.max_load_factor) == (200, 3, 20, 20, 0.85)
     merged, _ = B.emb_plan_merge([64] * 4, [0] * 4)
     tag_bits = B.emb_tag_bits(4)
-    dim, steps = 64, 260
+    # 260 steps by default (about 95 s); MTGR_CONFIG4_STEPS=1000 runs the configuration's whole stream (about 6 minutes)
+    dim, steps = 64, int(os.environ.get("MTGR_CONFIG4_STEPS", "260"))
     pair = Pair(dim, 0, capacity_log2=22, chunk_rows_log2=21, max_load_factor=w.max_load_factor, count_probes=True)
     buf = StepBuffers(512 * 1024 * 4, dim)
     tracked = tracked_subset(_hot_keys(w, tag_bits))
