@@ -65,7 +65,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, choices=[2, 5])
+    ap.add_argument("--config", type=int, default=2, choices=[2, 3, 5],
+                    help="2: long-sequence lookup (the headline); 5: large bf16 table; 3: table merging - the step over 32 "
+                         "logical tables merged into 4 hash tables against the same step over 32 separate tables")
     ap.add_argument("--batches", type=int, default=0,
                     help="distinct pre-generated batches cycled through (default: 4 for the long-sequence configuration, "
                          "which brings no new keys; warmup + steps for the large one, so that every step brings its "
@@ -98,6 +100,9 @@ def main() -> int:
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.config == 3:
+        print(json.dumps(table_merging_line(args, B, EmbeddingTable, StepBuffers, make_config, merged_inputs, dev)), flush=True)
+        return 0
     w = make_config(args.config)
     dims = [w.table_dim(t) for t in range(w.n_tables)]
     dtypes = [0 if w.table_dtype(t) == "f32" else 1 for t in range(w.n_tables)]
@@ -540,6 +545,111 @@ def main() -> int:
     print(json.dumps(result), flush=True)
     table.close()
     return 0
+
+
+def table_merging_line(args, B, EmbeddingTable, StepBuffers, make_config, merged_inputs, dev) -> dict:
+    """Table-merging configuration (Sec. 3.2): 32 logical tables with dims from {16, 32, 64, 128}, batch 1024 x 40 fields,
+    1-200 IDs per field.  The same forward+backward step over (a) the 4 hash tables the merge plan gives (one per dim, IDs
+    tagged with their logical table, Eq. 8) and (b) 32 separate hash tables, one per logical table: what merging buys on
+    this GPU is fewer, larger launches.  Tables start empty and fill during the warm-up steps."""
+    w = make_config(3)
+    dims = [w.table_dim(t) for t in range(w.n_tables)]
+    merged, n_merged = B.emb_plan_merge(dims, [0] * w.n_tables)
+    tag_bits, id_bits = w.tag_bits, w.id_bits
+    n_steps = args.warmup + args.steps
+    raw = [w.next_step(s) for s in range(n_steps)]
+
+    def build(plan, n_groups):
+        """tables, buffers and device inputs of every step for a grouping of the logical tables"""
+        group_dim = [dims[list(plan).index(g)] for g in range(n_groups)]
+        per_step = []
+        n_max = [1] * n_groups
+        for b in raw:
+            groups = []
+            for g in range(n_groups):
+                x, off, tags, _ = merged_inputs(w.features, b.ids, plan, g)
+                n_max[g] = max(n_max[g], len(x))
+                groups.append((torch.from_numpy(x.view(np.int64)).to(dev), torch.from_numpy(off).to(dev),
+                               torch.from_numpy(tags).to(dev), len(x)))
+            per_step.append(groups)
+        cap = 22 if n_groups == n_merged else 20
+        tables = [EmbeddingTable(group_dim[g], 0, capacity_log2=cap, chunk_rows_log2=cap - 2, initial_chunks=2)
+                  for g in range(n_groups)]
+        bufs = [StepBuffers(n_max[g], group_dim[g]) for g in range(n_groups)]
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(w.seed)
+        grads = [torch.randn((n_max[g], group_dim[g]), generator=gen, device=dev, dtype=torch.float32) for g in range(n_groups)]
+        return tables, bufs, grads, per_step, group_dim
+
+    def group_step(t, buf, grad, inp, step, stream=None):
+        dx, doff, dtag, n = inp
+        if n == 0:
+            return 0
+        B.emb_tag_dedup(dx, doff, dtag, tag_bits, id_bits, None, buf.uniq, None, None, buf.perm, None, buf.seg_of,
+                        buf.n_unique, buf.err_count, buf.tag_dedup_ws)
+        t.find_or_insert(buf.uniq, buf.n_unique, n, step + 1, buf.row_idx, buf.inserted, touch=False)
+        t.gather(buf.row_idx, buf.n_unique, n, buf.uniq_rows)
+        B.emb_expand_sorted(buf.uniq_rows, buf.seg_of, buf.perm, n, t.dim, 0, buf.out)
+        B.grad_segment_reduce(grad, 0, buf.seg_of, buf.perm, n, t.dim, buf.reduced, buf.reduce_ws)
+        t.apply_adagrad(buf.row_idx, buf.reduced, buf.n_unique, n, w.lr, w.eps, step + 1)
+        return n
+
+    def run(plan, n_groups, streams=None):
+        tables, bufs, grads, per_step, group_dim = build(plan, n_groups)
+        main = torch.cuda.current_stream()
+
+        def step_fn(step):
+            ids = 0
+            if streams is None:
+                for g in range(n_groups):
+                    ids += group_step(tables[g], bufs[g], grads[g], per_step[step][g], step)
+            else:
+                for g in range(n_groups):
+                    st = streams[g % len(streams)]
+                    st.wait_stream(main)
+                    with torch.cuda.stream(st):
+                        ids += group_step(tables[g], bufs[g], grads[g], per_step[step][g], step)
+                for st in streams:
+                    main.wait_stream(st)
+            return ids
+        for s_ in range(args.warmup):
+            step_fn(s_)
+        torch.cuda.synchronize()
+        live0 = sum(t.stats()["live"] for t in tables)
+        t0 = time.perf_counter()
+        ids = 0
+        for k in range(args.steps):
+            ids += step_fn(args.warmup + k)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        stats = [t.stats() for t in tables]
+        out = {"tables": n_groups, "ms_per_step": round(wall * 1e3 / args.steps, 4), "ids_per_sec": round(ids / wall, 1),
+               "ids_per_step": ids // args.steps, "live_keys_after": sum(s_["live"] for s_ in stats),
+               "new_keys_per_step": round((sum(s_["live"] for s_ in stats) - live0) / args.steps, 1),
+               "status": max(s_["status"] for s_ in stats)}
+        for t in tables:
+            t.close()
+        del tables, bufs, grads, per_step
+        torch.cuda.empty_cache()
+        return out, wall, ids
+
+    m, wall_m, ids_m = run(merged, n_merged)
+    log(f"merged: {m}")
+    m4, _, _ = run(merged, n_merged, [torch.cuda.Stream() for _ in range(n_merged)])
+    log(f"merged, one stream per table: {m4}")
+    u, _, _ = run(np.arange(w.n_tables, dtype=np.int32), w.n_tables)
+    log(f"unmerged: {u}")
+    return {
+        "metric": "embedding IDs/sec fwd+bwd", "value": m["ids_per_sec"], "unit": "IDs/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": m["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"config3:{w.name}", "logical_tables": w.n_tables, "merged_tables": int(n_merged),
+                   "fields": len(w.features), "batch": w.batch, "tag_bits": tag_bits, "ids_per_step": m["ids_per_step"]},
+        "merged": m, "merged_one_stream_per_table": m4, "separate_tables": u,
+        "speedup_from_merging": round(u["ms_per_step"] / m["ms_per_step"], 2),
+        "note": "the same forward+backward step over the 4 merged hash tables of the merge plan (one per dim, IDs tagged with "
+                "their logical table) and over 32 separate hash tables; tables start empty and keep inserting new keys",
+    }
 
 
 def probe_counts(B, table, batches, buf, tag_bits, id_bits, dim, dtype, cap_log2, chunk_log2) -> dict:
