@@ -253,7 +253,8 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
                                                        int last_level) {
     constexpr int kGroups = kWave / LPR;
     // fp32 gradient rows are loaded non-temporally (long-sequence step: reduce -36 us, whole step -17 us); for bf16
-    // gradients, whose fp32 sums are twice the size of the rows read, the same hint cost 0.1 ms per step
+    // gradients, whose fp32 sums are twice the size of the rows read, the hint showed no gain (large configuration,
+    // whose step times spread by 0.1 ms from run to run) and is left off
     constexpr bool kNtGrad = LEVEL1 && FPL == 4;
     const int lane = lane_id();
     const int sub = lane % LPR, grp = lane / LPR;
