@@ -384,6 +384,14 @@ __device__ inline void mark_tag_starts(const PkArgs& a, int64_t tile_base, unsig
     __syncthreads();
 }
 
+// The record before a lane's item `it` in sorted order (items are laid out it * 64 + lane within a wave's 1024):
+// the neighbouring lane's item, lane 63's previous item for lane 0, and one load per wave for its very first item.
+__device__ inline uint64_t prev_record(const uint64_t* r, int it, int lane, uint64_t before_wave) {
+    const uint64_t left = shfl64(r[it], lane == 0 ? 0 : lane - 1);
+    if (lane != 0) return left;
+    return it == 0 ? before_wave : shfl64(r[it - 1], kWave - 1);
+}
+
 __global__ __launch_bounds__(kThreads) void k_pk_heads_count(PkArgs a, const uint64_t* __restrict__ rec) {
     __shared__ unsigned s_w[kWaves];
     __shared__ unsigned s_bits[kTile / 32];
@@ -395,13 +403,22 @@ __global__ __launch_bounds__(kThreads) void k_pk_heads_count(PkArgs a, const uin
     const int lane = lane_id(), wave = threadIdx.x / kWave;
     const int e0 = wave * (kWave * kItems) + lane;
     unsigned cnt = 0;
+    uint64_t r[kItems];
+#pragma unroll
+    for (int it = 0; it < kItems; ++it) {
+        const int64_t j = tile_base + e0 + it * kWave;
+        r[it] = j < a.n ? rec[j] : 0ull;
+    }
+    const int64_t wave_first = tile_base + wave * (kWave * kItems);
+    const uint64_t before_wave = (wave_first > 0 && wave_first < a.n) ? rec[wave_first - 1] : 0ull;
 #pragma unroll
     for (int it = 0; it < kItems; ++it) {
         const int e = e0 + it * kWave;
         const int64_t j = tile_base + e;
+        const uint64_t prev = prev_record(r, it, lane, before_wave);
         if (j < a.n) {
             const bool start = (s_bits[e >> 5] >> (e & 31)) & 1u;
-            cnt += (j == 0 || start || (rec[j] >> a.pos_bits) != (rec[j - 1] >> a.pos_bits)) ? 1u : 0u;
+            cnt += (j == 0 || start || (r[it] >> a.pos_bits) != (prev >> a.pos_bits)) ? 1u : 0u;
         }
     }
     for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, kWave);
@@ -459,11 +476,18 @@ __global__ __launch_bounds__(kThreads) void k_pk_emit(PkArgs a, const uint64_t* 
     unsigned cnt = 0;
 #pragma unroll
     for (int it = 0; it < kItems; ++it) {
+        const int64_t j = tile_base + e0 + it * kWave;
+        r[it] = j < a.n ? rec[j] : 0ull;
+    }
+    const int64_t wave_first = tile_base + wave * (kWave * kItems);
+    const uint64_t before_wave = (wave_first > 0 && wave_first < a.n) ? rec[wave_first - 1] : 0ull;
+#pragma unroll
+    for (int it = 0; it < kItems; ++it) {
         const int e = e0 + it * kWave;
         const int64_t j = tile_base + e;
-        r[it] = j < a.n ? rec[j] : 0ull;
+        const uint64_t prev = prev_record(r, it, lane, before_wave);
         const bool start = (s_bits[e >> 5] >> (e & 31)) & 1u;
-        const bool head = j < a.n && (j == 0 || start || (r[it] >> a.pos_bits) != (rec[j - 1] >> a.pos_bits));
+        const bool head = j < a.n && (j == 0 || start || (r[it] >> a.pos_bits) != (prev >> a.pos_bits));
         headbits |= head ? (1u << it) : 0u;
         cnt += head ? 1u : 0u;
     }
