@@ -456,13 +456,26 @@ __global__ __launch_bounds__(1024) void k_pk_heads_scan(unsigned* __restrict__ t
     if (threadIdx.x == 0) *n_unique_out = (int64_t)s_carry;
 }
 
+// own_prefix: tile_heads holds the tiles' raw head counts and every block sums the counts of the tiles before its own
+// (a few KB from L2 per block, which saves the launch of a single-block scan between two dependent kernels; used up to
+// kOwnPrefixTiles tiles); otherwise tile_heads holds their exclusive prefix sums (k_pk_heads_scan).  The last tile
+// writes the number of distinct keys in the first case.
+constexpr unsigned kOwnPrefixTiles = 8192;
 __global__ __launch_bounds__(kThreads) void k_pk_emit(PkArgs a, const uint64_t* __restrict__ rec,
                                                      uint64_t* __restrict__ uniq, int32_t* __restrict__ inverse,
                                                      int32_t* __restrict__ perm, int32_t* __restrict__ seg_off,
-                                                     int32_t* __restrict__ seg_of) {
+                                                     int32_t* __restrict__ seg_of, int own_prefix,
+                                                     int64_t* __restrict__ n_unique_out) {
     __shared__ unsigned s_w[kWaves];
+    __shared__ unsigned s_pre[kWaves];
     __shared__ unsigned s_bits[kTile / 32];
     __shared__ unsigned s_tag_start[257];
+    unsigned before = 0;       // heads in the tiles before this one: this thread's share (own_prefix) or all (thread 0)
+    if (own_prefix) {
+        for (unsigned t = threadIdx.x; t < blockIdx.x; t += kThreads) before += a.tile_heads[t];
+    } else if (threadIdx.x == 0) {
+        before = a.tile_heads[blockIdx.x];
+    }
     for (int t = threadIdx.x; t < 257; t += kThreads) s_tag_start[t] = a.tag_start[t];
     __syncthreads();
     const int64_t tile_base = (int64_t)blockIdx.x * kTile;
@@ -492,10 +505,18 @@ __global__ __launch_bounds__(kThreads) void k_pk_emit(PkArgs a, const uint64_t* 
         cnt += head ? 1u : 0u;
     }
     unsigned wave_total = cnt;
-    for (int o = 32; o > 0; o >>= 1) wave_total += __shfl_xor(wave_total, o, kWave);
-    if (lane == 0) s_w[wave] = wave_total;
+    for (int o = 32; o > 0; o >>= 1) {
+        wave_total += __shfl_xor(wave_total, o, kWave);
+        before += __shfl_xor(before, o, kWave);
+    }
+    if (lane == 0) {
+        s_w[wave] = wave_total;
+        s_pre[wave] = before;
+    }
     __syncthreads();
-    unsigned running = a.tile_heads[blockIdx.x];
+    unsigned running = s_pre[0] + s_pre[1] + s_pre[2] + s_pre[3];
+    if (own_prefix && blockIdx.x == a.n_tiles - 1 && threadIdx.x == 0)
+        *n_unique_out = (int64_t)(running + s_w[0] + s_w[1] + s_w[2] + s_w[3]);
     for (int w = 0; w < wave; ++w) running += s_w[w];
     // pass 2: element order inside the wave is (it, lane)
 #pragma unroll
@@ -676,8 +697,10 @@ int emb_tag_dedup(const uint64_t* x, const int64_t* field_off, const uint8_t* fi
         dst = (dst == a.rec_a) ? a.rec_b : a.rec_a;
     }
     hipLaunchKernelGGL(k_pk_heads_count, dim3(L.n_tiles), dim3(kThreads), 0, s, a, src);
-    hipLaunchKernelGGL(k_pk_heads_scan, dim3(1), dim3(1024), 0, s, a.tile_heads, L.n_tiles, n_unique);
-    hipLaunchKernelGGL(k_pk_emit, dim3(L.n_tiles), dim3(kThreads), 0, s, a, src, uniq, inverse, perm, seg, seg_of);
+    const int own_prefix = L.n_tiles <= kOwnPrefixTiles ? 1 : 0;
+    if (!own_prefix) hipLaunchKernelGGL(k_pk_heads_scan, dim3(1), dim3(1024), 0, s, a.tile_heads, L.n_tiles, n_unique);
+    hipLaunchKernelGGL(k_pk_emit, dim3(L.n_tiles), dim3(kThreads), 0, s, a, src, uniq, inverse, perm, seg, seg_of, own_prefix,
+                       n_unique);
     MTGR_LAUNCH_CHECK();
     if (counts) {
         hipLaunchKernelGGL(k_pk_counts, dim3((unsigned)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, seg, n_unique, counts);

@@ -354,3 +354,53 @@ def test_dedup_beyond_2_pow_30_keys():
     seen = torch.zeros(n, dtype=torch.uint8, device="cuda")
     seen[perm.long()] = 1
     assert bool(seen.all())
+
+
+def test_tag_dedup_of_forty_million_ids_equals_tag_then_dedup():
+    """The fused call on more IDs than its smallest-launch layout covers (above 8192 sort tiles the per-tile counts
+    of distinct keys go through their own prefix-sum launch): every output must equal, bit for bit, that of the
+    unfused pair emb_tag_keys + emb_dedup, which shares no kernel with it; the properties that hold at any size are
+    checked on top (Eq. 8 keys, ascending distinct keys, stable order inside a segment)."""
+    n_fields, tag_bits, id_bits = 6, 4, 26
+    lens = [9_000_001, 3, 12_345_678, 0, 18_000_000, 654_321]
+    n = sum(lens)
+    assert n > 8192 * 4096
+    g = torch.Generator(device="cuda").manual_seed(11)
+    x = torch.randint(0, 1 << id_bits, (n,), generator=g, device="cuda", dtype=torch.int64)
+    x[: lens[0] // 2] &= (1 << 12) - 1                                    # long segments in the first field
+    x[-7:] = x[-8].clone()
+    off = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int64, device="cuda")
+    tags = torch.tensor([5, 0, 9, 3, 15, 1], dtype=torch.uint8, device="cuda")
+
+    def outputs():
+        return dict(key=torch.empty(n, dtype=torch.int64, device="cuda"), uniq=torch.empty(n, dtype=torch.int64, device="cuda"),
+                    inverse=torch.empty(n, dtype=torch.int32, device="cuda"), counts=torch.empty(n, dtype=torch.int32, device="cuda"),
+                    perm=torch.empty(n, dtype=torch.int32, device="cuda"), seg_off=torch.empty(n + 1, dtype=torch.int32, device="cuda"),
+                    seg_of=torch.empty(n, dtype=torch.int32, device="cuda"), n_unique=torch.zeros(1, dtype=torch.int64, device="cuda"),
+                    err=torch.zeros(1, dtype=torch.int64, device="cuda"))
+    a, b = outputs(), outputs()
+    ws = torch.empty(B.emb_tag_dedup_workspace_bytes(n, n_fields, tag_bits, id_bits), dtype=torch.uint8, device="cuda")
+    print(f"  n={n}", flush=True)
+    B.emb_tag_dedup(x, off, tags, tag_bits, id_bits, a["key"], a["uniq"], a["inverse"], a["counts"], a["perm"], a["seg_off"],
+                    a["seg_of"], a["n_unique"], a["err"], ws)
+    U = int(a["n_unique"].item())
+    print(f"  fused: U={U}", flush=True)
+    del ws
+    B.emb_tag_keys(x, off, tags, tag_bits, b["key"], b["err"])
+    ws = torch.empty(B.emb_dedup_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    B.emb_dedup(b["key"], n, b["uniq"], b["inverse"], b["counts"], b["perm"], b["seg_off"], b["seg_of"], b["n_unique"], ws)
+    assert int(b["n_unique"].item()) == U and int(a["err"].item()) == int(b["err"].item()) == 0
+    print("  unfused pair done", flush=True)
+    assert torch.equal(a["key"], b["key"])
+    for name, m in (("uniq", U), ("inverse", n), ("counts", U), ("perm", n), ("seg_off", U + 1), ("seg_of", n)):
+        assert torch.equal(a[name][:m], b[name][:m]), name
+    # properties
+    field = torch.repeat_interleave(tags.long(), torch.tensor(lens, device="cuda"))
+    assert torch.equal(a["key"], (field << (63 - tag_bits)) | x)          # Eq. 8, bit 63 stays clear
+    u = a["uniq"][:U]
+    assert bool((u[1:] > u[:-1]).all())
+    assert torch.equal(u[a["inverse"].long()], a["key"])
+    p = a["perm"].long()
+    sk = a["key"][p]
+    assert bool(((sk[1:] > sk[:-1]) | ((sk[1:] == sk[:-1]) & (p[1:] > p[:-1]))).all())
+    assert int(a["seg_off"][U].item()) == n and int(a["counts"][:U].long().sum().item()) == n
