@@ -14,7 +14,7 @@ using namespace mtgr;
 namespace {
 
 constexpr int kBlock = 256;
-constexpr int kUnroll = 4;            // segment reduce: rows a lane group fetches per batch at the first level
+constexpr int kUnroll = 8;            // segment reduce: rows a lane group fetches per batch at the first level
 constexpr int kUnrollUpper = 8;       // ... and at the upper levels
 constexpr int kPipeMax = 8;           // batches up to this size are double-buffered
 
@@ -320,7 +320,15 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce(LevelIn in, int dim, floa
                     const int sl = gbase + f % LPR;
                     const int src = __shfl(my_src[f / LPR], sl, kWave);
                     sg_[k] = __shfl(my_seg[f / LPR], sl, kWave);
-                    if (lane_on && sg_[k] >= 0) v_[k] = (kNtGrad ? ld16_nt : ld16)(in.rows + (size_t)src * (size_t)in.in_row_bytes + sub * 16);
+                    // The load must not sit behind a branch: with a data-dependent number of loads in flight the wait
+                    // before a fold is for all of them, the next batch's included, and the double buffer is void.  A lane
+                    // without a row reads the first 16 bytes of the matrix instead and masks them out; the mask is made
+                    // opaque to the compiler, which otherwise puts the branch back.
+                    const bool on = lane_on && sg_[k] >= 0;
+                    uint32_t keep = on ? 0xFFFFFFFFu : 0u;
+                    asm("" : "+v"(keep));
+                    const V16 t = (kNtGrad ? ld16_nt : ld16)(in.rows + (on ? (size_t)src * (size_t)in.in_row_bytes + sub * 16 : (size_t)0));
+                    v_[k] = V16{t.x & keep, t.y & keep, t.z & keep, t.w & keep};
                 }
             }
         };
