@@ -290,12 +290,19 @@ __global__ __launch_bounds__(kScThreads) void k_pk_scatter(PkArgs a, PassPlan p,
     unsigned rnk[kScItems];
     const int e0 = wave * (kWave * kScItems) + lane;
     unsigned unused_errs = 0;
+    // all loads first and none behind a branch (an element past the tile's end reads the tile's last one instead):
+    // a load inside a conditional makes the compiler wait for it on the spot, one round trip per item
+#pragma unroll
+    for (int it = 0; it < kScItems; ++it) {
+        const int e = e0 + it * kWave;
+        rec[it] = src[tile_base + (e < tile_n ? e : tile_n - 1)];
+    }
 #pragma unroll
     for (int it = 0; it < kScItems; ++it) {
         const int e = e0 + it * kWave;
         const bool ok = e < tile_n;
-        if (FIRST) rec[it] = ok ? (checked_id(src[tile_base + e], a, &unused_errs) << a.pos_bits) | (uint64_t)(tile_base + e) : ~0ull;
-        else rec[it] = ok ? src[tile_base + e] : ~0ull;
+        if (FIRST) rec[it] = ok ? (checked_id(rec[it], a, &unused_errs) << a.pos_bits) | (uint64_t)(tile_base + e) : ~0ull;
+        else rec[it] = ok ? rec[it] : ~0ull;
     }
     // rank of every record among the records of equal digit that precede it in this wave's share
 #pragma unroll
