@@ -222,6 +222,35 @@ __device__ inline void st16_nt(void* p, V16 v) {
     __builtin_nontemporal_store(v.w, reinterpret_cast<uint32_t*>(p) + 3);
 }
 
+// The same through a pointer that the compiler cannot prove to be global memory because it was itself loaded
+// from memory (the chunk directory).  Left generic, such an access becomes a "flat" instruction, which counts on
+// the LDS wait counter as well as on the memory one; the compiler then waits for it on the spot, and the loads of
+// a batch go out one round trip after the other.  The address-space cast makes it a plain global access.
+#define MTGR_AS_GLOBAL __attribute__((address_space(1)))
+__device__ inline V16 ldg16(const void* p) {
+    const MTGR_AS_GLOBAL uint32_t* q = (const MTGR_AS_GLOBAL uint32_t*)p;
+    return V16{q[0], q[1], q[2], q[3]};
+}
+__device__ inline V16 ldg16_nt(const void* p) {
+    const MTGR_AS_GLOBAL uint32_t* q = (const MTGR_AS_GLOBAL uint32_t*)p;
+    return V16{__builtin_nontemporal_load(q), __builtin_nontemporal_load(q + 1), __builtin_nontemporal_load(q + 2),
+               __builtin_nontemporal_load(q + 3)};
+}
+__device__ inline void stg16(void* p, V16 v) {
+    MTGR_AS_GLOBAL uint32_t* q = (MTGR_AS_GLOBAL uint32_t*)p;
+    q[0] = v.x;
+    q[1] = v.y;
+    q[2] = v.z;
+    q[3] = v.w;
+}
+__device__ inline void stg16_nt(void* p, V16 v) {
+    MTGR_AS_GLOBAL uint32_t* q = (MTGR_AS_GLOBAL uint32_t*)p;
+    __builtin_nontemporal_store(v.x, q + 0);
+    __builtin_nontemporal_store(v.y, q + 1);
+    __builtin_nontemporal_store(v.z, q + 2);
+    __builtin_nontemporal_store(v.w, q + 3);
+}
+
 inline int check_hip(hipError_t e) { return e == hipSuccess ? EMB_OK : EMB_ERR_HIP; }
 #define MTGR_LAUNCH_CHECK()                         \
     do {                                            \

@@ -718,42 +718,41 @@ __global__ __launch_bounds__(kBlock) void k_adagrad(HtView v, const int32_t* __r
         bool on[kRows];
         float acc_old[kRows];
         uint32_t freq_old[kRows], hot_old[kRows];
-        // all loads of the batch go out before anything waits: gradient row, weight row and the
-        // row's accumulator (its own cache line) are independent
+        // all loads of the batch go out before anything waits: gradient row, weight row and the row's record (its
+        // own cache line) are independent.  None sits behind a branch and all are plain global loads, or the
+        // compiler waits after each: an entry without a row reads row 0 and the wave's first gradient row instead and
+        // masks them out (the mask is opaque to the compiler, which would otherwise put the branch back).
+        V16 gq[kRows][kF / 4], rec[kRows];
+        uint32_t keep[kRows];
 #pragma unroll
         for (int u = 0; u < kRows; ++u) {
             const int r = r0 + u * kGroups + grp;
             idx[u] = __shfl(my_index, r & (kWave - 1), kWave);
             on[u] = r < rows_here && idx[u] >= 0;
+            keep[u] = on[u] ? 0xFFFFFFFFu : 0u;
+            asm("" : "+v"(keep[u]));
+            const uint32_t row = on[u] ? (uint32_t)idx[u] : 0u;
+            const RowMeta* m = staged_meta(v, s_meta, row);
+            rec[u] = TOUCH ? ldg16(m) : V16{__float_as_uint(((const MTGR_AS_GLOBAL RowMeta*)m)->acc), 0u, 0u, 0u};
+            const float* gp = g + (size_t)(wave_base + (on[u] ? r : 0)) * v.dim + (lane_on ? sub * kF : 0);
 #pragma unroll
-            for (int e = 0; e < kF; ++e) gv[u][e] = 0.0f;
-            wv[u] = V16{0u, 0u, 0u, 0u};
-            acc_old[u] = 0.0f;
-            freq_old[u] = hot_old[u] = 0u;
-            if (on[u]) {
-                const uint32_t row = (uint32_t)idx[u];
-                const RowMeta* m = staged_meta(v, s_meta, row);
-                if (TOUCH) {
-                    const V16 rec = ld16(m);
-                    acc_old[u] = __uint_as_float(rec.x);
-                    freq_old[u] = rec.z;
-                    hot_old[u] = rec.w;
-                } else {
-                    acc_old[u] = m->acc;
-                }
-            }
-            if (on[u] && lane_on) {
-                const float* gp = g + (size_t)(wave_base + r) * v.dim + sub * kF;
+            for (int q = 0; q < kF / 4; ++q) gq[u][q] = ld16_nt(gp + 4 * q);
+            wv[u] = ldg16_nt(staged_row(v, s_values, row) + (lane_on ? sub * 16 : 0));
+        }
 #pragma unroll
-                for (int q = 0; q < kF / 4; ++q) {
-                    V16 t = ld16_nt(gp + 4 * q);
-                    gv[u][4 * q] = __uint_as_float(t.x);
-                    gv[u][4 * q + 1] = __uint_as_float(t.y);
-                    gv[u][4 * q + 2] = __uint_as_float(t.z);
-                    gv[u][4 * q + 3] = __uint_as_float(t.w);
-                }
-                wv[u] = ld16_nt(staged_row(v, s_values, (uint32_t)idx[u]) + sub * 16);
+        for (int u = 0; u < kRows; ++u) {
+            const uint32_t k = lane_on ? keep[u] : 0u;
+#pragma unroll
+            for (int q = 0; q < kF / 4; ++q) {
+                gv[u][4 * q] = __uint_as_float(gq[u][q].x & k);
+                gv[u][4 * q + 1] = __uint_as_float(gq[u][q].y & k);
+                gv[u][4 * q + 2] = __uint_as_float(gq[u][q].z & k);
+                gv[u][4 * q + 3] = __uint_as_float(gq[u][q].w & k);
             }
+            wv[u] = V16{wv[u].x & k, wv[u].y & k, wv[u].z & k, wv[u].w & k};
+            acc_old[u] = __uint_as_float(rec[u].x & keep[u]);
+            freq_old[u] = rec[u].z & keep[u];
+            hot_old[u] = rec[u].w & keep[u];
         }
 #pragma unroll
         for (int u = 0; u < kRows; ++u) {
@@ -776,12 +775,12 @@ __global__ __launch_bounds__(kBlock) void k_adagrad(HtView v, const int32_t* __r
                     o.z = __float_as_uint(adagrad_w(__uint_as_float(wv[u].z), gv[u][2], scale));
                     o.w = __float_as_uint(adagrad_w(__uint_as_float(wv[u].w), gv[u][3], scale));
                 }
-                st16_nt(wp, o);
+                stg16_nt(wp, o);
             }
             if (sub == 0) {
                 RowMeta* m = staged_meta(v, s_meta, row);
-                if (TOUCH) st16(m, V16{__float_as_uint(acc), step, freq_old[u] + 1u, hot_old[u]});
-                else m->acc = acc;
+                if (TOUCH) stg16(m, V16{__float_as_uint(acc), step, freq_old[u] + 1u, hot_old[u]});
+                else ((MTGR_AS_GLOBAL RowMeta*)m)->acc = acc;
             }
         }
     }
