@@ -81,7 +81,7 @@ __global__ __launch_bounds__(kThreads) void k_tag(const uint64_t* __restrict__ x
 #pragma unroll
         for (int u = 0; u < kPer; ++u) {
             const int64_t e = base + u * kWave + lane;
-            v[u] = e < n ? x[e] : 0ull;
+            v[u] = x[e < n ? e : n - 1];      // no load behind a branch: see k_dd_masks
         }
 #pragma unroll
         for (int u = 0; u < kPer; ++u) {
@@ -149,15 +149,22 @@ __global__ __launch_bounds__(kThreads) void k_dd_masks(const uint64_t* __restric
     uint64_t o = 0ull, a = ~0ull;
     const int64_t base = (int64_t)tile * kTile + (threadIdx.x / kWave) * (kWave * kItems) + lane;
     unsigned d[kItems];
+    // The loads of a thread go out together, none behind a branch (an element past the end reads the last key
+    // instead): a load inside a conditional makes the compiler wait for it on the spot, one round trip per item.
+    uint64_t kv[kItems];
+#pragma unroll
+    for (int it = 0; it < kItems; ++it) {
+        const int64_t e = base + it * kWave;
+        kv[it] = key[e < n ? e : n - 1];
+    }
 #pragma unroll
     for (int it = 0; it < kItems; ++it) {
         const int64_t e = base + it * kWave;
         d[it] = kRadix;
         if (e < n) {
-            const uint64_t k = key[e];
-            o |= k;
-            a &= k;
-            d[it] = digit_of(k, 0);
+            o |= kv[it];
+            a &= kv[it];
+            d[it] = digit_of(kv[it], 0);
         }
     }
 #pragma unroll
@@ -236,10 +243,16 @@ __global__ __launch_bounds__(kThreads) void k_rs_hist(DdBuffers b, const DdHeade
     const int64_t base = (int64_t)tile * kTile + (threadIdx.x / kWave) * (kWave * kItems) + (threadIdx.x % kWave);
     const int lane = lane_id();
     unsigned d[kItems];
+    uint64_t kv[kItems];
 #pragma unroll
     for (int it = 0; it < kItems; ++it) {
         const int64_t e = base + it * kWave;
-        d[it] = e < n ? digit_of(keys[e], pass) : kRadix; // kRadix = no key
+        kv[it] = keys[e < n ? e : n - 1];     // all loads first, unconditional: see k_dd_masks
+    }
+#pragma unroll
+    for (int it = 0; it < kItems; ++it) {
+        const int64_t e = base + it * kWave;
+        d[it] = e < n ? digit_of(kv[it], pass) : kRadix; // kRadix = no key
     }
 #pragma unroll
     for (int it = 0; it < kItems; ++it) hist_add_runs(s_hist, d[it], lane);
@@ -316,9 +329,15 @@ __global__ __launch_bounds__(kScThreads) void k_rs_scatter(DdBuffers b, const Dd
 #pragma unroll
     for (int it = 0; it < kScItems; ++it) {
         const int e = e0 + it * kWave;
-        const bool ok = e < tile_n;
-        key[it] = ok ? in_k[tile_base + e] : ~0ull;
-        idx[it] = ok ? (in_i ? in_i[tile_base + e] : (uint32_t)(tile_base + e)) : 0xFFFFFFFFu;
+        const int ec = e < tile_n ? e : tile_n - 1;     // all loads first, unconditional: see k_dd_masks
+        key[it] = in_k[tile_base + ec];
+        idx[it] = in_i ? in_i[tile_base + ec] : (uint32_t)(tile_base + e);
+    }
+#pragma unroll
+    for (int it = 0; it < kScItems; ++it) {
+        const bool ok = e0 + it * kWave < tile_n;
+        key[it] = ok ? key[it] : ~0ull;
+        idx[it] = ok ? idx[it] : 0xFFFFFFFFu;
     }
     // rank of every key among the keys of equal digit that precede it in this wave's 1024
 #pragma unroll
@@ -399,10 +418,18 @@ __global__ __launch_bounds__(kThreads) void k_heads_count(DdBuffers b, const DdH
     const int lane = lane_id(), wave = threadIdx.x / kWave;
     const int64_t base = (int64_t)blockIdx.x * kTile + wave * (kWave * kItems) + lane;
     unsigned cnt = 0;
+    uint64_t cur[kItems], prev[kItems];
+#pragma unroll
+    for (int it = 0; it < kItems; ++it) {          // all loads first, unconditional: see k_dd_masks
+        const int64_t j = base + it * kWave;
+        const int64_t jc = j < n ? j : n - 1;
+        cur[it] = keys[jc];
+        prev[it] = keys[jc > 0 ? jc - 1 : 0];
+    }
 #pragma unroll
     for (int it = 0; it < kItems; ++it) {
         const int64_t j = base + it * kWave;
-        if (j < n) cnt += (j == 0 || keys[j] != keys[j - 1]) ? 1u : 0u;
+        if (j < n) cnt += (j == 0 || cur[it] != prev[it]) ? 1u : 0u;
     }
     for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, kWave);
     if (lane == 0) s_w[wave] = cnt;
@@ -453,14 +480,22 @@ __global__ __launch_bounds__(kThreads) void k_emit(DdBuffers b, const DdHeader* 
     const int lane = lane_id(), wave = threadIdx.x / kWave;
     const int64_t base = (int64_t)blockIdx.x * kTile + wave * (kWave * kItems) + lane;
     // pass 1: heads per wave
-    uint64_t key[kItems];
+    uint64_t key[kItems], prev[kItems];
+    uint32_t pos[kItems];
     unsigned headbits = 0; // bit it = element is a head
     unsigned cnt = 0;
 #pragma unroll
+    for (int it = 0; it < kItems; ++it) {          // all loads first, unconditional: see k_dd_masks
+        const int64_t j = base + it * kWave;
+        const int64_t jc = j < n ? j : n - 1;
+        key[it] = keys[jc];
+        prev[it] = keys[jc > 0 ? jc - 1 : 0];
+        pos[it] = idxs ? idxs[jc] : (uint32_t)j;
+    }
+#pragma unroll
     for (int it = 0; it < kItems; ++it) {
         const int64_t j = base + it * kWave;
-        key[it] = j < n ? keys[j] : 0ull;
-        const bool head = j < n && (j == 0 || key[it] != keys[j - 1]);
+        const bool head = j < n && (j == 0 || key[it] != prev[it]);
         headbits |= head ? (1u << it) : 0u;
         cnt += head ? 1u : 0u;
     }
@@ -479,7 +514,7 @@ __global__ __launch_bounds__(kThreads) void k_emit(DdBuffers b, const DdHeader* 
         const unsigned seg = running + (unsigned)rank_in(m, lane) + (head ? 1u : 0u) - 1u; // heads up to and incl. j, minus 1
         running += (unsigned)__popcll(m);
         if (j < n) {
-            const uint32_t p = idxs ? idxs[j] : (uint32_t)j;
+            const uint32_t p = pos[it];
             if (inverse) inverse[p] = (int32_t)seg;
             // the mapping is read again a gigabyte of traffic later (expand, reduce): no cache allocation
             if (perm) __builtin_nontemporal_store((int32_t)p, &perm[j]);
