@@ -16,6 +16,7 @@ namespace {
 constexpr int kBlock = 256;
 constexpr int kUnroll = 8;            // segment reduce: rows a lane group fetches per batch at the first level
 constexpr int kUnrollUpper = 8;       // ... and at the upper levels
+constexpr int kUnrollFused = 8;       // fused backward, first level: each item also carries a table row and a record
 constexpr int kPipeMax = 8;           // batches up to this size are double-buffered
 
 __device__ inline const char* chunk_row_cptr(const HtView& v, uint32_t row) {
@@ -438,7 +439,7 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce_apply(LevelIn in, int dim
             if (lane_on) {
                 char* wp = s_values[r >> fz.v.chunk_log2] + (size_t)(r & chunk_mask) * (size_t)fz.v.row_bytes + sub * kWB;
                 if (!TBL_BF16) {
-                    st16_nt(wp, V16{__float_as_uint(adagrad_w(__uint_as_float(w_.x), acc.f[0], scale)),
+                    stg16_nt(wp, V16{__float_as_uint(adagrad_w(__uint_as_float(w_.x), acc.f[0], scale)),
                                  __float_as_uint(adagrad_w(__uint_as_float(w_.y), acc.f[1], scale)),
                                  __float_as_uint(adagrad_w(__uint_as_float(w_.z), acc.f[2], scale)),
                                  __float_as_uint(adagrad_w(__uint_as_float(w_.w), acc.f[3], scale))});
@@ -448,16 +449,18 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce_apply(LevelIn in, int dim
                     if constexpr (FPL == 8) {
                         const uint32_t o2 = pack_bf16(adagrad_w(bf16lo(w_.z), acc.f[4], scale), adagrad_w(bf16hi(w_.z), acc.f[5], scale));
                         const uint32_t o3 = pack_bf16(adagrad_w(bf16lo(w_.w), acc.f[6], scale), adagrad_w(bf16hi(w_.w), acc.f[7], scale));
-                        st16_nt(wp, V16{o0, o1, o2, o3});
+                        stg16_nt(wp, V16{o0, o1, o2, o3});
                     } else {
-                        *reinterpret_cast<uint2*>(wp) = make_uint2(o0, o1);
+                        MTGR_AS_GLOBAL uint32_t* q = (MTGR_AS_GLOBAL uint32_t*)wp;
+                        q[0] = o0;
+                        q[1] = o1;
                     }
                 }
             }
             if (sub == 0) {
                 RowMeta* m = s_meta[r >> fz.v.chunk_log2] + (r & chunk_mask);
-                if (fz.touch) st16(m, V16{__float_as_uint(acc_new), fz.step, rec_freq + 1u, rec_hot});
-                else m->acc = acc_new;
+                if (fz.touch) stg16(m, V16{__float_as_uint(acc_new), fz.step, rec_freq + 1u, rec_hot});
+                else ((MTGR_AS_GLOBAL RowMeta*)m)->acc = acc_new;
             }
         }
         runs_closed++;
@@ -529,20 +532,27 @@ __global__ __launch_bounds__(kBlock) void k_seg_reduce_apply(LevelIn in, int dim
                     const int src = __shfl(pick(my_src, u), sl, kWave);
                     sg_[k] = __shfl(pick(my_seg, u), sl, kWave);
                     rw_[k] = __shfl(pick(my_row, u), sl, kWave);
-                    if (lane_on && sg_[k] >= 0) v_[k] = (kNtGrad ? ld16_nt : ld16)(in.rows + (size_t)src * (size_t)in.in_row_bytes + sub * 16);
-                    if (rw_[k] >= 0) {
-                        const uint32_t r = (uint32_t)rw_[k];
-                        if (lane_on) {
-                            const char* wp = s_values[r >> fz.v.chunk_log2] + (size_t)(r & chunk_mask) * (size_t)fz.v.row_bytes + sub * kWB;
-                            if (kWB == 16) w_[k] = ld16_nt(wp);
-                            else {
-                                const uint2 t = *reinterpret_cast<const uint2*>(wp);
-                                w_[k].x = t.x;
-                                w_[k].y = t.y;
-                            }
-                        }
-                        if (sub == 0) rec_[k] = ld16(s_meta[r >> fz.v.chunk_log2] + (r & chunk_mask));
+                    // every load unconditional and a plain global load, as in k_seg_reduce and k_adagrad: an item
+                    // without a gradient row reads the matrix's first bytes, one that ends no run here reads row 0 and
+                    // its record (cache hits), and opaque masks drop what was read
+                    const bool on = lane_on && sg_[k] >= 0;
+                    const bool ron = rw_[k] >= 0;
+                    uint32_t keep = on ? 0xFFFFFFFFu : 0u, keep_r = ron ? 0xFFFFFFFFu : 0u;
+                    asm("" : "+v"(keep), "+v"(keep_r));
+                    const V16 t = (kNtGrad ? ld16_nt : ld16)(in.rows + (on ? (size_t)src * (size_t)in.in_row_bytes + sub * 16 : (size_t)0));
+                    v_[k] = V16{t.x & keep, t.y & keep, t.z & keep, t.w & keep};
+                    const uint32_t r = ron ? (uint32_t)rw_[k] : 0u;
+                    const char* wp = s_values[r >> fz.v.chunk_log2] + (size_t)(r & chunk_mask) * (size_t)fz.v.row_bytes + (lane_on ? sub * kWB : 0);
+                    V16 wt{0u, 0u, 0u, 0u};
+                    if (kWB == 16) wt = ldg16_nt(wp);
+                    else {
+                        const MTGR_AS_GLOBAL uint32_t* q = (const MTGR_AS_GLOBAL uint32_t*)wp;
+                        wt.x = q[0];
+                        wt.y = q[1];
                     }
+                    w_[k] = V16{wt.x & keep_r, wt.y & keep_r, wt.z & keep_r, wt.w & keep_r};
+                    const V16 rt = ldg16(s_meta[r >> fz.v.chunk_log2] + (r & chunk_mask));
+                    rec_[k] = V16{rt.x & keep_r, rt.y & keep_r, rt.z & keep_r, rt.w & keep_r};
                 }
             }
         };
@@ -667,7 +677,7 @@ int launch_reduce_apply(const char* grad, int in_row_bytes, const int32_t* seg_o
         int32_t* pseg = reinterpret_cast<int32_t*>(ws + L.seg_off[l]);
         if (l == 0) {
             LevelIn in{grad, perm, nullptr, seg_of, n, in_row_bytes};
-            hipLaunchKernelGGL((k_seg_reduce_apply<LPR, FPL, true, kUnroll, kTblBf16>), dim3(grid), dim3(kBlock), 0, s, in, dim, prow, pseg, last, fz);
+            hipLaunchKernelGGL((k_seg_reduce_apply<LPR, FPL, true, kUnrollFused, kTblBf16>), dim3(grid), dim3(kBlock), 0, s, in, dim, prow, pseg, last, fz);
         } else {
             LevelIn in{ws + L.rows_off[l - 1], nullptr, nullptr, reinterpret_cast<const int32_t*>(ws + L.seg_off[l - 1]),
                        L.items[l], dim * 4};
