@@ -468,6 +468,15 @@ __global__ __launch_bounds__(1024) void k_pk_heads_scan(unsigned* __restrict__ t
 // kOwnPrefixTiles tiles); otherwise tile_heads holds their exclusive prefix sums (k_pk_heads_scan).  The last tile
 // writes the number of distinct keys in the first case.
 constexpr unsigned kOwnPrefixTiles = 8192;
+// the last t < 256 with tag_start[t] <= j
+__device__ inline int tag_of_sorted(const unsigned* s_tag_start, int64_t j) {
+    int lo = 0, hi = 256;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if ((int64_t)s_tag_start[mid] <= j) lo = mid; else hi = mid;
+    }
+    return lo;
+}
 __global__ __launch_bounds__(kThreads) void k_pk_emit(PkArgs a, const uint64_t* __restrict__ rec,
                                                      uint64_t* __restrict__ uniq, int32_t* __restrict__ inverse,
                                                      int32_t* __restrict__ perm, int32_t* __restrict__ seg_off,
@@ -525,6 +534,9 @@ __global__ __launch_bounds__(kThreads) void k_pk_emit(PkArgs a, const uint64_t* 
     if (own_prefix && blockIdx.x == a.n_tiles - 1 && threadIdx.x == 0)
         *n_unique_out = (int64_t)(running + s_w[0] + s_w[1] + s_w[2] + s_w[3]);
     for (int w = 0; w < wave; ++w) running += s_w[w];
+    const int64_t wave_last = wave_first + kWave * kItems - 1 < a.n ? wave_first + kWave * kItems - 1 : a.n - 1;
+    const int tag_lo = wave_first < a.n ? tag_of_sorted(s_tag_start, wave_first) : 0;
+    const int tag_hi = wave_first < a.n ? tag_of_sorted(s_tag_start, wave_last) : 0;
     // pass 2: element order inside the wave is (it, lane)
 #pragma unroll
     for (int it = 0; it < kItems; ++it) {
@@ -540,12 +552,10 @@ __global__ __launch_bounds__(kThreads) void k_pk_emit(PkArgs a, const uint64_t* 
             if (perm) __builtin_nontemporal_store((int32_t)p, &perm[j]);
             if (seg_of) __builtin_nontemporal_store((int32_t)seg, &seg_of[j]);
             if (head) {
-                // identifier of sorted position j: the last t with tag_start[t] <= j
-                int lo = 0, hi = 256;
-                while (hi - lo > 1) {
-                    const int mid = (lo + hi) >> 1;
-                    if ((int64_t)s_tag_start[mid] <= j) lo = mid; else hi = mid;
-                }
+                // identifier of sorted position j: the last t with tag_start[t] <= j (one search per wave when its
+                // 1024 positions carry one identifier, which is the rule: there are at most 256 boundaries)
+                int lo = tag_lo;
+                if (tag_lo != tag_hi) lo = tag_of_sorted(s_tag_start, j);
                 uniq[seg] = ((uint64_t)lo << a.tag_shift) | (r[it] >> a.pos_bits);
                 if (seg_off) seg_off[seg] = (int32_t)j;
             }
