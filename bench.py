@@ -934,10 +934,25 @@ def ceiling_probes(B, timed, dev) -> dict:
     out["row_read_sequential_gbps"] = round((nbytes + 8 * rows) / (ms * 1e-3) / 1e9, 1)
     ms = timed(lambda: B.grad_segment_reduce(src, 0, zeros, rnd, rows, dim, red, rws))
     out["row_read_random_gbps"] = round((nbytes + 8 * rows) / (ms * 1e-3) / 1e9, 1)
+    # bare access patterns (emb_probe_memory): what the memory system gives kernels that only read, only write, or
+    # store one row per 4 / per 64 rows read; 256-byte rows, 16 lanes per row, loads overlapped as in the row kernels
+    quarter_rows = torch.empty((rows // 4, dim), dtype=torch.float32, device=dev)
+    for name, pattern, idx, moved in (
+            ("bare_read_sequential_gbps", B.PROBE_READ, None, nbytes),
+            ("bare_read_random_rows_gbps", B.PROBE_READ, rnd, nbytes + 4 * rows),
+            ("bare_write_sequential_gbps", B.PROBE_WRITE, None, nbytes),
+            ("bare_write_random_rows_gbps", B.PROBE_WRITE, rnd, nbytes + 4 * rows),
+            ("bare_read_random_rows_store_every_64th_gbps", B.PROBE_READ_STORE_64TH, rnd, nbytes + 4 * rows + nbytes // 64),
+            ("bare_read_random_rows_store_every_4th_gbps", B.PROBE_READ_STORE_4TH, rnd, nbytes + 4 * rows + nbytes // 4)):
+        target = dst if pattern == B.PROBE_WRITE else quarter_rows
+        ms = timed(lambda: B.emb_probe_memory(pattern, src, target, idx, rows))
+        out[name] = round(moved / (ms * 1e-3) / 1e9, 1)
+    del quarter_rows
     out["note"] = ("kernels of this library on synthetic indices: row mover with identity index (streaming copy), with a "
                    "random permutation as source index (the gather's shape), with one source row per four positions and a "
                    "random destination permutation (the sorted expand's shape); segment reduction of all rows into one "
-                   "segment in sequential and in random row order (the reduce's shape: reads only)")
+                   "segment in sequential and in random row order (the reduce's shape: reads only); bare_*: "
+                   "emb_probe_memory, kernels that do nothing but the named accesses over the same 256-byte rows")
     return out
 
 

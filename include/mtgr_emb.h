@@ -230,6 +230,19 @@ int emb_tag_dedup(const uint64_t* x, const int64_t* field_off, const uint8_t* fi
 int emb_dedup_noalloc(const uint64_t* key, int64_t n, uint64_t* uniq, int32_t* inverse, int32_t* counts,
                       int32_t* perm, int32_t* seg_off, int32_t* seg_of, int64_t* n_unique, void* stream);
 
+/* Measuring aid, not a step of the paper's path: one launch of a bare access pattern over rows of 256 bytes
+ * (16 lanes x 16 bytes per row, as in the row kernels), so that the rates reported for those kernels can be read
+ * against what the memory system gives a kernel that only reads, only writes, or mixes the two.
+ * src, dst [dev, 256-byte rows, 16-byte aligned]; idx [dev, int32, rows entries, each in [0, rows)] or null = the
+ * rows in order; rows > 0, a multiple of 64.  Nothing is allocated; errors: EMB_ERR_INVALID_ARG, EMB_ERR_HIP.
+ *   EMB_PROBE_READ              rows src[idx[r]] are read once and summed; dst (any 4 device bytes) is not written
+ *   EMB_PROBE_WRITE             dst row idx[r] <- (float)r in all 64 elements          (dst: rows rows)
+ *   EMB_PROBE_READ_STORE_4TH    as READ, and dst row q <- src[idx[4q]] + ... + src[idx[4q+3]], added in that order
+ *                               elementwise in fp32, stored non-temporally             (dst: rows/4 rows)
+ *   EMB_PROBE_READ_STORE_64TH   the same with 64 rows per sum                          (dst: rows/64 rows) */
+enum { EMB_PROBE_READ = 0, EMB_PROBE_WRITE = 1, EMB_PROBE_READ_STORE_4TH = 2, EMB_PROBE_READ_STORE_64TH = 3 };
+int emb_probe_memory(int pattern, const void* src, void* dst, const int32_t* idx, int64_t rows, void* stream);
+
 /* Sec. 3.1 (real-time insertion; open addressing with cooperative probing; "Capacity Expansion"):
  * find each key; insert the absent ones (claim a never-used slot by compare-and-swap, allocate a row,
  * initialise the row from the key, acc = 0).  Every element counts one touch: freq += 1, last_seen = step.

@@ -59,7 +59,7 @@ EXPORTS = [
     "grad_segment_reduce_pooled", "ht_evict", "ht_export", "ht_put", "ht_set_hot_storage", "ht_promote", "ht_demote", "ht_put_hot", "ht_export_hot",
     "ht_find_or_insert_notouch", "ht_apply_adagrad_touch", "grad_reduce_apply_adagrad",
     "ht_find_or_insert_retry", "ht_clear_status", "emb_dedup_noalloc",
-    "emb_tag_dedup_workspace_bytes", "emb_tag_dedup",
+    "emb_tag_dedup_workspace_bytes", "emb_tag_dedup", "emb_probe_memory",
 ]
 
 
@@ -92,6 +92,7 @@ def load():
         "emb_tag_dedup_workspace_bytes": (C.c_size_t, [i64, i32, i32, i32]),
         "emb_tag_dedup": (C.c_int, [vp, vp, vp, i32, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]),
         "emb_dedup_noalloc": (C.c_int, [vp, i64, vp, vp, vp, vp, vp, vp, vp, vp]),
+        "emb_probe_memory": (C.c_int, [i32, vp, vp, vp, i64, vp]),
         "ht_find_or_insert": (C.c_int, [vp, vp, vp, i64, u32, vp, vp, vp]),
         "ht_find_or_insert_notouch": (C.c_int, [vp, vp, vp, i64, u32, vp, vp, vp]),
         "ht_find_or_insert_retry": (C.c_int, [vp, vp, vp, i64, u32, vp, vp, i32, vp]),
@@ -246,6 +247,14 @@ def emb_tag_dedup(x, field_off, field_tag, tag_bits: int, id_bits: int, key_out,
 def emb_dedup_noalloc(key, n: int, uniq, inverse, counts, perm, seg_off, seg_of, n_unique, stream=None) -> None:
     _check(load().emb_dedup_noalloc(_ptr(key), n, _ptr(uniq), _ptr(inverse), _ptr(counts), _ptr(perm), _ptr(seg_off),
                                     _ptr(seg_of), _ptr(n_unique), _stream(stream)), "emb_dedup_noalloc")
+
+
+PROBE_READ, PROBE_WRITE, PROBE_READ_STORE_4TH, PROBE_READ_STORE_64TH = 0, 1, 2, 3
+
+
+def emb_probe_memory(pattern: int, src, dst, idx, rows: int, stream=None) -> None:
+    """One launch of a bare access pattern over 256-byte rows (a measuring aid, see mtgr_emb.h)."""
+    _check(load().emb_probe_memory(pattern, _ptr(src), _ptr(dst), _ptr(idx), rows, _stream(stream)), "emb_probe_memory")
 
 
 def ht_find_or_insert(h, key, n_dev, n_max: int, step: int, row_idx, inserted=None, stream=None, touch: bool = True) -> int:
